@@ -1,0 +1,328 @@
+"""Python face of the CPU oracle -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+
+Thin ctypes marshalling around ``slonn_oracle.cpp`` plus the per-network loop
+(for l in layers: select, sparse layer; commented "k% forward propagation"
+procedure of Section 2.1).  Only tests, the smoke check and the CPU-baseline leg
+of the benchmark may import this module; it never touches the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import struct
+import subprocess
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "slonn_oracle.cpp")
+_LIB = os.path.join(_HERE, "libslonn_oracle.so")
+
+TIE_EPS = 1e-6
+BLOB_MAGIC = 0x544E4C53        # "SLNT"
+BLOB_VERSION = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with the host compiler (g++ -O2, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-pthread",
+                               "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.so_tables_build.restype = C.c_void_p
+        _lib.so_tables_from_lists.restype = C.c_void_p
+        _lib.so_tables_bucket_count.restype = C.c_int64
+        _lib.so_tables_csr.restype = C.c_int64
+        _lib.so_budget.restype = C.c_int32
+        _lib.so_budget.argtypes = [C.c_float, C.c_int32]
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def default_threads() -> int:
+    return max(1, len(os.sched_getaffinity(0)))
+
+
+def budget(keep: float, n: int) -> int:
+    return int(lib().so_budget(C.c_float(float(keep)), n))
+
+
+# --------------------------------------------------------------------------- #
+# layer-level calls
+# --------------------------------------------------------------------------- #
+def dense_layer(layer, X, threads=1, want_pre=False):
+    X = _f32(X)
+    N = X.shape[0]
+    out = np.empty((N, layer.d_out), np.float32)
+    pre = np.empty((N, layer.d_out), np.float32) if want_pre else None
+    W = np.ascontiguousarray(layer.W)
+    lib().so_dense_layer(_p(W), layer.w_dtype, _p(layer.bias), layer.d_in, layer.d_out, layer.act,
+                         _p(X), C.c_int64(N), _p(pre), _p(out), threads)
+    return (out, pre) if want_pre else out
+
+
+def dense_layer_ell(layer, idx, val, nnz, threads=1, rows_are_inputs=False):
+    idx = np.ascontiguousarray(idx, np.int32)
+    val = _f32(val)
+    nnz = np.ascontiguousarray(nnz, np.int32)
+    N = idx.shape[0]
+    out = np.empty((N, layer.d_out), np.float32)
+    W = np.ascontiguousarray(layer.W)
+    lib().so_dense_layer_ell(_p(W), layer.w_dtype, int(rows_are_inputs), _p(layer.bias), layer.d_in,
+                             layer.d_out, layer.act, _p(idx), _p(val), _p(nnz),
+                             C.c_int64(idx.shape[1]), C.c_int64(N), _p(out), threads)
+    return out
+
+
+def hash_project(layer, X, threads=1):
+    X = _f32(X)
+    N = X.shape[0]
+    hn = np.ascontiguousarray(layer.hash_nodes, np.int32)
+    Z = np.empty((N, hn.size), np.float32)
+    W = np.ascontiguousarray(layer.W)
+    lib().so_hash_project(_p(W), layer.w_dtype, _p(layer.bias), layer.d_in, _p(hn), hn.size,
+                          _p(X), C.c_int64(N), _p(Z), threads)
+    return Z
+
+
+def keys_from_z(Z, K, L, tie_eps=TIE_EPS):
+    Z = _f32(Z)
+    N = Z.shape[0]
+    keys = np.empty((N, L), np.uint32)
+    tie = np.empty(N, np.uint8)
+    lib().so_keys(_p(Z), C.c_int64(N), K, L, _p(keys), _p(tie), C.c_float(tie_eps))
+    return keys, tie.astype(bool)
+
+
+class Tables:
+    """Node Importance tables of one layer (owned handle)."""
+
+    def __init__(self, handle, n, K, L, list_cap):
+        self.h = C.c_void_p(handle)
+        self.n, self.K, self.L, self.list_cap = n, K, L, list_cap
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().so_tables_free(self.h)
+            self.h = None
+
+    @classmethod
+    def build(cls, n, K, L, list_cap, keys, act, keep_scores=False, threads=1):
+        keys = np.ascontiguousarray(keys, np.uint32)
+        act = _f32(act)
+        h = lib().so_tables_build(n, K, L, list_cap, _p(keys), _p(act), C.c_int64(act.shape[0]),
+                                  int(keep_scores), threads)
+        return cls(h, n, K, L, list_cap)
+
+    @classmethod
+    def from_lists(cls, n, K, L, list_cap, dir_, ids, global_rank):
+        dir_ = np.ascontiguousarray(dir_, np.uint32)
+        ids = np.ascontiguousarray(ids, np.int32)
+        gr = np.ascontiguousarray(global_rank, np.int32)
+        h = lib().so_tables_from_lists(n, K, L, list_cap, _p(dir_), _p(ids), _p(gr))
+        return cls(h, n, K, L, list_cap)
+
+    def bucket(self, b, key):
+        buf = np.empty(self.n, np.int32)
+        ln = lib().so_tables_bucket(self.h, b, C.c_uint32(int(key)), _p(buf), self.n)
+        return buf[:ln].copy()
+
+    def bucket_count(self, b, key):
+        return int(lib().so_tables_bucket_count(self.h, b, C.c_uint32(int(key))))
+
+    def bucket_scores(self, b, key):
+        out = np.zeros(self.n, np.float64)
+        ok = lib().so_tables_bucket_scores(self.h, b, C.c_uint32(int(key)), _p(out))
+        return out if ok else None
+
+    def global_rank(self):
+        r = np.empty(self.n, np.int32)
+        s = np.empty(self.n, np.float64)
+        lib().so_tables_global(self.h, _p(r), _p(s))
+        return r, s
+
+    def select(self, keys, keep, stride=None):
+        keys = np.ascontiguousarray(keys, np.uint32)
+        keep = _f32(keep).reshape(-1)
+        N = keys.shape[0]
+        stride = self.n if stride is None else stride
+        active = np.full((N, stride), -1, np.int32)
+        cnt = np.zeros(N, np.int32)
+        rc = lib().so_select(self.h, _p(keys), _p(keep), C.c_int64(1 if keep.size > 1 else 0),
+                             C.c_int64(N), _p(active), _p(cnt), C.c_int64(stride))
+        if rc != 0:
+            raise ValueError("budget exceeds the active-list stride")
+        return active, cnt
+
+    def csr(self):
+        """(dir uint32 [L][2^K+1], ids int32) -- the flat form the table blob stores."""
+        nb = 1 << self.K
+        dir_ = np.zeros((self.L, nb + 1), np.uint32)
+        total = int(lib().so_tables_csr(self.h, None, None))
+        ids = np.zeros(total, np.int32)
+        lib().so_tables_csr(self.h, _p(dir_), _p(ids))
+        # offsets run on across tables: dir[b][2^K] == dir[b+1][0]
+        return dir_, ids.astype(np.int32)
+
+
+def sparse_layer(layer, X, active, cnt, threads=1, want_pre=False):
+    X = _f32(X)
+    N = X.shape[0]
+    active = np.ascontiguousarray(active, np.int32)
+    cnt = np.ascontiguousarray(cnt, np.int32)
+    out = np.empty((N, layer.d_out), np.float32)
+    pre = np.empty((N, layer.d_out), np.float32) if want_pre else None
+    W = np.ascontiguousarray(layer.W)
+    lib().so_sparse_layer(_p(W), layer.w_dtype, _p(layer.bias), layer.d_in, layer.d_out, layer.act,
+                          _p(X), C.c_int64(N), _p(active), _p(cnt), C.c_int64(active.shape[1]),
+                          _p(pre), _p(out), threads)
+    return (out, pre) if want_pre else out
+
+
+def argmax(out, active=None, cnt=None):
+    out = _f32(out)
+    N, n = out.shape
+    pred = np.empty(N, np.int32)
+    if active is not None:
+        active = np.ascontiguousarray(active, np.int32)
+        cnt = np.ascontiguousarray(cnt, np.int32)
+        lib().so_argmax(_p(out), n, C.c_int64(N), _p(active), _p(cnt), C.c_int64(active.shape[1]),
+                        _p(pred))
+    else:
+        lib().so_argmax(_p(out), n, C.c_int64(N), None, None, C.c_int64(0), _p(pred))
+    return pred
+
+
+# --------------------------------------------------------------------------- #
+# whole network
+# --------------------------------------------------------------------------- #
+class OracleNet:
+    """The network loop: per layer, hash -> keys -> select -> sparse layer."""
+
+    def __init__(self, layers: Sequence, threads: Optional[int] = None,
+                 first_layer_rows_are_inputs: bool = False):
+        self.layers = list(layers)
+        self.threads = default_threads() if threads is None else threads
+        self.tables: List[Optional[Tables]] = [None] * len(self.layers)
+        self.rows_are_inputs0 = first_layer_rows_are_inputs
+
+    # -- first layer may take ELL input ------------------------------------- #
+    def _first(self, X):
+        if isinstance(X, tuple):
+            idx, val, nnz = X
+            return dense_layer_ell(self.layers[0], idx, val, nnz, self.threads, self.rows_are_inputs0)
+        return None
+
+    def dense_forward(self, X, upto: Optional[int] = None):
+        """Full network (all nodes).  Returns the list of layer outputs."""
+        outs = []
+        cur = X
+        for l, layer in enumerate(self.layers[:upto]):
+            if l == 0 and isinstance(X, tuple):
+                cur = self._first(X)
+            else:
+                cur = dense_layer(layer, cur, self.threads)
+            outs.append(cur)
+        return outs
+
+    def build_tables(self, X_build, keep_scores=False):
+        """Alg. 1 for every layer with a Node Activator; Input_l is the full
+        network's (all nodes computed) input to layer l on the training set."""
+        cur = X_build
+        for l, layer in enumerate(self.layers):
+            if layer.K > 0 and layer.L > 0:
+                if isinstance(cur, tuple):
+                    raise ValueError("a Node Activator on a sparse-input first layer is not supported")
+                Z = hash_project(layer, cur, self.threads)
+                keys, _ = keys_from_z(Z, layer.K, layer.L)
+                act = dense_layer(layer, cur, self.threads)
+                self.tables[l] = Tables.build(layer.d_out, layer.K, layer.L, layer.list_cap, keys, act,
+                                              keep_scores, self.threads)
+                cur = act
+            elif l == 0 and isinstance(cur, tuple):
+                cur = self._first(cur)
+            else:
+                cur = dense_layer(layer, cur, self.threads)
+        return self.tables
+
+    def sparse_forward(self, X, keep, taps=True):
+        """keep: scalar, [N] (one k per query for all layers) or [N][n_layers]."""
+        N = X[0].shape[0] if isinstance(X, tuple) else np.asarray(X).shape[0]
+        keep = np.asarray(keep, np.float32)
+        if keep.ndim == 0:
+            keep = np.full((N,), keep, np.float32)
+        res = {"layers": []}
+        cur = X
+        last_active = last_cnt = None
+        for l, layer in enumerate(self.layers):
+            k_l = keep if keep.ndim == 1 else np.ascontiguousarray(keep[:, l])
+            tap = {}
+            if layer.K > 0 and layer.L > 0:
+                Z = hash_project(layer, cur, self.threads)
+                keys, tie = keys_from_z(Z, layer.K, layer.L)
+                active, cnt = self.tables[l].select(keys, k_l)
+                out = sparse_layer(layer, cur, active, cnt, self.threads)
+                if taps:
+                    tap = {"z": Z, "codes": keys, "tie": tie, "active": active, "cnt": cnt}
+                last_active, last_cnt = active, cnt
+            else:
+                if l == 0 and isinstance(cur, tuple):
+                    out = self._first(cur)
+                else:
+                    out = dense_layer(layer, cur, self.threads)
+                last_active = last_cnt = None
+            if taps:
+                tap["out"] = out
+            res["layers"].append(tap)
+            cur = out
+        res["out"] = cur
+        res["argmax"] = argmax(cur, last_active, last_cnt)
+        return res
+
+    # -- table blob ---------------------------------------------------------- #
+    def export_tables(self) -> bytes:
+        sets = [(l, t) for l, t in enumerate(self.tables) if t is not None]
+        parts = [struct.pack("<4I", BLOB_MAGIC, BLOB_VERSION, len(sets), 0)]
+        for l, t in sets:
+            dir_, ids = t.csr()
+            gr, _ = t.global_rank()
+            hn = np.ascontiguousarray(self.layers[l].hash_nodes, np.int32)
+            parts.append(struct.pack("<8I", l, t.K, t.L, t.n, t.list_cap, ids.size, 0, 0))
+            parts += [hn.astype("<i4").tobytes(), dir_.astype("<u4").tobytes(),
+                      ids.astype("<i4").tobytes(), gr.astype("<i4").tobytes()]
+        return b"".join(parts)
+
+    def import_tables(self, blob: bytes):
+        magic, ver, nsets, _ = struct.unpack_from("<4I", blob, 0)
+        if magic != BLOB_MAGIC or ver != BLOB_VERSION:
+            raise ValueError("not a table blob")
+        off = 16
+        for _ in range(nsets):
+            l, K, L, n, cap, tot, _, _ = struct.unpack_from("<8I", blob, off)
+            off += 32
+            hn = np.frombuffer(blob, "<i4", K * L, off); off += 4 * K * L
+            nd = L * ((1 << K) + 1)
+            dir_ = np.frombuffer(blob, "<u4", nd, off); off += 4 * nd
+            ids = np.frombuffer(blob, "<i4", tot, off); off += 4 * tot
+            gr = np.frombuffer(blob, "<i4", n, off); off += 4 * n
+            if not np.array_equal(hn, np.asarray(self.layers[l].hash_nodes, np.int32)):
+                raise ValueError("blob hash nodes differ from the model's")
+            self.tables[l] = Tables.from_lists(n, K, L, cap, dir_, ids, gr)
+        return self.tables
