@@ -1,0 +1,191 @@
+/* slonn.h -- C ABI of the MI355X (gfx950) SLO-NN hot path.
+ *
+ * The library evaluates a fully-connected network with per-query dynamic node
+ * dropout as defined by "SLO-Aware Neural Networks" (arXiv 2204.08400): for every
+ * query and every layer that carries a Node Activator, FreeHash codes (Def. 2,
+ * Section 3.4) select one bucket in each of L Node Importance tables (Section 3.2,
+ * Alg. 1), the ranked node lists found there are merged into the top-k% active set
+ * (Fig. 2 steps 3-4, Section 3.3) and only those nodes' weight rows are evaluated;
+ * every other node of the layer outputs exactly +0.
+ *
+ * Conventions
+ *   - All tensor arguments are raw pointers.  "device" = HIP device memory on the
+ *     current device, "host" = ordinary host memory.  The library never takes
+ *     ownership of caller memory; handles (slonn_model, slonn_tables) are owned by
+ *     the library and released with the matching *_destroy call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
+ *     forward/select calls only enqueue work on it and never synchronise; build,
+ *     import and export synchronise (documented per call).
+ *   - Every function returns SLONN_OK (0) or a negative slonn_status; nothing throws
+ *     or aborts.  slonn_last_error() returns a thread-local description of the last
+ *     failure.  Argument validation happens before any device work is enqueued.
+ *   - A keep fraction k in (0, 1] becomes a node budget m = min(n, max(1,
+ *     floor(k*n + 0.5))) evaluated in double ("rounding to the nearest whole node",
+ *     at least one node).  m == n means the layer is computed in full.
+ *   - Matrices are row-major and dense unless a stride is given.
+ */
+#ifndef SLONN_H
+#define SLONN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SLONN_OK = 0,
+  SLONN_EINVAL = -1,       /* bad argument (null pointer, bad size, bad enum, ...)        */
+  SLONN_ENOMEM = -2,       /* host or device allocation failed / workspace too small      */
+  SLONN_EHIP = -3,         /* a HIP runtime call failed                                   */
+  SLONN_EUNSUPPORTED = -4, /* valid request the library cannot serve (stated per call)    */
+  SLONN_ECAP = -5          /* a budget exceeds list_cap or an output stride               */
+} slonn_status;
+
+enum { SLONN_F32 = 0, SLONN_BF16 = 1 };                 /* weight storage type            */
+enum { SLONN_ROWS_ARE_NODES = 0, SLONN_ROWS_ARE_INPUTS = 1 };
+enum { SLONN_ACT_NONE = 0, SLONN_ACT_RELU = 1, SLONN_ACT_SOFTMAX = 2 };
+enum { SLONN_DENSE = 0, SLONN_ELL = 1 };                /* first-layer input format       */
+
+#define SLONN_MAX_K 16      /* bits per key                                               */
+#define SLONN_MAX_L 64      /* tables per layer (one wavefront lane per table)            */
+#define SLONN_TABLE_BLOB_MAGIC 0x544E4C53u /* "SLNT" */
+#define SLONN_TABLE_BLOB_VERSION 1u
+
+typedef struct slonn_model slonn_model;
+typedef struct slonn_tables slonn_tables;
+
+/* One fully-connected layer y = act(W x + b).  Activations are always fp32.
+ * W: device, BORROWED for the lifetime of the model.  ROWS_ARE_NODES: [d_out][d_in],
+ * a node's weights are contiguous (required for every layer but the first);
+ * ROWS_ARE_INPUTS: [d_in][d_out], only for a first layer fed with SLONN_ELL input.
+ * bias: device [d_out], borrowed.
+ * K, L > 0 put a Node Activator on the layer: hash_nodes (HOST, [L*K], copied) lists
+ * the K*L distinct nodes of this layer whose weights and biases serve as FreeHash
+ * functions; entry b*K+j is bit j (little endian) of table b's key.  K = L = 0: the
+ * layer is always computed in full.  list_cap bounds the ids stored per bucket when
+ * tables are built (>= the largest budget below d_out that will be requested).   */
+typedef struct {
+  int32_t d_in, d_out;
+  int32_t w_dtype;           /* SLONN_F32 | SLONN_BF16                                    */
+  int32_t w_layout;          /* SLONN_ROWS_ARE_NODES | SLONN_ROWS_ARE_INPUTS              */
+  int32_t act;               /* SLONN_ACT_*  (SOFTMAX only on the last layer)             */
+  int32_t K, L;
+  int32_t list_cap;
+  const void* W;
+  const float* bias;
+  const int32_t* hash_nodes;
+} slonn_layer_desc;
+
+/* A batch of first-layer inputs, device memory, borrowed for the call.
+ * SLONN_DENSE: x [B][d0] fp32.  SLONN_ELL: idx/val [B][ell_stride], nnz [B]; row q has
+ * nnz[q] <= ell_stride (column, value) pairs, columns distinct and < d0.            */
+typedef struct {
+  int32_t format;
+  const float* x;
+  const int32_t* idx;
+  const float* val;
+  const int32_t* nnz;
+  int32_t ell_stride;
+} slonn_input;
+
+/* Caller-allocated device outputs of a forward call; any member may be NULL.
+ * dense: [B][d_last]; nodes that were not computed hold +0.0f.
+ * idx/val/cnt: compact form of the last layer when it carries a Node Activator:
+ *   idx[q][t], val[q][t] for t < cnt[q], in selection (priority) order; rows are
+ *   `stride` apart.  Ignored (cnt = d_last, idx ascending) when the last layer is
+ *   computed in full.
+ * argmax: [B] id of the computed node with the largest output (lowest id on ties). */
+typedef struct {
+  float* dense;
+  int32_t* idx;
+  float* val;
+  int32_t* cnt;
+  int32_t stride;
+  int32_t* argmax;
+} slonn_output;
+
+/* Optional per-layer taps for parity checks: arrays of n_layers device pointers (HOST
+ * arrays; each entry may be NULL).  Layers without a Node Activator only fill
+ * layer_out.  codes [B][L] uint32; z [B][K*L] fp32 hash projections; active_idx
+ * [B][d_out] int32 (selection order) with active_cnt [B]; layer_out [B][d_out].   */
+typedef struct {
+  uint32_t** codes;
+  float** z;
+  int32_t** active_idx;
+  int32_t** active_cnt;
+  float** layer_out;
+} slonn_debug_taps;
+
+/* Library / device self-description: fills a short human-readable string.          */
+int slonn_version(char* buf, size_t cap);
+
+/* Validate and register a network.  Copies the K*L FreeHash rows of each activated
+ * layer into library-owned device memory (synchronises the device once).
+ * Errors: EINVAL for null/negative sizes, K > SLONN_MAX_K, L > SLONN_MAX_L, K*L >
+ * d_out, duplicate or out-of-range hash nodes, d_in mismatch between consecutive
+ * layers, SOFTMAX before the last layer; EUNSUPPORTED for ROWS_ARE_INPUTS anywhere
+ * but on layer 0 or together with a Node Activator.                                 */
+int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model** out);
+int slonn_model_destroy(slonn_model* m);
+
+/* Alg. 1 for every activated layer, on the device.  X_build holds N training inputs
+ * (device).  Input_l is the full network's output of layer l-1 on X_build; the
+ * Activation summed into NodeScore is layer l's own output; each bucket keeps its
+ * positive-score nodes sorted from the highest sum to the lowest (ties: lower id),
+ * at most list_cap of them; the sums over all N inputs give the fallback ranking.
+ * Allocates temporary device memory, synchronises `stream`, returns owned tables.
+ * EUNSUPPORTED: d_out of an activated layer above 8192 (bucket sort runs in LDS).   */
+int slonn_build_tables(const slonn_model* m, const slonn_input* X_build, int64_t N, void* stream,
+                       slonn_tables** out);
+
+/* Table blob (host memory, little endian, all fields 4 bytes wide):
+ *   u32 magic, u32 version, u32 n_sets, u32 0
+ *   per set: u32 layer, K, L, n, list_cap, total_ids, 0, 0
+ *            i32 hash_nodes[L*K]; u32 dir[L][2^K+1]; i32 ids[total_ids]; i32 global_rank[n]
+ * dir[b][key] .. dir[b][key+1] delimit bucket (b,key)'s list inside ids; offsets run on
+ * from one table to the next.  export: call with buf == NULL to obtain *bytes, then
+ * with a buffer of that size.  import checks the blob against the model (layer ids,
+ * K, L, n, hash nodes, offsets monotone, ids in range) and uploads it.             */
+int slonn_tables_export(const slonn_tables* t, void* host_buf, size_t* bytes);
+int slonn_tables_import(const slonn_model* m, const void* host_buf, size_t bytes, slonn_tables** out);
+int slonn_tables_destroy(slonn_tables* t);
+
+/* Bytes of device workspace the select / forward calls need for batches up to B_max. */
+int slonn_workspace_bytes(const slonn_model* m, int B_max, size_t* out);
+
+/* Node Activator of one layer (Fig. 2 steps 1, 3, 4) on a batch of that layer's
+ * inputs X_l (device [B][d_in] fp32): FreeHash projections z = W_h x + b_h, keys, bucket
+ * lookup, rank-major merge of the L lists with first-occurrence de-duplication, the
+ * whole-set ranking as fallback, until the budget of each query is met.
+ * keep: device, query q uses keep[q*keep_stride] (stride 0 broadcasts one value).
+ * codes_out [B][L], z_out [B][K*L] nullable.  active_idx [B][idx_stride] receives the
+ * chosen ids in selection order, active_cnt [B] their number (== budget).
+ * ECAP when idx_stride < d_out (a budget may reach d_out).                          */
+int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const float* X_l, int B,
+                 const float* keep, int keep_stride, uint32_t* codes_out, float* z_out,
+                 int32_t* active_idx, int32_t* active_cnt, int idx_stride, void* workspace,
+                 size_t ws_bytes, void* stream);
+
+/* Whole network with node dropout: for each layer, select (if activated) then evaluate
+ * only the active rows; the sparse output feeds the next layer.  keep: device,
+ * query q / layer l uses keep[q*keep_qstride + l*keep_lstride] (0 strides broadcast;
+ * the paper uses one k per query for all layers: keep_lstride = 0).                 */
+int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
+                         const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
+                         const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
+                         void* stream);
+
+/* The full network (all nodes), the baseline every speed-up is measured against:
+ * per layer an MFMA GEMM + bias + activation.  Y device [B][d_last]; argmax nullable.
+ * layer_out: optional HOST array of n_layers device pointers ([B][d_out] each).     */
+int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float* Y, int32_t* argmax,
+                        float** layer_out, void* workspace, size_t ws_bytes, void* stream);
+
+const char* slonn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLONN_H */

@@ -1,0 +1,318 @@
+// Node Activator training on the device (Alg. 1, Section 3.2).  For one layer:
+//   keys       every training input is hashed into one bucket of each of the L tables;
+//   NodeScore  per bucket, the layer's output activations of its inputs are summed
+//              (double, in training-set order, so repeated builds are bit-identical);
+//   Rank       per bucket, nodes with a positive sum sorted from the highest sum to the
+//              lowest (equal sums: lower id first), truncated to list_cap;
+//   fallback   the same ranking over the sums of all inputs (all n nodes).
+// This is set-up work and is not timed; it favours determinism and small code.
+#include <algorithm>
+
+#include "slonn_internal.h"
+
+namespace slonn {
+namespace {
+
+constexpr int SORT_MAX = 8192;   // largest layer the LDS sort handles
+
+__global__ void keys_kernel(const float* __restrict__ Z, int K, int L, int64_t N,
+                            uint32_t* __restrict__ keys) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // (input, table)
+  if (e >= N * L) return;
+  const float* z = Z + e * K;      // Z is [N][L*K]: entry e = x*L + b starts at (x*L + b)*K
+  uint32_t key = 0;
+  for (int j = 0; j < K; ++j) key |= (z[j] > 0.0f ? 1u : 0u) << j;
+  keys[e] = key;
+}
+
+__global__ void histogram_kernel(const uint32_t* __restrict__ keys, int L, int b, int64_t N,
+                                 uint32_t* __restrict__ hist) {
+  const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (x < N) atomicAdd(&hist[keys[x * L + b]], 1u);
+}
+
+// members of each bucket in ascending input order; start[] are exclusive prefix sums of hist
+__global__ void bucket_members_kernel(const uint32_t* __restrict__ keys, int L, int b, int64_t N,
+                                      const uint32_t* __restrict__ start, int nb,
+                                      uint32_t* __restrict__ members) {
+  const int key = blockIdx.x * blockDim.x + threadIdx.x;
+  if (key >= nb) return;
+  uint32_t at = start[key];
+  const uint32_t end = start[key + 1];
+  if (at == end) return;
+  for (int64_t x = 0; x < N && at < end; ++x)
+    if (keys[x * L + b] == (uint32_t)key) members[at++] = (uint32_t)x;
+}
+
+// NodeScore[key][j] = sum of act[x][j] over the bucket's members, in order
+__global__ void node_score_kernel(const float* __restrict__ act, int n, const uint32_t* __restrict__ start,
+                                  const uint32_t* __restrict__ members, double* __restrict__ score,
+                                  uint32_t* __restrict__ npos) {
+  const int key = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  double s = 0.0;
+  for (uint32_t i = start[key]; i < start[key + 1]; ++i) s += (double)act[(size_t)members[i] * n + j];
+  score[(size_t)key * n + j] = s;
+  if (s > 0.0) atomicAdd(&npos[key], 1u);
+}
+
+__global__ void total_score_kernel(const float* __restrict__ act, int n, int64_t N,
+                                   double* __restrict__ score) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  double s = 0.0;
+  for (int64_t x = 0; x < N; ++x) s += (double)act[x * n + j];
+  score[j] = s;
+}
+
+__device__ __forceinline__ bool ranks_before(int a, int b, const double* sc) {
+  // -1 marks an absent entry and sorts last
+  if (a < 0) return false;
+  if (b < 0) return true;
+  const double sa = sc[a], sb = sc[b];
+  return sa > sb || (sa == sb && a < b);
+}
+
+// Bitonic sort of one bucket's node ids in LDS; scores stay in global memory (L2).
+// positive_only: nodes with a sum <= 0 are left out.  Writes the first out_len[bucket]
+// ids at out + out_off[bucket].
+__global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ score, int n, int P,
+                                                  int positive_only, const uint32_t* __restrict__ out_off,
+                                                  const uint32_t* __restrict__ out_len,
+                                                  int32_t* __restrict__ out) {
+  __shared__ int32_t ids[SORT_MAX];
+  const int bucket = blockIdx.x;
+  const uint32_t len = out_len[bucket];
+  if (len == 0) return;
+  const double* sc = score + (size_t)bucket * n;
+  for (int i = threadIdx.x; i < P; i += 256) {
+    int v = -1;
+    if (i < n && (!positive_only || sc[i] > 0.0)) v = i;
+    ids[i] = v;
+  }
+  __syncthreads();
+  for (int k = 2; k <= P; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = threadIdx.x; t < (P >> 1); t += 256) {
+        // t-th pair of this stage: i has bit j clear
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int p = i | j;
+        const int a = ids[i], b = ids[p];
+        const bool up = (i & k) == 0;          // ascending block: best first
+        const bool swap = up ? ranks_before(b, a, sc) : ranks_before(a, b, sc);
+        if (swap) { ids[i] = b; ids[p] = a; }
+      }
+      __syncthreads();
+    }
+  }
+  int32_t* dst = out + out_off[bucket];
+  for (uint32_t i = threadIdx.x; i < len; i += 256) dst[i] = ids[i];
+}
+
+template <class T>
+struct DevBuf {
+  T* p = nullptr;
+  ~DevBuf() { if (p) (void)hipFree(p); }
+  hipError_t alloc(size_t count) { return hipMalloc(&p, std::max<size_t>(count, 1) * sizeof(T)); }
+};
+
+}  // namespace
+
+void free_table_set(TableSet* ts) {
+  if (ts->d_dir) (void)hipFree(ts->d_dir);
+  if (ts->d_ids) (void)hipFree(ts->d_ids);
+  if (ts->d_global_rank) (void)hipFree(ts->d_global_rank);
+  ts->d_dir = nullptr; ts->d_ids = nullptr; ts->d_global_rank = nullptr;
+}
+
+int upload_table_set(TableSet* ts) {
+  SLONN_HIP(hipMalloc(&ts->d_dir, std::max<size_t>(ts->dir.size(), 1) * 4));
+  SLONN_HIP(hipMalloc(&ts->d_ids, std::max<size_t>(ts->ids.size(), 1) * 4));
+  SLONN_HIP(hipMalloc(&ts->d_global_rank, std::max<size_t>(ts->global_rank.size(), 1) * 4));
+  SLONN_HIP(hipMemcpy(ts->d_dir, ts->dir.data(), ts->dir.size() * 4, hipMemcpyHostToDevice));
+  if (!ts->ids.empty())
+    SLONN_HIP(hipMemcpy(ts->d_ids, ts->ids.data(), ts->ids.size() * 4, hipMemcpyHostToDevice));
+  SLONN_HIP(hipMemcpy(ts->d_global_rank, ts->global_rank.data(), ts->global_rank.size() * 4,
+                      hipMemcpyHostToDevice));
+  return SLONN_OK;
+}
+
+int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_t N, const float* act,
+                       TableSet* ts, hipStream_t s) {
+  const Layer& Ly = m->layers[layer];
+  const int n = Ly.d_out, K = Ly.K, L = Ly.L, H = Ly.H();
+  if (n > SORT_MAX)
+    SLONN_FAIL(SLONN_EUNSUPPORTED, "build: layer %d has %d nodes, the bucket sort handles up to %d", layer, n,
+               SORT_MAX);
+  if (N <= 0 || N > 0x7FFFFFFF) SLONN_FAIL(SLONN_EINVAL, "build: bad training-set size");
+  const int nb = 1 << K;
+  int P = 1;
+  while (P < n) P <<= 1;
+  if (P < 2) P = 2;
+  const int cap = std::min(Ly.list_cap, n);
+
+  ts->layer = layer; ts->K = K; ts->L = L; ts->n = n; ts->list_cap = Ly.list_cap;
+  ts->dir.assign((size_t)L * (nb + 1), 0);
+  ts->ids.clear();
+  ts->global_rank.assign(n, 0);
+
+  DevBuf<float> Z;
+  DevBuf<uint32_t> keys, hist, start, members, npos, off, len;
+  DevBuf<double> score;
+  DevBuf<int32_t> out;
+  SLONN_HIP(Z.alloc((size_t)N * H));
+  SLONN_HIP(keys.alloc((size_t)N * L));
+  SLONN_HIP(hist.alloc(nb));
+  SLONN_HIP(start.alloc(nb + 1));
+  SLONN_HIP(members.alloc(N));
+  SLONN_HIP(npos.alloc(nb));
+  SLONN_HIP(off.alloc(nb));
+  SLONN_HIP(len.alloc(nb));
+  SLONN_HIP(score.alloc((size_t)nb * n));
+  SLONN_HIP(out.alloc((size_t)std::min<int64_t>(nb, N) * cap));
+
+  int rc = launch_hash_project(X_l, Ly.d_in, Ly.Wh, Ly.bh, Z.p, (int)N, H, Ly.d_in, s);
+  if (rc) return rc;
+  {
+    const int64_t tot = N * L;
+    hipLaunchKernelGGL(keys_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s, Z.p, K, L, N, keys.p);
+    SLONN_HIP(hipGetLastError());
+  }
+
+  std::vector<uint32_t> h_hist(nb), h_start(nb + 1), h_npos(nb), h_off(nb), h_len(nb);
+  std::vector<int32_t> h_out;
+  uint32_t base = 0;
+  for (int b = 0; b < L; ++b) {
+    SLONN_HIP(hipMemsetAsync(hist.p, 0, (size_t)nb * 4, s));
+    SLONN_HIP(hipMemsetAsync(npos.p, 0, (size_t)nb * 4, s));
+    hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, keys.p, L, b, N,
+                       hist.p);
+    SLONN_HIP(hipGetLastError());
+    SLONN_HIP(hipMemcpyAsync(h_hist.data(), hist.p, (size_t)nb * 4, hipMemcpyDeviceToHost, s));
+    SLONN_HIP(hipStreamSynchronize(s));
+    h_start[0] = 0;
+    for (int k = 0; k < nb; ++k) h_start[k + 1] = h_start[k] + h_hist[k];
+    SLONN_HIP(hipMemcpyAsync(start.p, h_start.data(), (size_t)(nb + 1) * 4, hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(bucket_members_kernel, dim3((nb + 63) / 64), dim3(64), 0, s, keys.p, L, b, N, start.p,
+                       nb, members.p);
+    SLONN_HIP(hipGetLastError());
+    hipLaunchKernelGGL(node_score_kernel, dim3((n + 255) / 256, nb), dim3(256), 0, s, act, n, start.p,
+                       members.p, score.p, npos.p);
+    SLONN_HIP(hipGetLastError());
+    SLONN_HIP(hipMemcpyAsync(h_npos.data(), npos.p, (size_t)nb * 4, hipMemcpyDeviceToHost, s));
+    SLONN_HIP(hipStreamSynchronize(s));
+    uint32_t tot = 0;
+    for (int k = 0; k < nb; ++k) {
+      h_len[k] = std::min<uint32_t>(h_npos[k], (uint32_t)cap);
+      h_off[k] = tot;
+      ts->dir[(size_t)b * (nb + 1) + k] = base + tot;
+      tot += h_len[k];
+    }
+    ts->dir[(size_t)b * (nb + 1) + nb] = base + tot;
+    if (tot > 0) {
+      SLONN_HIP(hipMemcpyAsync(off.p, h_off.data(), (size_t)nb * 4, hipMemcpyHostToDevice, s));
+      SLONN_HIP(hipMemcpyAsync(len.p, h_len.data(), (size_t)nb * 4, hipMemcpyHostToDevice, s));
+      hipLaunchKernelGGL(rank_kernel, dim3(nb), dim3(256), 0, s, score.p, n, P, 1, off.p, len.p, out.p);
+      SLONN_HIP(hipGetLastError());
+      h_out.resize(tot);
+      SLONN_HIP(hipMemcpyAsync(h_out.data(), out.p, (size_t)tot * 4, hipMemcpyDeviceToHost, s));
+      SLONN_HIP(hipStreamSynchronize(s));
+      ts->ids.insert(ts->ids.end(), h_out.begin(), h_out.end());
+    }
+    base += tot;
+  }
+
+  // whole-set ranking: every node, zero sums included
+  hipLaunchKernelGGL(total_score_kernel, dim3((n + 255) / 256), dim3(256), 0, s, act, n, N, score.p);
+  SLONN_HIP(hipGetLastError());
+  const uint32_t zero = 0, all = (uint32_t)n;
+  SLONN_HIP(hipMemcpyAsync(off.p, &zero, 4, hipMemcpyHostToDevice, s));
+  SLONN_HIP(hipMemcpyAsync(len.p, &all, 4, hipMemcpyHostToDevice, s));
+  DevBuf<int32_t> gr;
+  SLONN_HIP(gr.alloc(n));
+  hipLaunchKernelGGL(rank_kernel, dim3(1), dim3(256), 0, s, score.p, n, P, 0, off.p, len.p, gr.p);
+  SLONN_HIP(hipGetLastError());
+  SLONN_HIP(hipMemcpyAsync(ts->global_rank.data(), gr.p, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+  SLONN_HIP(hipStreamSynchronize(s));
+  return upload_table_set(ts);
+}
+
+}  // namespace slonn
+
+using namespace slonn;
+
+extern "C" int slonn_build_tables(const slonn_model* m, const slonn_input* X_build, int64_t N, void* stream,
+                                  slonn_tables** out) {
+  if (!out) SLONN_FAIL(SLONN_EINVAL, "out is null");
+  *out = nullptr;
+  if (!m || !X_build) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  if (N <= 0 || N > 0x7FFFFFFF) SLONN_FAIL(SLONN_EINVAL, "N must be in 1 .. 2^31-1");
+  if (X_build->format == SLONN_DENSE) {
+    if (!X_build->x) SLONN_FAIL(SLONN_EINVAL, "dense input pointer is null");
+    if (m->layers[0].w_layout != SLONN_ROWS_ARE_NODES)
+      SLONN_FAIL(SLONN_EUNSUPPORTED, "dense input needs a node-major first layer");
+  } else if (X_build->format == SLONN_ELL) {
+    if (!X_build->idx || !X_build->val || !X_build->nnz || X_build->ell_stride <= 0)
+      SLONN_FAIL(SLONN_EINVAL, "ELL input needs idx, val, nnz and a positive ell_stride");
+    if (m->layers[0].activated())
+      SLONN_FAIL(SLONN_EUNSUPPORTED, "a Node Activator on a sparse-input first layer is not supported");
+  } else {
+    SLONN_FAIL(SLONN_EINVAL, "unknown input format %d", X_build->format);
+  }
+  for (const Layer& L : m->layers)
+    if (L.activated() && L.d_out > SORT_MAX)
+      SLONN_FAIL(SLONN_EUNSUPPORTED, "build: an activated layer has %d nodes, at most %d are supported",
+                 L.d_out, SORT_MAX);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  slonn_tables* t = new (std::nothrow) slonn_tables;
+  if (!t) SLONN_FAIL(SLONN_ENOMEM, "out of host memory");
+  t->model = m;
+  auto fail = [&](int code) {
+    slonn_tables_destroy(t);
+    return code;
+  };
+
+  const int nl = (int)m->layers.size();
+  int last_needed = -1;
+  for (int l = 0; l < nl; ++l)
+    if (m->layers[l].activated()) last_needed = l;
+  float* prev = nullptr;   // Input_l: the full network's output of layer l-1
+  const float* cur = X_build->x;
+  int rc = SLONN_OK;
+  for (int l = 0; l <= last_needed && rc == SLONN_OK; ++l) {
+    const Layer& L = m->layers[l];
+    float* act = nullptr;
+    hipError_t e = hipMalloc(&act, (size_t)N * L.d_out * 4);
+    if (e != hipSuccess) {
+      set_error("build: cannot allocate %zu bytes for layer %d activations", (size_t)N * L.d_out * 4, l);
+      rc = SLONN_ENOMEM;
+      break;
+    }
+    if (l == 0 && X_build->format == SLONN_ELL)
+      rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X_build->idx, X_build->val, X_build->nnz,
+                            X_build->ell_stride, act, L.d_out, (int)N, L.d_in, L.d_out, L.act, s);
+    else
+      rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, L.d_in, act, L.d_out, (int)N, L.d_in, L.d_out,
+                              L.act, s);
+    if (rc == SLONN_OK && L.act == SLONN_ACT_SOFTMAX)
+      rc = launch_finalize(act, L.d_out, L.d_out, nullptr, nullptr, 0, nullptr, 0, 1, nullptr, (int)N, s);
+    if (rc == SLONN_OK && L.activated()) {
+      TableSet ts;
+      rc = build_layer_tables(m, l, cur, N, act, &ts, s);
+      if (rc == SLONN_OK) t->sets.push_back(std::move(ts));
+      else free_table_set(&ts);
+    }
+    if (hipStreamSynchronize(s) != hipSuccess && rc == SLONN_OK) {
+      set_error("build: stream synchronisation failed at layer %d", l);
+      rc = SLONN_EHIP;
+    }
+    if (prev) (void)hipFree(prev);
+    prev = act;
+    cur = act;
+  }
+  if (prev) (void)hipFree(prev);
+  if (rc != SLONN_OK) return fail(rc);
+  *out = t;
+  return SLONN_OK;
+}

@@ -1,0 +1,174 @@
+// Full layer Y = act(X W^T + b): the baseline every SLO-NN speed-up is measured against
+// (Section 3.4: with all nodes computed an SLO-NN does the same work as the full
+// network; Section 4 compares against full forward passes).  This is a real dense
+// contraction, so it runs on the matrix cores: fp32 MFMA 32x32x2, fp32 accumulate,
+// no reduced-precision rounding of the inputs (bf16 weights widen exactly to fp32).
+//
+// 256 threads = 4 wavefronts in a 2x2 arrangement; a block owns a BM x BN tile of Y,
+// each wave a (BM/2) x (BN/2) sub-tile made of 32x32 MFMA blocks.  K is walked in
+// chunks of 32 staged through LDS; the next chunk's global loads are issued before
+// the current chunk's MFMAs so their latency hides behind the matrix work.
+#include "slonn_internal.h"
+
+namespace slonn {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int KC = 32;          // K chunk staged in LDS
+constexpr int LDT = KC + 4;     // padded LDS row (keeps 16-byte alignment, staggers banks)
+
+template <int WDT>
+__device__ __forceinline__ float4 load4(const void* base, size_t elem_off, bool vec, int valid) {
+  // four consecutive K elements starting at elem_off; `valid` of them exist
+  float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (valid <= 0) return r;
+  if (WDT == SLONN_F32) {
+    const float* p = static_cast<const float*>(base) + elem_off;
+    if (vec && valid == 4) return *reinterpret_cast<const float4*>(p);
+    r.x = p[0];
+    if (valid > 1) r.y = p[1];
+    if (valid > 2) r.z = p[2];
+    if (valid > 3) r.w = p[3];
+  } else {
+    const uint16_t* p = static_cast<const uint16_t*>(base) + elem_off;
+    if (vec && valid == 4) {
+      const uint2 u = *reinterpret_cast<const uint2*>(p);
+      r.x = __uint_as_float(u.x << 16);
+      r.y = __uint_as_float(u.x & 0xFFFF0000u);
+      r.z = __uint_as_float(u.y << 16);
+      r.w = __uint_as_float(u.y & 0xFFFF0000u);
+      return r;
+    }
+    r.x = __uint_as_float((uint32_t)p[0] << 16);
+    if (valid > 1) r.y = __uint_as_float((uint32_t)p[1] << 16);
+    if (valid > 2) r.z = __uint_as_float((uint32_t)p[2] << 16);
+    if (valid > 3) r.w = __uint_as_float((uint32_t)p[3] << 16);
+  }
+  return r;
+}
+
+template <int WDT, int BM, int BN>
+__global__ __launch_bounds__(256) void dense_layer_kernel(const void* __restrict__ W,
+                                                         const float* __restrict__ bias,
+                                                         const float* __restrict__ X, int ldx,
+                                                         float* __restrict__ Y, int ldy, int M, int N,
+                                                         int Kd, int act, int vecx, int vecw) {
+  constexpr int WM = BM / 2, WN = BN / 2;          // wave tile
+  constexpr int MB = WM / 32, NB = WN / 32;        // 32x32 MFMA blocks per wave
+  constexpr int PA = BM / 32, PB = BN / 32;        // loader passes (32 rows per pass)
+  __shared__ __align__(16) float As[BM * LDT];
+  __shared__ __align__(16) float Bs[BN * LDT];
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int lrow = tid >> 3, lk = (tid & 7) * 4;   // loader: row within pass, K offset in chunk
+  const int half = lane >> 5, l32 = lane & 31;
+
+  f32x16 acc[MB][NB];
+#pragma unroll
+  for (int a = 0; a < MB; ++a)
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+
+  float4 ra[PA], rb[PB];
+  auto fetch = [&](int k0) {
+    const int kk = k0 + lk;
+    const int valid = Kd - kk < 4 ? Kd - kk : 4;
+#pragma unroll
+    for (int p = 0; p < PA; ++p) {
+      const int row = m0 + lrow + 32 * p;
+      ra[p] = (row < M) ? load4<SLONN_F32>(X, (size_t)row * ldx + kk, vecx, valid)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int p = 0; p < PB; ++p) {
+      const int row = n0 + lrow + 32 * p;
+      rb[p] = (row < N) ? load4<WDT>(W, (size_t)row * Kd + kk, vecw, valid)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int p = 0; p < PA; ++p)
+      *reinterpret_cast<float4*>(&As[(lrow + 32 * p) * LDT + lk]) = ra[p];
+#pragma unroll
+    for (int p = 0; p < PB; ++p)
+      *reinterpret_cast<float4*>(&Bs[(lrow + 32 * p) * LDT + lk]) = rb[p];
+  };
+
+  fetch(0);
+  for (int k0 = 0; k0 < Kd; k0 += KC) {
+    stash();
+    __syncthreads();
+    if (k0 + KC < Kd) fetch(k0 + KC);
+#pragma unroll
+    for (int ks = 0; ks < KC; ks += 8) {
+      // lane (row l32, half) takes K elements ks+4*half .. +3 of its row for A and for B
+      float4 fa[MB], fb[NB];
+#pragma unroll
+      for (int a = 0; a < MB; ++a)
+        fa[a] = *reinterpret_cast<const float4*>(&As[(wm * WM + a * 32 + l32) * LDT + ks + 4 * half]);
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        fb[b] = *reinterpret_cast<const float4*>(&Bs[(wn * WN + b * 32 + l32) * LDT + ks + 4 * half]);
+#pragma unroll
+      for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a].x, fb[b].x, acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a].y, fb[b].y, acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a].z, fb[b].z, acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a].w, fb[b].w, acc[a][b], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+  }
+
+  // 32x32 block layout: register r of lane (l32, half) is row 8*(r/4) + 4*half + r%4, column l32
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const int col = n0 + wn * WN + b * 32 + l32;
+    if (col >= N) continue;
+    const float bv = bias[col];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * WM + a * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (row >= M) continue;
+        float z = acc[a][b][r] + bv;
+        if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+        Y[(size_t)row * ldy + col] = z;
+      }
+  }
+}
+
+}  // namespace
+
+int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
+                       float* Y, int ldy, int B, int d, int n, int act, hipStream_t s) {
+  if (B <= 0) return SLONN_OK;
+  const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
+  const int vecx = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);
+  const int vecw = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(W) % 16 == 0);
+  const long big_tiles = (long)((B + 127) / 128) * ((n + 127) / 128);
+  const bool big = big_tiles >= 512;
+#define SLONN_LAUNCH_DENSE(WDT, BM, BN)                                                            \
+  hipLaunchKernelGGL((dense_layer_kernel<WDT, BM, BN>), dim3((n + BN - 1) / BN, (B + BM - 1) / BM), \
+                     dim3(256), 0, s, W, bias, X, ldx, Y, ldy, B, n, d, a, vecx, vecw)
+  if (w_dtype == SLONN_F32) {
+    if (big) SLONN_LAUNCH_DENSE(SLONN_F32, 128, 128); else SLONN_LAUNCH_DENSE(SLONN_F32, 64, 64);
+  } else {
+    if (big) SLONN_LAUNCH_DENSE(SLONN_BF16, 128, 128); else SLONN_LAUNCH_DENSE(SLONN_BF16, 64, 64);
+  }
+#undef SLONN_LAUNCH_DENSE
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+}  // namespace slonn

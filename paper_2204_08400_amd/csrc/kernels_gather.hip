@@ -1,0 +1,269 @@
+// Sparse layer forward (Section 1 "avoiding computations for these nodes altogether";
+// Fig. 2 step 4): for each query only the selected nodes' weight rows are read and
+// evaluated, y_j = act(w_j . x + b_j); the select kernel has already written +0 for
+// every other node.  The work is a gather of whole contiguous rows: 0.5 flop per byte
+// in fp32, 1 flop per byte with bf16 weights -> bandwidth-bound, plain vector FMAs.
+//
+// Mapping: a 256-thread workgroup serves one query and a chunk of 64 entries of its
+// active list.  The query vector is staged once in LDS.  A row is read by a group of
+// 16 lanes (one DPP row), 16 bytes per lane per step, so every step of a group
+// covers 256 contiguous bytes of one weight row; the four rows a group owns are
+// streamed together so each LDS read of x is used four times and eight 16-byte loads
+// per lane are in flight.
+#include "slonn_internal.h"
+
+namespace slonn {
+namespace {
+
+constexpr int LANES_PER_ROW = 16;
+constexpr int ROWS_PER_GROUP = 4;
+constexpr int ROWS_PER_BLOCK = (256 / LANES_PER_ROW) * ROWS_PER_GROUP;   // 64
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+
+// 16 bytes of a weight row against the matching slice of x (in LDS)
+template <int WDT>
+struct Chunk;
+
+template <>
+struct Chunk<SLONN_F32> {
+  static constexpr int ELEMS = 4;
+  using vec_t = float4;
+  static __device__ __forceinline__ float dot(const vec_t& w, const float* xs, float acc) {
+    const float4 x = *reinterpret_cast<const float4*>(xs);
+    acc = fmaf(w.x, x.x, acc);
+    acc = fmaf(w.y, x.y, acc);
+    acc = fmaf(w.z, x.z, acc);
+    acc = fmaf(w.w, x.w, acc);
+    return acc;
+  }
+  static __device__ __forceinline__ float elem(const void* W, size_t i) {
+    return static_cast<const float*>(W)[i];
+  }
+};
+
+template <>
+struct Chunk<SLONN_BF16> {
+  static constexpr int ELEMS = 8;
+  using vec_t = uint4;
+  static __device__ __forceinline__ float dot(const vec_t& w, const float* xs, float acc) {
+    const float4 x0 = *reinterpret_cast<const float4*>(xs);
+    const float4 x1 = *reinterpret_cast<const float4*>(xs + 4);
+    acc = fmaf(bf16_lo(w.x), x0.x, acc);
+    acc = fmaf(bf16_hi(w.x), x0.y, acc);
+    acc = fmaf(bf16_lo(w.y), x0.z, acc);
+    acc = fmaf(bf16_hi(w.y), x0.w, acc);
+    acc = fmaf(bf16_lo(w.z), x1.x, acc);
+    acc = fmaf(bf16_hi(w.z), x1.y, acc);
+    acc = fmaf(bf16_lo(w.w), x1.z, acc);
+    acc = fmaf(bf16_hi(w.w), x1.w, acc);
+    return acc;
+  }
+  static __device__ __forceinline__ float elem(const void* W, size_t i) {
+    return bf16_lo(static_cast<const uint16_t*>(W)[i]);
+  }
+};
+
+__device__ __forceinline__ float reduce16(float v) {
+  v += __shfl_xor(v, 8, 16);
+  v += __shfl_xor(v, 4, 16);
+  v += __shfl_xor(v, 2, 16);
+  v += __shfl_xor(v, 1, 16);
+  return v;
+}
+
+// VECTOR: rows and x are 16-byte aligned and d is a multiple of the chunk size.
+template <int WDT, bool VECTOR>
+__global__ __launch_bounds__(256) void gather_forward_kernel(
+    const void* __restrict__ W, const float* __restrict__ bias, const float* __restrict__ X, int ldx,
+    const int32_t* __restrict__ active, const int32_t* __restrict__ cnt, int idx_stride,
+    float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int n, int act) {
+  extern __shared__ __align__(16) float xs[];
+  using C = Chunk<WDT>;
+  const int q = blockIdx.y;
+  const int c = active ? cnt[q] : n;
+  const int row0 = blockIdx.x * ROWS_PER_BLOCK;
+  if (row0 >= c) return;
+  const int tid = threadIdx.x;
+  const float* x = X + (size_t)q * ldx;
+  if (VECTOR) {
+    for (int i = tid; i < (d >> 2); i += 256)
+      reinterpret_cast<float4*>(xs)[i] = reinterpret_cast<const float4*>(x)[i];
+  } else {
+    for (int i = tid; i < d; i += 256) xs[i] = x[i];
+  }
+  __syncthreads();
+
+  const int g = tid / LANES_PER_ROW, l = tid % LANES_PER_ROW;
+  const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
+  int t[ROWS_PER_GROUP], j[ROWS_PER_GROUP];
+  float acc[ROWS_PER_GROUP];
+#pragma unroll
+  for (int k = 0; k < ROWS_PER_GROUP; ++k) {
+    t[k] = row0 + g + k * (256 / LANES_PER_ROW);
+    const int tt = t[k] < c ? t[k] : row0;          // surplus slots redo the first row
+    j[k] = list ? list[tt] : tt;
+    acc[k] = 0.0f;
+  }
+  if (t[0] >= c) return;                              // whole group beyond the list
+
+  if (VECTOR) {
+    using vec_t = typename C::vec_t;
+    const int nv = d / C::ELEMS;
+    const vec_t* w0 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                     (size_t)j[0] * d * (WDT == SLONN_F32 ? 4 : 2));
+    const vec_t* w1 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                     (size_t)j[1] * d * (WDT == SLONN_F32 ? 4 : 2));
+    const vec_t* w2 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                     (size_t)j[2] * d * (WDT == SLONN_F32 ? 4 : 2));
+    const vec_t* w3 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                     (size_t)j[3] * d * (WDT == SLONN_F32 ? 4 : 2));
+#pragma unroll 2
+    for (int i = l; i < nv; i += LANES_PER_ROW) {
+      const vec_t a0 = w0[i], a1 = w1[i], a2 = w2[i], a3 = w3[i];
+      const float* xp = xs + i * C::ELEMS;
+      acc[0] = C::dot(a0, xp, acc[0]);
+      acc[1] = C::dot(a1, xp, acc[1]);
+      acc[2] = C::dot(a2, xp, acc[2]);
+      acc[3] = C::dot(a3, xp, acc[3]);
+    }
+  } else {
+    for (int i = l; i < d; i += LANES_PER_ROW) {
+      const float xv = xs[i];
+#pragma unroll
+      for (int k = 0; k < ROWS_PER_GROUP; ++k)
+        acc[k] = fmaf(C::elem(W, (size_t)j[k] * d + i), xv, acc[k]);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < ROWS_PER_GROUP; ++k) acc[k] = reduce16(acc[k]);
+#pragma unroll
+  for (int k = 0; k < ROWS_PER_GROUP; ++k) {
+    if (l == k && t[k] < c) {
+      float z = acc[k] + bias[j[k]];
+      if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+      Y[(size_t)q * ldy + j[k]] = z;
+      if (yc) yc[(size_t)q * ldc + t[k]] = z;
+    }
+  }
+}
+
+// First layer on sparse (ELL) input.  With input-major storage every non-zero pulls
+// one contiguous row of n weights; thread j accumulates node j.
+template <int WDT>
+__global__ __launch_bounds__(256) void ell_layer_kernel(
+    const void* __restrict__ W, int w_layout, const float* __restrict__ bias,
+    const int32_t* __restrict__ idx, const float* __restrict__ val, const int32_t* __restrict__ nnz,
+    int ell_stride, float* __restrict__ Y, int ldy, int d, int n, int act) {
+  using C = Chunk<WDT>;
+  const int q = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const int c = nnz[q];
+  float acc = 0.0f;
+  for (int t = 0; t < c; ++t) {
+    const int i = idx[(size_t)q * ell_stride + t];
+    const float v = val[(size_t)q * ell_stride + t];
+    const size_t at = (w_layout == SLONN_ROWS_ARE_INPUTS) ? (size_t)i * n + j : (size_t)j * d + i;
+    acc = fmaf(C::elem(W, at), v, acc);
+  }
+  float z = acc + bias[j];
+  if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+  Y[(size_t)q * ldy + j] = z;
+}
+
+// Softmax over the computed nodes and/or argmax (lowest id among equal maxima).
+// One wavefront per query.
+__global__ __launch_bounds__(64) void finalize_kernel(float* __restrict__ Y, int ldy, int n,
+                                                     const int32_t* __restrict__ active,
+                                                     const int32_t* __restrict__ cnt, int idx_stride,
+                                                     float* __restrict__ yc, int ldc, int do_softmax,
+                                                     int32_t* __restrict__ argmax) {
+  const int q = blockIdx.x, lane = threadIdx.x;
+  const int c = active ? cnt[q] : n;
+  const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
+  float* y = Y + (size_t)q * ldy;
+  float best = -INFINITY;
+  int besti = 0x7FFFFFFF;
+  for (int t = lane; t < c; t += 64) {
+    const int j = list ? list[t] : t;
+    const float v = y[j];
+    if (v > best || (v == best && j < besti)) { best = v; besti = j; }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ob = __shfl_xor(best, o);
+    const int oi = __shfl_xor(besti, o);
+    if (ob > best || (ob == best && oi < besti)) { best = ob; besti = oi; }
+  }
+  if (argmax && lane == 0) argmax[q] = besti;
+  if (!do_softmax) return;
+  float sum = 0.0f;
+  for (int t = lane; t < c; t += 64) {
+    const int j = list ? list[t] : t;
+    sum += expf(y[j] - best);
+  }
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  const float inv = 1.0f / sum;
+  for (int t = lane; t < c; t += 64) {
+    const int j = list ? list[t] : t;
+    const float p = expf(y[j] - best) * inv;
+    y[j] = p;
+    if (yc) yc[(size_t)q * ldc + t] = p;
+  }
+}
+
+}  // namespace
+
+int launch_gather_forward(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
+                          const int32_t* active, const int32_t* cnt, int idx_stride, int max_rows,
+                          float* Y, int ldy, float* yc, int ldc, int B, int d, int n, int act,
+                          hipStream_t s) {
+  if (max_rows <= 0 || B <= 0) return SLONN_OK;
+  const int esz = (w_dtype == SLONN_F32) ? 4 : 2;
+  const int chunk = 16 / esz;
+  const bool vec = (d % chunk == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(W) % 16 == 0) &&
+                   (reinterpret_cast<uintptr_t>(X) % 16 == 0);
+  const size_t lds = ((size_t)d + 8) * sizeof(float);
+  if (lds > 65536) SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
+  dim3 grid((max_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, B);
+  const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
+#define SLONN_LAUNCH_GATHER(WDT, VEC)                                                              \
+  hipLaunchKernelGGL((gather_forward_kernel<WDT, VEC>), grid, dim3(256), lds, s, W, bias, X, ldx,  \
+                     active, cnt, idx_stride, Y, ldy, yc, ldc, d, n, a)
+  if (w_dtype == SLONN_F32) {
+    if (vec) SLONN_LAUNCH_GATHER(SLONN_F32, true); else SLONN_LAUNCH_GATHER(SLONN_F32, false);
+  } else {
+    if (vec) SLONN_LAUNCH_GATHER(SLONN_BF16, true); else SLONN_LAUNCH_GATHER(SLONN_BF16, false);
+  }
+#undef SLONN_LAUNCH_GATHER
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+int launch_ell_layer(const void* W, int w_dtype, int w_layout, const float* bias, const int32_t* idx,
+                     const float* val, const int32_t* nnz, int ell_stride, float* Y, int ldy, int B,
+                     int d, int n, int act, hipStream_t s) {
+  dim3 grid((n + 255) / 256, B);
+  const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
+  if (w_dtype == SLONN_F32)
+    hipLaunchKernelGGL((ell_layer_kernel<SLONN_F32>), grid, dim3(256), 0, s, W, w_layout, bias, idx, val,
+                       nnz, ell_stride, Y, ldy, d, n, a);
+  else
+    hipLaunchKernelGGL((ell_layer_kernel<SLONN_BF16>), grid, dim3(256), 0, s, W, w_layout, bias, idx,
+                       val, nnz, ell_stride, Y, ldy, d, n, a);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+int launch_finalize(float* Y, int ldy, int n, const int32_t* active, const int32_t* cnt,
+                    int idx_stride, float* yc, int ldc, int do_softmax, int32_t* argmax, int B,
+                    hipStream_t s) {
+  if (!do_softmax && !argmax) return SLONN_OK;
+  hipLaunchKernelGGL(finalize_kernel, dim3(B), dim3(64), 0, s, Y, ldy, n, active, cnt, idx_stride, yc,
+                     ldc, do_softmax, argmax);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+}  // namespace slonn

@@ -1,0 +1,509 @@
+// Host side of libslonn: argument validation, handles, the table blob, workspace
+// carving and the per-layer launch sequence.  No arithmetic of the method lives here.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "slonn_internal.h"
+
+namespace slonn {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// Carves the caller's workspace into the per-batch buffers of the forward pass.
+struct Workspace {
+  float* act[2] = {nullptr, nullptr};   // ping-pong layer outputs [B][max_n]
+  float* z = nullptr;                   // [B][max_H]
+  int32_t* active = nullptr;            // [B][max_n_activated]
+  int32_t* cnt = nullptr;               // [B]
+  float* keep_one = nullptr;            // one float holding 1.0 (unused slots)
+  size_t bytes = 0;
+  int max_n = 0, max_H = 0, max_na = 0;
+};
+
+void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
+  int max_n = 0, max_H = 0, max_na = 0;
+  for (const Layer& l : m->layers) {
+    max_n = std::max(max_n, l.d_out);
+    if (l.activated()) {
+      max_H = std::max(max_H, l.H());
+      max_na = std::max(max_na, l.d_out);
+    }
+  }
+  w->max_n = max_n; w->max_H = max_H; w->max_na = max_na;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off += align_up(bytes);
+    return p;
+  };
+  w->act[0] = reinterpret_cast<float*>(take((size_t)B * max_n * 4));
+  w->act[1] = reinterpret_cast<float*>(take((size_t)B * max_n * 4));
+  w->z = reinterpret_cast<float*>(take((size_t)B * std::max(max_H, 1) * 4));
+  w->active = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
+  w->cnt = reinterpret_cast<int32_t*>(take((size_t)B * 4));
+  w->bytes = off;
+}
+
+int check_input(const slonn_model* m, const slonn_input* X) {
+  if (!X) SLONN_FAIL(SLONN_EINVAL, "input descriptor is null");
+  if (X->format == SLONN_DENSE) {
+    if (!X->x) SLONN_FAIL(SLONN_EINVAL, "dense input pointer is null");
+    if (m->layers[0].w_layout != SLONN_ROWS_ARE_NODES)
+      SLONN_FAIL(SLONN_EUNSUPPORTED, "dense input needs a node-major first layer");
+  } else if (X->format == SLONN_ELL) {
+    if (!X->idx || !X->val || !X->nnz || X->ell_stride <= 0)
+      SLONN_FAIL(SLONN_EINVAL, "ELL input needs idx, val, nnz and a positive ell_stride");
+    if (m->layers[0].activated())
+      SLONN_FAIL(SLONN_EUNSUPPORTED, "a Node Activator on a sparse-input first layer is not supported");
+  } else {
+    SLONN_FAIL(SLONN_EINVAL, "unknown input format %d", X->format);
+  }
+  return SLONN_OK;
+}
+
+}  // namespace
+}  // namespace slonn
+
+using namespace slonn;
+
+extern "C" {
+
+const char* slonn_last_error(void) { return g_err; }
+
+int slonn_version(char* buf, size_t cap) {
+  if (!buf || cap == 0) SLONN_FAIL(SLONN_EINVAL, "null buffer");
+  snprintf(buf, cap, "slonn 0.1 (gfx950, wave64, HIP %d.%d)", HIP_VERSION_MAJOR, HIP_VERSION_MINOR);
+  return SLONN_OK;
+}
+
+int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model** out) {
+  if (!out) SLONN_FAIL(SLONN_EINVAL, "out is null");
+  *out = nullptr;
+  if (!layers || n_layers <= 0) SLONN_FAIL(SLONN_EINVAL, "no layers");
+  for (int l = 0; l < n_layers; ++l) {
+    const slonn_layer_desc& d = layers[l];
+    if (d.d_in <= 0 || d.d_out <= 0) SLONN_FAIL(SLONN_EINVAL, "layer %d: non-positive size", l);
+    if (l > 0 && d.d_in != layers[l - 1].d_out)
+      SLONN_FAIL(SLONN_EINVAL, "layer %d: d_in %d does not match previous d_out %d", l, d.d_in,
+                 layers[l - 1].d_out);
+    if (!d.W || !d.bias) SLONN_FAIL(SLONN_EINVAL, "layer %d: null weights or bias", l);
+    if (d.w_dtype != SLONN_F32 && d.w_dtype != SLONN_BF16)
+      SLONN_FAIL(SLONN_EINVAL, "layer %d: unknown weight type %d", l, d.w_dtype);
+    if (d.act != SLONN_ACT_NONE && d.act != SLONN_ACT_RELU && d.act != SLONN_ACT_SOFTMAX)
+      SLONN_FAIL(SLONN_EINVAL, "layer %d: unknown activation %d", l, d.act);
+    if (d.act == SLONN_ACT_SOFTMAX && l != n_layers - 1)
+      SLONN_FAIL(SLONN_EINVAL, "layer %d: softmax is only supported on the last layer", l);
+    if (d.w_layout != SLONN_ROWS_ARE_NODES && d.w_layout != SLONN_ROWS_ARE_INPUTS)
+      SLONN_FAIL(SLONN_EINVAL, "layer %d: unknown weight layout %d", l, d.w_layout);
+    if (d.w_layout == SLONN_ROWS_ARE_INPUTS && (l != 0 || d.K > 0 || d.L > 0))
+      SLONN_FAIL(SLONN_EUNSUPPORTED,
+                 "layer %d: input-major weights are only supported on a first layer without a Node Activator", l);
+    if ((d.K > 0) != (d.L > 0) || d.K < 0 || d.L < 0)
+      SLONN_FAIL(SLONN_EINVAL, "layer %d: K and L must both be positive or both zero", l);
+    if (d.K > SLONN_MAX_K) SLONN_FAIL(SLONN_EINVAL, "layer %d: K %d exceeds %d", l, d.K, SLONN_MAX_K);
+    if (d.L > SLONN_MAX_L) SLONN_FAIL(SLONN_EINVAL, "layer %d: L %d exceeds %d", l, d.L, SLONN_MAX_L);
+    if (d.K > 0) {
+      const long H = (long)d.K * d.L;
+      if (H > d.d_out) SLONN_FAIL(SLONN_EINVAL, "layer %d: K*L = %ld exceeds its %d nodes", l, H, d.d_out);
+      if (!d.hash_nodes) SLONN_FAIL(SLONN_EINVAL, "layer %d: hash_nodes is null", l);
+      if (d.list_cap <= 0) SLONN_FAIL(SLONN_EINVAL, "layer %d: list_cap must be positive", l);
+      std::vector<int32_t> s(d.hash_nodes, d.hash_nodes + H);
+      for (int32_t v : s)
+        if (v < 0 || v >= d.d_out) SLONN_FAIL(SLONN_EINVAL, "layer %d: hash node %d out of range", l, v);
+      std::sort(s.begin(), s.end());
+      if (std::adjacent_find(s.begin(), s.end()) != s.end())
+        SLONN_FAIL(SLONN_EINVAL, "layer %d: hash nodes are not distinct", l);
+    }
+  }
+
+  slonn_model* m = new (std::nothrow) slonn_model;
+  if (!m) SLONN_FAIL(SLONN_ENOMEM, "out of host memory");
+  m->layers.resize(n_layers);
+  for (int l = 0; l < n_layers; ++l) {
+    const slonn_layer_desc& d = layers[l];
+    Layer& L = m->layers[l];
+    L.d_in = d.d_in; L.d_out = d.d_out; L.w_dtype = d.w_dtype; L.w_layout = d.w_layout;
+    L.act = d.act; L.K = d.K; L.L = d.L; L.list_cap = d.K > 0 ? d.list_cap : 0;
+    L.W = d.W; L.bias = d.bias;
+    if (d.K > 0) L.hash_nodes.assign(d.hash_nodes, d.hash_nodes + (size_t)d.K * d.L);
+  }
+
+  auto fail = [&](int code) {
+    slonn_model_destroy(m);
+    return code;
+  };
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) {
+    set_error("hipGetDevice failed: %s", hipGetErrorString(e));
+    return fail(SLONN_EHIP);
+  }
+  int v = 0;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0)
+    m->max_lds_bytes = v;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+    m->n_cu = v;
+
+  // library-owned fp32 copies of the FreeHash rows, gathered once
+  for (Layer& L : m->layers) {
+    if (!L.activated()) continue;
+    const int H = L.H();
+    const size_t esz = L.w_dtype == SLONN_F32 ? 4 : 2;
+    std::vector<char> row((size_t)L.d_in * esz);
+    std::vector<float> wh((size_t)H * L.d_in), bh(H);
+    for (int h = 0; h < H; ++h) {
+      const char* src = static_cast<const char*>(L.W) + (size_t)L.hash_nodes[h] * L.d_in * esz;
+      e = hipMemcpy(row.data(), src, row.size(), hipMemcpyDeviceToHost);
+      if (e == hipSuccess)
+        e = hipMemcpy(&bh[h], L.bias + L.hash_nodes[h], sizeof(float), hipMemcpyDeviceToHost);
+      if (e != hipSuccess) {
+        set_error("copying FreeHash rows failed: %s", hipGetErrorString(e));
+        return fail(SLONN_EHIP);
+      }
+      for (int i = 0; i < L.d_in; ++i) {
+        if (L.w_dtype == SLONN_F32) {
+          std::memcpy(&wh[(size_t)h * L.d_in + i], row.data() + (size_t)i * 4, 4);
+        } else {
+          uint16_t b;
+          std::memcpy(&b, row.data() + (size_t)i * 2, 2);
+          uint32_t u = (uint32_t)b << 16;
+          std::memcpy(&wh[(size_t)h * L.d_in + i], &u, 4);
+        }
+      }
+    }
+    if ((e = hipMalloc(&L.Wh, wh.size() * 4)) != hipSuccess || (e = hipMalloc(&L.bh, bh.size() * 4)) != hipSuccess ||
+        (e = hipMemcpy(L.Wh, wh.data(), wh.size() * 4, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(L.bh, bh.data(), bh.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) {
+      set_error("uploading FreeHash rows failed: %s", hipGetErrorString(e));
+      return fail(SLONN_EHIP);
+    }
+  }
+  *out = m;
+  return SLONN_OK;
+}
+
+int slonn_model_destroy(slonn_model* m) {
+  if (!m) return SLONN_OK;
+  for (Layer& L : m->layers) {
+    if (L.Wh) (void)hipFree(L.Wh);
+    if (L.bh) (void)hipFree(L.bh);
+  }
+  delete m;
+  return SLONN_OK;
+}
+
+int slonn_workspace_bytes(const slonn_model* m, int B_max, size_t* out) {
+  if (!m || !out) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  if (B_max <= 0) SLONN_FAIL(SLONN_EINVAL, "B_max must be positive");
+  Workspace w;
+  plan_workspace(m, B_max, nullptr, &w);
+  *out = w.bytes;
+  return SLONN_OK;
+}
+
+// ------------------------------------------------------------------------------------ //
+// tables
+// ------------------------------------------------------------------------------------ //
+int slonn_tables_destroy(slonn_tables* t) {
+  if (!t) return SLONN_OK;
+  for (TableSet& s : t->sets) free_table_set(&s);
+  delete t;
+  return SLONN_OK;
+}
+
+int slonn_tables_export(const slonn_tables* t, void* host_buf, size_t* bytes) {
+  if (!t || !bytes) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  size_t need = 16;
+  for (const TableSet& s : t->sets)
+    need += 32 + 4 * ((size_t)s.K * s.L + s.dir.size() + s.ids.size() + s.global_rank.size());
+  if (!host_buf) {
+    *bytes = need;
+    return SLONN_OK;
+  }
+  if (*bytes < need) SLONN_FAIL(SLONN_ENOMEM, "export buffer holds %zu bytes, %zu needed", *bytes, need);
+  char* p = static_cast<char*>(host_buf);
+  auto put = [&](const void* src, size_t n) {
+    std::memcpy(p, src, n);
+    p += n;
+  };
+  const uint32_t head[4] = {SLONN_TABLE_BLOB_MAGIC, SLONN_TABLE_BLOB_VERSION, (uint32_t)t->sets.size(), 0};
+  put(head, 16);
+  for (const TableSet& s : t->sets) {
+    const uint32_t h[8] = {(uint32_t)s.layer, (uint32_t)s.K, (uint32_t)s.L, (uint32_t)s.n,
+                           (uint32_t)s.list_cap, (uint32_t)s.ids.size(), 0, 0};
+    put(h, 32);
+    const Layer& L = t->model->layers[s.layer];
+    put(L.hash_nodes.data(), 4 * L.hash_nodes.size());
+    put(s.dir.data(), 4 * s.dir.size());
+    put(s.ids.data(), 4 * s.ids.size());
+    put(s.global_rank.data(), 4 * s.global_rank.size());
+  }
+  *bytes = need;
+  return SLONN_OK;
+}
+
+int slonn_tables_import(const slonn_model* m, const void* host_buf, size_t bytes, slonn_tables** out) {
+  if (!out) SLONN_FAIL(SLONN_EINVAL, "out is null");
+  *out = nullptr;
+  if (!m || !host_buf) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  const char* p = static_cast<const char*>(host_buf);
+  const char* end = p + bytes;
+  auto have = [&](size_t n) { return (size_t)(end - p) >= n; };
+  uint32_t head[4];
+  if (!have(16)) SLONN_FAIL(SLONN_EINVAL, "blob shorter than its header");
+  std::memcpy(head, p, 16);
+  p += 16;
+  if (head[0] != SLONN_TABLE_BLOB_MAGIC || head[1] != SLONN_TABLE_BLOB_VERSION)
+    SLONN_FAIL(SLONN_EINVAL, "not a table blob (magic %08x version %u)", head[0], head[1]);
+  slonn_tables* t = new (std::nothrow) slonn_tables;
+  if (!t) SLONN_FAIL(SLONN_ENOMEM, "out of host memory");
+  t->model = m;
+  auto fail = [&](int code) {
+    slonn_tables_destroy(t);
+    return code;
+  };
+  for (uint32_t i = 0; i < head[2]; ++i) {
+    uint32_t h[8];
+    if (!have(32)) { set_error("blob truncated in set %u header", i); return fail(SLONN_EINVAL); }
+    std::memcpy(h, p, 32);
+    p += 32;
+    TableSet s;
+    s.layer = (int)h[0]; s.K = (int)h[1]; s.L = (int)h[2]; s.n = (int)h[3]; s.list_cap = (int)h[4];
+    const size_t total = h[5];
+    if (s.layer < 0 || s.layer >= (int)m->layers.size()) {
+      set_error("set %u names layer %d", i, s.layer);
+      return fail(SLONN_EINVAL);
+    }
+    const Layer& L = m->layers[s.layer];
+    if (!L.activated() || L.K != s.K || L.L != s.L || L.d_out != s.n) {
+      set_error("set %u (layer %d, K %d, L %d, n %d) does not match the model", i, s.layer, s.K, s.L, s.n);
+      return fail(SLONN_EINVAL);
+    }
+    if (t->for_layer(s.layer)) { set_error("layer %d appears twice", s.layer); return fail(SLONN_EINVAL); }
+    const size_t H = (size_t)s.K * s.L, nd = (size_t)s.L * (((size_t)1 << s.K) + 1);
+    if (!have(4 * (H + nd + total + (size_t)s.n))) {
+      set_error("blob truncated in set %u body", i);
+      return fail(SLONN_EINVAL);
+    }
+    if (std::memcmp(p, L.hash_nodes.data(), 4 * H) != 0) {
+      set_error("set %u was built with different hash nodes", i);
+      return fail(SLONN_EINVAL);
+    }
+    p += 4 * H;
+    s.dir.resize(nd);
+    std::memcpy(s.dir.data(), p, 4 * nd);
+    p += 4 * nd;
+    s.ids.resize(total);
+    std::memcpy(s.ids.data(), p, 4 * total);
+    p += 4 * total;
+    s.global_rank.resize(s.n);
+    std::memcpy(s.global_rank.data(), p, 4 * (size_t)s.n);
+    p += 4 * (size_t)s.n;
+    // structural checks: offsets monotone and inside ids, ids and ranking in range, ranking a permutation
+    uint32_t prev = 0;
+    for (uint32_t v : s.dir) {
+      if (v < prev || v > total) { set_error("set %u: bucket offsets not monotone", i); return fail(SLONN_EINVAL); }
+      prev = v;
+    }
+    for (int32_t v : s.ids)
+      if (v < 0 || v >= s.n) { set_error("set %u: node id %d out of range", i, v); return fail(SLONN_EINVAL); }
+    std::vector<char> seen(s.n, 0);
+    for (int32_t v : s.global_rank) {
+      if (v < 0 || v >= s.n || seen[v]) { set_error("set %u: ranking is not a permutation", i); return fail(SLONN_EINVAL); }
+      seen[v] = 1;
+    }
+    int rc = upload_table_set(&s);
+    if (rc != SLONN_OK) {
+      free_table_set(&s);
+      return fail(rc);
+    }
+    t->sets.push_back(std::move(s));
+  }
+  for (size_t l = 0; l < m->layers.size(); ++l)
+    if (m->layers[l].activated() && !t->for_layer((int)l)) {
+      set_error("blob has no tables for activated layer %zu", l);
+      return fail(SLONN_EINVAL);
+    }
+  *out = t;
+  return SLONN_OK;
+}
+
+// ------------------------------------------------------------------------------------ //
+// select / forward
+// ------------------------------------------------------------------------------------ //
+int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const float* X_l, int B,
+                 const float* keep, int keep_stride, uint32_t* codes_out, float* z_out,
+                 int32_t* active_idx, int32_t* active_cnt, int idx_stride, void* workspace,
+                 size_t ws_bytes, void* stream) {
+  if (!m || !t || !X_l || !keep || !active_idx || !active_cnt) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  if (t->model != m) SLONN_FAIL(SLONN_EINVAL, "tables belong to another model");
+  if (B <= 0) SLONN_FAIL(SLONN_EINVAL, "B must be positive");
+  if (layer < 0 || layer >= (int)m->layers.size()) SLONN_FAIL(SLONN_EINVAL, "no layer %d", layer);
+  if (keep_stride < 0) SLONN_FAIL(SLONN_EINVAL, "negative keep stride");
+  const Layer& L = m->layers[layer];
+  const TableSet* ts = t->for_layer(layer);
+  if (!L.activated() || !ts) SLONN_FAIL(SLONN_EINVAL, "layer %d has no Node Activator", layer);
+  if (idx_stride < L.d_out)
+    SLONN_FAIL(SLONN_ECAP, "idx_stride %d is below the layer's %d nodes", idx_stride, L.d_out);
+  float* z = z_out;
+  if (!z) {
+    const size_t need = (size_t)B * L.H() * 4;
+    if (!workspace || ws_bytes < need)
+      SLONN_FAIL(SLONN_ENOMEM, "workspace holds %zu bytes, %zu needed", ws_bytes, need);
+    z = static_cast<float*>(workspace);
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int rc = launch_hash_project(X_l, L.d_in, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
+  if (rc) return rc;
+  return launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank, keep, keep_stride,
+                       B, codes_out, active_idx, active_cnt, idx_stride, nullptr, 0, m->max_lds_bytes, s);
+}
+
+int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
+                         const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
+                         const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
+                         void* stream) {
+  if (!m || !X || !keep || !Y) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  if (B <= 0) SLONN_FAIL(SLONN_EINVAL, "B must be positive");
+  if (keep_qstride < 0 || keep_lstride < 0) SLONN_FAIL(SLONN_EINVAL, "negative keep stride");
+  int rc = check_input(m, X);
+  if (rc) return rc;
+  bool any_activated = false;
+  for (const Layer& L : m->layers) any_activated |= L.activated();
+  if (any_activated) {
+    if (!t) SLONN_FAIL(SLONN_EINVAL, "tables are null but the model has activated layers");
+    if (t->model != m) SLONN_FAIL(SLONN_EINVAL, "tables belong to another model");
+  }
+  const int nl = (int)m->layers.size();
+  const Layer& last = m->layers[nl - 1];
+  if ((Y->idx || Y->val) && last.activated()) {
+    if (!Y->cnt) SLONN_FAIL(SLONN_EINVAL, "compact output needs cnt");
+    if (Y->stride < last.d_out)
+      SLONN_FAIL(SLONN_ECAP, "compact output stride %d is below the last layer's %d nodes", Y->stride,
+                 last.d_out);
+  }
+  Workspace w;
+  plan_workspace(m, B, static_cast<char*>(workspace), &w);
+  if (!workspace || ws_bytes < w.bytes)
+    SLONN_FAIL(SLONN_ENOMEM, "workspace holds %zu bytes, %zu needed", ws_bytes, w.bytes);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  const float* cur = X->x;
+  int ldcur = m->layers[0].d_in;
+  for (int l = 0; l < nl; ++l) {
+    const Layer& L = m->layers[l];
+    const bool is_last = (l == nl - 1);
+    float* tap_out = taps && taps->layer_out ? taps->layer_out[l] : nullptr;
+    // write straight into the caller's buffer when one exists for this layer
+    float* out = is_last && Y->dense ? Y->dense : (tap_out ? tap_out : w.act[l & 1]);
+    const int ldo = L.d_out;
+    const int act = L.act;
+    const int32_t* act_list = nullptr;
+    const int32_t* act_cnt = nullptr;
+    int act_stride = 0;
+    float* yc = nullptr;
+    if (L.activated()) {
+      const TableSet* ts = t->for_layer(l);
+      float* z = taps && taps->z && taps->z[l] ? taps->z[l] : w.z;
+      uint32_t* codes = taps && taps->codes ? taps->codes[l] : nullptr;
+      int32_t* aidx = taps && taps->active_idx && taps->active_idx[l] ? taps->active_idx[l] : w.active;
+      int32_t* acnt = taps && taps->active_cnt && taps->active_cnt[l] ? taps->active_cnt[l] : w.cnt;
+      int astride = L.d_out;
+      if (is_last && Y->idx) { aidx = Y->idx; astride = Y->stride; }
+      if (is_last && Y->cnt) acnt = Y->cnt;
+      rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
+      if (rc) return rc;
+      rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank,
+                         keep + (size_t)l * keep_lstride, keep_qstride, B, codes, aidx, acnt, astride, out,
+                         ldo, m->max_lds_bytes, s);
+      if (rc) return rc;
+      act_list = aidx; act_cnt = acnt; act_stride = astride;
+      if (is_last && Y->val) yc = Y->val;
+      rc = launch_gather_forward(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, L.d_out, out, ldo,
+                                 yc, Y->stride, B, L.d_in, L.d_out, act, s);
+      if (rc) return rc;
+      if (is_last && Y->idx && taps && taps->active_idx && taps->active_idx[l] && taps->active_idx[l] != Y->idx) {
+        // both a tap and a compact output were requested: the tap gets a copy
+        SLONN_HIP(hipMemcpy2DAsync(taps->active_idx[l], (size_t)L.d_out * 4, Y->idx, (size_t)Y->stride * 4,
+                                   (size_t)L.d_out * 4, B, hipMemcpyDeviceToDevice, s));
+      }
+    } else if (l == 0 && X->format == SLONN_ELL) {
+      rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
+                            ldo, B, L.d_in, L.d_out, act, s);
+      if (rc) return rc;
+    } else {
+      rc = launch_gather_forward(L.W, L.w_dtype, L.bias, cur, ldcur, nullptr, nullptr, 0, L.d_out, out, ldo,
+                                 nullptr, 0, B, L.d_in, L.d_out, act, s);
+      if (rc) return rc;
+    }
+    if (is_last) {
+      if (!L.activated() && Y->cnt) {
+        if (Y->idx && Y->stride < L.d_out)
+          SLONN_FAIL(SLONN_ECAP, "compact output stride %d is below the last layer's %d nodes", Y->stride,
+                     L.d_out);
+        rc = launch_fill_iota(Y->idx, Y->stride, Y->cnt, L.d_out, B, s);
+        if (rc) return rc;
+      }
+      rc = launch_finalize(out, ldo, L.d_out, act_list, act_cnt, act_stride, yc, Y->stride,
+                           act == SLONN_ACT_SOFTMAX, Y->argmax, B, s);
+      if (rc) return rc;
+      if (tap_out && tap_out != out)
+        SLONN_HIP(hipMemcpyAsync(tap_out, out, (size_t)B * L.d_out * 4, hipMemcpyDeviceToDevice, s));
+    }
+    cur = out;
+    ldcur = ldo;
+  }
+  return SLONN_OK;
+}
+
+int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float* Y, int32_t* argmax,
+                        float** layer_out, void* workspace, size_t ws_bytes, void* stream) {
+  if (!m || !X || !Y) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  if (B <= 0) SLONN_FAIL(SLONN_EINVAL, "B must be positive");
+  int rc = check_input(m, X);
+  if (rc) return rc;
+  Workspace w;
+  plan_workspace(m, B, static_cast<char*>(workspace), &w);
+  if (!workspace || ws_bytes < w.bytes)
+    SLONN_FAIL(SLONN_ENOMEM, "workspace holds %zu bytes, %zu needed", ws_bytes, w.bytes);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int nl = (int)m->layers.size();
+  const float* cur = X->x;
+  int ldcur = m->layers[0].d_in;
+  for (int l = 0; l < nl; ++l) {
+    const Layer& L = m->layers[l];
+    const bool is_last = (l == nl - 1);
+    float* out = is_last ? Y : (layer_out && layer_out[l] ? layer_out[l] : w.act[l & 1]);
+    if (l == 0 && X->format == SLONN_ELL)
+      rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
+                            L.d_out, B, L.d_in, L.d_out, L.act, s);
+    else
+      rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, L.d_out, B, L.d_in, L.d_out, L.act, s);
+    if (rc) return rc;
+    if (is_last) {
+      rc = launch_finalize(out, L.d_out, L.d_out, nullptr, nullptr, 0, nullptr, 0, L.act == SLONN_ACT_SOFTMAX,
+                           argmax, B, s);
+      if (rc) return rc;
+      if (layer_out && layer_out[l] && layer_out[l] != out)
+        SLONN_HIP(hipMemcpyAsync(layer_out[l], out, (size_t)B * L.d_out * 4, hipMemcpyDeviceToDevice, s));
+    }
+    cur = out;
+    ldcur = L.d_out;
+  }
+  return SLONN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,116 @@
+// Internal declarations shared by the host side of libslonn and its kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "slonn.h"
+
+namespace slonn {
+
+void set_error(const char* fmt, ...);
+
+#define SLONN_FAIL(code, ...)        \
+  do {                               \
+    ::slonn::set_error(__VA_ARGS__); \
+    return (code);                   \
+  } while (0)
+
+#define SLONN_HIP(call)                                                                    \
+  do {                                                                                     \
+    hipError_t e_ = (call);                                                                \
+    if (e_ != hipSuccess) {                                                                \
+      ::slonn::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__,  \
+                         __LINE__);                                                        \
+      return SLONN_EHIP;                                                                   \
+    }                                                                                      \
+  } while (0)
+
+struct Layer {
+  int d_in = 0, d_out = 0;
+  int w_dtype = SLONN_F32, w_layout = SLONN_ROWS_ARE_NODES, act = SLONN_ACT_NONE;
+  int K = 0, L = 0, list_cap = 0;
+  const void* W = nullptr;       // borrowed device
+  const float* bias = nullptr;   // borrowed device
+  std::vector<int32_t> hash_nodes;
+  // library-owned device copies of the FreeHash rows (always fp32) and their biases
+  float* Wh = nullptr;           // [H][d_in]
+  float* bh = nullptr;           // [H]
+  int H() const { return K * L; }
+  bool activated() const { return K > 0 && L > 0; }
+};
+
+struct TableSet {                 // Node Importance tables of one layer
+  int layer = -1, K = 0, L = 0, n = 0, list_cap = 0;
+  std::vector<uint32_t> dir;      // host copy [L][2^K+1]
+  std::vector<int32_t> ids, global_rank;
+  uint32_t* d_dir = nullptr;      // device copies
+  int32_t* d_ids = nullptr;
+  int32_t* d_global_rank = nullptr;
+};
+
+}  // namespace slonn
+
+struct slonn_model {
+  std::vector<slonn::Layer> layers;
+  int max_lds_bytes = 65536;      // per-workgroup LDS the device grants on request
+  int n_cu = 256;
+};
+
+struct slonn_tables {
+  const slonn_model* model = nullptr;
+  std::vector<slonn::TableSet> sets;            // one per activated layer
+  const slonn::TableSet* for_layer(int l) const {
+    for (const auto& s : sets)
+      if (s.layer == l) return &s;
+    return nullptr;
+  }
+};
+
+namespace slonn {
+
+// ---- kernel launchers (each validates nothing: callers have checked shapes) ----
+
+// Z[q][h] = Wh[h] . X[q] + bh[h], fp64 accumulation, rounded once to fp32.
+int launch_hash_project(const float* X, int ldx, const float* Wh, const float* bh, float* Z, int B,
+                        int H, int d, hipStream_t s);
+
+// keys + bucket lookup + merge for one layer.  yzero (nullable): [B][ldy] rows to clear.
+int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,
+                  const int32_t* global_rank, const float* keep, int keep_stride, int B,
+                  uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
+                  int ldy, int max_lds, hipStream_t s);
+
+// y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).
+// yc (nullable) receives the values in list order.
+int launch_gather_forward(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
+                          const int32_t* active, const int32_t* cnt, int idx_stride, int max_rows,
+                          float* Y, int ldy, float* yc, int ldc, int B, int d, int n, int act,
+                          hipStream_t s);
+
+// First layer on ELL input: y[q][j] = act(sum_t val[q][t] * W(j, idx[q][t]) + b[j]).
+int launch_ell_layer(const void* W, int w_dtype, int w_layout, const float* bias, const int32_t* idx,
+                     const float* val, const int32_t* nnz, int ell_stride, float* Y, int ldy, int B,
+                     int d, int n, int act, hipStream_t s);
+
+// Softmax over the computed nodes (in place on Y and yc) and/or argmax, one wave per query.
+int launch_finalize(float* Y, int ldy, int n, const int32_t* active, const int32_t* cnt,
+                    int idx_stride, float* yc, int ldc, int do_softmax, int32_t* argmax, int B,
+                    hipStream_t s);
+
+// Dense layer Y = act(X W^T + b) as an MFMA GEMM (fp32 matrix cores).
+int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
+                       float* Y, int ldy, int B, int d, int n, int act, hipStream_t s);
+
+int launch_fill_iota(int32_t* idx, int stride, int32_t* cnt, int n, int B, hipStream_t s);
+
+// Alg. 1 on the device for one layer; fills ts (host + device copies).
+int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_t N, const float* act,
+                       TableSet* ts, hipStream_t s);
+int upload_table_set(TableSet* ts);
+void free_table_set(TableSet* ts);
+
+}  // namespace slonn

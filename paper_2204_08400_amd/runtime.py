@@ -1,0 +1,143 @@
+"""Convenience holder around the C-ABI binding: uploads a synthetic network's
+arrays with PyTorch (device memory only), keeps the handles and the workspace,
+and returns outputs as tensors.  No arithmetic happens here."""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import slonn
+
+
+def _dev(a: np.ndarray, device):
+    if a.dtype == np.uint16:          # bf16 bit patterns
+        return torch.from_numpy(a.view(np.int16).copy()).to(device)
+    if a.dtype == np.uint32:
+        return torch.from_numpy(a.view(np.int32).copy()).to(device)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+class Network:
+    def __init__(self, layers: Sequence, device="cuda:0", first_layer_rows_are_inputs=False):
+        """layers: workloads.LayerData-like objects (host numpy arrays)."""
+        self.device = torch.device(device)
+        self.host_layers = list(layers)
+        descs = []
+        for i, l in enumerate(layers):
+            descs.append(dict(
+                d_in=l.d_in, d_out=l.d_out, w_dtype=l.w_dtype, act=l.act, K=l.K, L=l.L,
+                list_cap=l.list_cap,
+                w_layout=slonn.ROWS_ARE_INPUTS if (i == 0 and first_layer_rows_are_inputs) else slonn.ROWS_ARE_NODES,
+                W=_dev(np.ascontiguousarray(l.W), self.device), bias=_dev(l.bias, self.device),
+                hash_nodes=None if l.hash_nodes is None else [int(v) for v in l.hash_nodes]))
+        self.model = slonn.slonn_model_create(descs)
+        self.n_layers = len(descs)
+        self.dims_out = [l.d_out for l in layers]
+        self.tables: Optional[slonn.Tables] = None
+        self._ws = None
+        self._ws_B = 0
+
+    # -- helpers -------------------------------------------------------------- #
+    def workspace(self, B: int):
+        if self._ws is None or B > self._ws_B:
+            nbytes = slonn.slonn_workspace_bytes(self.model, B)
+            self._ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self._ws_B = B
+        return self._ws
+
+    def to_input(self, X) -> slonn.Input:
+        if isinstance(X, slonn.Input):
+            return X
+        if isinstance(X, tuple):
+            idx, val, nnz = (t if torch.is_tensor(t) else _dev(np.ascontiguousarray(t), self.device) for t in X)
+            return slonn.make_input(idx=idx, val=val, nnz=nnz)
+        x = X if torch.is_tensor(X) else _dev(np.ascontiguousarray(X, np.float32), self.device)
+        return slonn.make_input(x=x)
+
+    @staticmethod
+    def batch_of(inp: slonn.Input) -> int:
+        x, idx, _, _ = inp._keep
+        return int(x.shape[0] if x is not None else idx.shape[0])
+
+    # -- tables --------------------------------------------------------------- #
+    def build_tables(self, X_build):
+        inp = self.to_input(X_build)
+        self.tables = slonn.slonn_build_tables(self.model, inp, self.batch_of(inp))
+        return self.tables
+
+    def import_tables(self, blob: bytes):
+        self.tables = slonn.slonn_tables_import(self.model, blob)
+        return self.tables
+
+    def export_tables(self) -> bytes:
+        return slonn.slonn_tables_export(self.tables)
+
+    # -- forward -------------------------------------------------------------- #
+    def sparse_forward(self, X, keep, taps: bool = False, compact: bool = False):
+        """keep: device float tensor [B] or [B][n_layers], or a python float."""
+        inp = self.to_input(X)
+        B = self.batch_of(inp)
+        dev = self.device
+        if not torch.is_tensor(keep):
+            keep = torch.full((1,), float(keep), dtype=torch.float32, device=dev)
+            qs, ls = 0, 0
+        elif keep.dim() == 1:
+            qs, ls = (1 if keep.numel() > 1 else 0), 0
+        else:
+            qs, ls = keep.shape[1], 1
+        n_last = self.dims_out[-1]
+        res = {}
+        dense = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+        argmax = torch.empty(B, dtype=torch.int32, device=dev)
+        kw = dict(dense=dense, argmax=argmax)
+        if compact:
+            res["idx"] = torch.full((B, n_last), -1, dtype=torch.int32, device=dev)
+            res["val"] = torch.zeros((B, n_last), dtype=torch.float32, device=dev)
+            res["cnt"] = torch.zeros(B, dtype=torch.int32, device=dev)
+            kw.update(idx=res["idx"], val=res["val"], cnt=res["cnt"], stride=n_last)
+        out = slonn.make_output(**kw)
+        tp = None
+        if taps:
+            codes, z, aidx, acnt, lout = [], [], [], [], []
+            for l in self.host_layers:
+                act = l.K > 0 and l.L > 0
+                codes.append(torch.zeros((B, l.L), dtype=torch.int32, device=dev) if act else None)
+                z.append(torch.zeros((B, l.K * l.L), dtype=torch.float32, device=dev) if act else None)
+                aidx.append(torch.full((B, l.d_out), -1, dtype=torch.int32, device=dev) if act else None)
+                acnt.append(torch.zeros(B, dtype=torch.int32, device=dev) if act else None)
+                lout.append(torch.empty((B, l.d_out), dtype=torch.float32, device=dev))
+            tp = slonn.make_taps(self.n_layers, codes, z, aidx, acnt, lout)
+            res["taps"] = dict(codes=codes, z=z, active=aidx, cnt=acnt, out=lout)
+        slonn.slonn_sparse_forward(self.model, self.tables, inp, B, keep, qs, ls, out, tp, self.workspace(B))
+        res["out"], res["argmax"] = dense, argmax
+        return res
+
+    def dense_forward(self, X, layer_outs: bool = False):
+        inp = self.to_input(X)
+        B = self.batch_of(inp)
+        dev = self.device
+        Y = torch.empty((B, self.dims_out[-1]), dtype=torch.float32, device=dev)
+        argmax = torch.empty(B, dtype=torch.int32, device=dev)
+        louts = None
+        if layer_outs:
+            louts = [torch.empty((B, n), dtype=torch.float32, device=dev) for n in self.dims_out]
+        slonn.slonn_dense_forward(self.model, inp, B, Y, argmax, louts, self.workspace(B))
+        return {"out": Y, "argmax": argmax, "layers": louts}
+
+    def select(self, layer: int, X_l, keep):
+        l = self.host_layers[layer]
+        x = X_l if torch.is_tensor(X_l) else _dev(np.ascontiguousarray(X_l, np.float32), self.device)
+        B = x.shape[0]
+        dev = self.device
+        if not torch.is_tensor(keep):
+            keep = torch.full((1,), float(keep), dtype=torch.float32, device=dev)
+        ks = 1 if keep.numel() > 1 else 0
+        codes = torch.zeros((B, l.L), dtype=torch.int32, device=dev)
+        z = torch.zeros((B, l.K * l.L), dtype=torch.float32, device=dev)
+        aidx = torch.full((B, l.d_out), -1, dtype=torch.int32, device=dev)
+        acnt = torch.zeros(B, dtype=torch.int32, device=dev)
+        slonn.slonn_select(self.model, self.tables, layer, x, B, keep, ks, codes, z, aidx, acnt, l.d_out,
+                           self.workspace(B))
+        return {"codes": codes, "z": z, "active": aidx, "cnt": acnt}

@@ -1,0 +1,257 @@
+"""ctypes binding of libslonn.so: argument marshalling only.
+
+Every step of the path (hash projection, selection, gathered-row forward, dense
+baseline, table build) runs in the HIP library; PyTorch appears here only as the
+owner of device memory and of the stream the kernels are enqueued on.  There is
+no CPU fallback: if the library is missing, or a call fails, an exception is
+raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libslonn.so")
+
+OK, EINVAL, ENOMEM, EHIP, EUNSUPPORTED, ECAP = 0, -1, -2, -3, -4, -5
+F32, BF16 = 0, 1
+ROWS_ARE_NODES, ROWS_ARE_INPUTS = 0, 1
+ACT_NONE, ACT_RELU, ACT_SOFTMAX = 0, 1, 2
+DENSE, ELL = 0, 1
+
+EXPORTS = [
+    "slonn_version", "slonn_model_create", "slonn_model_destroy", "slonn_build_tables",
+    "slonn_tables_export", "slonn_tables_import", "slonn_tables_destroy", "slonn_workspace_bytes",
+    "slonn_select", "slonn_sparse_forward", "slonn_dense_forward", "slonn_last_error",
+]
+
+
+class SlonnError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"slonn error {code}: {msg}")
+        self.code = code
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("w_dtype", C.c_int32),
+                ("w_layout", C.c_int32), ("act", C.c_int32), ("K", C.c_int32), ("L", C.c_int32),
+                ("list_cap", C.c_int32), ("W", C.c_void_p), ("bias", C.c_void_p),
+                ("hash_nodes", C.POINTER(C.c_int32))]
+
+
+class Input(C.Structure):
+    _fields_ = [("format", C.c_int32), ("x", C.c_void_p), ("idx", C.c_void_p), ("val", C.c_void_p),
+                ("nnz", C.c_void_p), ("ell_stride", C.c_int32)]
+
+
+class Output(C.Structure):
+    _fields_ = [("dense", C.c_void_p), ("idx", C.c_void_p), ("val", C.c_void_p), ("cnt", C.c_void_p),
+                ("stride", C.c_int32), ("argmax", C.c_void_p)]
+
+
+class DebugTaps(C.Structure):
+    _fields_ = [("codes", C.POINTER(C.c_void_p)), ("z", C.POINTER(C.c_void_p)),
+                ("active_idx", C.POINTER(C.c_void_p)), ("active_cnt", C.POINTER(C.c_void_p)),
+                ("layer_out", C.POINTER(C.c_void_p))]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load the library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2204_08400_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        lib.slonn_last_error.restype = C.c_char_p
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise SlonnError(rc, load().slonn_last_error().decode(errors="replace"))
+
+
+def _ptr(t) -> Optional[int]:
+    """device pointer of a torch tensor (or None)"""
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        if not torch.cuda.is_available():
+            return None
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def slonn_version() -> str:
+    buf = C.create_string_buffer(128)
+    _check(load().slonn_version(buf, C.c_size_t(128)))
+    return buf.value.decode()
+
+
+class Model:
+    """Owns a slonn_model handle; keeps the weight tensors it borrows alive."""
+
+    def __init__(self, layers: Sequence[dict]):
+        """layers: dicts with d_in, d_out, W (device tensor), bias (device tensor),
+        act, w_dtype, w_layout, K, L, list_cap, hash_nodes (host int32 sequence)."""
+        self._keep = []
+        descs = (LayerDesc * len(layers))()
+        for i, l in enumerate(layers):
+            d = descs[i]
+            d.d_in, d.d_out = int(l["d_in"]), int(l["d_out"])
+            d.w_dtype = int(l.get("w_dtype", F32))
+            d.w_layout = int(l.get("w_layout", ROWS_ARE_NODES))
+            d.act = int(l.get("act", ACT_NONE))
+            d.K, d.L = int(l.get("K", 0)), int(l.get("L", 0))
+            d.list_cap = int(l.get("list_cap", 0))
+            d.W = _ptr(l["W"]) if l.get("W") is not None else None
+            d.bias = _ptr(l["bias"]) if l.get("bias") is not None else None
+            hn = l.get("hash_nodes")
+            if hn is not None:
+                arr = (C.c_int32 * len(hn))(*[int(v) for v in hn])
+                self._keep.append(arr)
+                d.hash_nodes = C.cast(arr, C.POINTER(C.c_int32))
+            self._keep += [l.get("W"), l.get("bias")]
+        self.layers = [dict(l) for l in layers]
+        self.n_layers = len(layers)
+        h = C.c_void_p()
+        _check(load().slonn_model_create(descs, len(layers), C.byref(h)))
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            load().slonn_model_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+
+class Tables:
+    def __init__(self, model: Model, handle: C.c_void_p):
+        self.model, self.h = model, handle
+
+    def close(self):
+        if getattr(self, "h", None):
+            load().slonn_tables_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+
+def make_input(x=None, idx=None, val=None, nnz=None) -> Input:
+    inp = Input()
+    if x is not None:
+        inp.format, inp.x = DENSE, _ptr(x)
+    else:
+        inp.format = ELL
+        inp.idx, inp.val, inp.nnz = _ptr(idx), _ptr(val), _ptr(nnz)
+        inp.ell_stride = int(idx.shape[1])
+    inp._keep = (x, idx, val, nnz)
+    return inp
+
+
+def slonn_model_create(layers: Sequence[dict]) -> Model:
+    return Model(layers)
+
+
+def slonn_build_tables(model: Model, X_build: Input, N: int, stream=None) -> Tables:
+    h = C.c_void_p()
+    _check(load().slonn_build_tables(model.h, C.byref(X_build), C.c_int64(N),
+                                     C.c_void_p(_stream_ptr(stream)), C.byref(h)))
+    return Tables(model, h)
+
+
+def slonn_tables_export(tables: Tables) -> bytes:
+    n = C.c_size_t(0)
+    _check(load().slonn_tables_export(tables.h, None, C.byref(n)))
+    buf = C.create_string_buffer(n.value)
+    _check(load().slonn_tables_export(tables.h, buf, C.byref(n)))
+    return buf.raw[:n.value]
+
+
+def slonn_tables_import(model: Model, blob: bytes) -> Tables:
+    h = C.c_void_p()
+    _check(load().slonn_tables_import(model.h, blob, C.c_size_t(len(blob)), C.byref(h)))
+    return Tables(model, h)
+
+
+def slonn_workspace_bytes(model: Model, B_max: int) -> int:
+    n = C.c_size_t(0)
+    _check(load().slonn_workspace_bytes(model.h, int(B_max), C.byref(n)))
+    return n.value
+
+
+def slonn_select(model: Model, tables: Tables, layer: int, X_l, B: int, keep, keep_stride: int,
+                 codes_out, z_out, active_idx, active_cnt, idx_stride: int, workspace, stream=None):
+    _check(load().slonn_select(
+        model.h, tables.h, int(layer), C.c_void_p(_ptr(X_l)), int(B), C.c_void_p(_ptr(keep)),
+        int(keep_stride), C.c_void_p(_ptr(codes_out)), C.c_void_p(_ptr(z_out)),
+        C.c_void_p(_ptr(active_idx)), C.c_void_p(_ptr(active_cnt)), int(idx_stride),
+        C.c_void_p(_ptr(workspace)), C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
+        C.c_void_p(_stream_ptr(stream))))
+
+
+def _ptr_array(tensors: Optional[Sequence], n: int):
+    if tensors is None:
+        return None
+    arr = (C.c_void_p * n)()
+    for i, t in enumerate(tensors):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def make_taps(n_layers: int, codes=None, z=None, active_idx=None, active_cnt=None, layer_out=None):
+    taps = DebugTaps()
+    keep = []
+    for name, lst in (("codes", codes), ("z", z), ("active_idx", active_idx),
+                      ("active_cnt", active_cnt), ("layer_out", layer_out)):
+        arr = _ptr_array(lst, n_layers)
+        keep.append((arr, lst))
+        if arr is not None:
+            setattr(taps, name, C.cast(arr, C.POINTER(C.c_void_p)))
+    taps._keep = keep
+    return taps
+
+
+def make_output(dense=None, idx=None, val=None, cnt=None, stride=0, argmax=None) -> Output:
+    out = Output()
+    out.dense, out.idx, out.val, out.cnt = _ptr(dense), _ptr(idx), _ptr(val), _ptr(cnt)
+    out.stride, out.argmax = int(stride), _ptr(argmax)
+    out._keep = (dense, idx, val, cnt, argmax)
+    return out
+
+
+def slonn_sparse_forward(model: Model, tables: Optional[Tables], X: Input, B: int, keep,
+                         keep_qstride: int, keep_lstride: int, Y: Output, taps: Optional[DebugTaps],
+                         workspace, stream=None):
+    _check(load().slonn_sparse_forward(
+        model.h, tables.h if tables is not None else None, C.byref(X), int(B),
+        C.c_void_p(_ptr(keep)), int(keep_qstride), int(keep_lstride), C.byref(Y),
+        C.byref(taps) if taps is not None else None, C.c_void_p(_ptr(workspace)),
+        C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
+        C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_dense_forward(model: Model, X: Input, B: int, Y, argmax, layer_out: Optional[Sequence],
+                        workspace, stream=None):
+    arr = _ptr_array(layer_out, model.n_layers)
+    _check(load().slonn_dense_forward(
+        model.h, C.byref(X), int(B), C.c_void_p(_ptr(Y)), C.c_void_p(_ptr(argmax)),
+        C.cast(arr, C.POINTER(C.c_void_p)) if arr is not None else None,
+        C.c_void_p(_ptr(workspace)),
+        C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
+        C.c_void_p(_stream_ptr(stream))))

@@ -1,0 +1,102 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "slonn.h")
+
+
+@pytest.fixture(scope="module")
+def slonn():
+    from paper_2204_08400_amd import build, slonn as s
+    if not os.path.exists(s.LIB_PATH):
+        build.build_library()
+    s.load()
+    return s
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(slonn_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(slonn):
+    names = _declared()
+    assert len(names) >= 12
+    lib = slonn.load()
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in slonn.h but not exported"
+    assert set(names) == set(slonn.EXPORTS)
+
+
+def test_version_string(slonn):
+    assert "gfx950" in slonn.slonn_version()
+
+
+class _FakeTensor:
+    """stands in for a device tensor: validation never dereferences it"""
+    def __init__(self, addr=0x1000):
+        self._a = addr
+    def is_contiguous(self):
+        return True
+    def data_ptr(self):
+        return self._a
+
+
+def _layer(**kw):
+    d = dict(d_in=8, d_out=16, W=_FakeTensor(), bias=_FakeTensor(), act=1, K=0, L=0)
+    d.update(kw)
+    return d
+
+
+@pytest.mark.parametrize("layers, code", [
+    ([], -1),
+    ([_layer(d_in=0)], -1),
+    ([_layer(W=None)], -1),
+    ([_layer(), _layer(d_in=17)], -1),                                   # d_in mismatch
+    ([_layer(act=2), _layer(d_in=16)], -1),                              # softmax before the last layer
+    ([_layer(K=17, L=1, hash_nodes=list(range(17)), list_cap=4)], -1),   # K too large
+    ([_layer(K=1, L=65, hash_nodes=list(range(65)), list_cap=4, d_out=128)], -1),
+    ([_layer(K=3, L=6, hash_nodes=list(range(18)), list_cap=4)], -1),    # K*L > d_out
+    ([_layer(K=2, L=2, hash_nodes=[0, 1, 2, 2], list_cap=4)], -1),       # duplicate hash node
+    ([_layer(K=2, L=2, hash_nodes=[0, 1, 2, 16], list_cap=4)], -1),      # out of range
+    ([_layer(K=2, L=2, hash_nodes=[0, 1, 2, 3], list_cap=0)], -1),
+    ([_layer(K=2, L=0)], -1),
+    ([_layer(w_dtype=7)], -1),
+    ([_layer(), _layer(d_in=16, w_layout=1)], -4),                       # input-major beyond layer 0
+    ([_layer(w_layout=1, K=2, L=2, hash_nodes=[0, 1, 2, 3], list_cap=4)], -4),
+])
+def test_model_create_rejects(slonn, layers, code):
+    with pytest.raises(slonn.SlonnError) as e:
+        slonn.slonn_model_create(layers)
+    assert e.value.code == code
+    assert str(e.value)
+
+
+def test_null_handles_are_rejected(slonn):
+    lib = slonn.load()
+    n = C.c_size_t(0)
+    assert lib.slonn_workspace_bytes(None, 4, C.byref(n)) == slonn.EINVAL
+    assert lib.slonn_tables_export(None, None, C.byref(n)) == slonn.EINVAL
+    h = C.c_void_p()
+    assert lib.slonn_tables_import(None, b"x", C.c_size_t(1), C.byref(h)) == slonn.EINVAL
+    assert lib.slonn_build_tables(None, None, C.c_int64(1), None, C.byref(h)) == slonn.EINVAL
+    assert lib.slonn_sparse_forward(None, None, None, 1, None, 0, 0, None, None, None, C.c_size_t(0), None) == slonn.EINVAL
+    assert lib.slonn_dense_forward(None, None, 1, None, None, None, None, C.c_size_t(0), None) == slonn.EINVAL
+    assert lib.slonn_select(None, None, 0, None, 1, None, 0, None, None, None, None, 0, None, C.c_size_t(0), None) == slonn.EINVAL
+    assert lib.slonn_model_destroy(None) == 0 and lib.slonn_tables_destroy(None) == 0
+    assert slonn.load().slonn_last_error()
+
+
+def test_binding_fails_loudly_without_library(slonn, monkeypatch, tmp_path):
+    import importlib
+    monkeypatch.setattr(slonn, "LIB_PATH", str(tmp_path / "nope.so"))
+    monkeypatch.setattr(slonn, "_lib", None)
+    with pytest.raises(FileNotFoundError):
+        slonn.load()
