@@ -422,8 +422,11 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       int32_t* aidx = taps && taps->active_idx && taps->active_idx[l] ? taps->active_idx[l] : w.active;
       int32_t* acnt = taps && taps->active_cnt && taps->active_cnt[l] ? taps->active_cnt[l] : w.cnt;
       int astride = L.d_out;
-      if (is_last && Y->idx) { aidx = Y->idx; astride = Y->stride; }
-      if (is_last && Y->cnt) acnt = Y->cnt;
+      // the caller's compact output doubles as the active list unless a tap already does
+      const bool tap_idx = taps && taps->active_idx && taps->active_idx[l];
+      const bool tap_cnt = taps && taps->active_cnt && taps->active_cnt[l];
+      if (is_last && Y->idx && !tap_idx) { aidx = Y->idx; astride = Y->stride; }
+      if (is_last && Y->cnt && !tap_cnt) acnt = Y->cnt;
       rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
       if (rc) return rc;
       rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank,
@@ -435,11 +438,11 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       rc = launch_gather_forward(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, L.d_out, out, ldo,
                                  yc, Y->stride, B, L.d_in, L.d_out, act, s);
       if (rc) return rc;
-      if (is_last && Y->idx && taps && taps->active_idx && taps->active_idx[l] && taps->active_idx[l] != Y->idx) {
-        // both a tap and a compact output were requested: the tap gets a copy
-        SLONN_HIP(hipMemcpy2DAsync(taps->active_idx[l], (size_t)L.d_out * 4, Y->idx, (size_t)Y->stride * 4,
+      if (is_last && Y->idx && tap_idx)
+        SLONN_HIP(hipMemcpy2DAsync(Y->idx, (size_t)Y->stride * 4, aidx, (size_t)astride * 4,
                                    (size_t)L.d_out * 4, B, hipMemcpyDeviceToDevice, s));
-      }
+      if (is_last && Y->cnt && tap_cnt)
+        SLONN_HIP(hipMemcpyAsync(Y->cnt, acnt, (size_t)B * 4, hipMemcpyDeviceToDevice, s));
     } else if (l == 0 && X->format == SLONN_ELL) {
       rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
                             ldo, B, L.d_in, L.d_out, act, s);

@@ -82,14 +82,16 @@ def compare_sparse(res_gpu: dict, res_ref: dict, layers, what=""):
                 c = ref["cnt"][q]
                 assert np.array_equal(g["active"][l][q, :c], ref["active"][q, :c]), \
                     f"{what} layer {l} query {q}: active list differs"
-            np.testing.assert_allclose(g["z"][l][ok], ref["z"][ok], rtol=1e-6, atol=1e-7,
+            # projections of layer l > 0 inherit the fp32 rounding of the previous layer's output
+            zs = max(float(np.abs(ref["z"]).max()), 1e-30)
+            np.testing.assert_allclose(g["z"][l][ok], ref["z"][ok], rtol=REL_TOL, atol=1e-6 * zs,
                                        err_msg=f"{what} layer {l}: hash projections")
         ok = ~tainted
         rep["max_rel_err"] = max(rep["max_rel_err"],
                                  assert_close_rows(g["out"][l], ref["out"], ok, f"{what} layer {l} output"))
         # dropped nodes are exactly +0 on both sides
-        zero_ref = (ref["out"] == 0)
-        assert not np.signbit(g["out"][l]).any() or lay.act != wl.ACT_RELU
+        if lay.act == wl.ACT_RELU:
+            assert not np.signbit(g["out"][l]).any(), f"{what} layer {l}: negative zero or value after ReLU"
         if lay.K > 0:
             for q in np.nonzero(ok)[0][:64]:
                 mask = np.ones(lay.d_out, bool)
