@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the SLO-NN hot path on one MI355X.
+
+A step is one pass of the whole path (FreeHash projection, key + bucket lookup + merge,
+gathered-row forward, for every layer) over one batch of synthetic queries that already
+sit in HBM.  Workload: the 784-1024-1024-10 fp32 MLP, K=8, L=16 on both hidden layers,
+batch 256, keep fraction 0.25 (the other keep fractions of that workload, and the dense
+MFMA baseline, are timed briefly and reported beside it).  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--keep", type=float, default=0.25)
+    ap.add_argument("--config", default="C2")
+    ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: the path is data-parallel over queries with nothing "
+                 "exchanged between GPUs, and this build has no multi-GPU leg (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    from paper_2204_08400_amd import runtime, slonn, workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    slonn.load()
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    B = args.batch or cfg.batches[-1]
+    K, W = args.steps, args.warmup
+
+    # ---- synthetic workload (seeds: weights 0, build set 1, queries 2, hash nodes 3) ----
+    t0 = time.time()
+    layers = wl.make_mlp(cfg.dims, seed=0, w_dtype=cfg.w_dtype, last_act=cfg.last_act)
+    X_build = wl.make_inputs(cfg, cfg.n_inputs, seed=1)
+    X_query = wl.make_inputs(cfg, cfg.n_inputs, seed=2)
+    log(f"generated {args.config} in {time.time() - t0:.1f}s")
+
+    # hash nodes: variance of the full network's activations on the build set (device dense pass)
+    plain = runtime.Network(layers)
+    xb = torch.from_numpy(X_build).to(dev)
+    dn = plain.dense_forward(xb, layer_outs=True)
+    for l in cfg.hashed_layers:
+        var = dn["layers"][l].double().var(dim=0, unbiased=False).cpu().numpy()
+        layers[l].K, layers[l].L = cfg.K, cfg.L
+        layers[l].list_cap = layers[l].d_out
+        layers[l].hash_nodes = wl.sample_hash_nodes(var, cfg.K, cfg.L, seed=3 + l)
+    del plain, dn
+    net = runtime.Network(layers)
+    t0 = time.time()
+    net.build_tables(xb)
+    log(f"built tables on the device in {time.time() - t0:.2f}s")
+
+    xq = torch.from_numpy(X_query).to(dev)
+    nq = xq.shape[0]
+    n_batches = nq // B
+    batches = [slonn.make_input(x=xq[i * B:(i + 1) * B]) for i in range(n_batches)]
+    n_last = cfg.dims[-1]
+    out_dense = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+    out_arg = torch.empty(B, dtype=torch.int32, device=dev)
+    out = slonn.make_output(dense=out_dense, argmax=out_arg)
+    ws = net.workspace(B)
+    stream = torch.cuda.current_stream()
+
+    def run(keep_t, steps, first=0):
+        for i in range(steps):
+            slonn.slonn_sparse_forward(net.model, net.tables, batches[(first + i) % n_batches], B, keep_t,
+                                       0, 0, out, None, ws, stream)
+
+    def timed(keep, steps, warm):
+        keep_t = torch.full((1,), keep, dtype=torch.float32, device=dev)
+        run(keep_t, warm)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        run(keep_t, steps, warm)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return e0.elapsed_time(e1) / 1e3, wall
+
+    def gathered_bytes_per_query(keep):
+        tot = 0
+        for l, lay in enumerate(layers):
+            esz = 4 if lay.w_dtype == wl.W_F32 else 2
+            if lay.K > 0:
+                m = int(min(lay.d_out, max(1, np.floor(np.float64(np.float32(keep)) * lay.d_out + 0.5))))
+                tot += m * lay.d_in * esz
+        return tot
+
+    # ---- headline: K steps at the chosen keep fraction ----
+    dev_s, wall_s = timed(args.keep, K, W)
+    secs = max(dev_s, wall_s)             # the host loop must keep up: report the slower clock
+    qps = K * B / secs
+    eff_gbps = qps * gathered_bytes_per_query(args.keep) / 1e9
+    log(f"keep {args.keep}: {qps:,.0f} q/s, {secs / K * 1e6:.1f} us/step, effective {eff_gbps:,.0f} GB/s")
+
+    # ---- per-kernel durations over the same steps (HIP events on the launch stream) ----
+    keep_t = torch.full((1,), args.keep, dtype=torch.float32, device=dev)
+    slonn.slonn_profile_begin(K * 16)
+    run(keep_t, K, W)
+    prof = slonn.slonn_profile_end()
+    split_us = {k: (v[0] * 1e3 / max(v[1], 1)) for k, v in prof.items() if v[1]}
+    per_step_us = {k: v[0] * 1e3 / K for k, v in prof.items() if v[1]}
+    # dominant kernel: the gathered-row forward.  Algorithmic bytes per launch = selected rows x row
+    # bytes (activated layers) or the whole small matrix per query (output layer), averaged over its
+    # launches in a step.
+    g_ms, g_n = prof["gather"]
+    bytes_per_step = 0
+    for lay in layers:
+        esz = 4 if lay.w_dtype == wl.W_F32 else 2
+        if lay.K > 0:
+            m = int(min(lay.d_out, max(1, np.floor(np.float64(np.float32(args.keep)) * lay.d_out + 0.5))))
+        else:
+            m = lay.d_out
+        bytes_per_step += B * m * lay.d_in * esz
+    launches_per_step = g_n / K
+    avg_launch_s = g_ms / 1e3 / g_n
+    achieved = (bytes_per_step / launches_per_step) / avg_launch_s / 1e9
+    roofline = {"bound": "hbm", "kernel": "gather_forward_kernel", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": None, "avg_launch_us": round(avg_launch_s * 1e6, 2),
+                "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)}
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            roofline["traffic"] = json.load(open(tpath)).get(f"{args.config}_keep{args.keep}_B{B}")
+        except Exception:
+            pass
+
+    extra = {"effective_GBps": round(eff_gbps, 1), "frac_of_hbm_peak": round(eff_gbps / HBM_PEAK_GBPS, 4),
+             "per_step_us": {k: round(v, 2) for k, v in per_step_us.items()},
+             "avg_launch_us": {k: round(v, 2) for k, v in split_us.items()}}
+
+    # ---- the other keep fractions and the dense baseline, briefly ----
+    if not args.no_sweep:
+        sweep = {}
+        for keep in cfg.keeps:
+            d_s, w_s = timed(keep, 120, 20)
+            s = max(d_s, w_s)
+            q = 120 * B / s
+            sweep[str(keep)] = {"qps": round(q), "effective_GBps": round(q * gathered_bytes_per_query(keep) / 1e9, 1)}
+        extra["sweep"] = sweep
+        yd = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+        for i in range(20):
+            slonn.slonn_dense_forward(net.model, batches[i % n_batches], B, yd, out_arg, None, ws, stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(120):
+            slonn.slonn_dense_forward(net.model, batches[i % n_batches], B, yd, out_arg, None, ws, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        extra["dense_baseline_qps"] = round(120 * B / (e0.elapsed_time(e1) / 1e3))
+
+    # ---- CPU baseline: the oracle as it stands, on the host cores, bounded sample ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import slonn_oracle
+        onet = slonn_oracle.OracleNet(layers)
+        onet.import_tables(net.export_tables())
+        n_s = min(nq, 4096)
+        t0 = time.perf_counter()
+        onet.sparse_forward(X_query[:n_s], args.keep, taps=False)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(n_s / dt, 1), "unit": "queries/s", "cores": onet.threads, "kind": "oracle",
+               "sample": f"first {n_s} queries of the same query set, keep {args.keep}, all layers, "
+                         f"{onet.threads} threads over queries"}
+
+    line = {
+        "metric": "queries/sec and effective HBM GB/s (vs peak) for sparse forward at keep-fraction",
+        "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(secs / K * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if cfg.w_dtype == wl.W_F32 else "bf16 weights, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{args.config}: MLP {'-'.join(map(str, cfg.dims))}, K={cfg.K} L={cfg.L} on "
+                               f"{len(cfg.hashed_layers)} hidden layers, {nq} queries", "batch": B,
+                   "keep": args.keep, "queries_per_step": B},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    line.update(extra)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -183,6 +183,17 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
 int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float* Y, int32_t* argmax,
                         float** layer_out, void* workspace, size_t ws_bytes, void* stream);
 
+/* Per-kernel timing for measurement runs.  Between begin and end every kernel the
+ * select / forward calls launch is bracketed by two HIP events recorded on the launch
+ * stream (at most max_launches of them; later launches go untimed).  end synchronises
+ * the device, adds up the elapsed time and launch count per kernel kind into the two
+ * caller arrays of SLONN_PROF_KINDS entries (HOST), and switches timing off again.
+ * Not thread-safe; costs two event records per launch while on.                     */
+enum { SLONN_PROF_HASH = 0, SLONN_PROF_SELECT = 1, SLONN_PROF_GATHER = 2, SLONN_PROF_DENSE = 3,
+       SLONN_PROF_ELL = 4, SLONN_PROF_FINALIZE = 5, SLONN_PROF_KINDS = 6 };
+int slonn_profile_begin(int max_launches);
+int slonn_profile_end(double* ms_per_kind, int64_t* launches_per_kind);
+
 const char* slonn_last_error(void);
 
 #ifdef __cplusplus

@@ -152,6 +152,7 @@ __global__ __launch_bounds__(256) void dense_layer_kernel(const void* __restrict
 
 int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                        float* Y, int ldy, int B, int d, int n, int act, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_DENSE, s);
   if (B <= 0) return SLONN_OK;
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
   const int vecx = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);

@@ -219,6 +219,7 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
                           const int32_t* active, const int32_t* cnt, int idx_stride, int max_rows,
                           float* Y, int ldy, float* yc, int ldc, int B, int d, int n, int act,
                           hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_GATHER, s);
   if (max_rows <= 0 || B <= 0) return SLONN_OK;
   const int esz = (w_dtype == SLONN_F32) ? 4 : 2;
   const int chunk = 16 / esz;
@@ -244,6 +245,7 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
 int launch_ell_layer(const void* W, int w_dtype, int w_layout, const float* bias, const int32_t* idx,
                      const float* val, const int32_t* nnz, int ell_stride, float* Y, int ldy, int B,
                      int d, int n, int act, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_ELL, s);
   dim3 grid((n + 255) / 256, B);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
   if (w_dtype == SLONN_F32)
@@ -259,6 +261,7 @@ int launch_ell_layer(const void* W, int w_dtype, int w_layout, const float* bias
 int launch_finalize(float* Y, int ldy, int n, const int32_t* active, const int32_t* cnt,
                     int idx_stride, float* yc, int ldc, int do_softmax, int32_t* argmax, int B,
                     hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_FINALIZE, s);
   if (!do_softmax && !argmax) return SLONN_OK;
   hipLaunchKernelGGL(finalize_kernel, dim3(B), dim3(64), 0, s, Y, ldy, n, active, cnt, idx_stride, yc,
                      ldc, do_softmax, argmax);

@@ -65,6 +65,7 @@ __global__ __launch_bounds__(256) void hash_project_kernel(const float* __restri
 
 int launch_hash_project(const float* X, int ldx, const float* Wh, const float* bh, float* Z, int B,
                         int H, int d, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_HASH, s);
   dim3 grid((H + TH - 1) / TH, (B + TQ - 1) / TQ);
   hipLaunchKernelGGL(hash_project_kernel, grid, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H, d);
   SLONN_HIP(hipGetLastError());

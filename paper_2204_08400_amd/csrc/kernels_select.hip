@@ -145,6 +145,7 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
                   int ldy, int max_lds, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_SELECT, s);
   const size_t lds = 512 + (((size_t)n + 3) & ~(size_t)3);
   if (lds > (size_t)max_lds)
     SLONN_FAIL(SLONN_EUNSUPPORTED, "select: layer with %d nodes needs %zu bytes of LDS, device grants %d",

@@ -19,6 +19,25 @@ void set_error(const char* fmt, ...) {
 }
 
 namespace {
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> start, stop;
+  std::vector<int> kind;
+  size_t used = 0;
+} g_prof;
+}  // namespace
+
+ProfScope::ProfScope(int kind, hipStream_t s) : slot(-1), stream(s) {
+  if (!g_prof.on || g_prof.used >= g_prof.start.size()) return;
+  slot = (int)g_prof.used++;
+  g_prof.kind[slot] = kind;
+  (void)hipEventRecord(g_prof.start[slot], stream);
+}
+ProfScope::~ProfScope() {
+  if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], stream);
+}
+
+namespace {
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
@@ -82,6 +101,43 @@ using namespace slonn;
 extern "C" {
 
 const char* slonn_last_error(void) { return g_err; }
+
+int slonn_profile_begin(int max_launches) {
+  if (max_launches <= 0) SLONN_FAIL(SLONN_EINVAL, "max_launches must be positive");
+  if (g_prof.on) SLONN_FAIL(SLONN_EINVAL, "profiling is already on");
+  g_prof.start.assign(max_launches, nullptr);
+  g_prof.stop.assign(max_launches, nullptr);
+  g_prof.kind.assign(max_launches, 0);
+  g_prof.used = 0;
+  for (int i = 0; i < max_launches; ++i) {
+    SLONN_HIP(hipEventCreate(&g_prof.start[i]));
+    SLONN_HIP(hipEventCreate(&g_prof.stop[i]));
+  }
+  g_prof.on = true;
+  return SLONN_OK;
+}
+
+int slonn_profile_end(double* ms_per_kind, int64_t* launches_per_kind) {
+  if (!ms_per_kind || !launches_per_kind) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  if (!g_prof.on) SLONN_FAIL(SLONN_EINVAL, "profiling is not on");
+  g_prof.on = false;
+  for (int k = 0; k < SLONN_PROF_KINDS; ++k) { ms_per_kind[k] = 0.0; launches_per_kind[k] = 0; }
+  int rc = SLONN_OK;
+  if (hipDeviceSynchronize() != hipSuccess) { set_error("device synchronisation failed"); rc = SLONN_EHIP; }
+  for (size_t i = 0; i < g_prof.start.size(); ++i) {
+    if (rc == SLONN_OK && i < g_prof.used) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) == hipSuccess) {
+        ms_per_kind[g_prof.kind[i]] += ms;
+        launches_per_kind[g_prof.kind[i]] += 1;
+      }
+    }
+    if (g_prof.start[i]) (void)hipEventDestroy(g_prof.start[i]);
+    if (g_prof.stop[i]) (void)hipEventDestroy(g_prof.stop[i]);
+  }
+  g_prof.start.clear(); g_prof.stop.clear(); g_prof.kind.clear(); g_prof.used = 0;
+  return rc;
+}
 
 int slonn_version(char* buf, size_t cap) {
   if (!buf || cap == 0) SLONN_FAIL(SLONN_EINVAL, "null buffer");

@@ -72,6 +72,15 @@ struct slonn_tables {
 
 namespace slonn {
 
+// Optional per-kernel timing (slonn_profile_begin/end): a scope brackets one launch with
+// two events on the launch stream.  Does nothing unless profiling is switched on.
+struct ProfScope {
+  ProfScope(int kind, hipStream_t s);
+  ~ProfScope();
+  int slot;
+  hipStream_t stream;
+};
+
 // ---- kernel launchers (each validates nothing: callers have checked shapes) ----
 
 // Z[q][h] = Wh[h] . X[q] + bh[h], fp64 accumulation, rounded once to fp32.

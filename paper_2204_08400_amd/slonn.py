@@ -25,7 +25,9 @@ EXPORTS = [
     "slonn_version", "slonn_model_create", "slonn_model_destroy", "slonn_build_tables",
     "slonn_tables_export", "slonn_tables_import", "slonn_tables_destroy", "slonn_workspace_bytes",
     "slonn_select", "slonn_sparse_forward", "slonn_dense_forward", "slonn_last_error",
+    "slonn_profile_begin", "slonn_profile_end",
 ]
+PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize")
 
 
 class SlonnError(RuntimeError):
@@ -255,3 +257,15 @@ def slonn_dense_forward(model: Model, X: Input, B: int, Y, argmax, layer_out: Op
         C.c_void_p(_ptr(workspace)),
         C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
         C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_profile_begin(max_launches: int):
+    _check(load().slonn_profile_begin(int(max_launches)))
+
+
+def slonn_profile_end() -> dict:
+    """{kind: (total_ms, launches)} for the kernels launched since slonn_profile_begin."""
+    ms = (C.c_double * len(PROF_KINDS))()
+    cnt = (C.c_int64 * len(PROF_KINDS))()
+    _check(load().slonn_profile_end(ms, cnt))
+    return {k: (ms[i], cnt[i]) for i, k in enumerate(PROF_KINDS)}
