@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--path", default="auto", choices=["auto", "layers", "fused"])
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path is data-parallel over queries with nothing "
@@ -70,6 +71,7 @@ def main():
     net = runtime.Network(layers)
     t0 = time.time()
     net.build_tables(xb)
+    net.set_path(args.path)
     log(f"built tables on the device in {time.time() - t0:.2f}s")
 
     xq = torch.from_numpy(X_query).to(dev)
@@ -124,10 +126,9 @@ def main():
     prof = slonn.slonn_profile_end()
     split_us = {k: (v[0] * 1e3 / max(v[1], 1)) for k, v in prof.items() if v[1]}
     per_step_us = {k: v[0] * 1e3 / K for k, v in prof.items() if v[1]}
-    # dominant kernel: the gathered-row forward.  Algorithmic bytes per launch = selected rows x row
-    # bytes (activated layers) or the whole small matrix per query (output layer), averaged over its
-    # launches in a step.
-    g_ms, g_n = prof["gather"]
+    # dominant kernel: the one holding most of the step.  Its algorithmic bytes per launch are
+    # the weight rows the method must read: budget x row bytes for each activated layer, the whole
+    # matrix per query for a layer computed in full, summed over the layers that launch covers.
     bytes_per_step = 0
     for lay in layers:
         esz = 4 if lay.w_dtype == wl.W_F32 else 2
@@ -136,10 +137,13 @@ def main():
         else:
             m = lay.d_out
         bytes_per_step += B * m * lay.d_in * esz
+    dom = "fused" if prof["fused"][1] else "gather"
+    g_ms, g_n = prof[dom]
     launches_per_step = g_n / K
     avg_launch_s = g_ms / 1e3 / g_n
     achieved = (bytes_per_step / launches_per_step) / avg_launch_s / 1e9
-    roofline = {"bound": "hbm", "kernel": "gather_forward_kernel", "achieved": round(achieved, 1),
+    roofline = {"bound": "hbm", "kernel": "fused_forward_kernel" if dom == "fused" else "gather_forward_kernel",
+                "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": None, "avg_launch_us": round(avg_launch_s * 1e6, 2),
                 "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)}
@@ -197,7 +201,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.config}: MLP {'-'.join(map(str, cfg.dims))}, K={cfg.K} L={cfg.L} on "
                                f"{len(cfg.hashed_layers)} hidden layers, {nq} queries", "batch": B,
-                   "keep": args.keep, "queries_per_step": B},
+                   "keep": args.keep, "queries_per_step": B, "path": args.path},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     line.update(extra)

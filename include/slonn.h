@@ -130,6 +130,18 @@ int slonn_version(char* buf, size_t cap);
 int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model** out);
 int slonn_model_destroy(slonn_model* m);
 
+/* Execution path of slonn_sparse_forward.  The results are the same on every path.
+ * SLONN_PATH_LAYERS: one launch sequence per layer (hash projection as a batch-wide
+ *   MFMA contraction, select, gathered-row forward); serves every model and size.
+ * SLONN_PATH_FUSED: one workgroup carries one query through the whole network with its
+ *   activations in LDS, one launch per batch; for models whose layers are small enough
+ *   (every weight matrix at most 8 MiB, dense first-layer input, no Node Activator on
+ *   the last layer, row lengths a multiple of 16 bytes).  EUNSUPPORTED otherwise.
+ * SLONN_PATH_AUTO (default): FUSED when the model qualifies and no compact output is
+ *   requested, else LAYERS.                                                          */
+enum { SLONN_PATH_AUTO = 0, SLONN_PATH_LAYERS = 1, SLONN_PATH_FUSED = 2 };
+int slonn_model_set_path(slonn_model* m, int path);
+
 /* Alg. 1 for every activated layer, on the device.  X_build holds N training inputs
  * (device).  Input_l is the full network's output of layer l-1 on X_build; the
  * Activation summed into NodeScore is layer l's own output; each bucket keeps its
@@ -190,7 +202,7 @@ int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float
  * caller arrays of SLONN_PROF_KINDS entries (HOST), and switches timing off again.
  * Not thread-safe; costs two event records per launch while on.                     */
 enum { SLONN_PROF_HASH = 0, SLONN_PROF_SELECT = 1, SLONN_PROF_GATHER = 2, SLONN_PROF_DENSE = 3,
-       SLONN_PROF_ELL = 4, SLONN_PROF_FINALIZE = 5, SLONN_PROF_KINDS = 6 };
+       SLONN_PROF_ELL = 4, SLONN_PROF_FINALIZE = 5, SLONN_PROF_FUSED = 6, SLONN_PROF_KINDS = 7 };
 int slonn_profile_begin(int max_launches);
 int slonn_profile_end(double* ms_per_kind, int64_t* launches_per_kind);
 

@@ -1,0 +1,352 @@
+// Whole-network SLO-aware forward pass for small and medium layers: one 1024-thread
+// workgroup walks one query through every layer (the "k% forward propagation" loop of
+// Section 2.1: for each layer, ask the Node Activator for the active node ids, then
+// compute only those nodes).  The query's activations, hash projections, keys, the
+// de-duplication map and the active list live in LDS from the first layer to the last;
+// HBM/L2 only supplies weight rows, table entries and the query, and receives the
+// final output.  One launch per batch replaces seven, which is what matters when a
+// whole batch is only tens of microseconds of memory traffic.
+//
+// Per activated layer:
+//   hash    FreeHash projections (Def. 2) of the K*L sampled nodes, fp64 accumulation
+//           (the sign is a hash bit), 16 lanes per row;
+//   select  keys -> one bucket per table -> merge in rank-major, table-minor order.
+//           All 1024 threads take one slot each per round; a node's first occurrence is
+//           found with an LDS integer min over slot numbers (order-independent, hence
+//           deterministic), survivors are compacted in slot order with a ballot and a
+//           two-level prefix sum, no atomic counters;
+//   gather  y_j = act(w_j . x + b_j) for the active rows, four rows per 16-lane group
+//           in flight, written straight into the next layer's input in LDS (dropped
+//           nodes were zeroed there beforehand).
+#include "slonn_internal.h"
+
+namespace slonn {
+namespace {
+
+constexpr int NT = 1024;                 // threads per workgroup
+constexpr int NW = NT / 64;              // wavefronts
+constexpr int GROUPS = NT / 16;          // 16-lane row groups
+
+__device__ __forceinline__ int budget_of(float keep, int n) {
+  double m = floor((double)keep * (double)n + 0.5);
+  if (m < 1.0) m = 1.0;
+  if (m > (double)n) m = (double)n;
+  return (int)m;
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+
+__device__ __forceinline__ float reduce16(float v) {
+  v += __shfl_xor(v, 8, 16);
+  v += __shfl_xor(v, 4, 16);
+  v += __shfl_xor(v, 2, 16);
+  v += __shfl_xor(v, 1, 16);
+  return v;
+}
+__device__ __forceinline__ double reduce16(double v) {
+  v += __shfl_xor(v, 8, 16);
+  v += __shfl_xor(v, 4, 16);
+  v += __shfl_xor(v, 2, 16);
+  v += __shfl_xor(v, 1, 16);
+  return v;
+}
+
+// 16 bytes of a weight row against x (LDS), fp32
+template <int WDT>
+__device__ __forceinline__ float dot16(const uint4& w, const float* xs, float acc);
+template <>
+__device__ __forceinline__ float dot16<SLONN_F32>(const uint4& w, const float* xs, float acc) {
+  const float4 x = *reinterpret_cast<const float4*>(xs);
+  acc = fmaf(__uint_as_float(w.x), x.x, acc);
+  acc = fmaf(__uint_as_float(w.y), x.y, acc);
+  acc = fmaf(__uint_as_float(w.z), x.z, acc);
+  acc = fmaf(__uint_as_float(w.w), x.w, acc);
+  return acc;
+}
+template <>
+__device__ __forceinline__ float dot16<SLONN_BF16>(const uint4& w, const float* xs, float acc) {
+  const float4 x0 = *reinterpret_cast<const float4*>(xs);
+  const float4 x1 = *reinterpret_cast<const float4*>(xs + 4);
+  acc = fmaf(bf16_lo(w.x), x0.x, acc);
+  acc = fmaf(bf16_hi(w.x), x0.y, acc);
+  acc = fmaf(bf16_lo(w.y), x0.z, acc);
+  acc = fmaf(bf16_hi(w.y), x0.w, acc);
+  acc = fmaf(bf16_lo(w.z), x1.x, acc);
+  acc = fmaf(bf16_hi(w.z), x1.y, acc);
+  acc = fmaf(bf16_lo(w.w), x1.z, acc);
+  acc = fmaf(bf16_hi(w.w), x1.w, acc);
+  return acc;
+}
+
+// rows listed in LDS (list == nullptr: rows 0..count-1) -> dst[j] = act(w_j . x + b_j)
+template <int WDT>
+__device__ __forceinline__ void gather_rows(const void* __restrict__ W, const float* __restrict__ bias,
+                                            int d, const float* xs, const int32_t* list, int count,
+                                            int act, float* dst) {
+  constexpr int ELEMS = (WDT == SLONN_F32) ? 4 : 8;
+  constexpr int ESZ = (WDT == SLONN_F32) ? 4 : 2;
+  const int g = threadIdx.x >> 4, l = threadIdx.x & 15;
+  const int nv = d / ELEMS;
+  for (int t0 = g; t0 < count; t0 += 4 * GROUPS) {
+    int t[4], j[4];
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      t[k] = t0 + k * GROUPS;
+      const int tt = t[k] < count ? t[k] : t0;
+      j[k] = list ? list[tt] : tt;
+    }
+    const uint4* w0 = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j[0] * d * ESZ);
+    const uint4* w1 = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j[1] * d * ESZ);
+    const uint4* w2 = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j[2] * d * ESZ);
+    const uint4* w3 = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j[3] * d * ESZ);
+#pragma unroll 2
+    for (int i = l; i < nv; i += 16) {
+      const uint4 a0 = w0[i], a1 = w1[i], a2 = w2[i], a3 = w3[i];
+      const float* xp = xs + i * ELEMS;
+      acc[0] = dot16<WDT>(a0, xp, acc[0]);
+      acc[1] = dot16<WDT>(a1, xp, acc[1]);
+      acc[2] = dot16<WDT>(a2, xp, acc[2]);
+      acc[3] = dot16<WDT>(a3, xp, acc[3]);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] = reduce16(acc[k]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (l == k && t[k] < count) {
+        float z = acc[k] + bias[j[k]];
+        if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+        dst[j[k]] = z;
+      }
+  }
+}
+
+__global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* xbuf0 = reinterpret_cast<float*>(smem);
+  float* xbuf1 = xbuf0 + a.max_dim;
+  float* zs = xbuf1 + a.max_dim;
+  uint32_t* prio = reinterpret_cast<uint32_t*>(zs + a.max_H);
+  int32_t* alist = reinterpret_cast<int32_t*>(prio + a.max_na);
+  uint32_t* s_off = reinterpret_cast<uint32_t*>(alist + a.max_na);
+  uint32_t* s_len = s_off + 64;
+  int* wave_cnt = reinterpret_cast<int*>(s_len + 64);     // NW entries
+  uint32_t* s_misc = reinterpret_cast<uint32_t*>(wave_cnt + NW);   // [0] longest list
+
+  const int q = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+
+  float* xs = xbuf0;
+  float* xn = xbuf1;
+  {
+    const float4* x = reinterpret_cast<const float4*>(a.X + (size_t)q * a.ldx);
+    for (int i = tid; i < (a.layer[0].d_in >> 2); i += NT) reinterpret_cast<float4*>(xs)[i] = x[i];
+  }
+  __syncthreads();
+
+  for (int li = 0; li < a.n_layers; ++li) {
+    const FusedLayer& Ly = a.layer[li];
+    const int d = Ly.d_in, n = Ly.d_out;
+    const bool last = (li == a.n_layers - 1);
+    const bool activated = Ly.K > 0;
+    int m = n;
+    if (activated) m = budget_of(a.keep[(size_t)q * a.keep_qstride + (size_t)li * a.keep_lstride], n);
+    const int32_t* list = nullptr;
+
+    if (activated) {
+      // ---- hash: z_h = w_h . x + b_h in fp64, one 16-lane group per row ----
+      const int H = Ly.K * Ly.L;
+      const int g = tid >> 4, l = tid & 15;
+      const int nv = d >> 2;
+      for (int h0 = g; h0 < H; h0 += 2 * GROUPS) {
+        const int h1 = (h0 + GROUPS < H) ? h0 + GROUPS : h0;
+        const float4* w0 = reinterpret_cast<const float4*>(Ly.Wh + (size_t)h0 * d);
+        const float4* w1 = reinterpret_cast<const float4*>(Ly.Wh + (size_t)h1 * d);
+        double acc0 = 0.0, acc1 = 0.0;
+#pragma unroll 4
+        for (int i = l; i < nv; i += 16) {
+          const float4 u = w0[i], v = w1[i];
+          const float4 x = reinterpret_cast<const float4*>(xs)[i];
+          const double x0 = x.x, x1 = x.y, x2 = x.z, x3 = x.w;
+          acc0 = fma((double)u.x, x0, acc0);
+          acc0 = fma((double)u.y, x1, acc0);
+          acc0 = fma((double)u.z, x2, acc0);
+          acc0 = fma((double)u.w, x3, acc0);
+          acc1 = fma((double)v.x, x0, acc1);
+          acc1 = fma((double)v.y, x1, acc1);
+          acc1 = fma((double)v.z, x2, acc1);
+          acc1 = fma((double)v.w, x3, acc1);
+        }
+        acc0 = reduce16(acc0);
+        acc1 = reduce16(acc1);
+        if (l == 0) {
+          const float z0 = (float)(acc0 + (double)Ly.bh[h0]);
+          zs[h0] = z0;
+          if (Ly.tap_z) Ly.tap_z[(size_t)q * H + h0] = z0;
+          if (h1 != h0) {
+            const float z1 = (float)(acc1 + (double)Ly.bh[h1]);
+            zs[h1] = z1;
+            if (Ly.tap_z) Ly.tap_z[(size_t)q * H + h1] = z1;
+          }
+        }
+      }
+      // meanwhile: clear the next activation buffer and the first-occurrence map
+      for (int i = tid; i < n; i += NT) { xn[i] = 0.0f; prio[i] = 0xFFFFFFFFu; }
+      __syncthreads();
+
+      // ---- keys and bucket directory: one lane per table ----
+      if (wave == 0) {
+        const int nb1 = (1 << Ly.K) + 1;
+        uint32_t len = 0;
+        if (lane < Ly.L) {
+          uint32_t key = 0;
+          for (int j = 0; j < Ly.K; ++j) key |= (zs[lane * Ly.K + j] > 0.0f ? 1u : 0u) << j;
+          if (Ly.tap_codes) Ly.tap_codes[(size_t)q * Ly.L + lane] = key;
+          const uint32_t lo = Ly.dir[(size_t)lane * nb1 + key], hi = Ly.dir[(size_t)lane * nb1 + key + 1];
+          s_off[lane] = lo;
+          len = hi - lo;
+          s_len[lane] = len;
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+          const uint32_t other = __shfl_xor(len, o);
+          len = other > len ? other : len;
+        }
+        if (lane == 0) {
+          s_misc[0] = len;
+          if (Ly.tap_cnt) Ly.tap_cnt[q] = m;
+        }
+      }
+      __syncthreads();
+
+      if (m < n) {
+        // ---- merge: first m distinct nodes in slot order (slot = rank * L + table) ----
+        const int L = Ly.L;
+        const long long nslots = (long long)s_misc[0] * L;
+        int count = 0;
+        for (long long base = 0; base < nslots && count < m; base += NT) {
+          const long long s = base + tid;
+          const uint32_t r = (uint32_t)(s / L);
+          const int b = (int)(s - (long long)r * L);
+          const bool valid = s < nslots && r < s_len[b];
+          int node = -1;
+          if (valid) {
+            node = Ly.ids[s_off[b] + r];
+            atomicMin(&prio[node], (uint32_t)s);
+          }
+          __syncthreads();
+          const bool first = valid && prio[node] == (uint32_t)s;
+          const unsigned long long votes = __ballot(first);
+          if (lane == 0) wave_cnt[wave] = __popcll(votes);
+          __syncthreads();
+          int before = 0, total = 0;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) {
+            const int c = wave_cnt[w];
+            before += (w < wave) ? c : 0;
+            total += c;
+          }
+          if (first) {
+            const int pos = count + before + __popcll(votes & below);
+            if (pos < m) alist[pos] = node;
+          }
+          count += total;
+          __syncthreads();
+        }
+        // ---- the lists ran out: continue down the whole-set ranking (no duplicates) ----
+        for (int base = 0; base < n && count < m; base += NT) {
+          const int i = base + tid;
+          int node = -1;
+          bool first = false;
+          if (i < n) {
+            node = Ly.global_rank[i];
+            first = prio[node] == 0xFFFFFFFFu;
+          }
+          const unsigned long long votes = __ballot(first);
+          if (lane == 0) wave_cnt[wave] = __popcll(votes);
+          __syncthreads();
+          int before = 0, total = 0;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) {
+            const int c = wave_cnt[w];
+            before += (w < wave) ? c : 0;
+            total += c;
+          }
+          if (first) {
+            const int pos = count + before + __popcll(votes & below);
+            if (pos < m) alist[pos] = node;
+          }
+          count += total;
+          __syncthreads();
+        }
+        list = alist;
+        if (Ly.tap_idx)
+          for (int i = tid; i < m; i += NT) Ly.tap_idx[(size_t)q * n + i] = alist[i];
+      } else if (Ly.tap_idx) {
+        for (int i = tid; i < n; i += NT) Ly.tap_idx[(size_t)q * n + i] = i;
+      }
+    }
+
+    // ---- evaluate the active rows into the next layer's input ----
+    const int act = (Ly.act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
+    if (Ly.w_dtype == SLONN_F32)
+      gather_rows<SLONN_F32>(Ly.W, Ly.bias, d, xs, list, m, act, xn);
+    else
+      gather_rows<SLONN_BF16>(Ly.W, Ly.bias, d, xs, list, m, act, xn);
+    __syncthreads();
+
+    if (last) {
+      // every node of the last layer was computed (it carries no Node Activator here)
+      if (wave == 0) {
+        float best = -INFINITY;
+        int besti = 0x7FFFFFFF;
+        for (int j = lane; j < n; j += 64) {
+          const float v = xn[j];
+          if (v > best || (v == best && j < besti)) { best = v; besti = j; }
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+          const float ob = __shfl_xor(best, o);
+          const int oi = __shfl_xor(besti, o);
+          if (ob > best || (ob == best && oi < besti)) { best = ob; besti = oi; }
+        }
+        if (a.argmax && lane == 0) a.argmax[q] = besti;
+        if (Ly.act == SLONN_ACT_SOFTMAX) {
+          float sum = 0.0f;
+          for (int j = lane; j < n; j += 64) sum += expf(xn[j] - best);
+          for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+          const float inv = 1.0f / sum;
+          for (int j = lane; j < n; j += 64) xn[j] = expf(xn[j] - best) * inv;
+        }
+      }
+      __syncthreads();
+      if (a.Y)
+        for (int j = tid; j < n; j += NT) a.Y[(size_t)q * n + j] = xn[j];
+    }
+    if (Ly.tap_out)
+      for (int j = tid; j < n; j += NT) Ly.tap_out[(size_t)q * n + j] = xn[j];
+    float* t = xs; xs = xn; xn = t;
+    __syncthreads();
+  }
+}
+
+}  // namespace
+
+size_t fused_lds_bytes(const FusedArgs& a) {
+  return (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 + (64 + 64 + NW + 4) * 4;
+}
+
+int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_FUSED, s);
+  const size_t lds = fused_lds_bytes(a);
+  if (lds > (size_t)max_lds)
+    SLONN_FAIL(SLONN_EUNSUPPORTED, "fused path needs %zu bytes of LDS, device grants %d", lds, max_lds);
+  if (lds > 65536)
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(fused_forward_kernel, dim3(B), dim3(NT), lds, s, a);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+}  // namespace slonn

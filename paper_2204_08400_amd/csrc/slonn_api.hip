@@ -251,6 +251,51 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
   return SLONN_OK;
 }
 
+namespace slonn {
+namespace {
+
+// Can the whole-network kernel serve this model?  (reason != nullptr receives why not)
+bool fused_eligible(const slonn_model* m, const char** reason) {
+  const char* why = nullptr;
+  const int nl = (int)m->layers.size();
+  if (nl > FUSED_MAX_LAYERS) why = "too many layers";
+  for (int l = 0; l < nl && !why; ++l) {
+    const Layer& L = m->layers[l];
+    const int esz = L.w_dtype == SLONN_F32 ? 4 : 2;
+    if (L.w_layout != SLONN_ROWS_ARE_NODES) why = "input-major first layer";
+    else if ((size_t)L.d_in * L.d_out * esz > ((size_t)8 << 20)) why = "a weight matrix exceeds 8 MiB";
+    else if (((size_t)L.d_in * esz) % 16 != 0 || L.d_in % 4 != 0) why = "row length is not a multiple of 16 bytes";
+    else if (reinterpret_cast<uintptr_t>(L.W) % 16 != 0) why = "weights are not 16-byte aligned";
+    else if (l == nl - 1 && L.activated()) why = "Node Activator on the last layer";
+  }
+  if (!why) {
+    FusedArgs a{};
+    for (const Layer& L : m->layers) {
+      a.max_dim = std::max(a.max_dim, std::max(L.d_in, L.d_out));
+      if (L.activated()) { a.max_H = std::max(a.max_H, L.H()); a.max_na = std::max(a.max_na, L.d_out); }
+    }
+    a.max_dim = (a.max_dim + 7) & ~7;
+    if (fused_lds_bytes(a) > (size_t)m->max_lds_bytes) why = "activations do not fit in LDS";
+  }
+  if (reason) *reason = why;
+  return why == nullptr;
+}
+
+}  // namespace
+}  // namespace slonn
+
+int slonn_model_set_path(slonn_model* m, int path) {
+  if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
+  if (path != SLONN_PATH_AUTO && path != SLONN_PATH_LAYERS && path != SLONN_PATH_FUSED)
+    SLONN_FAIL(SLONN_EINVAL, "unknown path %d", path);
+  if (path == SLONN_PATH_FUSED) {
+    const char* why = nullptr;
+    if (!fused_eligible(m, &why)) SLONN_FAIL(SLONN_EUNSUPPORTED, "fused path unavailable: %s", why);
+  }
+  m->path = path;
+  return SLONN_OK;
+}
+
 int slonn_model_destroy(slonn_model* m) {
   if (!m) return SLONN_OK;
   for (Layer& L : m->layers) {
@@ -451,11 +496,53 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       SLONN_FAIL(SLONN_ECAP, "compact output stride %d is below the last layer's %d nodes", Y->stride,
                  last.d_out);
   }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  // ---- whole-network kernel ----
+  const bool wants_compact = Y->idx || Y->val || Y->cnt;
+  bool fused = false;
+  if (m->path != SLONN_PATH_LAYERS) {
+    const char* why = nullptr;
+    fused = fused_eligible(m, &why) && X->format == SLONN_DENSE && !wants_compact &&
+            reinterpret_cast<uintptr_t>(X->x) % 16 == 0;
+    if (!fused && m->path == SLONN_PATH_FUSED)
+      SLONN_FAIL(SLONN_EUNSUPPORTED, "fused path unavailable for this call: %s",
+                 why ? why : "needs dense 16-byte aligned input and no compact output");
+  }
+  if (fused) {
+    FusedArgs a{};
+    a.n_layers = nl;
+    for (int l = 0; l < nl; ++l) {
+      const Layer& L = m->layers[l];
+      FusedLayer& f = a.layer[l];
+      f.W = L.W; f.bias = L.bias; f.Wh = L.Wh; f.bh = L.bh;
+      f.d_in = L.d_in; f.d_out = L.d_out; f.act = L.act; f.w_dtype = L.w_dtype; f.K = L.K; f.L = L.L;
+      if (L.activated()) {
+        const TableSet* ts = t->for_layer(l);
+        f.dir = ts->d_dir; f.ids = ts->d_ids; f.global_rank = ts->d_global_rank;
+        a.max_H = std::max(a.max_H, L.H());
+        a.max_na = std::max(a.max_na, L.d_out);
+      }
+      a.max_dim = std::max(a.max_dim, std::max(L.d_in, L.d_out));
+      if (taps) {
+        f.tap_codes = taps->codes ? taps->codes[l] : nullptr;
+        f.tap_z = taps->z ? taps->z[l] : nullptr;
+        f.tap_idx = taps->active_idx ? taps->active_idx[l] : nullptr;
+        f.tap_cnt = taps->active_cnt ? taps->active_cnt[l] : nullptr;
+        f.tap_out = taps->layer_out ? taps->layer_out[l] : nullptr;
+      }
+    }
+    a.max_dim = (a.max_dim + 7) & ~7;
+    a.X = X->x; a.ldx = m->layers[0].d_in;
+    a.keep = keep; a.keep_qstride = keep_qstride; a.keep_lstride = keep_lstride;
+    a.Y = Y->dense; a.argmax = Y->argmax;
+    return launch_fused_forward(a, B, m->max_lds_bytes, s);
+  }
+
   Workspace w;
   plan_workspace(m, B, static_cast<char*>(workspace), &w);
   if (!workspace || ws_bytes < w.bytes)
     SLONN_FAIL(SLONN_ENOMEM, "workspace holds %zu bytes, %zu needed", ws_bytes, w.bytes);
-  hipStream_t s = static_cast<hipStream_t>(stream);
 
   const float* cur = X->x;
   int ldcur = m->layers[0].d_in;

@@ -56,6 +56,7 @@ struct TableSet {                 // Node Importance tables of one layer
 
 struct slonn_model {
   std::vector<slonn::Layer> layers;
+  int path = SLONN_PATH_AUTO;
   int max_lds_bytes = 65536;      // per-workgroup LDS the device grants on request
   int n_cu = 256;
 };
@@ -80,6 +81,35 @@ struct ProfScope {
   int slot;
   hipStream_t stream;
 };
+
+// Arguments of the whole-network kernel (passed by value as kernel arguments).
+constexpr int FUSED_MAX_LAYERS = 8;
+struct FusedLayer {
+  const void* W;
+  const float* bias;
+  const float* Wh;
+  const float* bh;
+  const uint32_t* dir;
+  const int32_t* ids;
+  const int32_t* global_rank;
+  uint32_t* tap_codes;
+  float* tap_z;
+  int32_t* tap_idx;
+  int32_t* tap_cnt;
+  float* tap_out;
+  int d_in, d_out, act, w_dtype, K, L;
+};
+struct FusedArgs {
+  FusedLayer layer[FUSED_MAX_LAYERS];
+  const float* X;
+  const float* keep;
+  float* Y;
+  int32_t* argmax;
+  int ldx, keep_qstride, keep_lstride, n_layers;
+  int max_dim, max_H, max_na;      // LDS carve-up: activations, projections, active list
+};
+size_t fused_lds_bytes(const FusedArgs& a);
+int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s);
 
 // ---- kernel launchers (each validates nothing: callers have checked shapes) ----
 

@@ -39,6 +39,10 @@ class Network:
         self._ws = None
         self._ws_B = 0
 
+    def set_path(self, path: str):
+        """'auto' | 'layers' | 'fused' (raises if the model does not qualify)."""
+        slonn.slonn_model_set_path(self.model, {"auto": 0, "layers": 1, "fused": 2}[path])
+
     # -- helpers -------------------------------------------------------------- #
     def workspace(self, B: int):
         if self._ws is None or B > self._ws_B:

@@ -25,9 +25,10 @@ EXPORTS = [
     "slonn_version", "slonn_model_create", "slonn_model_destroy", "slonn_build_tables",
     "slonn_tables_export", "slonn_tables_import", "slonn_tables_destroy", "slonn_workspace_bytes",
     "slonn_select", "slonn_sparse_forward", "slonn_dense_forward", "slonn_last_error",
-    "slonn_profile_begin", "slonn_profile_end",
+    "slonn_profile_begin", "slonn_profile_end", "slonn_model_set_path",
 ]
-PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize")
+PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused")
+PATH_AUTO, PATH_LAYERS, PATH_FUSED = 0, 1, 2
 
 
 class SlonnError(RuntimeError):
@@ -168,6 +169,10 @@ def make_input(x=None, idx=None, val=None, nnz=None) -> Input:
 
 def slonn_model_create(layers: Sequence[dict]) -> Model:
     return Model(layers)
+
+
+def slonn_model_set_path(model: Model, path: int):
+    _check(load().slonn_model_set_path(model.h, int(path)))
 
 
 def slonn_build_tables(model: Model, X_build: Input, N: int, stream=None) -> Tables:

@@ -31,10 +31,17 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _gpu_net(rt, layers, net, rows_are_inputs=False):
+def _gpu_net(rt, layers, net, rows_are_inputs=False, path="layers"):
     g = rt.Network(layers, first_layer_rows_are_inputs=rows_are_inputs)
     g.import_tables(net.export_tables())
+    g.set_path(path)
     return g
+
+
+def _fused_ok(case):
+    """row lengths must be multiples of 16 bytes for the whole-network kernel"""
+    mult = 8 if case.get("w_dtype", wl.W_F32) == wl.W_BF16 else 4
+    return all(d % mult == 0 for d in case["dims"][:-1])
 
 
 def _keep_tensor(keep):
@@ -54,6 +61,7 @@ def test_worked_example(rt, oracle):
         x = np.asarray([q["x"]], np.float32)
         for m in range(1, 7):
             _say(f"worked example x={q['x']} m={m}")
+            g.set_path("layers")     # d = 2: rows are not 16-byte multiples, per-layer path only
             r = to_numpy_result(g.sparse_forward(x, np.float32(m / 6), taps=True))
             assert r["taps"]["codes"][0][0].tolist() == q["keys"]
             assert r["taps"]["cnt"][0][0] == m
@@ -73,19 +81,20 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("path", ["layers", "fused"])
 @pytest.mark.parametrize("case", CASES, ids=lambda c: "x".join(map(str, c["dims"])))
-def test_sparse_forward_matches_oracle(rt, oracle, case):
+def test_sparse_forward_matches_oracle(rt, oracle, case, path):
     import torch
     dims, B = case["dims"], case["B"]
+    if path == "fused" and not _fused_ok(case):
+        pytest.skip("model does not qualify for the whole-network kernel")
     layers, net, Xb = make_case(oracle, dims, case["K"], case["L"], seed=17, cap=case.get("cap"),
                                 w_dtype=case.get("w_dtype", wl.W_F32), last_act=case.get("last_act", wl.ACT_NONE),
                                 kind=case["kind"])
-    g = _gpu_net(rt, layers, net)
+    g = _gpu_net(rt, layers, net, path=path)
     X = make_queries(dims, B, seed=99, kind=case["kind"])
     for keep in (0.05, 0.3, 0.77, 1.0):
-        _say(f"case {dims} keep={keep}")
-        if case.get("cap") and keep > 0.3 and keep < 1.0:
-            pass    # lists are capped: the fallback ranking takes over, still must match
+        _say(f"case {dims} path={path} keep={keep}")
         ref = net.sparse_forward(X, keep)
         got = to_numpy_result(g.sparse_forward(X, keep, taps=True))
         rep = compare_sparse(got, ref, layers, f"{dims} keep {keep}")
@@ -181,11 +190,12 @@ def test_ell_input_and_activated_softmax_output(rt, oracle):
             assert abs(got["val"][q, :c].sum() - 1.0) < 1e-4
 
 
-def test_edge_cases(rt, oracle):
+@pytest.mark.parametrize("path", ["layers", "fused"])
+def test_edge_cases(rt, oracle, path):
     import torch
     dims = (40, 64, 64, 8)
     layers, net, _ = make_case(oracle, dims, 3, 2, seed=41, cap=5)   # short lists: fallback dominates
-    g = _gpu_net(rt, layers, net)
+    g = _gpu_net(rt, layers, net, path=path)
     # single query, smallest budget, tiny keep
     X = make_queries(dims, 1, seed=8)
     for keep in (1e-6, 1.0 / 64, 0.999):
@@ -201,6 +211,9 @@ def test_edge_cases(rt, oracle):
     from paper_2204_08400_amd import slonn
     with pytest.raises(slonn.SlonnError):
         g.select(2, X, 0.5)              # output layer has no Node Activator
+    odd = rt.Network(wl.make_mlp((75, 33, 5), seed=1))
+    with pytest.raises(slonn.SlonnError):
+        odd.set_path("fused")            # 75 floats per row is not a multiple of 16 bytes
     with pytest.raises(slonn.SlonnError):
         slonn.slonn_sparse_forward(g.model, g.tables, g.to_input(X), 0, torch.ones(1, device="cuda"), 0, 0,
                                    slonn.make_output(), None, g.workspace(1))
