@@ -25,6 +25,7 @@ namespace {
 
 constexpr int NT = 1024;                 // threads per workgroup
 constexpr int NW = NT / 64;              // wavefronts
+constexpr int MU = 4;                    // most merge slots per thread per round
 constexpr int GROUPS = NT / 16;          // 16-lane row groups
 
 __device__ __forceinline__ int budget_of(float keep, int n) {
@@ -79,11 +80,62 @@ __device__ __forceinline__ float dot16<SLONN_BF16>(const uint4& w, const float* 
   return acc;
 }
 
+__device__ __forceinline__ float reduce64(float v) {
+  v += __shfl_xor(v, 32);
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 8);
+  v += __shfl_xor(v, 4);
+  v += __shfl_xor(v, 2);
+  v += __shfl_xor(v, 1);
+  return v;
+}
+
+// Few rows (a small output layer): one whole wavefront per row, four 16-byte steps in
+// flight, so that ten rows keep ten wavefronts busy instead of ten 16-lane groups.
+template <int WDT>
+__device__ __forceinline__ void gather_few_rows(const void* __restrict__ W, const float* __restrict__ bias,
+                                                int d, const float* xs, const int32_t* list, int count,
+                                                int act, float* dst) {
+  constexpr int ELEMS = (WDT == SLONN_F32) ? 4 : 8;
+  constexpr int ESZ = (WDT == SLONN_F32) ? 4 : 2;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nv = d / ELEMS;
+  for (int t = wave; t < count; t += NW) {
+    const int j = list ? list[t] : t;
+    const uint4* w = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j * d * ESZ);
+    const float b = bias[j];
+    float acc = 0.0f;
+    for (int i0 = 0; i0 < nv; i0 += 256) {
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * 64 + lane;
+        v[u] = (i < nv) ? w[i] : make_uint4(0u, 0u, 0u, 0u);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * 64 + lane;
+        if (i < nv) acc = dot16<WDT>(v[u], xs + i * ELEMS, acc);
+      }
+    }
+    acc = reduce64(acc);
+    if (lane == 0) {
+      float z = acc + b;
+      if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+      dst[j] = z;
+    }
+  }
+}
+
 // rows listed in LDS (list == nullptr: rows 0..count-1) -> dst[j] = act(w_j . x + b_j)
 template <int WDT>
 __device__ __forceinline__ void gather_rows(const void* __restrict__ W, const float* __restrict__ bias,
                                             int d, const float* xs, const int32_t* list, int count,
                                             int act, float* dst) {
+  if (count <= 2 * NW) {
+    gather_few_rows<WDT>(W, bias, d, xs, list, count, act, dst);
+    return;
+  }
   constexpr int ELEMS = (WDT == SLONN_F32) ? 4 : 8;
   constexpr int ESZ = (WDT == SLONN_F32) ? 4 : 2;
   const int g = threadIdx.x >> 4, l = threadIdx.x & 15;
@@ -131,8 +183,8 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
   int32_t* alist = reinterpret_cast<int32_t*>(prio + a.max_na);
   uint32_t* s_off = reinterpret_cast<uint32_t*>(alist + a.max_na);
   uint32_t* s_len = s_off + 64;
-  int* wave_cnt = reinterpret_cast<int*>(s_len + 64);     // NW entries
-  uint32_t* s_misc = reinterpret_cast<uint32_t*>(wave_cnt + NW);   // [0] longest list
+  int* wave_cnt = reinterpret_cast<int*>(s_len + 64);     // MU * NW entries
+  uint32_t* s_misc = reinterpret_cast<uint32_t*>(wave_cnt + MU * NW);   // [0] longest list
 
   const int q = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -222,36 +274,55 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
 
       if (m < n) {
         // ---- merge: first m distinct nodes in slot order (slot = rank * L + table) ----
-        const int L = Ly.L;
-        const long long nslots = (long long)s_misc[0] * L;
+        // Each thread takes `per` <= MU slots per round (slot numbers base + u*NT + tid), so a
+        // round covers per*NT slots with all their id loads in flight together.  Lists of
+        // similar buckets overlap heavily, so a round is sized to about twelve slots per
+        // wanted node: most queries then finish in one round (one table-memory latency).
+        const uint32_t L = (uint32_t)Ly.L;
+        const uint32_t nslots = s_misc[0] * L;          // <= d_out * 64 < 2^32
+        int per = (12 * m + NT - 1) / NT;
+        per = per < 1 ? 1 : (per > MU ? MU : per);
         int count = 0;
-        for (long long base = 0; base < nslots && count < m; base += NT) {
-          const long long s = base + tid;
-          const uint32_t r = (uint32_t)(s / L);
-          const int b = (int)(s - (long long)r * L);
-          const bool valid = s < nslots && r < s_len[b];
-          int node = -1;
-          if (valid) {
-            node = Ly.ids[s_off[b] + r];
-            atomicMin(&prio[node], (uint32_t)s);
-          }
-          __syncthreads();
-          const bool first = valid && prio[node] == (uint32_t)s;
-          const unsigned long long votes = __ballot(first);
-          if (lane == 0) wave_cnt[wave] = __popcll(votes);
-          __syncthreads();
-          int before = 0, total = 0;
+        for (uint32_t base = 0; base < nslots && count < m; base += NT * per) {
+          int node[MU];
+          uint32_t slot[MU];
+          bool valid[MU];
 #pragma unroll
-          for (int w = 0; w < NW; ++w) {
-            const int c = wave_cnt[w];
-            before += (w < wave) ? c : 0;
-            total += c;
+          for (int u = 0; u < MU; ++u) {
+            slot[u] = base + u * NT + tid;
+            const uint32_t r = slot[u] / L;
+            const uint32_t b = slot[u] - r * L;
+            valid[u] = u < per && slot[u] < nslots && r < s_len[b];
+            node[u] = valid[u] ? Ly.ids[s_off[b] + r] : -1;
           }
-          if (first) {
-            const int pos = count + before + __popcll(votes & below);
-            if (pos < m) alist[pos] = node;
+#pragma unroll
+          for (int u = 0; u < MU; ++u)
+            if (valid[u]) atomicMin(&prio[node[u]], slot[u]);
+          __syncthreads();
+          bool first[MU];
+          unsigned long long votes[MU];
+#pragma unroll
+          for (int u = 0; u < MU; ++u) {
+            first[u] = valid[u] && prio[node[u]] == slot[u];
+            votes[u] = __ballot(first[u]);
+            if (lane == 0) wave_cnt[u * NW + wave] = __popcll(votes[u]);
           }
-          count += total;
+          __syncthreads();
+#pragma unroll
+          for (int u = 0; u < MU; ++u) {
+            int before = 0, total = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+              const int c = wave_cnt[u * NW + w];
+              before += (w < wave) ? c : 0;
+              total += c;
+            }
+            if (first[u]) {
+              const int pos = count + before + __popcll(votes[u] & below);
+              if (pos < m) alist[pos] = node[u];
+            }
+            count += total;
+          }
           __syncthreads();
         }
         // ---- the lists ran out: continue down the whole-set ranking (no duplicates) ----
@@ -333,7 +404,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
 }  // namespace
 
 size_t fused_lds_bytes(const FusedArgs& a) {
-  return (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 + (64 + 64 + NW + 4) * 4;
+  return (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 + (64 + 64 + MU * NW + 4) * 4;
 }
 
 int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s) {
