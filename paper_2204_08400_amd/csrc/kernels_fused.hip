@@ -18,6 +18,7 @@
 //   gather  y_j = act(w_j . x + b_j) for the active rows, four rows per 16-lane group
 //           in flight, written straight into the next layer's input in LDS (dropped
 //           nodes were zeroed there beforehand).
+#include "select_block.h"
 #include "slonn_internal.h"
 
 namespace slonn {
@@ -25,7 +26,6 @@ namespace {
 
 constexpr int NT = 1024;                 // threads per workgroup
 constexpr int NW = NT / 64;              // wavefronts
-constexpr int MU = 4;                    // most merge slots per thread per round
 constexpr int GROUPS = NT / 16;          // 16-lane row groups
 
 __device__ __forceinline__ int budget_of(float keep, int n) {
@@ -181,14 +181,15 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
   float* zs = xbuf1 + a.max_dim;
   uint32_t* prio = reinterpret_cast<uint32_t*>(zs + a.max_H);
   int32_t* alist = reinterpret_cast<int32_t*>(prio + a.max_na);
-  uint32_t* s_off = reinterpret_cast<uint32_t*>(alist + a.max_na);
-  uint32_t* s_len = s_off + 64;
-  int* wave_cnt = reinterpret_cast<int*>(s_len + 64);     // MU * NW entries
-  uint32_t* s_misc = reinterpret_cast<uint32_t*>(wave_cnt + MU * NW);   // [0] longest list
+  SelectShared<NT> sh;
+  sh.prio = prio;
+  sh.s_off = reinterpret_cast<uint32_t*>(alist + a.max_na);
+  sh.s_len = sh.s_off + 64;
+  sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
+  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * NW);
 
   const int q = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 
   float* xs = xbuf0;
   float* xn = xbuf1;
@@ -248,114 +249,22 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
       for (int i = tid; i < n; i += NT) { xn[i] = 0.0f; prio[i] = 0xFFFFFFFFu; }
       __syncthreads();
 
-      // ---- keys and bucket directory: one lane per table ----
-      if (wave == 0) {
-        const int nb1 = (1 << Ly.K) + 1;
-        uint32_t len = 0;
-        if (lane < Ly.L) {
-          uint32_t key = 0;
-          for (int j = 0; j < Ly.K; ++j) key |= (zs[lane * Ly.K + j] > 0.0f ? 1u : 0u) << j;
-          if (Ly.tap_codes) Ly.tap_codes[(size_t)q * Ly.L + lane] = key;
-          const uint32_t lo = Ly.dir[(size_t)lane * nb1 + key], hi = Ly.dir[(size_t)lane * nb1 + key + 1];
-          s_off[lane] = lo;
-          len = hi - lo;
-          s_len[lane] = len;
-        }
-        for (int o = 32; o > 0; o >>= 1) {
-          const uint32_t other = __shfl_xor(len, o);
-          len = other > len ? other : len;
-        }
-        if (lane == 0) {
-          s_misc[0] = len;
-          if (Ly.tap_cnt) Ly.tap_cnt[q] = m;
-        }
-      }
-      __syncthreads();
-
+      if (wave == 0 && lane == 0 && Ly.tap_cnt) Ly.tap_cnt[q] = m;
       if (m < n) {
-        // ---- merge: first m distinct nodes in slot order (slot = rank * L + table) ----
-        // Each thread takes `per` <= MU slots per round (slot numbers base + u*NT + tid), so a
-        // round covers per*NT slots with all their id loads in flight together.  Lists of
-        // similar buckets overlap heavily, so a round is sized to about twelve slots per
-        // wanted node: most queries then finish in one round (one table-memory latency).
-        const uint32_t L = (uint32_t)Ly.L;
-        const uint32_t nslots = s_misc[0] * L;          // <= d_out * 64 < 2^32
-        int per = (12 * m + NT - 1) / NT;
-        per = per < 1 ? 1 : (per > MU ? MU : per);
-        int count = 0;
-        for (uint32_t base = 0; base < nslots && count < m; base += NT * per) {
-          int node[MU];
-          uint32_t slot[MU];
-          bool valid[MU];
-#pragma unroll
-          for (int u = 0; u < MU; ++u) {
-            slot[u] = base + u * NT + tid;
-            const uint32_t r = slot[u] / L;
-            const uint32_t b = slot[u] - r * L;
-            valid[u] = u < per && slot[u] < nslots && r < s_len[b];
-            node[u] = valid[u] ? Ly.ids[s_off[b] + r] : -1;
-          }
-#pragma unroll
-          for (int u = 0; u < MU; ++u)
-            if (valid[u]) atomicMin(&prio[node[u]], slot[u]);
-          __syncthreads();
-          bool first[MU];
-          unsigned long long votes[MU];
-#pragma unroll
-          for (int u = 0; u < MU; ++u) {
-            first[u] = valid[u] && prio[node[u]] == slot[u];
-            votes[u] = __ballot(first[u]);
-            if (lane == 0) wave_cnt[u * NW + wave] = __popcll(votes[u]);
-          }
-          __syncthreads();
-#pragma unroll
-          for (int u = 0; u < MU; ++u) {
-            int before = 0, total = 0;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-              const int c = wave_cnt[u * NW + w];
-              before += (w < wave) ? c : 0;
-              total += c;
-            }
-            if (first[u]) {
-              const int pos = count + before + __popcll(votes[u] & below);
-              if (pos < m) alist[pos] = node[u];
-            }
-            count += total;
-          }
-          __syncthreads();
-        }
-        // ---- the lists ran out: continue down the whole-set ranking (no duplicates) ----
-        for (int base = 0; base < n && count < m; base += NT) {
-          const int i = base + tid;
-          int node = -1;
-          bool first = false;
-          if (i < n) {
-            node = Ly.global_rank[i];
-            first = prio[node] == 0xFFFFFFFFu;
-          }
-          const unsigned long long votes = __ballot(first);
-          if (lane == 0) wave_cnt[wave] = __popcll(votes);
-          __syncthreads();
-          int before = 0, total = 0;
-#pragma unroll
-          for (int w = 0; w < NW; ++w) {
-            const int c = wave_cnt[w];
-            before += (w < wave) ? c : 0;
-            total += c;
-          }
-          if (first) {
-            const int pos = count + before + __popcll(votes & below);
-            if (pos < m) alist[pos] = node;
-          }
-          count += total;
-          __syncthreads();
-        }
+        // ---- keys, bucket lookup, merge: first m distinct nodes in slot order ----
+        select_block<NT>(zs, Ly.K, Ly.L, n, m, Ly.dir, Ly.ids, Ly.global_rank, sh,
+                         Ly.tap_codes ? Ly.tap_codes + (size_t)q * Ly.L : nullptr, alist);
         list = alist;
         if (Ly.tap_idx)
           for (int i = tid; i < m; i += NT) Ly.tap_idx[(size_t)q * n + i] = alist[i];
-      } else if (Ly.tap_idx) {
-        for (int i = tid; i < n; i += NT) Ly.tap_idx[(size_t)q * n + i] = i;
+      } else {
+        if (Ly.tap_codes && tid < Ly.L) {
+          uint32_t key = 0;
+          for (int j = 0; j < Ly.K; ++j) key |= (zs[tid * Ly.K + j] > 0.0f ? 1u : 0u) << j;
+          Ly.tap_codes[(size_t)q * Ly.L + tid] = key;
+        }
+        if (Ly.tap_idx)
+          for (int i = tid; i < n; i += NT) Ly.tap_idx[(size_t)q * n + i] = i;
       }
     }
 
@@ -404,7 +313,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
 }  // namespace
 
 size_t fused_lds_bytes(const FusedArgs& a) {
-  return (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 + (64 + 64 + MU * NW + 4) * 4;
+  return (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 + SelectShared<NT>::words_besides_prio * 4;
 }
 
 int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s) {

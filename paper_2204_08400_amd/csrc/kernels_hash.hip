@@ -4,10 +4,132 @@
 // fp32 x fp32 products are exact in fp64 and the result's sign then only depends on
 // summation order when |z| is at the 1e-15 level, instead of the 1e-7 level of an
 // fp32 accumulator.
+//
+// hash_project_mfma_kernel: fp64 matrix cores (v_mfma_f64_16x16x4_f64).  A workgroup owns a
+// 32x32 (large batches) or 16x16 (small batches) tile of Z; its 4 or 16 wavefronts split
+// the reduction dimension and their partial tiles are added in LDS in a fixed order.
+// Operands are read straight from global memory/L2 as 16-byte loads: lane (r = lane%16,
+// g = lane/16) fetches elements 16s+4g .. 16s+4g+3 of its row, and MFMA number c of that
+// step consumes element c from every lane -- the same K subset for the X and the Wh
+// operand, which is all the instruction needs.
+// hash_project_kernel: LDS-tiled fp64 FMAs on the vector ALUs, for rows that are not
+// 16-byte aligned multiples of four elements.
 #include "slonn_internal.h"
 
 namespace slonn {
 namespace {
+
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// Lane layout of v_mfma_f64_16x16x4_f64 (checked on gfx950): A[i][k] sits in lane i + 16k,
+// B[k][j] in lane j + 16k, D[i][j] in register i / 4 ... precisely: register v of lane l
+// holds D[4v + l/16][l%16].
+// TM x TN 16x16 MFMA tiles per wavefront; U reduction steps (16 elements each) are
+// loaded ahead of the MFMAs that consume them; KS wavefronts split the reduction
+// dimension (small batches need the extra wavefronts to cover the load latency).
+template <int TM, int TN, int U, int KS>
+__global__ __launch_bounds__(64 * KS) void hash_project_mfma_kernel(const float* __restrict__ X, int ldx,
+                                                               const float* __restrict__ Wh,
+                                                               const float* __restrict__ bh,
+                                                               float* __restrict__ Z, int B, int H, int d) {
+  __shared__ double part[KS - 1][64][TM * TN * 4];     // partial tiles of waves 1..KS-1
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r = lane & 15, g = lane >> 4;
+  const int q0 = blockIdx.y * (16 * TM), h0 = blockIdx.x * (16 * TN);
+  // rows this lane feeds (clamped: surplus rows recompute a valid row and are not stored)
+  const float* xr[TM];
+  const float* wr[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) xr[i] = X + (size_t)min(q0 + 16 * i + r, B - 1) * ldx;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) wr[j] = Wh + (size_t)min(h0 + 16 * j + r, H - 1) * d;
+  // this wave's share of the reduction dimension, in steps of 16 elements
+  const int steps = (d + 15) / 16;
+  const int per = (steps + KS - 1) / KS;
+  const int s_begin = wave * per, s_end = min(steps, s_begin + per);
+
+  f64x4 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
+
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 a[U][TM], b[U][TN];
+  auto fetch = [&](int s0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = 16 * (s0 + u) + 4 * g;
+      // d is a multiple of 4: a 16-byte load is entirely inside the row or entirely outside
+      // (out-of-range steps load element 0 and are zeroed afterwards: the load itself stays an
+      // unconditional 16-byte load)
+      const bool ok = (s0 + u < s_end) && k < d;
+      const int kk = ok ? k : 0;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const float4 v = *reinterpret_cast<const float4*>(xr[i] + kk);
+        a[u][i] = ok ? v : zero4;
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const float4 v = *reinterpret_cast<const float4*>(wr[j] + kk);
+        b[u][j] = ok ? v : zero4;
+      }
+    }
+  };
+  fetch(s_begin);
+  for (int s0 = s_begin; s0 < s_end; s0 += U) {
+    // widen the current operands, then start the next loads so they fly during the MFMAs
+    double da[U][TM][4], db[U][TN][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        da[u][i][0] = a[u][i].x; da[u][i][1] = a[u][i].y; da[u][i][2] = a[u][i].z; da[u][i][3] = a[u][i].w;
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        db[u][j][0] = b[u][j].x; db[u][j][1] = b[u][j].y; db[u][j][2] = b[u][j].z; db[u][j][3] = b[u][j].w;
+      }
+    }
+    if (s0 + U < s_end) fetch(s0 + U);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(da[u][i][c], db[u][j][c], acc[i][j], 0, 0, 0);
+  }
+
+  if (wave > 0) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) part[wave - 1][lane][(i * TN + j) * 4 + v] = acc[i][j][v];
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int h = h0 + 16 * j + r;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int q = q0 + 16 * i + 4 * v + g;
+          double sum = acc[i][j][v];
+#pragma unroll
+          for (int w = 0; w < KS - 1; ++w) sum += part[w][lane][(i * TN + j) * 4 + v];
+          if (q < B && h < H) Z[(size_t)q * H + h] = (float)(sum + (double)bh[h]);
+        }
+      }
+  }
+}
 
 constexpr int TQ = 32;   // queries per tile
 constexpr int TH = 64;   // hash nodes per tile
@@ -66,6 +188,21 @@ __global__ __launch_bounds__(256) void hash_project_kernel(const float* __restri
 int launch_hash_project(const float* X, int ldx, const float* Wh, const float* bh, float* Z, int B,
                         int H, int d, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_HASH, s);
+  const bool vec = (d % 4 == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
+                   (reinterpret_cast<uintptr_t>(Wh) % 16 == 0);
+  if (vec) {
+    // small problems: one 16x16 tile per wavefront so that there are enough workgroups
+    const long tiles32 = (long)((H + 31) / 32) * ((B + 31) / 32);
+    if (tiles32 >= 512) {
+      dim3 g((H + 31) / 32, (B + 31) / 32);
+      hipLaunchKernelGGL((hash_project_mfma_kernel<2, 2, 2, 4>), g, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H, d);
+    } else {
+      dim3 g((H + 15) / 16, (B + 15) / 16);
+      hipLaunchKernelGGL((hash_project_mfma_kernel<1, 1, 4, 16>), g, dim3(1024), 0, s, X, ldx, Wh, bh, Z, B, H, d);
+    }
+    SLONN_HIP(hipGetLastError());
+    return SLONN_OK;
+  }
   dim3 grid((H + TH - 1) / TH, (B + TQ - 1) / TQ);
   hipLaunchKernelGGL(hash_project_kernel, grid, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H, d);
   SLONN_HIP(hipGetLastError());

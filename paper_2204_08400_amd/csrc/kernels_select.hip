@@ -3,6 +3,11 @@
 // the first m distinct nodes in rank-major, table-minor order, continuing down the
 // whole-set ranking if the lists run out.
 //
+// Two kernels.  select_block_kernel: a 256-thread workgroup per query with a 4-byte
+// first-occurrence entry per node in LDS (select_block.h); used whenever that map fits.
+// select_wave_kernel: for very wide layers (a 100 000-node output layer needs 400 KB of
+// 4-byte entries), one wavefront per query and ONE BYTE per node:
+//
 // One wavefront serves one query.  A step looks at 64 consecutive slots of the merged
 // order (slot s = rank r * L + table b, one lane per slot).  A byte map in LDS, one
 // byte per node of the layer, resolves duplicates without atomics:
@@ -12,6 +17,7 @@
 // Lanes holding the same node lower the byte until it equals the smallest claiming
 // lane (+1); only that lane -- the first occurrence in merge order -- keeps the node.
 // Survivors are compacted with a ballot and a prefix population count.
+#include "select_block.h"
 #include "slonn_internal.h"
 
 namespace slonn {
@@ -24,7 +30,7 @@ __device__ __forceinline__ int budget_of(float keep, int n) {
   return (int)m;
 }
 
-__global__ __launch_bounds__(64) void select_kernel(
+__global__ __launch_bounds__(64) void select_wave_kernel(
     const float* __restrict__ Z, int K, int L, int n, const uint32_t* __restrict__ dir,
     const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
@@ -130,6 +136,45 @@ __global__ __launch_bounds__(64) void select_kernel(
   }
 }
 
+constexpr int SEL_NT = 256;
+
+__global__ __launch_bounds__(SEL_NT) void select_block_kernel(
+    const float* __restrict__ Z, int K, int L, int n, const uint32_t* __restrict__ dir,
+    const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
+    const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
+    int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
+    float* __restrict__ yzero, int ldy) {
+  extern __shared__ __align__(16) uint32_t smem32[];
+  SelectShared<SEL_NT> sh;
+  sh.prio = smem32;
+  sh.s_off = smem32 + n;
+  sh.s_len = sh.s_off + 64;
+  sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
+  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * (SEL_NT / 64));
+
+  const int q = blockIdx.x, tid = threadIdx.x;
+  const int m = budget_of(keep[(size_t)q * keep_stride], n);
+  int32_t* out = active + (size_t)q * idx_stride;
+  const float* z = Z + (size_t)q * K * L;
+  if (yzero) {
+    float* y = yzero + (size_t)q * ldy;
+    for (int i = tid; i < n; i += SEL_NT) y[i] = 0.0f;
+  }
+  if (tid == 0) cnt[q] = m;
+  if (m == n) {   // the layer is computed in full: ascending ids, no table access
+    if (codes && tid < L) {
+      uint32_t key = 0;
+      for (int j = 0; j < K; ++j) key |= (z[tid * K + j] > 0.0f ? 1u : 0u) << j;
+      codes[(size_t)q * L + tid] = key;
+    }
+    for (int i = tid; i < n; i += SEL_NT) out[i] = i;
+    return;
+  }
+  for (int i = tid; i < n; i += SEL_NT) sh.prio[i] = 0xFFFFFFFFu;
+  __syncthreads();
+  select_block<SEL_NT>(z, K, L, n, m, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr, out);
+}
+
 __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t* __restrict__ cnt,
                                  int n, int B) {
   const int q = blockIdx.y;
@@ -146,15 +191,25 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
                   int ldy, int max_lds, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_SELECT, s);
+  const size_t lds_block = ((size_t)n + SelectShared<SEL_NT>::words_besides_prio) * 4;
+  if (lds_block <= (size_t)max_lds) {
+    if (lds_block > 65536)
+      SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
+    hipLaunchKernelGGL(select_block_kernel, dim3(B), dim3(SEL_NT), lds_block, s, Z, K, L, n, dir, ids,
+                       global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy);
+    SLONN_HIP(hipGetLastError());
+    return SLONN_OK;
+  }
   const size_t lds = 512 + (((size_t)n + 3) & ~(size_t)3);
   if (lds > (size_t)max_lds)
     SLONN_FAIL(SLONN_EUNSUPPORTED, "select: layer with %d nodes needs %zu bytes of LDS, device grants %d",
                n, lds, max_lds);
   if (lds > 65536) {
-    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_wave_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   }
-  hipLaunchKernelGGL(select_kernel, dim3(B), dim3(64), lds, s, Z, K, L, n, dir, ids, global_rank, keep,
+  hipLaunchKernelGGL(select_wave_kernel, dim3(B), dim3(64), lds, s, Z, K, L, n, dir, ids, global_rank, keep,
                      keep_stride, codes, active, cnt, idx_stride, yzero, ldy);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;

@@ -1,0 +1,143 @@
+// Node Activator query by a whole workgroup (Fig. 2 steps 3-4; Section 3.3): keys ->
+// one bucket per table -> the first m distinct nodes in rank-major, table-minor order,
+// continuing down the whole-set ranking when the lists run out.  Shared by the
+// whole-network kernel and the stand-alone select kernel.
+//
+// Slots are numbered s = rank * L + table.  Every thread takes up to MU slots per round;
+// an LDS integer min over slot numbers finds each node's first occurrence (the result
+// does not depend on the order the threads arrive in), survivors are compacted in slot
+// order with a ballot and a two-level prefix sum -- no atomic counters.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace slonn {
+
+constexpr int SELECT_MU = 4;     // most slots per thread per round
+
+template <int NT>
+struct SelectShared {            // LDS regions the caller carves out
+  uint32_t* prio;                // [n]  first-occurrence map, 0xFFFFFFFF = node not seen
+  uint32_t* s_off;               // [64] list offsets of this query
+  uint32_t* s_len;               // [64] list lengths
+  int* wave_cnt;                 // [SELECT_MU * NT/64]
+  uint32_t* s_misc;              // [4]
+  static constexpr int words_besides_prio = 64 + 64 + SELECT_MU * (NT / 64) + 4;
+};
+
+// z: the query's K*L hash projections (LDS or global).  prio[0..n) must hold 0xFFFFFFFF
+// and be visible to all threads (caller clears it and synchronises).  On return (all
+// threads, after a barrier) out[0..m) holds the chosen ids in selection order.  m < n.
+template <int NT>
+__device__ __forceinline__ void select_block(const float* z, int K, int L_, int n, int m,
+                                             const uint32_t* __restrict__ dir,
+                                             const int32_t* __restrict__ ids,
+                                             const int32_t* __restrict__ global_rank,
+                                             const SelectShared<NT>& sh, uint32_t* codes_row,
+                                             int32_t* out) {
+  constexpr int NW = NT / 64;
+  constexpr int MU = SELECT_MU;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+
+  // keys and bucket directory: one lane per table
+  if (wave == 0) {
+    const int nb1 = (1 << K) + 1;
+    uint32_t len = 0;
+    if (lane < L_) {
+      uint32_t key = 0;
+      for (int j = 0; j < K; ++j) key |= (z[lane * K + j] > 0.0f ? 1u : 0u) << j;
+      if (codes_row) codes_row[lane] = key;
+      const uint32_t lo = dir[(size_t)lane * nb1 + key], hi = dir[(size_t)lane * nb1 + key + 1];
+      sh.s_off[lane] = lo;
+      len = hi - lo;
+      sh.s_len[lane] = len;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      const uint32_t other = __shfl_xor(len, o);
+      len = other > len ? other : len;
+    }
+    if (lane == 0) sh.s_misc[0] = len;
+  }
+  __syncthreads();
+
+  // A round covers per*NT slots with all their id loads in flight together.  Lists of
+  // similar buckets overlap heavily, so a round is sized to about twelve slots per wanted
+  // node: most queries then finish in one round, i.e. one table-memory latency.
+  const uint32_t L = (uint32_t)L_;
+  const uint32_t nslots = sh.s_misc[0] * L;            // <= n * 64 < 2^32
+  int per = (12 * m + NT - 1) / NT;
+  per = per < 1 ? 1 : (per > MU ? MU : per);
+  int count = 0;
+  for (uint32_t base = 0; base < nslots && count < m; base += NT * per) {
+    int node[MU];
+    uint32_t slot[MU];
+    bool valid[MU];
+#pragma unroll
+    for (int u = 0; u < MU; ++u) {
+      slot[u] = base + u * NT + tid;
+      const uint32_t r = slot[u] / L;
+      const uint32_t b = slot[u] - r * L;
+      valid[u] = u < per && slot[u] < nslots && r < sh.s_len[b];
+      node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < MU; ++u)
+      if (valid[u]) atomicMin(&sh.prio[node[u]], slot[u]);
+    __syncthreads();
+    bool first[MU];
+    unsigned long long votes[MU];
+#pragma unroll
+    for (int u = 0; u < MU; ++u) {
+      first[u] = valid[u] && sh.prio[node[u]] == slot[u];
+      votes[u] = __ballot(first[u]);
+      if (lane == 0) sh.wave_cnt[u * NW + wave] = __popcll(votes[u]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < MU; ++u) {
+      int before = 0, total = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const int c = sh.wave_cnt[u * NW + w];
+        before += (w < wave) ? c : 0;
+        total += c;
+      }
+      if (first[u]) {
+        const int pos = count + before + __popcll(votes[u] & below);
+        if (pos < m) out[pos] = node[u];
+      }
+      count += total;
+    }
+    __syncthreads();
+  }
+  // the lists ran out: continue down the whole-set ranking (a permutation: no duplicates)
+  for (int base = 0; base < n && count < m; base += NT) {
+    const int i = base + tid;
+    int node = -1;
+    bool first = false;
+    if (i < n) {
+      node = global_rank[i];
+      first = sh.prio[node] == 0xFFFFFFFFu;
+    }
+    const unsigned long long votes = __ballot(first);
+    if (lane == 0) sh.wave_cnt[wave] = __popcll(votes);
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const int c = sh.wave_cnt[w];
+      before += (w < wave) ? c : 0;
+      total += c;
+    }
+    if (first) {
+      const int pos = count + before + __popcll(votes & below);
+      if (pos < m) out[pos] = node;
+    }
+    count += total;
+    __syncthreads();
+  }
+}
+
+}  // namespace slonn

@@ -141,7 +141,13 @@ int slonn_profile_end(double* ms_per_kind, int64_t* launches_per_kind) {
 
 int slonn_version(char* buf, size_t cap) {
   if (!buf || cap == 0) SLONN_FAIL(SLONN_EINVAL, "null buffer");
-  snprintf(buf, cap, "slonn 0.1 (gfx950, wave64, HIP %d.%d)", HIP_VERSION_MAJOR, HIP_VERSION_MINOR);
+  int dev = 0, lds = 0, cus = 0;
+  if (hipGetDevice(&dev) == hipSuccess) {
+    (void)hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  }
+  snprintf(buf, cap, "slonn 0.1 (gfx950, wave64, HIP %d.%d; device: %d CUs, %d bytes LDS per workgroup)",
+           HIP_VERSION_MAJOR, HIP_VERSION_MINOR, cus, lds);
   return SLONN_OK;
 }
 

@@ -163,9 +163,14 @@ def test_select_teacher_forced(rt, oracle):
         cur = tap["out"]
 
 
-def test_ell_input_and_activated_softmax_output(rt, oracle):
-    """Wide sparse-input model with the Node Activator on the output layer only."""
-    dims = (5000, 128, 3000)
+@pytest.mark.parametrize("n_out", [3000, 50000], ids=["block-select", "wave-select"])
+def test_ell_input_and_activated_softmax_output(rt, oracle, n_out):
+    """Wide sparse-input model with the Node Activator on the output layer only.  The
+    50 000-node output is too wide for a 4-byte-per-node map in LDS and takes the
+    one-wavefront-per-query select kernel."""
+    dims = (5000, 128, n_out)
+    from paper_2204_08400_amd import slonn
+    _say(slonn.slonn_version())
     layers, net, _ = make_case(oracle, dims, 8, 12, seed=31, hashed=[1], cap=400, last_act=wl.ACT_SOFTMAX,
                                ell_nnz=40, N_build=300)
     # the GPU stores the first layer input-major
