@@ -272,3 +272,111 @@ def test_build_tables_matches_oracle(rt, oracle):
     g2 = rt.Network(layers)
     g2.build_tables(Xb)
     assert g2.export_tables() == blob
+
+
+# --------------------------------------------------------------------------- #
+# the benchmark configurations at their real shapes
+# --------------------------------------------------------------------------- #
+def _config_case(rt, cfg_name, n_build, n_query, seed_w=0):
+    """The network of a benchmark configuration exactly as bench.py sets it up: hash nodes
+    from the device's dense pass, tables built on the device; the oracle loads the same
+    table blob (the build itself is compared with the oracle's in its own test)."""
+    import torch
+    from oracle import slonn_oracle
+    cfg = wl.CONFIGS[cfg_name]
+    layers = wl.make_mlp(cfg.dims, seed=seed_w, w_dtype=cfg.w_dtype, last_act=cfg.last_act)
+    Xb = wl.make_inputs(cfg, n_build, seed=1)
+    plain = rt.Network(layers)
+    xb = torch.from_numpy(Xb).cuda()
+    dn = plain.dense_forward(xb, layer_outs=True)
+    for l in cfg.hashed_layers:
+        var = dn["layers"][l].double().var(dim=0, unbiased=False).cpu().numpy()
+        layers[l].K, layers[l].L = cfg.K, cfg.L
+        layers[l].list_cap = layers[l].d_out
+        layers[l].hash_nodes = wl.sample_hash_nodes(var, cfg.K, cfg.L, seed=3 + l)
+    del plain, dn
+    g = rt.Network(layers)
+    g.build_tables(xb)
+    net = slonn_oracle.OracleNet(layers)
+    net.import_tables(g.export_tables())
+    Xq = wl.make_inputs(cfg, n_query, seed=2)
+    return cfg, layers, g, net, Xq
+
+
+def test_config_c1_fmnist_shape(rt, oracle):
+    """784-112-10, K=6 L=10, keep 0.25, batches of 1 and 64 (full 1000-input sets)."""
+    cfg, layers, g, net, Xq = _config_case(rt, "C1", 1000, 1000)
+    ref = net.sparse_forward(Xq, 0.25)
+    for path in ("fused", "layers"):
+        g.set_path(path)
+        for B in (1, 64):
+            _say(f"C1 path={path} batch={B}")
+            n = 8 if B == 1 else 1000
+            outs = []
+            for s in range(0, n, B):
+                outs.append(to_numpy_result(g.sparse_forward(Xq[s:s + B], 0.25, taps=True)))
+            got = {"out": np.concatenate([o["out"] for o in outs]),
+                   "argmax": np.concatenate([o["argmax"] for o in outs]),
+                   "taps": {k: [None if outs[0]["taps"][k][l] is None else
+                                np.concatenate([o["taps"][k][l] for o in outs]) for l in range(2)]
+                            for k in outs[0]["taps"]}}
+            sub = {"out": ref["out"][:n], "argmax": ref["argmax"][:n],
+                   "layers": [{k: v[:n] for k, v in lay.items()} for lay in ref["layers"]]}
+            _say(f"  {compare_sparse(got, sub, layers, f'C1 {path} B={B}')}")
+
+
+def test_config_c2_bench_shape(rt, oracle):
+    """The workload bench.py times (784-1024-1024-10, K=8 L=16, batch 256, path auto):
+    full 10 000-input build set, the first 1024 queries in batches of 256, checked with
+    taps; then the same batches without taps, as timed, must give the same bits."""
+    import torch
+    cfg, layers, g, net, Xq = _config_case(rt, "C2", 10000, 1024)
+    g.set_path("auto")
+    for keep in (0.05, 0.25, 1.0):
+        _say(f"C2 keep={keep}")
+        ref = net.sparse_forward(Xq, keep)
+        for s in range(0, 1024, 256):
+            xb = Xq[s:s + 256]
+            got = to_numpy_result(g.sparse_forward(xb, keep, taps=True))
+            sub = {"out": ref["out"][s:s + 256], "argmax": ref["argmax"][s:s + 256],
+                   "layers": [{k: v[s:s + 256] for k, v in lay.items()} for lay in ref["layers"]]}
+            rep = compare_sparse(got, sub, layers, f"C2 keep {keep} batch {s // 256}")
+            plain = to_numpy_result(g.sparse_forward(xb, keep))
+            assert np.array_equal(plain["out"], got["out"]) and np.array_equal(plain["argmax"], got["argmax"])
+        _say(f"  last batch report {rep}")
+
+
+def test_config_c3_shape_sampled(rt, oracle):
+    """3072-4096-4096-4096-100, K=10 L=32 (per-layer path): tables from a 4096-input build
+    set, 48 queries checked in full against the oracle, batch 32 and a ragged batch of 16."""
+    cfg, layers, g, net, Xq = _config_case(rt, "C3", 4096, 48)
+    for keep in (0.05, 0.5):
+        _say(f"C3 keep={keep}")
+        ref = net.sparse_forward(Xq, keep)
+        outs = [to_numpy_result(g.sparse_forward(Xq[s:e], keep, taps=True)) for s, e in ((0, 32), (32, 48))]
+        got = {"out": np.concatenate([o["out"] for o in outs]),
+               "argmax": np.concatenate([o["argmax"] for o in outs]),
+               "taps": {k: [None if outs[0]["taps"][k][l] is None else
+                            np.concatenate([o["taps"][k][l] for o in outs]) for l in range(4)]
+                        for k in outs[0]["taps"]}}
+        _say(f"  {compare_sparse(got, ref, layers, f'C3 keep {keep}')}")
+
+
+def test_config_c5_shape_sampled(rt, oracle):
+    """Deep bf16 MLP with mixed per-query keep fractions, at reduced depth/width so the
+    oracle finishes in seconds: 1024-[2048]x3-1000, K=12 L=64, keep ~ U[0.02, 0.3]."""
+    import dataclasses
+    base = wl.CONFIGS["C5"]
+    cfg = dataclasses.replace(base, dims=(1024, 2048, 2048, 2048, 1000), hashed_layers=(0, 1, 2))
+    wl.CONFIGS["C5small"] = cfg
+    try:
+        cfg, layers, g, net, Xq = _config_case(rt, "C5small", 3000, 96)
+    finally:
+        del wl.CONFIGS["C5small"]
+    keep = wl.keep_uniform(96, 0.02, 0.3, 7)
+    ref = net.sparse_forward(Xq, keep)
+    for path in ("layers", "fused"):
+        g.set_path(path)
+        _say(f"C5-shaped path={path}")
+        got = to_numpy_result(g.sparse_forward(Xq, _keep_tensor(keep), taps=True))
+        _say(f"  {compare_sparse(got, ref, layers, f'C5-shaped {path}')}")
