@@ -149,6 +149,59 @@ __global__ __launch_bounds__(256) void gather_forward_kernel(
   }
 }
 
+// Row-block variant for layers whose weight matrix is much larger than an L2 slice:
+// workgroup (q, block) evaluates the rows of query q that lie in one block of consecutive
+// weight rows (about a megabyte).  The grid runs over queries fastest, so the workgroups
+// resident at any moment all read the same one or two row blocks and each XCD's L2
+// serves a row to every query that selected it instead of fetching it again.
+template <int WDT>
+__global__ __launch_bounds__(256) void gather_blocked_kernel(
+    const void* __restrict__ W, const float* __restrict__ bias, const float* __restrict__ X, int ldx,
+    RowBlocking rb, float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int act) {
+  extern __shared__ __align__(16) float xs[];
+  using C = Chunk<WDT>;
+  using vec_t = typename C::vec_t;
+  const int q = blockIdx.x, blk = blockIdx.y;
+  const int32_t* off = rb.blk_off + (size_t)q * (rb.nblk + 1);
+  const int c0 = off[blk], c1 = off[blk + 1];
+  if (c0 >= c1) return;
+  const int tid = threadIdx.x;
+  const float* x = X + (size_t)q * ldx;
+  for (int i = tid; i < (d >> 2); i += 256)
+    reinterpret_cast<float4*>(xs)[i] = reinterpret_cast<const float4*>(x)[i];
+  __syncthreads();
+  const int g = tid / LANES_PER_ROW, l = tid % LANES_PER_ROW;
+  const int nv = d / C::ELEMS;
+  const int32_t* pidx = rb.part_idx + (size_t)q * rb.stride;
+  const int32_t* ppos = rb.part_pos + (size_t)q * rb.stride;
+  // two rows per 16-lane group at a time
+  for (int t0 = c0 + 2 * g; t0 < c1; t0 += 2 * (256 / LANES_PER_ROW)) {
+    const bool two = t0 + 1 < c1;
+    const int j0 = pidx[t0], j1 = pidx[two ? t0 + 1 : t0];
+    const vec_t* w0 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                     (size_t)j0 * d * (WDT == SLONN_F32 ? 4 : 2));
+    const vec_t* w1 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                     (size_t)j1 * d * (WDT == SLONN_F32 ? 4 : 2));
+    float acc0 = 0.0f, acc1 = 0.0f;
+#pragma unroll 4
+    for (int i = l; i < nv; i += LANES_PER_ROW) {
+      const vec_t a0 = w0[i], a1 = w1[i];
+      const float* xp = xs + i * C::ELEMS;
+      acc0 = C::dot(a0, xp, acc0);
+      acc1 = C::dot(a1, xp, acc1);
+    }
+    acc0 = reduce16(acc0);
+    acc1 = reduce16(acc1);
+    if (l == 0 || (l == 1 && two)) {
+      const int j = l == 0 ? j0 : j1;
+      float z = (l == 0 ? acc0 : acc1) + bias[j];
+      if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+      Y[(size_t)q * ldy + j] = z;
+      if (yc) yc[(size_t)q * ldc + ppos[t0 + l]] = z;
+    }
+  }
+}
+
 // First layer on sparse (ELL) input.  With input-major storage every non-zero pulls
 // one contiguous row of n weights; thread j accumulates node j.
 template <int WDT>
@@ -238,6 +291,25 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
     if (vec) SLONN_LAUNCH_GATHER(SLONN_BF16, true); else SLONN_LAUNCH_GATHER(SLONN_BF16, false);
   }
 #undef SLONN_LAUNCH_GATHER
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+int launch_gather_blocked(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
+                          const RowBlocking& rb, float* Y, int ldy, float* yc, int ldc, int B, int d,
+                          int n, int act, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_GATHER, s);
+  if (B <= 0) return SLONN_OK;
+  const size_t lds = ((size_t)d + 8) * sizeof(float);
+  if (lds > 65536) SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
+  dim3 grid(B, rb.nblk);
+  const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
+  if (w_dtype == SLONN_F32)
+    hipLaunchKernelGGL((gather_blocked_kernel<SLONN_F32>), grid, dim3(256), lds, s, W, bias, X, ldx, rb, Y,
+                       ldy, yc, ldc, d, a);
+  else
+    hipLaunchKernelGGL((gather_blocked_kernel<SLONN_BF16>), grid, dim3(256), lds, s, W, bias, X, ldx, rb, Y,
+                       ldy, yc, ldc, d, a);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

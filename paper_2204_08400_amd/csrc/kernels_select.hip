@@ -143,7 +143,7 @@ __global__ __launch_bounds__(SEL_NT) void select_block_kernel(
     const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
-    float* __restrict__ yzero, int ldy) {
+    float* __restrict__ yzero, int ldy, RowBlocking rb) {
   extern __shared__ __align__(16) uint32_t smem32[];
   SelectShared<SEL_NT> sh;
   sh.prio = smem32;
@@ -168,11 +168,55 @@ __global__ __launch_bounds__(SEL_NT) void select_block_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += SEL_NT) out[i] = i;
+    if (rb.part_idx) {      // every row is active: the groups are the row blocks themselves
+      for (int i = tid; i < n; i += SEL_NT) {
+        rb.part_idx[(size_t)q * rb.stride + i] = i;
+        rb.part_pos[(size_t)q * rb.stride + i] = i;
+      }
+      for (int b = tid; b <= rb.nblk; b += SEL_NT)
+        rb.blk_off[(size_t)q * (rb.nblk + 1) + b] = min(b * rb.rows_per_block, n);
+    }
     return;
   }
   for (int i = tid; i < n; i += SEL_NT) sh.prio[i] = 0xFFFFFFFFu;
   __syncthreads();
   select_block<SEL_NT>(z, K, L, n, m, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr, out);
+
+  if (rb.part_idx) {
+    // Regroup the list by weight-row block (counting sort; the order inside a group does not
+    // matter: outputs are written by node id and by selection position).  The map's first
+    // nblk+1 words are free again and serve as the histogram.
+    uint32_t* hist = sh.prio;
+    for (int b = tid; b <= rb.nblk; b += SEL_NT) hist[b] = 0;
+    __syncthreads();
+    for (int t = tid; t < m; t += SEL_NT) atomicAdd(&hist[out[t] / rb.rows_per_block], 1u);
+    __syncthreads();
+    if (tid < 64) {         // exclusive prefix sum over the row blocks by one wavefront
+      uint32_t carry = 0;
+      for (int b0 = 0; b0 <= rb.nblk; b0 += 64) {
+        const int b = b0 + tid;
+        const uint32_t v = (b < rb.nblk) ? hist[b] : 0u;
+        uint32_t incl = v;
+        for (int o = 1; o < 64; o <<= 1) {
+          const uint32_t up = __shfl_up(incl, o);
+          if (tid >= o) incl += up;
+        }
+        if (b <= rb.nblk) {
+          const uint32_t excl = carry + incl - v;
+          hist[b] = excl;
+          rb.blk_off[(size_t)q * (rb.nblk + 1) + b] = (int32_t)excl;
+        }
+        carry += __shfl(incl, 63);
+      }
+    }
+    __syncthreads();
+    for (int t = tid; t < m; t += SEL_NT) {
+      const int id = out[t];
+      const uint32_t p = atomicAdd(&hist[id / rb.rows_per_block], 1u);
+      rb.part_idx[(size_t)q * rb.stride + p] = id;
+      rb.part_pos[(size_t)q * rb.stride + p] = t;
+    }
+  }
 }
 
 __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t* __restrict__ cnt,
@@ -189,7 +233,7 @@ __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t*
 int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
-                  int ldy, int max_lds, hipStream_t s) {
+                  int ldy, int max_lds, const RowBlocking* rb, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_SELECT, s);
   const size_t lds_block = ((size_t)n + SelectShared<SEL_NT>::words_besides_prio) * 4;
   if (lds_block <= (size_t)max_lds) {
@@ -197,7 +241,8 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
       SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
     hipLaunchKernelGGL(select_block_kernel, dim3(B), dim3(SEL_NT), lds_block, s, Z, K, L, n, dir, ids,
-                       global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy);
+                       global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy,
+                       rb ? *rb : RowBlocking{});
     SLONN_HIP(hipGetLastError());
     return SLONN_OK;
   }
@@ -213,6 +258,10 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
                      keep_stride, codes, active, cnt, idx_stride, yzero, ldy);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
+}
+
+bool select_fills_row_blocks(int n, int max_lds) {
+  return ((size_t)n + SelectShared<SEL_NT>::words_besides_prio) * 4 <= (size_t)max_lds;
 }
 
 int launch_fill_iota(int32_t* idx, int stride, int32_t* cnt, int n, int B, hipStream_t s) {

@@ -47,7 +47,9 @@ struct Workspace {
   float* z = nullptr;                   // [B][max_H]
   int32_t* active = nullptr;            // [B][max_n_activated]
   int32_t* cnt = nullptr;               // [B]
-  float* keep_one = nullptr;            // one float holding 1.0 (unused slots)
+  int32_t* part_idx = nullptr;          // [B][max_n_activated] lists regrouped by row block
+  int32_t* part_pos = nullptr;          // [B][max_n_activated]
+  int32_t* blk_off = nullptr;           // [B][MAX_ROW_BLOCKS + 1]
   size_t bytes = 0;
   int max_n = 0, max_H = 0, max_na = 0;
 };
@@ -73,6 +75,9 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   w->z = reinterpret_cast<float*>(take((size_t)B * std::max(max_H, 1) * 4));
   w->active = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->cnt = reinterpret_cast<int32_t*>(take((size_t)B * 4));
+  w->part_idx = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
+  w->part_pos = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
+  w->blk_off = reinterpret_cast<int32_t*>(take((size_t)B * (MAX_ROW_BLOCKS + 1) * 4));
   w->bytes = off;
 }
 
@@ -476,7 +481,8 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
   int rc = launch_hash_project(X_l, L.d_in, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
   if (rc) return rc;
   return launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank, keep, keep_stride,
-                       B, codes_out, active_idx, active_cnt, idx_stride, nullptr, 0, m->max_lds_bytes, s);
+                       B, codes_out, active_idx, active_cnt, idx_stride, nullptr, 0, m->max_lds_bytes,
+                       nullptr, s);
 }
 
 int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
@@ -578,14 +584,35 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       if (is_last && Y->cnt && !tap_cnt) acnt = Y->cnt;
       rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
       if (rc) return rc;
+      // Weight matrices well beyond an L2 slice are walked in blocks of rows (about 1 MiB)
+      // so that concurrently running workgroups share them; small ones are read as listed.
+      RowBlocking rb;
+      const size_t esz = L.w_dtype == SLONN_F32 ? 4 : 2;
+      const size_t row_bytes = (size_t)L.d_in * esz;
+      const bool rows_vec = row_bytes % 16 == 0 && L.d_in % 4 == 0 && ldcur % 4 == 0 &&
+                            reinterpret_cast<uintptr_t>(L.W) % 16 == 0 && reinterpret_cast<uintptr_t>(cur) % 16 == 0;
+      if (B >= 2 && rows_vec && row_bytes * L.d_out > ((size_t)3 << 20) &&
+          select_fills_row_blocks(L.d_out, m->max_lds_bytes)) {
+        int rpb = 16;
+        while ((size_t)rpb * 2 * row_bytes <= ((size_t)1 << 20)) rpb *= 2;
+        while ((L.d_out + rpb - 1) / rpb > MAX_ROW_BLOCKS) rpb *= 2;
+        rb.rows_per_block = rpb;
+        rb.nblk = (L.d_out + rpb - 1) / rpb;
+        rb.stride = w.max_na;
+        rb.part_idx = w.part_idx; rb.part_pos = w.part_pos; rb.blk_off = w.blk_off;
+      }
       rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank,
                          keep + (size_t)l * keep_lstride, keep_qstride, B, codes, aidx, acnt, astride, out,
-                         ldo, m->max_lds_bytes, s);
+                         ldo, m->max_lds_bytes, rb.part_idx ? &rb : nullptr, s);
       if (rc) return rc;
       act_list = aidx; act_cnt = acnt; act_stride = astride;
       if (is_last && Y->val) yc = Y->val;
-      rc = launch_gather_forward(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, L.d_out, out, ldo,
-                                 yc, Y->stride, B, L.d_in, L.d_out, act, s);
+      if (rb.part_idx)
+        rc = launch_gather_blocked(L.W, L.w_dtype, L.bias, cur, ldcur, rb, out, ldo, yc, Y->stride, B, L.d_in,
+                                   L.d_out, act, s);
+      else
+        rc = launch_gather_forward(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, L.d_out, out, ldo,
+                                   yc, Y->stride, B, L.d_in, L.d_out, act, s);
       if (rc) return rc;
       if (is_last && Y->idx && tap_idx)
         SLONN_HIP(hipMemcpy2DAsync(Y->idx, (size_t)Y->stride * 4, aidx, (size_t)astride * 4,

@@ -111,6 +111,16 @@ struct FusedArgs {
 size_t fused_lds_bytes(const FusedArgs& a);
 int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s);
 
+// Active lists regrouped by weight-row block, so that the workgroups running at the same
+// time read the same few megabytes of the weight matrix (L2-sized blocks of rows).
+struct RowBlocking {
+  int rows_per_block = 0, nblk = 0, stride = 0;
+  int32_t* part_idx = nullptr;   // [B][stride]  node ids, grouped by row block
+  int32_t* part_pos = nullptr;   // [B][stride]  position of each id in the selection order
+  int32_t* blk_off = nullptr;    // [B][nblk+1]  start of each row block's group
+};
+constexpr int MAX_ROW_BLOCKS = 1024;
+
 // ---- kernel launchers (each validates nothing: callers have checked shapes) ----
 
 // Z[q][h] = Wh[h] . X[q] + bh[h], fp64 accumulation, rounded once to fp32.
@@ -121,7 +131,15 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
 int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
-                  int ldy, int max_lds, hipStream_t s);
+                  int ldy, int max_lds, const RowBlocking* rb, hipStream_t s);
+// true when launch_select will fill rb for a layer of n nodes (the workgroup kernel is used)
+bool select_fills_row_blocks(int n, int max_lds);
+
+// Same result as launch_gather_forward from row-block-grouped lists: workgroup (q, block)
+// evaluates the rows of query q that fall into that block of the weight matrix.
+int launch_gather_blocked(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
+                          const RowBlocking& rb, float* Y, int ldy, float* yc, int ldc, int B, int d,
+                          int n, int act, hipStream_t s);
 
 // y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).
 // yc (nullable) receives the values in list order.

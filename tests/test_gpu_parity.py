@@ -41,7 +41,9 @@ def _gpu_net(rt, layers, net, rows_are_inputs=False, path="layers"):
 def _fused_ok(case):
     """row lengths must be multiples of 16 bytes for the whole-network kernel"""
     mult = 8 if case.get("w_dtype", wl.W_F32) == wl.W_BF16 else 4
-    return all(d % mult == 0 for d in case["dims"][:-1])
+    dims = case["dims"]
+    small = all(dims[i] * dims[i + 1] * (16 // mult) <= (8 << 20) for i in range(len(dims) - 1))
+    return small and all(d % mult == 0 for d in dims[:-1])
 
 
 def _keep_tensor(keep):
@@ -78,6 +80,7 @@ CASES = [
     dict(dims=(96, 1000, 640, 12), K=6, L=10, kind="u01", B=129, last_act=wl.ACT_SOFTMAX),
     dict(dims=(64, 384, 384, 10), K=4, L=8, kind="normal", B=65, w_dtype=wl.W_BF16),
     dict(dims=(75, 333, 21), K=3, L=64, kind="u01", B=5),                       # odd d: scalar path
+    dict(dims=(256, 4096, 520, 10), K=6, L=12, kind="clip3", B=37, N_build=128),  # > 3 MiB matrices: row-block gather
 ]
 
 
@@ -90,7 +93,7 @@ def test_sparse_forward_matches_oracle(rt, oracle, case, path):
         pytest.skip("model does not qualify for the whole-network kernel")
     layers, net, Xb = make_case(oracle, dims, case["K"], case["L"], seed=17, cap=case.get("cap"),
                                 w_dtype=case.get("w_dtype", wl.W_F32), last_act=case.get("last_act", wl.ACT_NONE),
-                                kind=case["kind"])
+                                kind=case["kind"], N_build=case.get("N_build", 256))
     g = _gpu_net(rt, layers, net, path=path)
     X = make_queries(dims, B, seed=99, kind=case["kind"])
     for keep in (0.05, 0.3, 0.77, 1.0):
