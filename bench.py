@@ -34,6 +34,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--path", default="auto", choices=["auto", "layers", "fused"])
+    ap.add_argument("--build-inputs", type=int, default=0, help="size of the table-training set (default: the config's)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, for scaling rocprofv3 byte counters")
     args = ap.parse_args()
@@ -56,7 +57,7 @@ def main():
     # ---- synthetic workload (seeds: weights 0, build set 1, queries 2, hash nodes 3) ----
     t0 = time.time()
     layers = wl.make_mlp(cfg.dims, seed=0, w_dtype=cfg.w_dtype, last_act=cfg.last_act)
-    X_build = wl.make_inputs(cfg, cfg.n_inputs, seed=1)
+    X_build = wl.make_inputs(cfg, args.build_inputs or cfg.n_inputs, seed=1)
     X_query = wl.make_inputs(cfg, cfg.n_inputs, seed=2)
     log(f"generated {args.config} in {time.time() - t0:.1f}s")
 
@@ -67,7 +68,9 @@ def main():
     for l in cfg.hashed_layers:
         var = dn["layers"][l].double().var(dim=0, unbiased=False).cpu().numpy()
         layers[l].K, layers[l].L = cfg.K, cfg.L
-        layers[l].list_cap = layers[l].d_out
+        # lists never need more entries than the largest budget below d_out that will be asked for
+        top = max([k for k in cfg.keeps if k < 1.0] + ([cfg.keep_range[1]] if cfg.keep_range else []) + [args.keep])
+        layers[l].list_cap = min(layers[l].d_out, int(np.ceil(top * layers[l].d_out)) + 1)
         layers[l].hash_nodes = wl.sample_hash_nodes(var, cfg.K, cfg.L, seed=3 + l)
     del plain, dn
     net = runtime.Network(layers)
@@ -89,8 +92,17 @@ def main():
 
     def run(keep_t, steps, first=0):
         for i in range(steps):
-            slonn.slonn_sparse_forward(net.model, net.tables, batches[(first + i) % n_batches], B, keep_t,
-                                       0, 0, out, None, ws, stream)
+            b = (first + i) % n_batches
+            if mixed is not None:      # one keep fraction per query (mixed SLOs in one batch)
+                slonn.slonn_sparse_forward(net.model, net.tables, batches[b], B, mixed[b * B:(b + 1) * B],
+                                           1, 0, out, None, ws, stream)
+            else:
+                slonn.slonn_sparse_forward(net.model, net.tables, batches[b], B, keep_t, 0, 0, out, None,
+                                           ws, stream)
+
+    mixed = None
+    if cfg.keep_range:
+        mixed = torch.from_numpy(wl.keep_uniform(nq, cfg.keep_range[0], cfg.keep_range[1], seed=6)).to(dev)
 
     def timed(keep, steps, warm):
         keep_t = torch.full((1,), keep, dtype=torch.float32, device=dev)
@@ -105,33 +117,33 @@ def main():
         wall = time.perf_counter() - t0
         return e0.elapsed_time(e1) / 1e3, wall
 
-    def gathered_bytes_per_query(keep):
-        tot = 0
-        for l, lay in enumerate(layers):
+    def mean_budget(keep, n):
+        """mean node budget of a layer of n nodes (nearest whole node, at least one)"""
+        k = mixed.cpu().numpy().astype(np.float64) if (mixed is not None and keep is None) else \
+            np.asarray([np.float32(keep)], np.float64)
+        return float(np.clip(np.floor(k * n + 0.5), 1, n).mean())
+
+    def gathered_bytes_per_query(keep, activated_only=True):
+        tot = 0.0
+        for lay in layers:
             esz = 4 if lay.w_dtype == wl.W_F32 else 2
             if lay.K > 0:
-                m = int(min(lay.d_out, max(1, np.floor(np.float64(np.float32(keep)) * lay.d_out + 0.5))))
-                tot += m * lay.d_in * esz
+                tot += mean_budget(keep, lay.d_out) * lay.d_in * esz
+            elif not activated_only:
+                tot += lay.d_out * lay.d_in * esz
         return tot
 
-    if args.calibrate_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)            # plain copy kernel: reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
-
+    head_keep = None if mixed is not None else args.keep
     # ---- headline: K steps at the chosen keep fraction ----
     dev_s, wall_s = timed(args.keep, K, W)
     secs = max(dev_s, wall_s)             # the host loop must keep up: report the slower clock
     qps = K * B / secs
-    eff_gbps = qps * gathered_bytes_per_query(args.keep) / 1e9
+    eff_gbps = qps * gathered_bytes_per_query(head_keep) / 1e9
     log(f"keep {args.keep}: {qps:,.0f} q/s, {secs / K * 1e6:.1f} us/step, effective {eff_gbps:,.0f} GB/s")
 
     # ---- per-kernel durations over the same steps (HIP events on the launch stream) ----
     keep_t = torch.full((1,), args.keep, dtype=torch.float32, device=dev)
-    slonn.slonn_profile_begin(K * 16)
+    slonn.slonn_profile_begin(K * (4 * len(layers) + 4))
     run(keep_t, K, W)
     prof = slonn.slonn_profile_end()
     split_us = {k: (v[0] * 1e3 / max(v[1], 1)) for k, v in prof.items() if v[1]}
@@ -139,14 +151,7 @@ def main():
     # dominant kernel: the one holding most of the step.  Its algorithmic bytes per launch are
     # the weight rows the method must read: budget x row bytes for each activated layer, the whole
     # matrix per query for a layer computed in full, summed over the layers that launch covers.
-    bytes_per_step = 0
-    for lay in layers:
-        esz = 4 if lay.w_dtype == wl.W_F32 else 2
-        if lay.K > 0:
-            m = int(min(lay.d_out, max(1, np.floor(np.float64(np.float32(args.keep)) * lay.d_out + 0.5))))
-        else:
-            m = lay.d_out
-        bytes_per_step += B * m * lay.d_in * esz
+    bytes_per_step = B * gathered_bytes_per_query(head_keep, activated_only=False)
     dom = "fused" if prof["fused"][1] else "gather"
     g_ms, g_n = prof[dom]
     launches_per_step = g_n / K
@@ -175,7 +180,7 @@ def main():
     # ---- the other keep fractions and the dense baseline, briefly ----
     if not args.no_sweep:
         sweep = {}
-        for keep in cfg.keeps:
+        for keep in (cfg.keeps if mixed is None else ()):
             d_s, w_s = timed(keep, 120, 20)
             s = max(d_s, w_s)
             q = 120 * B / s
@@ -201,7 +206,7 @@ def main():
         onet.import_tables(net.export_tables())
         n_s = min(nq, 4096)
         t0 = time.perf_counter()
-        onet.sparse_forward(X_query[:n_s], args.keep, taps=False)
+        onet.sparse_forward(X_query[:n_s], args.keep if mixed is None else mixed[:n_s].cpu().numpy(), taps=False)
         dt = time.perf_counter() - t0
         cpu = {"value": round(n_s / dt, 1), "unit": "queries/s", "cores": onet.threads, "kind": "oracle",
                "sample": f"first {n_s} queries of the same query set, keep {args.keep}, all layers, "
@@ -215,7 +220,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.config}: MLP {'-'.join(map(str, cfg.dims))}, K={cfg.K} L={cfg.L} on "
                                f"{len(cfg.hashed_layers)} hidden layers, {nq} queries", "batch": B,
-                   "keep": args.keep, "queries_per_step": B, "path": args.path},
+                   "keep": args.keep if mixed is None else f"per query U[{cfg.keep_range[0]}, {cfg.keep_range[1]}]",
+                   "queries_per_step": B, "path": args.path},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     line.update(extra)

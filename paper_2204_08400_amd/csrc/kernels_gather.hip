@@ -170,12 +170,14 @@ __global__ __launch_bounds__(256) void gather_blocked_kernel(
   for (int i = tid; i < (d >> 2); i += 256)
     reinterpret_cast<float4*>(xs)[i] = reinterpret_cast<const float4*>(x)[i];
   __syncthreads();
-  const int g = tid / LANES_PER_ROW, l = tid % LANES_PER_ROW;
+  // One wavefront per row, two rows in flight: a (query, block) pair often holds only a
+  // dozen rows, which would leave most 16-lane groups idle; these rows are long (the
+  // matrix is large), so 64 lanes x 16 bytes per step still means many steps per row.
+  const int wave = tid >> 6, lane = tid & 63;
   const int nv = d / C::ELEMS;
   const int32_t* pidx = rb.part_idx + (size_t)q * rb.stride;
   const int32_t* ppos = rb.part_pos + (size_t)q * rb.stride;
-  // two rows per 16-lane group at a time
-  for (int t0 = c0 + 2 * g; t0 < c1; t0 += 2 * (256 / LANES_PER_ROW)) {
+  for (int t0 = c0 + 2 * wave; t0 < c1; t0 += 8) {
     const bool two = t0 + 1 < c1;
     const int j0 = pidx[t0], j1 = pidx[two ? t0 + 1 : t0];
     const vec_t* w0 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
@@ -184,20 +186,23 @@ __global__ __launch_bounds__(256) void gather_blocked_kernel(
                                                      (size_t)j1 * d * (WDT == SLONN_F32 ? 4 : 2));
     float acc0 = 0.0f, acc1 = 0.0f;
 #pragma unroll 4
-    for (int i = l; i < nv; i += LANES_PER_ROW) {
+    for (int i = lane; i < nv; i += 64) {
       const vec_t a0 = w0[i], a1 = w1[i];
       const float* xp = xs + i * C::ELEMS;
       acc0 = C::dot(a0, xp, acc0);
       acc1 = C::dot(a1, xp, acc1);
     }
-    acc0 = reduce16(acc0);
-    acc1 = reduce16(acc1);
-    if (l == 0 || (l == 1 && two)) {
-      const int j = l == 0 ? j0 : j1;
-      float z = (l == 0 ? acc0 : acc1) + bias[j];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      acc0 += __shfl_xor(acc0, o);
+      acc1 += __shfl_xor(acc1, o);
+    }
+    if (lane == 0 || (lane == 1 && two)) {
+      const int j = lane == 0 ? j0 : j1;
+      float z = (lane == 0 ? acc0 : acc1) + bias[j];
       if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
       Y[(size_t)q * ldy + j] = z;
-      if (yc) yc[(size_t)q * ldc + ppos[t0 + l]] = z;
+      if (yc) yc[(size_t)q * ldc + ppos[t0 + lane]] = z;
     }
   }
 }

@@ -193,7 +193,7 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
   if (vec) {
     // small problems: one 16x16 tile per wavefront so that there are enough workgroups
     const long tiles32 = (long)((H + 31) / 32) * ((B + 31) / 32);
-    if (tiles32 >= 512) {
+    if (tiles32 >= 128) {
       dim3 g((H + 31) / 32, (B + 31) / 32);
       hipLaunchKernelGGL((hash_project_mfma_kernel<2, 2, 2, 4>), g, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H, d);
     } else {

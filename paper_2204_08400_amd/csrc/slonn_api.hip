@@ -584,7 +584,7 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       if (is_last && Y->cnt && !tap_cnt) acnt = Y->cnt;
       rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
       if (rc) return rc;
-      // Weight matrices well beyond an L2 slice are walked in blocks of rows (about 1 MiB)
+      // Weight matrices well beyond an L2 slice are walked in blocks of rows (about 2 MiB)
       // so that concurrently running workgroups share them; small ones are read as listed.
       RowBlocking rb;
       const size_t esz = L.w_dtype == SLONN_F32 ? 4 : 2;
@@ -594,7 +594,7 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       if (B >= 2 && rows_vec && row_bytes * L.d_out > ((size_t)3 << 20) &&
           select_fills_row_blocks(L.d_out, m->max_lds_bytes)) {
         int rpb = 16;
-        while ((size_t)rpb * 2 * row_bytes <= ((size_t)1 << 20)) rpb *= 2;
+        while ((size_t)rpb * 2 * row_bytes <= ((size_t)2 << 20)) rpb *= 2;
         while ((L.d_out + rpb - 1) / rpb > MAX_ROW_BLOCKS) rpb *= 2;
         rb.rows_per_block = rpb;
         rb.nblk = (L.d_out + rpb - 1) / rpb;
@@ -622,6 +622,10 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
     } else if (l == 0 && X->format == SLONN_ELL) {
       rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
                             ldo, B, L.d_in, L.d_out, act, s);
+      if (rc) return rc;
+    } else if ((size_t)((B + 63) / 64) * ((L.d_out + 63) / 64) >= 256) {
+      // a layer computed in full for a real batch is a dense contraction: matrix cores
+      rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out, act, s);
       if (rc) return rc;
     } else {
       rc = launch_gather_forward(L.W, L.w_dtype, L.bias, cur, ldcur, nullptr, nullptr, 0, L.d_out, out, ldo,
