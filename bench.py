@@ -62,31 +62,51 @@ def main():
     log(f"generated {args.config} in {time.time() - t0:.1f}s")
 
     # hash nodes: variance of the full network's activations on the build set (device dense pass)
-    plain = runtime.Network(layers)
-    xb = torch.from_numpy(X_build).to(dev)
+    ell = cfg.input_kind == "ell"
+    if ell:     # wide sparse-input model: first layer stored input-major on the device
+        layers[0].W = np.ascontiguousarray(layers[0].W.T)
+
+    def to_dev(X):
+        if ell:
+            return tuple(torch.from_numpy(np.ascontiguousarray(a)).to(dev) for a in X)
+        return torch.from_numpy(X).to(dev)
+
+    plain = runtime.Network(layers, first_layer_rows_are_inputs=ell)
+    xb = to_dev(X_build)
     dn = plain.dense_forward(xb, layer_outs=True)
     for l in cfg.hashed_layers:
-        var = dn["layers"][l].double().var(dim=0, unbiased=False).cpu().numpy()
+        var = dn["layers"][l].var(dim=0, unbiased=False).double().cpu().numpy()
         layers[l].K, layers[l].L = cfg.K, cfg.L
         # lists never need more entries than the largest budget below d_out that will be asked for
         top = max([k for k in cfg.keeps if k < 1.0] + ([cfg.keep_range[1]] if cfg.keep_range else []) + [args.keep])
         layers[l].list_cap = min(layers[l].d_out, int(np.ceil(top * layers[l].d_out)) + 1)
         layers[l].hash_nodes = wl.sample_hash_nodes(var, cfg.K, cfg.L, seed=3 + l)
     del plain, dn
-    net = runtime.Network(layers)
+    net = runtime.Network(layers, first_layer_rows_are_inputs=ell)
     t0 = time.time()
     net.build_tables(xb)
     net.set_path(args.path)
     log(f"built tables on the device in {time.time() - t0:.2f}s")
 
-    xq = torch.from_numpy(X_query).to(dev)
-    nq = xq.shape[0]
+    xq = to_dev(X_query)
+    nq = (xq[0] if ell else xq).shape[0]
     n_batches = nq // B
-    batches = [slonn.make_input(x=xq[i * B:(i + 1) * B]) for i in range(n_batches)]
+    if ell:
+        batches = [slonn.make_input(idx=xq[0][i * B:(i + 1) * B], val=xq[1][i * B:(i + 1) * B],
+                                    nnz=xq[2][i * B:(i + 1) * B]) for i in range(n_batches)]
+    else:
+        batches = [slonn.make_input(x=xq[i * B:(i + 1) * B]) for i in range(n_batches)]
     n_last = cfg.dims[-1]
-    out_dense = torch.empty((B, n_last), dtype=torch.float32, device=dev)
     out_arg = torch.empty(B, dtype=torch.int32, device=dev)
-    out = slonn.make_output(dense=out_dense, argmax=out_arg)
+    if layers[-1].K > 0:      # activated output layer: compact (id, value) output, no dense row
+        cap = layers[-1].list_cap
+        out_idx = torch.empty((B, n_last), dtype=torch.int32, device=dev)
+        out_val = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+        out_cnt = torch.empty(B, dtype=torch.int32, device=dev)
+        out = slonn.make_output(idx=out_idx, val=out_val, cnt=out_cnt, stride=n_last, argmax=out_arg)
+    else:
+        out_dense = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+        out = slonn.make_output(dense=out_dense, argmax=out_arg)
     ws = net.workspace(B)
     stream = torch.cuda.current_stream()
 
@@ -130,7 +150,10 @@ def main():
             if lay.K > 0:
                 tot += mean_budget(keep, lay.d_out) * lay.d_in * esz
             elif not activated_only:
-                tot += lay.d_out * lay.d_in * esz
+                if ell and lay is layers[0]:      # sparse input: one weight row per non-zero
+                    tot += cfg.ell_nnz * lay.d_out * esz
+                else:
+                    tot += lay.d_out * lay.d_in * esz
         return tot
 
     head_keep = None if mixed is not None else args.keep
@@ -187,6 +210,7 @@ def main():
             sweep[str(keep)] = {"qps": round(q), "effective_GBps": round(q * gathered_bytes_per_query(keep) / 1e9, 1)}
         extra["sweep"] = sweep
         yd = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
         for i in range(20):
             slonn.slonn_dense_forward(net.model, batches[i % n_batches], B, yd, out_arg, None, ws, stream)
         torch.cuda.synchronize()
@@ -202,11 +226,12 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import slonn_oracle
-        onet = slonn_oracle.OracleNet(layers)
+        onet = slonn_oracle.OracleNet(layers, first_layer_rows_are_inputs=ell)
         onet.import_tables(net.export_tables())
         n_s = min(nq, 4096)
+        Xs = tuple(a[:n_s] for a in X_query) if ell else X_query[:n_s]
         t0 = time.perf_counter()
-        onet.sparse_forward(X_query[:n_s], args.keep if mixed is None else mixed[:n_s].cpu().numpy(), taps=False)
+        onet.sparse_forward(Xs, args.keep if mixed is None else mixed[:n_s].cpu().numpy(), taps=False)
         dt = time.perf_counter() - t0
         cpu = {"value": round(n_s / dt, 1), "unit": "queries/s", "cores": onet.threads, "kind": "oracle",
                "sample": f"first {n_s} queries of the same query set, keep {args.keep}, all layers, "

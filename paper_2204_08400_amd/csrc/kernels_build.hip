@@ -110,6 +110,111 @@ __global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ sc
   for (uint32_t i = threadIdx.x; i < len; i += 256) dst[i] = ids[i];
 }
 
+// Layers wider than the LDS sort: only the best out_len[bucket] <= SORT_MAX nodes of a
+// bucket are wanted, so a score threshold is estimated from a sorted strided sample, checked
+// (and moved if needed) by counting passes over the bucket's scores, the nodes at or above it
+// are compacted into LDS in id order, sorted there with the exact (score, id) comparison and
+// the head of the result is written out.  fail[0] is set if no threshold isolates between
+// out_len and SORT_MAX candidates (masses of exactly equal scores).
+constexpr int SAMPLE = 4096;
+
+__device__ __forceinline__ int block_count_ge(const double* sc, int n, double thr, int* red) {
+  int c = 0;
+  for (int i = threadIdx.x; i < n; i += 256) c += (sc[i] >= thr && sc[i] > 0.0) ? 1 : 0;
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = c;
+  __syncthreads();
+  const int total = red[0] + red[1] + red[2] + red[3];
+  __syncthreads();
+  return total;
+}
+
+__global__ __launch_bounds__(256) void rank_wide_kernel(const double* __restrict__ score, int n,
+                                                       const uint32_t* __restrict__ out_off,
+                                                       const uint32_t* __restrict__ out_len,
+                                                       int32_t* __restrict__ out, int* __restrict__ fail) {
+  __shared__ double samp[SAMPLE];          // 32 KB, reused as the candidate id buffer
+  __shared__ int red[8];
+  int32_t* ids = reinterpret_cast<int32_t*>(samp);
+  const int bucket = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int len = (int)out_len[bucket];
+  if (len == 0) return;
+  const double* sc = score + (size_t)bucket * n;
+
+  // threshold: start from the sample value whose rank predicts about four times len candidates
+  for (int i = tid; i < SAMPLE; i += 256) samp[i] = sc[(size_t)i * n / SAMPLE];
+  __syncthreads();
+  for (int k = 2; k <= SAMPLE; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < (SAMPLE >> 1); t += 256) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), p = i | j;
+        const double a = samp[i], b = samp[p];
+        const bool up = (i & k) == 0;                       // descending order overall
+        if (up ? (b > a) : (a > b)) { samp[i] = b; samp[p] = a; }
+      }
+      __syncthreads();
+    }
+  int r = (int)((4.0 * len * SAMPLE) / n) + 16;
+  if (r > SAMPLE - 1) r = SAMPLE - 1;
+  double thr = samp[r];
+  int lo = 0, hi = SAMPLE - 1;                              // bracket of sample ranks still possible
+  int total = 0;
+  for (int it = 0; it < 14; ++it) {
+    total = block_count_ge(sc, n, thr, red);
+    if (total >= len && total <= SORT_MAX) break;
+    if (total < len) lo = r + 1; else hi = r - 1;
+    if (lo > hi) break;
+    r = (total < len) ? min(hi, 2 * r + 32) : max(lo, r / 2);
+    if (r < lo) r = lo;
+    if (r > hi) r = hi;
+    thr = samp[r];
+  }
+  if (total < len) {                                        // the whole sample is above: take every positive
+    thr = 0.0;
+    total = block_count_ge(sc, n, thr, red);
+  }
+  if (total < len || total > SORT_MAX) {
+    if (tid == 0) atomicExch(fail, 1);
+    return;
+  }
+  __syncthreads();                                          // the sample is no longer needed
+
+  // compact candidates in id order: ballot + prefix within a wave, wave totals through LDS
+  int P = 1;
+  while (P < total) P <<= 1;
+  if (P < 2) P = 2;
+  for (int i = tid; i < P; i += 256) ids[i] = -1;
+  __syncthreads();
+  int base = 0;
+  for (int i0 = 0; i0 < n; i0 += 256) {
+    const int i = i0 + tid;
+    const bool take = i < n && sc[i] >= thr && sc[i] > 0.0;
+    const unsigned long long votes = __ballot(take);
+    if (lane == 0) red[wave] = __popcll(votes);
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += red[w];
+    const int all = red[0] + red[1] + red[2] + red[3];
+    if (take) ids[base + before + __popcll(votes & ((lane == 0) ? 0ull : (~0ull >> (64 - lane))))] = i;
+    base += all;
+    __syncthreads();
+  }
+  // exact ordering of the candidates
+  for (int k = 2; k <= P; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < (P >> 1); t += 256) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), p = i | j;
+        const int a = ids[i], b = ids[p];
+        const bool up = (i & k) == 0;
+        const bool swap = up ? ranks_before(b, a, sc) : ranks_before(a, b, sc);
+        if (swap) { ids[i] = b; ids[p] = a; }
+      }
+      __syncthreads();
+    }
+  int32_t* dst = out + out_off[bucket];
+  for (int i = tid; i < len; i += 256) dst[i] = ids[i];
+}
+
 template <class T>
 struct DevBuf {
   T* p = nullptr;
@@ -142,9 +247,10 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
                        TableSet* ts, hipStream_t s) {
   const Layer& Ly = m->layers[layer];
   const int n = Ly.d_out, K = Ly.K, L = Ly.L, H = Ly.H();
-  if (n > SORT_MAX)
-    SLONN_FAIL(SLONN_EUNSUPPORTED, "build: layer %d has %d nodes, the bucket sort handles up to %d", layer, n,
-               SORT_MAX);
+  const bool wide = n > SORT_MAX;
+  if (wide && std::min(Ly.list_cap, n) > SORT_MAX)
+    SLONN_FAIL(SLONN_EUNSUPPORTED, "build: layer %d has %d nodes; lists of wide layers hold at most %d ids",
+               layer, n, SORT_MAX);
   if (N <= 0 || N > 0x7FFFFFFF) SLONN_FAIL(SLONN_EINVAL, "build: bad training-set size");
   const int nb = 1 << K;
   int P = 1;
@@ -161,6 +267,9 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
   DevBuf<uint32_t> keys, hist, start, members, npos, off, len;
   DevBuf<double> score;
   DevBuf<int32_t> out;
+  DevBuf<int> fail;
+  SLONN_HIP(fail.alloc(1));
+  SLONN_HIP(hipMemsetAsync(fail.p, 0, sizeof(int), s));
   SLONN_HIP(Z.alloc((size_t)N * H));
   SLONN_HIP(keys.alloc((size_t)N * L));
   SLONN_HIP(hist.alloc(nb));
@@ -213,7 +322,10 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
     if (tot > 0) {
       SLONN_HIP(hipMemcpyAsync(off.p, h_off.data(), (size_t)nb * 4, hipMemcpyHostToDevice, s));
       SLONN_HIP(hipMemcpyAsync(len.p, h_len.data(), (size_t)nb * 4, hipMemcpyHostToDevice, s));
-      hipLaunchKernelGGL(rank_kernel, dim3(nb), dim3(256), 0, s, score.p, n, P, 1, off.p, len.p, out.p);
+      if (wide)
+        hipLaunchKernelGGL(rank_wide_kernel, dim3(nb), dim3(256), 0, s, score.p, n, off.p, len.p, out.p, fail.p);
+      else
+        hipLaunchKernelGGL(rank_kernel, dim3(nb), dim3(256), 0, s, score.p, n, P, 1, off.p, len.p, out.p);
       SLONN_HIP(hipGetLastError());
       h_out.resize(tot);
       SLONN_HIP(hipMemcpyAsync(h_out.data(), out.p, (size_t)tot * 4, hipMemcpyDeviceToHost, s));
@@ -226,6 +338,22 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
   // whole-set ranking: every node, zero sums included
   hipLaunchKernelGGL(total_score_kernel, dim3((n + 255) / 256), dim3(256), 0, s, act, n, N, score.p);
   SLONN_HIP(hipGetLastError());
+  if (wide) {
+    // one ranking of all n nodes per layer: sorted on the host with the same comparison
+    int h_fail = 0;
+    std::vector<double> h_score(n);
+    SLONN_HIP(hipMemcpyAsync(&h_fail, fail.p, sizeof(int), hipMemcpyDeviceToHost, s));
+    SLONN_HIP(hipMemcpyAsync(h_score.data(), score.p, (size_t)n * 8, hipMemcpyDeviceToHost, s));
+    SLONN_HIP(hipStreamSynchronize(s));
+    if (h_fail)
+      SLONN_FAIL(SLONN_EUNSUPPORTED, "build: layer %d: a bucket has too many equal activation sums to rank", layer);
+    for (int j = 0; j < n; ++j) ts->global_rank[j] = j;
+    std::sort(ts->global_rank.begin(), ts->global_rank.end(), [&](int32_t a, int32_t b) {
+      if (h_score[a] != h_score[b]) return h_score[a] > h_score[b];
+      return a < b;
+    });
+    return upload_table_set(ts);
+  }
   const uint32_t zero = 0, all = (uint32_t)n;
   SLONN_HIP(hipMemcpyAsync(off.p, &zero, 4, hipMemcpyHostToDevice, s));
   SLONN_HIP(hipMemcpyAsync(len.p, &all, 4, hipMemcpyHostToDevice, s));
@@ -261,9 +389,10 @@ extern "C" int slonn_build_tables(const slonn_model* m, const slonn_input* X_bui
     SLONN_FAIL(SLONN_EINVAL, "unknown input format %d", X_build->format);
   }
   for (const Layer& L : m->layers)
-    if (L.activated() && L.d_out > SORT_MAX)
-      SLONN_FAIL(SLONN_EUNSUPPORTED, "build: an activated layer has %d nodes, at most %d are supported",
-                 L.d_out, SORT_MAX);
+    if (L.activated() && L.d_out > SORT_MAX && std::min(L.list_cap, L.d_out) > SORT_MAX)
+      SLONN_FAIL(SLONN_EUNSUPPORTED,
+                 "build: an activated layer has %d nodes; layers wider than %d need list_cap <= %d", L.d_out,
+                 SORT_MAX, SORT_MAX);
   hipStream_t s = static_cast<hipStream_t>(stream);
   slonn_tables* t = new (std::nothrow) slonn_tables;
   if (!t) SLONN_FAIL(SLONN_ENOMEM, "out of host memory");

@@ -148,6 +148,78 @@ __global__ __launch_bounds__(256) void dense_layer_kernel(const void* __restrict
   }
 }
 
+// Small problems (a batch of a few hundred queries against a layer of about a thousand
+// nodes) do not fill the chip with 64x64 tiles and their K loop is pure latency.  Here a
+// workgroup owns a 32x32 tile, its four wavefronts split the reduction dimension, operands
+// go straight from L2 to registers as 16-byte loads (lane (r, half) takes elements
+// 8s+4*half .. +3 of row r for both operands, MFMA c of the step consumes element c), U
+// steps are loaded ahead, and the four partial tiles are added in LDS in a fixed order.
+template <int WDT, int U>
+__global__ __launch_bounds__(256) void dense_direct_kernel(const void* __restrict__ W,
+                                                          const float* __restrict__ bias,
+                                                          const float* __restrict__ X, int ldx,
+                                                          float* __restrict__ Y, int ldy, int M, int N,
+                                                          int Kd, int act) {
+  __shared__ float part[3][64][16];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r = lane & 31, half = lane >> 5;
+  const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  const float* xr = X + (size_t)min(m0 + r, M - 1) * ldx;          // surplus rows recompute a valid row
+  const size_t wrow = (size_t)min(n0 + r, N - 1) * Kd;
+  const int steps = (Kd + 7) / 8;
+  const int per = (steps + 3) / 4;
+  const int s_begin = wave * per, s_end = min(steps, s_begin + per);
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s0 = s_begin; s0 < s_end; s0 += U) {
+    float4 a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = 8 * (s0 + u) + 4 * half;
+      const bool ok = (s0 + u < s_end) && k < Kd;     // Kd is a multiple of 4
+      const int kk = ok ? k : 0;
+      const float4 xa = *reinterpret_cast<const float4*>(xr + kk);
+      float4 wb;
+      if (WDT == SLONN_F32) {
+        wb = *reinterpret_cast<const float4*>(static_cast<const float*>(W) + wrow + kk);
+      } else {
+        const uint2 q = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(W) + wrow + kk);
+        wb.x = __uint_as_float(q.x << 16);
+        wb.y = __uint_as_float(q.x & 0xFFFF0000u);
+        wb.z = __uint_as_float(q.y << 16);
+        wb.w = __uint_as_float(q.y & 0xFFFF0000u);
+      }
+      a[u] = ok ? xa : zero4;
+      b[u] = ok ? wb : zero4;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].x, b[u].x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].y, b[u].y, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].z, b[u].z, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].w, b[u].w, acc, 0, 0, 0);
+    }
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) part[wave - 1][lane][v] = acc[v];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const int col = n0 + r;
+    const float bv = col < N ? bias[col] : 0.0f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = m0 + 8 * (v >> 2) + 4 * half + (v & 3);
+      float z = acc[v] + part[0][lane][v] + part[1][lane][v] + part[2][lane][v] + bv;
+      if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+      if (row < M && col < N) Y[(size_t)row * ldy + col] = z;
+    }
+  }
+}
+
 }  // namespace
 
 int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
@@ -159,6 +231,20 @@ int launch_dense_layer(const void* W, int w_dtype, const float* bias, const floa
   const int vecw = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(W) % 16 == 0);
   const long big_tiles = (long)((B + 127) / 128) * ((n + 127) / 128);
   const bool big = big_tiles >= 512;
+  const long tiles64 = (long)((B + 63) / 64) * ((n + 63) / 64);
+  const int wmul = (w_dtype == SLONN_F32) ? 4 : 8;      // row start alignment of the weight loads
+  if (tiles64 < 256 && vecx && d % 4 == 0 && d % wmul == 0 &&
+      reinterpret_cast<uintptr_t>(W) % (w_dtype == SLONN_F32 ? 16 : 8) == 0) {
+    dim3 grid((n + 31) / 32, (B + 31) / 32);
+    if (w_dtype == SLONN_F32)
+      hipLaunchKernelGGL((dense_direct_kernel<SLONN_F32, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
+                         B, n, d, a);
+    else
+      hipLaunchKernelGGL((dense_direct_kernel<SLONN_BF16, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
+                         B, n, d, a);
+    SLONN_HIP(hipGetLastError());
+    return SLONN_OK;
+  }
 #define SLONN_LAUNCH_DENSE(WDT, BM, BN)                                                            \
   hipLaunchKernelGGL((dense_layer_kernel<WDT, BM, BN>), dim3((n + BN - 1) / BN, (B + BM - 1) / BM), \
                      dim3(256), 0, s, W, bias, X, ldx, Y, ldy, B, n, d, a, vecx, vecw)

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void gather_forward_kernel(
     if (l == k && t[k] < c) {
       float z = acc[k] + bias[j[k]];
       if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-      Y[(size_t)q * ldy + j[k]] = z;
+      if (Y) Y[(size_t)q * ldy + j[k]] = z;
       if (yc) yc[(size_t)q * ldc + t[k]] = z;
     }
   }
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256) void gather_blocked_kernel(
       const int j = lane == 0 ? j0 : j1;
       float z = (lane == 0 ? acc0 : acc1) + bias[j];
       if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-      Y[(size_t)q * ldy + j] = z;
+      if (Y) Y[(size_t)q * ldy + j] = z;
       if (yc) yc[(size_t)q * ldc + ppos[t0 + lane]] = z;
     }
   }
@@ -232,7 +232,8 @@ __global__ __launch_bounds__(256) void ell_layer_kernel(
 }
 
 // Softmax over the computed nodes and/or argmax (lowest id among equal maxima).
-// One wavefront per query.
+// One wavefront per query.  Values are read from the dense row Y[q][id], or, when the
+// caller only keeps the compact form (Y == nullptr), from yc[q][t] in list order.
 __global__ __launch_bounds__(64) void finalize_kernel(float* __restrict__ Y, int ldy, int n,
                                                      const int32_t* __restrict__ active,
                                                      const int32_t* __restrict__ cnt, int idx_stride,
@@ -241,12 +242,13 @@ __global__ __launch_bounds__(64) void finalize_kernel(float* __restrict__ Y, int
   const int q = blockIdx.x, lane = threadIdx.x;
   const int c = active ? cnt[q] : n;
   const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
-  float* y = Y + (size_t)q * ldy;
+  float* y = Y ? Y + (size_t)q * ldy : nullptr;
+  float* yq = yc ? yc + (size_t)q * ldc : nullptr;
   float best = -INFINITY;
   int besti = 0x7FFFFFFF;
   for (int t = lane; t < c; t += 64) {
     const int j = list ? list[t] : t;
-    const float v = y[j];
+    const float v = y ? y[j] : yq[t];
     if (v > best || (v == best && j < besti)) { best = v; besti = j; }
   }
   for (int o = 32; o > 0; o >>= 1) {
@@ -259,15 +261,15 @@ __global__ __launch_bounds__(64) void finalize_kernel(float* __restrict__ Y, int
   float sum = 0.0f;
   for (int t = lane; t < c; t += 64) {
     const int j = list ? list[t] : t;
-    sum += expf(y[j] - best);
+    sum += expf((y ? y[j] : yq[t]) - best);
   }
   for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
   const float inv = 1.0f / sum;
   for (int t = lane; t < c; t += 64) {
     const int j = list ? list[t] : t;
-    const float p = expf(y[j] - best) * inv;
-    y[j] = p;
-    if (yc) yc[(size_t)q * ldc + t] = p;
+    const float p = expf((y ? y[j] : yq[t]) - best) * inv;
+    if (y) y[j] = p;
+    if (yq) yq[t] = p;
   }
 }
 

@@ -564,6 +564,8 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
     float* tap_out = taps && taps->layer_out ? taps->layer_out[l] : nullptr;
     // write straight into the caller's buffer when one exists for this layer
     float* out = is_last && Y->dense ? Y->dense : (tap_out ? tap_out : w.act[l & 1]);
+    // a last layer whose result is only wanted in compact form never materialises the dense row
+    if (is_last && L.activated() && !Y->dense && !tap_out && Y->val && Y->idx) out = nullptr;
     const int ldo = L.d_out;
     const int act = L.act;
     const int32_t* act_list = nullptr;

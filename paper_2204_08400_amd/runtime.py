@@ -79,7 +79,7 @@ class Network:
         return slonn.slonn_tables_export(self.tables)
 
     # -- forward -------------------------------------------------------------- #
-    def sparse_forward(self, X, keep, taps: bool = False, compact: bool = False):
+    def sparse_forward(self, X, keep, taps: bool = False, compact: bool = False, dense: bool = True):
         """keep: device float tensor [B] or [B][n_layers], or a python float."""
         inp = self.to_input(X)
         B = self.batch_of(inp)
@@ -93,7 +93,7 @@ class Network:
             qs, ls = keep.shape[1], 1
         n_last = self.dims_out[-1]
         res = {}
-        dense = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+        dense = torch.empty((B, n_last), dtype=torch.float32, device=dev) if dense else None
         argmax = torch.empty(B, dtype=torch.int32, device=dev)
         kw = dict(dense=dense, argmax=argmax)
         if compact:

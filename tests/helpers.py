@@ -108,7 +108,7 @@ def to_numpy_result(res: dict) -> dict:
     """GPU result (torch tensors) -> numpy, same structure."""
     def cv(t):
         return None if t is None else t.detach().cpu().numpy()
-    out = {"out": cv(res["out"]), "argmax": cv(res["argmax"])}
+    out = {"out": cv(res.get("out")), "argmax": cv(res["argmax"])}
     if "taps" in res:
         out["taps"] = {k: [cv(t) for t in v] for k, v in res["taps"].items()}
     for k in ("idx", "val", "cnt"):

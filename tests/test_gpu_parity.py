@@ -227,40 +227,48 @@ def test_edge_cases(rt, oracle, path):
                                    slonn.make_output(), None, g.workspace(1))
 
 
-def test_build_tables_matches_oracle(rt, oracle):
-    """Alg. 1 on the device against the oracle's: bucket membership exact, lists equal up
-    to swaps of nodes whose sums agree to 1e-5 relative; tables built on either side give
-    the same selection when both sides load the same blob."""
-    dims = (100, 300, 260, 37)
-    layers, net, Xb = make_case(oracle, dims, 4, 6, seed=17, cap=200, N_build=500)
+BUILD_CASES = [
+    dict(dims=(100, 300, 260, 37), K=4, L=6, cap=200, N=500, hashed=None, last_act=wl.ACT_NONE),
+    dict(dims=(48, 10000, 16), K=5, L=4, cap=400, N=300, hashed=[0], last_act=wl.ACT_NONE),       # wide ReLU layer
+    dict(dims=(48, 128, 12000), K=6, L=5, cap=300, N=300, hashed=[1], last_act=wl.ACT_SOFTMAX),   # wide softmax layer
+]
+
+
+@pytest.mark.parametrize("case", BUILD_CASES, ids=lambda c: "x".join(map(str, c["dims"])))
+def test_build_tables_matches_oracle(rt, oracle, case):
+    """Alg. 1 on the device against the oracle's: lists equal up to swaps of nodes whose sums
+    agree to 1e-5 relative (the device sums fp32 activations of its own dense pass); tables
+    built on either side give the same selection when both sides load the same blob."""
+    dims = case["dims"]
+    layers, net, Xb = make_case(oracle, dims, case["K"], case["L"], seed=17, cap=case["cap"], N_build=case["N"],
+                                hashed=case["hashed"], last_act=case["last_act"])
+    hashed = [l for l, lay in enumerate(layers) if lay.K > 0]
     g = rt.Network(layers)
-    _say("device build")
+    _say(f"device build {dims}")
     g.build_tables(Xb)
     blob = g.export_tables()
     net_g = oracle.OracleNet(layers)
     net_g.import_tables(blob)            # oracle consumes the device-built tables
     net_s = oracle.OracleNet(layers)
     net_s.build_tables(Xb, keep_scores=True)
-    for l in (0, 1):
+    for l in hashed:
         tg, ts = net_g.tables[l], net_s.tables[l]
-        n = layers[l].d_out
-        swaps = 0
+        swaps = mism = 0
         for b in range(layers[l].L):
             for key in range(1 << layers[l].K):
                 lg, ls = tg.bucket(b, key), ts.bucket(b, key)
                 if ls.size == 0 and lg.size == 0:
                     continue
                 sc = ts.bucket_scores(b, key)
-                if layers[l].list_cap < n and ls.size == layers[l].list_cap:
-                    # capped: compare as ranked sequences by score
-                    pass
-                assert lg.size == ls.size or l > 0, (l, b, key)
-                m = min(lg.size, ls.size)
-                for a, c in zip(lg[:m], ls[:m]):
+                if sc is None or lg.size != ls.size:
+                    mism += 1              # a training input hashed differently (projection within rounding of 0)
+                    continue
+                for a, c in zip(lg, ls):
                     if a != c:
                         swaps += 1
                         assert abs(sc[a] - sc[c]) <= 1e-5 * max(abs(sc[a]), abs(sc[c])), (l, b, key, a, c)
-        _say(f"layer {l}: {swaps} rank swaps among near-equal sums")
+        _say(f"layer {l}: {swaps} rank swaps among near-equal sums, {mism} buckets with different membership")
+        assert mism <= (2 if l > hashed[0] else 0)
         gg, _ = tg.global_rank()
         gs, ss = ts.global_rank()
         for a, c in zip(gg, gs):
@@ -268,8 +276,8 @@ def test_build_tables_matches_oracle(rt, oracle):
                 assert abs(ss[a] - ss[c]) <= 1e-5 * max(abs(ss[a]), abs(ss[c]), 1e-30)
     # same blob on both sides: selection and outputs agree
     X = make_queries(dims, 64, seed=9)
-    ref = net_g.sparse_forward(X, 0.2)
-    got = to_numpy_result(g.sparse_forward(X, 0.2, taps=True))
+    ref = net_g.sparse_forward(X, 0.02)
+    got = to_numpy_result(g.sparse_forward(X, 0.02, taps=True))
     compare_sparse(got, ref, layers, "device-built tables")
     # the device build is reproducible bit for bit
     g2 = rt.Network(layers)
@@ -383,3 +391,34 @@ def test_config_c5_shape_sampled(rt, oracle):
         _say(f"C5-shaped path={path}")
         got = to_numpy_result(g.sparse_forward(Xq, _keep_tensor(keep), taps=True))
         _say(f"  {compare_sparse(got, ref, layers, f'C5-shaped {path}')}")
+
+
+def test_config_c4_shape(rt, oracle):
+    """Wiki10/Delicious-shaped model at its real width: 100 000 sparse features (100
+    non-zeros) -> 128 -> 100 000 softmax outputs, K=12 L=50 on the output layer, keep
+    0.005 (500 nodes), batch 128.  Tables come from the oracle on a 256-input build set
+    (the device build does not cover layers this wide)."""
+    import copy
+    cfg = wl.CONFIGS["C4"]
+    layers, net, _ = make_case(oracle, cfg.dims, cfg.K, cfg.L, seed=0, hashed=[1], cap=600,
+                               last_act=wl.ACT_SOFTMAX, ell_nnz=cfg.ell_nnz, N_build=256)
+    glayers = [copy.copy(l) for l in layers]
+    glayers[0].W = np.ascontiguousarray(layers[0].W.T)        # input-major first layer on the device
+    g = rt.Network(glayers, first_layer_rows_are_inputs=True)
+    g.import_tables(net.export_tables())
+    X = make_queries(cfg.dims, 128, seed=2, ell_nnz=cfg.ell_nnz)
+    _say("C4 sparse forward")
+    ref = net.sparse_forward(X, 0.005)
+    got = to_numpy_result(g.sparse_forward(X, 0.005, taps=True, compact=True))
+    rep = compare_sparse(got, ref, layers, "C4")
+    _say(f"  {rep}")
+    ok = ~ref["layers"][1]["tie"]
+    assert (got["cnt"][ok] == 500).all()
+    for q in np.nonzero(ok)[0]:
+        assert np.array_equal(got["idx"][q, :500], ref["layers"][1]["active"][q, :500])
+        np.testing.assert_allclose(got["val"][q, :500], ref["out"][q, got["idx"][q, :500]], rtol=1e-4, atol=1e-9)
+    # compact-only output (no dense [B][100000] row is ever written): same ids, values, argmax
+    lean = to_numpy_result(g.sparse_forward(X, 0.005, compact=True, dense=False))
+    assert np.array_equal(lean["cnt"], got["cnt"]) and np.array_equal(lean["argmax"], got["argmax"])
+    assert np.array_equal(lean["idx"][:, :500], got["idx"][:, :500])
+    assert np.array_equal(lean["val"][:, :500], got["val"][:, :500])
