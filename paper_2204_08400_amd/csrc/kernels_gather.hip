@@ -10,6 +10,8 @@
 // covers 256 contiguous bytes of one weight row; the four rows a group owns are
 // streamed together so each LDS read of x is used four times and eight 16-byte loads
 // per lane are in flight.
+#include <algorithm>
+
 #include "slonn_internal.h"
 
 namespace slonn {
@@ -83,8 +85,7 @@ __global__ __launch_bounds__(256) void gather_forward_kernel(
   using C = Chunk<WDT>;
   const int q = blockIdx.y;
   const int c = active ? cnt[q] : n;
-  const int row0 = blockIdx.x * ROWS_PER_BLOCK;
-  if (row0 >= c) return;
+  if ((int)blockIdx.x * ROWS_PER_BLOCK >= c) return;
   const int tid = threadIdx.x;
   const float* x = X + (size_t)q * ldx;
   if (VECTOR) {
@@ -97,54 +98,58 @@ __global__ __launch_bounds__(256) void gather_forward_kernel(
 
   const int g = tid / LANES_PER_ROW, l = tid % LANES_PER_ROW;
   const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
-  int t[ROWS_PER_GROUP], j[ROWS_PER_GROUP];
-  float acc[ROWS_PER_GROUP];
+  // the grid holds a bounded number of chunks per query (the budget is only known on the
+  // device); a workgroup walks its chunks with the grid's stride
+  for (int row0 = blockIdx.x * ROWS_PER_BLOCK; row0 < c; row0 += gridDim.x * ROWS_PER_BLOCK) {
+    int t[ROWS_PER_GROUP], j[ROWS_PER_GROUP];
+    float acc[ROWS_PER_GROUP];
 #pragma unroll
-  for (int k = 0; k < ROWS_PER_GROUP; ++k) {
-    t[k] = row0 + g + k * (256 / LANES_PER_ROW);
-    const int tt = t[k] < c ? t[k] : row0;          // surplus slots redo the first row
-    j[k] = list ? list[tt] : tt;
-    acc[k] = 0.0f;
-  }
-  if (t[0] >= c) return;                              // whole group beyond the list
+    for (int k = 0; k < ROWS_PER_GROUP; ++k) {
+      t[k] = row0 + g + k * (256 / LANES_PER_ROW);
+      const int tt = t[k] < c ? t[k] : row0;          // surplus slots redo the first row
+      j[k] = list ? list[tt] : tt;
+      acc[k] = 0.0f;
+    }
+    if (t[0] >= c) break;                               // whole group beyond the list
 
-  if (VECTOR) {
-    using vec_t = typename C::vec_t;
-    const int nv = d / C::ELEMS;
-    const vec_t* w0 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
-                                                     (size_t)j[0] * d * (WDT == SLONN_F32 ? 4 : 2));
-    const vec_t* w1 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
-                                                     (size_t)j[1] * d * (WDT == SLONN_F32 ? 4 : 2));
-    const vec_t* w2 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
-                                                     (size_t)j[2] * d * (WDT == SLONN_F32 ? 4 : 2));
-    const vec_t* w3 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
-                                                     (size_t)j[3] * d * (WDT == SLONN_F32 ? 4 : 2));
+    if (VECTOR) {
+      using vec_t = typename C::vec_t;
+      const int nv = d / C::ELEMS;
+      const vec_t* w0 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                       (size_t)j[0] * d * (WDT == SLONN_F32 ? 4 : 2));
+      const vec_t* w1 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                       (size_t)j[1] * d * (WDT == SLONN_F32 ? 4 : 2));
+      const vec_t* w2 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                       (size_t)j[2] * d * (WDT == SLONN_F32 ? 4 : 2));
+      const vec_t* w3 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                       (size_t)j[3] * d * (WDT == SLONN_F32 ? 4 : 2));
 #pragma unroll 2
-    for (int i = l; i < nv; i += LANES_PER_ROW) {
-      const vec_t a0 = w0[i], a1 = w1[i], a2 = w2[i], a3 = w3[i];
-      const float* xp = xs + i * C::ELEMS;
-      acc[0] = C::dot(a0, xp, acc[0]);
-      acc[1] = C::dot(a1, xp, acc[1]);
-      acc[2] = C::dot(a2, xp, acc[2]);
-      acc[3] = C::dot(a3, xp, acc[3]);
+      for (int i = l; i < nv; i += LANES_PER_ROW) {
+        const vec_t a0 = w0[i], a1 = w1[i], a2 = w2[i], a3 = w3[i];
+        const float* xp = xs + i * C::ELEMS;
+        acc[0] = C::dot(a0, xp, acc[0]);
+        acc[1] = C::dot(a1, xp, acc[1]);
+        acc[2] = C::dot(a2, xp, acc[2]);
+        acc[3] = C::dot(a3, xp, acc[3]);
+      }
+    } else {
+      for (int i = l; i < d; i += LANES_PER_ROW) {
+        const float xv = xs[i];
+#pragma unroll
+        for (int k = 0; k < ROWS_PER_GROUP; ++k)
+          acc[k] = fmaf(C::elem(W, (size_t)j[k] * d + i), xv, acc[k]);
+      }
     }
-  } else {
-    for (int i = l; i < d; i += LANES_PER_ROW) {
-      const float xv = xs[i];
 #pragma unroll
-      for (int k = 0; k < ROWS_PER_GROUP; ++k)
-        acc[k] = fmaf(C::elem(W, (size_t)j[k] * d + i), xv, acc[k]);
-    }
-  }
+    for (int k = 0; k < ROWS_PER_GROUP; ++k) acc[k] = reduce16(acc[k]);
 #pragma unroll
-  for (int k = 0; k < ROWS_PER_GROUP; ++k) acc[k] = reduce16(acc[k]);
-#pragma unroll
-  for (int k = 0; k < ROWS_PER_GROUP; ++k) {
-    if (l == k && t[k] < c) {
-      float z = acc[k] + bias[j[k]];
-      if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-      if (Y) Y[(size_t)q * ldy + j[k]] = z;
-      if (yc) yc[(size_t)q * ldc + t[k]] = z;
+    for (int k = 0; k < ROWS_PER_GROUP; ++k) {
+      if (l == k && t[k] < c) {
+        float z = acc[k] + bias[j[k]];
+        if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+        if (Y) Y[(size_t)q * ldy + j[k]] = z;
+        if (yc) yc[(size_t)q * ldc + t[k]] = z;
+      }
     }
   }
 }
@@ -207,28 +212,52 @@ __global__ __launch_bounds__(256) void gather_blocked_kernel(
   }
 }
 
-// First layer on sparse (ELL) input.  With input-major storage every non-zero pulls
-// one contiguous row of n weights; thread j accumulates node j.
+// First layer on sparse (ELL) input.  With input-major storage every non-zero pulls one
+// contiguous row of n weights: a workgroup owns 64 consecutive nodes of one query (one lane
+// per node), its four wavefronts split the non-zeros (staged in LDS), eight row reads are in
+// flight per lane, and the four partial sums are added in LDS in a fixed order.
 template <int WDT>
 __global__ __launch_bounds__(256) void ell_layer_kernel(
     const void* __restrict__ W, int w_layout, const float* __restrict__ bias,
     const int32_t* __restrict__ idx, const float* __restrict__ val, const int32_t* __restrict__ nnz,
     int ell_stride, float* __restrict__ Y, int ldy, int d, int n, int act) {
+  extern __shared__ __align__(16) unsigned char ell_smem[];
   using C = Chunk<WDT>;
-  const int q = blockIdx.y;
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= n) return;
+  const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = nnz[q];
-  float acc = 0.0f;
-  for (int t = 0; t < c; ++t) {
-    const int i = idx[(size_t)q * ell_stride + t];
-    const float v = val[(size_t)q * ell_stride + t];
-    const size_t at = (w_layout == SLONN_ROWS_ARE_INPUTS) ? (size_t)i * n + j : (size_t)j * d + i;
-    acc = fmaf(C::elem(W, at), v, acc);
+  int32_t* s_idx = reinterpret_cast<int32_t*>(ell_smem);
+  float* s_val = reinterpret_cast<float*>(s_idx + ell_stride);
+  float* part = s_val + ell_stride;                       // [4][64]
+  for (int t = tid; t < c; t += 256) {
+    s_idx[t] = idx[(size_t)q * ell_stride + t];
+    s_val[t] = val[(size_t)q * ell_stride + t];
   }
-  float z = acc + bias[j];
-  if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-  Y[(size_t)q * ldy + j] = z;
+  __syncthreads();
+  const int j = blockIdx.x * 64 + lane;
+  const int jj = j < n ? j : n - 1;
+  const int per = (c + 3) / 4;
+  const int t0 = wave * per, t1 = min(c, t0 + per);
+  float acc = 0.0f;
+  for (int t = t0; t < t1; t += 8) {
+    float w[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int tt = t + u < t1 ? t + u : t0;
+      const int i = s_idx[tt];
+      const size_t at = (w_layout == SLONN_ROWS_ARE_INPUTS) ? (size_t)i * n + jj : (size_t)jj * d + i;
+      w[u] = C::elem(W, at);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (t + u < t1) acc = fmaf(w[u], s_val[t + u], acc);
+  }
+  part[wave * 64 + lane] = acc;
+  __syncthreads();
+  if (wave == 0 && j < n) {
+    float z = part[lane] + part[64 + lane] + part[128 + lane] + part[192 + lane] + bias[j];
+    if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+    Y[(size_t)q * ldy + j] = z;
+  }
 }
 
 // Softmax over the computed nodes and/or argmax (lowest id among equal maxima).
@@ -287,7 +316,11 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
                    (reinterpret_cast<uintptr_t>(X) % 16 == 0);
   const size_t lds = ((size_t)d + 8) * sizeof(float);
   if (lds > 65536) SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
-  dim3 grid((max_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, B);
+  // enough chunks per query to fill the chip, never more than the list can have
+  int chunks = (max_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+  const int want = std::max(4, (4096 + B - 1) / B);
+  if (active && chunks > want) chunks = want;
+  dim3 grid(chunks, B);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
 #define SLONN_LAUNCH_GATHER(WDT, VEC)                                                              \
   hipLaunchKernelGGL((gather_forward_kernel<WDT, VEC>), grid, dim3(256), lds, s, W, bias, X, ldx,  \
@@ -325,13 +358,15 @@ int launch_ell_layer(const void* W, int w_dtype, int w_layout, const float* bias
                      const float* val, const int32_t* nnz, int ell_stride, float* Y, int ldy, int B,
                      int d, int n, int act, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_ELL, s);
-  dim3 grid((n + 255) / 256, B);
+  dim3 grid((n + 63) / 64, B);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
+  const size_t lds = (size_t)ell_stride * 8 + 4 * 64 * 4;
+  if (lds > 65536) SLONN_FAIL(SLONN_EUNSUPPORTED, "ELL input with %d slots per row does not fit LDS", ell_stride);
   if (w_dtype == SLONN_F32)
-    hipLaunchKernelGGL((ell_layer_kernel<SLONN_F32>), grid, dim3(256), 0, s, W, w_layout, bias, idx, val,
+    hipLaunchKernelGGL((ell_layer_kernel<SLONN_F32>), grid, dim3(256), lds, s, W, w_layout, bias, idx, val,
                        nnz, ell_stride, Y, ldy, d, n, a);
   else
-    hipLaunchKernelGGL((ell_layer_kernel<SLONN_BF16>), grid, dim3(256), 0, s, W, w_layout, bias, idx,
+    hipLaunchKernelGGL((ell_layer_kernel<SLONN_BF16>), grid, dim3(256), lds, s, W, w_layout, bias, idx,
                        val, nnz, ell_stride, Y, ldy, d, n, a);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;

@@ -14,7 +14,7 @@
 
 namespace slonn {
 
-constexpr int SELECT_MU = 4;     // most slots per thread per round
+constexpr int SELECT_MU = 4;     // most slots per thread per round (header-wide constant)
 
 template <int NT>
 struct SelectShared {            // LDS regions the caller carves out
@@ -120,6 +120,149 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
     if (i < n) {
       node = global_rank[i];
       first = sh.prio[node] == 0xFFFFFFFFu;
+    }
+    const unsigned long long votes = __ballot(first);
+    if (lane == 0) sh.wave_cnt[wave] = __popcll(votes);
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const int c = sh.wave_cnt[w];
+      before += (w < wave) ? c : 0;
+      total += c;
+    }
+    if (first) {
+      const int pos = count + before + __popcll(votes & below);
+      if (pos < m) out[pos] = node;
+    }
+    count += total;
+    __syncthreads();
+  }
+}
+
+// Same query for layers too wide for a 4-byte map entry per node (hundreds of thousands of
+// output nodes): one BIT per node records the nodes taken in earlier rounds, and the nodes of
+// the current round meet in a small open-addressing table in LDS (node id -> smallest slot
+// number of the round), which is emptied again after each round.
+constexpr int SELECT_WIDE_TABLE = 4096;   // entries; a round holds at most SELECT_MU * NT <= half of it
+
+template <int NT>
+struct SelectSharedWide {
+  uint32_t* taken;               // [(n + 31) / 32] bitmap
+  int32_t* tkey;                 // [SELECT_WIDE_TABLE] node id or -1
+  uint32_t* tval;                // [SELECT_WIDE_TABLE] smallest slot of the round
+  uint32_t* s_off;               // [64]
+  uint32_t* s_len;               // [64]
+  int* wave_cnt;                 // [SELECT_MU * NT/64]
+  uint32_t* s_misc;              // [4]
+  static constexpr int words_besides_bitmap = 2 * SELECT_WIDE_TABLE + 64 + 64 + SELECT_MU * (NT / 64) + 4;
+};
+
+// taken[] must be zero and tkey[] = -1, tval[] = 0xFFFFFFFF on entry (caller + barrier).
+template <int NT>
+__device__ __forceinline__ void select_block_wide(const float* z, int K, int L_, int n, int m,
+                                                  const uint32_t* __restrict__ dir,
+                                                  const int32_t* __restrict__ ids,
+                                                  const int32_t* __restrict__ global_rank,
+                                                  const SelectSharedWide<NT>& sh, uint32_t* codes_row,
+                                                  int32_t* out) {
+  static_assert(SELECT_MU * NT * 2 <= SELECT_WIDE_TABLE, "round table too small");
+  constexpr int NW = NT / 64;
+  constexpr int MU = SELECT_MU;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+
+  if (wave == 0) {
+    const int nb1 = (1 << K) + 1;
+    uint32_t len = 0;
+    if (lane < L_) {
+      uint32_t key = 0;
+      for (int j = 0; j < K; ++j) key |= (z[lane * K + j] > 0.0f ? 1u : 0u) << j;
+      if (codes_row) codes_row[lane] = key;
+      const uint32_t lo = dir[(size_t)lane * nb1 + key], hi = dir[(size_t)lane * nb1 + key + 1];
+      sh.s_off[lane] = lo;
+      len = hi - lo;
+      sh.s_len[lane] = len;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      const uint32_t other = __shfl_xor(len, o);
+      len = other > len ? other : len;
+    }
+    if (lane == 0) sh.s_misc[0] = len;
+  }
+  __syncthreads();
+
+  const uint32_t L = (uint32_t)L_;
+  const unsigned long long nslots = (unsigned long long)sh.s_misc[0] * L;
+  int per = (12 * m + NT - 1) / NT;
+  per = per < 1 ? 1 : (per > MU ? MU : per);
+  int count = 0;
+  for (unsigned long long base = 0; base < nslots && count < m; base += (unsigned long long)NT * per) {
+    int node[MU], cell[MU];
+    uint32_t rel[MU];                      // slot number relative to the round
+    bool valid[MU];
+#pragma unroll
+    for (int u = 0; u < MU; ++u) {
+      rel[u] = u * NT + tid;
+      const unsigned long long slot = base + rel[u];
+      const uint32_t r = (uint32_t)(slot / L);
+      const uint32_t b = (uint32_t)(slot - (unsigned long long)r * L);
+      valid[u] = u < per && slot < nslots && r < sh.s_len[b];
+      node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
+      cell[u] = 0;
+    }
+#pragma unroll
+    for (int u = 0; u < MU; ++u) {
+      if (valid[u] && ((sh.taken[node[u] >> 5] >> (node[u] & 31)) & 1u)) valid[u] = false;   // earlier round
+      if (valid[u]) {
+        uint32_t h = ((uint32_t)node[u] * 2654435761u) >> 20;      // 12 bits
+        while (true) {
+          const int k = atomicCAS(&sh.tkey[h], -1, node[u]);
+          if (k == -1 || k == node[u]) break;
+          h = (h + 1) & (SELECT_WIDE_TABLE - 1);
+        }
+        atomicMin(&sh.tval[h], rel[u]);
+        cell[u] = (int)h;
+      }
+    }
+    __syncthreads();
+    bool first[MU];
+    unsigned long long votes[MU];
+#pragma unroll
+    for (int u = 0; u < MU; ++u) {
+      first[u] = valid[u] && sh.tval[cell[u]] == rel[u];
+      votes[u] = __ballot(first[u]);
+      if (lane == 0) sh.wave_cnt[u * NW + wave] = __popcll(votes[u]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < MU; ++u) {
+      int before = 0, total = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const int c = sh.wave_cnt[u * NW + w];
+        before += (w < wave) ? c : 0;
+        total += c;
+      }
+      if (first[u]) {
+        const int pos = count + before + __popcll(votes[u] & below);
+        if (pos < m) out[pos] = node[u];
+        atomicOr(&sh.taken[node[u] >> 5], 1u << (node[u] & 31));
+      }
+      count += total;
+    }
+#pragma unroll
+    for (int u = 0; u < MU; ++u)
+      if (valid[u]) { sh.tkey[cell[u]] = -1; sh.tval[cell[u]] = 0xFFFFFFFFu; }
+    __syncthreads();
+  }
+  for (int base = 0; base < n && count < m; base += NT) {
+    const int i = base + tid;
+    int node = -1;
+    bool first = false;
+    if (i < n) {
+      node = global_rank[i];
+      first = ((sh.taken[node >> 5] >> (node & 31)) & 1u) == 0;
     }
     const unsigned long long votes = __ballot(first);
     if (lane == 0) sh.wave_cnt[wave] = __popcll(votes);

@@ -586,14 +586,15 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       if (is_last && Y->cnt && !tap_cnt) acnt = Y->cnt;
       rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
       if (rc) return rc;
-      // Weight matrices well beyond an L2 slice are walked in blocks of rows (about 2 MiB)
-      // so that concurrently running workgroups share them; small ones are read as listed.
+      // Weight matrices well beyond an L2 slice (with rows long enough to occupy a wavefront)
+      // are walked in blocks of rows of about 2 MiB so that concurrently running workgroups
+      // share them; the others are read as listed.
       RowBlocking rb;
       const size_t esz = L.w_dtype == SLONN_F32 ? 4 : 2;
       const size_t row_bytes = (size_t)L.d_in * esz;
       const bool rows_vec = row_bytes % 16 == 0 && L.d_in % 4 == 0 && ldcur % 4 == 0 &&
                             reinterpret_cast<uintptr_t>(L.W) % 16 == 0 && reinterpret_cast<uintptr_t>(cur) % 16 == 0;
-      if (B >= 2 && rows_vec && row_bytes * L.d_out > ((size_t)3 << 20) &&
+      if (B >= 2 && rows_vec && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20) &&
           select_fills_row_blocks(L.d_out, m->max_lds_bytes)) {
         int rpb = 16;
         while ((size_t)rpb * 2 * row_bytes <= ((size_t)2 << 20)) rpb *= 2;

@@ -166,11 +166,11 @@ def test_select_teacher_forced(rt, oracle):
         cur = tap["out"]
 
 
-@pytest.mark.parametrize("n_out", [3000, 50000], ids=["block-select", "wave-select"])
+@pytest.mark.parametrize("n_out", [3000, 50000], ids=["block-select", "wide-select"])
 def test_ell_input_and_activated_softmax_output(rt, oracle, n_out):
     """Wide sparse-input model with the Node Activator on the output layer only.  The
-    50 000-node output is too wide for a 4-byte-per-node map in LDS and takes the
-    one-wavefront-per-query select kernel."""
+    50 000-node output is too wide for a 4-byte-per-node map in LDS and takes the select
+    kernel that keeps one bit per node."""
     dims = (5000, 128, n_out)
     from paper_2204_08400_amd import slonn
     _say(slonn.slonn_version())
