@@ -154,6 +154,59 @@ __global__ __launch_bounds__(256) void gather_forward_kernel(
   }
 }
 
+// Small batches: with only a few queries there are too few (query, 64-row chunk) pairs to
+// occupy the chip, so a workgroup takes 8 list entries at a time, one wavefront per row
+// (two rows in flight per wavefront), and the grid is eight times finer.
+constexpr int ROWS_PER_WAVE_BLOCK = 8;
+
+template <int WDT>
+__global__ __launch_bounds__(256) void gather_wave_kernel(
+    const void* __restrict__ W, const float* __restrict__ bias, const float* __restrict__ X, int ldx,
+    const int32_t* __restrict__ active, const int32_t* __restrict__ cnt, int idx_stride,
+    float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int n, int act) {
+  extern __shared__ __align__(16) float xs[];
+  using C = Chunk<WDT>;
+  using vec_t = typename C::vec_t;
+  const int q = blockIdx.y;
+  const int c = active ? cnt[q] : n;
+  if ((int)blockIdx.x * ROWS_PER_WAVE_BLOCK >= c) return;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float* x = X + (size_t)q * ldx;
+  for (int i = tid; i < (d >> 2); i += 256)
+    reinterpret_cast<float4*>(xs)[i] = reinterpret_cast<const float4*>(x)[i];
+  __syncthreads();
+  const int nv = d / C::ELEMS;
+  const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
+  for (int t0 = blockIdx.x * ROWS_PER_WAVE_BLOCK + 2 * wave; t0 < c; t0 += gridDim.x * ROWS_PER_WAVE_BLOCK) {
+    const bool two = t0 + 1 < c;
+    const int j0 = list ? list[t0] : t0, j1 = two ? (list ? list[t0 + 1] : t0 + 1) : j0;
+    const vec_t* w0 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                     (size_t)j0 * d * (WDT == SLONN_F32 ? 4 : 2));
+    const vec_t* w1 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                     (size_t)j1 * d * (WDT == SLONN_F32 ? 4 : 2));
+    float acc0 = 0.0f, acc1 = 0.0f;
+#pragma unroll 4
+    for (int i = lane; i < nv; i += 64) {
+      const vec_t a0 = w0[i], a1 = w1[i];
+      const float* xp = xs + i * C::ELEMS;
+      acc0 = C::dot(a0, xp, acc0);
+      acc1 = C::dot(a1, xp, acc1);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      acc0 += __shfl_xor(acc0, o);
+      acc1 += __shfl_xor(acc1, o);
+    }
+    if (lane == 0 || (lane == 1 && two)) {
+      const int j = lane == 0 ? j0 : j1;
+      float z = (lane == 0 ? acc0 : acc1) + bias[j];
+      if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+      if (Y) Y[(size_t)q * ldy + j] = z;
+      if (yc) yc[(size_t)q * ldc + t0 + lane] = z;
+    }
+  }
+}
+
 // Row-block variant for layers whose weight matrix is much larger than an L2 slice:
 // workgroup (q, block) evaluates the rows of query q that lie in one block of consecutive
 // weight rows (about a megabyte).  The grid runs over queries fastest, so the workgroups
@@ -316,12 +369,25 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
                    (reinterpret_cast<uintptr_t>(X) % 16 == 0);
   const size_t lds = ((size_t)d + 8) * sizeof(float);
   if (lds > 65536) SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
+  const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
+  if (vec && B <= 16 && (size_t)d * esz >= 1024) {        // few queries, long rows: one wavefront per row
+    int chunks = (max_rows + ROWS_PER_WAVE_BLOCK - 1) / ROWS_PER_WAVE_BLOCK;
+    chunks = std::min(chunks, std::max(4, 4096 / B));
+    dim3 grid(chunks, B);
+    if (w_dtype == SLONN_F32)
+      hipLaunchKernelGGL((gather_wave_kernel<SLONN_F32>), grid, dim3(256), lds, s, W, bias, X, ldx, active,
+                         cnt, idx_stride, Y, ldy, yc, ldc, d, n, a);
+    else
+      hipLaunchKernelGGL((gather_wave_kernel<SLONN_BF16>), grid, dim3(256), lds, s, W, bias, X, ldx, active,
+                         cnt, idx_stride, Y, ldy, yc, ldc, d, n, a);
+    SLONN_HIP(hipGetLastError());
+    return SLONN_OK;
+  }
   // enough chunks per query to fill the chip, never more than the list can have
   int chunks = (max_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
   const int want = std::max(4, (4096 + B - 1) / B);
   if (active && chunks > want) chunks = want;
   dim3 grid(chunks, B);
-  const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
 #define SLONN_LAUNCH_GATHER(WDT, VEC)                                                              \
   hipLaunchKernelGGL((gather_forward_kernel<WDT, VEC>), grid, dim3(256), lds, s, W, bias, X, ldx,  \
                      active, cnt, idx_stride, Y, ldy, yc, ldc, d, n, a)

@@ -131,6 +131,36 @@ __global__ __launch_bounds__(64 * KS) void hash_project_mfma_kernel(const float*
   }
 }
 
+// A handful of queries cannot fill a 16-row MFMA tile: one wavefront per (query, hash row),
+// fp64 FMAs on the vector ALUs, x staged in LDS, four 16-byte loads in flight per lane.
+__global__ __launch_bounds__(256) void hash_project_rowwise_kernel(const float* __restrict__ X, int ldx,
+                                                                  const float* __restrict__ Wh,
+                                                                  const float* __restrict__ bh,
+                                                                  float* __restrict__ Z, int H, int d) {
+  extern __shared__ __align__(16) float xs_hash[];
+  const int q = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float4* x4 = reinterpret_cast<const float4*>(X + (size_t)q * ldx);
+  for (int i = tid; i < (d >> 2); i += 256) reinterpret_cast<float4*>(xs_hash)[i] = x4[i];
+  __syncthreads();
+  const int h = blockIdx.x * 4 + wave;
+  if (h >= H) return;
+  const float4* w = reinterpret_cast<const float4*>(Wh + (size_t)h * d);
+  const int nv = d >> 2;
+  double acc = 0.0;
+#pragma unroll 4
+  for (int i = lane; i < nv; i += 64) {
+    const float4 a = w[i];
+    const float4 x = reinterpret_cast<const float4*>(xs_hash)[i];
+    acc = fma((double)a.x, (double)x.x, acc);
+    acc = fma((double)a.y, (double)x.y, acc);
+    acc = fma((double)a.z, (double)x.z, acc);
+    acc = fma((double)a.w, (double)x.w, acc);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+  if (lane == 0) Z[(size_t)q * H + h] = (float)(acc + (double)bh[h]);
+}
+
 constexpr int TQ = 32;   // queries per tile
 constexpr int TH = 64;   // hash nodes per tile
 constexpr int TK = 32;   // reduction chunk
@@ -190,6 +220,12 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
   ProfScope prof_(SLONN_PROF_HASH, s);
   const bool vec = (d % 4 == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
                    (reinterpret_cast<uintptr_t>(Wh) % 16 == 0);
+  if (vec && B <= 4 && (size_t)d * 4 + 64 <= 65536) {
+    hipLaunchKernelGGL(hash_project_rowwise_kernel, dim3((H + 3) / 4, B), dim3(256), (size_t)d * 4 + 64, s, X,
+                       ldx, Wh, bh, Z, H, d);
+    SLONN_HIP(hipGetLastError());
+    return SLONN_OK;
+  }
   if (vec) {
     // small problems: one 16x16 tile per wavefront so that there are enough workgroups
     const long tiles32 = (long)((H + 31) / 32) * ((B + 31) / 32);

@@ -21,7 +21,8 @@ __device__ __forceinline__ int budget_of(float keep, int n) {
   return (int)m;
 }
 
-constexpr int SEL_NT = 256;
+constexpr int SEL_NT = 256;      // workgroup size for real batches
+constexpr int SEL_NT_BIG = 1024; // few queries: four times as many slots per round
 
 // Regroup a finished list by weight-row block (counting sort; the order inside a group does
 // not matter: outputs are written by node id and by selection position).  hist: at least
@@ -30,9 +31,9 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
                                                uint32_t* hist) {
   const int tid = threadIdx.x;
   __syncthreads();
-  for (int b = tid; b <= rb.nblk; b += SEL_NT) hist[b] = 0;
+  for (int b = tid; b <= rb.nblk; b += blockDim.x) hist[b] = 0;
   __syncthreads();
-  for (int t = tid; t < m; t += SEL_NT) atomicAdd(&hist[out[t] / rb.rows_per_block], 1u);
+  for (int t = tid; t < m; t += blockDim.x) atomicAdd(&hist[out[t] / rb.rows_per_block], 1u);
   __syncthreads();
   if (tid < 64) {         // exclusive prefix sum over the row blocks by one wavefront
     uint32_t carry = 0;
@@ -53,7 +54,7 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
     }
   }
   __syncthreads();
-  for (int t = tid; t < m; t += SEL_NT) {
+  for (int t = tid; t < m; t += blockDim.x) {
     const int id = out[t];
     const uint32_t p = atomicAdd(&hist[id / rb.rows_per_block], 1u);
     rb.part_idx[(size_t)q * rb.stride + p] = id;
@@ -63,28 +64,29 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
 
 // Every row is active: the groups are the row blocks themselves.
 __device__ __forceinline__ void identity_rows(const RowBlocking& rb, int q, int n) {
-  for (int i = threadIdx.x; i < n; i += SEL_NT) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
     rb.part_idx[(size_t)q * rb.stride + i] = i;
     rb.part_pos[(size_t)q * rb.stride + i] = i;
   }
-  for (int b = threadIdx.x; b <= rb.nblk; b += SEL_NT)
+  for (int b = threadIdx.x; b <= rb.nblk; b += blockDim.x)
     rb.blk_off[(size_t)q * (rb.nblk + 1) + b] = min(b * rb.rows_per_block, n);
 }
 
 
-__global__ __launch_bounds__(SEL_NT) void select_block_kernel(
+template <int NT>
+__global__ __launch_bounds__(NT) void select_block_kernel(
     const float* __restrict__ Z, int K, int L, int n, const uint32_t* __restrict__ dir,
     const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
     float* __restrict__ yzero, int ldy, RowBlocking rb) {
   extern __shared__ __align__(16) uint32_t smem32[];
-  SelectShared<SEL_NT> sh;
+  SelectShared<NT> sh;
   sh.prio = smem32;
   sh.s_off = smem32 + n;
   sh.s_len = sh.s_off + 64;
   sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
-  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * (SEL_NT / 64));
+  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * (NT / 64));
 
   const int q = blockIdx.x, tid = threadIdx.x;
   const int m = budget_of(keep[(size_t)q * keep_stride], n);
@@ -92,7 +94,7 @@ __global__ __launch_bounds__(SEL_NT) void select_block_kernel(
   const float* z = Z + (size_t)q * K * L;
   if (yzero) {
     float* y = yzero + (size_t)q * ldy;
-    for (int i = tid; i < n; i += SEL_NT) y[i] = 0.0f;
+    for (int i = tid; i < n; i += NT) y[i] = 0.0f;
   }
   if (tid == 0) cnt[q] = m;
   if (m == n) {   // the layer is computed in full: ascending ids, no table access
@@ -101,13 +103,13 @@ __global__ __launch_bounds__(SEL_NT) void select_block_kernel(
       for (int j = 0; j < K; ++j) key |= (z[tid * K + j] > 0.0f ? 1u : 0u) << j;
       codes[(size_t)q * L + tid] = key;
     }
-    for (int i = tid; i < n; i += SEL_NT) out[i] = i;
+    for (int i = tid; i < n; i += NT) out[i] = i;
     if (rb.part_idx) identity_rows(rb, q, n);
     return;
   }
-  for (int i = tid; i < n; i += SEL_NT) sh.prio[i] = 0xFFFFFFFFu;
+  for (int i = tid; i < n; i += NT) sh.prio[i] = 0xFFFFFFFFu;
   __syncthreads();
-  select_block<SEL_NT>(z, K, L, n, m, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr, out);
+  select_block<NT>(z, K, L, n, m, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr, out);
 
   if (rb.part_idx) partition_rows(out, m, rb, q, sh.prio);
 }
@@ -172,14 +174,22 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
                   int ldy, int max_lds, const RowBlocking* rb, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_SELECT, s);
-  const size_t lds_block = ((size_t)n + SelectShared<SEL_NT>::words_besides_prio) * 4;
+  const size_t lds_block = ((size_t)n + SelectShared<SEL_NT_BIG>::words_besides_prio) * 4;
   if (lds_block <= (size_t)max_lds) {
-    if (lds_block > 65536)
-      SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
-    hipLaunchKernelGGL(select_block_kernel, dim3(B), dim3(SEL_NT), lds_block, s, Z, K, L, n, dir, ids,
-                       global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy,
-                       rb ? *rb : RowBlocking{});
+    const RowBlocking rbv = rb ? *rb : RowBlocking{};
+    if (B <= 64) {
+      if (lds_block > 65536)
+        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
+      hipLaunchKernelGGL((select_block_kernel<SEL_NT_BIG>), dim3(B), dim3(SEL_NT_BIG), lds_block, s, Z, K, L, n,
+                         dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv);
+    } else {
+      if (lds_block > 65536)
+        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
+      hipLaunchKernelGGL((select_block_kernel<SEL_NT>), dim3(B), dim3(SEL_NT), lds_block, s, Z, K, L, n, dir,
+                         ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv);
+    }
     SLONN_HIP(hipGetLastError());
     return SLONN_OK;
   }
