@@ -157,6 +157,14 @@ def main():
         return tot
 
     head_keep = None if mixed is not None else args.keep
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)            # plain copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- headline: K steps at the chosen keep fraction ----
     dev_s, wall_s = timed(args.keep, K, W)
     secs = max(dev_s, wall_s)             # the host loop must keep up: report the slower clock
