@@ -228,7 +228,11 @@ def main():
             slonn.slonn_dense_forward(net.model, batches[i % n_batches], B, yd, out_arg, None, ws, stream)
         e1.record(stream)
         torch.cuda.synchronize()
-        extra["dense_baseline_qps"] = round(120 * B / (e0.elapsed_time(e1) / 1e3))
+        dsec = e0.elapsed_time(e1) / 1e3
+        extra["dense_baseline_qps"] = round(120 * B / dsec)
+        dflops = 2.0 * sum(lay.d_in * lay.d_out for lay in layers if not (ell and lay is layers[0]))
+        extra["dense_baseline_tflops"] = round(dflops * 120 * B / dsec / 1e12, 2)
+        extra["dense_baseline_frac_of_fp32_mfma_peak"] = round(dflops * 120 * B / dsec / 157.3e12, 4)
 
     # ---- CPU baseline: the oracle as it stands, on the host cores, bounded sample ----
     cpu = None

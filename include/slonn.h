@@ -50,6 +50,7 @@ enum { SLONN_DENSE = 0, SLONN_ELL = 1 };                /* first-layer input for
 
 #define SLONN_MAX_K 16      /* bits per key                                               */
 #define SLONN_MAX_L 64      /* tables per layer (one wavefront lane per table)            */
+#define SLONN_MAX_BATCH 1048576 /* queries per call, and training inputs per table build   */
 #define SLONN_TABLE_BLOB_MAGIC 0x544E4C53u /* "SLNT" */
 #define SLONN_TABLE_BLOB_VERSION 1u
 
@@ -148,7 +149,8 @@ int slonn_model_set_path(slonn_model* m, int path);
  * positive-score nodes sorted from the highest sum to the lowest (ties: lower id),
  * at most list_cap of them; the sums over all N inputs give the fallback ranking.
  * Allocates temporary device memory, synchronises `stream`, returns owned tables.
- * EUNSUPPORTED: d_out of an activated layer above 8192 (bucket sort runs in LDS).   */
+ * N <= SLONN_MAX_BATCH.  EUNSUPPORTED: an activated layer wider than 8192 nodes whose
+ * list_cap also exceeds 8192 (wide layers rank only the head of each bucket).        */
 int slonn_build_tables(const slonn_model* m, const slonn_input* X_build, int64_t N, void* stream,
                        slonn_tables** out);
 

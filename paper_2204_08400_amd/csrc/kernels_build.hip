@@ -375,7 +375,7 @@ extern "C" int slonn_build_tables(const slonn_model* m, const slonn_input* X_bui
   if (!out) SLONN_FAIL(SLONN_EINVAL, "out is null");
   *out = nullptr;
   if (!m || !X_build) SLONN_FAIL(SLONN_EINVAL, "null argument");
-  if (N <= 0 || N > 0x7FFFFFFF) SLONN_FAIL(SLONN_EINVAL, "N must be in 1 .. 2^31-1");
+  if (N <= 0 || N > SLONN_MAX_BATCH) SLONN_FAIL(SLONN_EINVAL, "N must be in 1 .. %d", SLONN_MAX_BATCH);
   if (X_build->format == SLONN_DENSE) {
     if (!X_build->x) SLONN_FAIL(SLONN_EINVAL, "dense input pointer is null");
     if (m->layers[0].w_layout != SLONN_ROWS_ARE_NODES)

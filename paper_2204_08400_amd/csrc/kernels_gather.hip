@@ -83,9 +83,9 @@ __global__ __launch_bounds__(256) void gather_forward_kernel(
     float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int n, int act) {
   extern __shared__ __align__(16) float xs[];
   using C = Chunk<WDT>;
-  const int q = blockIdx.y;
+  const int q = blockIdx.x;              // queries on x (no 65535 limit), chunks on y
   const int c = active ? cnt[q] : n;
-  if ((int)blockIdx.x * ROWS_PER_BLOCK >= c) return;
+  if ((int)blockIdx.y * ROWS_PER_BLOCK >= c) return;
   const int tid = threadIdx.x;
   const float* x = X + (size_t)q * ldx;
   if (VECTOR) {
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void gather_forward_kernel(
   const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
   // the grid holds a bounded number of chunks per query (the budget is only known on the
   // device); a workgroup walks its chunks with the grid's stride
-  for (int row0 = blockIdx.x * ROWS_PER_BLOCK; row0 < c; row0 += gridDim.x * ROWS_PER_BLOCK) {
+  for (int row0 = blockIdx.y * ROWS_PER_BLOCK; row0 < c; row0 += gridDim.y * ROWS_PER_BLOCK) {
     int t[ROWS_PER_GROUP], j[ROWS_PER_GROUP];
     float acc[ROWS_PER_GROUP];
 #pragma unroll
@@ -167,9 +167,9 @@ __global__ __launch_bounds__(256) void gather_wave_kernel(
   extern __shared__ __align__(16) float xs[];
   using C = Chunk<WDT>;
   using vec_t = typename C::vec_t;
-  const int q = blockIdx.y;
+  const int q = blockIdx.x;
   const int c = active ? cnt[q] : n;
-  if ((int)blockIdx.x * ROWS_PER_WAVE_BLOCK >= c) return;
+  if ((int)blockIdx.y * ROWS_PER_WAVE_BLOCK >= c) return;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float* x = X + (size_t)q * ldx;
   for (int i = tid; i < (d >> 2); i += 256)
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256) void gather_wave_kernel(
   __syncthreads();
   const int nv = d / C::ELEMS;
   const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
-  for (int t0 = blockIdx.x * ROWS_PER_WAVE_BLOCK + 2 * wave; t0 < c; t0 += gridDim.x * ROWS_PER_WAVE_BLOCK) {
+  for (int t0 = blockIdx.y * ROWS_PER_WAVE_BLOCK + 2 * wave; t0 < c; t0 += gridDim.y * ROWS_PER_WAVE_BLOCK) {
     const bool two = t0 + 1 < c;
     const int j0 = list ? list[t0] : t0, j1 = two ? (list ? list[t0 + 1] : t0 + 1) : j0;
     const vec_t* w0 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) void ell_layer_kernel(
     int ell_stride, float* __restrict__ Y, int ldy, int d, int n, int act) {
   extern __shared__ __align__(16) unsigned char ell_smem[];
   using C = Chunk<WDT>;
-  const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = nnz[q];
   int32_t* s_idx = reinterpret_cast<int32_t*>(ell_smem);
   float* s_val = reinterpret_cast<float*>(s_idx + ell_stride);
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(256) void ell_layer_kernel(
     s_val[t] = val[(size_t)q * ell_stride + t];
   }
   __syncthreads();
-  const int j = blockIdx.x * 64 + lane;
+  const int j = blockIdx.y * 64 + lane;
   const int jj = j < n ? j : n - 1;
   const int per = (c + 3) / 4;
   const int t0 = wave * per, t1 = min(c, t0 + per);
@@ -373,7 +373,7 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
   if (vec && B <= 16 && (size_t)d * esz >= 1024) {        // few queries, long rows: one wavefront per row
     int chunks = (max_rows + ROWS_PER_WAVE_BLOCK - 1) / ROWS_PER_WAVE_BLOCK;
     chunks = std::min(chunks, std::max(4, 4096 / B));
-    dim3 grid(chunks, B);
+    dim3 grid(B, chunks);
     if (w_dtype == SLONN_F32)
       hipLaunchKernelGGL((gather_wave_kernel<SLONN_F32>), grid, dim3(256), lds, s, W, bias, X, ldx, active,
                          cnt, idx_stride, Y, ldy, yc, ldc, d, n, a);
@@ -386,8 +386,8 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
   // enough chunks per query to fill the chip, never more than the list can have
   int chunks = (max_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
   const int want = std::max(4, (4096 + B - 1) / B);
-  if (active && chunks > want) chunks = want;
-  dim3 grid(chunks, B);
+  if (chunks > want) chunks = want;
+  dim3 grid(B, chunks);
 #define SLONN_LAUNCH_GATHER(WDT, VEC)                                                              \
   hipLaunchKernelGGL((gather_forward_kernel<WDT, VEC>), grid, dim3(256), lds, s, W, bias, X, ldx,  \
                      active, cnt, idx_stride, Y, ldy, yc, ldc, d, n, a)
@@ -424,7 +424,8 @@ int launch_ell_layer(const void* W, int w_dtype, int w_layout, const float* bias
                      const float* val, const int32_t* nnz, int ell_stride, float* Y, int ldy, int B,
                      int d, int n, int act, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_ELL, s);
-  dim3 grid((n + 63) / 64, B);
+  if ((n + 63) / 64 > 65535) SLONN_FAIL(SLONN_EUNSUPPORTED, "sparse-input layer with %d nodes is too wide", n);
+  dim3 grid(B, (n + 63) / 64);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
   const size_t lds = (size_t)ell_stride * 8 + 4 * 64 * 4;
   if (lds > 65536) SLONN_FAIL(SLONN_EUNSUPPORTED, "ELL input with %d slots per row does not fit LDS", ell_stride);

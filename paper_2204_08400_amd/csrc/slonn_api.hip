@@ -319,7 +319,7 @@ int slonn_model_destroy(slonn_model* m) {
 
 int slonn_workspace_bytes(const slonn_model* m, int B_max, size_t* out) {
   if (!m || !out) SLONN_FAIL(SLONN_EINVAL, "null argument");
-  if (B_max <= 0) SLONN_FAIL(SLONN_EINVAL, "B_max must be positive");
+  if (B_max <= 0 || B_max > SLONN_MAX_BATCH) SLONN_FAIL(SLONN_EINVAL, "B_max must be in 1 .. %d", SLONN_MAX_BATCH);
   Workspace w;
   plan_workspace(m, B_max, nullptr, &w);
   *out = w.bytes;
@@ -462,7 +462,7 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
                  size_t ws_bytes, void* stream) {
   if (!m || !t || !X_l || !keep || !active_idx || !active_cnt) SLONN_FAIL(SLONN_EINVAL, "null argument");
   if (t->model != m) SLONN_FAIL(SLONN_EINVAL, "tables belong to another model");
-  if (B <= 0) SLONN_FAIL(SLONN_EINVAL, "B must be positive");
+  if (B <= 0 || B > SLONN_MAX_BATCH) SLONN_FAIL(SLONN_EINVAL, "B must be in 1 .. %d", SLONN_MAX_BATCH);
   if (layer < 0 || layer >= (int)m->layers.size()) SLONN_FAIL(SLONN_EINVAL, "no layer %d", layer);
   if (keep_stride < 0) SLONN_FAIL(SLONN_EINVAL, "negative keep stride");
   const Layer& L = m->layers[layer];
@@ -490,7 +490,7 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
                          const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
                          void* stream) {
   if (!m || !X || !keep || !Y) SLONN_FAIL(SLONN_EINVAL, "null argument");
-  if (B <= 0) SLONN_FAIL(SLONN_EINVAL, "B must be positive");
+  if (B <= 0 || B > SLONN_MAX_BATCH) SLONN_FAIL(SLONN_EINVAL, "B must be in 1 .. %d", SLONN_MAX_BATCH);
   if (keep_qstride < 0 || keep_lstride < 0) SLONN_FAIL(SLONN_EINVAL, "negative keep stride");
   int rc = check_input(m, X);
   if (rc) return rc;
@@ -658,7 +658,7 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
 int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float* Y, int32_t* argmax,
                         float** layer_out, void* workspace, size_t ws_bytes, void* stream) {
   if (!m || !X || !Y) SLONN_FAIL(SLONN_EINVAL, "null argument");
-  if (B <= 0) SLONN_FAIL(SLONN_EINVAL, "B must be positive");
+  if (B <= 0 || B > SLONN_MAX_BATCH) SLONN_FAIL(SLONN_EINVAL, "B must be in 1 .. %d", SLONN_MAX_BATCH);
   int rc = check_input(m, X);
   if (rc) return rc;
   Workspace w;

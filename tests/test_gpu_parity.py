@@ -422,3 +422,53 @@ def test_config_c4_shape(rt, oracle):
     assert np.array_equal(lean["cnt"], got["cnt"]) and np.array_equal(lean["argmax"], got["argmax"])
     assert np.array_equal(lean["idx"][:, :500], got["idx"][:, :500])
     assert np.array_equal(lean["val"][:, :500], got["val"][:, :500])
+
+
+def test_runs_are_bit_reproducible(rt, oracle):
+    """No float atomics or order-dependent reductions on the path: two runs of the same
+    batch give identical bits on both paths (a cheap race detector)."""
+    dims = (96, 1000, 640, 12)
+    layers, net, _ = make_case(oracle, dims, 6, 10, seed=23)
+    X = make_queries(dims, 200, seed=6)
+    keep = _keep_tensor(wl.keep_uniform(200, 0.01, 0.9, 8))
+    for path in ("layers", "fused"):
+        g = _gpu_net(rt, layers, net, path=path)
+        a = to_numpy_result(g.sparse_forward(X, keep, taps=True))
+        for _ in range(3):
+            b = to_numpy_result(g.sparse_forward(X, keep, taps=True))
+            assert np.array_equal(a["out"], b["out"]) and np.array_equal(a["argmax"], b["argmax"])
+            for l in (0, 1):
+                assert np.array_equal(a["taps"]["active"][l], b["taps"]["active"][l])
+                assert np.array_equal(a["taps"]["z"][l], b["taps"]["z"][l])
+
+
+def test_argument_errors_on_device(rt, oracle):
+    import torch
+    from paper_2204_08400_amd import slonn
+    dims = (40, 64, 64, 8)
+    layers, net, _ = make_case(oracle, dims, 3, 2, seed=41)
+    g = _gpu_net(rt, layers, net)
+    X = torch.from_numpy(make_queries(dims, 4, seed=8)).cuda()
+    keep = torch.full((1,), 0.5, device="cuda")
+    ws = g.workspace(4)
+    out = slonn.make_output(dense=torch.empty((4, 8), device="cuda"))
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(slonn.SlonnError) as e:       # workspace too small
+        g.set_path("layers")
+        slonn.slonn_sparse_forward(g.model, g.tables, g.to_input(X), 4, keep, 0, 0, out, None, small)
+    assert e.value.code == slonn.ENOMEM
+    with pytest.raises(slonn.SlonnError) as e:       # active-list stride below the layer width
+        slonn.slonn_select(g.model, g.tables, 0, X, 4, keep, 0, None, None,
+                           torch.empty((4, 10), dtype=torch.int32, device="cuda"),
+                           torch.empty(4, dtype=torch.int32, device="cuda"), 10, ws)
+    assert e.value.code == slonn.ECAP
+    with pytest.raises(slonn.SlonnError) as e:       # tables of another model
+        other = _gpu_net(rt, layers, net)
+        slonn.slonn_sparse_forward(g.model, other.tables, g.to_input(X), 4, keep, 0, 0, out, None, ws)
+    assert e.value.code == slonn.EINVAL
+    with pytest.raises(slonn.SlonnError):            # a corrupted blob is refused
+        blob = bytearray(net.export_tables())
+        blob[60] ^= 0xFF
+        g.import_tables(bytes(blob))
+    with pytest.raises(slonn.SlonnError):            # batch beyond the documented maximum
+        slonn.slonn_workspace_bytes(g.model, (1 << 20) + 1)
