@@ -215,11 +215,13 @@ __global__ __launch_bounds__(256) void gather_wave_kernel(
 template <int WDT>
 __global__ __launch_bounds__(256) void gather_blocked_kernel(
     const void* __restrict__ W, const float* __restrict__ bias, const float* __restrict__ X, int ldx,
-    RowBlocking rb, float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int act) {
+    RowBlocking rb, float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int act,
+    const int32_t* __restrict__ skip_group) {
   extern __shared__ __align__(16) float xs[];
   using C = Chunk<WDT>;
   using vec_t = typename C::vec_t;
   const int q = blockIdx.x, blk = blockIdx.y;
+  if (skip_group && skip_group[q >> 4]) return;      // served by the grouped evaluation
   const int32_t* off = rb.blk_off + (size_t)q * (rb.nblk + 1);
   const int c0 = off[blk], c1 = off[blk + 1];
   if (c0 >= c1) return;
@@ -403,7 +405,7 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
 
 int launch_gather_blocked(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                           const RowBlocking& rb, float* Y, int ldy, float* yc, int ldc, int B, int d,
-                          int n, int act, hipStream_t s) {
+                          int n, int act, const int32_t* skip_group, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_GATHER, s);
   if (B <= 0) return SLONN_OK;
   const size_t lds = ((size_t)d + 8) * sizeof(float);
@@ -412,10 +414,10 @@ int launch_gather_blocked(const void* W, int w_dtype, const float* bias, const f
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
   if (w_dtype == SLONN_F32)
     hipLaunchKernelGGL((gather_blocked_kernel<SLONN_F32>), grid, dim3(256), lds, s, W, bias, X, ldx, rb, Y,
-                       ldy, yc, ldc, d, a);
+                       ldy, yc, ldc, d, a, skip_group);
   else
     hipLaunchKernelGGL((gather_blocked_kernel<SLONN_BF16>), grid, dim3(256), lds, s, W, bias, X, ldx, rb, Y,
-                       ldy, yc, ldc, d, a);
+                       ldy, yc, ldc, d, a, skip_group);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

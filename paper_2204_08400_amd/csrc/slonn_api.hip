@@ -50,6 +50,7 @@ struct Workspace {
   int32_t* part_idx = nullptr;          // [B][max_n_activated] lists regrouped by row block
   int32_t* part_pos = nullptr;          // [B][max_n_activated]
   int32_t* blk_off = nullptr;           // [B][MAX_ROW_BLOCKS + 1]
+  void* grouped = nullptr;              // union lists of the grouped evaluation
   size_t bytes = 0;
   int max_n = 0, max_H = 0, max_na = 0;
 };
@@ -78,6 +79,7 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   w->part_idx = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->part_pos = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->blk_off = reinterpret_cast<int32_t*>(take((size_t)B * (MAX_ROW_BLOCKS + 1) * 4));
+  w->grouped = take(grouped_workspace_bytes(B, std::max(max_na, 1)));
   w->bytes = off;
 }
 
@@ -610,10 +612,21 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       if (rc) return rc;
       act_list = aidx; act_cnt = acnt; act_stride = astride;
       if (is_last && Y->val) yc = Y->val;
-      if (rb.part_idx)
+      if (rb.part_idx) {
+        // Large batches: groups of 16 queries whose lists overlap enough are evaluated together
+        // on the matrix cores (decided per group on the device); the rest is gathered per query.
+        const int32_t* gflag = nullptr;
+        const long tiles = (long)((B + 15) / 16) * ((L.d_out + 127) / 128);
+        if (tiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {
+          int32_t* flags = nullptr;
+          rc = launch_gather_grouped(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B,
+                                     L.d_in, L.d_out, act, w.grouped, m->max_lds_bytes, &flags, s);
+          if (rc) return rc;
+          gflag = flags;
+        }
         rc = launch_gather_blocked(L.W, L.w_dtype, L.bias, cur, ldcur, rb, out, ldo, yc, Y->stride, B, L.d_in,
-                                   L.d_out, act, s);
-      else
+                                   L.d_out, act, gflag, s);
+      } else
         rc = launch_gather_forward(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, L.d_out, out, ldo,
                                    yc, Y->stride, B, L.d_in, L.d_out, act, s);
       if (rc) return rc;

@@ -57,6 +57,7 @@ struct TableSet {                 // Node Importance tables of one layer
 struct slonn_model {
   std::vector<slonn::Layer> layers;
   int path = SLONN_PATH_AUTO;
+  bool path_grouped = true;       // allow the grouped (cross-query) evaluation on the per-layer path
   int max_lds_bytes = 65536;      // per-workgroup LDS the device grants on request
   int n_cu = 256;
 };
@@ -137,9 +138,22 @@ bool select_fills_row_blocks(int n, int max_lds);
 
 // Same result as launch_gather_forward from row-block-grouped lists: workgroup (q, block)
 // evaluates the rows of query q that fall into that block of the weight matrix.
+// skip_group (nullable): [ceil(B/16)] flags; queries of a flagged group are left to the
+// grouped evaluation below.
 int launch_gather_blocked(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                           const RowBlocking& rb, float* Y, int ldy, float* yc, int ldc, int B, int d,
-                          int n, int act, hipStream_t s);
+                          int n, int act, const int32_t* skip_group, hipStream_t s);
+
+// Groups of 16 queries: the union of their active rows evaluated as dense tiles on the matrix
+// cores, selected (query, node) pairs written to Y.  A group whose union is too large
+// relative to its lists is flagged 0 in *gflag_out (device array, [ceil(B/16)]) and left
+// untouched.  scratch: grouped_workspace_bytes(B, n) bytes of device memory.
+size_t grouped_workspace_bytes(int B, int n);
+bool grouped_supported(int n, int max_lds);
+int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
+                          const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy,
+                          int B, int d, int n, int act, void* scratch, int max_lds, int32_t** gflag_out,
+                          hipStream_t s);
 
 // y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).
 // yc (nullable) receives the values in list order.

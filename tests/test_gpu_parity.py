@@ -472,3 +472,27 @@ def test_argument_errors_on_device(rt, oracle):
         g.import_tables(bytes(blob))
     with pytest.raises(slonn.SlonnError):            # batch beyond the documented maximum
         slonn.slonn_workspace_bytes(g.model, (1 << 20) + 1)
+
+
+@pytest.mark.parametrize("w_dtype", [wl.W_F32, wl.W_BF16], ids=["f32", "bf16"])
+def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype):
+    """Large batch on the per-layer path: groups of 16 queries whose active sets overlap are
+    evaluated together on the matrix cores (union of rows x 16 queries, selected pairs kept);
+    groups with little overlap stay on the per-query gather.  Same results either way."""
+    from paper_2204_08400_amd import slonn
+    d = 512 if w_dtype == wl.W_F32 else 1024
+    dims = (d, 4096, 24)
+    layers, net, _ = make_case(oracle, dims, 6, 8, seed=61, hashed=[0], cap=1500, N_build=192, kind="clip3",
+                               w_dtype=w_dtype)
+    g = _gpu_net(rt, layers, net, path="layers")
+    B = 512 + 7                      # ragged last group
+    X = make_queries(dims, B, seed=62, kind="clip3")
+    for keep in (0.3, wl.keep_uniform(B, 0.0001, 0.3, 9)):
+        _say(f"grouped evaluation {'f32' if w_dtype == wl.W_F32 else 'bf16'} keep={'mixed' if np.ndim(keep) else keep}")
+        ref = net.sparse_forward(X, keep)
+        kt = _keep_tensor(keep) if np.ndim(keep) else keep
+        slonn.slonn_profile_begin(64)
+        got = to_numpy_result(g.sparse_forward(X, kt, taps=True))
+        prof = slonn.slonn_profile_end()
+        assert prof["gather"][1] == 3, prof     # grouped + per-query pass on layer 0, output layer
+        _say(f"  {compare_sparse(got, ref, layers, 'grouped')}")
