@@ -15,8 +15,11 @@
 //           found with an LDS integer min over slot numbers (order-independent, hence
 //           deterministic), survivors are compacted in slot order with a ballot and a
 //           two-level prefix sum, no atomic counters;
-//   gather  y_j = act(w_j . x + b_j) for the active rows, four rows per 16-lane group
-//           in flight, written straight into the next layer's input in LDS (dropped
+//   reuse   an active node that is also one of the layer's hash nodes already has its
+//           pre-activation: the hash projection IS w_j . x + b_j (Section 3.4, the hash is
+//           "free").  Its output is taken from there and the node leaves the gather list;
+//   gather  y_j = act(w_j . x + b_j) for the remaining active rows, four rows per 16-lane
+//           group in flight, written straight into the next layer's input in LDS (dropped
 //           nodes were zeroed there beforehand).
 #include "select_block.h"
 #include "slonn_internal.h"
@@ -127,6 +130,48 @@ __device__ __forceinline__ void gather_few_rows(const void* __restrict__ W, cons
   }
 }
 
+// One pass of the row gather: every 16-lane group takes up to R rows (t0, t0 + GROUPS, ...),
+// all R row streams in flight together.  R is the same for the whole workgroup, so a pass
+// over fewer rows than 4 * GROUPS issues no loads for rows that do not exist.
+template <int WDT, int R>
+__device__ __forceinline__ void gather_pass(const void* __restrict__ W, const float* __restrict__ bias,
+                                            int d, const float* xs, const int32_t* list, int t0, int count,
+                                            int act, float* dst) {
+  constexpr int ELEMS = (WDT == SLONN_F32) ? 4 : 8;
+  constexpr int ESZ = (WDT == SLONN_F32) ? 4 : 2;
+  const int l = threadIdx.x & 15;
+  const int nv = d / ELEMS;
+  int t[R], j[R];
+  float acc[R];
+  const uint4* w[R];
+#pragma unroll
+  for (int k = 0; k < R; ++k) {
+    t[k] = t0 + k * GROUPS;
+    const int tt = t[k] < count ? t[k] : t0;
+    j[k] = list ? list[tt] : tt;
+    acc[k] = 0.f;
+    w[k] = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j[k] * d * ESZ);
+  }
+#pragma unroll 2
+  for (int i = l; i < nv; i += 16) {
+    uint4 v[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) v[k] = w[k][i];
+    const float* xp = xs + i * ELEMS;
+#pragma unroll
+    for (int k = 0; k < R; ++k) acc[k] = dot16<WDT>(v[k], xp, acc[k]);
+  }
+#pragma unroll
+  for (int k = 0; k < R; ++k) acc[k] = reduce16(acc[k]);
+#pragma unroll
+  for (int k = 0; k < R; ++k)
+    if (l == k && t[k] < count) {
+      float z = acc[k] + bias[j[k]];
+      if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+      dst[j[k]] = z;
+    }
+}
+
 // rows listed in LDS (list == nullptr: rows 0..count-1) -> dst[j] = act(w_j . x + b_j)
 template <int WDT>
 __device__ __forceinline__ void gather_rows(const void* __restrict__ W, const float* __restrict__ bias,
@@ -136,41 +181,19 @@ __device__ __forceinline__ void gather_rows(const void* __restrict__ W, const fl
     gather_few_rows<WDT>(W, bias, d, xs, list, count, act, dst);
     return;
   }
-  constexpr int ELEMS = (WDT == SLONN_F32) ? 4 : 8;
-  constexpr int ESZ = (WDT == SLONN_F32) ? 4 : 2;
-  const int g = threadIdx.x >> 4, l = threadIdx.x & 15;
-  const int nv = d / ELEMS;
-  for (int t0 = g; t0 < count; t0 += 4 * GROUPS) {
-    int t[4], j[4];
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      t[k] = t0 + k * GROUPS;
-      const int tt = t[k] < count ? t[k] : t0;
-      j[k] = list ? list[tt] : tt;
+  const int g = threadIdx.x >> 4;
+  for (int base = 0; base < count; base += 4 * GROUPS) {
+    const int left = count - base;                       // same for every thread
+    const int t0 = base + g;
+    if (left > 3 * GROUPS) {
+      if (t0 < count) gather_pass<WDT, 4>(W, bias, d, xs, list, t0, count, act, dst);
+    } else if (left > 2 * GROUPS) {
+      if (t0 < count) gather_pass<WDT, 3>(W, bias, d, xs, list, t0, count, act, dst);
+    } else if (left > GROUPS) {
+      if (t0 < count) gather_pass<WDT, 2>(W, bias, d, xs, list, t0, count, act, dst);
+    } else {
+      if (t0 < count) gather_pass<WDT, 1>(W, bias, d, xs, list, t0, count, act, dst);
     }
-    const uint4* w0 = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j[0] * d * ESZ);
-    const uint4* w1 = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j[1] * d * ESZ);
-    const uint4* w2 = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j[2] * d * ESZ);
-    const uint4* w3 = reinterpret_cast<const uint4*>(static_cast<const char*>(W) + (size_t)j[3] * d * ESZ);
-#pragma unroll 2
-    for (int i = l; i < nv; i += 16) {
-      const uint4 a0 = w0[i], a1 = w1[i], a2 = w2[i], a3 = w3[i];
-      const float* xp = xs + i * ELEMS;
-      acc[0] = dot16<WDT>(a0, xp, acc[0]);
-      acc[1] = dot16<WDT>(a1, xp, acc[1]);
-      acc[2] = dot16<WDT>(a2, xp, acc[2]);
-      acc[3] = dot16<WDT>(a3, xp, acc[3]);
-    }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) acc[k] = reduce16(acc[k]);
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      if (l == k && t[k] < count) {
-        float z = acc[k] + bias[j[k]];
-        if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-        dst[j[k]] = z;
-      }
   }
 }
 
@@ -187,6 +210,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
   sh.s_len = sh.s_off + 64;
   sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
   sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * NW);
+  int16_t* hmap = reinterpret_cast<int16_t*>(sh.s_misc + 4);      // [max_na] node -> hash row or -1
 
   const int q = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -246,7 +270,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
         }
       }
       // meanwhile: clear the next activation buffer and the first-occurrence map
-      for (int i = tid; i < n; i += NT) { xn[i] = 0.0f; prio[i] = 0xFFFFFFFFu; }
+      for (int i = tid; i < n; i += NT) { xn[i] = 0.0f; prio[i] = 0xFFFFFFFFu; hmap[i] = Ly.hslot[i]; }
       __syncthreads();
 
       if (wave == 0 && lane == 0 && Ly.tap_cnt) Ly.tap_cnt[q] = m;
@@ -266,6 +290,36 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
         if (Ly.tap_idx)
           for (int i = tid; i < n; i += NT) Ly.tap_idx[(size_t)q * n + i] = i;
       }
+
+      // ---- reuse: active hash nodes take their output from the projections; the others
+      //      are compacted in place (a round writes below what the next round reads) ----
+      const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+      int kept = 0;
+      for (int base = 0; base < m; base += NT) {
+        const int i = base + tid;
+        const int node = i < m ? (list ? alist[i] : i) : -1;
+        const int hs = node >= 0 ? (int)hmap[node] : -1;
+        if (hs >= 0) {
+          const float z = zs[hs];
+          xn[node] = (Ly.act == SLONN_ACT_RELU && !(z > 0.0f)) ? 0.0f : z;
+        }
+        const bool stays = node >= 0 && hs < 0;
+        const unsigned long long votes = __ballot(stays);
+        if (lane == 0) sh.wave_cnt[wave] = __popcll(votes);
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          const int c = sh.wave_cnt[w];
+          before += (w < wave) ? c : 0;
+          total += c;
+        }
+        if (stays) alist[kept + before + __popcll(votes & below)] = node;
+        kept += total;
+        __syncthreads();
+      }
+      list = alist;
+      m = kept;
     }
 
     // ---- evaluate the active rows into the next layer's input ----
@@ -313,7 +367,8 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
 }  // namespace
 
 size_t fused_lds_bytes(const FusedArgs& a) {
-  return (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 + SelectShared<NT>::words_besides_prio * 4;
+  return (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 + SelectShared<NT>::words_besides_prio * 4 +
+         (((size_t)a.max_na * 2 + 15) & ~(size_t)15);
 }
 
 int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s) {

@@ -32,22 +32,29 @@ __global__ __launch_bounds__(256) void union_kernel(const int32_t* __restrict__ 
                                                    const int32_t* __restrict__ cnt, int idx_stride, int B,
                                                    int n, int32_t* __restrict__ urows,
                                                    uint32_t* __restrict__ umask, int32_t* __restrict__ ucnt,
-                                                   int32_t* __restrict__ gflag, int ustride) {
+                                                   int32_t* __restrict__ gflag, int ustride,
+                                                   const int16_t* __restrict__ skip_hslot) {
   extern __shared__ __align__(16) uint32_t mask2[];      // two 16-bit masks per word
   __shared__ int red[4];
+  __shared__ int listed;                                 // list entries that take part
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int q0 = g * GQ, nq = min(GQ, B - q0);
   const int words = (n + 1) >> 1;
   for (int i = tid; i < words; i += 256) mask2[i] = 0u;
+  if (tid == 0) listed = 0;
   __syncthreads();
+  int mine = 0;
   for (int qi = 0; qi < nq; ++qi) {
     const int c = cnt[q0 + qi];
     const int32_t* list = active + (size_t)(q0 + qi) * idx_stride;
     for (int t = tid; t < c; t += 256) {
       const int node = list[t];
+      if (skip_hslot && skip_hslot[node] >= 0) continue;   // output already taken from the projections
       atomicOr(&mask2[node >> 1], (1u << qi) << (16 * (node & 1)));
+      ++mine;
     }
   }
+  if (mine) atomicAdd(&listed, mine);
   __syncthreads();
   const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   int base = 0;
@@ -74,9 +81,7 @@ __global__ __launch_bounds__(256) void union_kernel(const int32_t* __restrict__ 
     // query's own list (measured break-even against the row-block gather on 4096-wide fp32
     // layers: union/list = 2.2 -> 0.74x the time, 3.9 -> 1.3x); otherwise the group stays on
     // the per-query gather.
-    long long msum = 0;
-    for (int qi = 0; qi < nq; ++qi) msum += cnt[q0 + qi];
-    gflag[g] = ((long long)base * nq <= 3 * msum) ? 1 : 0;
+    gflag[g] = ((long long)base * nq <= 3ll * listed) ? 1 : 0;
   }
 }
 
@@ -176,8 +181,8 @@ bool grouped_supported(int n, int max_lds) { return (size_t)((n + 1) / 2) * 4 + 
 
 int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                           const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy,
-                          int B, int d, int n, int act, void* scratch, int max_lds, int32_t** gflag_out,
-                          hipStream_t s) {
+                          int B, int d, int n, int act, const int16_t* skip_hslot, void* scratch, int max_lds,
+                          int32_t** gflag_out, hipStream_t s) {
   const int ng = (B + GQ - 1) / GQ;
   int32_t* urows = static_cast<int32_t*>(scratch);
   uint32_t* umask = reinterpret_cast<uint32_t*>(urows + (size_t)ng * n);
@@ -192,7 +197,7 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
       SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(union_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(union_kernel, dim3(ng), dim3(256), lds, s, active, cnt, idx_stride, B, n, urows, umask,
-                       ucnt, gflag, n);
+                       ucnt, gflag, n, skip_hslot);
     SLONN_HIP(hipGetLastError());
   }
   ProfScope prof_(SLONN_PROF_GATHER, s);

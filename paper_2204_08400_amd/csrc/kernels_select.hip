@@ -25,15 +25,28 @@ constexpr int SEL_NT = 256;      // workgroup size for real batches
 constexpr int SEL_NT_BIG = 1024; // few queries: four times as many slots per round
 
 // Regroup a finished list by weight-row block (counting sort; the order inside a group does
-// not matter: outputs are written by node id and by selection position).  hist: at least
-// nblk + 1 free words of LDS.  Called by the whole workgroup after the list is complete.
+// not matter: outputs are written by node id and by selection position).  Selected hash nodes
+// get their output from the projections z here and join no group.  hist: at least nblk + 1
+// free words of LDS.  Called by the whole workgroup after the list is complete (the list was
+// written by other threads: the barrier at the top also orders those global stores).
 __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const RowBlocking& rb, int q,
-                                               uint32_t* hist) {
+                                               const float* z, uint32_t* hist) {
   const int tid = threadIdx.x;
   __syncthreads();
   for (int b = tid; b <= rb.nblk; b += blockDim.x) hist[b] = 0;
   __syncthreads();
-  for (int t = tid; t < m; t += blockDim.x) atomicAdd(&hist[out[t] / rb.rows_per_block], 1u);
+  for (int t = tid; t < m; t += blockDim.x) {
+    const int id = out[t];
+    const int hs = rb.hslot ? (int)rb.hslot[id] : -1;
+    if (hs >= 0) {          // a selected hash node: its output is its projection
+      float v = z[hs];
+      if (rb.relu && !(v > 0.0f)) v = 0.0f;
+      if (rb.y) rb.y[(size_t)q * rb.ldy + id] = v;
+      if (rb.yc) rb.yc[(size_t)q * rb.ldc + t] = v;
+    } else {
+      atomicAdd(&hist[id / rb.rows_per_block], 1u);
+    }
+  }
   __syncthreads();
   if (tid < 64) {         // exclusive prefix sum over the row blocks by one wavefront
     uint32_t carry = 0;
@@ -56,22 +69,12 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
   __syncthreads();
   for (int t = tid; t < m; t += blockDim.x) {
     const int id = out[t];
+    if (rb.hslot && rb.hslot[id] >= 0) continue;
     const uint32_t p = atomicAdd(&hist[id / rb.rows_per_block], 1u);
     rb.part_idx[(size_t)q * rb.stride + p] = id;
     rb.part_pos[(size_t)q * rb.stride + p] = t;
   }
 }
-
-// Every row is active: the groups are the row blocks themselves.
-__device__ __forceinline__ void identity_rows(const RowBlocking& rb, int q, int n) {
-  for (int i = threadIdx.x; i < n; i += blockDim.x) {
-    rb.part_idx[(size_t)q * rb.stride + i] = i;
-    rb.part_pos[(size_t)q * rb.stride + i] = i;
-  }
-  for (int b = threadIdx.x; b <= rb.nblk; b += blockDim.x)
-    rb.blk_off[(size_t)q * (rb.nblk + 1) + b] = min(b * rb.rows_per_block, n);
-}
-
 
 template <int NT>
 __global__ __launch_bounds__(NT) void select_block_kernel(
@@ -104,14 +107,14 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += NT) out[i] = i;
-    if (rb.part_idx) identity_rows(rb, q, n);
+    if (rb.part_idx) partition_rows(out, n, rb, q, z, sh.prio);
     return;
   }
   for (int i = tid; i < n; i += NT) sh.prio[i] = 0xFFFFFFFFu;
   __syncthreads();
   select_block<NT>(z, K, L, n, m, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr, out);
 
-  if (rb.part_idx) partition_rows(out, m, rb, q, sh.prio);
+  if (rb.part_idx) partition_rows(out, m, rb, q, z, sh.prio);
 }
 
 __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
@@ -147,7 +150,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += SEL_NT) out[i] = i;
-    if (rb.part_idx) identity_rows(rb, q, n);
+    if (rb.part_idx) partition_rows(out, n, rb, q, z, sh.tval);
     return;
   }
   for (int i = tid; i < words; i += SEL_NT) sh.taken[i] = 0u;
@@ -155,7 +158,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   __syncthreads();
   select_block_wide<SEL_NT>(z, K, L, n, m, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr,
                             out);
-  if (rb.part_idx) partition_rows(out, m, rb, q, sh.tval);
+  if (rb.part_idx) partition_rows(out, m, rb, q, z, sh.tval);
 }
 
 __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t* __restrict__ cnt,

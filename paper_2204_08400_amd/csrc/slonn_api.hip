@@ -259,6 +259,15 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
       set_error("uploading FreeHash rows failed: %s", hipGetErrorString(e));
       return fail(SLONN_EHIP);
     }
+    // node -> hash row (K*L <= 1024 fits 16 bits): lets the forward pass take a selected hash
+    // node's output from its projection instead of fetching the row again
+    std::vector<int16_t> hslot((size_t)L.d_out, (int16_t)-1);
+    for (int h = 0; h < H; ++h) hslot[L.hash_nodes[h]] = (int16_t)h;
+    if ((e = hipMalloc(&L.hslot, hslot.size() * 2)) != hipSuccess ||
+        (e = hipMemcpy(L.hslot, hslot.data(), hslot.size() * 2, hipMemcpyHostToDevice)) != hipSuccess) {
+      set_error("uploading the hash-node map failed: %s", hipGetErrorString(e));
+      return fail(SLONN_EHIP);
+    }
   }
   *out = m;
   return SLONN_OK;
@@ -314,6 +323,7 @@ int slonn_model_destroy(slonn_model* m) {
   for (Layer& L : m->layers) {
     if (L.Wh) (void)hipFree(L.Wh);
     if (L.bh) (void)hipFree(L.bh);
+    if (L.hslot) (void)hipFree(L.hslot);
   }
   delete m;
   return SLONN_OK;
@@ -529,7 +539,7 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
     for (int l = 0; l < nl; ++l) {
       const Layer& L = m->layers[l];
       FusedLayer& f = a.layer[l];
-      f.W = L.W; f.bias = L.bias; f.Wh = L.Wh; f.bh = L.bh;
+      f.W = L.W; f.bias = L.bias; f.Wh = L.Wh; f.bh = L.bh; f.hslot = L.hslot;
       f.d_in = L.d_in; f.d_out = L.d_out; f.act = L.act; f.w_dtype = L.w_dtype; f.K = L.K; f.L = L.L;
       if (L.activated()) {
         const TableSet* ts = t->for_layer(l);
@@ -605,6 +615,11 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
         rb.nblk = (L.d_out + rpb - 1) / rpb;
         rb.stride = w.max_na;
         rb.part_idx = w.part_idx; rb.part_pos = w.part_pos; rb.blk_off = w.blk_off;
+        // selected hash nodes take their output from z (the hash is "free", Section 3.4)
+        rb.hslot = L.hslot;
+        rb.y = out; rb.ldy = ldo;
+        rb.yc = is_last ? Y->val : nullptr; rb.ldc = Y->stride;
+        rb.relu = act == SLONN_ACT_RELU;
       }
       rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank,
                          keep + (size_t)l * keep_lstride, keep_qstride, B, codes, aidx, acnt, astride, out,
@@ -620,7 +635,7 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
         if (tiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {
           int32_t* flags = nullptr;
           rc = launch_gather_grouped(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B,
-                                     L.d_in, L.d_out, act, w.grouped, m->max_lds_bytes, &flags, s);
+                                     L.d_in, L.d_out, act, rb.hslot, w.grouped, m->max_lds_bytes, &flags, s);
           if (rc) return rc;
           gflag = flags;
         }

@@ -39,6 +39,7 @@ struct Layer {
   // library-owned device copies of the FreeHash rows (always fp32) and their biases
   float* Wh = nullptr;           // [H][d_in]
   float* bh = nullptr;           // [H]
+  int16_t* hslot = nullptr;      // [d_out] device: index of the node among the hash rows, or -1
   int H() const { return K * L; }
   bool activated() const { return K > 0 && L > 0; }
 };
@@ -90,6 +91,7 @@ struct FusedLayer {
   const float* bias;
   const float* Wh;
   const float* bh;
+  const int16_t* hslot;
   const uint32_t* dir;
   const int32_t* ids;
   const int32_t* global_rank;
@@ -119,6 +121,13 @@ struct RowBlocking {
   int32_t* part_idx = nullptr;   // [B][stride]  node ids, grouped by row block
   int32_t* part_pos = nullptr;   // [B][stride]  position of each id in the selection order
   int32_t* blk_off = nullptr;    // [B][nblk+1]  start of each row block's group
+  // A selected node that is also a hash node already has its pre-activation among the
+  // projections (Section 3.4): the regrouping step writes its output from there and leaves
+  // it out of the groups, so its row is not fetched a second time.  hslot == nullptr: off.
+  const int16_t* hslot = nullptr; // [n] index among the hash rows or -1
+  float* y = nullptr;             // [B][ldy] dense outputs (nullable)
+  float* yc = nullptr;            // [B][ldc] outputs in selection order (nullable)
+  int ldy = 0, ldc = 0, relu = 0;
 };
 constexpr int MAX_ROW_BLOCKS = 1024;
 
@@ -147,13 +156,15 @@ int launch_gather_blocked(const void* W, int w_dtype, const float* bias, const f
 // Groups of 16 queries: the union of their active rows evaluated as dense tiles on the matrix
 // cores, selected (query, node) pairs written to Y.  A group whose union is too large
 // relative to its lists is flagged 0 in *gflag_out (device array, [ceil(B/16)]) and left
-// untouched.  scratch: grouped_workspace_bytes(B, n) bytes of device memory.
+// untouched.  skip_hslot (nullable): nodes with an entry >= 0 there are left out of the unions
+// (their outputs come from the hash projections).  scratch: grouped_workspace_bytes(B, n)
+// bytes of device memory.
 size_t grouped_workspace_bytes(int B, int n);
 bool grouped_supported(int n, int max_lds);
 int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                           const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy,
-                          int B, int d, int n, int act, void* scratch, int max_lds, int32_t** gflag_out,
-                          hipStream_t s);
+                          int B, int d, int n, int act, const int16_t* skip_hslot, void* scratch, int max_lds,
+                          int32_t** gflag_out, hipStream_t s);
 
 // y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).
 // yc (nullable) receives the values in list order.
