@@ -335,6 +335,60 @@ int so_select(const void* h, const uint32_t* keys, const float* keep, int64_t ke
   return 0;
 }
 
+// Selection when the hash nodes are always computed (Section 3.4: their pre-activations are
+// forward-pass values that exist as soon as the keys do, so they cost nothing more; the text
+// the authors left commented out there adds that the Node Activator therefore never selects
+// them).  Reading taken: the active set is the H = K*L hash nodes, in sampled order, followed
+// by the first max(m - H, 0) OTHER nodes in the merge order of so_select (a hash node met in
+// a list or in the whole-set ranking is passed over); so |active| = max(m, H).  m == n still
+// means every node in ascending id order.
+int so_select_hash_first(const void* h, const uint32_t* keys, const float* keep, int64_t keep_stride,
+                         int64_t N, const int32_t* hash_nodes, int32_t* active, int32_t* cnt,
+                         int64_t stride) {
+  const Tables* t = static_cast<const Tables*>(h);
+  const int n = t->n, L = t->L, H = t->K * t->L;
+  std::vector<uint8_t> chosen(n);
+  for (int64_t q = 0; q < N; ++q) {
+    const int32_t m = so_budget(keep[q * keep_stride], n);
+    const int32_t total = std::max<int32_t>(m, H);
+    if (total > stride) return -1;
+    int32_t* out = active + q * stride;
+    if (m == n) {
+      for (int j = 0; j < n; ++j) out[j] = j;
+      cnt[q] = n;
+      continue;
+    }
+    std::fill(chosen.begin(), chosen.end(), 0);
+    int32_t c = 0;
+    for (int i = 0; i < H; ++i) {
+      chosen[hash_nodes[i]] = 1;
+      out[c++] = hash_nodes[i];
+    }
+    // rank r = 0, 1, ...; within a rank tables 0 .. L-1
+    bool any = true;
+    for (size_t r = 0; any && c < total; ++r) {
+      any = false;
+      for (int b = 0; b < L && c < total; ++b) {
+        auto it = t->rank[b].find(keys[q * L + b]);
+        if (it == t->rank[b].end() || r >= it->second.size()) continue;
+        any = true;
+        const int32_t node = it->second[r];
+        if (chosen[node]) continue;
+        chosen[node] = 1;
+        out[c++] = node;
+      }
+    }
+    for (int i = 0; i < n && c < total; ++i) {
+      const int32_t node = t->global_rank[i];
+      if (chosen[node]) continue;
+      chosen[node] = 1;
+      out[c++] = node;
+    }
+    cnt[q] = c;
+  }
+  return 0;
+}
+
 // Sparse layer: y_j = act(w_j.x + b_j) for the active nodes, exactly +0 for the rest.
 // pre (nullable) receives the active nodes' pre-activations (0 elsewhere).  A softmax
 // layer normalises over the active nodes only.

@@ -158,15 +158,23 @@ class Tables:
         lib().so_tables_global(self.h, _p(r), _p(s))
         return r, s
 
-    def select(self, keys, keep, stride=None):
+    def select(self, keys, keep, stride=None, hash_first=None):
+        """hash_first: the layer's hash node ids when they are always computed and never
+        selected (active = hash nodes, then the others in merge order); None = plain."""
         keys = np.ascontiguousarray(keys, np.uint32)
         keep = _f32(keep).reshape(-1)
         N = keys.shape[0]
         stride = self.n if stride is None else stride
         active = np.full((N, stride), -1, np.int32)
         cnt = np.zeros(N, np.int32)
-        rc = lib().so_select(self.h, _p(keys), _p(keep), C.c_int64(1 if keep.size > 1 else 0),
-                             C.c_int64(N), _p(active), _p(cnt), C.c_int64(stride))
+        if hash_first is not None:
+            hn = np.ascontiguousarray(hash_first, np.int32)
+            assert hn.size == self.K * self.L
+            rc = lib().so_select_hash_first(self.h, _p(keys), _p(keep), C.c_int64(1 if keep.size > 1 else 0),
+                                            C.c_int64(N), _p(hn), _p(active), _p(cnt), C.c_int64(stride))
+        else:
+            rc = lib().so_select(self.h, _p(keys), _p(keep), C.c_int64(1 if keep.size > 1 else 0),
+                                 C.c_int64(N), _p(active), _p(cnt), C.c_int64(stride))
         if rc != 0:
             raise ValueError("budget exceeds the active-list stride")
         return active, cnt
@@ -217,8 +225,10 @@ class OracleNet:
     """The network loop: per layer, hash -> keys -> select -> sparse layer."""
 
     def __init__(self, layers: Sequence, threads: Optional[int] = None,
-                 first_layer_rows_are_inputs: bool = False):
+                 first_layer_rows_are_inputs: bool = False, hash_nodes_always_active: bool = False):
         self.layers = list(layers)
+        # Section 3.4 variant: hash nodes are always computed and never selected
+        self.hash_first = hash_nodes_always_active
         self.threads = default_threads() if threads is None else threads
         self.tables: List[Optional[Tables]] = [None] * len(self.layers)
         self.rows_are_inputs0 = first_layer_rows_are_inputs
@@ -277,7 +287,8 @@ class OracleNet:
             if layer.K > 0 and layer.L > 0:
                 Z = hash_project(layer, cur, self.threads)
                 keys, tie = keys_from_z(Z, layer.K, layer.L)
-                active, cnt = self.tables[l].select(keys, k_l)
+                active, cnt = self.tables[l].select(
+                    keys, k_l, hash_first=layer.hash_nodes if self.hash_first else None)
                 out = sparse_layer(layer, cur, active, cnt, self.threads)
                 if taps:
                     tap = {"z": Z, "codes": keys, "tie": tie, "active": active, "cnt": cnt}

@@ -496,3 +496,32 @@ def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype):
         prof = slonn.slonn_profile_end()
         assert prof["gather"][1] == 3, prof     # grouped + per-query pass on layer 0, output layer
         _say(f"  {compare_sparse(got, ref, layers, 'grouped')}")
+
+
+@pytest.mark.parametrize("path", ["layers", "fused"])
+def test_selected_hash_nodes_reuse_their_projection(rt, oracle, path):
+    """Section 3.4: a hash projection is the node's own pre-activation.  Where a hash node is
+    selected, the whole-network kernel and the row-block path take its output from the
+    projection (bit for bit act(z_h)) instead of fetching the row again; the oracle computes
+    every active node from its row, and both must agree to the usual tolerance."""
+    dims = (640, 1536, 40)           # 1536 x 640 fp32 = 3.75 MiB with 2560-byte rows: row-block path
+    layers, net, _ = make_case(oracle, dims, 5, 8, seed=71, hashed=[0], cap=800, N_build=160, kind="u01")
+    g = _gpu_net(rt, layers, net, path=path)
+    B = 48
+    X = make_queries(dims, B, seed=72, kind="u01")
+    hn = layers[0].hash_nodes
+    for keep in (0.2, 1.0):
+        _say(f"hash reuse path={path} keep={keep}")
+        ref = net.sparse_forward(X, keep)
+        got = to_numpy_result(g.sparse_forward(X, keep, taps=True))
+        _say(f"  {compare_sparse(got, ref, layers, 'reuse ' + path)}")
+        z = got["taps"]["z"][0]
+        out = got["taps"]["out"][0]
+        reused = 0
+        for q in range(B):
+            act = set(got["taps"]["active"][0][q, :got["taps"]["cnt"][0][q]].tolist())
+            for h, node in enumerate(hn):
+                if int(node) in act:
+                    assert out[q, node] == max(z[q, h], np.float32(0)), (q, h, node)
+                    reused += 1
+        assert reused > 0

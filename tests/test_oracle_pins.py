@@ -398,3 +398,110 @@ def test_planted_mistakes_are_caught(oracle, gold, gold_net):
     # table-major instead of rank-major merge would give 0,3,2,1 for the first query
     active, _ = gold_net.tables[0].select(np.asarray([[3, 2]], np.uint32), _keep_for(4, 6))
     assert active[0, :4].tolist() == [0, 3, 2, 5] != [0, 3, 2, 1]
+
+
+# --------------------------------------------------------------------------- #
+# Section 3.4 variant: hash nodes always computed, never selected
+# --------------------------------------------------------------------------- #
+def test_gold_queries_hash_nodes_always_active(oracle, gold, gold_net):
+    n, H = gold["n"], len(gold["hash_nodes"])
+    net = oracle.OracleNet(gold_net.layers, threads=1, hash_nodes_always_active=True)
+    net.tables = gold_net.tables
+    for q in gold["queries"]:
+        x = np.asarray([q["x"]], np.float32)
+        for m in range(1, n):
+            res = net.sparse_forward(x, _keep_for(m, n))
+            tap = res["layers"][0]
+            want = q["order_hash_first"][:max(m, H)]
+            assert tap["cnt"][0] == len(want)
+            assert tap["active"][0, :len(want)].tolist() == want
+            assert tap["codes"][0].tolist() == q["keys"]
+            if str(m) in q["outputs_hash_first"]:
+                assert res["out"][0].tolist() == q["outputs_hash_first"][str(m)]
+        res = net.sparse_forward(x, 1.0)
+        assert res["layers"][0]["active"][0].tolist() == list(range(n))
+        assert res["out"][0].tolist() == np.maximum(np.asarray(q["z_all"], np.float32), 0).tolist()
+
+
+def _brute_order(t, keys_row):
+    """All n nodes by slot priority (min over a node's slots of r*L+b; the whole-set
+    ranking's slots come after every table slot)."""
+    n, L = t.n, t.L
+    lists = [t.bucket(b, keys_row[b]).tolist() for b in range(L)]
+    prio = {}
+    for b, lst in enumerate(lists):
+        for r, node in enumerate(lst):
+            p = r * L + b
+            prio[node] = min(prio.get(node, p), p)
+    base = (max([len(x) for x in lists] + [0])) * L
+    gr, _ = t.global_rank()
+    for i, node in enumerate(gr.tolist()):
+        prio.setdefault(node, base + i)
+    return sorted(range(n), key=lambda j: prio[j])
+
+
+def test_hash_first_matches_bruteforce(oracle):
+    """The variant by an independent definition: the hash nodes, then the non-hash nodes with
+    the smallest slot priorities (a hash node keeps its slot, it is only passed over).  With a
+    single table this equals plain selection on a table whose lists had the hash nodes struck
+    out, which is checked through tables rebuilt from such lists."""
+    rng = np.random.default_rng(5)
+    for n, K, L, cap in [(16, 2, 4, 16), (14, 3, 3, 14), (12, 1, 2, 12), (20, 2, 3, 20), (16, 3, 1, 16)]:
+        net, _ = _small_net(oracle, (10, n, 4), K=K, L=L, seed=int(rng.integers(1 << 20)), hashed=[0],
+                            cap=cap, N_build=40)
+        t = net.tables[0]
+        hn = np.asarray(net.layers[0].hash_nodes, np.int32)
+        H = hn.size
+        hset = set(hn.tolist())
+        nb = 1 << K
+        t_f = None
+        if L == 1:
+            dir_ = np.zeros((1, nb + 1), np.uint32)
+            ids = []
+            for key in range(nb):
+                dir_[0, key] = len(ids)
+                ids += [j for j in t.bucket(0, key).tolist() if j not in hset]
+            dir_[0, nb] = len(ids)
+            gr, _ = t.global_rank()
+            gr_f = [j for j in gr.tolist() if j not in hset] + sorted(hset)
+            t_f = oracle.Tables.from_lists(n, K, 1, cap, dir_, np.asarray(ids, np.int32),
+                                           np.asarray(gr_f, np.int32))
+        for keys_row in itertools.islice(itertools.product(range(nb), repeat=L), 48):
+            kr = np.asarray([keys_row], np.uint32)
+            others = [j for j in _brute_order(t, keys_row) if j not in hset]
+            for m in range(1, n + 1):
+                active, cnt = t.select(kr, _keep_for(m, n), hash_first=hn)
+                got = active[0, :cnt[0]].tolist()
+                if m == n:
+                    assert got == list(range(n))
+                    continue
+                assert cnt[0] == max(m, H)
+                assert got[:H] == hn.tolist()
+                assert len(set(got)) == len(got)
+                rest = got[H:]
+                assert rest == others[:max(m - H, 0)]
+                if t_f is not None and m > H:
+                    assert rest == _brute_order(t_f, keys_row)[:m - H]
+
+
+def test_hash_first_forward_outputs(oracle):
+    """Outputs of the variant: hash nodes carry act(z_h) (their projections), the selected
+    others their own pre-activations, everything else +0; budget >= n gives the full layer."""
+    net, _ = _small_net(oracle, (24, 48, 6), K=3, L=4, seed=77, hashed=[0])
+    v = oracle.OracleNet(net.layers, threads=1, hash_nodes_always_active=True)
+    v.tables = net.tables
+    X = wl.inputs_uniform_half_zero(9, 24, 78)
+    lay = net.layers[0]
+    hn = np.asarray(lay.hash_nodes)
+    full = oracle.dense_layer(lay, X)
+    for keep in (0.1, 0.5, 1.0):
+        res = v.sparse_forward(X, keep)
+        tap = res["layers"][0]
+        for q in range(9):
+            act = tap["active"][q, :tap["cnt"][q]]
+            mask = np.zeros(48, bool)
+            mask[act] = True
+            assert mask[hn].all()
+            assert np.array_equal(tap["out"][q, mask], full[q, mask])
+            assert not tap["out"][q, ~mask].any()
+            assert np.array_equal(tap["out"][q, hn], np.maximum(tap["z"][q], 0))
