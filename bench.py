@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--path", default="auto", choices=["auto", "layers", "fused"])
+    ap.add_argument("--hash-nodes-always-active", action="store_true",
+                    help="Section 3.4 variant: hash nodes always computed, never selected (default off)")
     ap.add_argument("--build-inputs", type=int, default=0, help="size of the table-training set (default: the config's)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, for scaling rocprofv3 byte counters")
@@ -86,6 +88,7 @@ def main():
     t0 = time.time()
     net.build_tables(xb)
     net.set_path(args.path)
+    net.set_hash_nodes_always_active(args.hash_nodes_always_active)
     log(f"built tables on the device in {time.time() - t0:.2f}s")
 
     xq = to_dev(X_query)
@@ -238,7 +241,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import slonn_oracle
-        onet = slonn_oracle.OracleNet(layers, first_layer_rows_are_inputs=ell)
+        onet = slonn_oracle.OracleNet(layers, first_layer_rows_are_inputs=ell,
+                                      hash_nodes_always_active=args.hash_nodes_always_active)
         onet.import_tables(net.export_tables())
         n_s = min(nq, 4096)
         Xs = tuple(a[:n_s] for a in X_query) if ell else X_query[:n_s]
@@ -258,7 +262,8 @@ def main():
         "config": {"workload": f"{args.config}: MLP {'-'.join(map(str, cfg.dims))}, K={cfg.K} L={cfg.L} on "
                                f"{len(cfg.hashed_layers)} hidden layers, {nq} queries", "batch": B,
                    "keep": args.keep if mixed is None else f"per query U[{cfg.keep_range[0]}, {cfg.keep_range[1]}]",
-                   "queries_per_step": B, "path": args.path},
+                   "queries_per_step": B, "path": args.path,
+                   "hash_nodes_always_active": bool(args.hash_nodes_always_active)},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     line.update(extra)

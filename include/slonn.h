@@ -143,6 +143,18 @@ int slonn_model_destroy(slonn_model* m);
 enum { SLONN_PATH_AUTO = 0, SLONN_PATH_LAYERS = 1, SLONN_PATH_FUSED = 2 };
 int slonn_model_set_path(slonn_model* m, int path);
 
+/* Variant of Section 3.4 ("the hash is free"): the K*L FreeHash projections of a layer are
+ * the pre-activations of K*L of its own nodes, so those nodes can always be computed at no
+ * further cost, and the Node Activator then need not select them.  on != 0: for every
+ * activated layer and every query whose budget m is below the layer's n nodes, the active
+ * list is the K*L hash nodes in the order given at model creation, followed by the first
+ * max(m - K*L, 0) other nodes in the usual merge order (a hash node met in a ranked list or
+ * in the fallback ranking is passed over); active_cnt = max(m, K*L); the outputs of the hash
+ * nodes are act(projection).  m == n is unchanged (all nodes, ascending).  The same tables
+ * serve both settings.  on == 0 (default): the active set is exactly the m selected nodes.
+ * Applies to slonn_select and slonn_sparse_forward on every path.  EINVAL: null model.    */
+int slonn_model_set_hash_nodes_always_active(slonn_model* m, int on);
+
 /* Alg. 1 for every activated layer, on the device.  X_build holds N training inputs
  * (device).  Input_l is the full network's output of layer l-1 on X_build; the
  * Activation summed into NodeScore is layer l's own output; each bucket keeps its

@@ -273,14 +273,30 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
       for (int i = tid; i < n; i += NT) { xn[i] = 0.0f; prio[i] = 0xFFFFFFFFu; hmap[i] = Ly.hslot[i]; }
       __syncthreads();
 
-      if (wave == 0 && lane == 0 && Ly.tap_cnt) Ly.tap_cnt[q] = m;
+      // Section 3.4 variant: the H hash nodes head the active list and are never selected
+      const int Hf = (a.hash_first && m < n) ? H : 0;
+      const int msel = m > Hf ? m - Hf : 0;
+      if (wave == 0 && lane == 0 && Ly.tap_cnt) Ly.tap_cnt[q] = Hf + msel;
       if (m < n) {
-        // ---- keys, bucket lookup, merge: first m distinct nodes in slot order ----
-        select_block<NT>(zs, Ly.K, Ly.L, n, m, Ly.dir, Ly.ids, Ly.global_rank, sh,
-                         Ly.tap_codes ? Ly.tap_codes + (size_t)q * Ly.L : nullptr, alist);
+        // ---- keys, bucket lookup, merge: first msel distinct nodes in slot order ----
+        select_block<NT>(zs, Ly.K, Ly.L, n, msel, Ly.dir, Ly.ids, Ly.global_rank, sh,
+                         Ly.tap_codes ? Ly.tap_codes + (size_t)q * Ly.L : nullptr, alist, Hf ? hmap : nullptr);
         list = alist;
-        if (Ly.tap_idx)
-          for (int i = tid; i < m; i += NT) Ly.tap_idx[(size_t)q * n + i] = alist[i];
+        if (Ly.tap_idx) {
+          for (int i = tid; i < Hf; i += NT) Ly.tap_idx[(size_t)q * n + i] = Ly.hnodes[i];
+          for (int i = tid; i < msel; i += NT) Ly.tap_idx[(size_t)q * n + Hf + i] = alist[i];
+        }
+        if (Hf) {
+          // every hash node's output comes from its projection; the list holds none of them
+          for (int i = tid; i < n; i += NT) {
+            const int hs = hmap[i];
+            if (hs >= 0) {
+              const float z = zs[hs];
+              xn[i] = (Ly.act == SLONN_ACT_RELU && !(z > 0.0f)) ? 0.0f : z;
+            }
+          }
+        }
+        m = msel;
       } else {
         if (Ly.tap_codes && tid < Ly.L) {
           uint32_t key = 0;
@@ -295,7 +311,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
       //      are compacted in place (a round writes below what the next round reads) ----
       const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
       int kept = 0;
-      for (int base = 0; base < m; base += NT) {
+      for (int base = 0; base < (Hf ? 0 : m); base += NT) {
         const int i = base + tid;
         const int node = i < m ? (list ? alist[i] : i) : -1;
         const int hs = node >= 0 ? (int)hmap[node] : -1;
@@ -318,8 +334,7 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
         kept += total;
         __syncthreads();
       }
-      list = alist;
-      m = kept;
+      if (!Hf) { list = alist; m = kept; }
     }
 
     // ---- evaluate the active rows into the next layer's input ----

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
     const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
-    float* __restrict__ yzero, int ldy, RowBlocking rb) {
+    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf) {
   extern __shared__ __align__(16) uint32_t smem32[];
   SelectShared<NT> sh;
   sh.prio = smem32;
@@ -99,7 +99,9 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
     float* y = yzero + (size_t)q * ldy;
     for (int i = tid; i < n; i += NT) y[i] = 0.0f;
   }
-  if (tid == 0) cnt[q] = m;
+  const int H = hf.hnodes ? K * L : 0;          // hash nodes in front of the list (Section 3.4 variant)
+  const int total = (m == n || m > H) ? m : H;
+  if (tid == 0) cnt[q] = total;
   if (m == n) {   // the layer is computed in full: ascending ids, no table access
     if (codes && tid < L) {
       uint32_t key = 0;
@@ -111,10 +113,12 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
     return;
   }
   for (int i = tid; i < n; i += NT) sh.prio[i] = 0xFFFFFFFFu;
+  for (int h = tid; h < H; h += NT) out[h] = hf.hnodes[h];
   __syncthreads();
-  select_block<NT>(z, K, L, n, m, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr, out);
+  select_block<NT>(z, K, L, n, total - H, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr,
+                   out + H, H ? hf.hslot : nullptr);
 
-  if (rb.part_idx) partition_rows(out, m, rb, q, z, sh.prio);
+  if (rb.part_idx) partition_rows(out, total, rb, q, z, sh.prio);
 }
 
 __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
@@ -122,7 +126,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
     const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
-    float* __restrict__ yzero, int ldy, RowBlocking rb) {
+    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf) {
   extern __shared__ __align__(16) uint32_t smem32[];
   const int words = (n + 31) >> 5;
   SelectSharedWide<SEL_NT> sh;
@@ -142,7 +146,9 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
     float* y = yzero + (size_t)q * ldy;
     for (int i = tid; i < n; i += SEL_NT) y[i] = 0.0f;
   }
-  if (tid == 0) cnt[q] = m;
+  const int H = hf.hnodes ? K * L : 0;
+  const int total = (m == n || m > H) ? m : H;
+  if (tid == 0) cnt[q] = total;
   if (m == n) {
     if (codes && tid < L) {
       uint32_t key = 0;
@@ -155,10 +161,11 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   }
   for (int i = tid; i < words; i += SEL_NT) sh.taken[i] = 0u;
   for (int i = tid; i < SELECT_WIDE_TABLE; i += SEL_NT) { sh.tkey[i] = -1; sh.tval[i] = 0xFFFFFFFFu; }
+  for (int h = tid; h < H; h += SEL_NT) out[h] = hf.hnodes[h];
   __syncthreads();
-  select_block_wide<SEL_NT>(z, K, L, n, m, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr,
-                            out);
-  if (rb.part_idx) partition_rows(out, m, rb, q, z, sh.tval);
+  select_block_wide<SEL_NT>(z, K, L, n, total - H, dir, ids, global_rank, sh,
+                            codes ? codes + (size_t)q * L : nullptr, out + H, H ? hf.hslot : nullptr);
+  if (rb.part_idx) partition_rows(out, total, rb, q, z, sh.tval);
 }
 
 __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t* __restrict__ cnt,
@@ -175,8 +182,9 @@ __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t*
 int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
-                  int ldy, int max_lds, const RowBlocking* rb, hipStream_t s) {
+                  int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_SELECT, s);
+  const HashFirst hf = hash_first ? *hash_first : HashFirst{};
   const size_t lds_block = ((size_t)n + SelectShared<SEL_NT_BIG>::words_besides_prio) * 4;
   if (lds_block <= (size_t)max_lds) {
     const RowBlocking rbv = rb ? *rb : RowBlocking{};
@@ -185,13 +193,13 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
       hipLaunchKernelGGL((select_block_kernel<SEL_NT_BIG>), dim3(B), dim3(SEL_NT_BIG), lds_block, s, Z, K, L, n,
-                         dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv);
+                         dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf);
     } else {
       if (lds_block > 65536)
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
       hipLaunchKernelGGL((select_block_kernel<SEL_NT>), dim3(B), dim3(SEL_NT), lds_block, s, Z, K, L, n, dir,
-                         ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv);
+                         ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf);
     }
     SLONN_HIP(hipGetLastError());
     return SLONN_OK;
@@ -204,7 +212,7 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_wide_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(select_wide_kernel, dim3(B), dim3(SEL_NT), lds, s, Z, K, L, n, dir, ids, global_rank,
-                     keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rb ? *rb : RowBlocking{});
+                     keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rb ? *rb : RowBlocking{}, hf);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

@@ -28,14 +28,17 @@ struct SelectShared {            // LDS regions the caller carves out
 
 // z: the query's K*L hash projections (LDS or global).  prio[0..n) must hold 0xFFFFFFFF
 // and be visible to all threads (caller clears it and synchronises).  On return (all
-// threads, after a barrier) out[0..m) holds the chosen ids in selection order.  m < n.
+// threads, after a barrier) out[0..m) holds the chosen ids in selection order.  0 <= m < n.
+// hskip (nullable, LDS or global, [n]): nodes with an entry >= 0 are passed over wherever
+// they turn up (the variant of Section 3.4 in which hash nodes are computed anyway and the
+// Node Activator never selects them); the caller keeps m <= n minus their number.
 template <int NT>
 __device__ __forceinline__ void select_block(const float* z, int K, int L_, int n, int m,
                                              const uint32_t* __restrict__ dir,
                                              const int32_t* __restrict__ ids,
                                              const int32_t* __restrict__ global_rank,
                                              const SelectShared<NT>& sh, uint32_t* codes_row,
-                                             int32_t* out) {
+                                             int32_t* out, const int16_t* hskip = nullptr) {
   constexpr int NW = NT / 64;
   constexpr int MU = SELECT_MU;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -82,6 +85,11 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
       valid[u] = u < per && slot[u] < nslots && r < sh.s_len[b];
       node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
     }
+    if (hskip) {
+#pragma unroll
+      for (int u = 0; u < MU; ++u)
+        if (valid[u] && hskip[node[u]] >= 0) valid[u] = false;
+    }
 #pragma unroll
     for (int u = 0; u < MU; ++u)
       if (valid[u]) atomicMin(&sh.prio[node[u]], slot[u]);
@@ -119,7 +127,7 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
     bool first = false;
     if (i < n) {
       node = global_rank[i];
-      first = sh.prio[node] == 0xFFFFFFFFu;
+      first = sh.prio[node] == 0xFFFFFFFFu && !(hskip && hskip[node] >= 0);
     }
     const unsigned long long votes = __ballot(first);
     if (lane == 0) sh.wave_cnt[wave] = __popcll(votes);
@@ -165,7 +173,7 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
                                                   const int32_t* __restrict__ ids,
                                                   const int32_t* __restrict__ global_rank,
                                                   const SelectSharedWide<NT>& sh, uint32_t* codes_row,
-                                                  int32_t* out) {
+                                                  int32_t* out, const int16_t* hskip = nullptr) {
   static_assert(SELECT_MU * NT * 2 <= SELECT_WIDE_TABLE, "round table too small");
   constexpr int NW = NT / 64;
   constexpr int MU = SELECT_MU;
@@ -210,6 +218,11 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
       valid[u] = u < per && slot < nslots && r < sh.s_len[b];
       node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
       cell[u] = 0;
+    }
+    if (hskip) {
+#pragma unroll
+      for (int u = 0; u < MU; ++u)
+        if (valid[u] && hskip[node[u]] >= 0) valid[u] = false;
     }
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
@@ -262,7 +275,7 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
     bool first = false;
     if (i < n) {
       node = global_rank[i];
-      first = ((sh.taken[node >> 5] >> (node & 31)) & 1u) == 0;
+      first = ((sh.taken[node >> 5] >> (node & 31)) & 1u) == 0 && !(hskip && hskip[node] >= 0);
     }
     const unsigned long long votes = __ballot(first);
     if (lane == 0) sh.wave_cnt[wave] = __popcll(votes);

@@ -268,6 +268,11 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
       set_error("uploading the hash-node map failed: %s", hipGetErrorString(e));
       return fail(SLONN_EHIP);
     }
+    if ((e = hipMalloc(&L.hnodes, (size_t)H * 4)) != hipSuccess ||
+        (e = hipMemcpy(L.hnodes, L.hash_nodes.data(), (size_t)H * 4, hipMemcpyHostToDevice)) != hipSuccess) {
+      set_error("uploading the hash-node ids failed: %s", hipGetErrorString(e));
+      return fail(SLONN_EHIP);
+    }
   }
   *out = m;
   return SLONN_OK;
@@ -318,12 +323,19 @@ int slonn_model_set_path(slonn_model* m, int path) {
   return SLONN_OK;
 }
 
+int slonn_model_set_hash_nodes_always_active(slonn_model* m, int on) {
+  if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
+  m->hash_first = on != 0;
+  return SLONN_OK;
+}
+
 int slonn_model_destroy(slonn_model* m) {
   if (!m) return SLONN_OK;
   for (Layer& L : m->layers) {
     if (L.Wh) (void)hipFree(L.Wh);
     if (L.bh) (void)hipFree(L.bh);
     if (L.hslot) (void)hipFree(L.hslot);
+    if (L.hnodes) (void)hipFree(L.hnodes);
   }
   delete m;
   return SLONN_OK;
@@ -492,9 +504,11 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
   hipStream_t s = static_cast<hipStream_t>(stream);
   int rc = launch_hash_project(X_l, L.d_in, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
   if (rc) return rc;
+  HashFirst hf;
+  if (m->hash_first) { hf.hnodes = L.hnodes; hf.hslot = L.hslot; }
   return launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank, keep, keep_stride,
                        B, codes_out, active_idx, active_cnt, idx_stride, nullptr, 0, m->max_lds_bytes,
-                       nullptr, s);
+                       nullptr, m->hash_first ? &hf : nullptr, s);
 }
 
 int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
@@ -539,7 +553,7 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
     for (int l = 0; l < nl; ++l) {
       const Layer& L = m->layers[l];
       FusedLayer& f = a.layer[l];
-      f.W = L.W; f.bias = L.bias; f.Wh = L.Wh; f.bh = L.bh; f.hslot = L.hslot;
+      f.W = L.W; f.bias = L.bias; f.Wh = L.Wh; f.bh = L.bh; f.hslot = L.hslot; f.hnodes = L.hnodes;
       f.d_in = L.d_in; f.d_out = L.d_out; f.act = L.act; f.w_dtype = L.w_dtype; f.K = L.K; f.L = L.L;
       if (L.activated()) {
         const TableSet* ts = t->for_layer(l);
@@ -559,6 +573,7 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
     a.max_dim = (a.max_dim + 7) & ~7;
     a.X = X->x; a.ldx = m->layers[0].d_in;
     a.keep = keep; a.keep_qstride = keep_qstride; a.keep_lstride = keep_lstride;
+    a.hash_first = m->hash_first ? 1 : 0;
     a.Y = Y->dense; a.argmax = Y->argmax;
     return launch_fused_forward(a, B, m->max_lds_bytes, s);
   }
@@ -621,9 +636,11 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
         rb.yc = is_last ? Y->val : nullptr; rb.ldc = Y->stride;
         rb.relu = act == SLONN_ACT_RELU;
       }
+      HashFirst hf;
+      if (m->hash_first) { hf.hnodes = L.hnodes; hf.hslot = L.hslot; }
       rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank,
                          keep + (size_t)l * keep_lstride, keep_qstride, B, codes, aidx, acnt, astride, out,
-                         ldo, m->max_lds_bytes, rb.part_idx ? &rb : nullptr, s);
+                         ldo, m->max_lds_bytes, rb.part_idx ? &rb : nullptr, m->hash_first ? &hf : nullptr, s);
       if (rc) return rc;
       act_list = aidx; act_cnt = acnt; act_stride = astride;
       if (is_last && Y->val) yc = Y->val;

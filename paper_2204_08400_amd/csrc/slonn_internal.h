@@ -40,6 +40,7 @@ struct Layer {
   float* Wh = nullptr;           // [H][d_in]
   float* bh = nullptr;           // [H]
   int16_t* hslot = nullptr;      // [d_out] device: index of the node among the hash rows, or -1
+  int32_t* hnodes = nullptr;     // [H] device copy of hash_nodes
   int H() const { return K * L; }
   bool activated() const { return K > 0 && L > 0; }
 };
@@ -59,6 +60,7 @@ struct slonn_model {
   std::vector<slonn::Layer> layers;
   int path = SLONN_PATH_AUTO;
   bool path_grouped = true;       // allow the grouped (cross-query) evaluation on the per-layer path
+  bool hash_first = false;        // hash nodes always computed, never selected (Section 3.4 variant)
   int max_lds_bytes = 65536;      // per-workgroup LDS the device grants on request
   int n_cu = 256;
 };
@@ -92,6 +94,7 @@ struct FusedLayer {
   const float* Wh;
   const float* bh;
   const int16_t* hslot;
+  const int32_t* hnodes;
   const uint32_t* dir;
   const int32_t* ids;
   const int32_t* global_rank;
@@ -109,6 +112,7 @@ struct FusedArgs {
   float* Y;
   int32_t* argmax;
   int ldx, keep_qstride, keep_lstride, n_layers;
+  int hash_first;                  // hash nodes always computed, never selected
   int max_dim, max_H, max_na;      // LDS carve-up: activations, projections, active list
 };
 size_t fused_lds_bytes(const FusedArgs& a);
@@ -131,6 +135,14 @@ struct RowBlocking {
 };
 constexpr int MAX_ROW_BLOCKS = 1024;
 
+// Section 3.4 variant: the K*L hash nodes are always computed and the Node Activator never
+// selects them.  The active list then starts with the hash nodes in sampled order and
+// continues with the first max(m - K*L, 0) other nodes of the merge.  hnodes == nullptr: off.
+struct HashFirst {
+  const int32_t* hnodes = nullptr;   // [K*L] device
+  const int16_t* hslot = nullptr;    // [n] device: index among the hash rows or -1
+};
+
 // ---- kernel launchers (each validates nothing: callers have checked shapes) ----
 
 // Z[q][h] = Wh[h] . X[q] + bh[h], fp64 accumulation, rounded once to fp32.
@@ -141,7 +153,7 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
 int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
-                  int ldy, int max_lds, const RowBlocking* rb, hipStream_t s);
+                  int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first, hipStream_t s);
 // true when launch_select will fill rb for a layer of n nodes (the workgroup kernel is used)
 bool select_fills_row_blocks(int n, int max_lds);
 

@@ -43,6 +43,10 @@ class Network:
         """'auto' | 'layers' | 'fused' (raises if the model does not qualify)."""
         slonn.slonn_model_set_path(self.model, {"auto": 0, "layers": 1, "fused": 2}[path])
 
+    def set_hash_nodes_always_active(self, on: bool):
+        """Hash nodes always computed and never selected (see slonn.h)."""
+        slonn.slonn_model_set_hash_nodes_always_active(self.model, on)
+
     # -- helpers -------------------------------------------------------------- #
     def workspace(self, B: int):
         if self._ws is None or B > self._ws_B:

@@ -26,6 +26,7 @@ EXPORTS = [
     "slonn_tables_export", "slonn_tables_import", "slonn_tables_destroy", "slonn_workspace_bytes",
     "slonn_select", "slonn_sparse_forward", "slonn_dense_forward", "slonn_last_error",
     "slonn_profile_begin", "slonn_profile_end", "slonn_model_set_path",
+    "slonn_model_set_hash_nodes_always_active",
 ]
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused")
 PATH_AUTO, PATH_LAYERS, PATH_FUSED = 0, 1, 2
@@ -173,6 +174,10 @@ def slonn_model_create(layers: Sequence[dict]) -> Model:
 
 def slonn_model_set_path(model: Model, path: int):
     _check(load().slonn_model_set_path(model.h, int(path)))
+
+
+def slonn_model_set_hash_nodes_always_active(model: Model, on: bool):
+    _check(load().slonn_model_set_hash_nodes_always_active(model.h, 1 if on else 0))
 
 
 def slonn_build_tables(model: Model, X_build: Input, N: int, stream=None) -> Tables:

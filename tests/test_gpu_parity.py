@@ -525,3 +525,83 @@ def test_selected_hash_nodes_reuse_their_projection(rt, oracle, path):
                     assert out[q, node] == max(z[q, h], np.float32(0)), (q, h, node)
                     reused += 1
         assert reused > 0
+
+
+HASH_FIRST_CASES = [
+    # small layers (fused eligible), a row-block layer, a bf16 net, a wide activated output layer
+    dict(dims=(96, 1000, 640, 12), K=6, L=10, kind="u01", B=67, last_act=wl.ACT_SOFTMAX),
+    dict(dims=(640, 1536, 40), K=5, L=8, kind="u01", B=48, hashed=[0], cap=800),
+    dict(dims=(128, 768, 512, 10), K=4, L=16, kind="clip3", B=130, w_dtype=wl.W_BF16),
+]
+
+
+@pytest.mark.parametrize("path", ["layers", "fused"])
+@pytest.mark.parametrize("case", HASH_FIRST_CASES, ids=lambda c: "x".join(map(str, c["dims"])))
+def test_hash_nodes_always_active_matches_oracle(rt, oracle, case, path):
+    """Section 3.4 variant: hash nodes head every active list and are never selected;
+    budgets below K*L give exactly the hash nodes."""
+    dims = case["dims"]
+    layers, net, _ = make_case(oracle, dims, case["K"], case["L"], seed=81, hashed=case.get("hashed"),
+                               cap=case.get("cap"), N_build=200, kind=case["kind"],
+                               w_dtype=case.get("w_dtype", wl.W_F32), last_act=case.get("last_act", wl.ACT_NONE))
+    ref_net = oracle.OracleNet(layers, hash_nodes_always_active=True)
+    ref_net.tables = net.tables
+    g = _gpu_net(rt, layers, net, path=path)
+    g.set_hash_nodes_always_active(True)
+    B = case["B"]
+    X = make_queries(dims, B, seed=82, kind=case["kind"])
+    H = case["K"] * case["L"]
+    for keep in (0.01, 0.3, wl.keep_uniform(B, 0.0001, 1.0, 5), 1.0):
+        _say(f"hash-first {dims} path={path} keep={'mixed' if np.ndim(keep) else keep}")
+        ref = ref_net.sparse_forward(X, keep)
+        kt = _keep_tensor(keep) if np.ndim(keep) else keep
+        got = to_numpy_result(g.sparse_forward(X, kt, taps=True))
+        _say(f"  {compare_sparse(got, ref, layers, 'hash-first ' + path)}")
+        for l, lay in enumerate(layers):
+            if lay.K > 0:
+                c = got["taps"]["cnt"][l]
+                assert (c >= min(H, lay.d_out)).all()
+    # the stand-alone selection entry point follows the same setting
+    import torch
+    l0 = 0
+    ref = ref_net.sparse_forward(X, 0.3)["layers"][l0]
+    sel = g.select(l0, X, 0.3)
+    ok = ~ref["tie"]
+    cnt = sel["cnt"].cpu().numpy()
+    act = sel["active"].cpu().numpy()
+    assert np.array_equal(cnt[ok], ref["cnt"][ok])
+    for q in np.nonzero(ok)[0]:
+        assert np.array_equal(act[q, :cnt[q]], ref["active"][q, :cnt[q]])
+    g.set_hash_nodes_always_active(False)
+    plain = net.sparse_forward(X, 0.3)
+    got = to_numpy_result(g.sparse_forward(X, 0.3, taps=True))
+    compare_sparse(got, plain, layers, "back to plain " + path)
+
+
+def test_hash_nodes_always_active_wide_output_layer(rt, oracle):
+    """The variant on a wide activated softmax output layer (bitmap select kernel), compact output."""
+    d0, n_out = 4000, 50000
+    dims = (d0, 64, n_out)
+    layers, net, _ = make_case(oracle, dims, 6, 12, seed=91, hashed=[1], cap=600, N_build=96,
+                               last_act=wl.ACT_SOFTMAX, ell_nnz=30)
+    ref_net = oracle.OracleNet(layers, hash_nodes_always_active=True)
+    ref_net.tables = net.tables
+    import copy
+    glayers = [copy.copy(l) for l in layers]
+    glayers[0].W = np.ascontiguousarray(layers[0].W.T)      # the GPU stores the first layer input-major
+    g = rt.Network(glayers, first_layer_rows_are_inputs=True)
+    g.import_tables(net.export_tables())
+    g.set_hash_nodes_always_active(True)
+    X = make_queries(dims, 40, seed=92, ell_nnz=30)
+    for keep in (0.0005, 0.004):
+        _say(f"hash-first wide output keep={keep}")
+        ref = ref_net.sparse_forward(X, keep)
+        got = to_numpy_result(g.sparse_forward(X, keep, taps=True, compact=True))
+        _say(f"  {compare_sparse(got, ref, layers, 'hash-first wide')}")
+        ok = ~ref["layers"][1]["tie"]
+        for q in np.nonzero(ok)[0]:
+            c = ref["layers"][1]["cnt"][q]
+            assert got["cnt"][q] == c
+            assert np.array_equal(got["idx"][q, :c], ref["layers"][1]["active"][q, :c])
+            np.testing.assert_allclose(got["val"][q, :c], ref["out"][q, ref["layers"][1]["active"][q, :c]],
+                                       rtol=1e-4, atol=1e-6 * float(ref["out"][q].max()))

@@ -90,6 +90,8 @@ def test_null_handles_are_rejected(slonn):
     assert lib.slonn_sparse_forward(None, None, None, 1, None, 0, 0, None, None, None, C.c_size_t(0), None) == slonn.EINVAL
     assert lib.slonn_dense_forward(None, None, 1, None, None, None, None, C.c_size_t(0), None) == slonn.EINVAL
     assert lib.slonn_select(None, None, 0, None, 1, None, 0, None, None, None, None, 0, None, C.c_size_t(0), None) == slonn.EINVAL
+    assert lib.slonn_model_set_path(None, 0) == slonn.EINVAL
+    assert lib.slonn_model_set_hash_nodes_always_active(None, 1) == slonn.EINVAL
     assert lib.slonn_model_destroy(None) == 0 and lib.slonn_tables_destroy(None) == 0
     assert slonn.load().slonn_last_error()
 
