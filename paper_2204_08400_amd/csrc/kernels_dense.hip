@@ -222,6 +222,12 @@ __global__ __launch_bounds__(256) void dense_direct_kernel(const void* __restric
 
 }  // namespace
 
+bool dense_small_supported(const void* W, int w_dtype, const float* X, int ldx, int d) {
+  const int wmul = (w_dtype == SLONN_F32) ? 4 : 8;
+  return ldx % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0 && d % 4 == 0 && d % wmul == 0 &&
+         reinterpret_cast<uintptr_t>(W) % (w_dtype == SLONN_F32 ? 16 : 8) == 0;
+}
+
 int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                        float* Y, int ldy, int B, int d, int n, int act, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_DENSE, s);
@@ -232,9 +238,7 @@ int launch_dense_layer(const void* W, int w_dtype, const float* bias, const floa
   const long big_tiles = (long)((B + 127) / 128) * ((n + 127) / 128);
   const bool big = big_tiles >= 512;
   const long tiles64 = (long)((B + 63) / 64) * ((n + 63) / 64);
-  const int wmul = (w_dtype == SLONN_F32) ? 4 : 8;      // row start alignment of the weight loads
-  if (tiles64 < 256 && vecx && d % 4 == 0 && d % wmul == 0 &&
-      reinterpret_cast<uintptr_t>(W) % (w_dtype == SLONN_F32 ? 16 : 8) == 0) {
+  if (tiles64 < 256 && dense_small_supported(W, w_dtype, X, ldx, d)) {
     dim3 grid((n + 31) / 32, (B + 31) / 32);
     if (w_dtype == SLONN_F32)
       hipLaunchKernelGGL((dense_direct_kernel<SLONN_F32, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,

@@ -671,7 +671,8 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
                             ldo, B, L.d_in, L.d_out, act, s);
       if (rc) return rc;
-    } else if ((size_t)((B + 63) / 64) * ((L.d_out + 63) / 64) >= 256) {
+    } else if ((size_t)((B + 63) / 64) * ((L.d_out + 63) / 64) >= 256 ||
+               (B >= 32 && dense_small_supported(L.W, L.w_dtype, cur, ldcur, L.d_in))) {
       // a layer computed in full for a real batch is a dense contraction: matrix cores
       rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out, act, s);
       if (rc) return rc;

@@ -199,6 +199,10 @@ int launch_finalize(float* Y, int ldy, int n, const int32_t* active, const int32
 int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                        float* Y, int ldy, int B, int d, int n, int act, hipStream_t s);
 
+// true when a problem of fewer than 256 tiles of 64x64 can take the small-shape MFMA kernel
+// (operands straight from L2); otherwise such shapes are better served by the row gather.
+bool dense_small_supported(const void* W, int w_dtype, const float* X, int ldx, int d);
+
 int launch_fill_iota(int32_t* idx, int stride, int32_t* cnt, int n, int B, hipStream_t s);
 
 // Alg. 1 on the device for one layer; fills ts (host + device copies).
