@@ -22,6 +22,8 @@
 //   * a keep fraction becomes a node count by rounding to the nearest whole node,
 //     at least one node.
 //   * softmax / argmax run over the computed nodes only.
+//   * (variant) hash nodes always computed and never selected: so_select_hash_first.
+//   * confidence estimate with L tables: pooled mean over the L buckets (so_conf_estimate).
 //
 // Parity with the authors' own implementation is unpinned (no code or printed
 // vectors exist); the pins in tests/ check this file against the definitions.
@@ -439,6 +441,109 @@ int so_dense_layer_ell(const void* W, int w_dtype, int rows_are_inputs, const fl
     }
     if (act == ACT_SOFTMAX) softmax_over(all.data(), n, o);
   });
+  return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Choice of k per query (Section 2: ACLO and LCAO; Section 3.2: Confidence LSH tables and
+// latency profiles).  Mechanics only: the confidences c(k, x') of the training inputs and
+// the latency profile T(k, beta) are inputs.
+// ---------------------------------------------------------------------------
+
+// Confidence LSH tables: per table and bucket, the sum over the training inputs hashed
+// there of c(k_g, x') for every k_g of the grid, and how many inputs that is.
+struct ConfTables {
+  int K = 0, L = 0, G = 0;
+  int64_t N = 0;
+  std::vector<std::unordered_map<uint32_t, std::vector<double>>> sum;   // [b][key] -> G sums
+  std::vector<std::unordered_map<uint32_t, int64_t>> count;             // [b][key]
+  std::vector<double> total;                                             // G sums over all inputs
+};
+
+// Training: every input x' (in order) adds c(k_g, x') to its bucket in each table.
+void* so_conf_build(int K, int L, int G, const uint32_t* keys, const float* conf, int64_t N) {
+  ConfTables* t = new ConfTables;
+  t->K = K; t->L = L; t->G = G; t->N = N;
+  t->sum.resize(L); t->count.resize(L);
+  t->total.assign(G, 0.0);
+  for (int64_t x = 0; x < N; ++x) {
+    for (int b = 0; b < L; ++b) {
+      const uint32_t key = keys[x * L + b];
+      auto it = t->sum[b].find(key);
+      if (it == t->sum[b].end()) it = t->sum[b].emplace(key, std::vector<double>(G, 0.0)).first;
+      for (int g = 0; g < G; ++g) it->second[g] += static_cast<double>(conf[x * G + g]);
+      t->count[b][key] += 1;
+    }
+    for (int g = 0; g < G; ++g) t->total[g] += static_cast<double>(conf[x * G + g]);
+  }
+  return t;
+}
+
+void so_conf_free(void* h) { delete static_cast<ConfTables*>(h); }
+
+// Eq. 4 with the arithmetic mean as aggregation: c_hat(k_g, x) = mean of c(k_g, x') over the
+// training inputs x' that share a bucket with x.  Reading taken for L tables: LSH(x) is the
+// union of x's L buckets with multiplicity (an input that shares several buckets with x
+// counts once per bucket), i.e. (sum over tables of the bucket sums) / (sum over tables of
+// the bucket counts), tables visited in order.  With no bucket-mate at all the mean over the
+// whole training set stands in.  mates (nullable) receives the denominator.
+int so_conf_estimate(const void* h, const uint32_t* keys, int64_t Q, double* chat, int64_t* mates) {
+  const ConfTables* t = static_cast<const ConfTables*>(h);
+  const int L = t->L, G = t->G;
+  std::vector<double> s(G);
+  for (int64_t q = 0; q < Q; ++q) {
+    std::fill(s.begin(), s.end(), 0.0);
+    int64_t c = 0;
+    for (int b = 0; b < L; ++b) {
+      auto it = t->sum[b].find(keys[q * L + b]);
+      if (it == t->sum[b].end()) continue;
+      for (int g = 0; g < G; ++g) s[g] += it->second[g];
+      c += t->count[b].at(keys[q * L + b]);
+    }
+    for (int g = 0; g < G; ++g)
+      chat[q * G + g] = c > 0 ? s[g] / static_cast<double>(c) : t->total[g] / static_cast<double>(t->N);
+    if (mates) mates[q] = c;
+  }
+  return 0;
+}
+
+// ACLO (Section 2.2): minimise k subject to the accuracy constraint.  The constraint reaches
+// this code as a confidence threshold thr[q] (the calibration that ties a threshold to an
+// accuracy on held-out data is outside): the answer is the smallest k of the ascending grid
+// whose estimated confidence is at least the threshold; if none qualifies, the largest k.
+int so_choose_aclo(const void* h, const uint32_t* keys, int64_t Q, const float* k_grid, const float* thr,
+                   int64_t thr_stride, float* keep_out, int32_t* g_out) {
+  const ConfTables* t = static_cast<const ConfTables*>(h);
+  const int G = t->G;
+  std::vector<double> chat(G);
+  for (int64_t q = 0; q < Q; ++q) {
+    so_conf_estimate(h, keys + q * t->L, 1, chat.data(), nullptr);
+    int pick = G - 1;
+    for (int g = 0; g < G; ++g)
+      if (chat[g] >= static_cast<double>(thr[q * thr_stride])) { pick = g; break; }
+    keep_out[q] = k_grid[pick];
+    if (g_out) g_out[q] = pick;
+  }
+  return 0;
+}
+
+// LCAO (Section 2.3): maximise k subject to t0 + T(k, beta) <= tau.  T is the latency
+// profile [n_beta][G] (row beta[q] = the machine's current co-location state).  If no k of
+// the grid fits, the SLO cannot be met: the smallest k is returned and violated[q] is set.
+int so_choose_lcao(const float* k_grid, int G, const float* T, int n_beta, const float* tau,
+                   const float* t0, const int32_t* beta, int64_t Q, float* keep_out, int32_t* g_out,
+                   uint8_t* violated) {
+  for (int64_t q = 0; q < Q; ++q) {
+    if (beta[q] < 0 || beta[q] >= n_beta) return -1;
+    const float* row = T + static_cast<int64_t>(beta[q]) * G;
+    int pick = -1;
+    for (int g = 0; g < G; ++g)
+      if (static_cast<double>(t0[q]) + static_cast<double>(row[g]) <= static_cast<double>(tau[q])) pick = g;
+    if (violated) violated[q] = pick < 0 ? 1 : 0;
+    if (pick < 0) pick = 0;
+    keep_out[q] = k_grid[pick];
+    if (g_out) g_out[q] = pick;
+  }
   return 0;
 }
 

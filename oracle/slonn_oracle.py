@@ -43,6 +43,7 @@ def lib():
         _lib.so_tables_from_lists.restype = C.c_void_p
         _lib.so_tables_bucket_count.restype = C.c_int64
         _lib.so_tables_csr.restype = C.c_int64
+        _lib.so_conf_build.restype = C.c_void_p
         _lib.so_budget.restype = C.c_int32
         _lib.so_budget.argtypes = [C.c_float, C.c_int32]
     return _lib
@@ -219,6 +220,65 @@ def argmax(out, active=None, cnt=None):
 
 
 # --------------------------------------------------------------------------- #
+# choice of k per query (Section 2: ACLO / LCAO; Section 3.2: Confidence LSH tables)
+# --------------------------------------------------------------------------- #
+class ConfidenceTables:
+    """Per bucket, the sums and counts of the training inputs' confidences c(k_g, x')."""
+
+    def __init__(self, K, L, k_grid, keys, conf):
+        self.K, self.L = K, L
+        self.k_grid = _f32(k_grid).reshape(-1)
+        self.G = self.k_grid.size
+        keys = np.ascontiguousarray(keys, np.uint32)
+        conf = _f32(conf)
+        assert keys.shape[1] == L and conf.shape == (keys.shape[0], self.G)
+        self.h = C.c_void_p(lib().so_conf_build(K, L, self.G, _p(keys), _p(conf), C.c_int64(keys.shape[0])))
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().so_conf_free(self.h)
+            self.h = None
+
+    def estimate(self, keys):
+        """c_hat [Q][G] (float64) and the number of bucket-mates [Q]."""
+        keys = np.ascontiguousarray(keys, np.uint32)
+        Q = keys.shape[0]
+        chat = np.empty((Q, self.G), np.float64)
+        mates = np.empty(Q, np.int64)
+        lib().so_conf_estimate(self.h, _p(keys), C.c_int64(Q), _p(chat), _p(mates))
+        return chat, mates
+
+    def choose_aclo(self, keys, thr):
+        """ACLO: per query the smallest grid k whose estimated confidence reaches thr."""
+        keys = np.ascontiguousarray(keys, np.uint32)
+        Q = keys.shape[0]
+        thr = _f32(thr).reshape(-1)
+        keep = np.empty(Q, np.float32)
+        g = np.empty(Q, np.int32)
+        lib().so_choose_aclo(self.h, _p(keys), C.c_int64(Q), _p(self.k_grid), _p(thr),
+                             C.c_int64(1 if thr.size > 1 else 0), _p(keep), _p(g))
+        return keep, g
+
+
+def choose_lcao(k_grid, T, tau, t0, beta):
+    """LCAO: per query the largest grid k with t0 + T[beta][k] <= tau; (keep, grid index, violated)."""
+    k_grid = _f32(k_grid).reshape(-1)
+    T = _f32(T)
+    assert T.ndim == 2 and T.shape[1] == k_grid.size
+    tau, t0 = _f32(tau).reshape(-1), _f32(t0).reshape(-1)
+    beta = np.ascontiguousarray(beta, np.int32).reshape(-1)
+    Q = tau.size
+    keep = np.empty(Q, np.float32)
+    g = np.empty(Q, np.int32)
+    bad = np.empty(Q, np.uint8)
+    rc = lib().so_choose_lcao(_p(k_grid), k_grid.size, _p(T), T.shape[0], _p(tau), _p(t0), _p(beta),
+                              C.c_int64(Q), _p(keep), _p(g), _p(bad))
+    if rc != 0:
+        raise ValueError("beta out of range")
+    return keep, g, bad.astype(bool)
+
+
+# --------------------------------------------------------------------------- #
 # whole network
 # --------------------------------------------------------------------------- #
 class OracleNet:
@@ -305,6 +365,29 @@ class OracleNet:
             cur = out
         res["out"] = cur
         res["argmax"] = argmax(cur, last_active, last_cnt)
+        return res
+
+    # -- k chosen per query from the first activated layer's codes ----------- #
+    def first_activated(self) -> int:
+        return next(l for l, lay in enumerate(self.layers) if lay.K > 0 and lay.L > 0)
+
+    def first_codes(self, X):
+        """Keys of the first activated layer (its input is exact: every earlier layer is
+        computed in full).  Returns (keys, tie)."""
+        l0 = self.first_activated()
+        cur = X
+        for l in range(l0):
+            cur = self._first(cur) if (l == 0 and isinstance(cur, tuple)) else dense_layer(self.layers[l], cur, self.threads)
+        Z = hash_project(self.layers[l0], cur, self.threads)
+        return keys_from_z(Z, self.layers[l0].K, self.layers[l0].L)
+
+    def sparse_forward_aclo(self, X, conf_tables: "ConfidenceTables", thr, taps=True):
+        """Fig. 2 with step 2 under ACLO: the Confidence LSH tables are queried once per
+        request with the first activated layer's keys, the chosen k serves every layer."""
+        keys, _ = self.first_codes(X)
+        keep, g = conf_tables.choose_aclo(keys, thr)
+        res = self.sparse_forward(X, keep, taps=taps)
+        res["keep"], res["grid_idx"] = keep, g
         return res
 
     # -- table blob ---------------------------------------------------------- #

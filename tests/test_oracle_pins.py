@@ -505,3 +505,139 @@ def test_hash_first_forward_outputs(oracle):
             assert np.array_equal(tap["out"][q, mask], full[q, mask])
             assert not tap["out"][q, ~mask].any()
             assert np.array_equal(tap["out"][q, hn], np.maximum(tap["z"][q], 0))
+
+
+# --------------------------------------------------------------------------- #
+# choice of k per query (ACLO / LCAO, Confidence LSH tables)
+# --------------------------------------------------------------------------- #
+@pytest.fixture(scope="module")
+def kgold():
+    with open(os.path.join(os.path.dirname(__file__), "golden", "k_selection_example.json")) as f:
+        return json.load(f)
+
+
+def test_gold_k_selection(oracle, kgold):
+    t = oracle.ConfidenceTables(kgold["K"], kgold["L"], kgold["k_grid"], kgold["train_keys"], kgold["train_conf"])
+    for q in kgold["queries"]:
+        chat, mates = t.estimate(np.asarray([q["keys"]], np.uint32))
+        assert chat[0].tolist() == q["c_hat"]
+        assert mates[0] == q["mates"]
+    for a in kgold["aclo"]:
+        keep, g = t.choose_aclo(np.asarray([a["keys"]], np.uint32), [a["thr"]])
+        assert keep[0] == np.float32(a["keep"])
+        assert np.float32(kgold["k_grid"][g[0]]) == keep[0]
+    lc = kgold["lcao"]
+    for c in lc["cases"]:
+        keep, g, bad = oracle.choose_lcao(lc["k_grid"], lc["T"], [c["tau"]], [c["t0"]], [c["beta"]])
+        assert keep[0] == np.float32(c["keep"]) and bool(bad[0]) == c["violated"]
+
+
+def _dyadic(rng, shape):
+    """values -k/64: sums of a few thousand of them are exact in double, in any order"""
+    return (-rng.integers(0, 640, size=shape) / 64.0).astype(np.float32)
+
+
+def test_confidence_estimate_is_the_pooled_bucket_mean(oracle):
+    rng = np.random.default_rng(11)
+    for K, L, G, N in [(3, 1, 4, 200), (2, 4, 3, 150), (4, 3, 5, 400)]:
+        keys = rng.integers(0, 1 << K, size=(N, L)).astype(np.uint32)
+        keys[keys == 1] = 0                      # bucket 1 stays empty in every table
+        conf = _dyadic(rng, (N, G))
+        t = oracle.ConfidenceTables(K, L, np.linspace(0.1, 1.0, G), keys, conf)
+        Q = rng.integers(0, 1 << K, size=(60, L)).astype(np.uint32)
+        Q[:5] = 1                                # no bucket-mate in any table
+        chat, mates = t.estimate(Q)
+        for q in range(Q.shape[0]):
+            pool = np.concatenate([np.nonzero(keys[:, b] == Q[q, b])[0] for b in range(L)])
+            assert mates[q] == pool.size
+            if pool.size:
+                want = conf[pool].astype(np.float64).sum(axis=0) / pool.size
+            else:
+                want = conf.astype(np.float64).sum(axis=0) / N
+            assert np.array_equal(chat[q], want)
+        if L == 1:      # one table: plain mean of the bucket-mates (Eq. 4 as printed)
+            for q in range(5, 20):
+                mate = keys[:, 0] == Q[q, 0]
+                if mate.any():
+                    assert np.array_equal(chat[q], conf[mate].astype(np.float64).mean(axis=0))
+        # a constant confidence is reproduced for every key, seen or not
+        tc = oracle.ConfidenceTables(K, L, np.linspace(0.1, 1.0, G), keys, np.full((N, G), -0.375, np.float32))
+        assert (tc.estimate(Q)[0] == -0.375).all()
+
+
+def test_aclo_picks_the_smallest_sufficient_k(oracle):
+    rng = np.random.default_rng(12)
+    K, L, G, N = 3, 3, 6, 300
+    grid = np.asarray([0.05, 0.1, 0.25, 0.5, 0.75, 1.0], np.float32)
+    keys = rng.integers(0, 1 << K, size=(N, L)).astype(np.uint32)
+    conf = _dyadic(rng, (N, G))
+    conf[:, -1] = 0.0                              # the full network agrees with itself
+    t = oracle.ConfidenceTables(K, L, grid, keys, conf)
+    Q = rng.integers(0, 1 << K, size=(80, L)).astype(np.uint32)
+    chat, _ = t.estimate(Q)
+    prev = None
+    for thr in (-np.inf, -8.0, -5.0, -4.0, -2.0, 0.0, 1.0):
+        keep, g = t.choose_aclo(Q, np.full(80, thr, np.float32))
+        for q in range(80):
+            ok = np.nonzero(chat[q] >= thr)[0]
+            want = ok[0] if ok.size else G - 1
+            assert g[q] == want and keep[q] == grid[want]
+        if thr == -np.inf:
+            assert (g == 0).all()
+        if thr == 0.0:
+            assert (chat[np.arange(80), g] >= 0.0).all()      # k = 1.0 always qualifies at t <= 0
+        if prev is not None:
+            assert (keep >= prev).all()                        # a stricter target never lowers k
+        prev = keep
+    # one threshold per query
+    thr = rng.uniform(-9, 0, 80).astype(np.float32)
+    keep, g = t.choose_aclo(Q, thr)
+    for q in range(80):
+        ok = np.nonzero(chat[q] >= np.float64(thr[q]))[0]
+        assert g[q] == (ok[0] if ok.size else G - 1)
+
+
+def test_lcao_picks_the_largest_k_that_fits(oracle):
+    rng = np.random.default_rng(13)
+    grid = np.asarray([0.05, 0.1, 0.25, 0.5, 1.0], np.float32)
+    T = np.sort(rng.uniform(0.1, 5.0, size=(3, 5)).astype(np.float32), axis=1)
+    T[2] *= 2.0                                    # a heavier co-location state
+    Q = 200
+    tau = rng.uniform(0.0, 8.0, Q).astype(np.float32)
+    t0 = rng.uniform(0.0, 1.0, Q).astype(np.float32)
+    beta = rng.integers(0, 3, Q).astype(np.int32)
+    keep, g, bad = oracle.choose_lcao(grid, T, tau, t0, beta)
+    for q in range(Q):
+        fits = np.nonzero(t0[q].astype(np.float64) + T[beta[q]].astype(np.float64) <= np.float64(tau[q]))[0]
+        if fits.size:
+            assert not bad[q] and g[q] == fits.max() and keep[q] == grid[fits.max()]
+        else:
+            assert bad[q] and g[q] == 0 and keep[q] == grid[0]
+    assert bad.any() and (~bad).any()
+    # monotone profile: the answer is a binary search
+    for q in range(Q):
+        if not bad[q]:
+            assert g[q] == np.searchsorted(np.float64(t0[q]) + T[beta[q]].astype(np.float64),
+                                           np.float64(tau[q]), side="right") - 1
+    with pytest.raises(ValueError):
+        oracle.choose_lcao(grid, T, [1.0], [0.0], [3])
+
+
+def test_forward_under_aclo_equals_forward_with_the_chosen_k(oracle):
+    net, Xb = _small_net(oracle, (20, 48, 36, 5), K=3, L=4, seed=41)
+    rng = np.random.default_rng(14)
+    grid = np.asarray([0.1, 0.3, 0.6, 1.0], np.float32)
+    keys, _ = net.first_codes(Xb)
+    conf = _dyadic(rng, (Xb.shape[0], 4))
+    t = oracle.ConfidenceTables(3, 4, grid, keys, conf)
+    X = wl.inputs_uniform_half_zero(30, 20, 99)
+    thr = rng.uniform(-6, -3, 30).astype(np.float32)
+    res = net.sparse_forward_aclo(X, t, thr)
+    kq, _ = net.first_codes(X)
+    assert np.array_equal(kq, res["layers"][0]["codes"])
+    keep, g = t.choose_aclo(kq, thr)
+    assert np.array_equal(res["keep"], keep) and len(set(keep.tolist())) > 1
+    ref = net.sparse_forward(X, keep)
+    assert np.array_equal(res["out"], ref["out"])
+    for l in (0, 1):
+        assert np.array_equal(res["layers"][l]["cnt"], [oracle.budget(k, net.layers[l].d_out) for k in keep])
