@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "layers", "fused"])
     ap.add_argument("--hash-nodes-always-active", action="store_true",
                     help="Section 3.4 variant: hash nodes always computed, never selected (default off)")
+    ap.add_argument("--aclo", action="store_true",
+                    help="also time the pass with k chosen per query inside it (ACLO, Confidence LSH tables)")
     ap.add_argument("--build-inputs", type=int, default=0, help="size of the table-training set (default: the config's)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, for scaling rocprofv3 byte counters")
@@ -236,6 +238,53 @@ def main():
         dflops = 2.0 * sum(lay.d_in * lay.d_out for lay in layers if not (ell and lay is layers[0]))
         extra["dense_baseline_tflops"] = round(dflops * 120 * B / dsec / 1e12, 2)
         extra["dense_baseline_frac_of_fp32_mfma_peak"] = round(dflops * 120 * B / dsec / 157.3e12, 4)
+
+    # ---- k chosen per query inside the pass (ACLO): Confidence LSH tables trained on the build
+    #      set with c(k, x) = -cross-entropy(full prediction, prediction at k) (Eq. 3) ----
+    if args.aclo and mixed is None and not ell and cfg.hashed_layers[0] == 0:
+        grid = sorted(set(float(k) for k in cfg.keeps))
+        nb_ = min(xb.shape[0], 8192)
+        xb_ = xb[:nb_]
+        pf = torch.softmax(net.dense_forward(xb_)["out"].double(), dim=1)
+        conf = torch.empty((nb_, len(grid)), dtype=torch.float32, device=dev)
+        for gi, k in enumerate(grid):
+            yk = net.sparse_forward(xb_, k)["out"].double()
+            conf[:, gi] = (pf * torch.log_softmax(yk, dim=1)).sum(dim=1).float()
+        codes = net.select(0, xb_, 1.0)["codes"]
+        pol = slonn.slonn_policy_create(cfg.K, cfg.L, grid)
+        slonn.slonn_policy_train_confidence(pol, codes, conf, nb_)
+        # one threshold per query, drawn from the training confidences at the middle k, so that
+        # a batch mixes queries that are satisfied early with queries that need more nodes
+        pick = torch.from_numpy(np.random.default_rng(8).integers(0, nb_, nq)).to(dev)
+        thr_all = conf[:, len(grid) // 2][pick].contiguous()
+        keep_out = torch.zeros(B, dtype=torch.float32, device=dev)
+
+        def run_aclo(steps, first=0):
+            for i in range(steps):
+                b = (first + i) % n_batches
+                slonn.slonn_sparse_forward_aclo(net.model, net.tables, pol, batches[b], B,
+                                                thr_all[b * B:(b + 1) * B], 1, keep_out, out, None, ws, stream)
+        run_aclo(20)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        run_aclo(120, 20)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        a_s = max(e0.elapsed_time(e1) / 1e3, time.perf_counter() - t0)
+        chosen = []
+        for b in range(min(n_batches, 16)):
+            run_aclo(1, b)
+            chosen.append(keep_out.cpu().numpy().copy())
+        chosen = np.concatenate(chosen)
+        extra["aclo"] = {"qps": round(120 * B / a_s), "us_per_step": round(a_s / 120 * 1e6, 2),
+                         "k_grid": grid,
+                         "share_of_queries_per_k": [round(float((chosen == np.float32(k)).mean()), 4) for k in grid],
+                         "mean_keep": round(float(chosen.mean()), 4),
+                         "confidence": "-cross-entropy(softmax(full), softmax(at k)) on the first "
+                                       f"{nb_} build inputs; per-query thresholds drawn from those at k = {grid[len(grid) // 2]}"}
+        log(f"ACLO: {extra['aclo']}")
 
     # ---- CPU baseline: the oracle as it stands, on the host cores, bounded sample ----
     cpu = None

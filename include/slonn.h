@@ -50,12 +50,14 @@ enum { SLONN_DENSE = 0, SLONN_ELL = 1 };                /* first-layer input for
 
 #define SLONN_MAX_K 16      /* bits per key                                               */
 #define SLONN_MAX_L 64      /* tables per layer (one wavefront lane per table)            */
+#define SLONN_MAX_GRID 16       /* most keep fractions a policy's k grid may hold */
 #define SLONN_MAX_BATCH 1048576 /* queries per call, and training inputs per table build   */
 #define SLONN_TABLE_BLOB_MAGIC 0x544E4C53u /* "SLNT" */
 #define SLONN_TABLE_BLOB_VERSION 1u
 
 typedef struct slonn_model slonn_model;
 typedef struct slonn_tables slonn_tables;
+typedef struct slonn_policy slonn_policy;
 
 /* One fully-connected layer y = act(W x + b).  Activations are always fp32.
  * W: device, BORROWED for the lifetime of the model.  ROWS_ARE_NODES: [d_out][d_in],
@@ -202,6 +204,62 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
                          const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
                          const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
                          void* stream);
+
+/* ---- Choice of k per query (Section 2: ACLO and LCAO; Section 3.2: Confidence LSH tables,
+ * latency profiles; Fig. 2 step 2).  Mechanics only: the confidences c(k, x') of the
+ * training inputs (Eq. 3) and the latency profile T(k, beta) are supplied by the caller, and
+ * an accuracy target reaches the library as the confidence threshold it was calibrated to.
+ *
+ * A policy holds an ascending grid k_0 < ... < k_{G-1} of keep fractions (HOST, values in
+ * (0, 1], G <= SLONN_MAX_GRID), Confidence LSH tables over L tables of K-bit keys, and a
+ * latency profile.  The keys are those of the model's first activated layer (the tables
+ * share its hash functions), so K and L must equal that layer's.                          */
+int slonn_policy_create(int K, int L, const float* k_grid, int G, slonn_policy** out);
+int slonn_policy_destroy(slonn_policy* p);
+
+/* Confidence LSH tables.  codes: device [N][L] keys of the N training inputs (as returned
+ * by slonn_select's codes_out for the first activated layer), conf: device [N][G] with
+ * conf[x][g] = c(k_g, x).  Every bucket receives the sum (double, in input order) and the
+ * count of its inputs' confidences; a later call replaces the tables.  Synchronises the
+ * stream.  EINVAL: null argument, N outside 1 .. SLONN_MAX_BATCH, a key >= 2^K.            */
+int slonn_policy_train_confidence(slonn_policy* p, const uint32_t* codes, const float* conf, int64_t N,
+                                  void* stream);
+
+/* Latency profile T: HOST [n_beta][G], T[beta][g] = latency of a pass at k_g under
+ * co-location state beta (any unit; tau and t0 below use the same), entries >= 0.        */
+int slonn_policy_set_latency_profile(slonn_policy* p, const float* T, int n_beta);
+
+/* ACLO (Section 2.2): minimise k subject to the accuracy constraint.  For query q with keys
+ * codes[q][0..L) (device) the estimated confidence (Eq. 4, arithmetic mean) of grid point g is
+ *   c_hat(k_g, x) = (sum over tables of the bucket's sum) / (sum over tables of its count),
+ * i.e. the mean over the training inputs that share a bucket with x, an input counted once
+ * per shared bucket; with no such input, the mean over the whole training set.  keep_out[q]
+ * (device) = the smallest k_g with c_hat >= thr[q*thr_stride] (device; stride 0 broadcasts),
+ * else k_{G-1}.  grid_idx_out [B] int32 and c_hat_out [B][G] double are nullable (device).
+ * EINVAL: null argument, untrained tables, bad B.                                          */
+int slonn_policy_keep_aclo(const slonn_policy* p, const uint32_t* codes, int B, const float* thr,
+                           int thr_stride, float* keep_out, int32_t* grid_idx_out, double* c_hat_out,
+                           void* stream);
+
+/* LCAO (Section 2.3): maximise k subject to t0 + T(k, beta) <= tau.  All arrays device, with
+ * element strides (0 broadcasts): keep_out[q] = the largest k_g with
+ * t0[q] + T[beta[q]][g] <= tau[q] (evaluated in double); if no grid point fits, or beta[q]
+ * is outside 0 .. n_beta-1, the SLO cannot be met: keep_out[q] = k_0 and violated_out[q] = 1
+ * (else 0).  grid_idx_out, violated_out nullable.  EINVAL: null argument, no profile set.   */
+int slonn_policy_keep_lcao(const slonn_policy* p, int B, const float* tau, int tau_stride, const float* t0,
+                           int t0_stride, const int32_t* beta, int beta_stride, float* keep_out,
+                           int32_t* grid_idx_out, int32_t* violated_out, void* stream);
+
+/* slonn_sparse_forward with k chosen inside the pass under ACLO (Fig. 2: the Confidence LSH
+ * tables are queried once per request, the chosen k serves every layer): the keys of the
+ * first activated layer are computed once and used both for the choice of k and for that
+ * layer's Node Importance lookup.  thr as in slonn_policy_keep_aclo; keep_out [B] (device)
+ * receives the chosen keep fractions.  Everything else as slonn_sparse_forward.  EINVAL also
+ * when the policy's K, L differ from the first activated layer's or it is untrained.        */
+int slonn_sparse_forward_aclo(const slonn_model* m, const slonn_tables* t, const slonn_policy* p,
+                              const slonn_input* X, int B, const float* thr, int thr_stride, float* keep_out,
+                              slonn_output* Y, const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
+                              void* stream);
 
 /* The full network (all nodes), the baseline every speed-up is measured against:
  * per layer an MFMA GEMM + bias + activation.  Y device [B][d_last]; argmax nullable.

@@ -197,6 +197,14 @@ __device__ __forceinline__ void gather_rows(const void* __restrict__ W, const fl
   }
 }
 
+// LDS needed without the staging area of the in-kernel choice of k (a multiple of 16 bytes)
+__host__ __device__ inline size_t fused_lds_base(const FusedArgs& a) {
+  const size_t bytes = (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 +
+                       SelectShared<NT>::words_besides_prio * 4 + (64 + 4) * 4 + (size_t)a.max_na * 2;
+  return (bytes + 15) & ~(size_t)15;
+}
+
+template <bool POLICY>
 __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   float* xbuf0 = reinterpret_cast<float*>(smem);
@@ -210,7 +218,12 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
   sh.s_len = sh.s_off + 64;
   sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
   sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * NW);
-  int16_t* hmap = reinterpret_cast<int16_t*>(sh.s_misc + 4);      // [max_na] node -> hash row or -1
+  uint32_t* pkey = sh.s_misc + 4;                                 // [64] keys for the choice of k
+  float* s_keep = reinterpret_cast<float*>(pkey + 64);            // [4] keep fraction chosen in the kernel
+  int16_t* hmap = reinterpret_cast<int16_t*>(s_keep + 4);         // [max_na] node -> hash row or -1
+  // only with the choice of k inside the kernel: staged bucket sums [L][G] and counts [L]
+  double* pstage = reinterpret_cast<double*>(smem + fused_lds_base(a));
+  uint32_t* pcount = reinterpret_cast<uint32_t*>(pstage + SLONN_MAX_L * SLONN_MAX_GRID);
 
   const int q = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -229,8 +242,11 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
     const bool last = (li == a.n_layers - 1);
     const bool activated = Ly.K > 0;
     int m = n;
-    if (activated) m = budget_of(a.keep[(size_t)q * a.keep_qstride + (size_t)li * a.keep_lstride], n);
     const int32_t* list = nullptr;
+    // the caller's keep fraction is fetched now so that its latency hides behind the hash
+    float kq = 1.0f;
+    if (activated && !(POLICY && li >= a.pol.layer))
+      kq = a.keep[(size_t)q * a.keep_qstride + (size_t)li * a.keep_lstride];
 
     if (activated) {
       // ---- hash: z_h = w_h . x + b_h in fp64, one 16-lane group per row ----
@@ -272,6 +288,50 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
       // meanwhile: clear the next activation buffer and the first-occurrence map
       for (int i = tid; i < n; i += NT) { xn[i] = 0.0f; prio[i] = 0xFFFFFFFFu; hmap[i] = Ly.hslot[i]; }
       __syncthreads();
+
+      // ---- budget: from the caller, or chosen here from the Confidence LSH tables (ACLO,
+      //      Section 2.2 / Eq. 4) with this layer's keys; the choice serves all later layers ----
+      if (POLICY && li >= a.pol.layer) {
+        if (li == a.pol.layer) {
+          if (wave == 0 && lane < Ly.L) {
+            uint32_t key = 0;
+            for (int j = 0; j < Ly.K; ++j) key |= (zs[lane * Ly.K + j] > 0.0f ? 1u : 0u) << j;
+            pkey[lane] = key;
+          }
+          __syncthreads();
+          // all L*G bucket sums (<= 1024) are fetched at once, one per thread ...
+          const int G = a.pol.G, nb = 1 << Ly.K;
+          if (tid < Ly.L * G) {
+            const int b = tid / G, g = tid - b * G;
+            const size_t bk = (size_t)b * nb + pkey[b];
+            pstage[tid] = a.pol.sum[bk * G + g];
+            if (g == 0) pcount[b] = a.pol.cnt[bk];
+          }
+          __syncthreads();
+          if (wave == 0) {
+            // ... and pooled by lane g in table order (reproducible double sums; an empty
+            // bucket holds the sum +0 and the count 0)
+            bool ok = false;
+            if (lane < G) {
+              double sacc = 0.0;
+              unsigned long long c = 0;
+              for (int b = 0; b < Ly.L; ++b) { sacc += pstage[b * G + lane]; c += pcount[b]; }
+              const double chat = c > 0 ? sacc / (double)c : a.pol.total[lane] / (double)a.pol.N;
+              ok = chat >= (double)a.pol.thr[(size_t)q * a.pol.thr_stride];
+            }
+            const unsigned long long votes = __ballot(ok);
+            if (lane == 0) {
+              const int pick = votes ? (__ffsll((long long)votes) - 1) : a.pol.G - 1;
+              const float kk = a.pol.grid[pick];
+              s_keep[0] = kk;
+              a.pol.keep_out[q] = kk;
+            }
+          }
+          __syncthreads();
+        }
+        kq = s_keep[0];
+      }
+      m = budget_of(kq, n);
 
       // Section 3.4 variant: the H hash nodes head the active list and are never selected
       const int Hf = (a.hash_first && m < n) ? H : 0;
@@ -382,8 +442,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
 }  // namespace
 
 size_t fused_lds_bytes(const FusedArgs& a) {
-  return (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 + SelectShared<NT>::words_besides_prio * 4 +
-         (((size_t)a.max_na * 2 + 15) & ~(size_t)15);
+  size_t bytes = fused_lds_base(a);
+  if (a.pol.sum) bytes += (size_t)SLONN_MAX_L * SLONN_MAX_GRID * 8 + SLONN_MAX_L * 4;
+  return bytes;
 }
 
 int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s) {
@@ -391,10 +452,17 @@ int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s) 
   const size_t lds = fused_lds_bytes(a);
   if (lds > (size_t)max_lds)
     SLONN_FAIL(SLONN_EUNSUPPORTED, "fused path needs %zu bytes of LDS, device grants %d", lds, max_lds);
-  if (lds > 65536)
-    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(fused_forward_kernel, dim3(B), dim3(NT), lds, s, a);
+  if (a.pol.sum) {
+    if (lds > 65536)
+      SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(fused_forward_kernel<true>, dim3(B), dim3(NT), lds, s, a);
+  } else {
+    if (lds > 65536)
+      SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(fused_forward_kernel<false>, dim3(B), dim3(NT), lds, s, a);
+  }
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

@@ -511,10 +511,23 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
                        nullptr, m->hash_first ? &hf : nullptr, s);
 }
 
-int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
-                         const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
-                         const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
-                         void* stream) {
+namespace slonn {
+namespace {
+
+// ACLO inside the forward pass: k is chosen from the first activated layer's projections
+// (the Confidence LSH tables share that layer's hash functions) and serves every layer.
+struct PolicyHook {
+  const slonn_policy* p = nullptr;
+  const float* thr = nullptr;
+  int thr_stride = 0;
+  float* keep_out = nullptr;     // [B] device, receives the chosen keep fractions
+  int layer = -1;                // first activated layer
+};
+
+int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
+                 const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
+                 const slonn_debug_taps* taps, void* workspace, size_t ws_bytes, void* stream,
+                 const PolicyHook* hook) {
   if (!m || !X || !keep || !Y) SLONN_FAIL(SLONN_EINVAL, "null argument");
   if (B <= 0 || B > SLONN_MAX_BATCH) SLONN_FAIL(SLONN_EINVAL, "B must be in 1 .. %d", SLONN_MAX_BATCH);
   if (keep_qstride < 0 || keep_lstride < 0) SLONN_FAIL(SLONN_EINVAL, "negative keep stride");
@@ -574,6 +587,11 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
     a.X = X->x; a.ldx = m->layers[0].d_in;
     a.keep = keep; a.keep_qstride = keep_qstride; a.keep_lstride = keep_lstride;
     a.hash_first = m->hash_first ? 1 : 0;
+    if (hook) {
+      policy_fused_args(hook->p, &a.pol);
+      a.pol.thr = hook->thr; a.pol.thr_stride = hook->thr_stride; a.pol.keep_out = hook->keep_out;
+      a.pol.layer = hook->layer;
+    }
     a.Y = Y->dense; a.argmax = Y->argmax;
     return launch_fused_forward(a, B, m->max_lds_bytes, s);
   }
@@ -613,6 +631,13 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
       if (is_last && Y->cnt && !tap_cnt) acnt = Y->cnt;
       rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
       if (rc) return rc;
+      if (hook && l == hook->layer) {
+        // the budget of this and of every later layer comes from the confidence tables
+        rc = launch_policy_aclo(hook->p, nullptr, z, B, hook->thr, hook->thr_stride, hook->keep_out, nullptr,
+                                nullptr, s);
+        if (rc) return rc;
+        keep = hook->keep_out; keep_qstride = 1; keep_lstride = 0;
+      }
       // Weight matrices well beyond an L2 slice (with rows long enough to occupy a wavefront)
       // are walked in blocks of rows of about 2 MiB so that concurrently running workgroups
       // share them; the others are read as listed.
@@ -699,6 +724,36 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
     ldcur = ldo;
   }
   return SLONN_OK;
+}
+
+}  // namespace
+}  // namespace slonn
+
+int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
+                         const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
+                         const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
+                         void* stream) {
+  return forward_impl(m, t, X, B, keep, keep_qstride, keep_lstride, Y, taps, workspace, ws_bytes, stream,
+                      nullptr);
+}
+
+int slonn_sparse_forward_aclo(const slonn_model* m, const slonn_tables* t, const slonn_policy* p,
+                              const slonn_input* X, int B, const float* thr, int thr_stride, float* keep_out,
+                              slonn_output* Y, const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
+                              void* stream) {
+  if (!m || !p || !thr || !keep_out) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  if (thr_stride < 0) SLONN_FAIL(SLONN_EINVAL, "negative stride");
+  PolicyHook hook;
+  hook.p = p; hook.thr = thr; hook.thr_stride = thr_stride; hook.keep_out = keep_out;
+  for (int l = 0; l < (int)m->layers.size() && hook.layer < 0; ++l)
+    if (m->layers[l].activated()) hook.layer = l;
+  if (hook.layer < 0) SLONN_FAIL(SLONN_EINVAL, "the model has no activated layer to take keys from");
+  const slonn::Layer& L0 = m->layers[hook.layer];
+  if (!policy_matches(p, L0.K, L0.L))
+    SLONN_FAIL(SLONN_EINVAL, "the policy's K and L differ from those of layer %d", hook.layer);
+  if (!policy_trained(p)) SLONN_FAIL(SLONN_EINVAL, "the confidence tables have not been trained");
+  // keep_out doubles as the keep array of the pass; it is written before it is first read
+  return forward_impl(m, t, X, B, keep_out, 1, 0, Y, taps, workspace, ws_bytes, stream, &hook);
 }
 
 int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float* Y, int32_t* argmax,

@@ -86,6 +86,19 @@ struct ProfScope {
   hipStream_t stream;
 };
 
+// Confidence tables as the whole-network kernel sees them (sum == nullptr: keep fractions
+// come from the caller).
+struct PolicyArgs {
+  const double* sum = nullptr;     // [L][2^K][G]
+  const uint32_t* cnt = nullptr;   // [L][2^K]
+  const double* total = nullptr;   // [G]
+  const float* grid = nullptr;     // [G]
+  const float* thr = nullptr;      // [B] (stride thr_stride)
+  float* keep_out = nullptr;       // [B]
+  long long N = 0;
+  int G = 0, thr_stride = 0, layer = -1;
+};
+
 // Arguments of the whole-network kernel (passed by value as kernel arguments).
 constexpr int FUSED_MAX_LAYERS = 8;
 struct FusedLayer {
@@ -113,6 +126,7 @@ struct FusedArgs {
   int32_t* argmax;
   int ldx, keep_qstride, keep_lstride, n_layers;
   int hash_first;                  // hash nodes always computed, never selected
+  PolicyArgs pol;                  // choice of k inside the kernel (ACLO)
   int max_dim, max_H, max_na;      // LDS carve-up: activations, projections, active list
 };
 size_t fused_lds_bytes(const FusedArgs& a);
@@ -202,6 +216,14 @@ int launch_dense_layer(const void* W, int w_dtype, const float* bias, const floa
 // true when a problem of fewer than 256 tiles of 64x64 can take the small-shape MFMA kernel
 // (operands straight from L2); otherwise such shapes are better served by the row gather.
 bool dense_small_supported(const void* W, int w_dtype, const float* X, int ldx, int d);
+
+// k per query from the confidence tables (ACLO): keys from codes [B][L] or, when codes is
+// null, from the projections Z [B][K*L].
+int launch_policy_aclo(const slonn_policy* p, const uint32_t* codes, const float* Z, int B, const float* thr,
+                       int thr_stride, float* keep_out, int32_t* g_out, double* chat_out, hipStream_t s);
+void policy_fused_args(const slonn_policy* p, PolicyArgs* a);
+bool policy_matches(const slonn_policy* p, int K, int L);
+bool policy_trained(const slonn_policy* p);
 
 int launch_fill_iota(int32_t* idx, int stride, int32_t* cnt, int n, int B, hipStream_t s);
 

@@ -83,12 +83,20 @@ class Network:
         return slonn.slonn_tables_export(self.tables)
 
     # -- forward -------------------------------------------------------------- #
-    def sparse_forward(self, X, keep, taps: bool = False, compact: bool = False, dense: bool = True):
-        """keep: device float tensor [B] or [B][n_layers], or a python float."""
+    def sparse_forward(self, X, keep, taps: bool = False, compact: bool = False, dense: bool = True,
+                       policy=None, thr=None):
+        """keep: device float tensor [B] or [B][n_layers], or a python float.  With a policy
+        (slonn.Policy) and thr (device float tensor [B] or a python float) k is chosen inside the
+        pass under ACLO, keep is ignored and the chosen fractions come back as res["keep"]."""
         inp = self.to_input(X)
         B = self.batch_of(inp)
         dev = self.device
-        if not torch.is_tensor(keep):
+        if policy is not None:
+            if not torch.is_tensor(thr):
+                thr = torch.full((1,), float(thr), dtype=torch.float32, device=dev)
+            keep = torch.zeros(B, dtype=torch.float32, device=dev)
+            qs, ls = 1, 0
+        elif not torch.is_tensor(keep):
             keep = torch.full((1,), float(keep), dtype=torch.float32, device=dev)
             qs, ls = 0, 0
         elif keep.dim() == 1:
@@ -118,7 +126,12 @@ class Network:
                 lout.append(torch.empty((B, l.d_out), dtype=torch.float32, device=dev))
             tp = slonn.make_taps(self.n_layers, codes, z, aidx, acnt, lout)
             res["taps"] = dict(codes=codes, z=z, active=aidx, cnt=acnt, out=lout)
-        slonn.slonn_sparse_forward(self.model, self.tables, inp, B, keep, qs, ls, out, tp, self.workspace(B))
+        if policy is not None:
+            slonn.slonn_sparse_forward_aclo(self.model, self.tables, policy, inp, B, thr,
+                                            1 if thr.numel() > 1 else 0, keep, out, tp, self.workspace(B))
+            res["keep"] = keep
+        else:
+            slonn.slonn_sparse_forward(self.model, self.tables, inp, B, keep, qs, ls, out, tp, self.workspace(B))
         res["out"], res["argmax"] = dense, argmax
         return res
 

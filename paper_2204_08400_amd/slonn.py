@@ -27,6 +27,9 @@ EXPORTS = [
     "slonn_select", "slonn_sparse_forward", "slonn_dense_forward", "slonn_last_error",
     "slonn_profile_begin", "slonn_profile_end", "slonn_model_set_path",
     "slonn_model_set_hash_nodes_always_active",
+    "slonn_policy_create", "slonn_policy_destroy", "slonn_policy_train_confidence",
+    "slonn_policy_set_latency_profile", "slonn_policy_keep_aclo", "slonn_policy_keep_lcao",
+    "slonn_sparse_forward_aclo",
 ]
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused")
 PATH_AUTO, PATH_LAYERS, PATH_FUSED = 0, 1, 2
@@ -253,6 +256,66 @@ def slonn_sparse_forward(model: Model, tables: Optional[Tables], X: Input, B: in
     _check(load().slonn_sparse_forward(
         model.h, tables.h if tables is not None else None, C.byref(X), int(B),
         C.c_void_p(_ptr(keep)), int(keep_qstride), int(keep_lstride), C.byref(Y),
+        C.byref(taps) if taps is not None else None, C.c_void_p(_ptr(workspace)),
+        C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
+        C.c_void_p(_stream_ptr(stream))))
+
+
+class Policy:
+    """Owns a slonn_policy handle (k grid, Confidence LSH tables, latency profile)."""
+
+    def __init__(self, K: int, L: int, k_grid: Sequence[float]):
+        grid = (C.c_float * len(k_grid))(*[float(v) for v in k_grid])
+        h = C.c_void_p()
+        _check(load().slonn_policy_create(int(K), int(L), grid, len(k_grid), C.byref(h)))
+        self.h, self.K, self.L, self.G = h, int(K), int(L), len(k_grid)
+
+    def close(self):
+        if getattr(self, "h", None):
+            load().slonn_policy_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+
+def slonn_policy_create(K: int, L: int, k_grid: Sequence[float]) -> Policy:
+    return Policy(K, L, k_grid)
+
+
+def slonn_policy_train_confidence(policy: Policy, codes, conf, N: int, stream=None):
+    _check(load().slonn_policy_train_confidence(policy.h, C.c_void_p(_ptr(codes)), C.c_void_p(_ptr(conf)),
+                                                C.c_int64(int(N)), C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_policy_set_latency_profile(policy: Policy, T: Sequence[Sequence[float]]):
+    flat = [float(v) for row in T for v in row]
+    arr = (C.c_float * len(flat))(*flat)
+    _check(load().slonn_policy_set_latency_profile(policy.h, arr, len(T)))
+
+
+def slonn_policy_keep_aclo(policy: Policy, codes, B: int, thr, thr_stride: int, keep_out, grid_idx_out=None,
+                           c_hat_out=None, stream=None):
+    _check(load().slonn_policy_keep_aclo(policy.h, C.c_void_p(_ptr(codes)), int(B), C.c_void_p(_ptr(thr)),
+                                         int(thr_stride), C.c_void_p(_ptr(keep_out)),
+                                         C.c_void_p(_ptr(grid_idx_out)), C.c_void_p(_ptr(c_hat_out)),
+                                         C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_policy_keep_lcao(policy: Policy, B: int, tau, tau_stride: int, t0, t0_stride: int, beta,
+                           beta_stride: int, keep_out, grid_idx_out=None, violated_out=None, stream=None):
+    _check(load().slonn_policy_keep_lcao(policy.h, int(B), C.c_void_p(_ptr(tau)), int(tau_stride),
+                                         C.c_void_p(_ptr(t0)), int(t0_stride), C.c_void_p(_ptr(beta)),
+                                         int(beta_stride), C.c_void_p(_ptr(keep_out)),
+                                         C.c_void_p(_ptr(grid_idx_out)), C.c_void_p(_ptr(violated_out)),
+                                         C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_sparse_forward_aclo(model: Model, tables: Optional[Tables], policy: Policy, X: Input, B: int, thr,
+                              thr_stride: int, keep_out, Y: Output, taps: Optional[DebugTaps], workspace,
+                              stream=None):
+    _check(load().slonn_sparse_forward_aclo(
+        model.h, tables.h if tables is not None else None, policy.h, C.byref(X), int(B),
+        C.c_void_p(_ptr(thr)), int(thr_stride), C.c_void_p(_ptr(keep_out)), C.byref(Y),
         C.byref(taps) if taps is not None else None, C.c_void_p(_ptr(workspace)),
         C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
         C.c_void_p(_stream_ptr(stream))))

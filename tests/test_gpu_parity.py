@@ -606,3 +606,131 @@ def test_hash_nodes_always_active_wide_output_layer(rt, oracle):
             assert np.array_equal(got["idx"][q, :c], ref["layers"][1]["active"][q, :c])
             np.testing.assert_allclose(got["val"][q, :c], ref["out"][q, ref["layers"][1]["active"][q, :c]],
                                        rtol=1e-4, atol=1e-6 * float(ref["out"][q].max()))
+
+
+# --------------------------------------------------------------------------- #
+# choice of k per query (ACLO / LCAO)
+# --------------------------------------------------------------------------- #
+def _dyadic_conf(rng, shape):
+    """confidences -k/64 in [-10, 0], last grid point (the full network) exactly 0"""
+    c = (-rng.integers(0, 640, size=shape) / 64.0).astype(np.float32)
+    c[:, -1] = 0.0
+    return c
+
+
+def test_worked_k_selection_example(rt, oracle):
+    import torch
+    from paper_2204_08400_amd import slonn
+    with open(os.path.join(os.path.dirname(__file__), "golden", "k_selection_example.json")) as f:
+        gold = json.load(f)
+    dev = "cuda:0"
+    p = slonn.slonn_policy_create(gold["K"], gold["L"], gold["k_grid"])
+    codes = torch.tensor(gold["train_keys"], dtype=torch.int32, device=dev)
+    conf = torch.tensor(gold["train_conf"], dtype=torch.float32, device=dev)
+    slonn.slonn_policy_train_confidence(p, codes, conf, codes.shape[0])
+    for a in gold["aclo"]:
+        _say(f"worked ACLO example {a}")
+        kq = torch.tensor([a["keys"]], dtype=torch.int32, device=dev)
+        thr = torch.tensor([a["thr"]], dtype=torch.float32, device=dev)
+        keep = torch.zeros(1, dtype=torch.float32, device=dev)
+        chat = torch.zeros((1, 2), dtype=torch.float64, device=dev)
+        slonn.slonn_policy_keep_aclo(p, kq, 1, thr, 0, keep, None, chat)
+        assert keep.item() == np.float32(a["keep"])
+        want = next(q["c_hat"] for q in gold["queries"] if q["keys"] == a["keys"])
+        assert chat.cpu().numpy()[0].tolist() == want
+    lc = gold["lcao"]
+    p2 = slonn.slonn_policy_create(1, 1, lc["k_grid"])
+    slonn.slonn_policy_set_latency_profile(p2, lc["T"])
+    for c in lc["cases"] + [{"tau": 100.0, "t0": 0.0, "beta": 7, "keep": 0.1, "violated": True}]:
+        _say(f"worked LCAO example {c}")
+        tau = torch.tensor([c["tau"]], dtype=torch.float32, device=dev)
+        t0 = torch.tensor([c["t0"]], dtype=torch.float32, device=dev)
+        beta = torch.tensor([c["beta"]], dtype=torch.int32, device=dev)
+        keep = torch.zeros(1, dtype=torch.float32, device=dev)
+        bad = torch.zeros(1, dtype=torch.int32, device=dev)
+        slonn.slonn_policy_keep_lcao(p2, 1, tau, 0, t0, 0, beta, 0, keep, None, bad)
+        assert keep.item() == np.float32(c["keep"]) and bool(bad.item()) == c["violated"]
+
+
+def test_policy_tables_and_decisions_match_oracle(rt, oracle):
+    """Confidence tables trained on the device from random keys: estimates bit for bit equal
+    to the oracle's (double sums in the same order), same ACLO and LCAO decisions; sizes span
+    many 64-input chunks with a ragged tail, empty buckets and heavily loaded ones."""
+    import torch
+    from paper_2204_08400_amd import slonn
+    dev = "cuda:0"
+    rng = np.random.default_rng(21)
+    for K, L, G, N, B in [(8, 16, 5, 10000, 777), (3, 2, 1, 70, 5), (10, 32, 16, 4133, 300), (12, 5, 7, 999, 64)]:
+        _say(f"policy K={K} L={L} G={G} N={N} B={B}")
+        grid = np.sort(rng.choice(np.arange(1, 200), size=G, replace=False)).astype(np.float32) / 200.0
+        # skewed keys: a few heavy buckets and many empty ones
+        keys = (rng.integers(0, 1 << K, size=(N, L)) * rng.integers(0, 2, size=(N, L))).astype(np.uint32)
+        conf = rng.normal(-2.0, 1.0, size=(N, G)).astype(np.float32)
+        ot = oracle.ConfidenceTables(K, L, grid, keys, conf)
+        p = slonn.slonn_policy_create(K, L, grid.tolist())
+        slonn.slonn_policy_train_confidence(p, torch.from_numpy(keys.view(np.int32)).to(dev),
+                                            torch.from_numpy(conf).to(dev), N)
+        Q = rng.integers(0, 1 << K, size=(B, L)).astype(np.uint32)
+        Q[: B // 2] = keys[rng.integers(0, N, B // 2)]         # half the queries land in trained buckets
+        chat_ref, _ = ot.estimate(Q)
+        thr = rng.normal(-2.0, 0.5, B).astype(np.float32)
+        thr[:3] = chat_ref[:3, 0].astype(np.float32)            # thresholds right at an estimate
+        keep_ref, g_ref = ot.choose_aclo(Q, thr)
+        keep = torch.zeros(B, dtype=torch.float32, device=dev)
+        gi = torch.zeros(B, dtype=torch.int32, device=dev)
+        chat = torch.zeros((B, G), dtype=torch.float64, device=dev)
+        slonn.slonn_policy_keep_aclo(p, torch.from_numpy(Q.view(np.int32)).to(dev), B,
+                                     torch.from_numpy(thr).to(dev), 1, keep, gi, chat)
+        assert np.array_equal(chat.cpu().numpy(), chat_ref)
+        assert np.array_equal(gi.cpu().numpy(), g_ref)
+        assert np.array_equal(keep.cpu().numpy(), keep_ref)
+        # LCAO on the same grid
+        nbeta = 4
+        T = np.sort(rng.uniform(0.05, 3.0, size=(nbeta, G)).astype(np.float32), axis=1)
+        slonn.slonn_policy_set_latency_profile(p, T.tolist())
+        tau = rng.uniform(0.0, 4.0, B).astype(np.float32)
+        t0 = rng.uniform(0.0, 0.5, B).astype(np.float32)
+        beta = rng.integers(0, nbeta, B).astype(np.int32)
+        k_ref, g2_ref, bad_ref = oracle.choose_lcao(grid, T, tau, t0, beta)
+        bad = torch.zeros(B, dtype=torch.int32, device=dev)
+        slonn.slonn_policy_keep_lcao(p, B, torch.from_numpy(tau).to(dev), 1, torch.from_numpy(t0).to(dev), 1,
+                                     torch.from_numpy(beta).to(dev), 1, keep, gi, bad)
+        assert np.array_equal(keep.cpu().numpy(), k_ref)
+        assert np.array_equal(gi.cpu().numpy(), g2_ref)
+        assert np.array_equal(bad.cpu().numpy().astype(bool), bad_ref)
+
+
+@pytest.mark.parametrize("path", ["layers", "fused"])
+def test_forward_under_aclo_matches_oracle(rt, oracle, path):
+    """Fig. 2 with the choice of k inside the pass: the first activated layer's keys pick k
+    from the Confidence LSH tables, the pass continues with that k on every layer."""
+    import torch
+    from paper_2204_08400_amd import slonn
+    dims = (96, 1000, 640, 12)
+    K, L = 6, 10
+    layers, net, Xb = make_case(oracle, dims, K, L, seed=101, N_build=300, kind="u01", last_act=wl.ACT_SOFTMAX)
+    g = _gpu_net(rt, layers, net, path=path)
+    rng = np.random.default_rng(22)
+    grid = np.asarray([0.03, 0.1, 0.25, 0.5, 1.0], np.float32)
+    # training keys from the device (slonn_select's codes), confidences synthetic
+    sel = g.select(0, Xb, 0.5)
+    tkeys_gpu = sel["codes"].cpu().numpy().view(np.uint32)
+    tkeys, ttie = net.first_codes(Xb)
+    assert np.array_equal(tkeys_gpu[~ttie], tkeys[~ttie])
+    conf = _dyadic_conf(rng, (Xb.shape[0], grid.size))
+    ot = oracle.ConfidenceTables(K, L, grid, tkeys, conf)
+    p = slonn.slonn_policy_create(K, L, grid.tolist())
+    slonn.slonn_policy_train_confidence(p, torch.from_numpy(tkeys.view(np.int32)).cuda(),
+                                        torch.from_numpy(conf).cuda(), Xb.shape[0])
+    B = 150
+    X = make_queries(dims, B, seed=102, kind="u01")
+    for thr in (-4.0, rng.uniform(-7.0, -1.0, B).astype(np.float32)):
+        _say(f"ACLO forward path={path} thr={'per query' if np.ndim(thr) else thr}")
+        ref = net.sparse_forward_aclo(X, ot, thr)
+        tt = _keep_tensor(thr) if np.ndim(thr) else thr
+        got = to_numpy_result(g.sparse_forward(X, None, taps=True, policy=p, thr=tt))
+        keep = g.sparse_forward(X, None, policy=p, thr=tt)["keep"].cpu().numpy()
+        ok = ~ref["layers"][0]["tie"]
+        assert np.array_equal(keep[ok], ref["keep"][ok])
+        assert len(set(ref["keep"].tolist())) > 1
+        _say(f"  {compare_sparse(got, ref, layers, 'aclo ' + path)}")

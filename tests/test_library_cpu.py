@@ -93,6 +93,13 @@ def test_null_handles_are_rejected(slonn):
     assert lib.slonn_model_set_path(None, 0) == slonn.EINVAL
     assert lib.slonn_model_set_hash_nodes_always_active(None, 1) == slonn.EINVAL
     assert lib.slonn_model_destroy(None) == 0 and lib.slonn_tables_destroy(None) == 0
+    assert lib.slonn_policy_destroy(None) == 0
+    assert lib.slonn_policy_train_confidence(None, None, None, C.c_int64(1), None) == slonn.EINVAL
+    assert lib.slonn_policy_set_latency_profile(None, None, 1) == slonn.EINVAL
+    assert lib.slonn_policy_keep_aclo(None, None, 1, None, 0, None, None, None, None) == slonn.EINVAL
+    assert lib.slonn_policy_keep_lcao(None, 1, None, 0, None, 0, None, 0, None, None, None, None) == slonn.EINVAL
+    assert lib.slonn_sparse_forward_aclo(None, None, None, None, 1, None, 0, None, None, None, None,
+                                         C.c_size_t(0), None) == slonn.EINVAL
     assert slonn.load().slonn_last_error()
 
 
@@ -102,3 +109,20 @@ def test_binding_fails_loudly_without_library(slonn, monkeypatch, tmp_path):
     monkeypatch.setattr(slonn, "_lib", None)
     with pytest.raises(FileNotFoundError):
         slonn.load()
+
+
+@pytest.mark.parametrize("K,L,grid", [
+    (0, 4, [0.5]), (17, 4, [0.5]), (4, 0, [0.5]), (4, 65, [0.5]),          # K, L out of range
+    (4, 4, []), (4, 4, [0.1] * 17),                                         # grid size
+    (4, 4, [0.0, 0.5]), (4, 4, [0.5, 1.5]), (4, 4, [0.5, 0.5]), (4, 4, [0.5, 0.25]),   # values, order
+    (4, 4, [float("nan")]),
+])
+def test_policy_create_rejects(slonn, K, L, grid):
+    """argument checks that come before any device memory is touched"""
+    lib = slonn.load()
+    arr = (C.c_float * max(len(grid), 1))(*grid)
+    h = C.c_void_p()
+    assert lib.slonn_policy_create(K, L, arr, len(grid), C.byref(h)) == slonn.EINVAL
+    assert not h.value
+    assert lib.slonn_policy_create(4, 4, None, 1, C.byref(h)) == slonn.EINVAL
+    assert lib.slonn_policy_create(4, 4, arr, 1, None) == slonn.EINVAL
