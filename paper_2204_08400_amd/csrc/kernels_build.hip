@@ -8,6 +8,7 @@
 // This is set-up work and is not timed; it favours determinism and small code.
 #include <algorithm>
 
+#include "bucket_lists.h"
 #include "slonn_internal.h"
 
 namespace slonn {
@@ -25,25 +26,6 @@ __global__ void keys_kernel(const float* __restrict__ Z, int K, int L, int64_t N
   keys[e] = key;
 }
 
-__global__ void histogram_kernel(const uint32_t* __restrict__ keys, int L, int b, int64_t N,
-                                 uint32_t* __restrict__ hist) {
-  const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (x < N) atomicAdd(&hist[keys[x * L + b]], 1u);
-}
-
-// members of each bucket in ascending input order; start[] are exclusive prefix sums of hist
-__global__ void bucket_members_kernel(const uint32_t* __restrict__ keys, int L, int b, int64_t N,
-                                      const uint32_t* __restrict__ start, int nb,
-                                      uint32_t* __restrict__ members) {
-  const int key = blockIdx.x * blockDim.x + threadIdx.x;
-  if (key >= nb) return;
-  uint32_t at = start[key];
-  const uint32_t end = start[key + 1];
-  if (at == end) return;
-  for (int64_t x = 0; x < N && at < end; ++x)
-    if (keys[x * L + b] == (uint32_t)key) members[at++] = (uint32_t)x;
-}
-
 // NodeScore[key][j] = sum of act[x][j] over the bucket's members, in order
 __global__ void node_score_kernel(const float* __restrict__ act, int n, const uint32_t* __restrict__ start,
                                   const uint32_t* __restrict__ members, double* __restrict__ score,
@@ -52,7 +34,16 @@ __global__ void node_score_kernel(const float* __restrict__ act, int n, const ui
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
   double s = 0.0;
-  for (uint32_t i = start[key]; i < start[key + 1]; ++i) s += (double)act[(size_t)members[i] * n + j];
+  uint32_t i = start[key];
+  const uint32_t end = start[key + 1];
+  for (; i + 8 <= end; i += 8) {        // eight loads in flight, added in input order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = act[(size_t)members[i + u] * n + j];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += (double)v[u];
+  }
+  for (; i < end; ++i) s += (double)act[(size_t)members[i] * n + j];
   score[(size_t)key * n + j] = s;
   if (s > 0.0) atomicAdd(&npos[key], 1u);
 }
@@ -62,8 +53,55 @@ __global__ void total_score_kernel(const float* __restrict__ act, int n, int64_t
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
   double s = 0.0;
-  for (int64_t x = 0; x < N; ++x) s += (double)act[x * n + j];
+  int64_t x = 0;
+  for (; x + 8 <= N; x += 8) {          // eight loads in flight, added in input order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = act[(x + u) * n + j];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += (double)v[u];
+  }
+  for (; x < N; ++x) s += (double)act[x * n + j];
   score[j] = s;
+}
+
+// List lengths and places of one table: len[k] = min(npos[k], cap), off[k] = running offset
+// into the id array (continuing from *base, which is advanced by the table's total), and the
+// table's directory row dir[0..nb].  One workgroup.
+__global__ __launch_bounds__(256) void layout_kernel(const uint32_t* __restrict__ npos, int nb, uint32_t cap,
+                                                    uint32_t* __restrict__ base, uint32_t* __restrict__ off,
+                                                    uint32_t* __restrict__ len, uint32_t* __restrict__ dir) {
+  __shared__ uint32_t wsum[4];
+  __shared__ uint32_t carry_s;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) carry_s = base[0];
+  __syncthreads();
+  for (int k0 = 0; k0 < nb; k0 += 256) {
+    const int k = k0 + tid;
+    const uint32_t v = k < nb ? min(npos[k], cap) : 0u;
+    uint32_t incl = v;
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    uint32_t before = carry_s;
+    for (int w = 0; w < wave; ++w) before += wsum[w];
+    if (k < nb) { len[k] = v; off[k] = before + incl - v; dir[k] = before + incl - v; }
+    __syncthreads();
+    if (tid == 0) carry_s += wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    __syncthreads();
+  }
+  if (tid == 0) { dir[nb] = carry_s; base[0] = carry_s; }
+}
+
+// number of non-empty buckets over all tables
+__global__ void count_nonempty_kernel(const uint32_t* __restrict__ hist, int64_t cells, unsigned long long* out) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool ne = e < cells && hist[e] != 0u;
+  const unsigned long long votes = __ballot(ne);
+  if ((threadIdx.x & 63) == 0 && votes) atomicAdd(out, (unsigned long long)__popcll(votes));
 }
 
 __device__ __forceinline__ bool ranks_before(int a, int b, const double* sc) {
@@ -74,22 +112,35 @@ __device__ __forceinline__ bool ranks_before(int a, int b, const double* sc) {
   return sa > sb || (sa == sb && a < b);
 }
 
-// Bitonic sort of one bucket's node ids in LDS; scores stay in global memory (L2).
-// positive_only: nodes with a sum <= 0 are left out.  Writes the first out_len[bucket]
-// ids at out + out_off[bucket].
+__device__ __forceinline__ bool pair_before(double sa, int a, double sb, int b) {
+  if (a < 0) return false;
+  if (b < 0) return true;
+  return sa > sb || (sa == sb && a < b);
+}
+
+// Bitonic sort of one bucket's (score, node id) pairs in LDS (12 bytes per node: P doubles,
+// then P ids).  positive_only: nodes with a sum <= 0 are left out.  Writes the first
+// out_len[bucket] ids at out + out_off[bucket].
 __global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ score, int n, int P,
                                                   int positive_only, const uint32_t* __restrict__ out_off,
                                                   const uint32_t* __restrict__ out_len,
                                                   int32_t* __restrict__ out) {
-  __shared__ int32_t ids[SORT_MAX];
+  extern __shared__ __align__(16) unsigned char rank_smem[];
+  double* key = reinterpret_cast<double*>(rank_smem);
+  int32_t* ids = reinterpret_cast<int32_t*>(key + P);
   const int bucket = blockIdx.x;
   const uint32_t len = out_len[bucket];
   if (len == 0) return;
   const double* sc = score + (size_t)bucket * n;
   for (int i = threadIdx.x; i < P; i += 256) {
     int v = -1;
-    if (i < n && (!positive_only || sc[i] > 0.0)) v = i;
+    double sv = 0.0;
+    if (i < n) {
+      sv = sc[i];
+      if (!positive_only || sv > 0.0) v = i;
+    }
     ids[i] = v;
+    key[i] = sv;
   }
   __syncthreads();
   for (int k = 2; k <= P; k <<= 1) {
@@ -99,9 +150,10 @@ __global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ sc
         const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
         const int p = i | j;
         const int a = ids[i], b = ids[p];
+        const double sa = key[i], sb = key[p];
         const bool up = (i & k) == 0;          // ascending block: best first
-        const bool swap = up ? ranks_before(b, a, sc) : ranks_before(a, b, sc);
-        if (swap) { ids[i] = b; ids[p] = a; }
+        const bool swap = up ? pair_before(sb, b, sa, a) : pair_before(sa, a, sb, b);
+        if (swap) { ids[i] = b; ids[p] = a; key[i] = sb; key[p] = sa; }
       }
       __syncthreads();
     }
@@ -231,13 +283,16 @@ void free_table_set(TableSet* ts) {
   ts->d_dir = nullptr; ts->d_ids = nullptr; ts->d_global_rank = nullptr;
 }
 
-int upload_table_set(TableSet* ts) {
+int upload_table_set(TableSet* ts, const int32_t* d_ids_src) {
+  if (!d_ids_src) ts->n_ids = ts->ids.size();
   SLONN_HIP(hipMalloc(&ts->d_dir, std::max<size_t>(ts->dir.size(), 1) * 4));
-  SLONN_HIP(hipMalloc(&ts->d_ids, std::max<size_t>(ts->ids.size(), 1) * 4));
+  SLONN_HIP(hipMalloc(&ts->d_ids, std::max<size_t>(ts->n_ids, 1) * 4));
   SLONN_HIP(hipMalloc(&ts->d_global_rank, std::max<size_t>(ts->global_rank.size(), 1) * 4));
   SLONN_HIP(hipMemcpy(ts->d_dir, ts->dir.data(), ts->dir.size() * 4, hipMemcpyHostToDevice));
-  if (!ts->ids.empty())
-    SLONN_HIP(hipMemcpy(ts->d_ids, ts->ids.data(), ts->ids.size() * 4, hipMemcpyHostToDevice));
+  if (ts->n_ids)
+    SLONN_HIP(hipMemcpy(ts->d_ids, d_ids_src ? d_ids_src : ts->ids.data(), ts->n_ids * 4,
+                        d_ids_src ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice));
+  std::vector<int32_t>().swap(ts->ids);        // the lists live on the device from here on
   SLONN_HIP(hipMemcpy(ts->d_global_rank, ts->global_rank.data(), ts->global_rank.size() * 4,
                       hipMemcpyHostToDevice));
   return SLONN_OK;
@@ -257,6 +312,10 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
   while (P < n) P <<= 1;
   if (P < 2) P = 2;
   const int cap = std::min(Ly.list_cap, n);
+  const size_t rank_lds = (size_t)P * 12;           // (score, id) pairs of the LDS sort
+  if (!wide && rank_lds > 65536)
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)rank_lds));
 
   ts->layer = layer; ts->K = K; ts->L = L; ts->n = n; ts->list_cap = Ly.list_cap;
   ts->dir.assign((size_t)L * (nb + 1), 0);
@@ -264,7 +323,8 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
   ts->global_rank.assign(n, 0);
 
   DevBuf<float> Z;
-  DevBuf<uint32_t> keys, hist, start, members, npos, off, len;
+  DevBuf<uint32_t> keys, hist, start, cursor, members, npos, off, len, dir, base;
+  DevBuf<unsigned long long> nonempty;
   DevBuf<double> score;
   DevBuf<int32_t> out;
   DevBuf<int> fail;
@@ -272,68 +332,70 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
   SLONN_HIP(hipMemsetAsync(fail.p, 0, sizeof(int), s));
   SLONN_HIP(Z.alloc((size_t)N * H));
   SLONN_HIP(keys.alloc((size_t)N * L));
-  SLONN_HIP(hist.alloc(nb));
-  SLONN_HIP(start.alloc(nb + 1));
-  SLONN_HIP(members.alloc(N));
-  SLONN_HIP(npos.alloc(nb));
+  SLONN_HIP(hist.alloc((size_t)L * nb));
+  SLONN_HIP(start.alloc((size_t)L * (nb + 1)));
+  SLONN_HIP(cursor.alloc((size_t)L * nb));
+  SLONN_HIP(members.alloc((size_t)L * N));
+  SLONN_HIP(npos.alloc((size_t)L * nb));
   SLONN_HIP(off.alloc(nb));
   SLONN_HIP(len.alloc(nb));
+  SLONN_HIP(dir.alloc((size_t)L * (nb + 1)));
+  SLONN_HIP(base.alloc(1));
+  SLONN_HIP(nonempty.alloc(1));
   SLONN_HIP(score.alloc((size_t)nb * n));
-  SLONN_HIP(out.alloc((size_t)std::min<int64_t>(nb, N) * cap));
 
   int rc = launch_hash_project(X_l, Ly.d_in, Ly.Wh, Ly.bh, Z.p, (int)N, H, Ly.d_in, s);
   if (rc) return rc;
-  {
-    const int64_t tot = N * L;
-    hipLaunchKernelGGL(keys_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s, Z.p, K, L, N, keys.p);
-    SLONN_HIP(hipGetLastError());
-  }
+  const int64_t tot_keys = N * L;
+  hipLaunchKernelGGL(keys_kernel, dim3((unsigned)((tot_keys + 255) / 256)), dim3(256), 0, s, Z.p, K, L, N, keys.p);
+  SLONN_HIP(hipGetLastError());
 
-  std::vector<uint32_t> h_hist(nb), h_start(nb + 1), h_npos(nb), h_off(nb), h_len(nb);
-  std::vector<int32_t> h_out;
-  uint32_t base = 0;
+  // bucket member lists of all L tables at once
+  SLONN_HIP(hipMemsetAsync(hist.p, 0, (size_t)L * nb * 4, s));
+  SLONN_HIP(hipMemsetAsync(npos.p, 0, (size_t)L * nb * 4, s));
+  SLONN_HIP(hipMemsetAsync(base.p, 0, 4, s));
+  SLONN_HIP(hipMemsetAsync(nonempty.p, 0, 8, s));
+  hipLaunchKernelGGL(bucket_hist_kernel, dim3((unsigned)((tot_keys + 255) / 256)), dim3(256), 0, s, keys.p, N, L, nb,
+                     hist.p);
+  SLONN_HIP(hipGetLastError());
+  hipLaunchKernelGGL(bucket_scan_kernel, dim3(L), dim3(256), 0, s, hist.p, nb, start.p, cursor.p);
+  SLONN_HIP(hipGetLastError());
+  hipLaunchKernelGGL(bucket_members_kernel, dim3(L), dim3(64), 0, s, keys.p, N, L, K, nb, cursor.p, members.p);
+  SLONN_HIP(hipGetLastError());
+  const int64_t cells = (int64_t)L * nb;
+  hipLaunchKernelGGL(count_nonempty_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, s, hist.p, cells,
+                     nonempty.p);
+  SLONN_HIP(hipGetLastError());
+  // every non-empty bucket keeps at most cap ids: size the id array once, for all tables
+  unsigned long long h_nonempty = 0;
+  SLONN_HIP(hipMemcpyAsync(&h_nonempty, nonempty.p, 8, hipMemcpyDeviceToHost, s));
+  SLONN_HIP(hipStreamSynchronize(s));
+  const unsigned long long id_bound = h_nonempty * (unsigned long long)cap;
+  if (id_bound > 0xFFFFFFFFull)
+    SLONN_FAIL(SLONN_EUNSUPPORTED, "build: layer %d: up to %llu list entries do not fit 32-bit offsets", layer,
+               id_bound);
+  SLONN_HIP(out.alloc((size_t)id_bound));
+
+  // per table: NodeScore sums, list lengths and places, ranking -- no host round trip
   for (int b = 0; b < L; ++b) {
-    SLONN_HIP(hipMemsetAsync(hist.p, 0, (size_t)nb * 4, s));
-    SLONN_HIP(hipMemsetAsync(npos.p, 0, (size_t)nb * 4, s));
-    hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, keys.p, L, b, N,
-                       hist.p);
+    const uint32_t* st = start.p + (size_t)b * (nb + 1);
+    hipLaunchKernelGGL(node_score_kernel, dim3((n + 255) / 256, nb), dim3(256), 0, s, act, n, st,
+                       members.p + (size_t)b * N, score.p, npos.p + (size_t)b * nb);
     SLONN_HIP(hipGetLastError());
-    SLONN_HIP(hipMemcpyAsync(h_hist.data(), hist.p, (size_t)nb * 4, hipMemcpyDeviceToHost, s));
-    SLONN_HIP(hipStreamSynchronize(s));
-    h_start[0] = 0;
-    for (int k = 0; k < nb; ++k) h_start[k + 1] = h_start[k] + h_hist[k];
-    SLONN_HIP(hipMemcpyAsync(start.p, h_start.data(), (size_t)(nb + 1) * 4, hipMemcpyHostToDevice, s));
-    hipLaunchKernelGGL(bucket_members_kernel, dim3((nb + 63) / 64), dim3(64), 0, s, keys.p, L, b, N, start.p,
-                       nb, members.p);
+    hipLaunchKernelGGL(layout_kernel, dim3(1), dim3(256), 0, s, npos.p + (size_t)b * nb, nb, (uint32_t)cap, base.p,
+                       off.p, len.p, dir.p + (size_t)b * (nb + 1));
     SLONN_HIP(hipGetLastError());
-    hipLaunchKernelGGL(node_score_kernel, dim3((n + 255) / 256, nb), dim3(256), 0, s, act, n, start.p,
-                       members.p, score.p, npos.p);
+    if (wide)
+      hipLaunchKernelGGL(rank_wide_kernel, dim3(nb), dim3(256), 0, s, score.p, n, off.p, len.p, out.p, fail.p);
+    else
+      hipLaunchKernelGGL(rank_kernel, dim3(nb), dim3(256), rank_lds, s, score.p, n, P, 1, off.p, len.p, out.p);
     SLONN_HIP(hipGetLastError());
-    SLONN_HIP(hipMemcpyAsync(h_npos.data(), npos.p, (size_t)nb * 4, hipMemcpyDeviceToHost, s));
-    SLONN_HIP(hipStreamSynchronize(s));
-    uint32_t tot = 0;
-    for (int k = 0; k < nb; ++k) {
-      h_len[k] = std::min<uint32_t>(h_npos[k], (uint32_t)cap);
-      h_off[k] = tot;
-      ts->dir[(size_t)b * (nb + 1) + k] = base + tot;
-      tot += h_len[k];
-    }
-    ts->dir[(size_t)b * (nb + 1) + nb] = base + tot;
-    if (tot > 0) {
-      SLONN_HIP(hipMemcpyAsync(off.p, h_off.data(), (size_t)nb * 4, hipMemcpyHostToDevice, s));
-      SLONN_HIP(hipMemcpyAsync(len.p, h_len.data(), (size_t)nb * 4, hipMemcpyHostToDevice, s));
-      if (wide)
-        hipLaunchKernelGGL(rank_wide_kernel, dim3(nb), dim3(256), 0, s, score.p, n, off.p, len.p, out.p, fail.p);
-      else
-        hipLaunchKernelGGL(rank_kernel, dim3(nb), dim3(256), 0, s, score.p, n, P, 1, off.p, len.p, out.p);
-      SLONN_HIP(hipGetLastError());
-      h_out.resize(tot);
-      SLONN_HIP(hipMemcpyAsync(h_out.data(), out.p, (size_t)tot * 4, hipMemcpyDeviceToHost, s));
-      SLONN_HIP(hipStreamSynchronize(s));
-      ts->ids.insert(ts->ids.end(), h_out.begin(), h_out.end());
-    }
-    base += tot;
   }
+  uint32_t h_total = 0;
+  SLONN_HIP(hipMemcpyAsync(&h_total, base.p, 4, hipMemcpyDeviceToHost, s));
+  SLONN_HIP(hipMemcpyAsync(ts->dir.data(), dir.p, (size_t)L * (nb + 1) * 4, hipMemcpyDeviceToHost, s));
+  SLONN_HIP(hipStreamSynchronize(s));
+  ts->n_ids = h_total;                          // the lists stay on the device (export copies them out)
 
   // whole-set ranking: every node, zero sums included
   hipLaunchKernelGGL(total_score_kernel, dim3((n + 255) / 256), dim3(256), 0, s, act, n, N, score.p);
@@ -352,18 +414,18 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
       if (h_score[a] != h_score[b]) return h_score[a] > h_score[b];
       return a < b;
     });
-    return upload_table_set(ts);
+    return upload_table_set(ts, out.p);
   }
   const uint32_t zero = 0, all = (uint32_t)n;
   SLONN_HIP(hipMemcpyAsync(off.p, &zero, 4, hipMemcpyHostToDevice, s));
   SLONN_HIP(hipMemcpyAsync(len.p, &all, 4, hipMemcpyHostToDevice, s));
   DevBuf<int32_t> gr;
   SLONN_HIP(gr.alloc(n));
-  hipLaunchKernelGGL(rank_kernel, dim3(1), dim3(256), 0, s, score.p, n, P, 0, off.p, len.p, gr.p);
+  hipLaunchKernelGGL(rank_kernel, dim3(1), dim3(256), rank_lds, s, score.p, n, P, 0, off.p, len.p, gr.p);
   SLONN_HIP(hipGetLastError());
   SLONN_HIP(hipMemcpyAsync(ts->global_rank.data(), gr.p, (size_t)n * 4, hipMemcpyDeviceToHost, s));
   SLONN_HIP(hipStreamSynchronize(s));
-  return upload_table_set(ts);
+  return upload_table_set(ts, out.p);
 }
 
 }  // namespace slonn

@@ -245,4 +245,29 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
   return SLONN_OK;
 }
 
+// FreeHash rows are borrowed from the layer itself (Def. 2): copy them once into one contiguous
+// fp32 matrix so that the projection reads a dense operand.
+namespace {
+__global__ void gather_hash_rows_kernel(const void* __restrict__ W, int w_dtype, const float* __restrict__ bias,
+                                        const int32_t* __restrict__ hnodes, int d, float* __restrict__ Wh,
+                                        float* __restrict__ bh) {
+  const int h = blockIdx.x;
+  const size_t row = (size_t)hnodes[h] * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    float v;
+    if (w_dtype == SLONN_F32) v = static_cast<const float*>(W)[row + i];
+    else v = __uint_as_float((uint32_t) static_cast<const uint16_t*>(W)[row + i] << 16);
+    Wh[(size_t)h * d + i] = v;
+  }
+  if (threadIdx.x == 0) bh[h] = bias[hnodes[h]];
+}
+}  // namespace
+
+int launch_gather_hash_rows(const void* W, int w_dtype, const float* bias, const int32_t* hnodes, int H, int d,
+                            float* Wh, float* bh, hipStream_t s) {
+  hipLaunchKernelGGL(gather_hash_rows_kernel, dim3(H), dim3(256), 0, s, W, w_dtype, bias, hnodes, d, Wh, bh);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
 }  // namespace slonn

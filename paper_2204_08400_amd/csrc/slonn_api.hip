@@ -226,37 +226,20 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
   if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
     m->n_cu = v;
 
-  // library-owned fp32 copies of the FreeHash rows, gathered once
+  // library-owned fp32 copies of the FreeHash rows, gathered once (on the device)
   for (Layer& L : m->layers) {
     if (!L.activated()) continue;
     const int H = L.H();
-    const size_t esz = L.w_dtype == SLONN_F32 ? 4 : 2;
-    std::vector<char> row((size_t)L.d_in * esz);
-    std::vector<float> wh((size_t)H * L.d_in), bh(H);
-    for (int h = 0; h < H; ++h) {
-      const char* src = static_cast<const char*>(L.W) + (size_t)L.hash_nodes[h] * L.d_in * esz;
-      e = hipMemcpy(row.data(), src, row.size(), hipMemcpyDeviceToHost);
-      if (e == hipSuccess)
-        e = hipMemcpy(&bh[h], L.bias + L.hash_nodes[h], sizeof(float), hipMemcpyDeviceToHost);
-      if (e != hipSuccess) {
-        set_error("copying FreeHash rows failed: %s", hipGetErrorString(e));
-        return fail(SLONN_EHIP);
-      }
-      for (int i = 0; i < L.d_in; ++i) {
-        if (L.w_dtype == SLONN_F32) {
-          std::memcpy(&wh[(size_t)h * L.d_in + i], row.data() + (size_t)i * 4, 4);
-        } else {
-          uint16_t b;
-          std::memcpy(&b, row.data() + (size_t)i * 2, 2);
-          uint32_t u = (uint32_t)b << 16;
-          std::memcpy(&wh[(size_t)h * L.d_in + i], &u, 4);
-        }
-      }
+    if ((e = hipMalloc(&L.Wh, (size_t)H * L.d_in * 4)) != hipSuccess ||
+        (e = hipMalloc(&L.bh, (size_t)H * 4)) != hipSuccess ||
+        (e = hipMalloc(&L.hnodes, (size_t)H * 4)) != hipSuccess ||
+        (e = hipMemcpy(L.hnodes, L.hash_nodes.data(), (size_t)H * 4, hipMemcpyHostToDevice)) != hipSuccess) {
+      set_error("allocating the FreeHash rows failed: %s", hipGetErrorString(e));
+      return fail(SLONN_EHIP);
     }
-    if ((e = hipMalloc(&L.Wh, wh.size() * 4)) != hipSuccess || (e = hipMalloc(&L.bh, bh.size() * 4)) != hipSuccess ||
-        (e = hipMemcpy(L.Wh, wh.data(), wh.size() * 4, hipMemcpyHostToDevice)) != hipSuccess ||
-        (e = hipMemcpy(L.bh, bh.data(), bh.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) {
-      set_error("uploading FreeHash rows failed: %s", hipGetErrorString(e));
+    if (launch_gather_hash_rows(L.W, L.w_dtype, L.bias, L.hnodes, H, L.d_in, L.Wh, L.bh, nullptr) != SLONN_OK ||
+        (e = hipStreamSynchronize(nullptr)) != hipSuccess) {
+      if (e != hipSuccess) set_error("copying FreeHash rows failed: %s", hipGetErrorString(e));
       return fail(SLONN_EHIP);
     }
     // node -> hash row (K*L <= 1024 fits 16 bits): lets the forward pass take a selected hash
@@ -266,11 +249,6 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
     if ((e = hipMalloc(&L.hslot, hslot.size() * 2)) != hipSuccess ||
         (e = hipMemcpy(L.hslot, hslot.data(), hslot.size() * 2, hipMemcpyHostToDevice)) != hipSuccess) {
       set_error("uploading the hash-node map failed: %s", hipGetErrorString(e));
-      return fail(SLONN_EHIP);
-    }
-    if ((e = hipMalloc(&L.hnodes, (size_t)H * 4)) != hipSuccess ||
-        (e = hipMemcpy(L.hnodes, L.hash_nodes.data(), (size_t)H * 4, hipMemcpyHostToDevice)) != hipSuccess) {
-      set_error("uploading the hash-node ids failed: %s", hipGetErrorString(e));
       return fail(SLONN_EHIP);
     }
   }
@@ -364,7 +342,7 @@ int slonn_tables_export(const slonn_tables* t, void* host_buf, size_t* bytes) {
   if (!t || !bytes) SLONN_FAIL(SLONN_EINVAL, "null argument");
   size_t need = 16;
   for (const TableSet& s : t->sets)
-    need += 32 + 4 * ((size_t)s.K * s.L + s.dir.size() + s.ids.size() + s.global_rank.size());
+    need += 32 + 4 * ((size_t)s.K * s.L + s.dir.size() + s.n_ids + s.global_rank.size());
   if (!host_buf) {
     *bytes = need;
     return SLONN_OK;
@@ -379,12 +357,15 @@ int slonn_tables_export(const slonn_tables* t, void* host_buf, size_t* bytes) {
   put(head, 16);
   for (const TableSet& s : t->sets) {
     const uint32_t h[8] = {(uint32_t)s.layer, (uint32_t)s.K, (uint32_t)s.L, (uint32_t)s.n,
-                           (uint32_t)s.list_cap, (uint32_t)s.ids.size(), 0, 0};
+                           (uint32_t)s.list_cap, (uint32_t)s.n_ids, 0, 0};
     put(h, 32);
     const Layer& L = t->model->layers[s.layer];
     put(L.hash_nodes.data(), 4 * L.hash_nodes.size());
     put(s.dir.data(), 4 * s.dir.size());
-    put(s.ids.data(), 4 * s.ids.size());
+    if (s.n_ids) {                              // the lists are held on the device only
+      SLONN_HIP(hipMemcpy(p, s.d_ids, 4 * s.n_ids, hipMemcpyDeviceToHost));
+      p += 4 * s.n_ids;
+    }
     put(s.global_rank.data(), 4 * s.global_rank.size());
   }
   *bytes = need;

@@ -48,7 +48,9 @@ struct Layer {
 struct TableSet {                 // Node Importance tables of one layer
   int layer = -1, K = 0, L = 0, n = 0, list_cap = 0;
   std::vector<uint32_t> dir;      // host copy [L][2^K+1]
-  std::vector<int32_t> ids, global_rank;
+  std::vector<int32_t> ids;       // host staging of the lists (import only; emptied after the upload)
+  std::vector<int32_t> global_rank;
+  size_t n_ids = 0;               // list entries held in d_ids
   uint32_t* d_dir = nullptr;      // device copies
   int32_t* d_ids = nullptr;
   int32_t* d_global_rank = nullptr;
@@ -225,12 +227,18 @@ void policy_fused_args(const slonn_policy* p, PolicyArgs* a);
 bool policy_matches(const slonn_policy* p, int K, int L);
 bool policy_trained(const slonn_policy* p);
 
+// Wh[h][0..d) = row hnodes[h] of W widened to fp32, bh[h] = bias[hnodes[h]] (model set-up).
+int launch_gather_hash_rows(const void* W, int w_dtype, const float* bias, const int32_t* hnodes, int H, int d,
+                            float* Wh, float* bh, hipStream_t s);
+
 int launch_fill_iota(int32_t* idx, int stride, int32_t* cnt, int n, int B, hipStream_t s);
 
 // Alg. 1 on the device for one layer; fills ts (host + device copies).
 int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_t N, const float* act,
                        TableSet* ts, hipStream_t s);
-int upload_table_set(TableSet* ts);
+// device copies from the host vectors; the lists come from d_ids_src (device, ts->n_ids
+// entries) when given, else from ts->ids
+int upload_table_set(TableSet* ts, const int32_t* d_ids_src = nullptr);
 void free_table_set(TableSet* ts);
 
 }  // namespace slonn
