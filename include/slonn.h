@@ -58,6 +58,7 @@ enum { SLONN_DENSE = 0, SLONN_ELL = 1 };                /* first-layer input for
 typedef struct slonn_model slonn_model;
 typedef struct slonn_tables slonn_tables;
 typedef struct slonn_policy slonn_policy;
+typedef struct slonn_graph slonn_graph;
 
 /* One fully-connected layer y = act(W x + b).  Activations are always fp32.
  * W: device, BORROWED for the lifetime of the model.  ROWS_ARE_NODES: [d_out][d_in],
@@ -260,6 +261,19 @@ int slonn_sparse_forward_aclo(const slonn_model* m, const slonn_tables* t, const
                               const slonn_input* X, int B, const float* thr, int thr_stride, float* keep_out,
                               slonn_output* Y, const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
                               void* stream);
+
+/* A recorded forward pass, for batches so small that launching dominates (the paper serves one
+ * query at a time, Section 4): create runs slonn_sparse_forward once with the given arguments
+ * (same meaning, no debug taps) and then records the same call into a HIP graph; launch replays
+ * it on `stream` as one submission.  Every pointer is baked in: between launches the caller
+ * rewrites the input (X), keep and reads the output buffers in place; model, tables, workspace and
+ * buffers must outlive the graph, and launches of one graph must not overlap.  The recording
+ * holds kernel launches only (no memory-set nodes).  EINVAL also while per-kernel timing is on. */
+int slonn_forward_graph_create(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
+                               const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
+                               void* workspace, size_t ws_bytes, slonn_graph** out);
+int slonn_forward_graph_launch(slonn_graph* g, void* stream);
+int slonn_forward_graph_destroy(slonn_graph* g);
 
 /* The full network (all nodes), the baseline every speed-up is measured against:
  * per layer an MFMA GEMM + bias + activation.  Y device [B][d_last]; argmax nullable.

@@ -737,6 +737,73 @@ int slonn_sparse_forward_aclo(const slonn_model* m, const slonn_tables* t, const
   return forward_impl(m, t, X, B, keep_out, 1, 0, Y, taps, workspace, ws_bytes, stream, &hook);
 }
 
+// ---- a recorded forward pass for launch-bound batches ----
+struct slonn_graph {
+  hipStream_t capture_stream = nullptr;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+
+int slonn_forward_graph_destroy(slonn_graph* g) {
+  if (!g) return SLONN_OK;
+  if (g->exec) (void)hipGraphExecDestroy(g->exec);
+  if (g->graph) (void)hipGraphDestroy(g->graph);
+  if (g->capture_stream) (void)hipStreamDestroy(g->capture_stream);
+  delete g;
+  return SLONN_OK;
+}
+
+int slonn_forward_graph_create(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
+                               const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
+                               void* workspace, size_t ws_bytes, slonn_graph** out) {
+  if (!out) SLONN_FAIL(SLONN_EINVAL, "out is null");
+  *out = nullptr;
+  if (g_prof.on) SLONN_FAIL(SLONN_EINVAL, "switch per-kernel timing off before recording a graph");
+  slonn_graph* g = new (std::nothrow) slonn_graph;
+  if (!g) SLONN_FAIL(SLONN_ENOMEM, "out of host memory");
+  auto fail = [&](int code) {
+    slonn_forward_graph_destroy(g);
+    return code;
+  };
+  hipError_t e = hipStreamCreateWithFlags(&g->capture_stream, hipStreamNonBlocking);
+  if (e != hipSuccess) {
+    set_error("creating the capture stream failed: %s", hipGetErrorString(e));
+    return fail(SLONN_EHIP);
+  }
+  // one eager pass first: it validates the arguments and sets the kernels' LDS attributes
+  int rc = forward_impl(m, t, X, B, keep, keep_qstride, keep_lstride, Y, nullptr, workspace, ws_bytes,
+                        g->capture_stream, nullptr);
+  if (rc != SLONN_OK) return fail(rc);
+  if ((e = hipStreamSynchronize(g->capture_stream)) != hipSuccess) {
+    set_error("the eager pass before recording failed: %s", hipGetErrorString(e));
+    return fail(SLONN_EHIP);
+  }
+  if ((e = hipStreamBeginCapture(g->capture_stream, hipStreamCaptureModeThreadLocal)) != hipSuccess) {
+    set_error("hipStreamBeginCapture failed: %s", hipGetErrorString(e));
+    return fail(SLONN_EHIP);
+  }
+  rc = forward_impl(m, t, X, B, keep, keep_qstride, keep_lstride, Y, nullptr, workspace, ws_bytes,
+                    g->capture_stream, nullptr);
+  e = hipStreamEndCapture(g->capture_stream, &g->graph);      // always end the capture, also after an error
+  if (rc != SLONN_OK) return fail(rc);
+  if (e != hipSuccess || !g->graph) {
+    set_error("hipStreamEndCapture failed: %s", hipGetErrorString(e));
+    return fail(SLONN_EHIP);
+  }
+  if ((e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0)) != hipSuccess) {
+    set_error("hipGraphInstantiate failed: %s", hipGetErrorString(e));
+    return fail(SLONN_EHIP);
+  }
+  *out = g;
+  return SLONN_OK;
+}
+
+int slonn_forward_graph_launch(slonn_graph* g, void* stream) {
+  if (!g || !g->exec) SLONN_FAIL(SLONN_EINVAL, "graph is null");
+  SLONN_HIP(hipGraphLaunch(g->exec, static_cast<hipStream_t>(stream)));
+  return SLONN_OK;
+}
+
 int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float* Y, int32_t* argmax,
                         float** layer_out, void* workspace, size_t ws_bytes, void* stream) {
   if (!m || !X || !Y) SLONN_FAIL(SLONN_EINVAL, "null argument");

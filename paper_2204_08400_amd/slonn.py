@@ -30,6 +30,7 @@ EXPORTS = [
     "slonn_policy_create", "slonn_policy_destroy", "slonn_policy_train_confidence",
     "slonn_policy_set_latency_profile", "slonn_policy_keep_aclo", "slonn_policy_keep_lcao",
     "slonn_sparse_forward_aclo",
+    "slonn_forward_graph_create", "slonn_forward_graph_launch", "slonn_forward_graph_destroy",
 ]
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused")
 PATH_AUTO, PATH_LAYERS, PATH_FUSED = 0, 1, 2
@@ -319,6 +320,33 @@ def slonn_sparse_forward_aclo(model: Model, tables: Optional[Tables], policy: Po
         C.byref(taps) if taps is not None else None, C.c_void_p(_ptr(workspace)),
         C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
         C.c_void_p(_stream_ptr(stream))))
+
+
+class ForwardGraph:
+    """Owns a slonn_graph handle and keeps every baked-in buffer alive."""
+
+    def __init__(self, handle, keep_alive):
+        self.h, self._keep = handle, keep_alive
+
+    def launch(self, stream=None):
+        _check(load().slonn_forward_graph_launch(self.h, C.c_void_p(_stream_ptr(stream))))
+
+    def close(self):
+        if getattr(self, "h", None):
+            load().slonn_forward_graph_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+
+def slonn_forward_graph_create(model: Model, tables: Optional[Tables], X: Input, B: int, keep, keep_qstride: int,
+                               keep_lstride: int, Y: Output, workspace) -> ForwardGraph:
+    h = C.c_void_p()
+    _check(load().slonn_forward_graph_create(
+        model.h, tables.h if tables is not None else None, C.byref(X), int(B), C.c_void_p(_ptr(keep)),
+        int(keep_qstride), int(keep_lstride), C.byref(Y), C.c_void_p(_ptr(workspace)),
+        C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0), C.byref(h)))
+    return ForwardGraph(h, (model, tables, X, keep, Y, workspace))
 
 
 def slonn_dense_forward(model: Model, X: Input, B: int, Y, argmax, layer_out: Optional[Sequence],

@@ -734,3 +734,49 @@ def test_forward_under_aclo_matches_oracle(rt, oracle, path):
         assert np.array_equal(keep[ok], ref["keep"][ok])
         assert len(set(ref["keep"].tolist())) > 1
         _say(f"  {compare_sparse(got, ref, layers, 'aclo ' + path)}")
+
+
+@pytest.mark.parametrize("path,B", [("layers", 1), ("layers", 5), ("fused", 3)])
+def test_recorded_forward_replays_like_eager(rt, oracle, path, B):
+    """A forward pass recorded into a HIP graph: several replays with fresh inputs and keep
+    fractions written into the baked-in buffers, eager work and synchronisations in between,
+    every replay compared with the eager call bit for bit (and the first with the oracle)."""
+    import torch
+    from paper_2204_08400_amd import slonn
+    dims = (640, 1536, 520, 10)
+    layers, net, _ = make_case(oracle, dims, 5, 8, seed=111, cap=800, N_build=160, kind="u01")
+    g = _gpu_net(rt, layers, net, path=path)
+    dev = "cuda:0"
+    x_static = torch.zeros((B, dims[0]), dtype=torch.float32, device=dev)
+    keep_static = torch.zeros(B, dtype=torch.float32, device=dev)
+    y_static = torch.zeros((B, dims[-1]), dtype=torch.float32, device=dev)
+    a_static = torch.zeros(B, dtype=torch.int32, device=dev)
+    inp = slonn.make_input(x=x_static)
+    out = slonn.make_output(dense=y_static, argmax=a_static)
+    ws = g.workspace(B)
+    Xall = make_queries(dims, 6 * B, seed=112, kind="u01")
+    keeps = wl.keep_uniform(6 * B, 0.02, 0.6, 7)
+    x_static.copy_(torch.from_numpy(Xall[:B]))
+    keep_static.copy_(torch.from_numpy(keeps[:B]))
+    torch.cuda.synchronize()
+    graph = slonn.slonn_forward_graph_create(g.model, g.tables, inp, B, keep_static, 1, 0, out, ws)
+    stream = torch.cuda.current_stream()
+    for r in range(6):
+        _say(f"recorded forward path={path} B={B} replay {r}")
+        xs, ks = Xall[r * B:(r + 1) * B], keeps[r * B:(r + 1) * B]
+        x_static.copy_(torch.from_numpy(xs))
+        keep_static.copy_(torch.from_numpy(ks))
+        y_static.fill_(-1.0)
+        graph.launch(stream)
+        torch.cuda.synchronize()
+        got_y, got_a = y_static.cpu().numpy().copy(), a_static.cpu().numpy().copy()
+        # the program's own eager work between replays
+        eager = to_numpy_result(g.sparse_forward(xs, _keep_tensor(ks)))
+        assert np.array_equal(got_y, eager["out"]) and np.array_equal(got_a, eager["argmax"])
+        if r == 0:
+            ref = net.sparse_forward(xs, ks)
+            ok = np.ones(B, bool)
+            for l in (0, 1):
+                ok &= ~ref["layers"][l]["tie"]
+            assert_close_rows(got_y, ref["out"], ok, "recorded forward")
+    graph.close()
