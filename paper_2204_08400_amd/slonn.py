@@ -191,6 +191,13 @@ def slonn_build_tables(model: Model, X_build: Input, N: int, stream=None) -> Tab
     return Tables(model, h)
 
 
+def slonn_tables_export_bytes(tables: Tables) -> int:
+    """size of the blob slonn_tables_export would write"""
+    n = C.c_size_t(0)
+    _check(load().slonn_tables_export(tables.h, None, C.byref(n)))
+    return n.value
+
+
 def slonn_tables_export(tables: Tables) -> bytes:
     n = C.c_size_t(0)
     _check(load().slonn_tables_export(tables.h, None, C.byref(n)))
