@@ -780,3 +780,26 @@ def test_recorded_forward_replays_like_eager(rt, oracle, path, B):
                 ok &= ~ref["layers"][l]["tie"]
             assert_close_rows(got_y, ref["out"], ok, "recorded forward")
     graph.close()
+
+
+@pytest.mark.parametrize("path", ["layers", "fused"])
+def test_maximum_batch(rt, oracle, path):
+    """The documented maximum of 2^20 queries in one call (tiny layers so that the oracle
+    finishes in seconds): codes, active lists and outputs of every query."""
+    dims = (16, 32, 8)
+    layers, net, _ = make_case(oracle, dims, 2, 2, seed=121, hashed=[0])
+    g = _gpu_net(rt, layers, net, path=path)
+    B = 1 << 20
+    X = make_queries(dims, B, seed=122)
+    _say(f"maximum batch path={path}")
+    ref = net.sparse_forward(X, 0.25)
+    got = to_numpy_result(g.sparse_forward(X, 0.25, taps=True))
+    tap = ref["layers"][0]
+    ok = ~tap["tie"]
+    m = int(tap["cnt"][0])
+    assert (got["taps"]["cnt"][0] == m).all()
+    assert np.array_equal(got["taps"]["codes"][0].view(np.uint32)[ok], tap["codes"][ok])
+    assert np.array_equal(got["taps"]["active"][0][ok, :m], tap["active"][ok, :m])
+    assert np.array_equal(got["argmax"][ok], ref["argmax"][ok])
+    assert_close_rows(got["out"], ref["out"], ok, "maximum batch")
+    assert ok.sum() > 0.9 * B
