@@ -230,8 +230,36 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
     // small problems: one 16x16 tile per wavefront so that there are enough workgroups
     const long tiles32 = (long)((H + 31) / 32) * ((B + 31) / 32);
     if (tiles32 >= 128) {
-      dim3 g((H + 31) / 32, (B + 31) / 32);
-      hipLaunchKernelGGL((hash_project_mfma_kernel<2, 2, 2, 4>), g, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H, d);
+      // Tile shape per workgroup (TM x TN tiles of 16x16): the one whose workgroup count fills
+      // the compute units most evenly.  A workgroup count just above a multiple of the unit
+      // count leaves most of the chip idle for the last round (C3: 320 workgroups of 2x2 tiles
+      // on 256 units, against exactly 256 of 1x5).  Shapes with fewer operand loads per MFMA
+      // win ties.
+      static const int shapes[4][2] = {{2, 2}, {2, 3}, {1, 5}, {1, 4}};
+      int n_cu = 256, dev = 0;
+      if (hipGetDevice(&dev) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n_cu = v;
+      }
+      int best = 0;
+      double best_cost = 0.0;
+      for (int c = 0; c < 4; ++c) {
+        const int tm = shapes[c][0], tn = shapes[c][1];
+        const long wgs = (long)((B + 16 * tm - 1) / (16 * tm)) * ((H + 16 * tn - 1) / (16 * tn));
+        const long rounds = (wgs + n_cu - 1) / n_cu;
+        const double cost = (double)rounds * tm * tn * (1.0 + 0.25 * (tm + tn) / (tm * tn));
+        if (c == 0 || cost < best_cost * 0.97) { best = c; best_cost = cost; }
+      }
+      const int tm = shapes[best][0], tn = shapes[best][1];
+      dim3 g((H + 16 * tn - 1) / (16 * tn), (B + 16 * tm - 1) / (16 * tm));
+      if (best == 0)
+        hipLaunchKernelGGL((hash_project_mfma_kernel<2, 2, 2, 4>), g, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H, d);
+      else if (best == 1)
+        hipLaunchKernelGGL((hash_project_mfma_kernel<2, 3, 2, 4>), g, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H, d);
+      else if (best == 2)
+        hipLaunchKernelGGL((hash_project_mfma_kernel<1, 5, 2, 4>), g, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H, d);
+      else
+        hipLaunchKernelGGL((hash_project_mfma_kernel<1, 4, 2, 4>), g, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H, d);
     } else {
       dim3 g((H + 15) / 16, (B + 15) / 16);
       hipLaunchKernelGGL((hash_project_mfma_kernel<1, 1, 4, 16>), g, dim3(1024), 0, s, X, ldx, Wh, bh, Z, B, H, d);
