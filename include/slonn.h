@@ -21,7 +21,9 @@
  *     failure.  Argument validation happens before any device work is enqueued.
  *   - A keep fraction k in (0, 1] becomes a node budget m = min(n, max(1,
  *     floor(k*n + 0.5))) evaluated in double ("rounding to the nearest whole node",
- *     at least one node).  m == n means the layer is computed in full.
+ *     at least one node).  m == n means the layer is computed in full.  Keep fractions
+ *     live in device memory and are not validated: values at or below 0 (and NaN) give
+ *     m = 1, values above 1 give m = n.
  *   - Matrices are row-major and dense unless a stride is given.
  */
 #ifndef SLONN_H

@@ -123,8 +123,8 @@ extern "C" {
 // Keep fraction -> node budget: nearest whole node, at least one, at most n.
 int32_t so_budget(float keep, int32_t n) {
   double m = std::floor(static_cast<double>(keep) * static_cast<double>(n) + 0.5);
-  if (m < 1.0) m = 1.0;
-  if (m > n) m = n;
+  if (!(m >= 1.0)) m = 1.0;   // values at or below zero, and a fraction that is not a number
+  if (m > n) m = n;           // values above one
   return static_cast<int32_t>(m);
 }
 

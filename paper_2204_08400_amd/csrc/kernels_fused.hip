@@ -33,7 +33,7 @@ constexpr int GROUPS = NT / 16;          // 16-lane row groups
 
 __device__ __forceinline__ int budget_of(float keep, int n) {
   double m = floor((double)keep * (double)n + 0.5);
-  if (m < 1.0) m = 1.0;
+  if (!(m >= 1.0)) m = 1.0;        // also a keep fraction that is not a number
   if (m > (double)n) m = (double)n;
   return (int)m;
 }

@@ -210,6 +210,13 @@ def test_edge_cases(rt, oracle, path):
         ref = net.sparse_forward(X, keep)
         got = to_numpy_result(g.sparse_forward(X, keep, taps=True))
         compare_sparse(got, ref, layers, f"edge keep {keep}")
+    # keep fractions outside (0, 1] are clamped the same way on both sides
+    Xo = make_queries(dims, 6, seed=9)
+    odd_keep = np.asarray([0.0, -1.0, np.nan, 1.5, np.inf, 0.3], np.float32)
+    ref = net.sparse_forward(Xo, odd_keep)
+    got = to_numpy_result(g.sparse_forward(Xo, _keep_tensor(odd_keep), taps=True))
+    compare_sparse(got, ref, layers, "clamped keep")
+    assert got["taps"]["cnt"][0].tolist() == [1, 1, 1, 64, 64, 19]
     # an all-zero query (every projection equals the bias)
     Xz = np.zeros((3, 40), np.float32)
     ref = net.sparse_forward(Xz, 0.25)

@@ -106,6 +106,9 @@ def test_budget_rounding(oracle):
     assert oracle.budget(0.02, 8192) == 164 and oracle.budget(0.3, 8192) == 2458
     assert oracle.budget(0.5, 5) == 3      # 2.5 rounds up
     assert oracle.budget(1.0, 7) == 7
+    # out-of-range fractions are clamped, never rejected (they live in device memory)
+    assert oracle.budget(0.0, 9) == 1 and oracle.budget(-3.0, 9) == 1 and oracle.budget(float("nan"), 9) == 1
+    assert oracle.budget(1.5, 9) == 9 and oracle.budget(float("inf"), 9) == 9
 
 
 # --------------------------------------------------------------------------- #
