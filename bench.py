@@ -197,7 +197,7 @@ def main():
         # region times that kernel without the per-launch cost of the bracketing events
         avg_launch_s = min(avg_launch_s, dev_s / K)
     achieved = (bytes_per_step / launches_per_step) / avg_launch_s / 1e9
-    roofline = {"bound": "hbm", "kernel": "fused_forward_kernel" if dom == "fused" else "gather_forward_kernel",
+    roofline = {"bound": "hbm", "kernel": ("fused_wide_kernel" if ell else "fused_forward_kernel") if dom == "fused" else "gather_forward_kernel",
                 "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": None, "avg_launch_us": round(avg_launch_s * 1e6, 2),

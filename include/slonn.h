@@ -143,8 +143,12 @@ int slonn_model_destroy(slonn_model* m);
  *   activations in LDS, one launch per batch; for models whose layers are small enough
  *   (every weight matrix at most 8 MiB, dense first-layer input, no Node Activator on
  *   the last layer, row lengths a multiple of 16 bytes).  EUNSUPPORTED otherwise.
- * SLONN_PATH_AUTO (default): FUSED when the model qualifies and no compact output is
- *   requested, else LAYERS.                                                          */
+ *   A second whole-network kernel serves the wide sparse-input models (ELL input, exactly two
+ *   layers: a hidden layer of at most 4096 nodes stored input-major without a Node Activator,
+ *   then an activated output layer of any width; compact and/or dense output).
+ * SLONN_PATH_AUTO (default): FUSED when the model qualifies (for the first kernel: and no
+ *   compact output is requested; for the second: and the batch is at most two queries per
+ *   compute unit), else LAYERS.                                                      */
 enum { SLONN_PATH_AUTO = 0, SLONN_PATH_LAYERS = 1, SLONN_PATH_FUSED = 2 };
 int slonn_model_set_path(slonn_model* m, int path);
 

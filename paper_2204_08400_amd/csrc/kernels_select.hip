@@ -132,8 +132,8 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   SelectSharedWide<SEL_NT> sh;
   sh.taken = smem32;
   sh.tkey = reinterpret_cast<int32_t*>(smem32 + words);
-  sh.tval = smem32 + words + SELECT_WIDE_TABLE;
-  sh.s_off = sh.tval + SELECT_WIDE_TABLE;
+  sh.tval = smem32 + words + SelectWideTable<SEL_NT>::entries;
+  sh.s_off = sh.tval + SelectWideTable<SEL_NT>::entries;
   sh.s_len = sh.s_off + 64;
   sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
   sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * (SEL_NT / 64));
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
     return;
   }
   for (int i = tid; i < words; i += SEL_NT) sh.taken[i] = 0u;
-  for (int i = tid; i < SELECT_WIDE_TABLE; i += SEL_NT) { sh.tkey[i] = -1; sh.tval[i] = 0xFFFFFFFFu; }
+  for (int i = tid; i < SelectWideTable<SEL_NT>::entries; i += SEL_NT) { sh.tkey[i] = -1; sh.tval[i] = 0xFFFFFFFFu; }
   for (int h = tid; h < H; h += SEL_NT) out[h] = hf.hnodes[h];
   __syncthreads();
   select_block_wide<SEL_NT>(z, K, L, n, total - H, dir, ids, global_rank, sh,

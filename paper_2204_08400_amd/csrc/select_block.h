@@ -152,18 +152,25 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
 // output nodes): one BIT per node records the nodes taken in earlier rounds, and the nodes of
 // the current round meet in a small open-addressing table in LDS (node id -> smallest slot
 // number of the round), which is emptied again after each round.
-constexpr int SELECT_WIDE_TABLE = 4096;   // entries; a round holds at most SELECT_MU * NT <= half of it
+// Round table: a power of two of entries, at least twice the SELECT_MU * NT slots of a round.
+template <int NT>
+struct SelectWideTable {
+  static constexpr int bits = (SELECT_MU * NT * 2 <= 4096) ? 12 : 13;
+  static constexpr int entries = 1 << bits;
+  static_assert(SELECT_MU * NT * 2 <= entries, "round table too small");
+};
 
 template <int NT>
 struct SelectSharedWide {
   uint32_t* taken;               // [(n + 31) / 32] bitmap
-  int32_t* tkey;                 // [SELECT_WIDE_TABLE] node id or -1
-  uint32_t* tval;                // [SELECT_WIDE_TABLE] smallest slot of the round
+  int32_t* tkey;                 // [SelectWideTable<NT>::entries] node id or -1
+  uint32_t* tval;                // [SelectWideTable<NT>::entries] smallest slot of the round
   uint32_t* s_off;               // [64]
   uint32_t* s_len;               // [64]
   int* wave_cnt;                 // [SELECT_MU * NT/64]
   uint32_t* s_misc;              // [4]
-  static constexpr int words_besides_bitmap = 2 * SELECT_WIDE_TABLE + 64 + 64 + SELECT_MU * (NT / 64) + 4;
+  static constexpr int words_besides_bitmap =
+      2 * SelectWideTable<NT>::entries + 64 + 64 + SELECT_MU * (NT / 64) + 4;
 };
 
 // taken[] must be zero and tkey[] = -1, tval[] = 0xFFFFFFFF on entry (caller + barrier).
@@ -174,7 +181,8 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
                                                   const int32_t* __restrict__ global_rank,
                                                   const SelectSharedWide<NT>& sh, uint32_t* codes_row,
                                                   int32_t* out, const int16_t* hskip = nullptr) {
-  static_assert(SELECT_MU * NT * 2 <= SELECT_WIDE_TABLE, "round table too small");
+  constexpr int TABLE = SelectWideTable<NT>::entries;
+  constexpr int TBITS = SelectWideTable<NT>::bits;
   constexpr int NW = NT / 64;
   constexpr int MU = SELECT_MU;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -228,11 +236,11 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
     for (int u = 0; u < MU; ++u) {
       if (valid[u] && ((sh.taken[node[u] >> 5] >> (node[u] & 31)) & 1u)) valid[u] = false;   // earlier round
       if (valid[u]) {
-        uint32_t h = ((uint32_t)node[u] * 2654435761u) >> 20;      // 12 bits
+        uint32_t h = ((uint32_t)node[u] * 2654435761u) >> (32 - TBITS);
         while (true) {
           const int k = atomicCAS(&sh.tkey[h], -1, node[u]);
           if (k == -1 || k == node[u]) break;
-          h = (h + 1) & (SELECT_WIDE_TABLE - 1);
+          h = (h + 1) & (TABLE - 1);
         }
         atomicMin(&sh.tval[h], rel[u]);
         cell[u] = (int)h;

@@ -286,6 +286,32 @@ bool fused_eligible(const slonn_model* m, const char** reason) {
   return why == nullptr;
 }
 
+// Can the whole-network kernel for wide sparse-input models serve this model?  (two layers:
+// a small hidden layer stored input-major without a Node Activator, an activated output layer)
+bool fused_wide_eligible(const slonn_model* m, int ell_stride, const char** reason) {
+  const char* why = nullptr;
+  if (m->layers.size() != 2) why = "not a two-layer model";
+  else {
+    const Layer& A = m->layers[0];
+    const Layer& Bl = m->layers[1];
+    const int e0 = A.w_dtype == SLONN_F32 ? 4 : 8, e1 = Bl.w_dtype == SLONN_F32 ? 4 : 8;
+    if (A.activated() || A.w_layout != SLONN_ROWS_ARE_INPUTS) why = "first layer is not a plain input-major layer";
+    else if (!Bl.activated()) why = "output layer has no Node Activator";
+    else if (A.d_out > 4096 || A.d_out % e0 != 0 || A.d_out % e1 != 0 || A.d_out % 4 != 0)
+      why = "hidden width is above 4096 or not a multiple of 16 bytes";
+    else if (reinterpret_cast<uintptr_t>(A.W) % 16 != 0 || reinterpret_cast<uintptr_t>(Bl.W) % 16 != 0)
+      why = "weights are not 16-byte aligned";
+    else {
+      FusedWideArgs a{};
+      a.n1p = (A.d_out + 3) & ~3; a.Hp = (Bl.H() + 3) & ~3; a.ellp = (std::max(ell_stride, 1) + 3) & ~3;
+      a.n2 = Bl.d_out;
+      if (fused_wide_lds_bytes(a) > (size_t)m->max_lds_bytes) why = "the query's state does not fit in LDS";
+    }
+  }
+  if (reason) *reason = why;
+  return why == nullptr;
+}
+
 }  // namespace
 }  // namespace slonn
 
@@ -295,7 +321,8 @@ int slonn_model_set_path(slonn_model* m, int path) {
     SLONN_FAIL(SLONN_EINVAL, "unknown path %d", path);
   if (path == SLONN_PATH_FUSED) {
     const char* why = nullptr;
-    if (!fused_eligible(m, &why)) SLONN_FAIL(SLONN_EUNSUPPORTED, "fused path unavailable: %s", why);
+    if (!fused_eligible(m, &why) && !fused_wide_eligible(m, 1, nullptr))
+      SLONN_FAIL(SLONN_EUNSUPPORTED, "fused path unavailable: %s", why);
   }
   m->path = path;
   return SLONN_OK;
@@ -529,6 +556,56 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
                  last.d_out);
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
+
+  // ---- whole-network kernel for wide sparse-input models ----
+  // (one workgroup per query: ahead of the per-layer path, whose hash projection is a batch-wide
+  // MFMA contraction, up to about two queries per compute unit -- C4: 30 vs 44 us at batch 128,
+  // 116 vs 82 us at batch 1024)
+  if (m->path != SLONN_PATH_LAYERS && X->format == SLONN_ELL && !hook &&
+      (m->path == SLONN_PATH_FUSED || B <= 2 * m->n_cu) && fused_wide_eligible(m, X->ell_stride, nullptr)) {
+    Workspace w;
+    plan_workspace(m, B, static_cast<char*>(workspace), &w);
+    if (!workspace || ws_bytes < w.bytes)
+      SLONN_FAIL(SLONN_ENOMEM, "workspace holds %zu bytes, %zu needed", ws_bytes, w.bytes);
+    const Layer& A = m->layers[0];
+    const Layer& O = m->layers[1];
+    const TableSet* ts = t->for_layer(1);
+    FusedWideArgs a{};
+    a.W0 = A.W; a.b0 = A.bias; a.w0_dtype = A.w_dtype; a.act0 = A.act; a.n1 = A.d_out;
+    a.n1p = (A.d_out + 3) & ~3;
+    a.ccp = 1;
+    while (a.ccp * 4 < A.d_out) a.ccp *= 2;
+    a.idx = X->idx; a.val = X->val; a.nnz = X->nnz; a.ell_stride = X->ell_stride;
+    a.ellp = (X->ell_stride + 3) & ~3;
+    a.W1 = O.W; a.b1 = O.bias; a.w1_dtype = O.w_dtype; a.act1 = O.act; a.n2 = O.d_out;
+    a.Wh = O.Wh; a.bh = O.bh; a.K = O.K; a.L = O.L; a.Hp = (O.H() + 3) & ~3;
+    a.dir = ts->d_dir; a.ids = ts->d_ids; a.global_rank = ts->d_global_rank;
+    a.hnodes = O.hnodes; a.hslot = O.hslot; a.hash_first = m->hash_first ? 1 : 0;
+    a.keep = keep + (size_t)1 * keep_lstride; a.keep_qstride = keep_qstride;
+    int32_t* tap_idx = taps && taps->active_idx ? taps->active_idx[1] : nullptr;
+    int32_t* tap_cnt = taps && taps->active_cnt ? taps->active_cnt[1] : nullptr;
+    float* tap_out1 = taps && taps->layer_out ? taps->layer_out[1] : nullptr;
+    a.list = Y->idx ? Y->idx : (tap_idx ? tap_idx : w.active);
+    a.list_stride = Y->idx ? Y->stride : O.d_out;
+    a.cnt = Y->cnt ? Y->cnt : (tap_cnt ? tap_cnt : w.cnt);
+    a.vals = Y->val ? Y->val : w.act[0];
+    a.vals_stride = Y->val ? Y->stride : w.max_n;
+    a.dense = Y->dense ? Y->dense : tap_out1;
+    a.argmax = Y->argmax;
+    a.tap_codes = taps && taps->codes ? taps->codes[1] : nullptr;
+    a.tap_z = taps && taps->z ? taps->z[1] : nullptr;
+    a.tap_out0 = taps && taps->layer_out ? taps->layer_out[0] : nullptr;
+    rc = launch_fused_wide(a, B, m->max_lds_bytes, s);
+    if (rc) return rc;
+    if (tap_idx && a.list != tap_idx)
+      SLONN_HIP(hipMemcpy2DAsync(tap_idx, (size_t)O.d_out * 4, a.list, (size_t)a.list_stride * 4,
+                                 (size_t)O.d_out * 4, B, hipMemcpyDeviceToDevice, s));
+    if (tap_cnt && a.cnt != tap_cnt)
+      SLONN_HIP(hipMemcpyAsync(tap_cnt, a.cnt, (size_t)B * 4, hipMemcpyDeviceToDevice, s));
+    if (tap_out1 && a.dense != tap_out1)
+      SLONN_HIP(hipMemcpyAsync(tap_out1, a.dense, (size_t)B * O.d_out * 4, hipMemcpyDeviceToDevice, s));
+    return SLONN_OK;
+  }
 
   // ---- whole-network kernel ----
   const bool wants_compact = Y->idx || Y->val || Y->cnt;

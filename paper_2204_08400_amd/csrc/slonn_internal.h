@@ -134,6 +134,29 @@ struct FusedArgs {
 size_t fused_lds_bytes(const FusedArgs& a);
 int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s);
 
+// Arguments of the whole-network kernel for wide sparse-input models (ELL input, one small
+// hidden layer stored input-major, activated output layer).
+struct FusedWideArgs {
+  // hidden layer
+  const void* W0; const float* b0;
+  const int32_t* idx; const float* val; const int32_t* nnz;
+  int w0_dtype, act0, n1, n1p, ccp, ell_stride, ellp;
+  // output layer and its Node Activator
+  const void* W1; const float* b1; const float* Wh; const float* bh;
+  const uint32_t* dir; const int32_t* ids; const int32_t* global_rank;
+  const int32_t* hnodes; const int16_t* hslot;
+  int w1_dtype, act1, n2, K, L, Hp, hash_first;
+  const float* keep; int keep_qstride;
+  // outputs (list, vals, cnt always; dense, argmax and the taps nullable)
+  int32_t* list; int list_stride;
+  float* vals; int vals_stride;
+  int32_t* cnt;
+  float* dense; int32_t* argmax;
+  uint32_t* tap_codes; float* tap_z; float* tap_out0;
+};
+size_t fused_wide_lds_bytes(const FusedWideArgs& a);
+int launch_fused_wide(const FusedWideArgs& a, int B, int max_lds, hipStream_t s);
+
 // Active lists regrouped by weight-row block, so that the workgroups running at the same
 // time read the same few megabytes of the weight matrix (L2-sized blocks of rows).
 struct RowBlocking {

@@ -166,8 +166,9 @@ def test_select_teacher_forced(rt, oracle):
         cur = tap["out"]
 
 
+@pytest.mark.parametrize("path", ["auto", "layers"])
 @pytest.mark.parametrize("n_out", [3000, 50000], ids=["block-select", "wide-select"])
-def test_ell_input_and_activated_softmax_output(rt, oracle, n_out):
+def test_ell_input_and_activated_softmax_output(rt, oracle, n_out, path):
     """Wide sparse-input model with the Node Activator on the output layer only.  The
     50 000-node output is too wide for a 4-byte-per-node map in LDS and takes the select
     kernel that keeps one bit per node."""
@@ -182,13 +183,15 @@ def test_ell_input_and_activated_softmax_output(rt, oracle, n_out):
     glayers[0].W = np.ascontiguousarray(layers[0].W.T)
     g = rt.Network(glayers, first_layer_rows_are_inputs=True)
     g.import_tables(net.export_tables())
+    g.set_path(path)
     X = make_queries(dims, 50, seed=7, ell_nnz=40)
-    for keep in (0.005, 0.05, 0.2):
-        _say(f"ELL case keep={keep}")
-        ref = net.sparse_forward(X, keep)
+    for keep in (0.005, 0.05, 0.2, wl.keep_uniform(50, 0.0001, 1.0, 3)):
+        keep = _keep_tensor(keep) if np.ndim(keep) else keep
+        _say(f"ELL case path={path} keep={'mixed' if not np.isscalar(keep) else keep}")
+        ref = net.sparse_forward(X, keep.cpu().numpy() if not np.isscalar(keep) else keep)
         res = g.sparse_forward(X, keep, taps=True, compact=True)
         got = to_numpy_result(res)
-        compare_sparse(got, ref, layers, f"ELL keep {keep}")
+        compare_sparse(got, ref, layers, f"ELL {path}")
         ok = ~ref["layers"][1]["tie"]
         for q in np.nonzero(ok)[0]:
             c = ref["layers"][1]["cnt"][q]
@@ -400,7 +403,8 @@ def test_config_c5_shape_sampled(rt, oracle):
         _say(f"  {compare_sparse(got, ref, layers, f'C5-shaped {path}')}")
 
 
-def test_config_c4_shape(rt, oracle):
+@pytest.mark.parametrize("path", ["auto", "layers"])
+def test_config_c4_shape(rt, oracle, path):
     """Wiki10/Delicious-shaped model at its real width: 100 000 sparse features (100
     non-zeros) -> 128 -> 100 000 softmax outputs, K=12 L=50 on the output layer, keep
     0.005 (500 nodes), batch 128.  Tables come from the oracle on a 256-input build set
@@ -413,8 +417,14 @@ def test_config_c4_shape(rt, oracle):
     glayers[0].W = np.ascontiguousarray(layers[0].W.T)        # input-major first layer on the device
     g = rt.Network(glayers, first_layer_rows_are_inputs=True)
     g.import_tables(net.export_tables())
+    g.set_path(path)      # auto: the whole-network kernel for wide sparse-input models
     X = make_queries(cfg.dims, 128, seed=2, ell_nnz=cfg.ell_nnz)
-    _say("C4 sparse forward")
+    from paper_2204_08400_amd import slonn
+    slonn.slonn_profile_begin(32)
+    g.sparse_forward(X, 0.005, compact=True, dense=False)
+    prof = slonn.slonn_profile_end()
+    assert (prof["fused"][1] == 1) == (path == "auto"), prof
+    _say(f"C4 sparse forward path={path}")
     ref = net.sparse_forward(X, 0.005)
     got = to_numpy_result(g.sparse_forward(X, 0.005, taps=True, compact=True))
     rep = compare_sparse(got, ref, layers, "C4")
@@ -586,7 +596,8 @@ def test_hash_nodes_always_active_matches_oracle(rt, oracle, case, path):
     compare_sparse(got, plain, layers, "back to plain " + path)
 
 
-def test_hash_nodes_always_active_wide_output_layer(rt, oracle):
+@pytest.mark.parametrize("path", ["auto", "layers"])
+def test_hash_nodes_always_active_wide_output_layer(rt, oracle, path):
     """The variant on a wide activated softmax output layer (bitmap select kernel), compact output."""
     d0, n_out = 4000, 50000
     dims = (d0, 64, n_out)
@@ -599,6 +610,7 @@ def test_hash_nodes_always_active_wide_output_layer(rt, oracle):
     glayers[0].W = np.ascontiguousarray(layers[0].W.T)      # the GPU stores the first layer input-major
     g = rt.Network(glayers, first_layer_rows_are_inputs=True)
     g.import_tables(net.export_tables())
+    g.set_path(path)
     g.set_hash_nodes_always_active(True)
     X = make_queries(dims, 40, seed=92, ell_nnz=30)
     for keep in (0.0005, 0.004):
