@@ -26,6 +26,7 @@ namespace {
 constexpr int NT = 1024;
 constexpr int NW = NT / 64;
 constexpr int GROUPS = NT / 16;
+constexpr int VALS_LDS = 4096;     // lists up to this length keep their logits in LDS
 
 __device__ __forceinline__ int budget_of(float keep, int n) {
   double m = floor((double)keep * (double)n + 0.5);
@@ -70,37 +71,67 @@ __device__ __forceinline__ float dot4(const float4& w, const float* xs, float ac
   return acc;
 }
 
-// R rows per 16-lane group in flight: vals[t] = w_{list[t]} . x + b, t = t0 + k * GROUPS
-template <int R>
+template <int LPR>
+__device__ __forceinline__ float reduce_group(float v) {
+  if (LPR == 16) v += __shfl_xor(v, 8, 16);
+  v += __shfl_xor(v, 4, LPR);
+  v += __shfl_xor(v, 2, LPR);
+  v += __shfl_xor(v, 1, LPR);
+  return v;
+}
+
+// R rows per LPR-lane group in flight: vals[t] = w_{list[t]} . x + b for t = t0 + k * (NT / LPR).
+// Short rows (a few hundred bytes) take 8 lanes so that a pass covers twice as many rows.
+template <int R, int LPR>
 __device__ __forceinline__ void gather_pass(const void* __restrict__ W, int w_dtype,
                                             const float* __restrict__ bias, int d, const float* xs,
                                             const int32_t* list, int t0, int count, float* vals) {
-  const int l = threadIdx.x & 15;
+  constexpr int NG = NT / LPR;
+  const int l = threadIdx.x & (LPR - 1);
   const int nv = d >> 2;
   int t[R], j[R];
   float acc[R];
-  size_t row[R];
+  uint32_t row4[R];                 // row start in units of four elements (n * d / 4 < 2^32 is checked on the host)
 #pragma unroll
   for (int k = 0; k < R; ++k) {
-    t[k] = t0 + k * GROUPS;
+    t[k] = t0 + k * NG;
     const int tt = t[k] < count ? t[k] : t0;
     j[k] = list ? list[tt] : tt;
     acc[k] = 0.f;
-    row[k] = (size_t)j[k] * d;
+    row4[k] = (uint32_t)j[k] * (uint32_t)nv;
   }
 #pragma unroll 2
-  for (int i = l; i < nv; i += 16) {
+  for (int i = l; i < nv; i += LPR) {
     float4 v[R];
 #pragma unroll
-    for (int k = 0; k < R; ++k) v[k] = load_w4(W, w_dtype, row[k] + 4 * (size_t)i);
+    for (int k = 0; k < R; ++k) v[k] = load_w4(W, w_dtype, 4 * ((size_t)row4[k] + i));
 #pragma unroll
     for (int k = 0; k < R; ++k) acc[k] = dot4(v[k], xs + 4 * i, acc[k]);
   }
 #pragma unroll
-  for (int k = 0; k < R; ++k) acc[k] = reduce16(acc[k]);
+  for (int k = 0; k < R; ++k) acc[k] = reduce_group<LPR>(acc[k]);
 #pragma unroll
   for (int k = 0; k < R; ++k)
     if (l == k && t[k] < count) vals[t[k]] = acc[k] + bias[j[k]];
+}
+
+template <int LPR>
+__device__ __forceinline__ void gather_list(const void* __restrict__ W, int w_dtype,
+                                            const float* __restrict__ bias, int d, const float* xs,
+                                            const int32_t* list, int total, float* vals) {
+  constexpr int NG = NT / LPR;
+  constexpr int RMAX = (LPR == 16) ? 6 : 4;
+  const int g = threadIdx.x / LPR;
+  for (int base = 0; base < total; base += RMAX * NG) {
+    const int left = total - base;
+    const int t0 = base + g;
+    if (t0 >= total) continue;
+    if (LPR == 16 && left > 4 * NG) gather_pass<6, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+    else if (left > 3 * NG) gather_pass<4, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+    else if (left > 2 * NG) gather_pass<3, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+    else if (left > NG) gather_pass<2, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+    else gather_pass<1, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+  }
 }
 
 __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
@@ -113,7 +144,8 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
   float* s_val = reinterpret_cast<float*>(s_idx + a.ellp);            // [ellp]
   float* red_f = s_val + a.ellp;                                      // [NW] block reductions
   int32_t* red_i = reinterpret_cast<int32_t*>(red_f + NW);            // [NW]
-  uint32_t* wide = reinterpret_cast<uint32_t*>(red_i + NW);
+  float* lvals = reinterpret_cast<float*>(red_i + NW);                // [VALS_LDS] logits of a short list
+  uint32_t* wide = reinterpret_cast<uint32_t*>(lvals + VALS_LDS);
   const int words = (a.n2 + 31) >> 5;
   const int wordsp = (words + 3) & ~3;
   constexpr int TABLE = SelectWideTable<NT>::entries;
@@ -175,38 +207,45 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
     __syncthreads();
   }
 
-  // ---- hash: z_h = w_h . y1 + b_h in fp64, one 16-lane group per row, two rows in flight ----
+  // ---- hash: z_h = w_h . y1 + b_h in fp64, one 16-lane group per row, six rows in flight ----
   const int H = a.K * a.L;
   {
+    constexpr int R = 6;
     const int g = tid >> 4, l = tid & 15;
     const int nv = n1 >> 2;
-    for (int h0 = g; h0 < H; h0 += 2 * GROUPS) {
-      const int h1 = (h0 + GROUPS < H) ? h0 + GROUPS : h0;
-      const float4* w0 = reinterpret_cast<const float4*>(a.Wh + (size_t)h0 * n1);
-      const float4* w1 = reinterpret_cast<const float4*>(a.Wh + (size_t)h1 * n1);
-      double acc0 = 0.0, acc1 = 0.0;
-      for (int i = l; i < nv; i += 16) {
-        const float4 u = w0[i], v = w1[i];
-        const float4 x = reinterpret_cast<const float4*>(xs)[i];
-        acc0 = fma((double)u.x, (double)x.x, acc0);
-        acc0 = fma((double)u.y, (double)x.y, acc0);
-        acc0 = fma((double)u.z, (double)x.z, acc0);
-        acc0 = fma((double)u.w, (double)x.w, acc0);
-        acc1 = fma((double)v.x, (double)x.x, acc1);
-        acc1 = fma((double)v.y, (double)x.y, acc1);
-        acc1 = fma((double)v.z, (double)x.z, acc1);
-        acc1 = fma((double)v.w, (double)x.w, acc1);
+    for (int hb = g; hb < H; hb += R * GROUPS) {
+      const float4* w[R];
+      double acc[R];
+#pragma unroll
+      for (int k = 0; k < R; ++k) {
+        const int h = hb + k * GROUPS;
+        w[k] = reinterpret_cast<const float4*>(a.Wh + (size_t)(h < H ? h : hb) * n1);
+        acc[k] = 0.0;
       }
-      acc0 = reduce16(acc0);
-      acc1 = reduce16(acc1);
-      if (l == 0) {
-        const float z0 = (float)(acc0 + (double)a.bh[h0]);
-        zs[h0] = z0;
-        if (a.tap_z) a.tap_z[(size_t)q * H + h0] = z0;
-        if (h1 != h0) {
-          const float z1 = (float)(acc1 + (double)a.bh[h1]);
-          zs[h1] = z1;
-          if (a.tap_z) a.tap_z[(size_t)q * H + h1] = z1;
+#pragma unroll 2
+      for (int i = l; i < nv; i += 16) {
+        float4 u[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) u[k] = w[k][i];
+        const float4 x = reinterpret_cast<const float4*>(xs)[i];
+        const double x0 = x.x, x1 = x.y, x2 = x.z, x3 = x.w;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+          acc[k] = fma((double)u[k].x, x0, acc[k]);
+          acc[k] = fma((double)u[k].y, x1, acc[k]);
+          acc[k] = fma((double)u[k].z, x2, acc[k]);
+          acc[k] = fma((double)u[k].w, x3, acc[k]);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < R; ++k) acc[k] = reduce16(acc[k]);
+#pragma unroll
+      for (int k = 0; k < R; ++k) {
+        const int h = hb + k * GROUPS;
+        if (l == k && h < H) {
+          const float z = (float)(acc[k] + (double)a.bh[h]);
+          zs[h] = z;
+          if (a.tap_z) a.tap_z[(size_t)q * H + h] = z;
         }
       }
     }
@@ -224,7 +263,6 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
   const int Hf = (a.hash_first && m < n2) ? H : 0;       // hash nodes at the head of the list
   const int total = (m == n2 || m > Hf) ? m : Hf;
   int32_t* list = a.list + (size_t)q * a.list_stride;
-  float* vals = a.vals + (size_t)q * a.vals_stride;
   if (tid == 0) a.cnt[q] = total;
   if (m == n2) {
     if (a.tap_codes && tid < a.L) {
@@ -241,20 +279,13 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
   }
   __syncthreads();          // the list (global memory) is complete and visible to the workgroup
 
-  // ---- logits of the listed nodes ----
+  // ---- logits of the listed nodes (kept in LDS while they fit, else in the caller's array) ----
+  float* gv = a.vals + (size_t)q * a.vals_stride;
+  float* vals = total <= VALS_LDS ? lvals : gv;
   {
-    const int g = tid >> 4;
     const int32_t* lp = (m == n2) ? nullptr : list;
-    for (int base = 0; base < total; base += 4 * GROUPS) {
-      const int left = total - base;
-      const int t0 = base + g;
-      if (t0 < total) {
-        if (left > 3 * GROUPS) gather_pass<4>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, t0, total, vals);
-        else if (left > 2 * GROUPS) gather_pass<3>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, t0, total, vals);
-        else if (left > GROUPS) gather_pass<2>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, t0, total, vals);
-        else gather_pass<1>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, t0, total, vals);
-      }
-    }
+    if (n1 <= 256) gather_list<8>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, total, vals);
+    else gather_list<16>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, total, vals);
   }
   __syncthreads();
 
@@ -298,7 +329,7 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
     float v = vals[t];
     if (a.act1 == SLONN_ACT_SOFTMAX) v = expf(v - best) * inv;
     else if (a.act1 == SLONN_ACT_RELU) v = v > 0.0f ? v : 0.0f;
-    vals[t] = v;
+    gv[t] = v;
     if (y) y[(m == n2) ? t : list[t]] = v;
   }
 }
@@ -307,7 +338,7 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
 
 size_t fused_wide_lds_bytes(const FusedWideArgs& a) {
   const size_t words = ((size_t)((a.n2 + 31) >> 5) + 3) & ~(size_t)3;
-  return (size_t)NT * 16 + ((size_t)a.n1p + a.Hp + 2 * (size_t)a.ellp + 2 * NW) * 4 +
+  return (size_t)NT * 16 + ((size_t)a.n1p + a.Hp + 2 * (size_t)a.ellp + 2 * NW + VALS_LDS) * 4 +
          (words + SelectSharedWide<NT>::words_besides_bitmap) * 4;
 }
 

@@ -301,6 +301,8 @@ bool fused_wide_eligible(const slonn_model* m, int ell_stride, const char** reas
       why = "hidden width is above 4096 or not a multiple of 16 bytes";
     else if (reinterpret_cast<uintptr_t>(A.W) % 16 != 0 || reinterpret_cast<uintptr_t>(Bl.W) % 16 != 0)
       why = "weights are not 16-byte aligned";
+    else if ((unsigned long long)Bl.d_out * (unsigned long long)(A.d_out / 4) > 0xFFFFFFFFull)
+      why = "output weight matrix too large for 32-bit row offsets";
     else {
       FusedWideArgs a{};
       a.n1p = (A.d_out + 3) & ~3; a.Hp = (Bl.H() + 3) & ~3; a.ellp = (std::max(ell_stride, 1) + 3) & ~3;
