@@ -339,6 +339,20 @@ def main():
             onet.sparse_forward(Xs, ks, taps=False)
             dt += time.perf_counter() - t0
             done += n_s
+        # the same oracle on one thread, briefly (about three seconds)
+        one = slonn_oracle.OracleNet(layers, threads=1, first_layer_rows_are_inputs=ell,
+                                     hash_nodes_always_active=args.hash_nodes_always_active)
+        one.tables = onet.tables
+        n_1 = min(n_s, 256)
+        X1 = tuple(a[:n_1] for a in Xs) if ell else Xs[:n_1]
+        k1 = ks if np.ndim(ks) == 0 else ks[:n_1]
+        done1, dt1 = 0, 0.0
+        while dt1 < 3.0 and done1 < 400 * n_1:
+            t0 = time.perf_counter()
+            one.sparse_forward(X1, k1, taps=False)
+            dt1 += time.perf_counter() - t0
+            done1 += n_1
+        extra["cpu_baseline_one_thread_qps"] = round(done1 / dt1, 1)
         cpu = {"value": round(done / dt, 1), "unit": "queries/s", "cores": onet.threads, "kind": "oracle",
                "sample": f"first {n_s} queries of the same query set, {done // n_s} passes ({dt:.1f} s of CPU work), "
                          f"keep {args.keep if mixed is None else 'per query'}, all layers, "

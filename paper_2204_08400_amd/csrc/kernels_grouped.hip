@@ -28,26 +28,30 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int GQ = 16;            // queries per group
 constexpr int ROWS_PER_WG = 128;  // union rows per workgroup pass (4 wavefronts x 32)
 
-__global__ __launch_bounds__(256) void union_kernel(const int32_t* __restrict__ active,
+constexpr int UNT = 1024;          // threads of the union kernel (few workgroups: one per 16 queries)
+constexpr int UNW = UNT / 64;
+
+__global__ __launch_bounds__(UNT) void union_kernel(const int32_t* __restrict__ active,
                                                    const int32_t* __restrict__ cnt, int idx_stride, int B,
                                                    int n, int32_t* __restrict__ urows,
                                                    uint32_t* __restrict__ umask, int32_t* __restrict__ ucnt,
                                                    int32_t* __restrict__ gflag, int ustride,
                                                    const int16_t* __restrict__ skip_hslot) {
   extern __shared__ __align__(16) uint32_t mask2[];      // two 16-bit masks per word
-  __shared__ int red[4];
+  __shared__ int red[UNW];
   __shared__ int listed;                                 // list entries that take part
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int q0 = g * GQ, nq = min(GQ, B - q0);
   const int words = (n + 1) >> 1;
-  for (int i = tid; i < words; i += 256) mask2[i] = 0u;
+  for (int i = tid; i < words; i += UNT) mask2[i] = 0u;
   if (tid == 0) listed = 0;
   __syncthreads();
   int mine = 0;
-  for (int qi = 0; qi < nq; ++qi) {
+  for (int qi = wave; qi < nq; qi += UNW) {               // one wavefront per query's list
     const int c = cnt[q0 + qi];
     const int32_t* list = active + (size_t)(q0 + qi) * idx_stride;
-    for (int t = tid; t < c; t += 256) {
+#pragma unroll 4
+    for (int t = lane; t < c; t += 64) {
       const int node = list[t];
       if (skip_hslot && skip_hslot[node] >= 0) continue;   // output already taken from the projections
       atomicOr(&mask2[node >> 1], (1u << qi) << (16 * (node & 1)));
@@ -58,7 +62,7 @@ __global__ __launch_bounds__(256) void union_kernel(const int32_t* __restrict__ 
   __syncthreads();
   const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   int base = 0;
-  for (int i0 = 0; i0 < n; i0 += 256) {
+  for (int i0 = 0; i0 < n; i0 += UNT) {
     const int i = i0 + tid;
     const uint32_t mk = i < n ? (mask2[i >> 1] >> (16 * (i & 1))) & 0xFFFFu : 0u;
     const unsigned long long votes = __ballot(mk != 0u);
@@ -66,7 +70,8 @@ __global__ __launch_bounds__(256) void union_kernel(const int32_t* __restrict__ 
     __syncthreads();
     int before = 0;
     for (int w = 0; w < wave; ++w) before += red[w];
-    const int all = red[0] + red[1] + red[2] + red[3];
+    int all = 0;
+    for (int w = 0; w < UNW; ++w) all += red[w];
     if (mk != 0u) {
       const int pos = base + before + __popcll(votes & below);
       urows[(size_t)g * ustride + pos] = i;
@@ -196,7 +201,7 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
     if (lds > 65536)
       SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(union_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(union_kernel, dim3(ng), dim3(256), lds, s, active, cnt, idx_stride, B, n, urows, umask,
+    hipLaunchKernelGGL(union_kernel, dim3(ng), dim3(UNT), lds, s, active, cnt, idx_stride, B, n, urows, umask,
                        ucnt, gflag, n, skip_hslot);
     SLONN_HIP(hipGetLastError());
   }
