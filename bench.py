@@ -201,7 +201,10 @@ def main():
                 "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": None, "avg_launch_us": round(avg_launch_s * 1e6, 2),
-                "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)}
+                "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step),
+                "note": "algorithmic bytes = the weight rows the method must evaluate (budget x row bytes per "
+                        "activated layer, whole matrix per query for layers computed in full); a fraction above 1 "
+                        "means rows were served to several queries from L2 (traffic = bytes that reached HBM)"}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:

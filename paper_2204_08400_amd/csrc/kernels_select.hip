@@ -76,6 +76,10 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
   }
 }
 
+// slots per thread per round: both workgroup sizes cover up to 4096 slots in one round
+template <int NT>
+struct BlockMU { static constexpr int value = 4096 / NT; };
+
 template <int NT>
 __global__ __launch_bounds__(NT) void select_block_kernel(
     const float* __restrict__ Z, int K, int L, int n, const uint32_t* __restrict__ dir,
@@ -84,12 +88,13 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
     float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf) {
   extern __shared__ __align__(16) uint32_t smem32[];
-  SelectShared<NT> sh;
+  constexpr int MU = BlockMU<NT>::value;
+  SelectShared<NT, MU> sh;
   sh.prio = smem32;
   sh.s_off = smem32 + n;
   sh.s_len = sh.s_off + 64;
   sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
-  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * (NT / 64));
+  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + MU * (NT / 64));
 
   const int q = blockIdx.x, tid = threadIdx.x;
   const int m = budget_of(keep[(size_t)q * keep_stride], n);
@@ -115,8 +120,8 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
   for (int i = tid; i < n; i += NT) sh.prio[i] = 0xFFFFFFFFu;
   for (int h = tid; h < H; h += NT) out[h] = hf.hnodes[h];
   __syncthreads();
-  select_block<NT>(z, K, L, n, total - H, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr,
-                   out + H, H ? hf.hslot : nullptr);
+  select_block<NT, MU>(z, K, L, n, total - H, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr,
+                       out + H, H ? hf.hslot : nullptr);
 
   if (rb.part_idx) partition_rows(out, total, rb, q, z, sh.prio);
 }
@@ -185,7 +190,7 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
                   int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_SELECT, s);
   const HashFirst hf = hash_first ? *hash_first : HashFirst{};
-  const size_t lds_block = ((size_t)n + SelectShared<SEL_NT_BIG>::words_besides_prio) * 4;
+  const size_t lds_block = ((size_t)n + SelectShared<SEL_NT, BlockMU<SEL_NT>::value>::words_besides_prio) * 4;
   if (lds_block <= (size_t)max_lds) {
     const RowBlocking rbv = rb ? *rb : RowBlocking{};
     if (B <= 64) {

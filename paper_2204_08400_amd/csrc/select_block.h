@@ -14,16 +14,17 @@
 
 namespace slonn {
 
-constexpr int SELECT_MU = 4;     // most slots per thread per round (header-wide constant)
+constexpr int SELECT_MU = 4;     // default number of slots per thread per round
 
-template <int NT>
+// MU: most slots a thread takes per round (a round covers up to MU * NT slots)
+template <int NT, int MU = SELECT_MU>
 struct SelectShared {            // LDS regions the caller carves out
   uint32_t* prio;                // [n]  first-occurrence map, 0xFFFFFFFF = node not seen
   uint32_t* s_off;               // [64] list offsets of this query
   uint32_t* s_len;               // [64] list lengths
-  int* wave_cnt;                 // [SELECT_MU * NT/64]
+  int* wave_cnt;                 // [MU * NT/64]
   uint32_t* s_misc;              // [4]
-  static constexpr int words_besides_prio = 64 + 64 + SELECT_MU * (NT / 64) + 4;
+  static constexpr int words_besides_prio = 64 + 64 + MU * (NT / 64) + 4;
 };
 
 // z: the query's K*L hash projections (LDS or global).  prio[0..n) must hold 0xFFFFFFFF
@@ -32,15 +33,14 @@ struct SelectShared {            // LDS regions the caller carves out
 // hskip (nullable, LDS or global, [n]): nodes with an entry >= 0 are passed over wherever
 // they turn up (the variant of Section 3.4 in which hash nodes are computed anyway and the
 // Node Activator never selects them); the caller keeps m <= n minus their number.
-template <int NT>
+template <int NT, int MU = SELECT_MU>
 __device__ __forceinline__ void select_block(const float* z, int K, int L_, int n, int m,
                                              const uint32_t* __restrict__ dir,
                                              const int32_t* __restrict__ ids,
                                              const int32_t* __restrict__ global_rank,
-                                             const SelectShared<NT>& sh, uint32_t* codes_row,
+                                             const SelectShared<NT, MU>& sh, uint32_t* codes_row,
                                              int32_t* out, const int16_t* hskip = nullptr) {
   constexpr int NW = NT / 64;
-  constexpr int MU = SELECT_MU;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 
