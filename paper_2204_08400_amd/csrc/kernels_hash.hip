@@ -236,10 +236,13 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
       // on 256 units, against exactly 256 of 1x5).  Shapes with fewer operand loads per MFMA
       // win ties.
       static const int shapes[4][2] = {{2, 2}, {2, 3}, {1, 5}, {1, 4}};
-      int n_cu = 256, dev = 0;
-      if (hipGetDevice(&dev) == hipSuccess) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n_cu = v;
+      static int n_cu = 0;                  // compute units of the device (looked up once)
+      if (n_cu == 0) {
+        int dev = 0, v = 0;
+        n_cu = 256;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+          n_cu = v;
       }
       int best = 0;
       double best_cost = 0.0;

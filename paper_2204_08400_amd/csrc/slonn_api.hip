@@ -56,12 +56,13 @@ struct Workspace {
 };
 
 void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
-  int max_n = 0, max_H = 0, max_na = 0;
+  int max_n = 0, max_H = 0, max_na = 0, d_bf16 = 0;
   for (const Layer& l : m->layers) {
     max_n = std::max(max_n, l.d_out);
     if (l.activated()) {
       max_H = std::max(max_H, l.H());
       max_na = std::max(max_na, l.d_out);
+      if (l.w_dtype == SLONN_BF16) d_bf16 = std::max(d_bf16, l.d_in);
     }
   }
   w->max_n = max_n; w->max_H = max_H; w->max_na = max_na;
@@ -79,7 +80,7 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   w->part_idx = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->part_pos = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->blk_off = reinterpret_cast<int32_t*>(take((size_t)B * (MAX_ROW_BLOCKS + 1) * 4));
-  w->grouped = take(grouped_workspace_bytes(B, std::max(max_na, 1)));
+  w->grouped = take(grouped_workspace_bytes(B, std::max(max_na, 1), d_bf16));
   w->bytes = off;
 }
 

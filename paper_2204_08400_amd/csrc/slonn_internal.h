@@ -210,7 +210,9 @@ int launch_gather_blocked(const void* W, int w_dtype, const float* bias, const f
 // untouched.  skip_hslot (nullable): nodes with an entry >= 0 there are left out of the unions
 // (their outputs come from the hash projections).  scratch: grouped_workspace_bytes(B, n)
 // bytes of device memory.
-size_t grouped_workspace_bytes(int B, int n);
+// d_bf16: widest input of an activated layer with bf16 weights (0: none); its activations are
+// split into three bf16 parts for the bf16 matrix cores.
+size_t grouped_workspace_bytes(int B, int n, int d_bf16);
 bool grouped_supported(int n, int max_lds);
 int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                           const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy,
