@@ -338,7 +338,9 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
   // row-block gather for every group measured (8192-wide bf16 layers, unions up to 6x the mean
   // list: 9.2 -> 6.3 ms of gather per 2048 queries), so every group takes it (a union is never
   // larger than the sum of its lists, i.e. 16x the mean list).
-  const int thr10 = bf16_cores ? 160 : 30;
+  // (bf16 rows that cannot take the bf16 path -- length not a multiple of 8 -- cost the gather
+  // half the bytes of fp32 rows at the same fp32 MFMA work: break-even 1.5)
+  const int thr10 = bf16_cores ? 160 : (w_dtype == SLONN_F32 ? 30 : 15);
   const size_t lds = (size_t)((n + 1) / 2) * 4;
   {
     ProfScope prof_(SLONN_PROF_SELECT, s);
