@@ -298,7 +298,7 @@ def test_build_tables_matches_oracle(rt, oracle, case):
 # --------------------------------------------------------------------------- #
 # the benchmark configurations at their real shapes
 # --------------------------------------------------------------------------- #
-def _config_case(rt, cfg_name, n_build, n_query, seed_w=0):
+def _config_case(rt, cfg_name, n_build, n_query, seed_w=0, list_cap=None):
     """The network of a benchmark configuration exactly as bench.py sets it up: hash nodes
     from the device's dense pass, tables built on the device; the oracle loads the same
     table blob (the build itself is compared with the oracle's in its own test)."""
@@ -313,7 +313,7 @@ def _config_case(rt, cfg_name, n_build, n_query, seed_w=0):
     for l in cfg.hashed_layers:
         var = dn["layers"][l].double().var(dim=0, unbiased=False).cpu().numpy()
         layers[l].K, layers[l].L = cfg.K, cfg.L
-        layers[l].list_cap = layers[l].d_out
+        layers[l].list_cap = layers[l].d_out if list_cap is None else list_cap
         layers[l].hash_nodes = wl.sample_hash_nodes(var, cfg.K, cfg.L, seed=3 + l)
     del plain, dn
     g = rt.Network(layers)
@@ -401,6 +401,33 @@ def test_config_c5_shape_sampled(rt, oracle):
         _say(f"C5-shaped path={path}")
         got = to_numpy_result(g.sparse_forward(Xq, _keep_tensor(keep), taps=True))
         _say(f"  {compare_sparse(got, ref, layers, f'C5-shaped {path}')}")
+
+
+@pytest.mark.timeout(900)
+def test_config_c5_full_width_sampled(rt, oracle):
+    """C5 at its real shape (1024-[8192]x6-1000, bf16 weights, K=12 L=64, batch 2048, per-query
+    keep ~ U[0.02, 0.3]) in the launch configuration bench.py times (path auto: per-layer path,
+    every group of 16 queries evaluated on the bf16 matrix cores).  Tables are built on the
+    device from 256 inputs to keep the blob the oracle loads near 1 GB; the oracle then computes
+    a sample of queries one by one."""
+    from paper_2204_08400_amd import slonn
+    B = 2048
+    cfg, layers, g, net, Xq = _config_case(rt, "C5", 256, B, list_cap=2459)
+    keep = wl.keep_uniform(B, cfg.keep_range[0], cfg.keep_range[1], 6)
+    _say("C5 full width: GPU pass")
+    slonn.slonn_profile_begin(64)
+    res = g.sparse_forward(Xq, _keep_tensor(keep), taps=True)
+    prof = slonn.slonn_profile_end()
+    assert prof["gather"][1] == 2 * len(cfg.hashed_layers), prof     # grouped + (idle) per-query launch per layer
+    got = to_numpy_result(res)
+    sample = np.asarray([0, 1, 15, 16, 17, 31, 500, 777, 1023, 1024, 1029, 1500, 2032, 2040, 2046, 2047])
+    _say("C5 full width: oracle on the sampled queries")
+    ref = net.sparse_forward(Xq[sample], keep[sample])
+    sub = {"out": got["out"][sample], "argmax": got["argmax"][sample],
+           "taps": {k: [None if t is None else t[sample] for t in v] for k, v in got["taps"].items()}}
+    rep = compare_sparse(sub, ref, layers, "C5 full width")
+    _say(f"  {rep}")
+    assert rep["tainted"] < len(sample)
 
 
 @pytest.mark.parametrize("path", ["auto", "layers"])
