@@ -383,6 +383,27 @@ def test_config_c3_shape_sampled(rt, oracle):
         _say(f"  {compare_sparse(got, ref, layers, f'C3 keep {keep}')}")
 
 
+@pytest.mark.timeout(600)
+def test_config_c3_timed_batch_sampled(rt, oracle):
+    """C3 at the batch bench.py times (1024 queries, keep 0.25, path auto: row-block gather plus
+    grouped evaluation on the fp32 matrix cores); the oracle computes a sample of the queries."""
+    from paper_2204_08400_amd import slonn
+    B = 1024
+    cfg, layers, g, net, Xq = _config_case(rt, "C3", 4096, B, list_cap=2049)
+    for keep in (0.25, 0.05):
+        _say(f"C3 batch 1024 keep={keep}: GPU pass")
+        slonn.slonn_profile_begin(64)
+        res = g.sparse_forward(Xq, keep, taps=True)
+        prof = slonn.slonn_profile_end()
+        assert prof["gather"][1] == 2 * len(cfg.hashed_layers) and prof["dense"][1] == 1, prof
+        got = to_numpy_result(res)
+        sample = np.asarray([0, 1, 15, 16, 17, 100, 511, 512, 513, 800, 1008, 1022, 1023])
+        ref = net.sparse_forward(Xq[sample], keep)
+        sub = {"out": got["out"][sample], "argmax": got["argmax"][sample],
+               "taps": {k: [None if t is None else t[sample] for t in v] for k, v in got["taps"].items()}}
+        _say(f"  {compare_sparse(sub, ref, layers, 'C3 batch 1024')}")
+
+
 def test_config_c5_shape_sampled(rt, oracle):
     """Deep bf16 MLP with mixed per-query keep fractions, at reduced depth/width so the
     oracle finishes in seconds: 1024-[2048]x3-1000, K=12 L=64, keep ~ U[0.02, 0.3]."""
