@@ -36,7 +36,9 @@ __global__ __launch_bounds__(UNT) void union_kernel(const int32_t* __restrict__ 
                                                    int n, int32_t* __restrict__ urows,
                                                    uint32_t* __restrict__ umask, int32_t* __restrict__ ucnt,
                                                    int32_t* __restrict__ gflag, int ustride,
-                                                   const int16_t* __restrict__ skip_hslot, int thr10) {
+                                                   const int16_t* __restrict__ skip_hslot,
+                                                   const float* __restrict__ Z, int H, int relu,
+                                                   float* __restrict__ Y, int ldy, int thr10) {
   extern __shared__ __align__(16) uint32_t mask2[];      // two 16-bit masks per word
   __shared__ int red[UNW];
   __shared__ int listed;                                 // list entries that take part
@@ -53,7 +55,17 @@ __global__ __launch_bounds__(UNT) void union_kernel(const int32_t* __restrict__ 
 #pragma unroll 4
     for (int t = lane; t < c; t += 64) {
       const int node = list[t];
-      if (skip_hslot && skip_hslot[node] >= 0) continue;   // output already taken from the projections
+      if (skip_hslot) {
+        const int hs = skip_hslot[node];
+        if (hs >= 0) {                  // a selected hash node: its output is its projection
+          if (Z) {
+            float v = Z[(size_t)(q0 + qi) * H + hs];
+            if (relu && !(v > 0.0f)) v = 0.0f;
+            Y[(size_t)(q0 + qi) * ldy + node] = v;
+          }
+          continue;
+        }
+      }
       atomicOr(&mask2[node >> 1], (1u << qi) << (16 * (node & 1)));
       ++mine;
     }
@@ -320,8 +332,9 @@ bool grouped_uses_bf16_cores(const void* W, int w_dtype, int d) {
 
 int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                           const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy,
-                          int B, int d, int n, int act, const int16_t* skip_hslot, void* scratch, int max_lds,
+                          int B, int d, int n, int act, const GroupedReuse* reuse, void* scratch, int max_lds,
                           int32_t** gflag_out, hipStream_t s) {
+  const GroupedReuse ru = reuse ? *reuse : GroupedReuse{};
   const int ng = (B + GQ - 1) / GQ;
   int32_t* urows = static_cast<int32_t*>(scratch);
   uint32_t* umask = reinterpret_cast<uint32_t*>(urows + (size_t)ng * n);
@@ -349,7 +362,7 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
       SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(union_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(union_kernel, dim3(ng), dim3(UNT), lds, s, active, cnt, idx_stride, B, n, urows, umask,
-                       ucnt, gflag, n, skip_hslot, thr10);
+                       ucnt, gflag, n, ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, thr10);
     SLONN_HIP(hipGetLastError());
     if (bf16_cores) {
       hipLaunchKernelGGL(split_x_kernel, dim3(B, (d + 255) / 256), dim3(256), 0, s, X, ldx, B, d, xs3);

@@ -707,7 +707,13 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       const size_t row_bytes = (size_t)L.d_in * esz;
       const bool rows_vec = row_bytes % 16 == 0 && L.d_in % 4 == 0 && ldcur % 4 == 0 &&
                             reinterpret_cast<uintptr_t>(L.W) % 16 == 0 && reinterpret_cast<uintptr_t>(cur) % 16 == 0;
-      if (B >= 2 && rows_vec && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20) &&
+      // Large batches of a bf16-weight layer: every group of 16 queries is evaluated on the bf16
+      // matrix cores; no per-query gather runs, so the lists are not regrouped by row block.
+      const long gtiles = (long)((B + 15) / 16) * ((L.d_out + 127) / 128);
+      const bool all_grouped = gtiles >= 1024 && out && !(is_last && Y->val) && m->path_grouped && rows_vec &&
+                               grouped_supported(L.d_out, m->max_lds_bytes) &&
+                               grouped_uses_bf16_cores(L.W, L.w_dtype, L.d_in);
+      if (!all_grouped && B >= 2 && rows_vec && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20) &&
           select_fills_row_blocks(L.d_out, m->max_lds_bytes)) {
         int rpb = 16;
         while ((size_t)rpb * 2 * row_bytes <= ((size_t)2 << 20)) rpb *= 2;
@@ -730,15 +736,22 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       if (rc) return rc;
       act_list = aidx; act_cnt = acnt; act_stride = astride;
       if (is_last && Y->val) yc = Y->val;
-      if (rb.part_idx) {
+      if (all_grouped) {
+        GroupedReuse reuse;
+        reuse.hslot = L.hslot; reuse.Z = z; reuse.H = L.H(); reuse.relu = act == SLONN_ACT_RELU;
+        int32_t* flags = nullptr;
+        rc = launch_gather_grouped(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B,
+                                   L.d_in, L.d_out, act, &reuse, w.grouped, m->max_lds_bytes, &flags, s);
+      } else if (rb.part_idx) {
         // Large batches: groups of 16 queries whose lists overlap enough are evaluated together
         // on the matrix cores (decided per group on the device); the rest is gathered per query.
         const int32_t* gflag = nullptr;
-        const long tiles = (long)((B + 15) / 16) * ((L.d_out + 127) / 128);
-        if (tiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {
+        if (gtiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {
           int32_t* flags = nullptr;
+          GroupedReuse reuse;
+          reuse.hslot = rb.hslot;        // outputs of selected hash nodes were written by the regrouping step
           rc = launch_gather_grouped(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B,
-                                     L.d_in, L.d_out, act, rb.hslot, w.grouped, m->max_lds_bytes, &flags, s);
+                                     L.d_in, L.d_out, act, &reuse, w.grouped, m->max_lds_bytes, &flags, s);
           if (rc) return rc;
           gflag = flags;
         }

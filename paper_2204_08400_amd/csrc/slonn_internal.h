@@ -204,19 +204,29 @@ int launch_gather_blocked(const void* W, int w_dtype, const float* bias, const f
                           const RowBlocking& rb, float* Y, int ldy, float* yc, int ldc, int B, int d,
                           int n, int act, const int32_t* skip_group, hipStream_t s);
 
+// Selected hash nodes in the grouped evaluation: nodes with hslot[node] >= 0 are left out of the
+// unions (their outputs come from the hash projections, Section 3.4).  With Z set the union
+// step also writes those outputs, Y[q][node] = act(Z[q][hslot[node]]); with Z null somebody else
+// already has (the row-block regrouping step).  hslot null: no reuse.
+struct GroupedReuse {
+  const int16_t* hslot = nullptr;
+  const float* Z = nullptr;      // [B][H] projections
+  int H = 0, relu = 0;
+};
+
 // Groups of 16 queries: the union of their active rows evaluated as dense tiles on the matrix
 // cores, selected (query, node) pairs written to Y.  A group whose union is too large
 // relative to its lists is flagged 0 in *gflag_out (device array, [ceil(B/16)]) and left
-// untouched.  skip_hslot (nullable): nodes with an entry >= 0 there are left out of the unions
-// (their outputs come from the hash projections).  scratch: grouped_workspace_bytes(B, n)
-// bytes of device memory.
+// untouched (with bf16 weights on the bf16 cores every group is taken).  scratch:
+// grouped_workspace_bytes(B, n, d) bytes of device memory.
 // d_bf16: widest input of an activated layer with bf16 weights (0: none); its activations are
 // split into three bf16 parts for the bf16 matrix cores.
 size_t grouped_workspace_bytes(int B, int n, int d_bf16);
 bool grouped_supported(int n, int max_lds);
+bool grouped_uses_bf16_cores(const void* W, int w_dtype, int d);
 int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                           const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy,
-                          int B, int d, int n, int act, const int16_t* skip_hslot, void* scratch, int max_lds,
+                          int B, int d, int n, int act, const GroupedReuse* reuse, void* scratch, int max_lds,
                           int32_t** gflag_out, hipStream_t s);
 
 // y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).

@@ -439,7 +439,7 @@ def test_config_c5_full_width_sampled(rt, oracle):
     slonn.slonn_profile_begin(64)
     res = g.sparse_forward(Xq, _keep_tensor(keep), taps=True)
     prof = slonn.slonn_profile_end()
-    assert prof["gather"][1] == 2 * len(cfg.hashed_layers), prof     # grouped + (idle) per-query launch per layer
+    assert prof["gather"][1] == len(cfg.hashed_layers), prof     # one grouped launch per hidden layer
     got = to_numpy_result(res)
     sample = np.asarray([0, 1, 15, 16, 17, 31, 500, 777, 1023, 1024, 1029, 1500, 2032, 2040, 2046, 2047])
     _say("C5 full width: oracle on the sampled queries")
@@ -559,7 +559,8 @@ def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype):
         slonn.slonn_profile_begin(64)
         got = to_numpy_result(g.sparse_forward(X, kt, taps=True))
         prof = slonn.slonn_profile_end()
-        assert prof["gather"][1] == 2, prof     # grouped + per-query pass on layer 0
+        # fp32: grouped + per-query pass on layer 0; bf16: every group on the bf16 cores, one launch
+        assert prof["gather"][1] == (2 if w_dtype == wl.W_F32 else 1), prof
         assert prof["dense"][1] == 1, prof      # the small output layer, on the matrix cores
         _say(f"  {compare_sparse(got, ref, layers, 'grouped')}")
 
