@@ -73,15 +73,22 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
   int per = (12 * m + NT - 1) / NT;
   per = per < 1 ? 1 : (per > MU ? MU : per);
   int count = 0;
+  // slot / L without a division per slot: the round's first slot is divided once, the offset
+  // inside the round (below 16384) by multiplication with ceil(2^20 / L)
+  static_assert(MU * NT + 64 <= 16384, "round too large for the multiplicative division");
+  const uint32_t magic = ((1u << 20) + L - 1) / L;
   for (uint32_t base = 0; base < nslots && count < m; base += NT * per) {
+    const uint32_t r_base = base / L, rem_base = base - r_base * L;
     int node[MU];
     uint32_t slot[MU];
     bool valid[MU];
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
       slot[u] = base + u * NT + tid;
-      const uint32_t r = slot[u] / L;
-      const uint32_t b = slot[u] - r * L;
+      const uint32_t off = rem_base + u * NT + tid;
+      const uint32_t dr = (uint32_t)(((unsigned long long)off * magic) >> 20);
+      const uint32_t r = r_base + dr;
+      const uint32_t b = off - dr * L;
       valid[u] = u < per && slot[u] < nslots && r < sh.s_len[b];
       node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
     }
@@ -213,7 +220,10 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
   int per = (12 * m + NT - 1) / NT;
   per = per < 1 ? 1 : (per > MU ? MU : per);
   int count = 0;
+  static_assert(MU * NT + 64 <= 16384, "round too large for the multiplicative division");
+  const uint32_t magic = ((1u << 20) + L - 1) / L;      // see select_block
   for (unsigned long long base = 0; base < nslots && count < m; base += (unsigned long long)NT * per) {
+    const uint32_t r_base = (uint32_t)(base / L), rem_base = (uint32_t)(base - (unsigned long long)r_base * L);
     int node[MU], cell[MU];
     uint32_t rel[MU];                      // slot number relative to the round
     bool valid[MU];
@@ -221,8 +231,10 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
     for (int u = 0; u < MU; ++u) {
       rel[u] = u * NT + tid;
       const unsigned long long slot = base + rel[u];
-      const uint32_t r = (uint32_t)(slot / L);
-      const uint32_t b = (uint32_t)(slot - (unsigned long long)r * L);
+      const uint32_t off = rem_base + rel[u];
+      const uint32_t dr = (uint32_t)(((unsigned long long)off * magic) >> 20);
+      const uint32_t r = r_base + dr;
+      const uint32_t b = off - dr * L;
       valid[u] = u < per && slot < nslots && r < sh.s_len[b];
       node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
       cell[u] = 0;
