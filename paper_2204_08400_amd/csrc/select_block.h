@@ -76,6 +76,7 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
   // slot / L without a division per slot: the round's first slot is divided once, the offset
   // inside the round (below 16384) by multiplication with ceil(2^20 / L)
   static_assert(MU * NT + 64 <= 16384, "round too large for the multiplicative division");
+  static_assert(MU * NW <= 64, "one wavefront scans the wave counts of a round");
   const uint32_t magic = ((1u << 20) + L - 1) / L;
   for (uint32_t base = 0; base < nslots && count < m; base += NT * per) {
     const uint32_t r_base = base / L, rem_base = base - r_base * L;
@@ -110,20 +111,46 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
       if (lane == 0) sh.wave_cnt[u * NW + wave] = __popcll(votes[u]);
     }
     __syncthreads();
+    if (NW > 4) {
+      // many wavefronts: an exclusive prefix over the MU * NW wave counts in (u, wave) order
+      // (= slot order) by the first wavefront, so that every thread needs one LDS read per slot
+      // instead of NW; with four wavefronts the extra barrier costs more than it saves
+      if (wave == 0) {
+        const int c = lane < MU * NW ? sh.wave_cnt[lane] : 0;
+        int incl = c;
 #pragma unroll
-    for (int u = 0; u < MU; ++u) {
-      int before = 0, total = 0;
+        for (int o = 1; o < 64; o <<= 1) {
+          const int up = __shfl_up(incl, o);
+          if (lane >= o) incl += up;
+        }
+        if (lane < MU * NW) sh.wave_cnt[lane] = incl - c;
+        if (lane == 63) sh.s_misc[1] = (uint32_t)incl;     // survivors of the round
+      }
+      __syncthreads();
 #pragma unroll
-      for (int w = 0; w < NW; ++w) {
-        const int c = sh.wave_cnt[u * NW + w];
-        before += (w < wave) ? c : 0;
-        total += c;
+      for (int u = 0; u < MU; ++u) {
+        if (first[u]) {
+          const int pos = count + sh.wave_cnt[u * NW + wave] + __popcll(votes[u] & below);
+          if (pos < m) out[pos] = node[u];
+        }
       }
-      if (first[u]) {
-        const int pos = count + before + __popcll(votes[u] & below);
-        if (pos < m) out[pos] = node[u];
+      count += (int)sh.s_misc[1];
+    } else {
+#pragma unroll
+      for (int u = 0; u < MU; ++u) {
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          const int c = sh.wave_cnt[u * NW + w];
+          before += (w < wave) ? c : 0;
+          total += c;
+        }
+        if (first[u]) {
+          const int pos = count + before + __popcll(votes[u] & below);
+          if (pos < m) out[pos] = node[u];
+        }
+        count += total;
       }
-      count += total;
     }
     __syncthreads();
   }
@@ -268,21 +295,45 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
       if (lane == 0) sh.wave_cnt[u * NW + wave] = __popcll(votes[u]);
     }
     __syncthreads();
+    if (NW > 4) {              // exclusive prefix over the wave counts in slot order (see select_block)
+      if (wave == 0) {
+        const int c = lane < MU * NW ? sh.wave_cnt[lane] : 0;
+        int incl = c;
 #pragma unroll
-    for (int u = 0; u < MU; ++u) {
-      int before = 0, total = 0;
+        for (int o = 1; o < 64; o <<= 1) {
+          const int up = __shfl_up(incl, o);
+          if (lane >= o) incl += up;
+        }
+        if (lane < MU * NW) sh.wave_cnt[lane] = incl - c;
+        if (lane == 63) sh.s_misc[1] = (uint32_t)incl;
+      }
+      __syncthreads();
 #pragma unroll
-      for (int w = 0; w < NW; ++w) {
-        const int c = sh.wave_cnt[u * NW + w];
-        before += (w < wave) ? c : 0;
-        total += c;
+      for (int u = 0; u < MU; ++u) {
+        if (first[u]) {
+          const int pos = count + sh.wave_cnt[u * NW + wave] + __popcll(votes[u] & below);
+          if (pos < m) out[pos] = node[u];
+          atomicOr(&sh.taken[node[u] >> 5], 1u << (node[u] & 31));
+        }
       }
-      if (first[u]) {
-        const int pos = count + before + __popcll(votes[u] & below);
-        if (pos < m) out[pos] = node[u];
-        atomicOr(&sh.taken[node[u] >> 5], 1u << (node[u] & 31));
+      count += (int)sh.s_misc[1];
+    } else {
+#pragma unroll
+      for (int u = 0; u < MU; ++u) {
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          const int c = sh.wave_cnt[u * NW + w];
+          before += (w < wave) ? c : 0;
+          total += c;
+        }
+        if (first[u]) {
+          const int pos = count + before + __popcll(votes[u] & below);
+          if (pos < m) out[pos] = node[u];
+          atomicOr(&sh.taken[node[u] >> 5], 1u << (node[u] & 31));
+        }
+        count += total;
       }
-      count += total;
     }
 #pragma unroll
     for (int u = 0; u < MU; ++u)
