@@ -150,24 +150,26 @@ __global__ __launch_bounds__(256) void dense_layer_kernel(const void* __restrict
 
 // Small problems (a batch of a few hundred queries against a layer of about a thousand
 // nodes) do not fill the chip with 64x64 tiles and their K loop is pure latency.  Here a
-// workgroup owns a 32x32 tile, its four wavefronts split the reduction dimension, operands
+// workgroup owns a 32x32 tile, its KS (4 or 16) wavefronts split the reduction dimension, operands
 // go straight from L2 to registers as 16-byte loads (lane (r, half) takes elements
 // 8s+4*half .. +3 of row r for both operands, MFMA c of the step consumes element c), U
-// steps are loaded ahead, and the four partial tiles are added in LDS in a fixed order.
-template <int WDT, int U>
-__global__ __launch_bounds__(256) void dense_direct_kernel(const void* __restrict__ W,
+// steps are loaded ahead, and the partial tiles are added in LDS in a fixed order.  Skinny
+// problems (a 100-node output layer) have only a handful of tiles: sixteen wavefronts per tile
+// then shorten the latency-bound reduction loop fourfold.
+template <int WDT, int U, int KS>
+__global__ __launch_bounds__(64 * KS) void dense_direct_kernel(const void* __restrict__ W,
                                                           const float* __restrict__ bias,
                                                           const float* __restrict__ X, int ldx,
                                                           float* __restrict__ Y, int ldy, int M, int N,
                                                           int Kd, int act) {
-  __shared__ float part[3][64][16];
+  __shared__ float part[KS - 1][64][16];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 31, half = lane >> 5;
   const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
   const float* xr = X + (size_t)min(m0 + r, M - 1) * ldx;          // surplus rows recompute a valid row
   const size_t wrow = (size_t)min(n0 + r, N - 1) * Kd;
   const int steps = (Kd + 7) / 8;
-  const int per = (steps + 3) / 4;
+  const int per = (steps + KS - 1) / KS;
   const int s_begin = wave * per, s_end = min(steps, s_begin + per);
   f32x16 acc;
 #pragma unroll
@@ -213,7 +215,10 @@ __global__ __launch_bounds__(256) void dense_direct_kernel(const void* __restric
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int row = m0 + 8 * (v >> 2) + 4 * half + (v & 3);
-      float z = acc[v] + part[0][lane][v] + part[1][lane][v] + part[2][lane][v] + bv;
+      float z = acc[v];
+#pragma unroll
+      for (int w = 0; w < KS - 1; ++w) z += part[w][lane][v];       // fixed order
+      z += bv;
       if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
       if (row < M && col < N) Y[(size_t)row * ldy + col] = z;
     }
@@ -240,12 +245,22 @@ int launch_dense_layer(const void* W, int w_dtype, const float* bias, const floa
   const long tiles64 = (long)((B + 63) / 64) * ((n + 63) / 64);
   if (tiles64 < 256 && dense_small_supported(W, w_dtype, X, ldx, d)) {
     dim3 grid((n + 31) / 32, (B + 31) / 32);
-    if (w_dtype == SLONN_F32)
-      hipLaunchKernelGGL((dense_direct_kernel<SLONN_F32, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
-                         B, n, d, a);
-    else
-      hipLaunchKernelGGL((dense_direct_kernel<SLONN_BF16, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
-                         B, n, d, a);
+    const bool few = (long)grid.x * grid.y < 512 && d >= 1024;
+    if (w_dtype == SLONN_F32) {
+      if (few)
+        hipLaunchKernelGGL((dense_direct_kernel<SLONN_F32, 4, 16>), grid, dim3(1024), 0, s, W, bias, X, ldx, Y, ldy,
+                           B, n, d, a);
+      else
+        hipLaunchKernelGGL((dense_direct_kernel<SLONN_F32, 4, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
+                           B, n, d, a);
+    } else {
+      if (few)
+        hipLaunchKernelGGL((dense_direct_kernel<SLONN_BF16, 4, 16>), grid, dim3(1024), 0, s, W, bias, X, ldx, Y, ldy,
+                           B, n, d, a);
+      else
+        hipLaunchKernelGGL((dense_direct_kernel<SLONN_BF16, 4, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
+                           B, n, d, a);
+    }
     SLONN_HIP(hipGetLastError());
     return SLONN_OK;
   }

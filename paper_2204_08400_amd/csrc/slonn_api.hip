@@ -771,7 +771,8 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
                             ldo, B, L.d_in, L.d_out, act, s);
       if (rc) return rc;
     } else if ((size_t)((B + 63) / 64) * ((L.d_out + 63) / 64) >= 256 ||
-               (B >= 32 && dense_small_supported(L.W, L.w_dtype, cur, ldcur, L.d_in))) {
+               ((size_t)((B + 31) / 32) * ((L.d_out + 31) / 32) >= 64 &&
+                dense_small_supported(L.W, L.w_dtype, cur, ldcur, L.d_in))) {
       // a layer computed in full for a real batch is a dense contraction: matrix cores
       rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out, act, s);
       if (rc) return rc;

@@ -559,9 +559,11 @@ def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype):
         slonn.slonn_profile_begin(64)
         got = to_numpy_result(g.sparse_forward(X, kt, taps=True))
         prof = slonn.slonn_profile_end()
-        # fp32: grouped + per-query pass on layer 0; bf16: every group on the bf16 cores, one launch
-        assert prof["gather"][1] == (2 if w_dtype == wl.W_F32 else 1), prof
-        assert prof["dense"][1] == 1, prof      # the small output layer, on the matrix cores
+        # fp32: grouped + per-query pass on layer 0; bf16: every group on the bf16 cores, one launch;
+        # the output layer (17 tiles of 32x32) is too small for the matrix-core kernel and takes
+        # one more gather launch with the identity list
+        assert prof["gather"][1] == (3 if w_dtype == wl.W_F32 else 2), prof
+        assert prof["dense"][1] == 0, prof
         _say(f"  {compare_sparse(got, ref, layers, 'grouped')}")
 
 
