@@ -344,7 +344,7 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
   SLONN_HIP(nonempty.alloc(1));
   SLONN_HIP(score.alloc((size_t)nb * n));
 
-  int rc = launch_hash_project(X_l, Ly.d_in, Ly.Wh, Ly.bh, Z.p, (int)N, H, Ly.d_in, s);
+  int rc = launch_hash_project(X_l, Ly.d_in, Ly.Wh, Ly.bh, Z.p, (int)N, H, Ly.d_in, nullptr, nullptr, s);
   if (rc) return rc;
   const int64_t tot_keys = N * L;
   hipLaunchKernelGGL(keys_kernel, dim3((unsigned)((tot_keys + 255) / 256)), dim3(256), 0, s, Z.p, K, L, N, keys.p);

@@ -8,12 +8,18 @@
 // hash_project_mfma_kernel: fp64 matrix cores (v_mfma_f64_16x16x4_f64).  A workgroup owns a
 // 32x32 (large batches) or 16x16 (small batches) tile of Z; its 4 or 16 wavefronts split
 // the reduction dimension and their partial tiles are added in LDS in a fixed order.
+// A medium batch (a few dozen queries) has only a few dozen 16x16 tiles, and a tile's operand
+// rows would reach one compute unit at that unit's own L2 bandwidth; there the reduction
+// dimension is also split over several workgroups (grid.z).  Each writes its partial sums in
+// fp64 and hash_split_sum_kernel adds them in split order.
 // Operands are read straight from global memory/L2 as 16-byte loads: lane (r = lane%16,
 // g = lane/16) fetches elements 16s+4g .. 16s+4g+3 of its row, and MFMA number c of that
 // step consumes element c from every lane -- the same K subset for the X and the Wh
 // operand, which is all the instruction needs.
 // hash_project_kernel: LDS-tiled fp64 FMAs on the vector ALUs, for rows that are not
 // 16-byte aligned multiples of four elements.
+#include <algorithm>
+
 #include "slonn_internal.h"
 
 namespace slonn {
@@ -27,11 +33,12 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 // TM x TN 16x16 MFMA tiles per wavefront; U reduction steps (16 elements each) are
 // loaded ahead of the MFMAs that consume them; KS wavefronts split the reduction
 // dimension (small batches need the extra wavefronts to cover the load latency).
-template <int TM, int TN, int U, int KS>
+template <int TM, int TN, int U, int KS, bool SPLIT = false>
 __global__ __launch_bounds__(64 * KS) void hash_project_mfma_kernel(const float* __restrict__ X, int ldx,
                                                                const float* __restrict__ Wh,
                                                                const float* __restrict__ bh,
-                                                               float* __restrict__ Z, int B, int H, int d) {
+                                                               float* __restrict__ Z, int B, int H, int d,
+                                                               double* __restrict__ gpart = nullptr) {
   __shared__ double part[KS - 1][64][TM * TN * 4];     // partial tiles of waves 1..KS-1
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
@@ -43,10 +50,17 @@ __global__ __launch_bounds__(64 * KS) void hash_project_mfma_kernel(const float*
   for (int i = 0; i < TM; ++i) xr[i] = X + (size_t)min(q0 + 16 * i + r, B - 1) * ldx;
 #pragma unroll
   for (int j = 0; j < TN; ++j) wr[j] = Wh + (size_t)min(h0 + 16 * j + r, H - 1) * d;
-  // this wave's share of the reduction dimension, in steps of 16 elements
+  // this wave's share of the reduction dimension, in steps of 16 elements (with SPLIT the
+  // workgroup itself owns one of gridDim.z consecutive ranges of steps)
   const int steps = (d + 15) / 16;
-  const int per = (steps + KS - 1) / KS;
-  const int s_begin = wave * per, s_end = min(steps, s_begin + per);
+  int wg_begin = 0, wg_end = steps;
+  if (SPLIT) {
+    const int per_wg = (steps + (int)gridDim.z - 1) / (int)gridDim.z;
+    wg_begin = min(steps, (int)blockIdx.z * per_wg);
+    wg_end = min(steps, wg_begin + per_wg);
+  }
+  const int per = (wg_end - wg_begin + KS - 1) / KS;
+  const int s_begin = min(wg_end, wg_begin + wave * per), s_end = min(wg_end, s_begin + per);
 
   f64x4 acc[TM][TN];
 #pragma unroll
@@ -113,7 +127,17 @@ __global__ __launch_bounds__(64 * KS) void hash_project_mfma_kernel(const float*
         for (int v = 0; v < 4; ++v) part[wave - 1][lane][(i * TN + j) * 4 + v] = acc[i][j][v];
   }
   __syncthreads();
-  if (wave == 0) {
+  if (wave != 0) return;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+#pragma unroll
+        for (int w = 0; w < KS - 1; ++w) acc[i][j][v] += part[w][lane][(i * TN + j) * 4 + v];
+  if (SPLIT) {
+    // partial sums [split][query][hash row] in fp64; hash_split_sum_kernel adds them
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -122,13 +146,22 @@ __global__ __launch_bounds__(64 * KS) void hash_project_mfma_kernel(const float*
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int q = q0 + 16 * i + 4 * v + g;
-          double sum = acc[i][j][v];
-#pragma unroll
-          for (int w = 0; w < KS - 1; ++w) sum += part[w][lane][(i * TN + j) * 4 + v];
-          if (q < B && h < H) Z[(size_t)q * H + h] = (float)(sum + (double)bh[h]);
+          if (q < B && h < H) gpart[((size_t)blockIdx.z * B + q) * H + h] = acc[i][j][v];
         }
       }
+    return;
   }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int h = h0 + 16 * j + r;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int q = q0 + 16 * i + 4 * v + g;
+        if (q < B && h < H) Z[(size_t)q * H + h] = (float)(acc[i][j][v] + (double)bh[h]);
+      }
+    }
 }
 
 // A handful of queries cannot fill a 16-row MFMA tile: one wavefront per (query, hash row),
@@ -213,13 +246,55 @@ __global__ __launch_bounds__(256) void hash_project_kernel(const float* __restri
   }
 }
 
+// Splitting the reduction over workgroups: at most SPLIT_MAX_WGS workgroups, each with its
+// partial 16x16 tile in fp64.
+constexpr int SPLIT_MAX_WGS = 512;
+
+__global__ __launch_bounds__(256) void hash_split_sum_kernel(const double* __restrict__ gpart, int S,
+                                                            const float* __restrict__ bh,
+                                                            float* __restrict__ Z, int B, int H) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= B * H) return;
+  double sum = 0.0;
+  for (int z = 0; z < S; ++z) sum += gpart[(size_t)z * B * H + i];
+  Z[i] = (float)(sum + (double)bh[i % H]);
+}
+
 }  // namespace
 
+size_t hash_split_workspace_bytes() { return (size_t)SPLIT_MAX_WGS * 256 * sizeof(double); }
+
+int hash_split_factor(int B, int H, int d) {
+  if (B <= 4 || d % 4 != 0) return 1;
+  const long tiles32 = (long)((H + 31) / 32) * ((B + 31) / 32);
+  if (tiles32 >= 128) return 1;
+  const int tiles16 = ((H + 15) / 16) * ((B + 15) / 16);
+  const int steps = (d + 15) / 16;
+  // at least 8 steps (128 elements of the rows) per workgroup
+  const int S = std::min(std::min(8, SPLIT_MAX_WGS / tiles16), steps / 8);
+  return S >= 2 ? S : 1;
+}
+
 int launch_hash_project(const float* X, int ldx, const float* Wh, const float* bh, float* Z, int B,
-                        int H, int d, hipStream_t s) {
+                        int H, int d, void* split_scratch, HashSplit* pending, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_HASH, s);
   const bool vec = (d % 4 == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
                    (reinterpret_cast<uintptr_t>(Wh) % 16 == 0);
+  const int S = (vec && split_scratch) ? hash_split_factor(B, H, d) : 1;
+  if (S > 1) {
+    double* gpart = static_cast<double*>(split_scratch);
+    dim3 g((H + 15) / 16, (B + 15) / 16, S);
+    hipLaunchKernelGGL((hash_project_mfma_kernel<1, 1, 4, 4, true>), g, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H,
+                       d, gpart);
+    SLONN_HIP(hipGetLastError());
+    if (pending) {
+      pending->part = gpart; pending->S = S; pending->bh = bh; pending->Z = Z;
+      return SLONN_OK;
+    }
+    hipLaunchKernelGGL(hash_split_sum_kernel, dim3((B * H + 255) / 256), dim3(256), 0, s, gpart, S, bh, Z, B, H);
+    SLONN_HIP(hipGetLastError());
+    return SLONN_OK;
+  }
   if (vec && B <= 4 && (size_t)d * 4 + 64 <= 65536) {
     hipLaunchKernelGGL(hash_project_rowwise_kernel, dim3((H + 3) / 4, B), dim3(256), (size_t)d * 4 + 64, s, X,
                        ldx, Wh, bh, Z, H, d);

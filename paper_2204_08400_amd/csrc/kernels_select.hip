@@ -76,17 +76,31 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
   }
 }
 
+// A medium batch leaves the hash projection's reduction split in hs.S partial sums per
+// (query, hash row).  Add them in split order, add the bias, and store the projections of
+// query q for this kernel and for the later readers.  Whole workgroup; ends with a barrier.
+__device__ __forceinline__ void sum_split_projections(const HashSplit& hs, int q, int B, int H) {
+  if (!hs.part) return;
+  const size_t plane = (size_t)B * H;
+  for (int h = threadIdx.x; h < H; h += blockDim.x) {
+    double sum = 0.0;
+    for (int z = 0; z < hs.S; ++z) sum += hs.part[z * plane + (size_t)q * H + h];
+    hs.Z[(size_t)q * H + h] = (float)(sum + (double)hs.bh[h]);
+  }
+  __syncthreads();
+}
+
 // slots per thread per round: both workgroup sizes cover up to 4096 slots in one round
 template <int NT>
 struct BlockMU { static constexpr int value = 4096 / NT; };
 
 template <int NT>
 __global__ __launch_bounds__(NT) void select_block_kernel(
-    const float* __restrict__ Z, int K, int L, int n, const uint32_t* __restrict__ dir,
+    const float* Z, int K, int L, int n, const uint32_t* __restrict__ dir,
     const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
-    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf) {
+    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf, HashSplit hsp) {
   extern __shared__ __align__(16) uint32_t smem32[];
   constexpr int MU = BlockMU<NT>::value;
   SelectShared<NT, MU> sh;
@@ -100,6 +114,7 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
   const int m = budget_of(keep[(size_t)q * keep_stride], n);
   int32_t* out = active + (size_t)q * idx_stride;
   const float* z = Z + (size_t)q * K * L;
+  sum_split_projections(hsp, q, gridDim.x, K * L);
   if (yzero) {
     float* y = yzero + (size_t)q * ldy;
     for (int i = tid; i < n; i += NT) y[i] = 0.0f;
@@ -127,11 +142,11 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
 }
 
 __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
-    const float* __restrict__ Z, int K, int L, int n, const uint32_t* __restrict__ dir,
+    const float* Z, int K, int L, int n, const uint32_t* __restrict__ dir,
     const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
-    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf) {
+    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf, HashSplit hsp) {
   extern __shared__ __align__(16) uint32_t smem32[];
   const int words = (n + 31) >> 5;
   SelectSharedWide<SEL_NT> sh;
@@ -147,6 +162,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   const int m = budget_of(keep[(size_t)q * keep_stride], n);
   int32_t* out = active + (size_t)q * idx_stride;
   const float* z = Z + (size_t)q * K * L;
+  sum_split_projections(hsp, q, gridDim.x, K * L);
   if (yzero) {
     float* y = yzero + (size_t)q * ldy;
     for (int i = tid; i < n; i += SEL_NT) y[i] = 0.0f;
@@ -187,9 +203,11 @@ __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t*
 int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
-                  int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first, hipStream_t s) {
+                  int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first,
+                  const HashSplit* split, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_SELECT, s);
   const HashFirst hf = hash_first ? *hash_first : HashFirst{};
+  const HashSplit hsp = split ? *split : HashSplit{};
   const size_t lds_block = ((size_t)n + SelectShared<SEL_NT, BlockMU<SEL_NT>::value>::words_besides_prio) * 4;
   if (lds_block <= (size_t)max_lds) {
     const RowBlocking rbv = rb ? *rb : RowBlocking{};
@@ -198,13 +216,13 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
       hipLaunchKernelGGL((select_block_kernel<SEL_NT_BIG>), dim3(B), dim3(SEL_NT_BIG), lds_block, s, Z, K, L, n,
-                         dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf);
+                         dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp);
     } else {
       if (lds_block > 65536)
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
       hipLaunchKernelGGL((select_block_kernel<SEL_NT>), dim3(B), dim3(SEL_NT), lds_block, s, Z, K, L, n, dir,
-                         ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf);
+                         ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp);
     }
     SLONN_HIP(hipGetLastError());
     return SLONN_OK;
@@ -217,7 +235,7 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_wide_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(select_wide_kernel, dim3(B), dim3(SEL_NT), lds, s, Z, K, L, n, dir, ids, global_rank,
-                     keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rb ? *rb : RowBlocking{}, hf);
+                     keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rb ? *rb : RowBlocking{}, hf, hsp);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

@@ -51,6 +51,7 @@ struct Workspace {
   int32_t* part_pos = nullptr;          // [B][max_n_activated]
   int32_t* blk_off = nullptr;           // [B][MAX_ROW_BLOCKS + 1]
   void* grouped = nullptr;              // union lists of the grouped evaluation
+  void* hash_split = nullptr;           // partial sums of the split hash projection
   size_t bytes = 0;
   int max_n = 0, max_H = 0, max_na = 0;
 };
@@ -81,6 +82,7 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   w->part_pos = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->blk_off = reinterpret_cast<int32_t*>(take((size_t)B * (MAX_ROW_BLOCKS + 1) * 4));
   w->grouped = take(grouped_workspace_bytes(B, std::max(max_na, 1), d_bf16));
+  w->hash_split = take(hash_split_workspace_bytes());
   w->bytes = off;
 }
 
@@ -513,13 +515,13 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
     z = static_cast<float*>(workspace);
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  int rc = launch_hash_project(X_l, L.d_in, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
+  int rc = launch_hash_project(X_l, L.d_in, L.Wh, L.bh, z, B, L.H(), L.d_in, nullptr, nullptr, s);
   if (rc) return rc;
   HashFirst hf;
   if (m->hash_first) { hf.hnodes = L.hnodes; hf.hslot = L.hslot; }
   return launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank, keep, keep_stride,
                        B, codes_out, active_idx, active_cnt, idx_stride, nullptr, 0, m->max_lds_bytes,
-                       nullptr, m->hash_first ? &hf : nullptr, s);
+                       nullptr, m->hash_first ? &hf : nullptr, nullptr, s);
 }
 
 namespace slonn {
@@ -690,9 +692,14 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       const bool tap_cnt = taps && taps->active_cnt && taps->active_cnt[l];
       if (is_last && Y->idx && !tap_idx) { aidx = Y->idx; astride = Y->stride; }
       if (is_last && Y->cnt && !tap_cnt) acnt = Y->cnt;
-      rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, s);
+      // (a medium batch leaves the projection's reduction split; the select kernel finishes it,
+      // unless the policy kernel needs the projections first)
+      HashSplit split;
+      const bool policy_here = hook && l == hook->layer;
+      rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, w.hash_split,
+                               policy_here ? nullptr : &split, s);
       if (rc) return rc;
-      if (hook && l == hook->layer) {
+      if (policy_here) {
         // the budget of this and of every later layer comes from the confidence tables
         rc = launch_policy_aclo(hook->p, nullptr, z, B, hook->thr, hook->thr_stride, hook->keep_out, nullptr,
                                 nullptr, s);
@@ -732,7 +739,8 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       if (m->hash_first) { hf.hnodes = L.hnodes; hf.hslot = L.hslot; }
       rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank,
                          keep + (size_t)l * keep_lstride, keep_qstride, B, codes, aidx, acnt, astride, out,
-                         ldo, m->max_lds_bytes, rb.part_idx ? &rb : nullptr, m->hash_first ? &hf : nullptr, s);
+                         ldo, m->max_lds_bytes, rb.part_idx ? &rb : nullptr, m->hash_first ? &hf : nullptr,
+                         split.part ? &split : nullptr, s);
       if (rc) return rc;
       act_list = aidx; act_cnt = acnt; act_stride = astride;
       if (is_last && Y->val) yc = Y->val;

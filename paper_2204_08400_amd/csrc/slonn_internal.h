@@ -182,17 +182,33 @@ struct HashFirst {
   const int16_t* hslot = nullptr;    // [n] device: index among the hash rows or -1
 };
 
+// A hash projection whose reduction is still split in S partial sums (medium batches): the
+// select kernel adds them.  part: [S][B][H] fp64 device; Z: [B][H] receives the projections.
+struct HashSplit {
+  const double* part = nullptr;
+  int S = 0;
+  const float* bh = nullptr;
+  float* Z = nullptr;
+};
+
 // ---- kernel launchers (each validates nothing: callers have checked shapes) ----
 
 // Z[q][h] = Wh[h] . X[q] + bh[h], fp64 accumulation, rounded once to fp32.
+// split_scratch (nullable): hash_split_workspace_bytes() of device memory; with it a medium
+// batch splits the reduction dimension over workgroups (hash_split_factor > 1 tells when).
+// pending (nullable): when the reduction was split, receives the partial sums for launch_select
+// to add, and Z is not written here; without it a small kernel adds them right away.
 int launch_hash_project(const float* X, int ldx, const float* Wh, const float* bh, float* Z, int B,
-                        int H, int d, hipStream_t s);
+                        int H, int d, void* split_scratch, HashSplit* pending, hipStream_t s);
+size_t hash_split_workspace_bytes();
+int hash_split_factor(int B, int H, int d);
 
 // keys + bucket lookup + merge for one layer.  yzero (nullable): [B][ldy] rows to clear.
 int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
-                  int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first, hipStream_t s);
+                  int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first,
+                  const HashSplit* split, hipStream_t s);
 // true when launch_select will fill rb for a layer of n nodes (the workgroup kernel is used)
 bool select_fills_row_blocks(int n, int max_lds);
 
