@@ -79,12 +79,12 @@ def main():
     xb = to_dev(X_build)
     dn = plain.dense_forward(xb, layer_outs=True)
     for l in cfg.hashed_layers:
-        var = dn["layers"][l].var(dim=0, unbiased=False).double().cpu().numpy()
         layers[l].K, layers[l].L = cfg.K, cfg.L
         # lists never need more entries than the largest budget below d_out that will be asked for
         top = max([k for k in cfg.keeps if k < 1.0] + ([cfg.keep_range[1]] if cfg.keep_range else []) + [args.keep])
         layers[l].list_cap = min(layers[l].d_out, int(np.ceil(top * layers[l].d_out)) + 1)
-        layers[l].hash_nodes = wl.sample_hash_nodes(var, cfg.K, cfg.L, seed=3 + l)
+        layers[l].hash_nodes = runtime.hash_nodes_by_variance(dn["layers"][l], cfg.K, cfg.L,
+                                                              wl.hash_node_draws(cfg.K, cfg.L, seed=3 + l))
     del plain, dn
     net = runtime.Network(layers, first_layer_rows_are_inputs=ell)
     t0 = time.time()

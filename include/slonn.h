@@ -164,6 +164,27 @@ int slonn_model_set_path(slonn_model* m, int path);
  * Applies to slonn_select and slonn_sparse_forward on every path.  EINVAL: null model.    */
 int slonn_model_set_hash_nodes_always_active(slonn_model* m, int on);
 
+/* Choice of the FreeHash nodes (Section 3.4): the K*L hash nodes of a layer are drawn with
+ * probability proportional to the variance of the nodes' activations over the training set of
+ * the tables.  Two steps, both before slonn_model_create (hash_nodes is one of its inputs).
+ *
+ * slonn_activation_variance: A is a device matrix [N][n] (row stride lda >= n, in floats) of
+ * one layer's activations over N inputs, e.g. a layer output of slonn_dense_forward.
+ * var_out[j] (device, n doubles) = (1/N) sum_i (A[i][j] - mean_j)^2 with mean_j = (1/N) sum_i
+ * A[i][j], both sums in fp64 over i ascending per quarter of the rows, the four quarters added
+ * in order.  Asynchronous on `stream`.  EINVAL: null pointer, N < 1, n < 1, lda < n.
+ *
+ * slonn_sample_hash_nodes: host arrays.  variance[n] (negative or non-finite entries count as
+ * 0), u[K*L] uniform draws in [0,1) supplied by the caller.  K*L sequential draws without
+ * replacement: with P_i the running sum of the remaining variances v_0..v_i in fp64, i
+ * ascending, draw j takes the first i with P_i > u[j] * P_{n-1} (the last node if rounding
+ * leaves none; from there the next node with v > 0, cyclically, if that one is exhausted) and
+ * then sets v_i = 0.  When no variance is left, the lowest node id not drawn yet.
+ * hash_nodes_out[j] serves table j / K, bit j % K.  EINVAL: null pointer, K*L < 1, K*L > n.  */
+int slonn_activation_variance(const float* A, int64_t N, int n, int64_t lda, double* var_out, void* stream);
+int slonn_sample_hash_nodes(const double* variance, int n, int K, int L, const double* u,
+                            int32_t* hash_nodes_out);
+
 /* Alg. 1 for every activated layer, on the device.  X_build holds N training inputs
  * (device).  Input_l is the full network's output of layer l-1 on X_build; the
  * Activation summed into NodeScore is layer l's own output; each bucket keeps its

@@ -222,6 +222,46 @@ def argmax(out, active=None, cnt=None):
 # --------------------------------------------------------------------------- #
 # choice of k per query (Section 2: ACLO / LCAO; Section 3.2: Confidence LSH tables)
 # --------------------------------------------------------------------------- #
+def activation_variance(A) -> np.ndarray:
+    """Per-node variance of the activations A [N][n] over the N inputs, in float64
+    (Section 3.4: the statistic the FreeHash nodes are sampled by); 1/N normalisation."""
+    A = np.asarray(A, dtype=np.float64)
+    mean = A.sum(axis=0) / A.shape[0]
+    return ((A - mean) ** 2).sum(axis=0) / A.shape[0]
+
+
+def sample_hash_nodes(variance, K: int, L: int, u) -> np.ndarray:
+    """K*L distinct node ids drawn with probability proportional to ``variance``
+    (Section 3.4), one uniform u[j] in [0, 1) per draw, sequentially and without
+    replacement: draw j inverts the running sums of the remaining variances at
+    u[j] times their total, then removes the drawn node.  Negative or non-finite
+    variances count as zero; zero-variance nodes are only drawn (lowest id first)
+    once no variance is left.  The j-th id serves table j // K, bit j % K.
+    """
+    v = np.asarray(variance, dtype=np.float64).copy()
+    n, H = v.shape[0], K * L
+    if H > n:
+        raise ValueError("K*L exceeds the number of nodes in the layer")
+    v[~np.isfinite(v)] = 0.0
+    v = np.maximum(v, 0.0)
+    out = np.empty(H, dtype=np.int32)
+    taken = np.zeros(n, dtype=bool)
+    for j in range(H):
+        c = np.cumsum(v)                       # running sums, left to right
+        total = c[-1]
+        if total > 0.0:
+            i = int(np.searchsorted(c, u[j] * total, side="right"))   # first running sum above the target
+            i = min(i, n - 1)
+            while v[i] <= 0.0:                 # landed on an exhausted id through rounding
+                i = (i + 1) % n
+        else:                                  # no variance left: lowest unused id
+            i = int(np.argmin(taken))
+        out[j] = i
+        taken[i] = True
+        v[i] = 0.0
+    return out
+
+
 class ConfidenceTables:
     """Per bucket, the sums and counts of the training inputs' confidences c(k_g, x')."""
 

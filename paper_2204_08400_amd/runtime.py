@@ -19,6 +19,14 @@ def _dev(a: np.ndarray, device):
     return torch.from_numpy(np.ascontiguousarray(a)).to(device)
 
 
+def hash_nodes_by_variance(acts: torch.Tensor, K: int, L: int, u: np.ndarray) -> np.ndarray:
+    """K*L hash nodes of a layer from its activations [N][n] over the tables' training set
+    (device tensor): variance on the device, the draws u consumed by the library's sampler."""
+    var = torch.empty(acts.shape[1], dtype=torch.float64, device=acts.device)
+    slonn.slonn_activation_variance(acts, var)
+    return slonn.slonn_sample_hash_nodes(var.cpu().numpy(), K, L, u)
+
+
 class Network:
     def __init__(self, layers: Sequence, device="cuda:0", first_layer_rows_are_inputs=False):
         """layers: workloads.LayerData-like objects (host numpy arrays)."""

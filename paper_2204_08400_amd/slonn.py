@@ -10,6 +10,8 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+
+import numpy as np
 from typing import List, Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -31,6 +33,7 @@ EXPORTS = [
     "slonn_policy_set_latency_profile", "slonn_policy_keep_aclo", "slonn_policy_keep_lcao",
     "slonn_sparse_forward_aclo",
     "slonn_forward_graph_create", "slonn_forward_graph_launch", "slonn_forward_graph_destroy",
+    "slonn_activation_variance", "slonn_sample_hash_nodes",
 ]
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused")
 PATH_AUTO, PATH_LAYERS, PATH_FUSED = 0, 1, 2
@@ -327,6 +330,28 @@ def slonn_sparse_forward_aclo(model: Model, tables: Optional[Tables], policy: Po
         C.byref(taps) if taps is not None else None, C.c_void_p(_ptr(workspace)),
         C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
         C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_activation_variance(A, var_out, stream=None):
+    """A: device float32 [N][n] (rows may be strided), var_out: device float64 [n]."""
+    if A.dim() != 2 or A.stride(1) != 1:
+        raise ValueError("A must be a 2-D tensor with unit column stride")
+    _check(load().slonn_activation_variance(C.c_void_p(A.data_ptr()), C.c_int64(A.shape[0]), int(A.shape[1]),
+                                            C.c_int64(A.stride(0)), C.c_void_p(_ptr(var_out)),
+                                            C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_sample_hash_nodes(variance: np.ndarray, K: int, L: int, u: np.ndarray) -> np.ndarray:
+    """Host arrays: variance float64 [n], u float64 [K*L] in [0, 1); returns int32 [K*L]."""
+    variance = np.ascontiguousarray(variance, dtype=np.float64)
+    u = np.ascontiguousarray(u, dtype=np.float64)
+    if u.shape[0] != K * L:
+        raise ValueError("u must hold K*L draws")
+    out = np.empty(K * L, dtype=np.int32)
+    _check(load().slonn_sample_hash_nodes(variance.ctypes.data_as(C.c_void_p), int(variance.shape[0]), int(K),
+                                          int(L), u.ctypes.data_as(C.c_void_p),
+                                          out.ctypes.data_as(C.c_void_p)))
+    return out
 
 
 class ForwardGraph:

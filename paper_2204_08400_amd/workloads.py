@@ -168,38 +168,10 @@ def keep_uniform(N: int, lo: float, hi: float, seed: int) -> np.ndarray:
     return (lo + (hi - lo) * uniform01(seed, 6, 0, N)).astype(np.float32)
 
 
-def sample_hash_nodes(variance: np.ndarray, K: int, L: int, seed: int) -> np.ndarray:
-    """Draw K*L distinct node ids with probability proportional to ``variance``.
-
-    Sequential draws without replacement; nodes with zero variance are never
-    drawn while a positive-variance node remains (Section 3.4: FreeHash nodes
-    are sampled proportionally to the variance of their activations over the
-    LSH training set).  The j-th id drawn serves table j // K, bit j % K.
-    """
-    v = np.asarray(variance, dtype=np.float64).copy()
-    n = v.shape[0]
-    H = K * L
-    if H > n:
-        raise ValueError("K*L exceeds the number of nodes in the layer")
-    v[~np.isfinite(v)] = 0.0
-    v = np.maximum(v, 0.0)
-    u = uniform01(seed, 7, 0, H)
-    out = np.empty(H, dtype=np.int32)
-    taken = np.zeros(n, dtype=bool)
-    for j in range(H):
-        total = v.sum()
-        if total > 0.0:
-            c = np.cumsum(v)
-            i = int(np.searchsorted(c, u[j] * total, side="right"))
-            i = min(i, n - 1)
-            while v[i] <= 0.0:            # guard against landing on an exhausted id
-                i = (i + 1) % n
-        else:                             # no variance left: lowest unused id
-            i = int(np.argmin(taken))
-        out[j] = i
-        taken[i] = True
-        v[i] = 0.0
-    return out
+def hash_node_draws(K: int, L: int, seed: int) -> np.ndarray:
+    """The K*L uniform draws in [0, 1) that the sampling of a layer's hash nodes consumes
+    (an input to both implementations of that sampling)."""
+    return uniform01(seed, 7, 0, K * L)
 
 
 # --------------------------------------------------------------------------- #

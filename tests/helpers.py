@@ -26,7 +26,8 @@ def make_case(oracle, dims, K, L, seed, hashed=None, cap=None, N_build=256, w_dt
         lay = layers[l]
         lay.K, lay.L = K, L
         lay.list_cap = lay.d_out if cap is None else cap
-        lay.hash_nodes = wl.sample_hash_nodes(dense[l].astype(np.float64).var(axis=0), K, L, seed + 3 + l)
+        lay.hash_nodes = oracle.sample_hash_nodes(oracle.activation_variance(dense[l]), K, L,
+                                                  wl.hash_node_draws(K, L, seed + 3 + l))
     net.build_tables(Xb)
     return layers, net, Xb
 

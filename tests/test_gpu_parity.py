@@ -237,6 +237,32 @@ def test_edge_cases(rt, oracle, path):
                                    slonn.make_output(), None, g.workspace(1))
 
 
+@pytest.mark.gpu
+def test_hash_node_choice_matches_oracle(rt, oracle):
+    """Section 3.4: per-node activation variance on the device against the oracle's float64
+    variance (same activation matrix; ragged sizes, a strided view, a single row), then the
+    variance-proportional draws, id for id."""
+    import torch
+    from paper_2204_08400_amd import slonn
+    rng = np.random.default_rng(21)
+    for N, n, pad in [(1003, 130, 0), (257, 64, 5), (1, 70, 0), (4099, 1000, 24), (3, 1, 0)]:
+        _say(f"activation variance N={N} n={n} pad={pad}")
+        A = np.maximum(rng.normal(size=(N, n + pad)) * rng.random(n + pad) * 3 + 0.2, 0).astype(np.float32)
+        A[:, ::7] = 0.0                                   # dead nodes: variance exactly 0
+        dev = torch.from_numpy(A).cuda()
+        view = dev[:, :n]                                 # row stride n + pad
+        var = torch.empty(n, dtype=torch.float64, device="cuda")
+        slonn.slonn_activation_variance(view, var)
+        got = var.cpu().numpy()
+        want = oracle.activation_variance(A[:, :n])
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=0)
+        assert (got[::7] == 0).all()
+        if n >= 64:
+            K, L = 4, 8
+            u = wl.hash_node_draws(K, L, seed=N)
+            assert rt.hash_nodes_by_variance(view, K, L, u).tolist() == oracle.sample_hash_nodes(want, K, L, u).tolist()
+
+
 BUILD_CASES = [
     dict(dims=(100, 300, 260, 37), K=4, L=6, cap=200, N=500, hashed=None, last_act=wl.ACT_NONE),
     dict(dims=(48, 10000, 16), K=5, L=4, cap=400, N=300, hashed=[0], last_act=wl.ACT_NONE),       # wide ReLU layer
@@ -311,10 +337,10 @@ def _config_case(rt, cfg_name, n_build, n_query, seed_w=0, list_cap=None):
     xb = torch.from_numpy(Xb).cuda()
     dn = plain.dense_forward(xb, layer_outs=True)
     for l in cfg.hashed_layers:
-        var = dn["layers"][l].double().var(dim=0, unbiased=False).cpu().numpy()
         layers[l].K, layers[l].L = cfg.K, cfg.L
         layers[l].list_cap = layers[l].d_out if list_cap is None else list_cap
-        layers[l].hash_nodes = wl.sample_hash_nodes(var, cfg.K, cfg.L, seed=3 + l)
+        layers[l].hash_nodes = rt.hash_nodes_by_variance(dn["layers"][l], cfg.K, cfg.L,
+                                                         wl.hash_node_draws(cfg.K, cfg.L, seed=3 + l))
     del plain, dn
     g = rt.Network(layers)
     g.build_tables(xb)

@@ -126,3 +126,31 @@ def test_policy_create_rejects(slonn, K, L, grid):
     assert not h.value
     assert lib.slonn_policy_create(4, 4, None, 1, C.byref(h)) == slonn.EINVAL
     assert lib.slonn_policy_create(4, 4, arr, 1, None) == slonn.EINVAL
+
+
+def test_sample_hash_nodes_matches_oracle(slonn):
+    """The library's host-side sampler (Section 3.4) against the oracle's, id for id, on
+    variances with zeros, negatives, NaN and infinities, including samples that exhaust the
+    positive-variance nodes."""
+    from oracle import slonn_oracle
+    rng = np.random.default_rng(5)
+    for n, K, L, zero_frac in [(7, 1, 7, 0.0), (64, 4, 6, 0.3), (500, 6, 10, 0.9), (300, 8, 16, 0.5),
+                               (1000, 12, 50, 0.2), (33, 3, 11, 1.0)]:
+        v = rng.random(n) * rng.choice([1e-6, 1.0, 1e6], size=n)
+        v[rng.random(n) < zero_frac] = 0.0
+        if n >= 64:
+            v[3], v[10], v[20] = -1.0, np.nan, np.inf
+        u = rng.random(K * L)
+        got = slonn.slonn_sample_hash_nodes(v, K, L, u)
+        want = slonn_oracle.sample_hash_nodes(v, K, L, u)
+        assert got.tolist() == want.tolist(), (n, K, L)
+
+
+def test_sample_hash_nodes_rejects(slonn):
+    v = np.ones(8)
+    with pytest.raises(slonn.SlonnError) as e:
+        slonn.slonn_sample_hash_nodes(v, 3, 3, np.zeros(9))      # K*L > n
+    assert e.value.code == -1
+    lib = slonn.load()
+    assert lib.slonn_sample_hash_nodes(None, 8, 1, 1, None, None) == -1
+    assert lib.slonn_activation_variance(None, C.c_int64(4), 4, C.c_int64(4), None, None) == -1

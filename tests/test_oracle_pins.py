@@ -126,7 +126,8 @@ def _small_net(oracle, dims, K, L, seed, hashed=None, cap=None, N_build=200, w_d
         lay = layers[l]
         lay.K, lay.L = K, L
         lay.list_cap = lay.d_out if cap is None else cap
-        lay.hash_nodes = wl.sample_hash_nodes(dense[l].var(axis=0), K, L, seed + 3 + l)
+        lay.hash_nodes = oracle.sample_hash_nodes(oracle.activation_variance(dense[l]), K, L,
+                                                  wl.hash_node_draws(K, L, seed + 3 + l))
     net.build_tables(Xb, keep_scores=keep_scores)
     return net, Xb
 
@@ -644,3 +645,57 @@ def test_forward_under_aclo_equals_forward_with_the_chosen_k(oracle):
     assert np.array_equal(res["out"], ref["out"])
     for l in (0, 1):
         assert np.array_equal(res["layers"][l]["cnt"], [oracle.budget(k, net.layers[l].d_out) for k in keep])
+
+
+# --------------------------------------------------------------------------- #
+# choice of the FreeHash nodes (Section 3.4): variance-proportional sampling
+# --------------------------------------------------------------------------- #
+def test_activation_variance_closed_forms(oracle):
+    """Columns with a known variance: a constant (0), the ramp 0..N-1 ((N^2-1)/12), a
+    two-valued column (p(1-p)(a-b)^2), and a shifted copy (variance ignores the shift)."""
+    N = 1000
+    ramp = np.arange(N, dtype=np.float64)
+    two = np.where(np.arange(N) % 4 == 0, 3.0, -1.0)          # p = 1/4, a - b = 4
+    A = np.stack([np.full(N, 7.5), ramp, two, ramp + 1e3], axis=1).astype(np.float32)
+    var = oracle.activation_variance(A)
+    want = [0.0, (N * N - 1) / 12.0, 0.25 * 0.75 * 16.0, (N * N - 1) / 12.0]
+    np.testing.assert_allclose(var, want, rtol=1e-12, atol=1e-12)
+    rng = np.random.default_rng(4)
+    R = rng.normal(size=(257, 33)).astype(np.float32)
+    np.testing.assert_allclose(oracle.activation_variance(R), R.astype(np.float64).var(axis=0), rtol=1e-12)
+
+
+def test_sample_hash_nodes_worked_draws(oracle):
+    """Draws worked by hand from the rule: running sums of the remaining variances, first
+    running sum above u * total, drawn node removed."""
+    # v = [1, 0, 3]: sums [1, 1, 4], target .5 * 4 = 2 -> node 2; then [1, 0, 0]: sums [1, 1, 1],
+    # target .9 -> node 0; nothing left -> lowest unused id, node 1
+    assert oracle.sample_hash_nodes([1.0, 0.0, 3.0], 3, 1, [0.5, 0.9, 0.3]).tolist() == [2, 0, 1]
+    # v = [2, 2, 2, 2]: target 0 -> node 0; [0, 2, 2, 2] sums [0, 2, 4, 6], target .99 * 6 -> node 3;
+    # [0, 2, 2, 0] sums [0, 2, 4, 4], target .5 * 4 = 2: the first sum ABOVE 2 is node 2's; then node 1
+    assert oracle.sample_hash_nodes([2.0] * 4, 2, 2, [0.0, 0.99, 0.5, 0.5]).tolist() == [0, 3, 2, 1]
+    # negative and non-finite variances count as zero
+    assert oracle.sample_hash_nodes([-5.0, np.nan, 1.0, np.inf], 1, 2, [0.7, 0.2]).tolist() == [2, 0]
+
+
+def test_sample_hash_nodes_is_proportional_and_without_replacement(oracle):
+    """First draw: over an even grid of u the frequency of node i is v_i / sum(v) (inverse
+    CDF).  Whole sample: distinct ids; zero-variance nodes only after every other node."""
+    v = np.array([1.0, 2.0, 3.0, 4.0])
+    G = 10000
+    first = np.array([oracle.sample_hash_nodes(v, 1, 1, [(g + 0.5) / G])[0] for g in range(G)])
+    np.testing.assert_array_equal(np.bincount(first, minlength=4), (v / v.sum() * G).astype(int))
+    rng = np.random.default_rng(11)
+    v = rng.random(200)
+    v[rng.random(200) < 0.4] = 0.0
+    pos = int((v > 0).sum())
+    ids = oracle.sample_hash_nodes(v, 10, 15, rng.random(150))
+    assert len(set(ids.tolist())) == 150
+    assert (v[ids[:min(pos, 150)]] > 0).all()
+    if pos < 150:
+        rest = ids[pos:]
+        assert (v[rest] == 0).all() and (np.diff(rest) > 0).all()      # lowest unused id first
+    # second draw conditioned on the first: proportional among the remaining nodes
+    v = np.array([5.0, 1.0, 2.0, 2.0])
+    second = np.array([oracle.sample_hash_nodes(v, 2, 1, [0.1, (g + 0.5) / G])[1] for g in range(G)])
+    np.testing.assert_array_equal(np.bincount(second, minlength=4), [0, 2000, 4000, 4000])
