@@ -565,13 +565,13 @@ def test_argument_errors_on_device(rt, oracle):
         slonn.slonn_workspace_bytes(g.model, (1 << 20) + 1)
 
 
-@pytest.mark.parametrize("w_dtype", [wl.W_F32, wl.W_BF16], ids=["f32", "bf16"])
-def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype):
+@pytest.mark.parametrize("w_dtype,d", [(wl.W_F32, 512), (wl.W_F32, 520), (wl.W_BF16, 1024), (wl.W_BF16, 1032)],
+                         ids=["f32", "f32-ragged-rows", "bf16", "bf16-ragged-rows"])
+def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d):
     """Large batch on the per-layer path: groups of 16 queries whose active sets overlap are
     evaluated together on the matrix cores (union of rows x 16 queries, selected pairs kept);
     groups with little overlap stay on the per-query gather.  Same results either way."""
     from paper_2204_08400_amd import slonn
-    d = 512 if w_dtype == wl.W_F32 else 1024
     dims = (d, 4096, 24)
     layers, net, _ = make_case(oracle, dims, 6, 8, seed=61, hashed=[0], cap=1500, N_build=192, kind="clip3",
                                w_dtype=w_dtype)
