@@ -170,6 +170,21 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- what a plain device copy reaches on this GPU (256 MiB read + 256 MiB written) ----
+    src = torch.empty(1 << 26, dtype=torch.float32, device=dev).fill_(1.0)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 20 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    log(f"plain device copy: {copy_gbps:,.0f} GB/s (read + write)")
+
     # ---- headline: K steps at the chosen keep fraction ----
     dev_s, wall_s = timed(args.keep, K, W)
     secs = max(dev_s, wall_s)             # the host loop must keep up: report the slower clock
@@ -213,6 +228,7 @@ def main():
             pass
 
     extra = {"effective_GBps": round(eff_gbps, 1), "frac_of_hbm_peak": round(eff_gbps / HBM_PEAK_GBPS, 4),
+             "measured_copy_GBps": round(copy_gbps, 1), "frac_of_measured_copy": round(eff_gbps / copy_gbps, 4),
              "per_step_us_with_event_overhead": {k: round(v, 2) for k, v in per_step_us.items()},
              "avg_launch_us_with_event_overhead": {k: round(v, 2) for k, v in split_us.items()}}
 
