@@ -1,0 +1,276 @@
+// Large batches of a large fp32 layer: evaluation of the selected (query, node) pairs as masked
+// dense tiles on the bf16 matrix cores (the paper's Section 6 names batch inference as future
+// work).  At batch 1024 every 128-node block of a layer is wanted by some of any 128 queries,
+// and a per-query gather moves keep x batch times the bytes of the matrix; a tile kernel moves
+// the matrix once per 128 queries and leaves the arithmetic to the matrix cores.
+//
+// Arithmetic: an fp32 number is the exact sum of three bf16 numbers (8 + 8 + 8 significand
+// bits): w = w_hi + w_mid + w_lo, x = x_hi + x_mid + x_lo.  Of the nine partial products the six
+// with at most 16 bits of combined offset are accumulated (each exact in fp32, smallest first);
+// the three left out (mid x lo, lo x mid, lo x lo) are below 2^-24 of the product, the size of
+// one fp32 rounding.  Six v_mfma_f32_16x16x32_bf16 replace sixteen fp32 MFMAs of the same
+// 16 x 16 x 32 block at a sixteenth of the cost each.
+//
+//   split3_kernel        fp32 rows -> three bf16 parts, interleaved per eight elements: element k
+//                        of part p of row i at i * 3 d + (k / 8) * 24 + 8 p + k % 8, so a row's
+//                        chunk of 32 elements is 192 contiguous bytes.  Weights once at model
+//                        creation, activations once per layer call.
+//   pair_mask_kernel     one bit per (query, node) pair of the active lists; per 128 queries the
+//                        decision whether the tile kernel or the per-query gather serves them.
+//   masked_tiles_kernel  128 queries x 128 nodes per workgroup, four wavefronts in 2 x 2, each
+//                        4 x 4 blocks of 16 x 16; chunks of 32 elements staged through LDS, the
+//                        next chunk's global loads in flight during the MFMAs; only selected
+//                        pairs are written.
+#include <algorithm>
+
+#include "slonn_internal.h"
+
+namespace slonn {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte piece (native vector: stays in registers)
+
+constexpr int TM = 128;           // queries per tile
+constexpr int TN = 128;           // nodes per tile
+constexpr int PIECES = 12;        // 16-byte pieces per row and chunk: 4 groups of 8 elements x 3 parts
+constexpr int ROW16 = PIECES + 1; // LDS row in 16-byte units (padded: 208 bytes staggers the banks)
+
+__global__ void split3_kernel(const float* __restrict__ X, int64_t ldx, int d, uint16_t* __restrict__ out) {
+  const int64_t row = blockIdx.x;
+  const int i = blockIdx.y * blockDim.x + threadIdx.x;
+  if (i >= d) return;
+  const float x = X[row * ldx + i];
+  const uint32_t hb = __float_as_uint(x) & 0xFFFF0000u;
+  const float r1 = x - __uint_as_float(hb);             // exact: hi keeps the leading bits of x
+  const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
+  const float r2 = r1 - __uint_as_float(mb);            // exact, at most 8 significant bits left
+  const size_t at = (size_t)row * 3 * d + (size_t)(i >> 3) * 24 + (i & 7);
+  out[at] = (uint16_t)(hb >> 16);
+  out[at + 8] = (uint16_t)(mb >> 16);
+  out[at + 16] = (uint16_t)(__float_as_uint(r2) >> 16);
+}
+
+// One workgroup per query.  mask[q][w] bit j: node 32 w + j is in the query's list and is not a
+// hash node whose output was already taken from its projection.  flags (one per 16 queries, the
+// unit the per-query gather skips by): 1 when the 128 queries of the tile list at least
+// min_pairs (query, node) pairs together, i.e. the tile kernel is the cheaper way.
+__global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restrict__ active,
+                                                       const int32_t* __restrict__ cnt, int idx_stride, int B,
+                                                       int n, const int16_t* __restrict__ skip_hslot,
+                                                       uint32_t* __restrict__ mask, int32_t* __restrict__ flags,
+                                                       long long min_pairs) {
+  extern __shared__ uint32_t bits[];
+  const int q = blockIdx.x, tid = threadIdx.x;
+  const int words = (n + 31) >> 5;
+  for (int i = tid; i < words; i += 256) bits[i] = 0u;
+  __syncthreads();
+  const int c = cnt[q];
+  const int32_t* list = active + (size_t)q * idx_stride;
+  for (int t = tid; t < c; t += 256) {
+    const int node = list[t];
+    if (skip_hslot && skip_hslot[node] >= 0) continue;
+    atomicOr(&bits[node >> 5], 1u << (node & 31));
+  }
+  __syncthreads();
+  for (int i = tid; i < words; i += 256) mask[(size_t)q * words + i] = bits[i];
+  if (q % TM == 0 && tid < 64) {
+    long long sum = 0;
+    for (int i = tid; i < TM && q + i < B; i += 64) sum += cnt[q + i];
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    const int f = sum >= min_pairs ? 1 : 0;
+    if (tid < TM / 16) flags[q / 16 + tid] = f;
+  }
+}
+
+// Barrier that orders LDS traffic only: global loads issued before it stay in flight across it
+// (__syncthreads would wait for them as well).
+__device__ __forceinline__ void lds_only_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// X3, W3: rows in three interleaved bf16 parts (see above); d a multiple of 32.
+// Lane layout of v_mfma_f32_16x16x32_bf16 (checked on gfx950): lane l feeds row l % 16 of its
+// operand with the eight elements 8 (l / 16) .. + 7 of the step; register v of lane l holds
+// D[4 (l / 16) + v][l % 16], rows from the first operand (here: nodes), columns from the second
+// (queries).
+__global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __restrict__ X3,
+                                                          const uint16_t* __restrict__ W3,
+                                                          const float* __restrict__ bias,
+                                                          const uint32_t* __restrict__ mask,
+                                                          const int32_t* __restrict__ flags,
+                                                          float* __restrict__ Y, int ldy, int B, int n, int d,
+                                                          int act) {
+  extern __shared__ u32x4 tiles_lds[];     // two buffers of [TM + TN rows][ROW16]
+  constexpr int BUF16 = (TM + TN) * ROW16;
+  const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+  if (!flags[m0 / 16]) return;             // these queries are served by the per-query gather
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wq = wave >> 1, wn = wave & 1;
+  const int r = lane & 15, kg = lane >> 4;
+
+  // loader: 128 rows x 12 pieces per operand and chunk, six pieces per thread; rows beyond the
+  // batch or the layer repeat the last valid row (their results are dropped)
+  const u32x4* xsrc[6];
+  const u32x4* wsrc[6];
+  int dst[6];
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    const int idx = tid + 256 * i, row = idx / PIECES, piece = idx % PIECES;
+    xsrc[i] = reinterpret_cast<const u32x4*>(X3 + (size_t)min(m0 + row, B - 1) * 3 * d) + piece;
+    wsrc[i] = reinterpret_cast<const u32x4*>(W3 + (size_t)min(n0 + row, n - 1) * 3 * d) + piece;
+    dst[i] = row * ROW16 + piece;
+  }
+  // Chunk c is multiplied out of LDS buffer c % 2 while chunk c + 1 moves from registers into the
+  // other buffer and chunk c + 2 is on its way from L2 (one barrier per chunk, and one that
+  // orders LDS traffic only: the global loads stay in flight across it).  Chunks past the end
+  // repeat the last one and are dropped.  A chunk of 32 elements is 12 pieces per row.
+  const int nchunks = d / 32;
+  u32x4 rx[6], rw[6];
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    rx[i] = xsrc[i][0];
+    rw[i] = wsrc[i][0];
+  }
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    tiles_lds[dst[i]] = rx[i];
+    tiles_lds[TM * ROW16 + dst[i]] = rw[i];
+  }
+  {
+    const size_t next = (size_t)min(1, nchunks - 1) * PIECES;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      rx[i] = xsrc[i][next];
+      rw[i] = wsrc[i][next];
+    }
+  }
+  lds_only_barrier();
+
+  f32x4 acc[4][4];                         // [node block][query block]
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  for (int c = 0; c < nchunks; ++c) {
+    const u32x4* Xs = tiles_lds + (c & 1) * BUF16;
+    const u32x4* Ws = Xs + TM * ROW16;
+    bf16x8 xb[4][3];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int p = 0; p < 3; ++p) xb[b][p] = as_bf16x8(Xs[(wq * 64 + b * 16 + r) * ROW16 + kg * 3 + p]);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      bf16x8 wa[3];
+#pragma unroll
+      for (int p = 0; p < 3; ++p) wa[p] = as_bf16x8(Ws[(wn * 64 + a * 16 + r) * ROW16 + kg * 3 + p]);
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        f32x4 v = acc[a][b];               // smallest partial products first
+        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[2], xb[b][0], v, 0, 0, 0);
+        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[1], xb[b][1], v, 0, 0, 0);
+        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][2], v, 0, 0, 0);
+        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[1], xb[b][0], v, 0, 0, 0);
+        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][1], v, 0, 0, 0);
+        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][0], v, 0, 0, 0);
+        acc[a][b] = v;
+      }
+    }
+    u32x4* Xn = tiles_lds + ((c + 1) & 1) * BUF16;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      Xn[dst[i]] = rx[i];
+      Xn[TM * ROW16 + dst[i]] = rw[i];
+    }
+    const size_t next = (size_t)min(c + 2, nchunks - 1) * PIECES;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      rx[i] = xsrc[i][next];
+      rw[i] = wsrc[i][next];
+    }
+    lds_only_barrier();
+  }
+
+  // register v of block (a, b): node n0 + 64 wn + 16 a + 4 kg + v, query m0 + 64 wq + 16 b + r
+  const int words = (n + 31) >> 5;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int q = m0 + wq * 64 + b * 16 + r;
+    if (q >= B) continue;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int node = n0 + wn * 64 + a * 16 + 4 * kg;      // a multiple of 4: its four bits share a word
+      if (node >= n) continue;
+      const uint32_t four = (mask[(size_t)q * words + (node >> 5)] >> (node & 31)) & 0xFu;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        if (((four >> v) & 1u) && node + v < n) {
+          float z = acc[a][b][v] + bias[node + v];
+          if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+          Y[(size_t)q * ldy + node + v] = z;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+bool masked_tiles_supported(int w_dtype, int d, int n, int max_lds) {
+  return w_dtype == SLONN_F32 && d % 32 == 0 && (size_t)((n + 31) / 32) * 4 <= (size_t)max_lds &&
+         (size_t)2 * (TM + TN) * ROW16 * 16 <= (size_t)max_lds;
+}
+
+size_t masked_tiles_workspace_bytes(int B, int n, int d) {
+  const size_t mask = ((size_t)B * ((n + 31) / 32) * 4 + 255) / 256 * 256;
+  const size_t flags = ((size_t)(B / 16 + TM / 16 + 1) * 4 + 255) / 256 * 256;
+  return mask + flags + (size_t)B * 3 * d * 2 + 256;
+}
+
+int launch_split3(const float* X, int64_t ldx, int64_t rows, int d, uint16_t* out, hipStream_t s) {
+  hipLaunchKernelGGL(split3_kernel, dim3((unsigned)rows, (d + 255) / 256), dim3(256), 0, s, X, ldx, d, out);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+int launch_masked_tiles(const uint16_t* W3, const float* bias, const float* X, int ldx, const int32_t* active,
+                        const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d, int n, int act,
+                        const int16_t* skip_hslot, int min_keep_permille, void* scratch, int32_t** flags_out,
+                        hipStream_t s) {
+  const int words = (n + 31) / 32;
+  const size_t mask_bytes = ((size_t)B * words * 4 + 255) / 256 * 256;
+  const size_t flag_bytes = ((size_t)(B / 16 + TM / 16 + 1) * 4 + 255) / 256 * 256;
+  uint32_t* mask = static_cast<uint32_t*>(scratch);
+  int32_t* flags = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + mask_bytes);
+  uint16_t* X3 = reinterpret_cast<uint16_t*>(static_cast<char*>(scratch) + mask_bytes + flag_bytes);
+  *flags_out = flags;
+  {
+    ProfScope prof_(SLONN_PROF_SELECT, s);
+    // the tile kernel serves 128 queries when they list at least this many pairs together
+    const long long min_pairs = (long long)TM * n * min_keep_permille / 1000;
+    hipLaunchKernelGGL(pair_mask_kernel, dim3(B), dim3(256), (size_t)words * 4, s, active, cnt, idx_stride, B, n,
+                       skip_hslot, mask, flags, min_pairs);
+    SLONN_HIP(hipGetLastError());
+    int rc = launch_split3(X, ldx, B, d, X3, s);
+    if (rc) return rc;
+  }
+  ProfScope prof_(SLONN_PROF_GATHER, s);
+  const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
+  constexpr size_t lds = (size_t)2 * (TM + TN) * ROW16 * 16;
+  static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
+  SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(masked_tiles_kernel, dim3((n + TN - 1) / TN, (B + TM - 1) / TM), dim3(256), lds, s, X3, W3,
+                     bias, mask, flags, Y, ldy, B, n, d, a);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+}  // namespace slonn

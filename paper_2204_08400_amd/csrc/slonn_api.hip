@@ -81,7 +81,10 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   w->part_idx = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->part_pos = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->blk_off = reinterpret_cast<int32_t*>(take((size_t)B * (MAX_ROW_BLOCKS + 1) * 4));
-  w->grouped = take(grouped_workspace_bytes(B, std::max(max_na, 1), d_bf16));
+  size_t grouped_bytes = grouped_workspace_bytes(B, std::max(max_na, 1), d_bf16);
+  for (const Layer& l : m->layers)
+    if (l.W3) grouped_bytes = std::max(grouped_bytes, masked_tiles_workspace_bytes(B, l.d_out, l.d_in));
+  w->grouped = take(grouped_bytes);
   w->hash_split = take(hash_split_workspace_bytes());
   w->bytes = off;
 }
@@ -254,6 +257,21 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
       set_error("uploading the hash-node map failed: %s", hipGetErrorString(e));
       return fail(SLONN_EHIP);
     }
+    // Large fp32 layers (the ones the forward pass walks in row blocks): the weights once more as
+    // three bf16 parts, for the masked tiles that serve large batches on the bf16 matrix cores.
+    // Without the memory for it large batches stay on the other paths.
+    const size_t row_bytes = (size_t)L.d_in * 4;
+    if (masked_tiles_supported(L.w_dtype, L.d_in, L.d_out, m->max_lds_bytes) &&
+        L.w_layout == SLONN_ROWS_ARE_NODES && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20)) {
+      if (hipMalloc(&L.W3, (size_t)3 * L.d_out * L.d_in * 2) != hipSuccess) {
+        (void)hipGetLastError();
+        L.W3 = nullptr;
+      } else if (launch_split3(static_cast<const float*>(L.W), L.d_in, L.d_out, L.d_in, L.W3, nullptr) != SLONN_OK ||
+                 (e = hipStreamSynchronize(nullptr)) != hipSuccess) {
+        if (e != hipSuccess) set_error("splitting the weights failed: %s", hipGetErrorString(e));
+        return fail(SLONN_EHIP);
+      }
+    }
   }
   *out = m;
   return SLONN_OK;
@@ -346,6 +364,7 @@ int slonn_model_destroy(slonn_model* m) {
     if (L.bh) (void)hipFree(L.bh);
     if (L.hslot) (void)hipFree(L.hslot);
     if (L.hnodes) (void)hipFree(L.hnodes);
+    if (L.W3) (void)hipFree(L.W3);
   }
   delete m;
   return SLONN_OK;
@@ -529,6 +548,10 @@ namespace {
 
 // ACLO inside the forward pass: k is chosen from the first activated layer's projections
 // (the Confidence LSH tables share that layer's hash functions) and serves every layer.
+// Masked tiles serve 128 queries when their mean list is at least this share of the layer
+// (below it the per-query gather moves fewer bytes than the tiles compute).
+constexpr int MASKED_TILES_MIN_KEEP_PERMILLE = 100;
+
 struct PolicyHook {
   const slonn_policy* p = nullptr;
   const float* thr = nullptr;
@@ -754,7 +777,14 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         // Large batches: groups of 16 queries whose lists overlap enough are evaluated together
         // on the matrix cores (decided per group on the device); the rest is gathered per query.
         const int32_t* gflag = nullptr;
-        if (gtiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {
+        if (L.W3 && gtiles >= 1024 && out && !yc && m->path_grouped) {
+          // fp32 layer with split weights: masked tiles on the bf16 matrix cores
+          int32_t* flags = nullptr;
+          rc = launch_masked_tiles(L.W3, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B, L.d_in, L.d_out,
+                                   act, rb.hslot, MASKED_TILES_MIN_KEEP_PERMILLE, w.grouped, &flags, s);
+          if (rc) return rc;
+          gflag = flags;
+        } else if (gtiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {
           int32_t* flags = nullptr;
           GroupedReuse reuse;
           reuse.hslot = rb.hslot;        // outputs of selected hash nodes were written by the regrouping step

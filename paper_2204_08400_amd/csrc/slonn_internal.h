@@ -41,6 +41,7 @@ struct Layer {
   float* bh = nullptr;           // [H]
   int16_t* hslot = nullptr;      // [d_out] device: index of the node among the hash rows, or -1
   int32_t* hnodes = nullptr;     // [H] device copy of hash_nodes
+  uint16_t* W3 = nullptr;        // large fp32 layers: the weights as three interleaved bf16 parts [d_out][3 d_in]
   int H() const { return K * L; }
   bool activated() const { return K > 0 && L > 0; }
 };
@@ -244,6 +245,21 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
                           const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy,
                           int B, int d, int n, int act, const GroupedReuse* reuse, void* scratch, int max_lds,
                           int32_t** gflag_out, hipStream_t s);
+
+// Large batches of a large fp32 layer: the selected (query, node) pairs evaluated as masked
+// dense tiles on the bf16 matrix cores (fp32 operands as three bf16 parts each).  W3: the
+// layer's weights through launch_split3.  Per 128 queries the device decides between the tile
+// kernel and the per-query gather: *flags_out (device, one per 16 queries) is 1 where the tiles
+// served them (mean list at least min_keep_permille / 1000 of the layer).  skip_hslot
+// (nullable): nodes with an entry >= 0 are left out (their outputs were taken from the hash
+// projections).  scratch: masked_tiles_workspace_bytes(B, n, d) bytes.
+bool masked_tiles_supported(int w_dtype, int d, int n, int max_lds);
+size_t masked_tiles_workspace_bytes(int B, int n, int d);
+int launch_split3(const float* X, int64_t ldx, int64_t rows, int d, uint16_t* out, hipStream_t s);
+int launch_masked_tiles(const uint16_t* W3, const float* bias, const float* X, int ldx, const int32_t* active,
+                        const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d, int n, int act,
+                        const int16_t* skip_hslot, int min_keep_permille, void* scratch, int32_t** flags_out,
+                        hipStream_t s);
 
 // y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).
 // yc (nullable) receives the values in list order.

@@ -565,20 +565,27 @@ def test_argument_errors_on_device(rt, oracle):
         slonn.slonn_workspace_bytes(g.model, (1 << 20) + 1)
 
 
-@pytest.mark.parametrize("w_dtype,d", [(wl.W_F32, 512), (wl.W_F32, 520), (wl.W_BF16, 1024), (wl.W_BF16, 1032)],
-                         ids=["f32", "f32-ragged-rows", "bf16", "bf16-ragged-rows"])
-def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d):
-    """Large batch on the per-layer path: groups of 16 queries whose active sets overlap are
-    evaluated together on the matrix cores (union of rows x 16 queries, selected pairs kept);
-    groups with little overlap stay on the per-query gather.  Same results either way."""
+@pytest.mark.parametrize("w_dtype,d,n", [(wl.W_F32, 512, 4096), (wl.W_F32, 544, 4040), (wl.W_F32, 520, 4096),
+                                         (wl.W_BF16, 1024, 4096), (wl.W_BF16, 1032, 4096)],
+                         ids=["f32-tiles", "f32-tiles-ragged", "f32-rows-not-32", "bf16", "bf16-ragged-rows"])
+def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d, n):
+    """Large batch on the per-layer path, evaluation across queries on the matrix cores.
+    fp32 rows of a multiple of 32 elements: masked 128 x 128 tiles on the bf16 cores (three
+    bf16 parts per operand), decided per 128 queries by their mean budget; other fp32 rows:
+    groups of 16 queries whose lists overlap, union of rows on the fp32 cores; bf16 weights:
+    every group of 16 on the bf16 cores.  The rest stays on the per-query gather.  Same results
+    either way."""
     from paper_2204_08400_amd import slonn
-    dims = (d, 4096, 24)
+    dims = (d, n, 24)
     layers, net, _ = make_case(oracle, dims, 6, 8, seed=61, hashed=[0], cap=1500, N_build=192, kind="clip3",
                                w_dtype=w_dtype)
     g = _gpu_net(rt, layers, net, path="layers")
     B = 512 + 7                      # ragged last group
     X = make_queries(dims, B, seed=62, kind="clip3")
-    for keep in (0.3, wl.keep_uniform(B, 0.0001, 0.3, 9)):
+    # third case: the first 128 queries with small budgets (their tile stays on the per-query
+    # gather), the others large
+    split = np.where(np.arange(B) < 128, 0.02, 0.35).astype(np.float32)
+    for keep in (0.3, wl.keep_uniform(B, 0.0001, 0.3, 9), split):
         _say(f"grouped evaluation {'f32' if w_dtype == wl.W_F32 else 'bf16'} keep={'mixed' if np.ndim(keep) else keep}")
         ref = net.sparse_forward(X, keep)
         kt = _keep_tensor(keep) if np.ndim(keep) else keep
