@@ -99,6 +99,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // operand with the eight elements 8 (l / 16) .. + 7 of the step; register v of lane l holds
 // D[4 (l / 16) + v][l % 16], rows from the first operand (here: nodes), columns from the second
 // (queries).
+template <int TQ>   // queries per tile: 128 (one workgroup per compute unit) or 64 (two)
 __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __restrict__ X3,
                                                           const uint16_t* __restrict__ W3,
                                                           const float* __restrict__ bias,
@@ -107,8 +108,10 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
                                                           float* __restrict__ Y, int ldy, int B, int n, int d,
                                                           int act) {
   extern __shared__ u32x4 tiles_lds[];     // two buffers of [TM + TN rows][ROW16]
-  constexpr int BUF16 = (TM + TN) * ROW16;
-  const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+  constexpr int BUF16 = (TQ + TN) * ROW16;
+  constexpr int QB = TQ / 32;              // 16-query blocks per wavefront
+  constexpr int XP = TQ * PIECES / 256;    // X pieces per thread and chunk
+  const int m0 = blockIdx.y * TQ, n0 = blockIdx.x * TN;
   if (!flags[m0 / 16]) return;             // these queries are served by the per-query gather
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wq = wave >> 1, wn = wave & 1;
@@ -116,63 +119,68 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
 
   // loader: 128 rows x 12 pieces per operand and chunk, six pieces per thread; rows beyond the
   // batch or the layer repeat the last valid row (their results are dropped)
-  const u32x4* xsrc[6];
+  const u32x4* xsrc[XP];
   const u32x4* wsrc[6];
   int dst[6];
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
     const int idx = tid + 256 * i, row = idx / PIECES, piece = idx % PIECES;
-    xsrc[i] = reinterpret_cast<const u32x4*>(X3 + (size_t)min(m0 + row, B - 1) * 3 * d) + piece;
+    if (i < XP) xsrc[i] = reinterpret_cast<const u32x4*>(X3 + (size_t)min(m0 + row, B - 1) * 3 * d) + piece;
     wsrc[i] = reinterpret_cast<const u32x4*>(W3 + (size_t)min(n0 + row, n - 1) * 3 * d) + piece;
     dst[i] = row * ROW16 + piece;
   }
   // Chunk c is multiplied out of LDS buffer c % 2 while chunk c + 1 moves from registers into the
-  // other buffer and chunk c + 2 is on its way from L2 (one barrier per chunk, and one that
-  // orders LDS traffic only: the global loads stay in flight across it).  Chunks past the end
-  // repeat the last one and are dropped.  A chunk of 32 elements is 12 pieces per row.
+  // other buffer and chunks c + 2 and c + 3 are on their way from L2 (two register sets: a
+  // load has two chunks' worth of MFMAs to arrive).  One barrier per chunk, and one that orders
+  // LDS traffic only: the global loads stay in flight across it.  Chunks past the end repeat the
+  // last one and are dropped.  A chunk of 32 elements is 12 pieces per row.
   const int nchunks = d / 32;
-  u32x4 rx[6], rw[6];
-#pragma unroll
-  for (int i = 0; i < 6; ++i) {
-    rx[i] = xsrc[i][0];
-    rw[i] = wsrc[i][0];
+  const int last = nchunks - 1;
+  u32x4 r0x[XP], r0w[6], r1x[XP], r1w[6];
+#define SLONN_TILES_LOAD(RX, RW, CHUNK)                         \
+  {                                                            \
+    const size_t off_ = (size_t)min((CHUNK), last) * PIECES;   \
+    _Pragma("unroll") for (int i = 0; i < 6; ++i) {            \
+      if (i < XP) RX[i] = xsrc[i][off_];                       \
+      RW[i] = wsrc[i][off_];                                   \
+    }                                                          \
   }
-#pragma unroll
-  for (int i = 0; i < 6; ++i) {
-    tiles_lds[dst[i]] = rx[i];
-    tiles_lds[TM * ROW16 + dst[i]] = rw[i];
+#define SLONN_TILES_STORE(BUF, RX, RW)                         \
+  {                                                            \
+    u32x4* Xn_ = tiles_lds + (BUF) * BUF16;                    \
+    _Pragma("unroll") for (int i = 0; i < 6; ++i) {            \
+      if (i < XP) Xn_[dst[i]] = RX[i];                         \
+      Xn_[TQ * ROW16 + dst[i]] = RW[i];                        \
+    }                                                          \
   }
-  {
-    const size_t next = (size_t)min(1, nchunks - 1) * PIECES;
-#pragma unroll
-    for (int i = 0; i < 6; ++i) {
-      rx[i] = xsrc[i][next];
-      rw[i] = wsrc[i][next];
-    }
-  }
+  SLONN_TILES_LOAD(r0x, r0w, 0);
+  SLONN_TILES_LOAD(r1x, r1w, 1);
+  SLONN_TILES_STORE(0, r0x, r0w);
+  SLONN_TILES_LOAD(r0x, r0w, 2);
   lds_only_barrier();
+  // now: LDS buffer 0 holds chunk 0, r1 chunk 1, r0 chunk 2
 
-  f32x4 acc[4][4];                         // [node block][query block]
+  f32x4 acc[4][QB];                        // [node block][query block]
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int b = 0; b < 4; ++b) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < QB; ++b) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  for (int c = 0; c < nchunks; ++c) {
-    const u32x4* Xs = tiles_lds + (c & 1) * BUF16;
-    const u32x4* Ws = Xs + TM * ROW16;
-    bf16x8 xb[4][3];
+  auto multiply = [&](int buf) {
+    const u32x4* Xs = tiles_lds + buf * BUF16;
+    const u32x4* Ws = Xs + TQ * ROW16;
+    bf16x8 xb[QB][3];
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < QB; ++b)
 #pragma unroll
-      for (int p = 0; p < 3; ++p) xb[b][p] = as_bf16x8(Xs[(wq * 64 + b * 16 + r) * ROW16 + kg * 3 + p]);
+      for (int p = 0; p < 3; ++p) xb[b][p] = as_bf16x8(Xs[(wq * (TQ / 2) + b * 16 + r) * ROW16 + kg * 3 + p]);
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
       bf16x8 wa[3];
 #pragma unroll
       for (int p = 0; p < 3; ++p) wa[p] = as_bf16x8(Ws[(wn * 64 + a * 16 + r) * ROW16 + kg * 3 + p]);
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
+      for (int b = 0; b < QB; ++b) {
         f32x4 v = acc[a][b];               // smallest partial products first
         v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[2], xb[b][0], v, 0, 0, 0);
         v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[1], xb[b][1], v, 0, 0, 0);
@@ -183,26 +191,27 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
         acc[a][b] = v;
       }
     }
-    u32x4* Xn = tiles_lds + ((c + 1) & 1) * BUF16;
-#pragma unroll
-    for (int i = 0; i < 6; ++i) {
-      Xn[dst[i]] = rx[i];
-      Xn[TM * ROW16 + dst[i]] = rw[i];
-    }
-    const size_t next = (size_t)min(c + 2, nchunks - 1) * PIECES;
-#pragma unroll
-    for (int i = 0; i < 6; ++i) {
-      rx[i] = xsrc[i][next];
-      rw[i] = wsrc[i][next];
-    }
+  };
+  int c = 0;
+  for (; c + 2 <= nchunks; c += 2) {       // chunks c (buffer 0) and c + 1 (buffer 1)
+    multiply(0);
+    SLONN_TILES_STORE(1, r1x, r1w);        // chunk c + 1
+    SLONN_TILES_LOAD(r1x, r1w, c + 3);
+    lds_only_barrier();
+    multiply(1);
+    SLONN_TILES_STORE(0, r0x, r0w);        // chunk c + 2
+    SLONN_TILES_LOAD(r0x, r0w, c + 4);
     lds_only_barrier();
   }
+  if (c < nchunks) multiply(0);            // an odd number of chunks
+#undef SLONN_TILES_LOAD
+#undef SLONN_TILES_STORE
 
-  // register v of block (a, b): node n0 + 64 wn + 16 a + 4 kg + v, query m0 + 64 wq + 16 b + r
+  // register v of block (a, b): node n0 + 64 wn + 16 a + 4 kg + v, query m0 + (TQ / 2) wq + 16 b + r
   const int words = (n + 31) >> 5;
 #pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const int q = m0 + wq * 64 + b * 16 + r;
+  for (int b = 0; b < QB; ++b) {
+    const int q = m0 + wq * (TQ / 2) + b * 16 + r;
     if (q >= B) continue;
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
@@ -263,11 +272,12 @@ int launch_masked_tiles(const uint16_t* W3, const float* bias, const float* X, i
   }
   ProfScope prof_(SLONN_PROF_GATHER, s);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
-  constexpr size_t lds = (size_t)2 * (TM + TN) * ROW16 * 16;
+  constexpr int TQ = 64;
+  constexpr size_t lds = (size_t)2 * (TQ + TN) * ROW16 * 16;
   static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
-  SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel),
+  SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(masked_tiles_kernel, dim3((n + TN - 1) / TN, (B + TM - 1) / TM), dim3(256), lds, s, X3, W3,
+  hipLaunchKernelGGL(masked_tiles_kernel<TQ>, dim3((n + TN - 1) / TN, (B + TQ - 1) / TQ), dim3(256), lds, s, X3, W3,
                      bias, mask, flags, Y, ldy, B, n, d, a);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
