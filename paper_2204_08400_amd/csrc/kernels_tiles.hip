@@ -15,8 +15,9 @@
 //                        of part p of row i at i * 3 d + (k / 8) * 24 + 8 p + k % 8, so a row's
 //                        chunk of 32 elements is 192 contiguous bytes.  Weights once at model
 //                        creation, activations once per layer call.
-//   pair_mask_kernel     one bit per (query, node) pair of the active lists; per 128 queries the
-//                        decision whether the tile kernel or the per-query gather serves them.
+//   pair_mask_kernel     per 128 queries the decision whether the tile kernel or the per-query
+//                        gather serves them; for served queries one bit per (query, node) pair
+//                        of the active lists and the activations in three parts.
 //   masked_tiles_kernel  128 queries x 128 nodes per workgroup, four wavefronts in 2 x 2, each
 //                        4 x 4 blocks of 16 x 16; chunks of 32 elements staged through LDS, the
 //                        next chunk's global loads in flight during the MFMAs; only selected
@@ -52,20 +53,34 @@ __global__ void split3_kernel(const float* __restrict__ X, int64_t ldx, int d, u
   out[at + 16] = (uint16_t)(__float_as_uint(r2) >> 16);
 }
 
-// One workgroup per query.  mask[q][w] bit j: node 32 w + j is in the query's list and is not a
-// hash node whose output was already taken from its projection.  flags (one per 16 queries, the
-// unit the per-query gather skips by): 1 when the 128 queries of the tile list at least
-// min_pairs (query, node) pairs together, i.e. the tile kernel is the cheaper way.
+// One workgroup per query.  The 128 queries of a tile are served by the tile kernel when they
+// list at least min_pairs (query, node) pairs together (every workgroup adds up its tile's list
+// lengths itself); flags holds that decision once per 16 queries, the unit the per-query gather
+// skips by.  For a served query: mask[q][w] bit j = node 32 w + j is in the query's list and is
+// not a hash node whose output was already taken from its projection, and X3 row q = the
+// activations in three bf16 parts.
 __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restrict__ active,
                                                        const int32_t* __restrict__ cnt, int idx_stride, int B,
                                                        int n, const int16_t* __restrict__ skip_hslot,
                                                        uint32_t* __restrict__ mask, int32_t* __restrict__ flags,
-                                                       long long min_pairs) {
+                                                       long long min_pairs, const float* __restrict__ X, int ldx,
+                                                       int d, uint16_t* __restrict__ X3) {
   extern __shared__ uint32_t bits[];
+  __shared__ int served;
   const int q = blockIdx.x, tid = threadIdx.x;
   const int words = (n + 31) >> 5;
+  if (tid < 64) {
+    const int q0 = q - q % TM;
+    long long sum = 0;
+    for (int i = tid; i < TM && q0 + i < B; i += 64) sum += cnt[q0 + i];
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    const int f = sum >= min_pairs ? 1 : 0;
+    if (tid == 0) served = f;
+    if (q == q0 && tid < TM / 16) flags[q / 16 + tid] = f;
+  }
   for (int i = tid; i < words; i += 256) bits[i] = 0u;
   __syncthreads();
+  if (!served) return;
   const int c = cnt[q];
   const int32_t* list = active + (size_t)q * idx_stride;
   for (int t = tid; t < c; t += 256) {
@@ -73,15 +88,19 @@ __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restric
     if (skip_hslot && skip_hslot[node] >= 0) continue;
     atomicOr(&bits[node >> 5], 1u << (node & 31));
   }
+  for (int i = tid; i < d; i += 256) {
+    const float x = X[(size_t)q * ldx + i];
+    const uint32_t hb = __float_as_uint(x) & 0xFFFF0000u;
+    const float r1 = x - __uint_as_float(hb);
+    const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
+    const float r2 = r1 - __uint_as_float(mb);
+    const size_t at = (size_t)q * 3 * d + (size_t)(i >> 3) * 24 + (i & 7);
+    X3[at] = (uint16_t)(hb >> 16);
+    X3[at + 8] = (uint16_t)(mb >> 16);
+    X3[at + 16] = (uint16_t)(__float_as_uint(r2) >> 16);
+  }
   __syncthreads();
   for (int i = tid; i < words; i += 256) mask[(size_t)q * words + i] = bits[i];
-  if (q % TM == 0 && tid < 64) {
-    long long sum = 0;
-    for (int i = tid; i < TM && q + i < B; i += 64) sum += cnt[q + i];
-    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-    const int f = sum >= min_pairs ? 1 : 0;
-    if (tid < TM / 16) flags[q / 16 + tid] = f;
-  }
 }
 
 // Barrier that orders LDS traffic only: global loads issued before it stay in flight across it
@@ -265,10 +284,8 @@ int launch_masked_tiles(const uint16_t* W3, const float* bias, const float* X, i
     // the tile kernel serves 128 queries when they list at least this many pairs together
     const long long min_pairs = (long long)TM * n * min_keep_permille / 1000;
     hipLaunchKernelGGL(pair_mask_kernel, dim3(B), dim3(256), (size_t)words * 4, s, active, cnt, idx_stride, B, n,
-                       skip_hslot, mask, flags, min_pairs);
+                       skip_hslot, mask, flags, min_pairs, X, ldx, d, X3);
     SLONN_HIP(hipGetLastError());
-    int rc = launch_split3(X, ldx, B, d, X3, s);
-    if (rc) return rc;
   }
   ProfScope prof_(SLONN_PROF_GATHER, s);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;

@@ -549,8 +549,10 @@ namespace {
 // ACLO inside the forward pass: k is chosen from the first activated layer's projections
 // (the Confidence LSH tables share that layer's hash functions) and serves every layer.
 // Masked tiles serve 128 queries when their mean list is at least this share of the layer
-// (below it the per-query gather moves fewer bytes than the tiles compute).
-constexpr int MASKED_TILES_MIN_KEEP_PERMILLE = 100;
+// (below it the per-query gather, whose cost grows with batch x budget, is cheaper than the
+// tiles, whose cost per layer is about constant while they fit the chip once: measured
+// break-even on 4096-wide fp32 layers 0.2 at batch 256, 0.12 at 512, 0.1 at 1024).
+int masked_tiles_min_keep_permille(int B) { return B >= 1024 ? 100 : (B >= 512 ? 120 : 200); }
 
 struct PolicyHook {
   const slonn_policy* p = nullptr;
@@ -777,11 +779,12 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         // Large batches: groups of 16 queries whose lists overlap enough are evaluated together
         // on the matrix cores (decided per group on the device); the rest is gathered per query.
         const int32_t* gflag = nullptr;
-        if (L.W3 && gtiles >= 1024 && out && !yc && m->path_grouped) {
+        const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);   // workgroups of the tile kernel
+        if (L.W3 && mtiles >= 128 && out && !yc && m->path_grouped) {
           // fp32 layer with split weights: masked tiles on the bf16 matrix cores
           int32_t* flags = nullptr;
           rc = launch_masked_tiles(L.W3, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B, L.d_in, L.d_out,
-                                   act, rb.hslot, MASKED_TILES_MIN_KEEP_PERMILLE, w.grouped, &flags, s);
+                                   act, rb.hslot, masked_tiles_min_keep_permille(B), w.grouped, &flags, s);
           if (rc) return rc;
           gflag = flags;
         } else if (gtiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {
