@@ -38,11 +38,16 @@ __global__ __launch_bounds__(UNT) void union_kernel(const int32_t* __restrict__ 
                                                    int32_t* __restrict__ gflag, int ustride,
                                                    const int16_t* __restrict__ skip_hslot,
                                                    const float* __restrict__ Z, int H, int relu,
-                                                   float* __restrict__ Y, int ldy, int thr10) {
+                                                   float* __restrict__ Y, int ldy, int thr10,
+                                                   const int32_t* __restrict__ served) {
   extern __shared__ __align__(16) uint32_t mask2[];      // two 16-bit masks per word
   __shared__ int red[UNW];
   __shared__ int listed;                                 // list entries that take part
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (served && served[g]) {             // these 16 queries were evaluated as masked tiles
+    if (tid == 0) { ucnt[g] = 0; gflag[g] = 0; }
+    return;
+  }
   const int q0 = g * GQ, nq = min(GQ, B - q0);
   const int words = (n + 1) >> 1;
   for (int i = tid; i < words; i += UNT) mask2[i] = 0u;
@@ -332,8 +337,8 @@ bool grouped_uses_bf16_cores(const void* W, int w_dtype, int d) {
 
 int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                           const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy,
-                          int B, int d, int n, int act, const GroupedReuse* reuse, void* scratch, int max_lds,
-                          int32_t** gflag_out, hipStream_t s) {
+                          int B, int d, int n, int act, const GroupedReuse* reuse, const int32_t* served,
+                          void* scratch, int max_lds, int32_t** gflag_out, hipStream_t s) {
   const GroupedReuse ru = reuse ? *reuse : GroupedReuse{};
   const int ng = (B + GQ - 1) / GQ;
   int32_t* urows = static_cast<int32_t*>(scratch);
@@ -362,7 +367,7 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
       SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(union_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(union_kernel, dim3(ng), dim3(UNT), lds, s, active, cnt, idx_stride, B, n, urows, umask,
-                       ucnt, gflag, n, ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, thr10);
+                       ucnt, gflag, n, ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, thr10, served);
     SLONN_HIP(hipGetLastError());
     if (bf16_cores) {
       hipLaunchKernelGGL(split_x_kernel, dim3(B, (d + 255) / 256), dim3(256), 0, s, X, ldx, B, d, xs3);

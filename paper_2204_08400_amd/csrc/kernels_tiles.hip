@@ -57,11 +57,14 @@ __global__ void split3_kernel(const float* __restrict__ X, int64_t ldx, int d, u
 // list at least min_pairs (query, node) pairs together (every workgroup adds up its tile's list
 // lengths itself); flags holds that decision once per 16 queries, the unit the per-query gather
 // skips by.  For a served query: mask[q][w] bit j = node 32 w + j is in the query's list and is
-// not a hash node whose output was already taken from its projection, and X3 row q = the
-// activations in three bf16 parts.
+// not a hash node (skip_hslot entry >= 0: its output is its projection, written here from Z when
+// Z is given, else already written by the caller), and X3 row q = the activations in three
+// bf16 parts.
 __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restrict__ active,
                                                        const int32_t* __restrict__ cnt, int idx_stride, int B,
                                                        int n, const int16_t* __restrict__ skip_hslot,
+                                                       const float* __restrict__ Z, int H, int relu,
+                                                       float* __restrict__ Y, int ldy,
                                                        uint32_t* __restrict__ mask, int32_t* __restrict__ flags,
                                                        long long min_pairs, const float* __restrict__ X, int ldx,
                                                        int d, uint16_t* __restrict__ X3) {
@@ -85,7 +88,17 @@ __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restric
   const int32_t* list = active + (size_t)q * idx_stride;
   for (int t = tid; t < c; t += 256) {
     const int node = list[t];
-    if (skip_hslot && skip_hslot[node] >= 0) continue;
+    if (skip_hslot) {
+      const int hs = skip_hslot[node];
+      if (hs >= 0) {                     // a selected hash node: its output is its projection
+        if (Z) {
+          float v = Z[(size_t)q * H + hs];
+          if (relu && !(v > 0.0f)) v = 0.0f;
+          Y[(size_t)q * ldy + node] = v;
+        }
+        continue;
+      }
+    }
     atomicOr(&bits[node >> 5], 1u << (node & 31));
   }
   for (int i = tid; i < d; i += 256) {
@@ -113,64 +126,69 @@ __device__ __forceinline__ void lds_only_barrier() {
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// X3, W3: rows in three interleaved bf16 parts (see above); d a multiple of 32.
+// X3: activation rows in three interleaved bf16 parts (see above).  Wp: weight rows, for WP = 3 in
+// the same three-part layout, for WP = 1 plain bf16 rows (bf16 weights: w x_hi, w x_mid, w x_lo
+// are each exact in fp32, three MFMAs per block).  d a multiple of 32.
 // Lane layout of v_mfma_f32_16x16x32_bf16 (checked on gfx950): lane l feeds row l % 16 of its
 // operand with the eight elements 8 (l / 16) .. + 7 of the step; register v of lane l holds
 // D[4 (l / 16) + v][l % 16], rows from the first operand (here: nodes), columns from the second
 // (queries).
-template <int TQ>   // queries per tile: 128 (one workgroup per compute unit) or 64 (two)
+template <int TQ, int WP>   // TQ queries per tile (64: two workgroups per compute unit); WP weight parts
 __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __restrict__ X3,
-                                                          const uint16_t* __restrict__ W3,
+                                                          const uint16_t* __restrict__ Wp,
                                                           const float* __restrict__ bias,
                                                           const uint32_t* __restrict__ mask,
                                                           const int32_t* __restrict__ flags,
                                                           float* __restrict__ Y, int ldy, int B, int n, int d,
                                                           int act) {
-  extern __shared__ u32x4 tiles_lds[];     // two buffers of [TM + TN rows][ROW16]
-  constexpr int BUF16 = (TQ + TN) * ROW16;
+  extern __shared__ u32x4 tiles_lds[];     // two buffers of [TQ rows of X | TN rows of W]
+  constexpr int PX = PIECES, PW = 4 * WP;  // 16-byte pieces per row and chunk of 32 elements
+  constexpr int ROWX = PX + 1, ROWW = PW + 1;   // LDS rows, padded by one piece (208 / 80 bytes stagger the banks)
+  constexpr int BUF16 = TQ * ROWX + TN * ROWW;
   constexpr int QB = TQ / 32;              // 16-query blocks per wavefront
-  constexpr int XP = TQ * PIECES / 256;    // X pieces per thread and chunk
+  constexpr int XP = TQ * PX / 256;        // X pieces per thread and chunk
+  constexpr int WT = TN * PW / 256;        // W pieces per thread and chunk
   const int m0 = blockIdx.y * TQ, n0 = blockIdx.x * TN;
-  if (!flags[m0 / 16]) return;             // these queries are served by the per-query gather
+  if (!flags[m0 / 16]) return;             // these queries are served another way
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wq = wave >> 1, wn = wave & 1;
   const int r = lane & 15, kg = lane >> 4;
 
-  // loader: 128 rows x 12 pieces per operand and chunk, six pieces per thread; rows beyond the
-  // batch or the layer repeat the last valid row (their results are dropped)
+  // loader: rows beyond the batch or the layer repeat the last valid row (their results are dropped)
   const u32x4* xsrc[XP];
-  const u32x4* wsrc[6];
-  int dst[6];
+  const u32x4* wsrc[WT];
+  int dstx[XP], dstw[WT];
 #pragma unroll
-  for (int i = 0; i < 6; ++i) {
-    const int idx = tid + 256 * i, row = idx / PIECES, piece = idx % PIECES;
-    if (i < XP) xsrc[i] = reinterpret_cast<const u32x4*>(X3 + (size_t)min(m0 + row, B - 1) * 3 * d) + piece;
-    wsrc[i] = reinterpret_cast<const u32x4*>(W3 + (size_t)min(n0 + row, n - 1) * 3 * d) + piece;
-    dst[i] = row * ROW16 + piece;
+  for (int i = 0; i < XP; ++i) {
+    const int idx = tid + 256 * i, row = idx / PX, piece = idx % PX;
+    xsrc[i] = reinterpret_cast<const u32x4*>(X3 + (size_t)min(m0 + row, B - 1) * 3 * d) + piece;
+    dstx[i] = row * ROWX + piece;
+  }
+#pragma unroll
+  for (int i = 0; i < WT; ++i) {
+    const int idx = tid + 256 * i, row = idx / PW, piece = idx % PW;
+    wsrc[i] = reinterpret_cast<const u32x4*>(Wp + (size_t)min(n0 + row, n - 1) * WP * d) + piece;
+    dstw[i] = TQ * ROWX + row * ROWW + piece;
   }
   // Chunk c is multiplied out of LDS buffer c % 2 while chunk c + 1 moves from registers into the
   // other buffer and chunks c + 2 and c + 3 are on their way from L2 (two register sets: a
   // load has two chunks' worth of MFMAs to arrive).  One barrier per chunk, and one that orders
   // LDS traffic only: the global loads stay in flight across it.  Chunks past the end repeat the
-  // last one and are dropped.  A chunk of 32 elements is 12 pieces per row.
+  // last one and are dropped.
   const int nchunks = d / 32;
   const int last = nchunks - 1;
-  u32x4 r0x[XP], r0w[6], r1x[XP], r1w[6];
-#define SLONN_TILES_LOAD(RX, RW, CHUNK)                         \
-  {                                                            \
-    const size_t off_ = (size_t)min((CHUNK), last) * PIECES;   \
-    _Pragma("unroll") for (int i = 0; i < 6; ++i) {            \
-      if (i < XP) RX[i] = xsrc[i][off_];                       \
-      RW[i] = wsrc[i][off_];                                   \
-    }                                                          \
+  u32x4 r0x[XP], r0w[WT], r1x[XP], r1w[WT];
+#define SLONN_TILES_LOAD(RX, RW, CHUNK)                                            \
+  {                                                                               \
+    const size_t c_ = (size_t)min((CHUNK), last);                                 \
+    _Pragma("unroll") for (int i = 0; i < XP; ++i) RX[i] = xsrc[i][c_ * PX];      \
+    _Pragma("unroll") for (int i = 0; i < WT; ++i) RW[i] = wsrc[i][c_ * PW];      \
   }
-#define SLONN_TILES_STORE(BUF, RX, RW)                         \
-  {                                                            \
-    u32x4* Xn_ = tiles_lds + (BUF) * BUF16;                    \
-    _Pragma("unroll") for (int i = 0; i < 6; ++i) {            \
-      if (i < XP) Xn_[dst[i]] = RX[i];                         \
-      Xn_[TQ * ROW16 + dst[i]] = RW[i];                        \
-    }                                                          \
+#define SLONN_TILES_STORE(BUF, RX, RW)                                             \
+  {                                                                               \
+    u32x4* buf_ = tiles_lds + (BUF) * BUF16;                                      \
+    _Pragma("unroll") for (int i = 0; i < XP; ++i) buf_[dstx[i]] = RX[i];         \
+    _Pragma("unroll") for (int i = 0; i < WT; ++i) buf_[dstw[i]] = RW[i];         \
   }
   SLONN_TILES_LOAD(r0x, r0w, 0);
   SLONN_TILES_LOAD(r1x, r1w, 1);
@@ -187,26 +205,32 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
 
   auto multiply = [&](int buf) {
     const u32x4* Xs = tiles_lds + buf * BUF16;
-    const u32x4* Ws = Xs + TQ * ROW16;
+    const u32x4* Ws = Xs + TQ * ROWX;
     bf16x8 xb[QB][3];
 #pragma unroll
     for (int b = 0; b < QB; ++b)
 #pragma unroll
-      for (int p = 0; p < 3; ++p) xb[b][p] = as_bf16x8(Xs[(wq * (TQ / 2) + b * 16 + r) * ROW16 + kg * 3 + p]);
+      for (int p = 0; p < 3; ++p) xb[b][p] = as_bf16x8(Xs[(wq * (TQ / 2) + b * 16 + r) * ROWX + kg * 3 + p]);
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
-      bf16x8 wa[3];
+      bf16x8 wa[WP];
 #pragma unroll
-      for (int p = 0; p < 3; ++p) wa[p] = as_bf16x8(Ws[(wn * 64 + a * 16 + r) * ROW16 + kg * 3 + p]);
+      for (int p = 0; p < WP; ++p) wa[p] = as_bf16x8(Ws[(wn * 64 + a * 16 + r) * ROWW + kg * WP + p]);
 #pragma unroll
       for (int b = 0; b < QB; ++b) {
         f32x4 v = acc[a][b];               // smallest partial products first
-        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[2], xb[b][0], v, 0, 0, 0);
-        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[1], xb[b][1], v, 0, 0, 0);
-        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][2], v, 0, 0, 0);
-        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[1], xb[b][0], v, 0, 0, 0);
-        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][1], v, 0, 0, 0);
-        v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][0], v, 0, 0, 0);
+        if (WP == 3) {
+          v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[WP - 1], xb[b][0], v, 0, 0, 0);
+          v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[WP / 2], xb[b][1], v, 0, 0, 0);
+          v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][2], v, 0, 0, 0);
+          v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[WP / 2], xb[b][0], v, 0, 0, 0);
+          v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][1], v, 0, 0, 0);
+          v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][0], v, 0, 0, 0);
+        } else {
+          v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][2], v, 0, 0, 0);
+          v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][1], v, 0, 0, 0);
+          v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][0], v, 0, 0, 0);
+        }
         acc[a][b] = v;
       }
     }
@@ -249,11 +273,14 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
   }
 }
 
+constexpr int TILE_Q = 64;
+template <int WP>
+constexpr size_t tiles_lds_bytes() { return (size_t)2 * (TILE_Q * (PIECES + 1) + TN * (4 * WP + 1)) * 16; }
+
 }  // namespace
 
-bool masked_tiles_supported(int w_dtype, int d, int n, int max_lds) {
-  return w_dtype == SLONN_F32 && d % 32 == 0 && (size_t)((n + 31) / 32) * 4 <= (size_t)max_lds &&
-         (size_t)2 * (TM + TN) * ROW16 * 16 <= (size_t)max_lds;
+bool masked_tiles_supported(int d, int n, int max_lds) {
+  return d % 32 == 0 && (size_t)((n + 31) / 32) * 4 <= (size_t)max_lds && tiles_lds_bytes<3>() <= (size_t)max_lds;
 }
 
 size_t masked_tiles_workspace_bytes(int B, int n, int d) {
@@ -268,10 +295,11 @@ int launch_split3(const float* X, int64_t ldx, int64_t rows, int d, uint16_t* ou
   return SLONN_OK;
 }
 
-int launch_masked_tiles(const uint16_t* W3, const float* bias, const float* X, int ldx, const int32_t* active,
-                        const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d, int n, int act,
-                        const int16_t* skip_hslot, int min_keep_permille, void* scratch, int32_t** flags_out,
-                        hipStream_t s) {
+int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx,
+                        const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d,
+                        int n, int act, const TilesReuse* reuse, int min_keep_permille, void* scratch,
+                        int32_t** flags_out, hipStream_t s) {
+  const TilesReuse ru = reuse ? *reuse : TilesReuse{};
   const int words = (n + 31) / 32;
   const size_t mask_bytes = ((size_t)B * words * 4 + 255) / 256 * 256;
   const size_t flag_bytes = ((size_t)(B / 16 + TM / 16 + 1) * 4 + 255) / 256 * 256;
@@ -284,18 +312,24 @@ int launch_masked_tiles(const uint16_t* W3, const float* bias, const float* X, i
     // the tile kernel serves 128 queries when they list at least this many pairs together
     const long long min_pairs = (long long)TM * n * min_keep_permille / 1000;
     hipLaunchKernelGGL(pair_mask_kernel, dim3(B), dim3(256), (size_t)words * 4, s, active, cnt, idx_stride, B, n,
-                       skip_hslot, mask, flags, min_pairs, X, ldx, d, X3);
+                       ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, mask, flags, min_pairs, X, ldx, d, X3);
     SLONN_HIP(hipGetLastError());
   }
   ProfScope prof_(SLONN_PROF_GATHER, s);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
-  constexpr int TQ = 64;
-  constexpr size_t lds = (size_t)2 * (TQ + TN) * ROW16 * 16;
-  static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
-  SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(masked_tiles_kernel<TQ>, dim3((n + TN - 1) / TN, (B + TQ - 1) / TQ), dim3(256), lds, s, X3, W3,
-                     bias, mask, flags, Y, ldy, B, n, d, a);
+  const dim3 grid((n + TN - 1) / TN, (B + TILE_Q - 1) / TILE_Q);
+  if (w_parts == 3) {
+    constexpr size_t lds = tiles_lds_bytes<3>();
+    static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TILE_Q, 3>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((masked_tiles_kernel<TILE_Q, 3>), grid, dim3(256), lds, s, X3, Wp, bias, mask, flags, Y, ldy,
+                       B, n, d, a);
+  } else {
+    constexpr size_t lds = tiles_lds_bytes<1>();
+    hipLaunchKernelGGL((masked_tiles_kernel<TILE_Q, 1>), grid, dim3(256), lds, s, X3, Wp, bias, mask, flags, Y, ldy,
+                       B, n, d, a);
+  }
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

@@ -51,6 +51,7 @@ struct Workspace {
   int32_t* part_pos = nullptr;          // [B][max_n_activated]
   int32_t* blk_off = nullptr;           // [B][MAX_ROW_BLOCKS + 1]
   void* grouped = nullptr;              // union lists of the grouped evaluation
+  void* tiles = nullptr;                // pair masks and split activations of the masked tiles
   void* hash_split = nullptr;           // partial sums of the split hash projection
   size_t bytes = 0;
   int max_n = 0, max_H = 0, max_na = 0;
@@ -81,10 +82,12 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   w->part_idx = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->part_pos = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->blk_off = reinterpret_cast<int32_t*>(take((size_t)B * (MAX_ROW_BLOCKS + 1) * 4));
-  size_t grouped_bytes = grouped_workspace_bytes(B, std::max(max_na, 1), d_bf16);
+  w->grouped = take(grouped_workspace_bytes(B, std::max(max_na, 1), d_bf16));
+  size_t tiles_bytes = 0;
   for (const Layer& l : m->layers)
-    if (l.W3) grouped_bytes = std::max(grouped_bytes, masked_tiles_workspace_bytes(B, l.d_out, l.d_in));
-  w->grouped = take(grouped_bytes);
+    if (l.activated() && (l.W3 || l.w_dtype == SLONN_BF16) && masked_tiles_supported(l.d_in, l.d_out, m->max_lds_bytes))
+      tiles_bytes = std::max(tiles_bytes, masked_tiles_workspace_bytes(B, l.d_out, l.d_in));
+  w->tiles = take(tiles_bytes);
   w->hash_split = take(hash_split_workspace_bytes());
   w->bytes = off;
 }
@@ -261,8 +264,8 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
     // three bf16 parts, for the masked tiles that serve large batches on the bf16 matrix cores.
     // Without the memory for it large batches stay on the other paths.
     const size_t row_bytes = (size_t)L.d_in * 4;
-    if (masked_tiles_supported(L.w_dtype, L.d_in, L.d_out, m->max_lds_bytes) &&
-        L.w_layout == SLONN_ROWS_ARE_NODES && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20)) {
+    if (L.w_dtype == SLONN_F32 && masked_tiles_supported(L.d_in, L.d_out, m->max_lds_bytes) &&
+        reinterpret_cast<uintptr_t>(L.W) % 16 == 0 && L.w_layout == SLONN_ROWS_ARE_NODES && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20)) {
       if (hipMalloc(&L.W3, (size_t)3 * L.d_out * L.d_in * 2) != hipSuccess) {
         (void)hipGetLastError();
         L.W3 = nullptr;
@@ -552,6 +555,9 @@ namespace {
 // (below it the per-query gather, whose cost grows with batch x budget, is cheaper than the
 // tiles, whose cost per layer is about constant while they fit the chip once: measured
 // break-even on 4096-wide fp32 layers 0.2 at batch 256, 0.12 at 512, 0.1 at 1024).
+// bf16 weights (three MFMAs per block; the alternative is the union of 16 queries' rows on the
+// same cores, whose cost follows the union's size)
+constexpr int BF16_TILES_MIN_KEEP_PERMILLE = 100;
 int masked_tiles_min_keep_permille(int B) { return B >= 1024 ? 100 : (B >= 512 ? 120 : 200); }
 
 struct PolicyHook {
@@ -772,9 +778,22 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       if (all_grouped) {
         GroupedReuse reuse;
         reuse.hslot = L.hslot; reuse.Z = z; reuse.H = L.H(); reuse.relu = act == SLONN_ACT_RELU;
+        // tiles of 128 queries with large budgets: masked dense tiles; the others: unions of 16
+        const int32_t* served = nullptr;
+        const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);
+        if (mtiles >= 128 && masked_tiles_supported(L.d_in, L.d_out, m->max_lds_bytes)) {
+          TilesReuse tr;
+          tr.hslot = L.hslot; tr.Z = z; tr.H = L.H(); tr.relu = reuse.relu;
+          int32_t* tflags = nullptr;
+          rc = launch_masked_tiles(static_cast<const uint16_t*>(L.W), 1, L.bias, cur, ldcur, aidx, acnt, astride, out,
+                                   ldo, B, L.d_in, L.d_out, act, &tr, BF16_TILES_MIN_KEEP_PERMILLE, w.tiles, &tflags,
+                                   s);
+          if (rc) return rc;
+          served = tflags;
+        }
         int32_t* flags = nullptr;
         rc = launch_gather_grouped(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B,
-                                   L.d_in, L.d_out, act, &reuse, w.grouped, m->max_lds_bytes, &flags, s);
+                                   L.d_in, L.d_out, act, &reuse, served, w.grouped, m->max_lds_bytes, &flags, s);
       } else if (rb.part_idx) {
         // Large batches: groups of 16 queries whose lists overlap enough are evaluated together
         // on the matrix cores (decided per group on the device); the rest is gathered per query.
@@ -783,8 +802,10 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         if (L.W3 && mtiles >= 128 && out && !yc && m->path_grouped) {
           // fp32 layer with split weights: masked tiles on the bf16 matrix cores
           int32_t* flags = nullptr;
-          rc = launch_masked_tiles(L.W3, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B, L.d_in, L.d_out,
-                                   act, rb.hslot, masked_tiles_min_keep_permille(B), w.grouped, &flags, s);
+          TilesReuse tr;
+          tr.hslot = rb.hslot;           // outputs of selected hash nodes were written by the regrouping step
+          rc = launch_masked_tiles(L.W3, 3, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B, L.d_in, L.d_out,
+                                   act, &tr, masked_tiles_min_keep_permille(B), w.tiles, &flags, s);
           if (rc) return rc;
           gflag = flags;
         } else if (gtiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {
@@ -792,7 +813,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
           GroupedReuse reuse;
           reuse.hslot = rb.hslot;        // outputs of selected hash nodes were written by the regrouping step
           rc = launch_gather_grouped(L.W, L.w_dtype, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B,
-                                     L.d_in, L.d_out, act, &reuse, w.grouped, m->max_lds_bytes, &flags, s);
+                                     L.d_in, L.d_out, act, &reuse, nullptr, w.grouped, m->max_lds_bytes, &flags, s);
           if (rc) return rc;
           gflag = flags;
         }

@@ -234,7 +234,9 @@ struct GroupedReuse {
 // Groups of 16 queries: the union of their active rows evaluated as dense tiles on the matrix
 // cores, selected (query, node) pairs written to Y.  A group whose union is too large
 // relative to its lists is flagged 0 in *gflag_out (device array, [ceil(B/16)]) and left
-// untouched (with bf16 weights on the bf16 cores every group is taken).  scratch:
+// untouched (with bf16 weights on the bf16 cores every group is taken).  served (nullable,
+// device, one per 16 queries): groups with a non-zero entry were evaluated another way and are
+// skipped altogether.  scratch:
 // grouped_workspace_bytes(B, n, d) bytes of device memory.
 // d_bf16: widest input of an activated layer with bf16 weights (0: none); its activations are
 // split into three bf16 parts for the bf16 matrix cores.
@@ -243,23 +245,28 @@ bool grouped_supported(int n, int max_lds);
 bool grouped_uses_bf16_cores(const void* W, int w_dtype, int d);
 int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
                           const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy,
-                          int B, int d, int n, int act, const GroupedReuse* reuse, void* scratch, int max_lds,
-                          int32_t** gflag_out, hipStream_t s);
+                          int B, int d, int n, int act, const GroupedReuse* reuse, const int32_t* served,
+                          void* scratch, int max_lds, int32_t** gflag_out, hipStream_t s);
 
-// Large batches of a large fp32 layer: the selected (query, node) pairs evaluated as masked
-// dense tiles on the bf16 matrix cores (fp32 operands as three bf16 parts each).  W3: the
-// layer's weights through launch_split3.  Per 128 queries the device decides between the tile
-// kernel and the per-query gather: *flags_out (device, one per 16 queries) is 1 where the tiles
-// served them (mean list at least min_keep_permille / 1000 of the layer).  skip_hslot
-// (nullable): nodes with an entry >= 0 are left out (their outputs were taken from the hash
-// projections).  scratch: masked_tiles_workspace_bytes(B, n, d) bytes.
-bool masked_tiles_supported(int w_dtype, int d, int n, int max_lds);
+// Large batches of a large layer: the selected (query, node) pairs evaluated as masked dense
+// tiles on the bf16 matrix cores (activations as three bf16 parts).  Wp: w_parts == 3: fp32
+// weights through launch_split3; w_parts == 1: the layer's own bf16 rows.  Per 128 queries the
+// device decides whether the tiles serve them: *flags_out (device, one per 16 queries) is 1
+// where they did (mean list at least min_keep_permille / 1000 of the layer).  reuse (nullable):
+// nodes with an hslot entry >= 0 are left out; with Z their outputs act(Z) are written for the
+// served queries.  scratch: masked_tiles_workspace_bytes(B, n, d) bytes.
+struct TilesReuse {
+  const int16_t* hslot = nullptr;
+  const float* Z = nullptr;      // [B][H] projections
+  int H = 0, relu = 0;
+};
+bool masked_tiles_supported(int d, int n, int max_lds);
 size_t masked_tiles_workspace_bytes(int B, int n, int d);
 int launch_split3(const float* X, int64_t ldx, int64_t rows, int d, uint16_t* out, hipStream_t s);
-int launch_masked_tiles(const uint16_t* W3, const float* bias, const float* X, int ldx, const int32_t* active,
-                        const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d, int n, int act,
-                        const int16_t* skip_hslot, int min_keep_permille, void* scratch, int32_t** flags_out,
-                        hipStream_t s);
+int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx,
+                        const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d,
+                        int n, int act, const TilesReuse* reuse, int min_keep_permille, void* scratch,
+                        int32_t** flags_out, hipStream_t s);
 
 // y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).
 // yc (nullable) receives the values in list order.
