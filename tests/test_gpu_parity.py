@@ -600,6 +600,15 @@ def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d, n):
         assert prof["gather"][1] == (2 if (w_dtype == wl.W_BF16 and d % 32) else 3), prof
         assert prof["dense"][1] == 0, prof
         _say(f"  {compare_sparse(got, ref, layers, 'grouped')}")
+    # the same launch configuration with the hash nodes at the head of every list (Section 3.4
+    # variant): their outputs come from the projections, the tiles and unions leave them out
+    ref_net = oracle.OracleNet(layers, hash_nodes_always_active=True)
+    ref_net.tables = net.tables
+    g.set_hash_nodes_always_active(True)
+    _say("grouped evaluation, hash nodes always active")
+    ref = ref_net.sparse_forward(X, split)
+    got = to_numpy_result(g.sparse_forward(X, _keep_tensor(split), taps=True))
+    _say(f"  {compare_sparse(got, ref, layers, 'grouped hash-first')}")
 
 
 @pytest.mark.parametrize("path", ["layers", "fused"])
