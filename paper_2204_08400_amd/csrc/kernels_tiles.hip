@@ -18,10 +18,10 @@
 //   pair_mask_kernel     per 128 queries the decision whether the tile kernel or the per-query
 //                        gather serves them; for served queries one bit per (query, node) pair
 //                        of the active lists and the activations in three parts.
-//   masked_tiles_kernel  128 queries x 128 nodes per workgroup, four wavefronts in 2 x 2, each
-//                        4 x 4 blocks of 16 x 16; chunks of 32 elements staged through LDS, the
-//                        next chunk's global loads in flight during the MFMAs; only selected
-//                        pairs are written.
+//   masked_tiles_kernel  128 (or 64) queries x 128 nodes per workgroup, eight (four) wavefronts
+//                        as 2 query halves x 4 (2) node strips; chunks of 32 elements double-
+//                        buffered in LDS, the next chunks' global loads in flight during the
+//                        MFMAs; only selected pairs are written.
 #include <algorithm>
 
 #include "slonn_internal.h"
@@ -33,7 +33,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte piece (native vector: stays in registers)
 
-constexpr int TM = 128;           // queries per tile
+constexpr int TM = 128;           // queries per decision unit
 constexpr int TN = 128;           // nodes per tile
 constexpr int PIECES = 12;        // 16-byte pieces per row and chunk: 4 groups of 8 elements x 3 parts
 constexpr int ROW16 = PIECES + 1; // LDS row in 16-byte units (padded: 208 bytes staggers the banks)
@@ -133,8 +133,9 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // operand with the eight elements 8 (l / 16) .. + 7 of the step; register v of lane l holds
 // D[4 (l / 16) + v][l % 16], rows from the first operand (here: nodes), columns from the second
 // (queries).
-template <int TQ, int WP>   // TQ queries per tile (64: two workgroups per compute unit); WP weight parts
-__global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __restrict__ X3,
+// TQ queries per tile; WP weight parts; NT threads (wavefronts in 2 x NT / 128: query halves x node strips)
+template <int TQ, int WP, int NT>
+__global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __restrict__ X3,
                                                           const uint16_t* __restrict__ Wp,
                                                           const float* __restrict__ bias,
                                                           const uint32_t* __restrict__ mask,
@@ -146,12 +147,15 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
   constexpr int ROWX = PX + 1, ROWW = PW + 1;   // LDS rows, padded by one piece (208 / 80 bytes stagger the banks)
   constexpr int BUF16 = TQ * ROWX + TN * ROWW;
   constexpr int QB = TQ / 32;              // 16-query blocks per wavefront
-  constexpr int XP = TQ * PX / 256;        // X pieces per thread and chunk
-  constexpr int WT = TN * PW / 256;        // W pieces per thread and chunk
+  constexpr int XP = TQ * PX / NT;         // X pieces per thread and chunk
+  constexpr int WT = TN * PW / NT;         // W pieces per thread and chunk
+  constexpr int WN = NT / 128;             // node strips (wavefronts along the nodes)
+  constexpr int NB = TN / (16 * WN);       // 16-node blocks per wavefront
+  static_assert(TQ * PX % NT == 0 && TN * PW % NT == 0, "loader pieces must divide evenly");
   const int m0 = blockIdx.y * TQ, n0 = blockIdx.x * TN;
   if (!flags[m0 / 16]) return;             // these queries are served another way
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wq = wave >> 1, wn = wave & 1;
+  const int wq = wave / WN, wn = wave % WN;
   const int r = lane & 15, kg = lane >> 4;
 
   // loader: rows beyond the batch or the layer repeat the last valid row (their results are dropped)
@@ -160,13 +164,13 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
   int dstx[XP], dstw[WT];
 #pragma unroll
   for (int i = 0; i < XP; ++i) {
-    const int idx = tid + 256 * i, row = idx / PX, piece = idx % PX;
+    const int idx = tid + NT * i, row = idx / PX, piece = idx % PX;
     xsrc[i] = reinterpret_cast<const u32x4*>(X3 + (size_t)min(m0 + row, B - 1) * 3 * d) + piece;
     dstx[i] = row * ROWX + piece;
   }
 #pragma unroll
   for (int i = 0; i < WT; ++i) {
-    const int idx = tid + 256 * i, row = idx / PW, piece = idx % PW;
+    const int idx = tid + NT * i, row = idx / PW, piece = idx % PW;
     wsrc[i] = reinterpret_cast<const u32x4*>(Wp + (size_t)min(n0 + row, n - 1) * WP * d) + piece;
     dstw[i] = TQ * ROWX + row * ROWW + piece;
   }
@@ -197,9 +201,9 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
   lds_only_barrier();
   // now: LDS buffer 0 holds chunk 0, r1 chunk 1, r0 chunk 2
 
-  f32x4 acc[4][QB];                        // [node block][query block]
+  f32x4 acc[NB][QB];                       // [node block][query block]
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < NB; ++a)
 #pragma unroll
     for (int b = 0; b < QB; ++b) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
@@ -212,10 +216,10 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
 #pragma unroll
       for (int p = 0; p < 3; ++p) xb[b][p] = as_bf16x8(Xs[(wq * (TQ / 2) + b * 16 + r) * ROWX + kg * 3 + p]);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
+    for (int a = 0; a < NB; ++a) {
       bf16x8 wa[WP];
 #pragma unroll
-      for (int p = 0; p < WP; ++p) wa[p] = as_bf16x8(Ws[(wn * 64 + a * 16 + r) * ROWW + kg * WP + p]);
+      for (int p = 0; p < WP; ++p) wa[p] = as_bf16x8(Ws[(wn * 16 * NB + a * 16 + r) * ROWW + kg * WP + p]);
 #pragma unroll
       for (int b = 0; b < QB; ++b) {
         f32x4 v = acc[a][b];               // smallest partial products first
@@ -250,15 +254,15 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
 #undef SLONN_TILES_LOAD
 #undef SLONN_TILES_STORE
 
-  // register v of block (a, b): node n0 + 64 wn + 16 a + 4 kg + v, query m0 + (TQ / 2) wq + 16 b + r
+  // register v of block (a, b): node n0 + 16 NB wn + 16 a + 4 kg + v, query m0 + (TQ / 2) wq + 16 b + r
   const int words = (n + 31) >> 5;
 #pragma unroll
   for (int b = 0; b < QB; ++b) {
     const int q = m0 + wq * (TQ / 2) + b * 16 + r;
     if (q >= B) continue;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const int node = n0 + wn * 64 + a * 16 + 4 * kg;      // a multiple of 4: its four bits share a word
+    for (int a = 0; a < NB; ++a) {
+      const int node = n0 + wn * 16 * NB + a * 16 + 4 * kg; // a multiple of 4: its four bits share a word
       if (node >= n) continue;
       const uint32_t four = (mask[(size_t)q * words + (node >> 5)] >> (node & 31)) & 0xFu;
 #pragma unroll
@@ -273,14 +277,13 @@ __global__ __launch_bounds__(256) void masked_tiles_kernel(const uint16_t* __res
   }
 }
 
-constexpr int TILE_Q = 64;
-template <int WP>
-constexpr size_t tiles_lds_bytes() { return (size_t)2 * (TILE_Q * (PIECES + 1) + TN * (4 * WP + 1)) * 16; }
+template <int TQ, int WP>
+constexpr size_t tiles_lds_bytes() { return (size_t)2 * (TQ * (PIECES + 1) + TN * (4 * WP + 1)) * 16; }
 
 }  // namespace
 
 bool masked_tiles_supported(int d, int n, int max_lds) {
-  return d % 32 == 0 && (size_t)((n + 31) / 32) * 4 <= (size_t)max_lds && tiles_lds_bytes<3>() <= (size_t)max_lds;
+  return d % 32 == 0 && (size_t)((n + 31) / 32) * 4 <= (size_t)max_lds && tiles_lds_bytes<128, 3>() <= (size_t)max_lds;
 }
 
 size_t masked_tiles_workspace_bytes(int B, int n, int d) {
@@ -317,19 +320,25 @@ int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, cons
   }
   ProfScope prof_(SLONN_PROF_GATHER, s);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
-  const dim3 grid((n + TN - 1) / TN, (B + TILE_Q - 1) / TILE_Q);
-  if (w_parts == 3) {
-    constexpr size_t lds = tiles_lds_bytes<3>();
-    static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
-    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TILE_Q, 3>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL((masked_tiles_kernel<TILE_Q, 3>), grid, dim3(256), lds, s, X3, Wp, bias, mask, flags, Y, ldy,
-                       B, n, d, a);
-  } else {
-    constexpr size_t lds = tiles_lds_bytes<1>();
-    hipLaunchKernelGGL((masked_tiles_kernel<TILE_Q, 1>), grid, dim3(256), lds, s, X3, Wp, bias, mask, flags, Y, ldy,
-                       B, n, d, a);
+  // 128 x 128 tiles with eight wavefronts once they fill the chip (each weight tile is fetched
+  // half as often: C3 batch 1024 190 -> 160 us per layer); 64 x 128 tiles with four, two
+  // workgroups per compute unit, for smaller batches
+  const bool big = (long)((B + 127) / 128) * ((n + TN - 1) / TN) >= 256;
+#define SLONN_LAUNCH_TILES(TQ_, WP_, NT_)                                                                        \
+  {                                                                                                             \
+    constexpr size_t lds = tiles_lds_bytes<TQ_, WP_>();                                                         \
+    static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");                   \
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, WP_, NT_>),            \
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                       \
+    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, WP_, NT_>), dim3((n + TN - 1) / TN, (B + TQ_ - 1) / TQ_),      \
+                       dim3(NT_), lds, s, X3, Wp, bias, mask, flags, Y, ldy, B, n, d, a);                       \
   }
+  if (w_parts == 3) {
+    if (big) SLONN_LAUNCH_TILES(128, 3, 512) else SLONN_LAUNCH_TILES(64, 3, 256)
+  } else {
+    if (big) SLONN_LAUNCH_TILES(128, 1, 512) else SLONN_LAUNCH_TILES(64, 1, 256)
+  }
+#undef SLONN_LAUNCH_TILES
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }
