@@ -152,6 +152,13 @@ int slonn_model_destroy(slonn_model* m);
 enum { SLONN_PATH_AUTO = 0, SLONN_PATH_LAYERS = 1, SLONN_PATH_FUSED = 2 };
 int slonn_model_set_path(slonn_model* m, int path);
 
+/* Large batches compute the FreeHash projections on the int8 matrix cores from fixed-point
+ * digits of the operands; a projection counts as certain when |z| exceeds `margin` times a
+ * rigorous bound on what the fixed-point form loses, every other one is recomputed in fp64.
+ * margin >= 1 (default 2).  Results do not depend on it (a huge margin sends every projection
+ * through the fp64 recomputation: a diagnostic).  EINVAL: null model, margin < 1 or NaN.      */
+int slonn_model_set_hash_margin(slonn_model* m, double margin);
+
 /* Variant of Section 3.4 ("the hash is free"): the K*L FreeHash projections of a layer are
  * the pre-activations of K*L of its own nodes, so those nodes can always be computed at no
  * further cost, and the Node Activator then need not select them.  on != 0: for every

@@ -1,0 +1,319 @@
+// FreeHash projections of a large batch (Def. 2, Section 3.4) on the int8 matrix cores, with the
+// sign of every projection certified.
+//
+// A hash bit is the sign of z = w . x + b, so z has to be right wherever it is close to zero.
+// The fp64 matrix cores give that (hash_project_mfma_kernel) at 78 TFLOP/s; the int8 cores run
+// at 5 POP/s, and integer dot products are exact.  Every row (a hash row of the layer, a query's
+// activations) is written as a fixed-point number per element relative to a power of two above
+// the row's largest magnitude, |v| < 2^e:  V = trunc(v * 2^(35 - e)), a signed 36-bit integer,
+// cut into five signed 7-bit digits V = sum_s V_s 128^s.  Then
+//     sum_k W[k] X[k] = sum_{s,t} 128^(s+t) sum_k W_s[k] X_t[k],
+// every inner sum an exact int32 (|.| <= d * 127^2, five of them per accumulator: d <= 26 000).
+// The digit pairs with s + t >= 3 are kept (19 of 25).  What is lost is bounded rigorously:
+// truncation of the operands by d * 2^(e_w + e_x - 34), the dropped pairs by
+// d * 2^(e_w + e_x - 39), together below BOUND = d * 2^(e_w + e_x - 33).  A projection with
+// |z| > margin * BOUND has a certain sign and an fp32-accurate value; the few others (and rows
+// with non-finite entries) are recomputed in fp64 like the fp64 kernel does.
+//
+//   slice5_kernel         one workgroup per row: row maximum -> e, five int8 digits per element,
+//                         interleaved per 16 elements (element k, digit s of row i at
+//                         i * 5 d + (k / 16) * 80 + 16 s + k % 16).
+//   hash_int_tiles_kernel 128 queries x 64 hash rows per workgroup and slice of the reduction
+//                         dimension, eight wavefronts (4 x 2) of 2 x 2 blocks, six int32
+//                         accumulators per block (one per s + t), v_mfma_i32_16x16x64_i8,
+//                         chunks of 64 elements double-buffered in LDS; writes the partial
+//                         sums as fp64 integers.
+//   hash_int_finish_kernel adds the partial sums, scales, adds the bias, certifies; the lanes
+//                         whose projection is not certain are recomputed by their wavefront in
+//                         fp64, one after the other.
+#include <algorithm>
+#include <climits>
+
+#include "slonn_internal.h"
+
+namespace slonn {
+namespace {
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int DIGITS = 5;          // 7-bit digits per element
+constexpr int FRAC_BITS = 35;      // fixed point: 35 bits below 2^e
+constexpr int CLASSES = 6;         // s + t = 3 .. 8
+constexpr int HQ = 128, HH = 64;   // queries x hash rows per tile
+constexpr int HPIECES = 4 * DIGITS;  // 16-byte pieces per row and chunk of 64 elements
+constexpr int HROW = HPIECES + 1;    // LDS row in pieces (336 bytes: staggers the banks)
+constexpr int BAD_ROW = INT_MIN;   // exponent entry of a row with a non-finite element
+
+__global__ __launch_bounds__(256) void slice5_kernel(const float* __restrict__ X, int64_t ldx, int d,
+                                                    int8_t* __restrict__ out, int32_t* __restrict__ expo) {
+  __shared__ float red[4];
+  __shared__ int s_e;
+  const int64_t row = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* x = X + row * ldx;
+  float mx = 0.0f;
+  bool bad = false;
+  for (int i = tid; i < d; i += 256) {
+    const float v = fabsf(x[i]);
+    if (!(v <= 3.0e38f)) bad = true;          // infinity or NaN
+    mx = fmaxf(mx, v);
+  }
+  if (bad) mx = __int_as_float(0x7f800000);
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  if (tid == 0) {
+    const float m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    int e = 0;
+    if (!(m <= 3.0e38f)) e = BAD_ROW;
+    else if (m > 0.0f) (void)frexpf(m, &e);   // m = f * 2^e with f in [0.5, 1): |x| < 2^e
+    s_e = e;
+    expo[row] = e;
+  }
+  __syncthreads();
+  const int e = s_e;
+  int8_t* o = out + (size_t)row * DIGITS * d;
+  const double scale = e == BAD_ROW ? 0.0 : ldexp(1.0, FRAC_BITS - e);
+  for (int i = tid; i < d; i += 256) {
+    const double sv = (double)x[i] * scale;   // exact: a power of two times an fp32 number
+    const long long V = e == BAD_ROW ? 0 : (long long)sv;   // truncation towards zero, |V| < 2^35
+    const unsigned long long a = (unsigned long long)(V < 0 ? -V : V);
+    const size_t at = (size_t)(i >> 4) * (16 * DIGITS) + (i & 15);
+#pragma unroll
+    for (int s = 0; s < DIGITS; ++s) {
+      const int dig = (int)((a >> (7 * s)) & 127u);
+      o[at + 16 * s] = (int8_t)(V < 0 ? -dig : dig);
+    }
+  }
+}
+
+// Barrier that orders LDS traffic only: global loads issued before it stay in flight across it.
+__device__ __forceinline__ void lds_only_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ i32x4 as_i32x4(u32x4 v) { return __builtin_bit_cast(i32x4, v); }
+
+// X5, W5: rows in five interleaved digits (see above); d a multiple of 64.  part[z][q][h]
+// receives sum over the workgroup's chunks of sum_c 128^(c - 3) P_c (an integer below 2^66,
+// rounded to fp64: relative 2^-53, far below the bound).
+// Lane layout of v_mfma_i32_16x16x64_i8 (checked on gfx950): lane l feeds row l % 16 of its
+// operand with the sixteen elements 16 (l / 16) .. + 15 of the step; register v of lane l holds
+// D[4 (l / 16) + v][l % 16], rows from the first operand (here: hash rows), columns from the
+// second (queries).
+__global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __restrict__ X5,
+                                                            const int8_t* __restrict__ W5,
+                                                            double* __restrict__ part, int B, int H, int d) {
+  extern __shared__ u32x4 hash_lds[];       // two buffers of [HQ rows of X | HH rows of W][HROW]
+  constexpr int BUF = (HQ + HH) * HROW;
+  constexpr int TOTAL = (HQ + HH) * HPIECES;         // pieces per chunk
+  constexpr int PER = (TOTAL + 511) / 512;           // per thread (the last one partly repeated)
+  const int q0 = blockIdx.y * HQ, h0 = blockIdx.x * HH;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wq = wave >> 1, wh = wave & 1;           // 4 query strips x 2 hash-row strips of 32
+  const int r = lane & 15, kg = lane >> 4;
+
+  const u32x4* src[PER];
+  int dst[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int idx = min(tid + 512 * i, TOTAL - 1);   // surplus slots repeat the last piece
+    const bool isx = idx < HQ * HPIECES;
+    const int j = isx ? idx : idx - HQ * HPIECES;
+    const int row = j / HPIECES, piece = j % HPIECES;
+    const int8_t* base = isx ? X5 + (size_t)min(q0 + row, B - 1) * DIGITS * d
+                             : W5 + (size_t)min(h0 + row, H - 1) * DIGITS * d;
+    src[i] = reinterpret_cast<const u32x4*>(base) + piece;
+    dst[i] = (isx ? row : HQ + row) * HROW + piece;
+  }
+  // this workgroup's chunks of 64 elements
+  const int nchunks = d / 64;
+  const int per_z = (nchunks + (int)gridDim.z - 1) / (int)gridDim.z;
+  const int c_begin = min(nchunks, (int)blockIdx.z * per_z), c_end = min(nchunks, c_begin + per_z);
+  const int last = max(c_end - 1, c_begin);
+
+  i32x4 acc[2][2][CLASSES];                 // [hash block][query block][s + t - 3]
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int c = 0; c < CLASSES; ++c) acc[a][b][c] = (i32x4){0, 0, 0, 0};
+
+  u32x4 r0[PER];
+#define SLONN_HASH_LOAD(R, CHUNK)                                                          \
+  {                                                                                        \
+    const size_t c_ = (size_t)min((CHUNK), last);                                          \
+    _Pragma("unroll") for (int i = 0; i < PER; ++i) R[i] = src[i][c_ * HPIECES];           \
+  }
+#define SLONN_HASH_STORE(BUFI, R)                                                          \
+  {                                                                                        \
+    u32x4* b_ = hash_lds + (BUFI) * BUF;                                                   \
+    _Pragma("unroll") for (int i = 0; i < PER; ++i) b_[dst[i]] = R[i];                     \
+  }
+  auto multiply = [&](int buf) {
+    const u32x4* Xs = hash_lds + buf * BUF;
+    const u32x4* Ws = Xs + HQ * HROW;
+    // An MFMA consumes the whole chunk of 64 elements: lane (r, kg) supplies the 16 elements of
+    // group kg, i.e. piece kg * DIGITS + digit of its row.  One MFMA per digit pair and block.
+    i32x4 xd[2][DIGITS];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int t = 0; t < DIGITS; ++t)
+        xd[b][t] = as_i32x4(Xs[(wq * 32 + b * 16 + r) * HROW + kg * DIGITS + t]);
+#pragma unroll
+    for (int s = 0; s < DIGITS; ++s) {
+      i32x4 wd[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) wd[a] = as_i32x4(Ws[(wh * 32 + a * 16 + r) * HROW + kg * DIGITS + s]);
+#pragma unroll
+      for (int t = 0; t < DIGITS; ++t) {
+        if (s + t < 3) continue;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+            acc[a][b][s + t - 3] =
+                __builtin_amdgcn_mfma_i32_16x16x64_i8(wd[a], xd[b][t], acc[a][b][s + t - 3], 0, 0, 0);
+      }
+    }
+  };
+
+  // chunk c is multiplied out of buffer (c - c_begin) % 2 while chunk c + 1 moves from registers into
+  // the other buffer and chunk c + 2 is on its way from L2; one LDS-only barrier per chunk
+  if (c_begin < c_end) {
+    SLONN_HASH_LOAD(r0, c_begin);
+    SLONN_HASH_STORE(0, r0);
+    SLONN_HASH_LOAD(r0, c_begin + 1);
+    lds_only_barrier();
+    for (int c = c_begin; c < c_end; ++c) {
+      const int cur = (c - c_begin) & 1;
+      multiply(cur);
+      SLONN_HASH_STORE(cur ^ 1, r0);
+      SLONN_HASH_LOAD(r0, c + 2);
+      lds_only_barrier();
+    }
+  }
+#undef SLONN_HASH_LOAD
+#undef SLONN_HASH_STORE
+
+  // register v of block (a, b): hash row h0 + 32 wh + 16 a + 4 kg + v, query q0 + 32 wq + 16 b + r
+  double* mine = part + (size_t)blockIdx.z * B * H;
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int q = q0 + wq * 32 + b * 16 + r;
+    if (q >= B) continue;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int h = h0 + wh * 32 + a * 16 + 4 * kg + v;
+        if (h >= H) continue;
+        double sum = 0.0;
+#pragma unroll
+        for (int c = CLASSES - 1; c >= 0; --c) sum = sum * 128.0 + (double)acc[a][b][c][v];
+        mine[(size_t)q * H + h] = sum;       // = sum_c 128^c P_c, in units of 128^3
+      }
+  }
+}
+
+// One lane per (query, hash row).  z = 128^3 * sum of the partial sums * 2^(e_w + e_x - 70) + bias.
+__global__ __launch_bounds__(256) void hash_int_finish_kernel(const double* __restrict__ part, int S,
+                                                             const int32_t* __restrict__ ex,
+                                                             const int32_t* __restrict__ ew,
+                                                             const float* __restrict__ X, int ldx,
+                                                             const float* __restrict__ Wh,
+                                                             const float* __restrict__ bh, float* __restrict__ Z,
+                                                             int B, int H, int d, double margin) {
+  const size_t total = (size_t)B * H;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  bool redo = false;
+  int q = 0, h = 0;
+  if (i < total) {
+    q = (int)(i / H);
+    h = (int)(i % H);
+    const int eq = ex[q], eh = ew[h];
+    if (eq == BAD_ROW || eh == BAD_ROW) {
+      redo = true;
+    } else {
+      double sum = 0.0;
+      for (int z = 0; z < S; ++z) sum += part[(size_t)z * total + i];
+      const double dot = ldexp(sum, 21 + eq + eh - 2 * FRAC_BITS);
+      const double zz = dot + (double)bh[h];
+      const double bound = ldexp((double)d, eq + eh - 33);
+      if (fabs(zz) > margin * bound) Z[i] = (float)zz;
+      else redo = true;
+    }
+  }
+  // the uncertain ones: the whole wavefront recomputes them in fp64, one after the other
+  unsigned long long todo = __ballot(redo);
+  while (todo) {
+    const int src = __ffsll((long long)todo) - 1;
+    todo &= todo - 1;
+    const int qq = __shfl(q, src), hh = __shfl(h, src);
+    const float* x = X + (size_t)qq * ldx;
+    const float* w = Wh + (size_t)hh * d;
+    double acc = 0.0;
+    for (int k = lane; k < d; k += 64) acc = fma((double)w[k], (double)x[k], acc);
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == src) Z[i] = (float)(acc + (double)bh[hh]);
+  }
+}
+
+}  // namespace
+
+bool hash_int_supported(int d) { return d % 64 == 0 && d <= 16384; }
+
+// Slices of the reduction dimension: as many as keep the grid within one round of workgroups (one
+// workgroup per compute unit: the two tile buffers take most of its LDS), at least 8 chunks each.
+int hash_int_splits(int B, int H, int d) {
+  const int tiles = ((B + HQ - 1) / HQ) * ((H + HH - 1) / HH);
+  const int nchunks = d / 64;
+  int S = 1;
+  while (tiles * S * 2 <= 256 && S * 2 <= 8 && nchunks / (S * 2) >= 8) S *= 2;
+  return S;
+}
+
+size_t hash_int_workspace_bytes(int B, int H, int d) {
+  const size_t x5 = ((size_t)B * DIGITS * d + 255) / 256 * 256;
+  const size_t ex = ((size_t)B * 4 + 255) / 256 * 256;
+  return x5 + ex + (size_t)8 * B * H * sizeof(double) + 256;
+}
+
+int launch_slice5(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s) {
+  hipLaunchKernelGGL(slice5_kernel, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8_t* W5, const int32_t* ew,
+                            const float* bh, float* Z, int B, int H, int d, double margin, void* scratch,
+                            hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_HASH, s);
+  const size_t x5_bytes = ((size_t)B * DIGITS * d + 255) / 256 * 256;
+  const size_t ex_bytes = ((size_t)B * 4 + 255) / 256 * 256;
+  int8_t* X5 = static_cast<int8_t*>(scratch);
+  int32_t* ex = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + x5_bytes);
+  double* part = reinterpret_cast<double*>(static_cast<char*>(scratch) + x5_bytes + ex_bytes);
+  int rc = launch_slice5(X, ldx, B, d, X5, ex, s);
+  if (rc) return rc;
+  const int S = hash_int_splits(B, H, d);
+  constexpr size_t lds = (size_t)2 * (HQ + HH) * HROW * 16;
+  static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
+  SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(hash_int_tiles_kernel, dim3((H + HH - 1) / HH, (B + HQ - 1) / HQ, S), dim3(512), lds, s, X5, W5,
+                     part, B, H, d);
+  SLONN_HIP(hipGetLastError());
+  hipLaunchKernelGGL(hash_int_finish_kernel, dim3((unsigned)(((size_t)B * H + 255) / 256)), dim3(256), 0, s, part, S,
+                     ex, ew, X, ldx, Wh, bh, Z, B, H, d, margin);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+}  // namespace slonn

@@ -41,6 +41,10 @@ namespace {
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
+// from this batch on the hash projections run on the int8 matrix cores (below it the fp64 kernels
+// are latency-bound anyway and the slicing pass would not pay)
+constexpr int HASH_INT_MIN_BATCH = 512;
+
 // Carves the caller's workspace into the per-batch buffers of the forward pass.
 struct Workspace {
   float* act[2] = {nullptr, nullptr};   // ping-pong layer outputs [B][max_n]
@@ -52,6 +56,7 @@ struct Workspace {
   int32_t* blk_off = nullptr;           // [B][MAX_ROW_BLOCKS + 1]
   void* grouped = nullptr;              // union lists of the grouped evaluation
   void* tiles = nullptr;                // pair masks and split activations of the masked tiles
+  void* hash_int = nullptr;             // digits of the activations and partial sums of the integer hash
   void* hash_split = nullptr;           // partial sums of the split hash projection
   size_t bytes = 0;
   int max_n = 0, max_H = 0, max_na = 0;
@@ -89,6 +94,11 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
       tiles_bytes = std::max(tiles_bytes, masked_tiles_workspace_bytes(B, l.d_out, l.d_in));
   w->tiles = take(tiles_bytes);
   w->hash_split = take(hash_split_workspace_bytes());
+  size_t hint = 0;
+  if (B >= HASH_INT_MIN_BATCH)
+    for (const Layer& l : m->layers)
+      if (l.Wh5) hint = std::max(hint, hash_int_workspace_bytes(B, l.H(), l.d_in));
+  w->hash_int = hint ? take(hint) : nullptr;
   w->bytes = off;
 }
 
@@ -260,6 +270,19 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
       set_error("uploading the hash-node map failed: %s", hipGetErrorString(e));
       return fail(SLONN_EHIP);
     }
+    // the hash rows once more as fixed-point digits for the int8 matrix cores (large batches)
+    if (hash_int_supported(L.d_in)) {
+      if (hipMalloc(&L.Wh5, (size_t)H * 5 * L.d_in) != hipSuccess ||
+          hipMalloc(&L.ewh, (size_t)H * 4) != hipSuccess) {
+        (void)hipGetLastError();
+        if (L.Wh5) (void)hipFree(L.Wh5);
+        L.Wh5 = nullptr;
+      } else if (launch_slice5(L.Wh, L.d_in, H, L.d_in, L.Wh5, L.ewh, nullptr) != SLONN_OK ||
+                 (e = hipStreamSynchronize(nullptr)) != hipSuccess) {
+        if (e != hipSuccess) set_error("slicing the FreeHash rows failed: %s", hipGetErrorString(e));
+        return fail(SLONN_EHIP);
+      }
+    }
     // Large fp32 layers (the ones the forward pass walks in row blocks): the weights once more as
     // three bf16 parts, for the masked tiles that serve large batches on the bf16 matrix cores.
     // Without the memory for it large batches stay on the other paths.
@@ -354,6 +377,13 @@ int slonn_model_set_path(slonn_model* m, int path) {
   return SLONN_OK;
 }
 
+int slonn_model_set_hash_margin(slonn_model* m, double margin) {
+  if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
+  if (!(margin >= 1.0)) SLONN_FAIL(SLONN_EINVAL, "margin must be at least 1");
+  m->hash_margin = margin;
+  return SLONN_OK;
+}
+
 int slonn_model_set_hash_nodes_always_active(slonn_model* m, int on) {
   if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
   m->hash_first = on != 0;
@@ -368,6 +398,8 @@ int slonn_model_destroy(slonn_model* m) {
     if (L.hslot) (void)hipFree(L.hslot);
     if (L.hnodes) (void)hipFree(L.hnodes);
     if (L.W3) (void)hipFree(L.W3);
+    if (L.Wh5) (void)hipFree(L.Wh5);
+    if (L.ewh) (void)hipFree(L.ewh);
   }
   delete m;
   return SLONN_OK;
@@ -727,8 +759,12 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       // unless the policy kernel needs the projections first)
       HashSplit split;
       const bool policy_here = hook && l == hook->layer;
-      rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, w.hash_split,
-                               policy_here ? nullptr : &split, s);
+      if (L.Wh5 && w.hash_int && B >= HASH_INT_MIN_BATCH)
+        rc = launch_hash_project_int(cur, ldcur, L.Wh, L.Wh5, L.ewh, L.bh, z, B, L.H(), L.d_in, m->hash_margin,
+                                     w.hash_int, s);
+      else
+        rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, w.hash_split,
+                                 policy_here ? nullptr : &split, s);
       if (rc) return rc;
       if (policy_here) {
         // the budget of this and of every later layer comes from the confidence tables

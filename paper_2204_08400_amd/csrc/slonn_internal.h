@@ -42,6 +42,8 @@ struct Layer {
   int16_t* hslot = nullptr;      // [d_out] device: index of the node among the hash rows, or -1
   int32_t* hnodes = nullptr;     // [H] device copy of hash_nodes
   uint16_t* W3 = nullptr;        // large fp32 layers: the weights as three interleaved bf16 parts [d_out][3 d_in]
+  int8_t* Wh5 = nullptr;         // the FreeHash rows as five interleaved 7-bit digits [H][5 d_in] (int8 cores)
+  int32_t* ewh = nullptr;        // [H] their fixed-point exponents
   int H() const { return K * L; }
   bool activated() const { return K > 0 && L > 0; }
 };
@@ -64,6 +66,7 @@ struct slonn_model {
   int path = SLONN_PATH_AUTO;
   bool path_grouped = true;       // allow the grouped (cross-query) evaluation on the per-layer path
   bool hash_first = false;        // hash nodes always computed, never selected (Section 3.4 variant)
+  double hash_margin = 2.0;       // integer hash projections: |z| must exceed this many error bounds
   int max_lds_bytes = 65536;      // per-workgroup LDS the device grants on request
   int n_cu = 256;
 };
@@ -203,6 +206,17 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
                         int H, int d, void* split_scratch, HashSplit* pending, hipStream_t s);
 size_t hash_split_workspace_bytes();
 int hash_split_factor(int B, int H, int d);
+
+// The same projections for a large batch on the int8 matrix cores: fixed-point digits, exact
+// integer dot products, every sign certified against a rigorous error bound, the uncertain
+// projections recomputed in fp64.  W5, ew: the hash rows through launch_slice5 (model set-up).
+// d a multiple of 64 (hash_int_supported).  scratch: hash_int_workspace_bytes(B, H, d) bytes.
+bool hash_int_supported(int d);
+size_t hash_int_workspace_bytes(int B, int H, int d);
+int launch_slice5(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s);
+int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8_t* W5, const int32_t* ew,
+                            const float* bh, float* Z, int B, int H, int d, double margin, void* scratch,
+                            hipStream_t s);
 
 // keys + bucket lookup + merge for one layer.  yzero (nullable): [B][ldy] rows to clear.
 int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,

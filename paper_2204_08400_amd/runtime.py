@@ -55,6 +55,10 @@ class Network:
         """Hash nodes always computed and never selected (see slonn.h)."""
         slonn.slonn_model_set_hash_nodes_always_active(self.model, on)
 
+    def set_hash_margin(self, margin: float):
+        """Certification margin of the integer hash projections (diagnostic, see slonn.h)."""
+        slonn.slonn_model_set_hash_margin(self.model, margin)
+
     # -- helpers -------------------------------------------------------------- #
     def workspace(self, B: int):
         if self._ws is None or B > self._ws_B:

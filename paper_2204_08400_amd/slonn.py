@@ -33,7 +33,7 @@ EXPORTS = [
     "slonn_policy_set_latency_profile", "slonn_policy_keep_aclo", "slonn_policy_keep_lcao",
     "slonn_sparse_forward_aclo",
     "slonn_forward_graph_create", "slonn_forward_graph_launch", "slonn_forward_graph_destroy",
-    "slonn_activation_variance", "slonn_sample_hash_nodes",
+    "slonn_activation_variance", "slonn_sample_hash_nodes", "slonn_model_set_hash_margin",
 ]
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused")
 PATH_AUTO, PATH_LAYERS, PATH_FUSED = 0, 1, 2
@@ -330,6 +330,10 @@ def slonn_sparse_forward_aclo(model: Model, tables: Optional[Tables], policy: Po
         C.byref(taps) if taps is not None else None, C.c_void_p(_ptr(workspace)),
         C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
         C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_model_set_hash_margin(model: Model, margin: float):
+    _check(load().slonn_model_set_hash_margin(model.h, C.c_double(margin)))
 
 
 def slonn_activation_variance(A, var_out, stream=None):

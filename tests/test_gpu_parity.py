@@ -611,6 +611,41 @@ def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d, n):
     _say(f"  {compare_sparse(got, ref, layers, 'grouped hash-first')}")
 
 
+@pytest.mark.parametrize("w_dtype", [wl.W_F32, wl.W_BF16], ids=["f32", "bf16"])
+def test_integer_hash_projection_matches_oracle(rt, oracle, w_dtype):
+    """Large batches take their hash projections from the int8 matrix cores (fixed-point digits,
+    exact integer sums, every sign certified against a rigorous bound, uncertain projections
+    recomputed in fp64).  Codes and active sets match the oracle bit for bit as everywhere;
+    with a margin that sends EVERY projection through the fp64 recomputation the codes and
+    active sets stay the same and the outputs agree to the usual tolerance; rows of zeros, tiny
+    and huge magnitudes go through the same path."""
+    dims = (192, 640, 2048, 16)           # d = 192 and 640: multiples of 64, several chunks, ragged tiles
+    layers, net, _ = make_case(oracle, dims, 5, 9, seed=131, cap=700, N_build=160, kind="clip3", w_dtype=w_dtype)
+    g = _gpu_net(rt, layers, net, path="layers")
+    B = 600                               # ragged: four full 128-query tiles and a tail of 88
+    X = make_queries(dims, B, seed=132, kind="clip3")
+    X[5] = 0.0                            # a row of zeros: projections are the biases
+    X[6] *= 1e-20                         # tiny inputs
+    X[7] *= 1e15                          # huge inputs
+    X[8, 1:] = 0.0                        # a single non-zero
+    keep = wl.keep_uniform(B, 0.02, 0.5, 3)
+    _say("integer hash: oracle")
+    ref = net.sparse_forward(X, keep)
+    _say("integer hash: default margin")
+    got = to_numpy_result(g.sparse_forward(X, _keep_tensor(keep), taps=True))
+    _say(f"  {compare_sparse(got, ref, layers, 'integer hash')}")
+    g.set_hash_margin(1e300)
+    _say("integer hash: every projection recomputed")
+    got2 = to_numpy_result(g.sparse_forward(X, _keep_tensor(keep), taps=True))
+    _say(f"  {compare_sparse(got2, ref, layers, 'integer hash, all recomputed')}")
+    ok = np.ones(B, bool)
+    for l in range(len(layers) - 1):
+        ok &= ~ref["layers"][l]["tie"]
+    for l in range(len(layers) - 1):
+        assert np.array_equal(got["taps"]["codes"][l][ok], got2["taps"]["codes"][l][ok])
+    g.set_hash_margin(2.0)
+
+
 @pytest.mark.parametrize("path", ["layers", "fused"])
 def test_selected_hash_nodes_reuse_their_projection(rt, oracle, path):
     """Section 3.4: a hash projection is the node's own pre-activation.  Where a hash node is

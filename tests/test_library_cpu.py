@@ -154,3 +154,4 @@ def test_sample_hash_nodes_rejects(slonn):
     lib = slonn.load()
     assert lib.slonn_sample_hash_nodes(None, 8, 1, 1, None, None) == -1
     assert lib.slonn_activation_variance(None, C.c_int64(4), 4, C.c_int64(4), None, None) == -1
+    assert lib.slonn_model_set_hash_margin(None, C.c_double(2.0)) == -1
