@@ -12,8 +12,12 @@
 // The digit pairs with s + t >= 3 are kept (19 of 25).  What is lost is bounded rigorously:
 // truncation of the operands by d * 2^(e_w + e_x - 34), the dropped pairs by
 // d * 2^(e_w + e_x - 39), together below BOUND = d * 2^(e_w + e_x - 33).  A projection with
-// |z| > margin * BOUND has a certain sign and an fp32-accurate value; the few others (and rows
-// with non-finite entries) are recomputed in fp64 like the fp64 kernel does.
+// |z| > margin * BOUND has a certain sign; the few others (and rows with non-finite entries) are
+// recomputed in fp64 like the fp64 kernel does.  The value itself is off by at most BOUND, and
+// typically by about BOUND / sqrt(d) (truncation errors of either sign): the size of the
+// rounding error of an fp32 evaluation of the same dot product (2^-24 of the partial sums), which
+// is the accuracy of every other node's output (Section 3.4 lets a selected hash node take its
+// output from its projection).
 //
 //   slice5_kernel         one workgroup per row: row maximum -> e, five int8 digits per element,
 //                         interleaved per 16 elements (element k, digit s of row i at
