@@ -204,8 +204,9 @@ __global__ __launch_bounds__(256) void gather_grouped_kernel(
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __global__ void split_x_kernel(const float* __restrict__ X, int ldx, int B, int d,
-                               uint16_t* __restrict__ xs3) {
+                               uint16_t* __restrict__ xs3, const int32_t* __restrict__ served) {
   const int q = blockIdx.x;                             // queries on grid.x: batches up to 2^20
+  if (served && served[q >> 4]) return;                 // evaluated as masked tiles: not needed here
   const int i = blockIdx.y * blockDim.x + threadIdx.x;
   if (i >= d) return;
   const float x = X[(size_t)q * ldx + i];
@@ -370,7 +371,7 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
                        ucnt, gflag, n, ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, thr10, served);
     SLONN_HIP(hipGetLastError());
     if (bf16_cores) {
-      hipLaunchKernelGGL(split_x_kernel, dim3(B, (d + 255) / 256), dim3(256), 0, s, X, ldx, B, d, xs3);
+      hipLaunchKernelGGL(split_x_kernel, dim3(B, (d + 255) / 256), dim3(256), 0, s, X, ldx, B, d, xs3, served);
       SLONN_HIP(hipGetLastError());
     }
   }

@@ -79,16 +79,28 @@ __global__ __launch_bounds__(256) void slice5_kernel(const float* __restrict__ X
   const int e = s_e;
   int8_t* o = out + (size_t)row * DIGITS * d;
   const double scale = e == BAD_ROW ? 0.0 : ldexp(1.0, FRAC_BITS - e);
-  for (int i = tid; i < d; i += 256) {
-    const double sv = (double)x[i] * scale;   // exact: a power of two times an fp32 number
-    const long long V = e == BAD_ROW ? 0 : (long long)sv;   // truncation towards zero, |V| < 2^35
-    const unsigned long long a = (unsigned long long)(V < 0 ? -V : V);
-    const size_t at = (size_t)(i >> 4) * (16 * DIGITS) + (i & 15);
+  // sixteen elements per thread: five 16-byte stores (d is a multiple of 64)
+  for (int g16 = tid; g16 < (d >> 4); g16 += 256) {
+    uint32_t packed[DIGITS][4];
 #pragma unroll
-    for (int s = 0; s < DIGITS; ++s) {
-      const int dig = (int)((a >> (7 * s)) & 127u);
-      o[at + 16 * s] = (int8_t)(V < 0 ? -dig : dig);
+    for (int s = 0; s < DIGITS; ++s)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) packed[s][w] = 0u;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const double sv = (double)x[16 * g16 + j] * scale;   // exact: a power of two times an fp32 number
+      const long long V = e == BAD_ROW ? 0 : (long long)sv;   // truncation towards zero, |V| < 2^35
+      const unsigned long long a = (unsigned long long)(V < 0 ? -V : V);
+#pragma unroll
+      for (int s = 0; s < DIGITS; ++s) {
+        const int dig = (int)((a >> (7 * s)) & 127u);
+        const uint32_t byte = (uint32_t)(uint8_t)(int8_t)(V < 0 ? -dig : dig);
+        packed[s][j >> 2] |= byte << (8 * (j & 3));
+      }
     }
+    u32x4* op = reinterpret_cast<u32x4*>(o + (size_t)g16 * (16 * DIGITS));
+#pragma unroll
+    for (int s = 0; s < DIGITS; ++s) op[s] = (u32x4){packed[s][0], packed[s][1], packed[s][2], packed[s][3]};
   }
 }
 

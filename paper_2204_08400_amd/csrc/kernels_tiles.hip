@@ -101,16 +101,39 @@ __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restric
     }
     atomicOr(&bits[node >> 5], 1u << (node & 31));
   }
-  for (int i = tid; i < d; i += 256) {
-    const float x = X[(size_t)q * ldx + i];
-    const uint32_t hb = __float_as_uint(x) & 0xFFFF0000u;
-    const float r1 = x - __uint_as_float(hb);
-    const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
-    const float r2 = r1 - __uint_as_float(mb);
-    const size_t at = (size_t)q * 3 * d + (size_t)(i >> 3) * 24 + (i & 7);
-    X3[at] = (uint16_t)(hb >> 16);
-    X3[at + 8] = (uint16_t)(mb >> 16);
-    X3[at + 16] = (uint16_t)(__float_as_uint(r2) >> 16);
+  // eight elements per thread: two 16-byte loads, three 16-byte stores (d is a multiple of 32)
+  const bool vec = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);
+  for (int g8 = tid; g8 < (d >> 3); g8 += 256) {
+    float xv[8];
+    const float* xp = X + (size_t)q * ldx + 8 * g8;
+    if (vec) {
+      const float4 a = *reinterpret_cast<const float4*>(xp), b = *reinterpret_cast<const float4*>(xp + 4);
+      xv[0] = a.x; xv[1] = a.y; xv[2] = a.z; xv[3] = a.w; xv[4] = b.x; xv[5] = b.y; xv[6] = b.z; xv[7] = b.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xv[e] = xp[e];
+    }
+    uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      uint32_t h2[2], m2[2], l2[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const float x = xv[e + j];
+        const uint32_t hb = __float_as_uint(x) & 0xFFFF0000u;
+        const float r1 = x - __uint_as_float(hb);
+        const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
+        const float r2 = r1 - __uint_as_float(mb);
+        h2[j] = hb >> 16; m2[j] = mb >> 16; l2[j] = __float_as_uint(r2) >> 16;
+      }
+      hi[e >> 1] = h2[0] | (h2[1] << 16);
+      mid[e >> 1] = m2[0] | (m2[1] << 16);
+      lo[e >> 1] = l2[0] | (l2[1] << 16);
+    }
+    u32x4* o = reinterpret_cast<u32x4*>(X3 + (size_t)q * 3 * d + (size_t)g8 * 24);
+    o[0] = (u32x4){hi[0], hi[1], hi[2], hi[3]};
+    o[1] = (u32x4){mid[0], mid[1], mid[2], mid[3]};
+    o[2] = (u32x4){lo[0], lo[1], lo[2], lo[3]};
   }
   __syncthreads();
   for (int i = tid; i < words; i += 256) mask[(size_t)q * words + i] = bits[i];
