@@ -176,7 +176,7 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
   constexpr int NB = TN / (16 * WN);       // 16-node blocks per wavefront
   static_assert(TQ * PX % NT == 0 && TN * PW % NT == 0, "loader pieces must divide evenly");
   const int m0 = blockIdx.y * TQ, n0 = blockIdx.x * TN;
-  if (!flags[m0 / 16]) return;             // these queries are served another way
+  if (flags && !flags[m0 / 16]) return;    // these queries are served another way (no flags: all are served here)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wq = wave / WN, wn = wave % WN;
   const int r = lane & 15, kg = lane >> 4;
@@ -287,7 +287,8 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
     for (int a = 0; a < NB; ++a) {
       const int node = n0 + wn * 16 * NB + a * 16 + 4 * kg; // a multiple of 4: its four bits share a word
       if (node >= n) continue;
-      const uint32_t four = (mask[(size_t)q * words + (node >> 5)] >> (node & 31)) & 0xFu;
+      // (no mask: a layer computed in full, every pair is written)
+      const uint32_t four = mask ? (mask[(size_t)q * words + (node >> 5)] >> (node & 31)) & 0xFu : 0xFu;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         if (((four >> v) & 1u) && node + v < n) {
@@ -351,6 +352,37 @@ int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, cons
   {                                                                                                             \
     constexpr size_t lds = tiles_lds_bytes<TQ_, WP_>();                                                         \
     static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");                   \
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, WP_, NT_>),            \
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                       \
+    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, WP_, NT_>), dim3((n + TN - 1) / TN, (B + TQ_ - 1) / TQ_),      \
+                       dim3(NT_), lds, s, X3, Wp, bias, mask, flags, Y, ldy, B, n, d, a);                       \
+  }
+  if (w_parts == 3) {
+    if (big) SLONN_LAUNCH_TILES(128, 3, 512) else SLONN_LAUNCH_TILES(64, 3, 256)
+  } else {
+    if (big) SLONN_LAUNCH_TILES(128, 1, 512) else SLONN_LAUNCH_TILES(64, 1, 256)
+  }
+#undef SLONN_LAUNCH_TILES
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+// A layer computed in full for a large batch through the same tiles (no mask, every query
+// served): bf16 weights as they are (w_parts 1) or fp32 weights in three parts (w_parts 3).
+// scratch: 3 * B * d * 2 bytes for the split activations.
+int launch_dense_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx, float* Y,
+                       int ldy, int B, int d, int n, int act, void* scratch, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_DENSE, s);
+  uint16_t* X3 = static_cast<uint16_t*>(scratch);
+  int rc = launch_split3(X, ldx, B, d, X3, s);
+  if (rc) return rc;
+  const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
+  const uint32_t* mask = nullptr;
+  const int32_t* flags = nullptr;
+  const bool big = (long)((B + 127) / 128) * ((n + TN - 1) / TN) >= 256;
+#define SLONN_LAUNCH_TILES(TQ_, WP_, NT_)                                                                        \
+  {                                                                                                             \
+    constexpr size_t lds = tiles_lds_bytes<TQ_, WP_>();                                                         \
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, WP_, NT_>),            \
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                       \
     hipLaunchKernelGGL((masked_tiles_kernel<TQ_, WP_, NT_>), dim3((n + TN - 1) / TN, (B + TQ_ - 1) / TQ_),      \

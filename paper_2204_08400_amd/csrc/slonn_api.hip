@@ -56,6 +56,7 @@ struct Workspace {
   int32_t* blk_off = nullptr;           // [B][MAX_ROW_BLOCKS + 1]
   void* grouped = nullptr;              // union lists of the grouped evaluation
   void* tiles = nullptr;                // pair masks and split activations of the masked tiles
+  size_t tiles_bytes = 0;
   void* hash_int = nullptr;             // digits of the activations and partial sums of the integer hash
   void* hash_split = nullptr;           // partial sums of the split hash projection
   size_t bytes = 0;
@@ -92,7 +93,12 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   for (const Layer& l : m->layers)
     if (l.activated() && (l.W3 || l.w_dtype == SLONN_BF16) && masked_tiles_supported(l.d_in, l.d_out, m->max_lds_bytes))
       tiles_bytes = std::max(tiles_bytes, masked_tiles_workspace_bytes(B, l.d_out, l.d_in));
-  w->tiles = take(tiles_bytes);
+  // (a bf16 layer computed in full uses the same buffer for its split activations)
+  for (const Layer& l : m->layers)
+    if (!l.activated() && l.w_dtype == SLONN_BF16 && l.d_in % 32 == 0 && B >= 256)
+      tiles_bytes = std::max(tiles_bytes, (size_t)3 * B * l.d_in * 2 + 256);
+  w->tiles = tiles_bytes ? take(tiles_bytes) : nullptr;
+  w->tiles_bytes = tiles_bytes;
   w->hash_split = take(hash_split_workspace_bytes());
   size_t hint = 0;
   if (B >= HASH_INT_MIN_BATCH)
@@ -867,6 +873,13 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
     } else if (l == 0 && X->format == SLONN_ELL) {
       rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
                             ldo, B, L.d_in, L.d_out, act, s);
+      if (rc) return rc;
+    } else if (w.tiles && L.w_dtype == SLONN_BF16 && L.d_in % 32 == 0 && reinterpret_cast<uintptr_t>(L.W) % 16 == 0 &&
+               (long)((B + 63) / 64) * ((L.d_out + 127) / 128) >= 128 && (size_t)3 * B * L.d_in * 2 <= w.tiles_bytes) {
+      // a bf16-weight layer computed in full for a large batch: the tiles of the masked evaluation
+      // without a mask, on the bf16 matrix cores (three parts of the activations, fp32 accuracy)
+      rc = launch_dense_tiles(static_cast<const uint16_t*>(L.W), 1, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out,
+                              act, w.tiles, s);
       if (rc) return rc;
     } else if ((size_t)((B + 63) / 64) * ((L.d_out + 63) / 64) >= 256 ||
                ((size_t)((B + 31) / 32) * ((L.d_out + 31) / 32) >= 64 &&

@@ -277,6 +277,8 @@ struct TilesReuse {
 bool masked_tiles_supported(int d, int n, int max_lds);
 size_t masked_tiles_workspace_bytes(int B, int n, int d);
 int launch_split3(const float* X, int64_t ldx, int64_t rows, int d, uint16_t* out, hipStream_t s);
+int launch_dense_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx, float* Y,
+                       int ldy, int B, int d, int n, int act, void* scratch, hipStream_t s);
 int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx,
                         const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d,
                         int n, int act, const TilesReuse* reuse, int min_keep_permille, void* scratch,
