@@ -156,8 +156,8 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // operand with the eight elements 8 (l / 16) .. + 7 of the step; register v of lane l holds
 // D[4 (l / 16) + v][l % 16], rows from the first operand (here: nodes), columns from the second
 // (queries).
-// TQ queries per tile; WP weight parts; NT threads (wavefronts in 2 x NT / 128: query halves x node strips)
-template <int TQ, int WP, int NT>
+// TQ queries x TNN nodes per tile; WP weight parts; NT threads (wavefronts in 2 x NT / 128: query halves x node strips)
+template <int TQ, int TNN, int WP, int NT>
 __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __restrict__ X3,
                                                           const uint16_t* __restrict__ Wp,
                                                           const float* __restrict__ bias,
@@ -165,17 +165,17 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
                                                           const int32_t* __restrict__ flags,
                                                           float* __restrict__ Y, int ldy, int B, int n, int d,
                                                           int act) {
-  extern __shared__ u32x4 tiles_lds[];     // two buffers of [TQ rows of X | TN rows of W]
+  extern __shared__ u32x4 tiles_lds[];     // two buffers of [TQ rows of X | TNN rows of W]
   constexpr int PX = PIECES, PW = 4 * WP;  // 16-byte pieces per row and chunk of 32 elements
   constexpr int ROWX = PX + 1, ROWW = PW + 1;   // LDS rows, padded by one piece (208 / 80 bytes stagger the banks)
-  constexpr int BUF16 = TQ * ROWX + TN * ROWW;
+  constexpr int BUF16 = TQ * ROWX + TNN * ROWW;
   constexpr int QB = TQ / 32;              // 16-query blocks per wavefront
   constexpr int XP = TQ * PX / NT;         // X pieces per thread and chunk
-  constexpr int WT = TN * PW / NT;         // W pieces per thread and chunk
+  constexpr int WT = TNN * PW / NT;         // W pieces per thread and chunk
   constexpr int WN = NT / 128;             // node strips (wavefronts along the nodes)
-  constexpr int NB = TN / (16 * WN);       // 16-node blocks per wavefront
-  static_assert(TQ * PX % NT == 0 && TN * PW % NT == 0, "loader pieces must divide evenly");
-  const int m0 = blockIdx.y * TQ, n0 = blockIdx.x * TN;
+  constexpr int NB = TNN / (16 * WN);       // 16-node blocks per wavefront
+  static_assert(TQ * PX % NT == 0 && TNN * PW % NT == 0, "loader pieces must divide evenly");
+  const int m0 = blockIdx.y * TQ, n0 = blockIdx.x * TNN;
   if (flags && !flags[m0 / 16]) return;    // these queries are served another way (no flags: all are served here)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wq = wave / WN, wn = wave % WN;
@@ -301,13 +301,13 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
   }
 }
 
-template <int TQ, int WP>
-constexpr size_t tiles_lds_bytes() { return (size_t)2 * (TQ * (PIECES + 1) + TN * (4 * WP + 1)) * 16; }
+template <int TQ, int TNN, int WP>
+constexpr size_t tiles_lds_bytes() { return (size_t)2 * (TQ * (PIECES + 1) + TNN * (4 * WP + 1)) * 16; }
 
 }  // namespace
 
 bool masked_tiles_supported(int d, int n, int max_lds) {
-  return d % 32 == 0 && (size_t)((n + 31) / 32) * 4 <= (size_t)max_lds && tiles_lds_bytes<128, 3>() <= (size_t)max_lds;
+  return d % 32 == 0 && (size_t)((n + 31) / 32) * 4 <= (size_t)max_lds && tiles_lds_bytes<128, 128, 3>() <= (size_t)max_lds;
 }
 
 size_t masked_tiles_workspace_bytes(int B, int n, int d) {
@@ -348,19 +348,22 @@ int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, cons
   // half as often: C3 batch 1024 190 -> 160 us per layer); 64 x 128 tiles with four, two
   // workgroups per compute unit, for smaller batches
   const bool big = (long)((B + 127) / 128) * ((n + TN - 1) / TN) >= 256;
-#define SLONN_LAUNCH_TILES(TQ_, WP_, NT_)                                                                        \
+  const bool wide = (long)((B + 127) / 128) * ((n + 255) / 256) >= 256;
+#define SLONN_LAUNCH_TILES(TQ_, TN_, WP_, NT_)                                                                        \
   {                                                                                                             \
-    constexpr size_t lds = tiles_lds_bytes<TQ_, WP_>();                                                         \
+    constexpr size_t lds = tiles_lds_bytes<TQ_, TN_, WP_>();                                                         \
     static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");                   \
-    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, WP_, NT_>),            \
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, TN_, WP_, NT_>),            \
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                       \
-    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, WP_, NT_>), dim3((n + TN - 1) / TN, (B + TQ_ - 1) / TQ_),      \
+    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, TN_, WP_, NT_>), dim3((n + TN_ - 1) / TN_, (B + TQ_ - 1) / TQ_),      \
                        dim3(NT_), lds, s, X3, Wp, bias, mask, flags, Y, ldy, B, n, d, a);                       \
   }
   if (w_parts == 3) {
-    if (big) SLONN_LAUNCH_TILES(128, 3, 512) else SLONN_LAUNCH_TILES(64, 3, 256)
+    if (big) SLONN_LAUNCH_TILES(128, 128, 3, 512) else SLONN_LAUNCH_TILES(64, 128, 3, 256)
   } else {
-    if (big) SLONN_LAUNCH_TILES(128, 1, 512) else SLONN_LAUNCH_TILES(64, 1, 256)
+    // one weight part: twice the node strip per wavefront keeps the LDS reads per MFMA down
+    if (wide) SLONN_LAUNCH_TILES(128, 256, 1, 512) else if (big) SLONN_LAUNCH_TILES(128, 128, 1, 512)
+    else SLONN_LAUNCH_TILES(64, 128, 1, 256)
   }
 #undef SLONN_LAUNCH_TILES
   SLONN_HIP(hipGetLastError());
@@ -380,18 +383,21 @@ int launch_dense_tiles(const uint16_t* Wp, int w_parts, const float* bias, const
   const uint32_t* mask = nullptr;
   const int32_t* flags = nullptr;
   const bool big = (long)((B + 127) / 128) * ((n + TN - 1) / TN) >= 256;
-#define SLONN_LAUNCH_TILES(TQ_, WP_, NT_)                                                                        \
+  const bool wide = (long)((B + 127) / 128) * ((n + 255) / 256) >= 256;
+#define SLONN_LAUNCH_TILES(TQ_, TN_, WP_, NT_)                                                                        \
   {                                                                                                             \
-    constexpr size_t lds = tiles_lds_bytes<TQ_, WP_>();                                                         \
-    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, WP_, NT_>),            \
+    constexpr size_t lds = tiles_lds_bytes<TQ_, TN_, WP_>();                                                         \
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, TN_, WP_, NT_>),            \
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                       \
-    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, WP_, NT_>), dim3((n + TN - 1) / TN, (B + TQ_ - 1) / TQ_),      \
+    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, TN_, WP_, NT_>), dim3((n + TN_ - 1) / TN_, (B + TQ_ - 1) / TQ_),      \
                        dim3(NT_), lds, s, X3, Wp, bias, mask, flags, Y, ldy, B, n, d, a);                       \
   }
   if (w_parts == 3) {
-    if (big) SLONN_LAUNCH_TILES(128, 3, 512) else SLONN_LAUNCH_TILES(64, 3, 256)
+    if (big) SLONN_LAUNCH_TILES(128, 128, 3, 512) else SLONN_LAUNCH_TILES(64, 128, 3, 256)
   } else {
-    if (big) SLONN_LAUNCH_TILES(128, 1, 512) else SLONN_LAUNCH_TILES(64, 1, 256)
+    // one weight part: twice the node strip per wavefront keeps the LDS reads per MFMA down
+    if (wide) SLONN_LAUNCH_TILES(128, 256, 1, 512) else if (big) SLONN_LAUNCH_TILES(128, 128, 1, 512)
+    else SLONN_LAUNCH_TILES(64, 128, 1, 256)
   }
 #undef SLONN_LAUNCH_TILES
   SLONN_HIP(hipGetLastError());
