@@ -44,7 +44,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int DIGITS = 5;          // 7-bit digits per element
 constexpr int FRAC_BITS = 35;      // fixed point: 35 bits below 2^e
 constexpr int CLASSES = 6;         // s + t = 3 .. 8
-constexpr int HQ = 128, HH = 64;   // queries x hash rows per tile
+constexpr int HQ = 128;            // queries per tile (hash rows per tile: 64 or 48, see the launcher)
 constexpr int HPIECES = 4 * DIGITS;  // 16-byte pieces per row and chunk of 64 elements
 constexpr int HROW = HPIECES + 1;    // LDS row in pieces (336 bytes: staggers the banks)
 constexpr int BAD_ROW = INT_MIN;   // exponent entry of a row with a non-finite element
@@ -120,6 +120,8 @@ __device__ __forceinline__ i32x4 as_i32x4(u32x4 v) { return __builtin_bit_cast(i
 // operand with the sixteen elements 16 (l / 16) .. + 15 of the step; register v of lane l holds
 // D[4 (l / 16) + v][l % 16], rows from the first operand (here: hash rows), columns from the
 // second (queries).
+// HH hash rows per tile, wavefronts as WQ query strips x WH hash-row strips (WQ * WH = 8)
+template <int HH, int WQ, int WH>
 __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __restrict__ X5,
                                                             const int8_t* __restrict__ W5,
                                                             double* __restrict__ part, int B, int H, int d) {
@@ -129,7 +131,9 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
   constexpr int PER = (TOTAL + 511) / 512;           // per thread (the last one partly repeated)
   const int q0 = blockIdx.y * HQ, h0 = blockIdx.x * HH;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wq = wave >> 1, wh = wave & 1;           // 4 query strips x 2 hash-row strips of 32
+  constexpr int NBQ = HQ / (16 * WQ), NBH = HH / (16 * WH);   // 16 x 16 blocks per wavefront
+  static_assert(WQ * WH == 8 && HQ % (16 * WQ) == 0 && HH % (16 * WH) == 0, "wavefront grid must cover the tile");
+  const int wq = wave / WH, wh = wave % WH;
   const int r = lane & 15, kg = lane >> 4;
 
   const u32x4* src[PER];
@@ -151,11 +155,11 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
   const int c_begin = min(nchunks, (int)blockIdx.z * per_z), c_end = min(nchunks, c_begin + per_z);
   const int last = max(c_end - 1, c_begin);
 
-  i32x4 acc[2][2][CLASSES];                 // [hash block][query block][s + t - 3]
+  i32x4 acc[NBH][NBQ][CLASSES];             // [hash block][query block][s + t - 3]
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < NBH; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NBQ; ++b)
 #pragma unroll
       for (int c = 0; c < CLASSES; ++c) acc[a][b][c] = (i32x4){0, 0, 0, 0};
 
@@ -175,24 +179,24 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
     const u32x4* Ws = Xs + HQ * HROW;
     // An MFMA consumes the whole chunk of 64 elements: lane (r, kg) supplies the 16 elements of
     // group kg, i.e. piece kg * DIGITS + digit of its row.  One MFMA per digit pair and block.
-    i32x4 xd[2][DIGITS];
+    i32x4 xd[NBQ][DIGITS];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NBQ; ++b)
 #pragma unroll
       for (int t = 0; t < DIGITS; ++t)
-        xd[b][t] = as_i32x4(Xs[(wq * 32 + b * 16 + r) * HROW + kg * DIGITS + t]);
+        xd[b][t] = as_i32x4(Xs[(wq * 16 * NBQ + b * 16 + r) * HROW + kg * DIGITS + t]);
 #pragma unroll
     for (int s = 0; s < DIGITS; ++s) {
-      i32x4 wd[2];
+      i32x4 wd[NBH];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) wd[a] = as_i32x4(Ws[(wh * 32 + a * 16 + r) * HROW + kg * DIGITS + s]);
+      for (int a = 0; a < NBH; ++a) wd[a] = as_i32x4(Ws[(wh * 16 * NBH + a * 16 + r) * HROW + kg * DIGITS + s]);
 #pragma unroll
       for (int t = 0; t < DIGITS; ++t) {
         if (s + t < 3) continue;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < NBH; ++a)
 #pragma unroll
-          for (int b = 0; b < 2; ++b)
+          for (int b = 0; b < NBQ; ++b)
             acc[a][b][s + t - 3] =
                 __builtin_amdgcn_mfma_i32_16x16x64_i8(wd[a], xd[b][t], acc[a][b][s + t - 3], 0, 0, 0);
       }
@@ -217,17 +221,17 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
 #undef SLONN_HASH_LOAD
 #undef SLONN_HASH_STORE
 
-  // register v of block (a, b): hash row h0 + 32 wh + 16 a + 4 kg + v, query q0 + 32 wq + 16 b + r
+  // register v of block (a, b): hash row h0 + 16 NBH wh + 16 a + 4 kg + v, query q0 + 16 NBQ wq + 16 b + r
   double* mine = part + (size_t)blockIdx.z * B * H;
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    const int q = q0 + wq * 32 + b * 16 + r;
+  for (int b = 0; b < NBQ; ++b) {
+    const int q = q0 + wq * 16 * NBQ + b * 16 + r;
     if (q >= B) continue;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < NBH; ++a)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int h = h0 + wh * 32 + a * 16 + 4 * kg + v;
+        const int h = h0 + wh * 16 * NBH + a * 16 + 4 * kg + v;
         if (h >= H) continue;
         double sum = 0.0;
 #pragma unroll
@@ -285,14 +289,24 @@ __global__ __launch_bounds__(256) void hash_int_finish_kernel(const double* __re
 
 bool hash_int_supported(int d) { return d % 64 == 0 && d <= 16384; }
 
-// Slices of the reduction dimension: as many as keep the grid within one round of workgroups (one
-// workgroup per compute unit: the two tile buffers take most of its LDS), at least 8 chunks each.
-int hash_int_splits(int B, int H, int d) {
-  const int tiles = ((B + HQ - 1) / HQ) * ((H + HH - 1) / HH);
+// Tile height (64 or 48 hash rows) and slices of the reduction dimension: the pair that fills one
+// round of workgroups best (one workgroup per compute unit: the two tile buffers take most of
+// its LDS), slices of at least 8 chunks.
+void hash_int_plan(int B, int H, int d, int* hh_out, int* s_out) {
   const int nchunks = d / 64;
-  int S = 1;
-  while (tiles * S * 2 <= 256 && S * 2 <= 8 && nchunks / (S * 2) >= 8) S *= 2;
-  return S;
+  int best_hh = 64, best_s = 1;
+  long best_fill = -1;
+  for (int hh : {64, 48}) {
+    const int tiles = ((B + HQ - 1) / HQ) * ((H + hh - 1) / hh);
+    int S = 1;
+    while (tiles * S * 2 <= 256 && S * 2 <= 8 && nchunks / (S * 2) >= 8) S *= 2;
+    // useful work per slot of the rounds the grid takes (rows beyond H are wasted work)
+    const long rounds = (tiles * S + 255) / 256;
+    const long fill = (long)H * 1000 / ((H + hh - 1) / hh * hh) * (tiles * S) / (rounds * 256);
+    if (fill > best_fill) { best_fill = fill; best_hh = hh; best_s = S; }
+  }
+  *hh_out = best_hh;
+  *s_out = best_s;
 }
 
 size_t hash_int_workspace_bytes(int B, int H, int d) {
@@ -318,13 +332,22 @@ int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8
   double* part = reinterpret_cast<double*>(static_cast<char*>(scratch) + x5_bytes + ex_bytes);
   int rc = launch_slice5(X, ldx, B, d, X5, ex, s);
   if (rc) return rc;
-  const int S = hash_int_splits(B, H, d);
-  constexpr size_t lds = (size_t)2 * (HQ + HH) * HROW * 16;
-  static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
-  SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(hash_int_tiles_kernel, dim3((H + HH - 1) / HH, (B + HQ - 1) / HQ, S), dim3(512), lds, s, X5, W5,
-                     part, B, H, d);
+  int hh = 64, S = 1;
+  hash_int_plan(B, H, d, &hh, &S);
+  if (hh == 64) {
+    constexpr size_t lds = (size_t)2 * (HQ + 64) * HROW * 16;
+    static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel<64, 4, 2>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((hash_int_tiles_kernel<64, 4, 2>), dim3((H + 63) / 64, (B + HQ - 1) / HQ, S), dim3(512), lds, s,
+                       X5, W5, part, B, H, d);
+  } else {
+    constexpr size_t lds = (size_t)2 * (HQ + 48) * HROW * 16;
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel<48, 8, 1>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((hash_int_tiles_kernel<48, 8, 1>), dim3((H + 47) / 48, (B + HQ - 1) / HQ, S), dim3(512), lds, s,
+                       X5, W5, part, B, H, d);
+  }
   SLONN_HIP(hipGetLastError());
   hipLaunchKernelGGL(hash_int_finish_kernel, dim3((unsigned)(((size_t)B * H + 255) / 256)), dim3(256), 0, s, part, S,
                      ex, ew, X, ldx, Wh, bh, Z, B, H, d, margin);
