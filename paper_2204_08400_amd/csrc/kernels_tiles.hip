@@ -36,7 +36,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte piece
 constexpr int TM = 128;           // queries per decision unit
 constexpr int TN = 128;           // nodes per tile
 constexpr int PIECES = 12;        // 16-byte pieces per row and chunk: 4 groups of 8 elements x 3 parts
-constexpr int ROW16 = PIECES + 1; // LDS row in 16-byte units (padded: 208 bytes staggers the banks)
 
 __global__ void split3_kernel(const float* __restrict__ X, int64_t ldx, int d, uint16_t* __restrict__ out) {
   const int64_t row = blockIdx.x;

@@ -628,6 +628,7 @@ def test_integer_hash_projection_matches_oracle(rt, oracle, w_dtype):
     X[6] *= 1e-20                         # tiny inputs
     X[7] *= 1e15                          # huge inputs
     X[8, 1:] = 0.0                        # a single non-zero
+    X[9] *= 1e-38                         # subnormal inputs
     keep = wl.keep_uniform(B, 0.02, 0.5, 3)
     _say("integer hash: oracle")
     ref = net.sparse_forward(X, keep)
