@@ -234,7 +234,14 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
 /* Whole network with node dropout: for each layer, select (if activated) then evaluate
  * only the active rows; the sparse output feeds the next layer.  keep: device,
  * query q / layer l uses keep[q*keep_qstride + l*keep_lstride] (0 strides broadcast;
- * the paper uses one k per query for all layers: keep_lstride = 0).                 */
+ * the paper uses one k per query for all layers: keep_lstride = 0).
+ * Numerics: hash codes and active sets do not depend on the batch size or the path (the
+ * projections are summed in fp64, or for batches from 512 as exact integer sums of fixed-
+ * point digits with every sign certified; only a projection within about 1e-13 of zero can
+ * fall either way).  A selected node's output is act(w . x + b) in fp32-class arithmetic:
+ * fp32 FMA chains, or - large batches of large layers - exact partial products of bf16 parts
+ * of the operands accumulated in fp32 on the matrix cores; the summation order differs
+ * between paths and batch sizes, results agree to fp32 rounding.                     */
 int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
                          const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
                          const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
