@@ -387,7 +387,10 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
   const size_t lds = ((size_t)d + 8) * sizeof(float);
   if (lds > 65536) SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
-  if (vec && B <= 16 && (size_t)d * esz >= 1024) {        // few queries, long rows: one wavefront per row
+  // few queries, or few rows each (a skinny layer computed in full): the 64-row chunks of the
+  // general kernel would leave most of the chip idle; long rows: one wavefront per row
+  const long coarse_wgs = (long)B * ((max_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
+  if (vec && (B <= 16 || coarse_wgs < 1024) && (size_t)d * esz >= 1024) {
     int chunks = (max_rows + ROWS_PER_WAVE_BLOCK - 1) / ROWS_PER_WAVE_BLOCK;
     chunks = std::min(chunks, std::max(4, 4096 / B));
     dim3 grid(B, chunks);
