@@ -287,7 +287,9 @@ __global__ __launch_bounds__(256) void hash_int_finish_kernel(const double* __re
 
 }  // namespace
 
-bool hash_int_supported(int d) { return d % 64 == 0 && d <= 16384; }
+bool hash_int_supported(int d, int max_lds) {
+  return d % 64 == 0 && d <= 16384 && (size_t)2 * (HQ + 64) * HROW * 16 <= (size_t)max_lds;
+}
 
 // Tile height (64 or 48 hash rows) and slices of the reduction dimension: the pair that fills one
 // round of workgroups best (one workgroup per compute unit: the two tile buffers take most of

@@ -277,7 +277,7 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
       return fail(SLONN_EHIP);
     }
     // the hash rows once more as fixed-point digits for the int8 matrix cores (large batches)
-    if (hash_int_supported(L.d_in)) {
+    if (hash_int_supported(L.d_in, m->max_lds_bytes)) {
       if (hipMalloc(&L.Wh5, (size_t)H * 5 * L.d_in) != hipSuccess ||
           hipMalloc(&L.ewh, (size_t)H * 4) != hipSuccess) {
         (void)hipGetLastError();

@@ -210,8 +210,8 @@ int hash_split_factor(int B, int H, int d);
 // The same projections for a large batch on the int8 matrix cores: fixed-point digits, exact
 // integer dot products, every sign certified against a rigorous error bound, the uncertain
 // projections recomputed in fp64.  W5, ew: the hash rows through launch_slice5 (model set-up).
-// d a multiple of 64 (hash_int_supported).  scratch: hash_int_workspace_bytes(B, H, d) bytes.
-bool hash_int_supported(int d);
+// d a multiple of 64 and two tile buffers within the LDS the device grants (hash_int_supported).  scratch: hash_int_workspace_bytes(B, H, d) bytes.
+bool hash_int_supported(int d, int max_lds);
 size_t hash_int_workspace_bytes(int B, int H, int d);
 int launch_slice5(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s);
 int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8_t* W5, const int32_t* ew,
