@@ -3,10 +3,11 @@
 // continuing down the whole-set ranking when the lists run out.  Shared by the
 // whole-network kernel and the stand-alone select kernel.
 //
-// Slots are numbered s = rank * L + table.  Every thread takes up to MU slots per round;
-// an LDS integer min over slot numbers finds each node's first occurrence (the result
+// Slots are numbered s = rank * L + table.  Every thread takes up to MU consecutive slots per
+// round; an LDS integer min over slot numbers finds each node's first occurrence (the result
 // does not depend on the order the threads arrive in), survivors are compacted in slot
-// order with a ballot and a two-level prefix sum -- no atomic counters.
+// order: one count per thread, a prefix over the lanes from one ballot per bit of the count,
+// a prefix over the wavefronts from their totals in LDS -- no atomic counters.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -22,7 +23,7 @@ struct SelectShared {            // LDS regions the caller carves out
   uint32_t* prio;                // [n]  first-occurrence map, 0xFFFFFFFF = node not seen
   uint32_t* s_off;               // [64] list offsets of this query
   uint32_t* s_len;               // [64] list lengths
-  int* wave_cnt;                 // [MU * NT/64]
+  int* wave_cnt;                 // [MU * NT/64], the first NT/64 in use
   uint32_t* s_misc;              // [4]
   static constexpr int words_besides_prio = 64 + 64 + MU * (NT / 64) + 4;
 };
@@ -68,30 +69,32 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
   // A round covers per*NT slots with all their id loads in flight together.  Lists of
   // similar buckets overlap heavily, so a round is sized to about twelve slots per wanted
   // node: most queries then finish in one round, i.e. one table-memory latency.
+  // A thread takes `per` consecutive slots (consecutive tables of one rank), so that positions
+  // in slot order follow from one count per thread, and the lanes of a wavefront that read
+  // the same table read consecutive ranks of it.
   const uint32_t L = (uint32_t)L_;
   const uint32_t nslots = sh.s_misc[0] * L;            // <= n * 64 < 2^32
   int per = (12 * m + NT - 1) / NT;
   per = per < 1 ? 1 : (per > MU ? MU : per);
   int count = 0;
-  // slot / L without a division per slot: the round's first slot is divided once, the offset
+  // slot / L without a division per thread: the round's first slot is divided once, the offset
   // inside the round (below 16384) by multiplication with ceil(2^20 / L)
   static_assert(MU * NT + 64 <= 16384, "round too large for the multiplicative division");
-  static_assert(MU * NW <= 64, "one wavefront scans the wave counts of a round");
+  static_assert(MU <= 32, "a thread's first occurrences are kept in a 32-bit mask");
   const uint32_t magic = ((1u << 20) + L - 1) / L;
   for (uint32_t base = 0; base < nslots && count < m; base += NT * per) {
     const uint32_t r_base = base / L, rem_base = base - r_base * L;
+    const uint32_t slot0 = base + tid * per;
+    const uint32_t off = rem_base + tid * per;
+    const uint32_t dr = (uint32_t)(((unsigned long long)off * magic) >> 20);
+    uint32_t r = r_base + dr, b = off - dr * L;
     int node[MU];
-    uint32_t slot[MU];
     bool valid[MU];
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
-      slot[u] = base + u * NT + tid;
-      const uint32_t off = rem_base + u * NT + tid;
-      const uint32_t dr = (uint32_t)(((unsigned long long)off * magic) >> 20);
-      const uint32_t r = r_base + dr;
-      const uint32_t b = off - dr * L;
-      valid[u] = u < per && slot[u] < nslots && r < sh.s_len[b];
+      valid[u] = u < per && slot0 + u < nslots && r < sh.s_len[b];
       node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
+      if (++b == L) { b = 0; ++r; }
     }
     if (hskip) {
 #pragma unroll
@@ -100,60 +103,43 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
     }
 #pragma unroll
     for (int u = 0; u < MU; ++u)
-      if (valid[u]) atomicMin(&sh.prio[node[u]], slot[u]);
+      if (valid[u]) atomicMin(&sh.prio[node[u]], slot0 + u);
     __syncthreads();
-    bool first[MU];
-    unsigned long long votes[MU];
+    uint32_t firsts = 0;
+#pragma unroll
+    for (int u = 0; u < MU; ++u)
+      if (valid[u] && sh.prio[node[u]] == slot0 + u) firsts |= 1u << u;
+    // first occurrences in the lanes below this one and in the wavefront, from one ballot per
+    // bit of the thread's count
+    const int mine = __popc(firsts);
+    int before = 0, in_wave = 0;
+#pragma unroll
+    for (int bit = 0; (1 << bit) <= MU; ++bit) {
+      const unsigned long long has = __ballot((mine >> bit) & 1);
+      before += __popcll(has & below) << bit;
+      in_wave += __popcll(has) << bit;
+    }
+    if (lane == 0) sh.wave_cnt[wave] = in_wave;
+    __syncthreads();
+    // (the next write of wave_cnt comes after the next round's first barrier: no barrier here)
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const int c = sh.wave_cnt[w];
+      before += (w < wave) ? c : 0;
+      total += c;
+    }
+    int pos = count + before;
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
-      first[u] = valid[u] && sh.prio[node[u]] == slot[u];
-      votes[u] = __ballot(first[u]);
-      if (lane == 0) sh.wave_cnt[u * NW + wave] = __popcll(votes[u]);
-    }
-    __syncthreads();
-    if (NW > 4) {
-      // many wavefronts: an exclusive prefix over the MU * NW wave counts in (u, wave) order
-      // (= slot order) by the first wavefront, so that every thread needs one LDS read per slot
-      // instead of NW; with four wavefronts the extra barrier costs more than it saves
-      if (wave == 0) {
-        const int c = lane < MU * NW ? sh.wave_cnt[lane] : 0;
-        int incl = c;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const int up = __shfl_up(incl, o);
-          if (lane >= o) incl += up;
-        }
-        if (lane < MU * NW) sh.wave_cnt[lane] = incl - c;
-        if (lane == 63) sh.s_misc[1] = (uint32_t)incl;     // survivors of the round
-      }
-      __syncthreads();
-#pragma unroll
-      for (int u = 0; u < MU; ++u) {
-        if (first[u]) {
-          const int pos = count + sh.wave_cnt[u * NW + wave] + __popcll(votes[u] & below);
-          if (pos < m) out[pos] = node[u];
-        }
-      }
-      count += (int)sh.s_misc[1];
-    } else {
-#pragma unroll
-      for (int u = 0; u < MU; ++u) {
-        int before = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-          const int c = sh.wave_cnt[u * NW + w];
-          before += (w < wave) ? c : 0;
-          total += c;
-        }
-        if (first[u]) {
-          const int pos = count + before + __popcll(votes[u] & below);
-          if (pos < m) out[pos] = node[u];
-        }
-        count += total;
+      if ((firsts >> u) & 1u) {
+        if (pos < m) out[pos] = node[u];
+        ++pos;
       }
     }
-    __syncthreads();
+    count += total;
   }
+  __syncthreads();        // the last round's counts have been read
   // the lists ran out: continue down the whole-set ranking (a permutation: no duplicates)
   for (int base = 0; base < n && count < m; base += NT) {
     const int i = base + tid;
