@@ -5,31 +5,35 @@
 // The fp64 matrix cores give that (hash_project_mfma_kernel) at 78 TFLOP/s; the int8 cores run
 // at 5 POP/s, and integer dot products are exact.  Every row (a hash row of the layer, a query's
 // activations) is written as a fixed-point number per element relative to a power of two above
-// the row's largest magnitude, |v| < 2^e:  V = trunc(v * 2^(35 - e)), a signed 36-bit integer,
-// cut into five signed 7-bit digits V = sum_s V_s 128^s.  Then
+// the row's largest magnitude, |v| < 2^e:  V = trunc(v * 2^(28 - e)), a signed 29-bit integer,
+// cut into four signed 7-bit digits V = sum_s V_s 128^s.  Then
 //     sum_k W[k] X[k] = sum_{s,t} 128^(s+t) sum_k W_s[k] X_t[k],
-// every inner sum an exact int32 (|.| <= d * 127^2, five of them per accumulator: d <= 26 000).
-// The digit pairs with s + t >= 3 are kept (19 of 25).  What is lost is bounded rigorously:
-// truncation of the operands by d * 2^(e_w + e_x - 34), the dropped pairs by
-// d * 2^(e_w + e_x - 39), together below BOUND = d * 2^(e_w + e_x - 33).  A projection with
-// |z| > margin * BOUND has a certain sign; the few others (and rows with non-finite entries) are
-// recomputed in fp64 like the fp64 kernel does.  The value itself is off by at most BOUND, and
-// typically by about BOUND / sqrt(d) (truncation errors of either sign): the size of the
-// rounding error of an fp32 evaluation of the same dot product (2^-24 of the partial sums), which
-// is the accuracy of every other node's output (Section 3.4 lets a selected hash node take its
-// output from its projection).
+// every inner sum an exact int32 (|.| <= d * 127^2, at most four of them per accumulator:
+// d <= 33 000).  The digit pairs with s + t >= 3 are kept (10 of 16).  What is lost is bounded
+// rigorously, per element of the dot product and in units of 2^(e_w + e_x):
+//   truncation of the operands   |w x - w' x'| < 2^-27 (1 + 2^-29)
+//   the six dropped pairs        127^2 (1 + 2 * 128 + 3 * 128^2) 2^-56 < 2^-26.43
+// together 1.86e-8 < 2^-25, so the projection is off by less than BOUND = d * 2^(e_w + e_x - 25).
+// A projection with |z| > margin * BOUND has a certain sign; the others (about one in 10^4 on
+// normal data of width 8192) and rows with non-finite entries are recomputed in fp64 like the
+// fp64 kernel does.  The value itself is typically off by a few 10^-8 of its own size (the
+// truncation errors and the dropped low digits have either sign and add up like a random walk):
+// the size of the rounding error of an fp32 evaluation of the same dot product, which is the
+// accuracy of every other node's output (Section 3.4 lets a selected hash node take its output
+// from its projection).  A fifth digit and the pairs down to s + t = 3 of five (19 MFMAs per
+// block instead of 10) tightened BOUND by 2^8 and took twice the time.
 //
-//   slice5_kernel         one workgroup per row: row maximum -> e, five int8 digits per element,
+//   slice_digits_kernel   one workgroup per row: row maximum -> e, four int8 digits per element,
 //                         interleaved per 16 elements (element k, digit s of row i at
-//                         i * 5 d + (k / 16) * 80 + 16 s + k % 16).
+//                         i * 4 d + (k / 16) * 64 + 16 s + k % 16).
 //   hash_int_tiles_kernel 128 queries x 64 hash rows per workgroup and slice of the reduction
-//                         dimension, eight wavefronts (4 x 2) of 2 x 2 blocks, six int32
+//                         dimension, eight wavefronts (4 x 2) of 2 x 2 blocks, four int32
 //                         accumulators per block (one per s + t), v_mfma_i32_16x16x64_i8,
 //                         chunks of 64 elements double-buffered in LDS; writes the partial
 //                         sums as fp64 integers.
-//   hash_int_finish_kernel adds the partial sums, scales, adds the bias, certifies; the lanes
-//                         whose projection is not certain are recomputed by their wavefront in
-//                         fp64, one after the other.
+//   hash_int_finish_kernel adds the partial sums, scales, adds the bias, certifies; the
+//                         projections that are not certain are recomputed in fp64 by their
+//                         workgroup, one after the other.
 #include <algorithm>
 #include <climits>
 
@@ -41,15 +45,17 @@ namespace {
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int DIGITS = 5;          // 7-bit digits per element
-constexpr int FRAC_BITS = 35;      // fixed point: 35 bits below 2^e
-constexpr int CLASSES = 6;         // s + t = 3 .. 8
+constexpr int DIGITS = 4;          // 7-bit digits per element
+constexpr int FRAC_BITS = 7 * DIGITS;   // fixed point: 28 bits below 2^e
+constexpr int MIN_PAIR = 3;        // digit pairs with s + t below it are dropped
+constexpr int CLASSES = 2 * (DIGITS - 1) - MIN_PAIR + 1;   // s + t = 3 .. 6
+constexpr int BOUND_EXP = -25;     // BOUND = d * 2^(e_w + e_x + BOUND_EXP), derived above
 constexpr int HQ = 128;            // queries per tile (hash rows per tile: 64 or 48, see the launcher)
 constexpr int HPIECES = 4 * DIGITS;  // 16-byte pieces per row and chunk of 64 elements
-constexpr int HROW = HPIECES + 1;    // LDS row in pieces (336 bytes: staggers the banks)
+constexpr int HROW = HPIECES + 1;    // LDS row in pieces (272 bytes: staggers the banks)
 constexpr int BAD_ROW = INT_MIN;   // exponent entry of a row with a non-finite element
 
-__global__ __launch_bounds__(256) void slice5_kernel(const float* __restrict__ X, int64_t ldx, int d,
+__global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restrict__ X, int64_t ldx, int d,
                                                     int8_t* __restrict__ out, int32_t* __restrict__ expo) {
   __shared__ float red[4];
   __shared__ int s_e;
@@ -79,7 +85,7 @@ __global__ __launch_bounds__(256) void slice5_kernel(const float* __restrict__ X
   const int e = s_e;
   int8_t* o = out + (size_t)row * DIGITS * d;
   const double scale = e == BAD_ROW ? 0.0 : ldexp(1.0, FRAC_BITS - e);
-  // sixteen elements per thread: five 16-byte stores (d is a multiple of 64)
+  // sixteen elements per thread: one 16-byte store per digit (d is a multiple of 64)
   for (int g16 = tid; g16 < (d >> 4); g16 += 256) {
     uint32_t packed[DIGITS][4];
 #pragma unroll
@@ -89,7 +95,7 @@ __global__ __launch_bounds__(256) void slice5_kernel(const float* __restrict__ X
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const double sv = (double)x[16 * g16 + j] * scale;   // exact: a power of two times an fp32 number
-      const long long V = e == BAD_ROW ? 0 : (long long)sv;   // truncation towards zero, |V| < 2^35
+      const long long V = e == BAD_ROW ? 0 : (long long)sv;   // truncation towards zero, |V| < 2^28
       const unsigned long long a = (unsigned long long)(V < 0 ? -V : V);
 #pragma unroll
       for (int s = 0; s < DIGITS; ++s) {
@@ -113,17 +119,17 @@ __device__ __forceinline__ void lds_only_barrier() {
 
 __device__ __forceinline__ i32x4 as_i32x4(u32x4 v) { return __builtin_bit_cast(i32x4, v); }
 
-// X5, W5: rows in five interleaved digits (see above); d a multiple of 64.  part[z][q][h]
-// receives sum over the workgroup's chunks of sum_c 128^(c - 3) P_c (an integer below 2^66,
-// rounded to fp64: relative 2^-53, far below the bound).
+// Xd, Wd: rows in interleaved digits (see above); d a multiple of 64.  part[z][q][h]
+// receives sum over the workgroup's chunks of sum_c 128^(c - 3) P_c (an integer below 2^52:
+// exact in fp64).
 // Lane layout of v_mfma_i32_16x16x64_i8 (checked on gfx950): lane l feeds row l % 16 of its
 // operand with the sixteen elements 16 (l / 16) .. + 15 of the step; register v of lane l holds
 // D[4 (l / 16) + v][l % 16], rows from the first operand (here: hash rows), columns from the
 // second (queries).
 // HH hash rows per tile, wavefronts as WQ query strips x WH hash-row strips (WQ * WH = 8)
 template <int HH, int WQ, int WH>
-__global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __restrict__ X5,
-                                                            const int8_t* __restrict__ W5,
+__global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __restrict__ Xd,
+                                                            const int8_t* __restrict__ Wd,
                                                             double* __restrict__ part, int B, int H, int d) {
   extern __shared__ u32x4 hash_lds[];       // two buffers of [HQ rows of X | HH rows of W][HROW]
   constexpr int BUF = (HQ + HH) * HROW;
@@ -144,8 +150,8 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
     const bool isx = idx < HQ * HPIECES;
     const int j = isx ? idx : idx - HQ * HPIECES;
     const int row = j / HPIECES, piece = j % HPIECES;
-    const int8_t* base = isx ? X5 + (size_t)min(q0 + row, B - 1) * DIGITS * d
-                             : W5 + (size_t)min(h0 + row, H - 1) * DIGITS * d;
+    const int8_t* base = isx ? Xd + (size_t)min(q0 + row, B - 1) * DIGITS * d
+                             : Wd + (size_t)min(h0 + row, H - 1) * DIGITS * d;
     src[i] = reinterpret_cast<const u32x4*>(base) + piece;
     dst[i] = (isx ? row : HQ + row) * HROW + piece;
   }
@@ -192,13 +198,13 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
       for (int a = 0; a < NBH; ++a) wd[a] = as_i32x4(Ws[(wh * 16 * NBH + a * 16 + r) * HROW + kg * DIGITS + s]);
 #pragma unroll
       for (int t = 0; t < DIGITS; ++t) {
-        if (s + t < 3) continue;
+        if (s + t < MIN_PAIR) continue;
 #pragma unroll
         for (int a = 0; a < NBH; ++a)
 #pragma unroll
           for (int b = 0; b < NBQ; ++b)
-            acc[a][b][s + t - 3] =
-                __builtin_amdgcn_mfma_i32_16x16x64_i8(wd[a], xd[b][t], acc[a][b][s + t - 3], 0, 0, 0);
+            acc[a][b][s + t - MIN_PAIR] =
+                __builtin_amdgcn_mfma_i32_16x16x64_i8(wd[a], xd[b][t], acc[a][b][s + t - MIN_PAIR], 0, 0, 0);
       }
     }
   };
@@ -241,7 +247,10 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
   }
 }
 
-// One lane per (query, hash row).  z = 128^3 * sum of the partial sums * 2^(e_w + e_x - 70) + bias.
+// One lane per (query, hash row).  z = 128^3 * sum of the partial sums * 2^(e_w + e_x - 56) + bias.
+// The projections that are not certain are listed in LDS and recomputed in fp64 by the whole
+// workgroup, one after the other: every thread takes up to four 16-byte pieces of both rows at
+// once (rows of a multiple of 64 elements), so a row of 4096 elements is one round trip to L2.
 __global__ __launch_bounds__(256) void hash_int_finish_kernel(const double* __restrict__ part, int S,
                                                              const int32_t* __restrict__ ex,
                                                              const int32_t* __restrict__ ew,
@@ -249,43 +258,87 @@ __global__ __launch_bounds__(256) void hash_int_finish_kernel(const double* __re
                                                              const float* __restrict__ Wh,
                                                              const float* __restrict__ bh, float* __restrict__ Z,
                                                              int B, int H, int d, double margin) {
+  __shared__ int s_n;
+  __shared__ int s_list[256];
+  __shared__ double s_part[4];
   const size_t total = (size_t)B * H;
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const int lane = threadIdx.x & 63;
-  bool redo = false;
-  int q = 0, h = 0;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const size_t i0 = (size_t)blockIdx.x * 256;
+  const size_t i = i0 + tid;
+  if (tid == 0) s_n = 0;
+  __syncthreads();
   if (i < total) {
-    q = (int)(i / H);
-    h = (int)(i % H);
+    const int q = (int)(i / H), h = (int)(i % H);
     const int eq = ex[q], eh = ew[h];
-    if (eq == BAD_ROW || eh == BAD_ROW) {
-      redo = true;
-    } else {
+    bool redo = true;
+    if (eq != BAD_ROW && eh != BAD_ROW) {
       double sum = 0.0;
       for (int z = 0; z < S; ++z) sum += part[(size_t)z * total + i];
-      const double dot = ldexp(sum, 21 + eq + eh - 2 * FRAC_BITS);
+      const double dot = ldexp(sum, 7 * MIN_PAIR + eq + eh - 2 * FRAC_BITS);
       const double zz = dot + (double)bh[h];
-      const double bound = ldexp((double)d, eq + eh - 33);
-      if (fabs(zz) > margin * bound) Z[i] = (float)zz;
-      else redo = true;
+      const double bound = ldexp((double)d, eq + eh + BOUND_EXP);
+      if (fabs(zz) > margin * bound) {
+        Z[i] = (float)zz;
+        redo = false;
+      }
     }
+    if (redo) s_list[atomicAdd(&s_n, 1)] = tid;
   }
-  // the uncertain ones: the whole wavefront recomputes them in fp64, one after the other
-  unsigned long long todo = __ballot(redo);
-  while (todo) {
-    const int src = __ffsll((long long)todo) - 1;
-    todo &= todo - 1;
-    const int qq = __shfl(q, src), hh = __shfl(h, src);
+  __syncthreads();
+  const int n_redo = s_n;
+  for (int t = 0; t < n_redo; ++t) {        // (the order of the list does not enter any result)
+    const size_t ii = i0 + s_list[t];
+    const int qq = (int)(ii / H), hh = (int)(ii % H);
     const float* x = X + (size_t)qq * ldx;
     const float* w = Wh + (size_t)hh * d;
-    double acc = 0.0;
-    for (int k = lane; k < d; k += 64) acc = fma((double)w[k], (double)x[k], acc);
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    if (lane == src) Z[i] = (float)(acc + (double)bh[hh]);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    if (((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w)) & 15) == 0) {
+      const float4* x4 = reinterpret_cast<const float4*>(x);
+      const float4* w4 = reinterpret_cast<const float4*>(w);
+      const int n4 = d >> 2;
+      for (int k0 = 0; k0 < n4; k0 += 1024) {
+        float4 wv[4], xv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int k = k0 + 256 * j + tid;
+          const bool in = k < n4;
+          wv[j] = in ? w4[k] : make_float4(0.f, 0.f, 0.f, 0.f);
+          xv[j] = in ? x4[k] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          acc[j] = fma((double)wv[j].x, (double)xv[j].x, acc[j]);
+          acc[j] = fma((double)wv[j].y, (double)xv[j].y, acc[j]);
+          acc[j] = fma((double)wv[j].z, (double)xv[j].z, acc[j]);
+          acc[j] = fma((double)wv[j].w, (double)xv[j].w, acc[j]);
+        }
+      }
+    } else {
+      for (int k0 = 0; k0 < d; k0 += 2048) {
+        float wv[8], xv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int k = k0 + 256 * j + tid;
+          const bool in = k < d;
+          wv[j] = in ? w[k] : 0.f;
+          xv[j] = in ? x[k] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j & 3] = fma((double)wv[j], (double)xv[j], acc[j & 3]);
+      }
+    }
+    double sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) s_part[wave] = sum;
+    __syncthreads();
+    if (tid == s_list[t]) Z[ii] = (float)(((s_part[0] + s_part[1]) + (s_part[2] + s_part[3])) + (double)bh[hh]);
+    __syncthreads();
   }
 }
 
 }  // namespace
+
+int hash_int_digits() { return DIGITS; }
 
 bool hash_int_supported(int d, int max_lds) {
   return d % 64 == 0 && d <= 16384 && (size_t)2 * (HQ + 64) * HROW * 16 <= (size_t)max_lds;
@@ -317,22 +370,22 @@ size_t hash_int_workspace_bytes(int B, int H, int d) {
   return x5 + ex + (size_t)8 * B * H * sizeof(double) + 256;
 }
 
-int launch_slice5(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s) {
-  hipLaunchKernelGGL(slice5_kernel, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo);
+int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s) {
+  hipLaunchKernelGGL(slice_digits_kernel, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }
 
-int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8_t* W5, const int32_t* ew,
+int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8_t* Wd, const int32_t* ew,
                             const float* bh, float* Z, int B, int H, int d, double margin, void* scratch,
                             hipStream_t s) {
   ProfScope prof_(SLONN_PROF_HASH, s);
   const size_t x5_bytes = ((size_t)B * DIGITS * d + 255) / 256 * 256;
   const size_t ex_bytes = ((size_t)B * 4 + 255) / 256 * 256;
-  int8_t* X5 = static_cast<int8_t*>(scratch);
+  int8_t* Xd = static_cast<int8_t*>(scratch);
   int32_t* ex = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + x5_bytes);
   double* part = reinterpret_cast<double*>(static_cast<char*>(scratch) + x5_bytes + ex_bytes);
-  int rc = launch_slice5(X, ldx, B, d, X5, ex, s);
+  int rc = launch_slice_digits(X, ldx, B, d, Xd, ex, s);
   if (rc) return rc;
   int hh = 64, S = 1;
   hash_int_plan(B, H, d, &hh, &S);
@@ -342,13 +395,13 @@ int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel<64, 4, 2>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((hash_int_tiles_kernel<64, 4, 2>), dim3((H + 63) / 64, (B + HQ - 1) / HQ, S), dim3(512), lds, s,
-                       X5, W5, part, B, H, d);
+                       Xd, Wd, part, B, H, d);
   } else {
     constexpr size_t lds = (size_t)2 * (HQ + 48) * HROW * 16;
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel<48, 8, 1>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((hash_int_tiles_kernel<48, 8, 1>), dim3((H + 47) / 48, (B + HQ - 1) / HQ, S), dim3(512), lds, s,
-                       X5, W5, part, B, H, d);
+                       Xd, Wd, part, B, H, d);
   }
   SLONN_HIP(hipGetLastError());
   hipLaunchKernelGGL(hash_int_finish_kernel, dim3((unsigned)(((size_t)B * H + 255) / 256)), dim3(256), 0, s, part, S,

@@ -103,7 +103,7 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   size_t hint = 0;
   if (B >= HASH_INT_MIN_BATCH)
     for (const Layer& l : m->layers)
-      if (l.Wh5) hint = std::max(hint, hash_int_workspace_bytes(B, l.H(), l.d_in));
+      if (l.Whd) hint = std::max(hint, hash_int_workspace_bytes(B, l.H(), l.d_in));
   w->hash_int = hint ? take(hint) : nullptr;
   w->bytes = off;
 }
@@ -278,12 +278,12 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
     }
     // the hash rows once more as fixed-point digits for the int8 matrix cores (large batches)
     if (hash_int_supported(L.d_in, m->max_lds_bytes)) {
-      if (hipMalloc(&L.Wh5, (size_t)H * 5 * L.d_in) != hipSuccess ||
+      if (hipMalloc(&L.Whd, (size_t)H * hash_int_digits() * L.d_in) != hipSuccess ||
           hipMalloc(&L.ewh, (size_t)H * 4) != hipSuccess) {
         (void)hipGetLastError();
-        if (L.Wh5) (void)hipFree(L.Wh5);
-        L.Wh5 = nullptr;
-      } else if (launch_slice5(L.Wh, L.d_in, H, L.d_in, L.Wh5, L.ewh, nullptr) != SLONN_OK ||
+        if (L.Whd) (void)hipFree(L.Whd);
+        L.Whd = nullptr;
+      } else if (launch_slice_digits(L.Wh, L.d_in, H, L.d_in, L.Whd, L.ewh, nullptr) != SLONN_OK ||
                  (e = hipStreamSynchronize(nullptr)) != hipSuccess) {
         if (e != hipSuccess) set_error("slicing the FreeHash rows failed: %s", hipGetErrorString(e));
         return fail(SLONN_EHIP);
@@ -404,7 +404,7 @@ int slonn_model_destroy(slonn_model* m) {
     if (L.hslot) (void)hipFree(L.hslot);
     if (L.hnodes) (void)hipFree(L.hnodes);
     if (L.W3) (void)hipFree(L.W3);
-    if (L.Wh5) (void)hipFree(L.Wh5);
+    if (L.Whd) (void)hipFree(L.Whd);
     if (L.ewh) (void)hipFree(L.ewh);
   }
   delete m;
@@ -765,8 +765,8 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       // unless the policy kernel needs the projections first)
       HashSplit split;
       const bool policy_here = hook && l == hook->layer;
-      if (L.Wh5 && w.hash_int && B >= HASH_INT_MIN_BATCH)
-        rc = launch_hash_project_int(cur, ldcur, L.Wh, L.Wh5, L.ewh, L.bh, z, B, L.H(), L.d_in, m->hash_margin,
+      if (L.Whd && w.hash_int && B >= HASH_INT_MIN_BATCH)
+        rc = launch_hash_project_int(cur, ldcur, L.Wh, L.Whd, L.ewh, L.bh, z, B, L.H(), L.d_in, m->hash_margin,
                                      w.hash_int, s);
       else
         rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, w.hash_split,

@@ -42,7 +42,7 @@ struct Layer {
   int16_t* hslot = nullptr;      // [d_out] device: index of the node among the hash rows, or -1
   int32_t* hnodes = nullptr;     // [H] device copy of hash_nodes
   uint16_t* W3 = nullptr;        // large fp32 layers: the weights as three interleaved bf16 parts [d_out][3 d_in]
-  int8_t* Wh5 = nullptr;         // the FreeHash rows as five interleaved 7-bit digits [H][5 d_in] (int8 cores)
+  int8_t* Whd = nullptr;         // the FreeHash rows as interleaved 7-bit digits [H][hash_int_digits() * d_in] (int8 cores)
   int32_t* ewh = nullptr;        // [H] their fixed-point exponents
   int H() const { return K * L; }
   bool activated() const { return K > 0 && L > 0; }
@@ -209,12 +209,14 @@ int hash_split_factor(int B, int H, int d);
 
 // The same projections for a large batch on the int8 matrix cores: fixed-point digits, exact
 // integer dot products, every sign certified against a rigorous error bound, the uncertain
-// projections recomputed in fp64.  W5, ew: the hash rows through launch_slice5 (model set-up).
+// projections recomputed in fp64.  Wd, ew: the hash rows through launch_slice_digits (model set-up),
+// hash_int_digits() bytes per element.
 // d a multiple of 64 and two tile buffers within the LDS the device grants (hash_int_supported).  scratch: hash_int_workspace_bytes(B, H, d) bytes.
 bool hash_int_supported(int d, int max_lds);
+int hash_int_digits();
 size_t hash_int_workspace_bytes(int B, int H, int d);
-int launch_slice5(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s);
-int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8_t* W5, const int32_t* ew,
+int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s);
+int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8_t* Wd, const int32_t* ew,
                             const float* bh, float* Z, int B, int H, int d, double margin, void* scratch,
                             hipStream_t s);
 
