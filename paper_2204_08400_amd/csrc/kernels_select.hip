@@ -8,6 +8,8 @@
 // wide for that (a 100 000-node output layer would need 400 KB), keeps one bit per node
 // plus a small per-round table.  Both can also regroup the finished list by weight-row
 // block for the row-block gather.
+#include <algorithm>
+
 #include "select_block.h"
 #include "slonn_internal.h"
 
@@ -100,7 +102,8 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
     const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
-    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf, HashSplit hsp) {
+    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf, HashSplit hsp,
+    const int32_t* __restrict__ order) {
   extern __shared__ __align__(16) uint32_t smem32[];
   constexpr int MU = BlockMU<NT>::value;
   SelectShared<NT, MU> sh;
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
   sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
   sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + MU * (NT / 64));
 
-  const int q = blockIdx.x, tid = threadIdx.x;
+  const int q = order ? order[blockIdx.x] : (int)blockIdx.x, tid = threadIdx.x;
   const int m = budget_of(keep[(size_t)q * keep_stride], n);
   int32_t* out = active + (size_t)q * idx_stride;
   const float* z = Z + (size_t)q * K * L;
@@ -146,7 +149,8 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
     const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
-    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf, HashSplit hsp) {
+    float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf, HashSplit hsp,
+    const int32_t* __restrict__ order) {
   extern __shared__ __align__(16) uint32_t smem32[];
   const int words = (n + 31) >> 5;
   SelectSharedWide<SEL_NT> sh;
@@ -158,7 +162,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
   sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * (SEL_NT / 64));
 
-  const int q = blockIdx.x, tid = threadIdx.x;
+  const int q = order ? order[blockIdx.x] : (int)blockIdx.x, tid = threadIdx.x;
   const int m = budget_of(keep[(size_t)q * keep_stride], n);
   int32_t* out = active + (size_t)q * idx_stride;
   const float* z = Z + (size_t)q * K * L;
@@ -189,6 +193,38 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   if (rb.part_idx) partition_rows(out, total, rb, q, z, sh.tval);
 }
 
+// Queries in descending order of their budget (256 classes of the keep fraction; the order inside
+// a class is whatever the atomics give: it only decides which workgroup starts first).
+__global__ __launch_bounds__(1024) void order_by_budget_kernel(const float* __restrict__ keep, int keep_stride,
+                                                              int B, int32_t* __restrict__ order) {
+  __shared__ uint32_t hist[256];
+  const int tid = threadIdx.x;
+  auto klass = [&](int q) {
+    float k = keep[(size_t)q * keep_stride];
+    k = k > 0.0f ? (k < 1.0f ? k : 1.0f) : 0.0f;        // also a keep fraction that is not a number
+    return 255 - (int)(k * 255.0f);
+  };
+  if (tid < 256) hist[tid] = 0;
+  __syncthreads();
+  for (int q = tid; q < B; q += 1024) atomicAdd(&hist[klass(q)], 1u);
+  __syncthreads();
+  if (tid < 64) {         // exclusive prefix over the classes: four per lane
+    uint32_t c[4], sum = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { c[j] = hist[4 * tid + j]; sum += c[j]; }
+    uint32_t incl = sum;
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t up = __shfl_up(incl, o);
+      if (tid >= o) incl += up;
+    }
+    uint32_t run = incl - sum;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { hist[4 * tid + j] = run; run += c[j]; }
+  }
+  __syncthreads();
+  for (int q = tid; q < B; q += 1024) order[atomicAdd(&hist[klass(q)], 1u)] = q;
+}
+
 __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t* __restrict__ cnt,
                                  int n, int B) {
   const int q = blockIdx.y;
@@ -204,7 +240,7 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
                   int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first,
-                  const HashSplit* split, hipStream_t s) {
+                  const HashSplit* split, const int32_t* order, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_SELECT, s);
   const HashFirst hf = hash_first ? *hash_first : HashFirst{};
   const HashSplit hsp = split ? *split : HashSplit{};
@@ -216,13 +252,13 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
       hipLaunchKernelGGL((select_block_kernel<SEL_NT_BIG>), dim3(B), dim3(SEL_NT_BIG), lds_block, s, Z, K, L, n,
-                         dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp);
+                         dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp, order);
     } else {
       if (lds_block > 65536)
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
       hipLaunchKernelGGL((select_block_kernel<SEL_NT>), dim3(B), dim3(SEL_NT), lds_block, s, Z, K, L, n, dir,
-                         ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp);
+                         ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp, order);
     }
     SLONN_HIP(hipGetLastError());
     return SLONN_OK;
@@ -235,7 +271,23 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_wide_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(select_wide_kernel, dim3(B), dim3(SEL_NT), lds, s, Z, K, L, n, dir, ids, global_rank,
-                     keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rb ? *rb : RowBlocking{}, hf, hsp);
+                     keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rb ? *rb : RowBlocking{}, hf, hsp, order);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+// More queries than workgroups of the select kernel fit on the device at once: the queries with
+// the largest budgets (the longest merges) should start first.
+bool select_wants_order(int n, int B, int max_lds, int n_cu) {
+  const size_t lds_block = ((size_t)n + SelectShared<SEL_NT, BlockMU<SEL_NT>::value>::words_besides_prio) * 4;
+  if (lds_block > (size_t)max_lds || B <= 64) return false;
+  const size_t per_cu = std::min<size_t>(8, std::max<size_t>(1, ((size_t)160 << 10) / lds_block));
+  return (size_t)B > per_cu * (size_t)n_cu;
+}
+
+int launch_order_by_budget(const float* keep, int keep_stride, int B, int32_t* order, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_SELECT, s);
+  hipLaunchKernelGGL(order_by_budget_kernel, dim3(1), dim3(1024), 0, s, keep, keep_stride, B, order);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

@@ -51,6 +51,7 @@ struct Workspace {
   float* z = nullptr;                   // [B][max_H]
   int32_t* active = nullptr;            // [B][max_n_activated]
   int32_t* cnt = nullptr;               // [B]
+  int32_t* order = nullptr;             // [B] queries by descending budget
   int32_t* part_idx = nullptr;          // [B][max_n_activated] lists regrouped by row block
   int32_t* part_pos = nullptr;          // [B][max_n_activated]
   int32_t* blk_off = nullptr;           // [B][MAX_ROW_BLOCKS + 1]
@@ -85,6 +86,7 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   w->z = reinterpret_cast<float*>(take((size_t)B * std::max(max_H, 1) * 4));
   w->active = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->cnt = reinterpret_cast<int32_t*>(take((size_t)B * 4));
+  w->order = reinterpret_cast<int32_t*>(take((size_t)B * 4));
   w->part_idx = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->part_pos = reinterpret_cast<int32_t*>(take((size_t)B * std::max(max_na, 1) * 4));
   w->blk_off = reinterpret_cast<int32_t*>(take((size_t)B * (MAX_ROW_BLOCKS + 1) * 4));
@@ -581,7 +583,7 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
   if (m->hash_first) { hf.hnodes = L.hnodes; hf.hslot = L.hslot; }
   return launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank, keep, keep_stride,
                        B, codes_out, active_idx, active_cnt, idx_stride, nullptr, 0, m->max_lds_bytes,
-                       nullptr, m->hash_first ? &hf : nullptr, nullptr, s);
+                       nullptr, m->hash_first ? &hf : nullptr, nullptr, nullptr, s);
 }
 
 namespace slonn {
@@ -735,6 +737,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
 
   const float* cur = X->x;
   int ldcur = m->layers[0].d_in;
+  bool order_ready = false;
   for (int l = 0; l < nl; ++l) {
     const Layer& L = m->layers[l];
     const bool is_last = (l == nl - 1);
@@ -810,10 +813,21 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       }
       HashFirst hf;
       if (m->hash_first) { hf.hnodes = L.hnodes; hf.hslot = L.hslot; }
+      // a batch beyond what the device holds at once starts its longest merges first; with one
+      // keep fraction per query for all layers the order is found once per call
+      const int32_t* order = nullptr;
+      if (select_wants_order(L.d_out, B, m->max_lds_bytes, m->n_cu)) {
+        if (!order_ready || keep_lstride != 0) {
+          rc = launch_order_by_budget(keep + (size_t)l * keep_lstride, keep_qstride, B, w.order, s);
+          if (rc) return rc;
+          order_ready = true;
+        }
+        order = w.order;
+      }
       rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank,
                          keep + (size_t)l * keep_lstride, keep_qstride, B, codes, aidx, acnt, astride, out,
                          ldo, m->max_lds_bytes, rb.part_idx ? &rb : nullptr, m->hash_first ? &hf : nullptr,
-                         split.part ? &split : nullptr, s);
+                         split.part ? &split : nullptr, order, s);
       if (rc) return rc;
       act_list = aidx; act_cnt = acnt; act_stride = astride;
       if (is_last && Y->val) yc = Y->val;

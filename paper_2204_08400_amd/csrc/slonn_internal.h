@@ -225,7 +225,12 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
                   int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first,
-                  const HashSplit* split, hipStream_t s);
+                  const HashSplit* split, const int32_t* order, hipStream_t s);
+// order (nullable): [B] permutation of the queries; workgroup i serves query order[i].
+// launch_order_by_budget fills it with the queries in descending order of their budgets, for
+// batches that do not fit the device at once (select_wants_order).
+bool select_wants_order(int n, int B, int max_lds, int n_cu);
+int launch_order_by_budget(const float* keep, int keep_stride, int B, int32_t* order, hipStream_t s);
 // true when launch_select will fill rb for a layer of n nodes (the workgroup kernel is used)
 bool select_fills_row_blocks(int n, int max_lds);
 

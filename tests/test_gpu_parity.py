@@ -467,6 +467,9 @@ def test_config_c5_full_width_sampled(rt, oracle):
     res = g.sparse_forward(Xq, _keep_tensor(keep), taps=True)
     prof = slonn.slonn_profile_end()
     assert prof["gather"][1] == 2 * len(cfg.hashed_layers), prof     # tiles + unions per hidden layer
+    # per hidden layer the select kernel, the pair masks of the tiles and the unions; 2048 select
+    # workgroups do not fit the device at once: one more launch orders them by budget
+    assert prof["select"][1] == 3 * len(cfg.hashed_layers) + 1, prof
     got = to_numpy_result(res)
     sample = np.asarray([0, 1, 15, 16, 17, 31, 500, 777, 1023, 1024, 1029, 1500, 2032, 2040, 2046, 2047])
     _say("C5 full width: oracle on the sampled queries")
