@@ -55,20 +55,49 @@ constexpr int HPIECES = 4 * DIGITS;  // 16-byte pieces per row and chunk of 64 e
 constexpr int HROW = HPIECES + 1;    // LDS row in pieces (272 bytes: staggers the banks)
 constexpr int BAD_ROW = INT_MIN;   // exponent entry of a row with a non-finite element
 
+// One workgroup per row; a thread holds up to four groups of sixteen consecutive elements in
+// registers (d <= 16384), so the row is read once: maximum, exponent, digits.
 __global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restrict__ X, int64_t ldx, int d,
                                                     int8_t* __restrict__ out, int32_t* __restrict__ expo) {
+  constexpr int MAXG = 4;
   __shared__ float red[4];
   __shared__ int s_e;
   const int64_t row = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* x = X + row * ldx;
+  const bool vec = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);
+  const int ngroups = d >> 4;                  // d is a multiple of 64
+  float xv[MAXG][16];
+#pragma unroll
+  for (int g = 0; g < MAXG; ++g) {
+    const int g16 = tid + 256 * g;
+    if (g16 < ngroups) {
+      const float* xp = x + 16 * g16;
+      if (vec) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float4 v = reinterpret_cast<const float4*>(xp)[j];
+          xv[g][4 * j] = v.x; xv[g][4 * j + 1] = v.y; xv[g][4 * j + 2] = v.z; xv[g][4 * j + 3] = v.w;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) xv[g][j] = xp[j];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) xv[g][j] = 0.0f;
+    }
+  }
   float mx = 0.0f;
   bool bad = false;
-  for (int i = tid; i < d; i += 256) {
-    const float v = fabsf(x[i]);
-    if (!(v <= 3.0e38f)) bad = true;          // infinity or NaN
-    mx = fmaxf(mx, v);
-  }
+#pragma unroll
+  for (int g = 0; g < MAXG; ++g)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float v = fabsf(xv[g][j]);
+      if (!(v <= 3.0e38f)) bad = true;          // infinity or NaN
+      mx = fmaxf(mx, v);
+    }
   if (bad) mx = __int_as_float(0x7f800000);
   for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
   if (lane == 0) red[wave] = mx;
@@ -85,8 +114,11 @@ __global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restri
   const int e = s_e;
   int8_t* o = out + (size_t)row * DIGITS * d;
   const double scale = e == BAD_ROW ? 0.0 : ldexp(1.0, FRAC_BITS - e);
-  // sixteen elements per thread: one 16-byte store per digit (d is a multiple of 64)
-  for (int g16 = tid; g16 < (d >> 4); g16 += 256) {
+  // per group of sixteen elements one 16-byte store per digit
+#pragma unroll
+  for (int g = 0; g < MAXG; ++g) {
+    const int g16 = tid + 256 * g;
+    if (g16 >= ngroups) break;
     uint32_t packed[DIGITS][4];
 #pragma unroll
     for (int s = 0; s < DIGITS; ++s)
@@ -94,9 +126,9 @@ __global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restri
       for (int w = 0; w < 4; ++w) packed[s][w] = 0u;
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
-      const double sv = (double)x[16 * g16 + j] * scale;   // exact: a power of two times an fp32 number
-      const long long V = e == BAD_ROW ? 0 : (long long)sv;   // truncation towards zero, |V| < 2^28
-      const unsigned long long a = (unsigned long long)(V < 0 ? -V : V);
+      const double sv = (double)xv[g][j] * scale;          // exact: a power of two times an fp32 number
+      const int V = e == BAD_ROW ? 0 : (int)sv;            // truncation towards zero, |V| < 2^28
+      const uint32_t a = (uint32_t)(V < 0 ? -V : V);
 #pragma unroll
       for (int s = 0; s < DIGITS; ++s) {
         const int dig = (int)((a >> (7 * s)) & 127u);
@@ -340,7 +372,7 @@ __global__ __launch_bounds__(256) void hash_int_finish_kernel(const double* __re
 
 int hash_int_digits() { return DIGITS; }
 
-bool hash_int_supported(int d, int max_lds) {
+bool hash_int_supported(int d, int max_lds) {      // (d <= 16384: the slicing kernel holds a row in registers)
   return d % 64 == 0 && d <= 16384 && (size_t)2 * (HQ + 64) * HROW * 16 <= (size_t)max_lds;
 }
 

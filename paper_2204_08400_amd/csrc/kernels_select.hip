@@ -118,14 +118,13 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
   int32_t* out = active + (size_t)q * idx_stride;
   const float* z = Z + (size_t)q * K * L;
   sum_split_projections(hsp, q, gridDim.x, K * L);
-  if (yzero) {
-    float* y = yzero + (size_t)q * ldy;
-    for (int i = tid; i < n; i += NT) y[i] = 0.0f;
-  }
+  float* y = yzero ? yzero + (size_t)q * ldy : nullptr;
   const int H = hf.hnodes ? K * L : 0;          // hash nodes in front of the list (Section 3.4 variant)
   const int total = (m == n || m > H) ? m : H;
   if (tid == 0) cnt[q] = total;
   if (m == n) {   // the layer is computed in full: ascending ids, no table access
+    if (y)
+      for (int i = tid; i < n; i += NT) y[i] = 0.0f;
     if (codes && tid < L) {
       uint32_t key = 0;
       for (int j = 0; j < K; ++j) key |= (z[tid * K + j] > 0.0f ? 1u : 0u) << j;
@@ -135,11 +134,21 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
     if (rb.part_idx) partition_rows(out, n, rb, q, z, sh.prio);
     return;
   }
-  for (int i = tid; i < n; i += NT) sh.prio[i] = 0xFFFFFFFFu;
-  for (int h = tid; h < H; h += NT) out[h] = hf.hnodes[h];
+  // The last wavefront forms the keys and fetches the bucket directory (two dependent memory
+  // round trips) while the others clear the output row and the map.
+  uint32_t* codes_row = codes ? codes + (size_t)q * L : nullptr;
+  const int16_t* hskip = H ? hf.hslot : nullptr;
+  constexpr int NI = NT - 64;          // threads that clear
+  if (tid >= NI) {
+    select_keys<NT, MU>(z, K, L, dir, sh, codes_row);
+  } else {
+    if (y)
+      for (int i = tid; i < n; i += NI) y[i] = 0.0f;
+    for (int i = tid; i < n; i += NI) sh.prio[i] = 0xFFFFFFFFu;
+    for (int h = tid; h < H; h += NI) out[h] = hf.hnodes[h];
+  }
   __syncthreads();
-  select_block<NT, MU>(z, K, L, n, total - H, dir, ids, global_rank, sh, codes ? codes + (size_t)q * L : nullptr,
-                       out + H, H ? hf.hslot : nullptr);
+  select_merge<NT, MU>(L, n, total - H, ids, global_rank, sh, out + H, hskip);
 
   if (rb.part_idx) partition_rows(out, total, rb, q, z, sh.prio);
 }

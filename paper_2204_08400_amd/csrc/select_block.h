@@ -28,43 +28,44 @@ struct SelectShared {            // LDS regions the caller carves out
   static constexpr int words_besides_prio = 64 + 64 + MU * (NT / 64) + 4;
 };
 
-// z: the query's K*L hash projections (LDS or global).  prio[0..n) must hold 0xFFFFFFFF
-// and be visible to all threads (caller clears it and synchronises).  On return (all
-// threads, after a barrier) out[0..m) holds the chosen ids in selection order.  0 <= m < n.
+// Keys and bucket directory of one query, by ONE wavefront (one lane per table): fills s_off,
+// s_len and s_misc[0] (the longest list).  z: the query's K*L hash projections (LDS or global).
+template <int NT, int MU = SELECT_MU>
+__device__ __forceinline__ void select_keys(const float* z, int K, int L_, const uint32_t* __restrict__ dir,
+                                            const SelectShared<NT, MU>& sh, uint32_t* codes_row) {
+  const int lane = threadIdx.x & 63;
+  const int nb1 = (1 << K) + 1;
+  uint32_t len = 0;
+  if (lane < L_) {
+    uint32_t key = 0;
+    for (int j = 0; j < K; ++j) key |= (z[lane * K + j] > 0.0f ? 1u : 0u) << j;
+    if (codes_row) codes_row[lane] = key;
+    const uint32_t lo = dir[(size_t)lane * nb1 + key], hi = dir[(size_t)lane * nb1 + key + 1];
+    sh.s_off[lane] = lo;
+    len = hi - lo;
+    sh.s_len[lane] = len;
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint32_t other = __shfl_xor(len, o);
+    len = other > len ? other : len;
+  }
+  if (lane == 0) sh.s_misc[0] = len;
+}
+
+// The merge, by the whole workgroup, after select_keys and a barrier.  prio[0..n) must hold
+// 0xFFFFFFFF and be visible to all threads.  On return (all threads, after a barrier)
+// out[0..m) holds the chosen ids in selection order.  0 <= m < n.
 // hskip (nullable, LDS or global, [n]): nodes with an entry >= 0 are passed over wherever
 // they turn up (the variant of Section 3.4 in which hash nodes are computed anyway and the
 // Node Activator never selects them); the caller keeps m <= n minus their number.
 template <int NT, int MU = SELECT_MU>
-__device__ __forceinline__ void select_block(const float* z, int K, int L_, int n, int m,
-                                             const uint32_t* __restrict__ dir,
-                                             const int32_t* __restrict__ ids,
+__device__ __forceinline__ void select_merge(int L_, int n, int m, const int32_t* __restrict__ ids,
                                              const int32_t* __restrict__ global_rank,
-                                             const SelectShared<NT, MU>& sh, uint32_t* codes_row,
-                                             int32_t* out, const int16_t* hskip = nullptr) {
+                                             const SelectShared<NT, MU>& sh, int32_t* out,
+                                             const int16_t* hskip = nullptr) {
   constexpr int NW = NT / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-
-  // keys and bucket directory: one lane per table
-  if (wave == 0) {
-    const int nb1 = (1 << K) + 1;
-    uint32_t len = 0;
-    if (lane < L_) {
-      uint32_t key = 0;
-      for (int j = 0; j < K; ++j) key |= (z[lane * K + j] > 0.0f ? 1u : 0u) << j;
-      if (codes_row) codes_row[lane] = key;
-      const uint32_t lo = dir[(size_t)lane * nb1 + key], hi = dir[(size_t)lane * nb1 + key + 1];
-      sh.s_off[lane] = lo;
-      len = hi - lo;
-      sh.s_len[lane] = len;
-    }
-    for (int o = 32; o > 0; o >>= 1) {
-      const uint32_t other = __shfl_xor(len, o);
-      len = other > len ? other : len;
-    }
-    if (lane == 0) sh.s_misc[0] = len;
-  }
-  __syncthreads();
 
   // A round covers per*NT slots with all their id loads in flight together.  Lists of
   // similar buckets overlap heavily, so a round is sized to about twelve slots per wanted
@@ -166,6 +167,21 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
     count += total;
     __syncthreads();
   }
+}
+
+// Keys by the first wavefront, then the merge: for callers whose projections are only ready
+// now.  prio[0..n) must hold 0xFFFFFFFF and be visible to all threads (caller clears it and
+// synchronises).
+template <int NT, int MU = SELECT_MU>
+__device__ __forceinline__ void select_block(const float* z, int K, int L_, int n, int m,
+                                             const uint32_t* __restrict__ dir,
+                                             const int32_t* __restrict__ ids,
+                                             const int32_t* __restrict__ global_rank,
+                                             const SelectShared<NT, MU>& sh, uint32_t* codes_row,
+                                             int32_t* out, const int16_t* hskip = nullptr) {
+  if (threadIdx.x < 64) select_keys<NT, MU>(z, K, L_, dir, sh, codes_row);
+  __syncthreads();
+  select_merge<NT, MU>(L_, n, m, ids, global_rank, sh, out, hskip);
 }
 
 // Same query for layers too wide for a 4-byte map entry per node (hundreds of thousands of
