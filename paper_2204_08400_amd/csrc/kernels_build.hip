@@ -485,7 +485,7 @@ extern "C" int slonn_build_tables(const slonn_model* m, const slonn_input* X_bui
                             X_build->ell_stride, act, L.d_out, (int)N, L.d_in, L.d_out, L.act, s);
     else
       rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, L.d_in, act, L.d_out, (int)N, L.d_in, L.d_out,
-                              L.act, s);
+                              L.act, nullptr, s);
     if (rc == SLONN_OK && L.act == SLONN_ACT_SOFTMAX)
       rc = launch_finalize(act, L.d_out, L.d_out, nullptr, nullptr, 0, nullptr, 0, 1, nullptr, (int)N, s);
     if (rc == SLONN_OK && L.activated()) {

@@ -161,16 +161,19 @@ __global__ __launch_bounds__(64 * KS) void dense_direct_kernel(const void* __res
                                                           const float* __restrict__ bias,
                                                           const float* __restrict__ X, int ldx,
                                                           float* __restrict__ Y, int ldy, int M, int N,
-                                                          int Kd, int act) {
+                                                          int Kd, int act, float* __restrict__ split_out) {
   __shared__ float part[KS - 1][64][16];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 31, half = lane >> 5;
   const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
   const float* xr = X + (size_t)min(m0 + r, M - 1) * ldx;          // surplus rows recompute a valid row
   const size_t wrow = (size_t)min(n0 + r, N - 1) * Kd;
+  // blockIdx.z: slice of the reduction dimension (split_out then receives the slice's sums)
   const int steps = (Kd + 7) / 8;
-  const int per = (steps + KS - 1) / KS;
-  const int s_begin = wave * per, s_end = min(steps, s_begin + per);
+  const int per_z = (steps + (int)gridDim.z - 1) / (int)gridDim.z;
+  const int z_begin = min(steps, (int)blockIdx.z * per_z), z_end = min(steps, z_begin + per_z);
+  const int per = (z_end - z_begin + KS - 1) / KS;
+  const int s_begin = min(z_end, z_begin + wave * per), s_end = min(z_end, s_begin + per);
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
@@ -218,11 +221,29 @@ __global__ __launch_bounds__(64 * KS) void dense_direct_kernel(const void* __res
       float z = acc[v];
 #pragma unroll
       for (int w = 0; w < KS - 1; ++w) z += part[w][lane][v];       // fixed order
+      if (split_out) {
+        if (row < M && col < N) split_out[((size_t)blockIdx.z * M + row) * N + col] = z;
+        continue;
+      }
       z += bv;
       if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
       if (row < M && col < N) Y[(size_t)row * ldy + col] = z;
     }
   }
+}
+
+// Y = act(sum of the S slices in slice order + bias): the second half of a split reduction.
+__global__ __launch_bounds__(256) void dense_split_sum_kernel(const float* __restrict__ part, int S,
+                                                             const float* __restrict__ bias, float* __restrict__ Y,
+                                                             int ldy, int M, int N, int act) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, total = (size_t)M * N;
+  if (i >= total) return;
+  const int row = (int)(i / N), col = (int)(i % N);
+  float z = part[i];
+  for (int k = 1; k < S; ++k) z += part[(size_t)k * total + i];
+  z += bias[col];
+  if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+  Y[(size_t)row * ldy + col] = z;
 }
 
 }  // namespace
@@ -233,8 +254,22 @@ bool dense_small_supported(const void* W, int w_dtype, const float* X, int ldx, 
          reinterpret_cast<uintptr_t>(W) % (w_dtype == SLONN_F32 ? 16 : 8) == 0;
 }
 
+// Slices of the reduction dimension for a problem with only a few 32x32 tiles: as many as fill
+// two workgroups per compute unit, each at least 512 elements long.
+static int dense_split_factor(int B, int n, int d) {
+  const long tiles32 = (long)((B + 31) / 32) * ((n + 31) / 32);
+  int S = 1;
+  while (S < 8 && tiles32 * S * 2 <= 512 && d / (S * 2) >= 512) S *= 2;
+  return S;
+}
+
+size_t dense_split_workspace_bytes(int B, int n, int d) {
+  const int S = dense_split_factor(B, n, d);
+  return S > 1 ? (size_t)S * B * n * sizeof(float) : 0;
+}
+
 int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
-                       float* Y, int ldy, int B, int d, int n, int act, hipStream_t s) {
+                       float* Y, int ldy, int B, int d, int n, int act, void* split_scratch, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_DENSE, s);
   if (B <= 0) return SLONN_OK;
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
@@ -244,24 +279,33 @@ int launch_dense_layer(const void* W, int w_dtype, const float* bias, const floa
   const bool big = big_tiles >= 512;
   const long tiles64 = (long)((B + 63) / 64) * ((n + 63) / 64);
   if (tiles64 < 256 && dense_small_supported(W, w_dtype, X, ldx, d)) {
-    dim3 grid((n + 31) / 32, (B + 31) / 32);
-    const bool few = (long)grid.x * grid.y < 512 && d >= 1024;
+    const bool few = (long)((n + 31) / 32) * ((B + 31) / 32) < 512 && d >= 1024;
+    // a handful of tiles (a skinny output layer): the reduction is split over workgroups as well,
+    // a second kernel adds the slices in order
+    const int S = (few && split_scratch) ? dense_split_factor(B, n, d) : 1;
+    float* split_out = S > 1 ? static_cast<float*>(split_scratch) : nullptr;
+    dim3 grid((n + 31) / 32, (B + 31) / 32, S);
     if (w_dtype == SLONN_F32) {
       if (few)
         hipLaunchKernelGGL((dense_direct_kernel<SLONN_F32, 4, 16>), grid, dim3(1024), 0, s, W, bias, X, ldx, Y, ldy,
-                           B, n, d, a);
+                           B, n, d, a, split_out);
       else
         hipLaunchKernelGGL((dense_direct_kernel<SLONN_F32, 4, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
-                           B, n, d, a);
+                           B, n, d, a, split_out);
     } else {
       if (few)
         hipLaunchKernelGGL((dense_direct_kernel<SLONN_BF16, 4, 16>), grid, dim3(1024), 0, s, W, bias, X, ldx, Y, ldy,
-                           B, n, d, a);
+                           B, n, d, a, split_out);
       else
         hipLaunchKernelGGL((dense_direct_kernel<SLONN_BF16, 4, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
-                           B, n, d, a);
+                           B, n, d, a, split_out);
     }
     SLONN_HIP(hipGetLastError());
+    if (S > 1) {
+      hipLaunchKernelGGL(dense_split_sum_kernel, dim3((unsigned)(((size_t)B * n + 255) / 256)), dim3(256), 0, s,
+                         split_out, S, bias, Y, ldy, B, n, a);
+      SLONN_HIP(hipGetLastError());
+    }
     return SLONN_OK;
   }
 #define SLONN_LAUNCH_DENSE(WDT, BM, BN)                                                            \

@@ -60,6 +60,7 @@ struct Workspace {
   size_t tiles_bytes = 0;
   void* hash_int = nullptr;             // digits of the activations and partial sums of the integer hash
   void* hash_split = nullptr;           // partial sums of the split hash projection
+  void* dense_split = nullptr;          // partial sums of a skinny dense layer's split reduction
   size_t bytes = 0;
   int max_n = 0, max_H = 0, max_na = 0;
 };
@@ -102,6 +103,9 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   w->tiles = tiles_bytes ? take(tiles_bytes) : nullptr;
   w->tiles_bytes = tiles_bytes;
   w->hash_split = take(hash_split_workspace_bytes());
+  size_t dsplit = 0;
+  for (const Layer& l : m->layers) dsplit = std::max(dsplit, dense_split_workspace_bytes(B, l.d_out, l.d_in));
+  w->dense_split = dsplit ? take(dsplit) : nullptr;
   size_t hint = 0;
   if (B >= HASH_INT_MIN_BATCH)
     for (const Layer& l : m->layers)
@@ -899,7 +903,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
                ((size_t)((B + 31) / 32) * ((L.d_out + 31) / 32) >= 64 &&
                 dense_small_supported(L.W, L.w_dtype, cur, ldcur, L.d_in))) {
       // a layer computed in full for a real batch is a dense contraction: matrix cores
-      rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out, act, s);
+      rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out, act, w.dense_split, s);
       if (rc) return rc;
     } else {
       rc = launch_gather_forward(L.W, L.w_dtype, L.bias, cur, ldcur, nullptr, nullptr, 0, L.d_out, out, ldo,
@@ -1045,7 +1049,8 @@ int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float
       rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
                             L.d_out, B, L.d_in, L.d_out, L.act, s);
     else
-      rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, L.d_out, B, L.d_in, L.d_out, L.act, s);
+      rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, L.d_out, B, L.d_in, L.d_out, L.act,
+                              w.dense_split, s);
     if (rc) return rc;
     if (is_last) {
       rc = launch_finalize(out, L.d_out, L.d_out, nullptr, nullptr, 0, nullptr, 0, L.act == SLONN_ACT_SOFTMAX,

@@ -308,9 +308,12 @@ int launch_finalize(float* Y, int ldy, int n, const int32_t* active, const int32
                     int idx_stride, float* yc, int ldc, int do_softmax, int32_t* argmax, int B,
                     hipStream_t s);
 
-// Dense layer Y = act(X W^T + b) as an MFMA GEMM (fp32 matrix cores).
+// Dense layer Y = act(X W^T + b) as an MFMA GEMM (fp32 matrix cores).  split_scratch (nullable):
+// dense_split_workspace_bytes(B, n, d) bytes; with it a problem of only a few tiles (a skinny
+// output layer) splits its reduction over more workgroups.
 int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
-                       float* Y, int ldy, int B, int d, int n, int act, hipStream_t s);
+                       float* Y, int ldy, int B, int d, int n, int act, void* split_scratch, hipStream_t s);
+size_t dense_split_workspace_bytes(int B, int n, int d);
 
 // true when a problem of fewer than 256 tiles of 64x64 can take the small-shape MFMA kernel
 // (operands straight from L2); otherwise such shapes are better served by the row gather.
