@@ -205,19 +205,20 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __global__ void split_x_kernel(const float* __restrict__ X, int ldx, int B, int d,
                                uint16_t* __restrict__ xs3, const int32_t* __restrict__ served) {
-  const int q = blockIdx.x;                             // queries on grid.x: batches up to 2^20
+  const int q = blockIdx.x;                             // one workgroup per query
   if (served && served[q >> 4]) return;                 // evaluated as masked tiles: not needed here
-  const int i = blockIdx.y * blockDim.x + threadIdx.x;
-  if (i >= d) return;
-  const float x = X[(size_t)q * ldx + i];
-  const uint32_t hb = __float_as_uint(x) & 0xFFFF0000u;
-  const float r1 = x - __uint_as_float(hb);             // exact: hi keeps the leading bits of x
-  const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
-  const float r2 = r1 - __uint_as_float(mb);            // exact, at most 8 significant bits left
-  const size_t plane = (size_t)B * d, at = (size_t)q * d + i;
-  xs3[at] = (uint16_t)(hb >> 16);
-  xs3[plane + at] = (uint16_t)(mb >> 16);
-  xs3[2 * plane + at] = (uint16_t)(__float_as_uint(r2) >> 16);
+  const size_t plane = (size_t)B * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    const float x = X[(size_t)q * ldx + i];
+    const uint32_t hb = __float_as_uint(x) & 0xFFFF0000u;
+    const float r1 = x - __uint_as_float(hb);           // exact: hi keeps the leading bits of x
+    const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
+    const float r2 = r1 - __uint_as_float(mb);          // exact, at most 8 significant bits left
+    const size_t at = (size_t)q * d + i;
+    xs3[at] = (uint16_t)(hb >> 16);
+    xs3[plane + at] = (uint16_t)(mb >> 16);
+    xs3[2 * plane + at] = (uint16_t)(__float_as_uint(r2) >> 16);
+  }
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) {
@@ -371,7 +372,7 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
                        ucnt, gflag, n, ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, thr10, served);
     SLONN_HIP(hipGetLastError());
     if (bf16_cores) {
-      hipLaunchKernelGGL(split_x_kernel, dim3(B, (d + 255) / 256), dim3(256), 0, s, X, ldx, B, d, xs3, served);
+      hipLaunchKernelGGL(split_x_kernel, dim3(B), dim3(256), 0, s, X, ldx, B, d, xs3, served);
       SLONN_HIP(hipGetLastError());
     }
   }
