@@ -156,22 +156,28 @@ __global__ __launch_bounds__(256) void dense_layer_kernel(const void* __restrict
 // steps are loaded ahead, and the partial tiles are added in LDS in a fixed order.  Skinny
 // problems (a 100-node output layer) have only a handful of tiles: sixteen wavefronts per tile
 // then shorten the latency-bound reduction loop fourfold.
-template <int WDT, int U, int KS>
+template <int WDT, int U, int KS, bool SPLIT = false>
 __global__ __launch_bounds__(64 * KS) void dense_direct_kernel(const void* __restrict__ W,
                                                           const float* __restrict__ bias,
                                                           const float* __restrict__ X, int ldx,
                                                           float* __restrict__ Y, int ldy, int M, int N,
-                                                          int Kd, int act, float* __restrict__ split_out) {
+                                                          int Kd, int act, float* __restrict__ split_out,
+                                                          int nslices) {
   __shared__ float part[KS - 1][64][16];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 31, half = lane >> 5;
   const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
   const float* xr = X + (size_t)min(m0 + r, M - 1) * ldx;          // surplus rows recompute a valid row
   const size_t wrow = (size_t)min(n0 + r, N - 1) * Kd;
-  // blockIdx.z: slice of the reduction dimension (split_out then receives the slice's sums)
+  // blockIdx.z: slice of the reduction dimension (split_out then receives the slice's sums);
+  // nslices = gridDim.z, handed over as an argument (cheaper to reach than the dispatch packet)
   const int steps = (Kd + 7) / 8;
-  const int per_z = (steps + (int)gridDim.z - 1) / (int)gridDim.z;
-  const int z_begin = min(steps, (int)blockIdx.z * per_z), z_end = min(steps, z_begin + per_z);
+  int z_begin = 0, z_end = steps;
+  if (SPLIT) {
+    const int per_z = (steps + nslices - 1) / nslices;
+    z_begin = min(steps, (int)blockIdx.z * per_z);
+    z_end = min(steps, z_begin + per_z);
+  }
   const int per = (z_end - z_begin + KS - 1) / KS;
   const int s_begin = min(z_end, z_begin + wave * per), s_end = min(z_end, s_begin + per);
   f32x16 acc;
@@ -221,7 +227,7 @@ __global__ __launch_bounds__(64 * KS) void dense_direct_kernel(const void* __res
       float z = acc[v];
 #pragma unroll
       for (int w = 0; w < KS - 1; ++w) z += part[w][lane][v];       // fixed order
-      if (split_out) {
+      if (SPLIT) {
         if (row < M && col < N) split_out[((size_t)blockIdx.z * M + row) * N + col] = z;
         continue;
       }
@@ -254,12 +260,13 @@ bool dense_small_supported(const void* W, int w_dtype, const float* X, int ldx, 
          reinterpret_cast<uintptr_t>(W) % (w_dtype == SLONN_F32 ? 16 : 8) == 0;
 }
 
-// Slices of the reduction dimension for a problem with only a few 32x32 tiles: as many as fill
-// two workgroups per compute unit, each at least 512 elements long.
+// Slices of the reduction dimension for a problem whose 32x32 tiles leave at least half of the
+// compute units idle: up to two workgroups per unit, each slice at least 1024 elements long
+// (shorter ones do not repay the second kernel).
 static int dense_split_factor(int B, int n, int d) {
   const long tiles32 = (long)((B + 31) / 32) * ((n + 31) / 32);
   int S = 1;
-  while (S < 8 && tiles32 * S * 2 <= 512 && d / (S * 2) >= 512) S *= 2;
+  while (S < 8 && tiles32 <= 128 && tiles32 * S * 2 <= 512 && d / (S * 2) >= 1024) S *= 2;
   return S;
 }
 
@@ -285,21 +292,19 @@ int launch_dense_layer(const void* W, int w_dtype, const float* bias, const floa
     const int S = (few && split_scratch) ? dense_split_factor(B, n, d) : 1;
     float* split_out = S > 1 ? static_cast<float*>(split_scratch) : nullptr;
     dim3 grid((n + 31) / 32, (B + 31) / 32, S);
+#define SLONN_LAUNCH_DIRECT(WDT, KS, SPLIT)                                                             \
+  hipLaunchKernelGGL((dense_direct_kernel<WDT, 4, KS, SPLIT>), grid, dim3(64 * KS), 0, s, W, bias, X, ldx, Y, \
+                     ldy, B, n, d, a, split_out, S)
     if (w_dtype == SLONN_F32) {
-      if (few)
-        hipLaunchKernelGGL((dense_direct_kernel<SLONN_F32, 4, 16>), grid, dim3(1024), 0, s, W, bias, X, ldx, Y, ldy,
-                           B, n, d, a, split_out);
-      else
-        hipLaunchKernelGGL((dense_direct_kernel<SLONN_F32, 4, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
-                           B, n, d, a, split_out);
+      if (S > 1) SLONN_LAUNCH_DIRECT(SLONN_F32, 16, true);
+      else if (few) SLONN_LAUNCH_DIRECT(SLONN_F32, 16, false);
+      else SLONN_LAUNCH_DIRECT(SLONN_F32, 4, false);
     } else {
-      if (few)
-        hipLaunchKernelGGL((dense_direct_kernel<SLONN_BF16, 4, 16>), grid, dim3(1024), 0, s, W, bias, X, ldx, Y, ldy,
-                           B, n, d, a, split_out);
-      else
-        hipLaunchKernelGGL((dense_direct_kernel<SLONN_BF16, 4, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, Y, ldy,
-                           B, n, d, a, split_out);
+      if (S > 1) SLONN_LAUNCH_DIRECT(SLONN_BF16, 16, true);
+      else if (few) SLONN_LAUNCH_DIRECT(SLONN_BF16, 16, false);
+      else SLONN_LAUNCH_DIRECT(SLONN_BF16, 4, false);
     }
+#undef SLONN_LAUNCH_DIRECT
     SLONN_HIP(hipGetLastError());
     if (S > 1) {
       hipLaunchKernelGGL(dense_split_sum_kernel, dim3((unsigned)(((size_t)B * n + 255) / 256)), dim3(256), 0, s,
