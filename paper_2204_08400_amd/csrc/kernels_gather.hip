@@ -80,7 +80,8 @@ template <int WDT, bool VECTOR>
 __global__ __launch_bounds__(256) void gather_forward_kernel(
     const void* __restrict__ W, const float* __restrict__ bias, const float* __restrict__ X, int ldx,
     const int32_t* __restrict__ active, const int32_t* __restrict__ cnt, int idx_stride,
-    float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int n, int act) {
+    float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int n, int act,
+    int ychunks) {             // ychunks = gridDim.y (an argument is quicker to reach than the dispatch packet)
   extern __shared__ __align__(16) float xs[];
   using C = Chunk<WDT>;
   const int q = blockIdx.x;              // queries on x (no 65535 limit), chunks on y
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(256) void gather_forward_kernel(
   const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
   // the grid holds a bounded number of chunks per query (the budget is only known on the
   // device); a workgroup walks its chunks with the grid's stride
-  for (int row0 = blockIdx.y * ROWS_PER_BLOCK; row0 < c; row0 += gridDim.y * ROWS_PER_BLOCK) {
+  for (int row0 = blockIdx.y * ROWS_PER_BLOCK; row0 < c; row0 += ychunks * ROWS_PER_BLOCK) {
     int t[ROWS_PER_GROUP], j[ROWS_PER_GROUP];
     float acc[ROWS_PER_GROUP];
 #pragma unroll
@@ -163,7 +164,8 @@ template <int WDT>
 __global__ __launch_bounds__(256) void gather_wave_kernel(
     const void* __restrict__ W, const float* __restrict__ bias, const float* __restrict__ X, int ldx,
     const int32_t* __restrict__ active, const int32_t* __restrict__ cnt, int idx_stride,
-    float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int n, int act) {
+    float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int n, int act,
+    int ychunks) {             // ychunks = gridDim.y (an argument is quicker to reach than the dispatch packet)
   extern __shared__ __align__(16) float xs[];
   using C = Chunk<WDT>;
   using vec_t = typename C::vec_t;
@@ -177,7 +179,7 @@ __global__ __launch_bounds__(256) void gather_wave_kernel(
   __syncthreads();
   const int nv = d / C::ELEMS;
   const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
-  for (int t0 = blockIdx.y * ROWS_PER_WAVE_BLOCK + 2 * wave; t0 < c; t0 += gridDim.y * ROWS_PER_WAVE_BLOCK) {
+  for (int t0 = blockIdx.y * ROWS_PER_WAVE_BLOCK + 2 * wave; t0 < c; t0 += ychunks * ROWS_PER_WAVE_BLOCK) {
     const bool two = t0 + 1 < c;
     const int j0 = list ? list[t0] : t0, j1 = two ? (list ? list[t0 + 1] : t0 + 1) : j0;
     const vec_t* w0 = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
@@ -396,10 +398,10 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
     dim3 grid(B, chunks);
     if (w_dtype == SLONN_F32)
       hipLaunchKernelGGL((gather_wave_kernel<SLONN_F32>), grid, dim3(256), lds, s, W, bias, X, ldx, active,
-                         cnt, idx_stride, Y, ldy, yc, ldc, d, n, a);
+                         cnt, idx_stride, Y, ldy, yc, ldc, d, n, a, (int)grid.y);
     else
       hipLaunchKernelGGL((gather_wave_kernel<SLONN_BF16>), grid, dim3(256), lds, s, W, bias, X, ldx, active,
-                         cnt, idx_stride, Y, ldy, yc, ldc, d, n, a);
+                         cnt, idx_stride, Y, ldy, yc, ldc, d, n, a, (int)grid.y);
     SLONN_HIP(hipGetLastError());
     return SLONN_OK;
   }
@@ -410,7 +412,7 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
   dim3 grid(B, chunks);
 #define SLONN_LAUNCH_GATHER(WDT, VEC)                                                              \
   hipLaunchKernelGGL((gather_forward_kernel<WDT, VEC>), grid, dim3(256), lds, s, W, bias, X, ldx,  \
-                     active, cnt, idx_stride, Y, ldy, yc, ldc, d, n, a)
+                     active, cnt, idx_stride, Y, ldy, yc, ldc, d, n, a, (int)grid.y)
   if (w_dtype == SLONN_F32) {
     if (vec) SLONN_LAUNCH_GATHER(SLONN_F32, true); else SLONN_LAUNCH_GATHER(SLONN_F32, false);
   } else {

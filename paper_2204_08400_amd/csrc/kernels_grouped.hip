@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void gather_grouped_kernel(
     const void* __restrict__ W, const float* __restrict__ bias, const float* __restrict__ X, int ldx,
     const int32_t* __restrict__ urows, const uint32_t* __restrict__ umask,
     const int32_t* __restrict__ ucnt, const int32_t* __restrict__ gflag, int ustride, float* __restrict__ Y,
-    int ldy, int B, int d, int act) {
+    int ldy, int B, int d, int act, int ychunks) {      // ychunks = gridDim.y
   const int g = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   if (!gflag[g]) return;                 // this group is served by the per-query gather
   const int r = lane & 15, kg = lane >> 4;
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void gather_grouped_kernel(
   const int steps = (d + 15) / 16;
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
 
-  for (int r0 = blockIdx.y * ROWS_PER_WG + wave * 32; r0 < uc; r0 += gridDim.y * ROWS_PER_WG) {
+  for (int r0 = blockIdx.y * ROWS_PER_WG + wave * 32; r0 < uc; r0 += ychunks * ROWS_PER_WG) {
     const size_t wa = (size_t)rows[min(r0 + r, uc - 1)] * d;        // surplus lanes redo a valid row
     const size_t wb = (size_t)rows[min(r0 + 16 + r, uc - 1)] * d;
     f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
@@ -208,7 +208,7 @@ __global__ void split_x_kernel(const float* __restrict__ X, int ldx, int B, int 
   const int q = blockIdx.x;                             // one workgroup per query
   if (served && served[q >> 4]) return;                 // evaluated as masked tiles: not needed here
   const size_t plane = (size_t)B * d;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+  for (int i = threadIdx.x; i < d; i += 256) {
     const float x = X[(size_t)q * ldx + i];
     const uint32_t hb = __float_as_uint(x) & 0xFFFF0000u;
     const float r1 = x - __uint_as_float(hb);           // exact: hi keeps the leading bits of x
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(256) void gather_grouped_bf16_kernel(
     const uint16_t* __restrict__ W, const float* __restrict__ bias, const uint16_t* __restrict__ xs3,
     const int32_t* __restrict__ urows, const uint32_t* __restrict__ umask,
     const int32_t* __restrict__ ucnt, const int32_t* __restrict__ gflag, int ustride, float* __restrict__ Y,
-    int ldy, int B, int d, int act) {
+    int ldy, int B, int d, int act, int ychunks) {      // ychunks = gridDim.y
   const int g = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   if (!gflag[g]) return;                 // this group is served by the per-query gather
   const int r = lane & 15, kg = lane >> 4;
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(256) void gather_grouped_bf16_kernel(
   const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
   constexpr int ROWS_WG = 4 * 16 * T;
 
-  for (int r0 = blockIdx.y * ROWS_WG + wave * 16 * T; r0 < uc; r0 += gridDim.y * ROWS_WG) {
+  for (int r0 = blockIdx.y * ROWS_WG + wave * 16 * T; r0 < uc; r0 += ychunks * ROWS_WG) {
     const uint16_t* wr[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) wr[t] = W + (size_t)rows[min(r0 + 16 * t + r, uc - 1)] * d;   // surplus lanes redo a valid row
@@ -385,7 +385,7 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
     int chunks = (n + 64 * T - 1) / (64 * T);
     chunks = std::min(chunks, std::max(4, 4096 / ng));
     hipLaunchKernelGGL((gather_grouped_bf16_kernel<T>), dim3(ng, chunks), dim3(256), 0, s,
-                       static_cast<const uint16_t*>(W), bias, xs3, urows, umask, ucnt, gflag, n, Y, ldy, B, d, a);
+                       static_cast<const uint16_t*>(W), bias, xs3, urows, umask, ucnt, gflag, n, Y, ldy, B, d, a, chunks);
     SLONN_HIP(hipGetLastError());
     return SLONN_OK;
   }
@@ -394,10 +394,10 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
   dim3 grid(ng, chunks);
   if (w_dtype == SLONN_F32)
     hipLaunchKernelGGL((gather_grouped_kernel<SLONN_F32, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, urows,
-                       umask, ucnt, gflag, n, Y, ldy, B, d, a);
+                       umask, ucnt, gflag, n, Y, ldy, B, d, a, chunks);
   else
     hipLaunchKernelGGL((gather_grouped_kernel<SLONN_BF16, 4>), grid, dim3(256), 0, s, W, bias, X, ldx, urows,
-                       umask, ucnt, gflag, n, Y, ldy, B, d, a);
+                       umask, ucnt, gflag, n, Y, ldy, B, d, a, chunks);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

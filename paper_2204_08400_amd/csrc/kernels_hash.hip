@@ -38,7 +38,8 @@ __global__ __launch_bounds__(64 * KS) void hash_project_mfma_kernel(const float*
                                                                const float* __restrict__ Wh,
                                                                const float* __restrict__ bh,
                                                                float* __restrict__ Z, int B, int H, int d,
-                                                               double* __restrict__ gpart = nullptr) {
+                                                               double* __restrict__ gpart = nullptr,
+                                                               int nslices = 1) {
   __shared__ double part[KS - 1][64][TM * TN * 4];     // partial tiles of waves 1..KS-1
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
@@ -51,11 +52,12 @@ __global__ __launch_bounds__(64 * KS) void hash_project_mfma_kernel(const float*
 #pragma unroll
   for (int j = 0; j < TN; ++j) wr[j] = Wh + (size_t)min(h0 + 16 * j + r, H - 1) * d;
   // this wave's share of the reduction dimension, in steps of 16 elements (with SPLIT the
-  // workgroup itself owns one of gridDim.z consecutive ranges of steps)
+  // workgroup itself owns one of nslices = gridDim.z consecutive ranges of steps; the count
+  // comes as an argument, which is quicker to reach than the dispatch packet)
   const int steps = (d + 15) / 16;
   int wg_begin = 0, wg_end = steps;
   if (SPLIT) {
-    const int per_wg = (steps + (int)gridDim.z - 1) / (int)gridDim.z;
+    const int per_wg = (steps + nslices - 1) / nslices;
     wg_begin = min(steps, (int)blockIdx.z * per_wg);
     wg_end = min(steps, wg_begin + per_wg);
   }
@@ -285,10 +287,10 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
     double* gpart = static_cast<double*>(split_scratch);
     dim3 g((H + 15) / 16, (B + 15) / 16, S);
     hipLaunchKernelGGL((hash_project_mfma_kernel<1, 1, 4, 4, true>), g, dim3(256), 0, s, X, ldx, Wh, bh, Z, B, H,
-                       d, gpart);
+                       d, gpart, S);
     SLONN_HIP(hipGetLastError());
     if (pending) {
-      pending->part = gpart; pending->S = S; pending->bh = bh; pending->Z = Z;
+      pending->part = gpart; pending->S = S; pending->B = B; pending->bh = bh; pending->Z = Z;
       return SLONN_OK;
     }
     hipLaunchKernelGGL(hash_split_sum_kernel, dim3((B * H + 255) / 256), dim3(256), 0, s, gpart, S, bh, Z, B, H);

@@ -162,7 +162,8 @@ __device__ __forceinline__ i32x4 as_i32x4(u32x4 v) { return __builtin_bit_cast(i
 template <int HH, int WQ, int WH>
 __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __restrict__ Xd,
                                                             const int8_t* __restrict__ Wd,
-                                                            double* __restrict__ part, int B, int H, int d) {
+                                                            double* __restrict__ part, int B, int H, int d,
+                                                            int nslices) {
   extern __shared__ u32x4 hash_lds[];       // two buffers of [HQ rows of X | HH rows of W][HROW]
   constexpr int BUF = (HQ + HH) * HROW;
   constexpr int TOTAL = (HQ + HH) * HPIECES;         // pieces per chunk
@@ -189,7 +190,7 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
   }
   // this workgroup's chunks of 64 elements
   const int nchunks = d / 64;
-  const int per_z = (nchunks + (int)gridDim.z - 1) / (int)gridDim.z;
+  const int per_z = (nchunks + nslices - 1) / nslices;      // nslices = gridDim.z, as an argument
   const int c_begin = min(nchunks, (int)blockIdx.z * per_z), c_end = min(nchunks, c_begin + per_z);
   const int last = max(c_end - 1, c_begin);
 
@@ -427,13 +428,13 @@ int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel<64, 4, 2>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((hash_int_tiles_kernel<64, 4, 2>), dim3((H + 63) / 64, (B + HQ - 1) / HQ, S), dim3(512), lds, s,
-                       Xd, Wd, part, B, H, d);
+                       Xd, Wd, part, B, H, d, S);
   } else {
     constexpr size_t lds = (size_t)2 * (HQ + 48) * HROW * 16;
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel<48, 8, 1>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((hash_int_tiles_kernel<48, 8, 1>), dim3((H + 47) / 48, (B + HQ - 1) / HQ, S), dim3(512), lds, s,
-                       Xd, Wd, part, B, H, d);
+                       Xd, Wd, part, B, H, d, S);
   }
   SLONN_HIP(hipGetLastError());
   hipLaunchKernelGGL(hash_int_finish_kernel, dim3((unsigned)(((size_t)B * H + 255) / 256)), dim3(256), 0, s, part, S,

@@ -31,13 +31,14 @@ constexpr int SEL_NT_BIG = 1024; // few queries: four times as many slots per ro
 // get their output from the projections z here and join no group.  hist: at least nblk + 1
 // free words of LDS.  Called by the whole workgroup after the list is complete (the list was
 // written by other threads: the barrier at the top also orders those global stores).
+template <int NT>
 __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const RowBlocking& rb, int q,
                                                const float* z, uint32_t* hist) {
   const int tid = threadIdx.x;
   __syncthreads();
-  for (int b = tid; b <= rb.nblk; b += blockDim.x) hist[b] = 0;
+  for (int b = tid; b <= rb.nblk; b += NT) hist[b] = 0;
   __syncthreads();
-  for (int t = tid; t < m; t += blockDim.x) {
+  for (int t = tid; t < m; t += NT) {
     const int id = out[t];
     const int hs = rb.hslot ? (int)rb.hslot[id] : -1;
     if (hs >= 0) {          // a selected hash node: its output is its projection
@@ -69,7 +70,7 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
     }
   }
   __syncthreads();
-  for (int t = tid; t < m; t += blockDim.x) {
+  for (int t = tid; t < m; t += NT) {
     const int id = out[t];
     if (rb.hslot && rb.hslot[id] >= 0) continue;
     const uint32_t p = atomicAdd(&hist[id / rb.rows_per_block], 1u);
@@ -81,10 +82,11 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
 // A medium batch leaves the hash projection's reduction split in hs.S partial sums per
 // (query, hash row).  Add them in split order, add the bias, and store the projections of
 // query q for this kernel and for the later readers.  Whole workgroup; ends with a barrier.
-__device__ __forceinline__ void sum_split_projections(const HashSplit& hs, int q, int B, int H) {
+template <int NT>
+__device__ __forceinline__ void sum_split_projections(const HashSplit& hs, int q, int H) {
   if (!hs.part) return;
-  const size_t plane = (size_t)B * H;
-  for (int h = threadIdx.x; h < H; h += blockDim.x) {
+  const size_t plane = (size_t)hs.B * H;
+  for (int h = threadIdx.x; h < H; h += NT) {
     double sum = 0.0;
     for (int z = 0; z < hs.S; ++z) sum += hs.part[z * plane + (size_t)q * H + h];
     hs.Z[(size_t)q * H + h] = (float)(sum + (double)hs.bh[h]);
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
   const int m = budget_of(keep[(size_t)q * keep_stride], n);
   int32_t* out = active + (size_t)q * idx_stride;
   const float* z = Z + (size_t)q * K * L;
-  sum_split_projections(hsp, q, gridDim.x, K * L);
+  sum_split_projections<NT>(hsp, q, K * L);
   float* y = yzero ? yzero + (size_t)q * ldy : nullptr;
   const int H = hf.hnodes ? K * L : 0;          // hash nodes in front of the list (Section 3.4 variant)
   const int total = (m == n || m > H) ? m : H;
@@ -131,7 +133,7 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += NT) out[i] = i;
-    if (rb.part_idx) partition_rows(out, n, rb, q, z, sh.prio);
+    if (rb.part_idx) partition_rows<NT>(out, n, rb, q, z, sh.prio);
     return;
   }
   // The last wavefront forms the keys and fetches the bucket directory (two dependent memory
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
   __syncthreads();
   select_merge<NT, MU>(L, n, total - H, ids, global_rank, sh, out + H, hskip);
 
-  if (rb.part_idx) partition_rows(out, total, rb, q, z, sh.prio);
+  if (rb.part_idx) partition_rows<NT>(out, total, rb, q, z, sh.prio);
 }
 
 __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   const int m = budget_of(keep[(size_t)q * keep_stride], n);
   int32_t* out = active + (size_t)q * idx_stride;
   const float* z = Z + (size_t)q * K * L;
-  sum_split_projections(hsp, q, gridDim.x, K * L);
+  sum_split_projections<SEL_NT>(hsp, q, K * L);
   if (yzero) {
     float* y = yzero + (size_t)q * ldy;
     for (int i = tid; i < n; i += SEL_NT) y[i] = 0.0f;
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += SEL_NT) out[i] = i;
-    if (rb.part_idx) partition_rows(out, n, rb, q, z, sh.tval);
+    if (rb.part_idx) partition_rows<SEL_NT>(out, n, rb, q, z, sh.tval);
     return;
   }
   for (int i = tid; i < words; i += SEL_NT) sh.taken[i] = 0u;
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   __syncthreads();
   select_block_wide<SEL_NT>(z, K, L, n, total - H, dir, ids, global_rank, sh,
                             codes ? codes + (size_t)q * L : nullptr, out + H, H ? hf.hslot : nullptr);
-  if (rb.part_idx) partition_rows(out, total, rb, q, z, sh.tval);
+  if (rb.part_idx) partition_rows<SEL_NT>(out, total, rb, q, z, sh.tval);
 }
 
 // Queries in descending order of their budget (256 classes of the keep fraction; the order inside

@@ -191,6 +191,7 @@ struct HashFirst {
 struct HashSplit {
   const double* part = nullptr;
   int S = 0;
+  int B = 0;
   const float* bh = nullptr;
   float* Z = nullptr;
 };
