@@ -209,6 +209,60 @@ __global__ __launch_bounds__(256) void gather_wave_kernel(
   }
 }
 
+// A handful of queries: one workgroup per (query, list entry).  Nothing is staged: a thread's
+// pieces of the row and of the activations go from memory to registers with all loads in flight
+// together (the list entry is fetched beside the list length, before either is known to be
+// needed), so a 16 KB row costs about two memory round trips instead of the six of a
+// wavefront walking it after the query vector has been staged in LDS.
+template <int WDT>
+__global__ __launch_bounds__(256) void gather_row_kernel(
+    const void* __restrict__ W, const float* __restrict__ bias, const float* __restrict__ X, int ldx,
+    const int32_t* __restrict__ active, const int32_t* __restrict__ cnt, int idx_stride,
+    float* __restrict__ Y, int ldy, float* __restrict__ yc, int ldc, int d, int n, int act, int xstride) {
+  __shared__ float part[4];
+  using C = Chunk<WDT>;
+  using vec_t = typename C::vec_t;
+  constexpr int U = 4;                     // pieces per thread held at once
+  const int q = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int32_t* list = active ? active + (size_t)q * idx_stride : nullptr;
+  // (idx_stride >= n >= gridDim.x: the entry exists whatever the list's length)
+  int j = list ? list[blockIdx.x] : (int)blockIdx.x;
+  const int c = active ? cnt[q] : n;
+  const float* x = X + (size_t)q * ldx;
+  const int nv = d / C::ELEMS;
+  for (int t = blockIdx.x; t < c; t += xstride) {
+    if (t != (int)blockIdx.x) j = list ? list[t] : t;
+    const vec_t* w = reinterpret_cast<const vec_t*>(static_cast<const char*>(W) +
+                                                    (size_t)j * d * (WDT == SLONN_F32 ? 4 : 2));
+    float acc = 0.0f;
+    for (int i0 = tid; i0 < nv; i0 += 256 * U) {
+      vec_t wv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = i0 + 256 * u;
+        wv[u] = w[i < nv ? i : tid];        // a surplus piece repeats a valid one and is not used
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = i0 + 256 * u;
+        if (i < nv) acc = C::dot(wv[u], x + (size_t)i * C::ELEMS, acc);
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) part[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+      float z = ((part[0] + part[1]) + (part[2] + part[3])) + bias[j];
+      if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+      if (Y) Y[(size_t)q * ldy + j] = z;
+      if (yc) yc[(size_t)q * ldc + t] = z;
+    }
+    __syncthreads();
+  }
+}
+
 // Row-block variant for layers whose weight matrix is much larger than an L2 slice:
 // workgroup (q, block) evaluates the rows of query q that lie in one block of consecutive
 // weight rows (about a megabyte).  The grid runs over queries fastest, so the workgroups
@@ -374,6 +428,9 @@ __global__ __launch_bounds__(64) void finalize_kernel(float* __restrict__ Y, int
   }
 }
 
+// entries a query's list buffer is sure to hold (no list: ids are the positions themselves)
+inline int idx_stride_or(const int32_t* active, int idx_stride, int n) { return active ? idx_stride : n; }
+
 }  // namespace
 
 int launch_gather_forward(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
@@ -392,6 +449,18 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
   // few queries, or few rows each (a skinny layer computed in full): the 64-row chunks of the
   // general kernel would leave most of the chip idle; long rows: one wavefront per row
   const long coarse_wgs = (long)B * ((max_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
+  if (vec && B <= GATHER_ROW_MAX_BATCH && (size_t)d * esz >= 4096 && max_rows <= idx_stride_or(active, idx_stride, n)) {
+    // one workgroup per list entry (at most 2048 per query, strided beyond)
+    dim3 grid(std::min(max_rows, 2048), B);
+    if (w_dtype == SLONN_F32)
+      hipLaunchKernelGGL((gather_row_kernel<SLONN_F32>), grid, dim3(256), 0, s, W, bias, X, ldx, active, cnt,
+                         idx_stride, Y, ldy, yc, ldc, d, n, a, (int)grid.x);
+    else
+      hipLaunchKernelGGL((gather_row_kernel<SLONN_BF16>), grid, dim3(256), 0, s, W, bias, X, ldx, active, cnt,
+                         idx_stride, Y, ldy, yc, ldc, d, n, a, (int)grid.x);
+    SLONN_HIP(hipGetLastError());
+    return SLONN_OK;
+  }
   if (vec && (B <= 16 || coarse_wgs < 1024) && (size_t)d * esz >= 1024) {
     int chunks = (max_rows + ROWS_PER_WAVE_BLOCK - 1) / ROWS_PER_WAVE_BLOCK;
     chunks = std::min(chunks, std::max(4, 4096 / B));

@@ -38,7 +38,14 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
   __syncthreads();
   for (int b = tid; b <= rb.nblk; b += NT) hist[b] = 0;
   __syncthreads();
-  for (int t = tid; t < m; t += NT) {
+  // (a thread's first KEEP entries stay in registers for the second pass; rows_per_block is a
+  // power of two)
+  constexpr int KEEP = 4;
+  const int shift = __ffs(rb.rows_per_block) - 1;
+  int id_r[KEEP];
+#pragma unroll
+  for (int u = 0; u < KEEP; ++u) id_r[u] = -1;         // -1: no entry, or a hash node (joins no group)
+  auto first_pass = [&](int t) {
     const int id = out[t];
     const int hs = rb.hslot ? (int)rb.hslot[id] : -1;
     if (hs >= 0) {          // a selected hash node: its output is its projection
@@ -46,10 +53,15 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
       if (rb.relu && !(v > 0.0f)) v = 0.0f;
       if (rb.y) rb.y[(size_t)q * rb.ldy + id] = v;
       if (rb.yc) rb.yc[(size_t)q * rb.ldc + t] = v;
-    } else {
-      atomicAdd(&hist[id / rb.rows_per_block], 1u);
+      return -1;
     }
-  }
+    atomicAdd(&hist[id >> shift], 1u);
+    return id;
+  };
+#pragma unroll
+  for (int u = 0; u < KEEP; ++u)
+    if (tid + NT * u < m) id_r[u] = first_pass(tid + NT * u);
+  for (int t = tid + NT * KEEP; t < m; t += NT) (void)first_pass(t);
   __syncthreads();
   if (tid < 64) {         // exclusive prefix sum over the row blocks by one wavefront
     uint32_t carry = 0;
@@ -70,12 +82,18 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
     }
   }
   __syncthreads();
-  for (int t = tid; t < m; t += NT) {
-    const int id = out[t];
-    if (rb.hslot && rb.hslot[id] >= 0) continue;
-    const uint32_t p = atomicAdd(&hist[id / rb.rows_per_block], 1u);
+  auto place = [&](int id, int t) {
+    const uint32_t p = atomicAdd(&hist[id >> shift], 1u);
     rb.part_idx[(size_t)q * rb.stride + p] = id;
     rb.part_pos[(size_t)q * rb.stride + p] = t;
+  };
+#pragma unroll
+  for (int u = 0; u < KEEP; ++u)
+    if (id_r[u] >= 0) place(id_r[u], tid + NT * u);
+  for (int t = tid + NT * KEEP; t < m; t += NT) {
+    const int id = out[t];
+    if (rb.hslot && rb.hslot[id] >= 0) continue;
+    place(id, t);
   }
 }
 

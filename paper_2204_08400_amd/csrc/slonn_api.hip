@@ -45,6 +45,12 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 // are latency-bound anyway and the slicing pass would not pay)
 constexpr int HASH_INT_MIN_BATCH = 512;
 
+// up to GATHER_ROW_MAX_BATCH queries the selected rows are fetched by one workgroup each
+// (launch_gather_forward); beyond it large layers are walked in row blocks shared between the
+// queries (C3 keep .25, whole step: batch 2 71 against 97 us, batch 4 86 against 103, batch 6 107
+// against 112, batch 8 122 against 114)
+constexpr int ROW_BLOCK_MIN_BATCH = GATHER_ROW_MAX_BATCH + 1;
+
 // Carves the caller's workspace into the per-batch buffers of the forward pass.
 struct Workspace {
   float* act[2] = {nullptr, nullptr};   // ping-pong layer outputs [B][max_n]
@@ -800,7 +806,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       const bool all_grouped = gtiles >= 1024 && out && !(is_last && Y->val) && m->path_grouped && rows_vec &&
                                grouped_supported(L.d_out, m->max_lds_bytes) &&
                                grouped_uses_bf16_cores(L.W, L.w_dtype, L.d_in);
-      if (!all_grouped && B >= 2 && rows_vec && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20) &&
+      if (!all_grouped && B >= ROW_BLOCK_MIN_BATCH && rows_vec && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20) &&
           select_fills_row_blocks(L.d_out, m->max_lds_bytes)) {
         int rpb = 16;
         while ((size_t)rpb * 2 * row_bytes <= ((size_t)2 << 20)) rpb *= 2;

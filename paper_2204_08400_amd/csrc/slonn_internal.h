@@ -235,6 +235,9 @@ int launch_order_by_budget(const float* keep, int keep_stride, int B, int32_t* o
 // true when launch_select will fill rb for a layer of n nodes (the workgroup kernel is used)
 bool select_fills_row_blocks(int n, int max_lds);
 
+// batches up to this size fetch every selected row with a workgroup of its own
+constexpr int GATHER_ROW_MAX_BATCH = 6;
+
 // Same result as launch_gather_forward from row-block-grouped lists: workgroup (q, block)
 // evaluates the rows of query q that fall into that block of the weight matrix.
 // skip_group (nullable): [ceil(B/16)] flags; queries of a flagged group are left to the
