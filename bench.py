@@ -220,6 +220,24 @@ def main():
                 "note": "algorithmic bytes = the weight rows the method must evaluate (budget x row bytes per "
                         "activated layer, whole matrix per query for layers computed in full); a fraction above 1 "
                         "means rows were served to several queries from L2 (traffic = bytes that reached HBM)"}
+    if dom == "gather" and prof["tiles"][1] and prof["tiles"][0] > prof["gather"][0]:
+        # large batches: most of the step is the masked tiles on the bf16 matrix cores, a dense
+        # contraction.  Flops per launch = every (query, node) pair of the layer, 2 d flops each,
+        # times the bf16 products per fp32 product (6 with fp32 weights in three parts, 3 with bf16
+        # weights); the selected pairs are the part of them that is written.
+        t_ms, t_n = prof["tiles"]
+        tile_flops = sum(2.0 * B * lay.d_in * lay.d_out * (3 if lay.w_dtype == wl.W_BF16 else 6)
+                         for lay in layers if lay.K > 0)
+        per_launch = tile_flops / max(1, sum(1 for lay in layers if lay.K > 0))
+        avg_s = t_ms / 1e3 / t_n
+        peak = 2500.0
+        roofline = {"bound": "mfma", "kernel": "masked_tiles_kernel", "achieved": round(per_launch / avg_s / 1e12, 1),
+                    "peak": peak, "unit": "TFLOP/s", "frac": round(per_launch / avg_s / 1e12 / peak, 4),
+                    "traffic": None, "avg_launch_us": round(avg_s * 1e6, 2),
+                    "flops_per_launch": int(per_launch),
+                    "note": "bf16 MFMA flops issued per launch (all pairs of a 128-query tile, fp32 operands as "
+                            "three bf16 parts) over the mean launch duration of the masked tiles; the gathered-bytes "
+                            "figure of the whole step is effective_GBps"}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:

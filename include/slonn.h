@@ -329,7 +329,9 @@ int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float
  * caller arrays of SLONN_PROF_KINDS entries (HOST), and switches timing off again.
  * Not thread-safe; costs two event records per launch while on.                     */
 enum { SLONN_PROF_HASH = 0, SLONN_PROF_SELECT = 1, SLONN_PROF_GATHER = 2, SLONN_PROF_DENSE = 3,
-       SLONN_PROF_ELL = 4, SLONN_PROF_FINALIZE = 5, SLONN_PROF_FUSED = 6, SLONN_PROF_KINDS = 7 };
+       SLONN_PROF_ELL = 4, SLONN_PROF_FINALIZE = 5, SLONN_PROF_FUSED = 6,
+       SLONN_PROF_TILES = 7,   /* selected pairs evaluated as masked tiles on the matrix cores */
+       SLONN_PROF_KINDS = 8 };
 int slonn_profile_begin(int max_launches);
 int slonn_profile_end(double* ms_per_kind, int64_t* launches_per_kind);
 

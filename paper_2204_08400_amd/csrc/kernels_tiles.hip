@@ -341,7 +341,7 @@ int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, cons
                        ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, mask, flags, min_pairs, X, ldx, d, X3);
     SLONN_HIP(hipGetLastError());
   }
-  ProfScope prof_(SLONN_PROF_GATHER, s);
+  ProfScope prof_(SLONN_PROF_TILES, s);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
   // 128 x 128 tiles with eight wavefronts once they fill the chip (each weight tile is fetched
   // half as often: C3 batch 1024 190 -> 160 us per layer); 64 x 128 tiles with four, two

@@ -35,7 +35,7 @@ EXPORTS = [
     "slonn_forward_graph_create", "slonn_forward_graph_launch", "slonn_forward_graph_destroy",
     "slonn_activation_variance", "slonn_sample_hash_nodes", "slonn_model_set_hash_margin",
 ]
-PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused")
+PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused", "tiles")
 PATH_AUTO, PATH_LAYERS, PATH_FUSED = 0, 1, 2
 
 

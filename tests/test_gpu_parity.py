@@ -421,7 +421,9 @@ def test_config_c3_timed_batch_sampled(rt, oracle):
         slonn.slonn_profile_begin(64)
         res = g.sparse_forward(Xq, keep, taps=True)
         prof = slonn.slonn_profile_end()
-        assert prof["gather"][1] == 2 * len(cfg.hashed_layers) and prof["dense"][1] == 1, prof
+        # per hidden layer the masked tiles and the per-query pass for what they leave
+        assert prof["tiles"][1] == len(cfg.hashed_layers) and prof["gather"][1] == len(cfg.hashed_layers), prof
+        assert prof["dense"][1] == 1, prof
         got = to_numpy_result(res)
         sample = np.asarray([0, 1, 15, 16, 17, 100, 511, 512, 513, 800, 1008, 1022, 1023])
         ref = net.sparse_forward(Xq[sample], keep)
@@ -466,7 +468,8 @@ def test_config_c5_full_width_sampled(rt, oracle):
     slonn.slonn_profile_begin(64)
     res = g.sparse_forward(Xq, _keep_tensor(keep), taps=True)
     prof = slonn.slonn_profile_end()
-    assert prof["gather"][1] == 2 * len(cfg.hashed_layers), prof     # tiles + unions per hidden layer
+    # tiles + unions per hidden layer
+    assert prof["tiles"][1] == len(cfg.hashed_layers) and prof["gather"][1] == len(cfg.hashed_layers), prof
     # per hidden layer the select kernel, the pair masks of the tiles and the unions; 2048 select
     # workgroups do not fit the device at once: one more launch orders them by budget
     assert prof["select"][1] == 3 * len(cfg.hashed_layers) + 1, prof
@@ -600,7 +603,8 @@ def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d, n):
         # 16 for bf16 (unions only when the rows are not a multiple of 32 elements); the output
         # layer (17 tiles of 32x32) is too small for the matrix-core kernel and takes one more
         # gather launch with the identity list
-        assert prof["gather"][1] == (2 if (w_dtype == wl.W_BF16 and d % 32) else 3), prof
+        assert prof["tiles"][1] == (0 if d % 32 else 1), prof
+        assert prof["tiles"][1] + prof["gather"][1] == (2 if (w_dtype == wl.W_BF16 and d % 32) else 3), prof
         assert prof["dense"][1] == 0, prof
         _say(f"  {compare_sparse(got, ref, layers, 'grouped')}")
     # the same launch configuration with the hash nodes at the head of every list (Section 3.4
