@@ -25,6 +25,7 @@ __device__ __forceinline__ int budget_of(float keep, int n) {
 
 constexpr int SEL_NT = 256;      // workgroup size for real batches
 constexpr int SEL_NT_BIG = 1024; // few queries: four times as many slots per round
+constexpr int WIDE_MU = 4;       // slots per thread per round of the kernel for very wide layers (1024 per round)
 
 // Regroup a finished list by weight-row block (counting sort; the order inside a group does
 // not matter: outputs are written by node id and by selection position).  Selected hash nodes
@@ -182,14 +183,14 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
     const int32_t* __restrict__ order) {
   extern __shared__ __align__(16) uint32_t smem32[];
   const int words = (n + 31) >> 5;
-  SelectSharedWide<SEL_NT> sh;
+  SelectSharedWide<SEL_NT, WIDE_MU> sh;
   sh.taken = smem32;
   sh.tkey = reinterpret_cast<int32_t*>(smem32 + words);
-  sh.tval = smem32 + words + SelectWideTable<SEL_NT>::entries;
-  sh.s_off = sh.tval + SelectWideTable<SEL_NT>::entries;
+  sh.tval = smem32 + words + SelectWideTable<SEL_NT, WIDE_MU>::entries;
+  sh.s_off = sh.tval + SelectWideTable<SEL_NT, WIDE_MU>::entries;
   sh.s_len = sh.s_off + 64;
   sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
-  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * (SEL_NT / 64));
+  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + WIDE_MU * (SEL_NT / 64));
 
   const int q = order ? order[blockIdx.x] : (int)blockIdx.x, tid = threadIdx.x;
   const int m = budget_of(keep[(size_t)q * keep_stride], n);
@@ -214,10 +215,10 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
     return;
   }
   for (int i = tid; i < words; i += SEL_NT) sh.taken[i] = 0u;
-  for (int i = tid; i < SelectWideTable<SEL_NT>::entries; i += SEL_NT) { sh.tkey[i] = -1; sh.tval[i] = 0xFFFFFFFFu; }
+  for (int i = tid; i < SelectWideTable<SEL_NT, WIDE_MU>::entries; i += SEL_NT) { sh.tkey[i] = -1; sh.tval[i] = 0xFFFFFFFFu; }
   for (int h = tid; h < H; h += SEL_NT) out[h] = hf.hnodes[h];
   __syncthreads();
-  select_block_wide<SEL_NT>(z, K, L, n, total - H, dir, ids, global_rank, sh,
+  select_block_wide<SEL_NT, WIDE_MU>(z, K, L, n, total - H, dir, ids, global_rank, sh,
                             codes ? codes + (size_t)q * L : nullptr, out + H, H ? hf.hslot : nullptr);
   if (rb.part_idx) partition_rows<SEL_NT>(out, total, rb, q, z, sh.tval);
 }
@@ -292,7 +293,7 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
     SLONN_HIP(hipGetLastError());
     return SLONN_OK;
   }
-  const size_t lds = ((size_t)((n + 31) >> 5) + SelectSharedWide<SEL_NT>::words_besides_bitmap) * 4;
+  const size_t lds = ((size_t)((n + 31) >> 5) + SelectSharedWide<SEL_NT, WIDE_MU>::words_besides_bitmap) * 4;
   if (lds > (size_t)max_lds)
     SLONN_FAIL(SLONN_EUNSUPPORTED, "select: layer with %d nodes needs %zu bytes of LDS, device grants %d",
                n, lds, max_lds);
@@ -322,7 +323,7 @@ int launch_order_by_budget(const float* keep, int keep_stride, int B, int32_t* o
 }
 
 bool select_fills_row_blocks(int n, int max_lds) {
-  return ((size_t)((n + 31) >> 5) + SelectSharedWide<SEL_NT>::words_besides_bitmap) * 4 <= (size_t)max_lds;
+  return ((size_t)((n + 31) >> 5) + SelectSharedWide<SEL_NT, WIDE_MU>::words_besides_bitmap) * 4 <= (size_t)max_lds;
 }
 
 int launch_fill_iota(int32_t* idx, int stride, int32_t* cnt, int n, int B, hipStream_t s) {

@@ -188,39 +188,40 @@ __device__ __forceinline__ void select_block(const float* z, int K, int L_, int 
 // output nodes): one BIT per node records the nodes taken in earlier rounds, and the nodes of
 // the current round meet in a small open-addressing table in LDS (node id -> smallest slot
 // number of the round), which is emptied again after each round.
-// Round table: a power of two of entries, at least twice the SELECT_MU * NT slots of a round.
-template <int NT>
+// Round table: a power of two of entries, at least twice the MU * NT slots of a round.
+template <int NT, int MU = SELECT_MU>
 struct SelectWideTable {
-  static constexpr int bits = (SELECT_MU * NT * 2 <= 4096) ? 12 : 13;
+  static constexpr int bits = (MU * NT * 2 <= 4096) ? 12 : 13;
   static constexpr int entries = 1 << bits;
-  static_assert(SELECT_MU * NT * 2 <= entries, "round table too small");
+  static_assert(MU * NT * 2 <= entries, "round table too small");
 };
 
-template <int NT>
+template <int NT, int MU = SELECT_MU>
 struct SelectSharedWide {
   uint32_t* taken;               // [(n + 31) / 32] bitmap
-  int32_t* tkey;                 // [SelectWideTable<NT>::entries] node id or -1
-  uint32_t* tval;                // [SelectWideTable<NT>::entries] smallest slot of the round
+  int32_t* tkey;                 // [SelectWideTable<NT, MU>::entries] node id or -1
+  uint32_t* tval;                // [SelectWideTable<NT, MU>::entries] smallest slot of the round
   uint32_t* s_off;               // [64]
   uint32_t* s_len;               // [64]
-  int* wave_cnt;                 // [SELECT_MU * NT/64]
+  int* wave_cnt;                 // [MU * NT/64], the first NT/64 in use
   uint32_t* s_misc;              // [4]
   static constexpr int words_besides_bitmap =
-      2 * SelectWideTable<NT>::entries + 64 + 64 + SELECT_MU * (NT / 64) + 4;
+      2 * SelectWideTable<NT, MU>::entries + 64 + 64 + MU * (NT / 64) + 4;
 };
 
 // taken[] must be zero and tkey[] = -1, tval[] = 0xFFFFFFFF on entry (caller + barrier).
-template <int NT>
+// Slots, rounds and compaction as in select_merge (a thread takes consecutive slots; positions
+// from one count per thread); a third barrier per round lets the round table be emptied.
+template <int NT, int MU = SELECT_MU>
 __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_, int n, int m,
                                                   const uint32_t* __restrict__ dir,
                                                   const int32_t* __restrict__ ids,
                                                   const int32_t* __restrict__ global_rank,
-                                                  const SelectSharedWide<NT>& sh, uint32_t* codes_row,
+                                                  const SelectSharedWide<NT, MU>& sh, uint32_t* codes_row,
                                                   int32_t* out, const int16_t* hskip = nullptr) {
-  constexpr int TABLE = SelectWideTable<NT>::entries;
-  constexpr int TBITS = SelectWideTable<NT>::bits;
+  constexpr int TABLE = SelectWideTable<NT, MU>::entries;
+  constexpr int TBITS = SelectWideTable<NT, MU>::bits;
   constexpr int NW = NT / 64;
-  constexpr int MU = SELECT_MU;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 
@@ -250,23 +251,22 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
   per = per < 1 ? 1 : (per > MU ? MU : per);
   int count = 0;
   static_assert(MU * NT + 64 <= 16384, "round too large for the multiplicative division");
-  const uint32_t magic = ((1u << 20) + L - 1) / L;      // see select_block
+  static_assert(MU <= 32, "a thread's first occurrences are kept in a 32-bit mask");
+  const uint32_t magic = ((1u << 20) + L - 1) / L;      // see select_merge
   for (unsigned long long base = 0; base < nslots && count < m; base += (unsigned long long)NT * per) {
     const uint32_t r_base = (uint32_t)(base / L), rem_base = (uint32_t)(base - (unsigned long long)r_base * L);
+    const uint32_t rel0 = tid * per;                     // slot numbers relative to the round
+    const uint32_t off = rem_base + rel0;
+    const uint32_t dr = (uint32_t)(((unsigned long long)off * magic) >> 20);
+    uint32_t r = r_base + dr, b = off - dr * L;
     int node[MU], cell[MU];
-    uint32_t rel[MU];                      // slot number relative to the round
     bool valid[MU];
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
-      rel[u] = u * NT + tid;
-      const unsigned long long slot = base + rel[u];
-      const uint32_t off = rem_base + rel[u];
-      const uint32_t dr = (uint32_t)(((unsigned long long)off * magic) >> 20);
-      const uint32_t r = r_base + dr;
-      const uint32_t b = off - dr * L;
-      valid[u] = u < per && slot < nslots && r < sh.s_len[b];
+      valid[u] = u < per && base + rel0 + u < nslots && r < sh.s_len[b];
       node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
       cell[u] = 0;
+      if (++b == L) { b = 0; ++r; }
     }
     if (hskip) {
 #pragma unroll
@@ -283,60 +283,42 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
           if (k == -1 || k == node[u]) break;
           h = (h + 1) & (TABLE - 1);
         }
-        atomicMin(&sh.tval[h], rel[u]);
+        atomicMin(&sh.tval[h], rel0 + u);
         cell[u] = (int)h;
       }
     }
     __syncthreads();
-    bool first[MU];
-    unsigned long long votes[MU];
+    uint32_t firsts = 0;
+#pragma unroll
+    for (int u = 0; u < MU; ++u)
+      if (valid[u] && sh.tval[cell[u]] == rel0 + u) firsts |= 1u << u;
+    const int mine = __popc(firsts);
+    int before = 0, in_wave = 0;
+#pragma unroll
+    for (int bit = 0; (1 << bit) <= MU; ++bit) {
+      const unsigned long long has = __ballot((mine >> bit) & 1);
+      before += __popcll(has & below) << bit;
+      in_wave += __popcll(has) << bit;
+    }
+    if (lane == 0) sh.wave_cnt[wave] = in_wave;
+    __syncthreads();
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const int c = sh.wave_cnt[w];
+      before += (w < wave) ? c : 0;
+      total += c;
+    }
+    int pos = count + before;
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
-      first[u] = valid[u] && sh.tval[cell[u]] == rel[u];
-      votes[u] = __ballot(first[u]);
-      if (lane == 0) sh.wave_cnt[u * NW + wave] = __popcll(votes[u]);
-    }
-    __syncthreads();
-    if (NW > 4) {              // exclusive prefix over the wave counts in slot order (see select_block)
-      if (wave == 0) {
-        const int c = lane < MU * NW ? sh.wave_cnt[lane] : 0;
-        int incl = c;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          const int up = __shfl_up(incl, o);
-          if (lane >= o) incl += up;
-        }
-        if (lane < MU * NW) sh.wave_cnt[lane] = incl - c;
-        if (lane == 63) sh.s_misc[1] = (uint32_t)incl;
-      }
-      __syncthreads();
-#pragma unroll
-      for (int u = 0; u < MU; ++u) {
-        if (first[u]) {
-          const int pos = count + sh.wave_cnt[u * NW + wave] + __popcll(votes[u] & below);
-          if (pos < m) out[pos] = node[u];
-          atomicOr(&sh.taken[node[u] >> 5], 1u << (node[u] & 31));
-        }
-      }
-      count += (int)sh.s_misc[1];
-    } else {
-#pragma unroll
-      for (int u = 0; u < MU; ++u) {
-        int before = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-          const int c = sh.wave_cnt[u * NW + w];
-          before += (w < wave) ? c : 0;
-          total += c;
-        }
-        if (first[u]) {
-          const int pos = count + before + __popcll(votes[u] & below);
-          if (pos < m) out[pos] = node[u];
-          atomicOr(&sh.taken[node[u] >> 5], 1u << (node[u] & 31));
-        }
-        count += total;
+      if ((firsts >> u) & 1u) {
+        if (pos < m) out[pos] = node[u];
+        ++pos;
+        atomicOr(&sh.taken[node[u] >> 5], 1u << (node[u] & 31));
       }
     }
+    count += total;
 #pragma unroll
     for (int u = 0; u < MU; ++u)
       if (valid[u]) { sh.tkey[cell[u]] = -1; sh.tval[cell[u]] = 0xFFFFFFFFu; }
