@@ -8,6 +8,8 @@
 // each wave a (BM/2) x (BN/2) sub-tile made of 32x32 MFMA blocks.  K is walked in
 // chunks of 32 staged through LDS; the next chunk's global loads are issued before
 // the current chunk's MFMAs so their latency hides behind the matrix work.
+#include <algorithm>
+
 #include "slonn_internal.h"
 
 namespace slonn {
@@ -270,9 +272,13 @@ static int dense_split_factor(int B, int n, int d) {
   return S;
 }
 
+// Scratch for the slices: an upper bound that never shrinks as the batch grows (a caller may size
+// its workspace for the largest batch and run smaller ones): at most 8 slices of at most 128
+// tiles of 32 x 32 sums.
 size_t dense_split_workspace_bytes(int B, int n, int d) {
-  const int S = dense_split_factor(B, n, d);
-  return S > 1 ? (size_t)S * B * n * sizeof(float) : 0;
+  if (d < 2048) return 0;
+  const size_t sums = std::min<size_t>((size_t)B * n, (size_t)128 * 32 * 32);
+  return 8 * sums * sizeof(float);
 }
 
 int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,

@@ -540,6 +540,30 @@ def test_runs_are_bit_reproducible(rt, oracle):
                 assert np.array_equal(a["taps"]["z"][l], b["taps"]["z"][l])
 
 
+def test_workspace_for_a_large_batch_serves_smaller_ones(rt, oracle):
+    """A workspace sized for the largest batch must serve every smaller one: the size never
+    shrinks as the batch grows (also where a small batch uses scratch a large one does not: the
+    split reduction of a skinny output layer), and a pass in the larger workspace gives the
+    bits of a pass in its own."""
+    import torch
+    from paper_2204_08400_amd import slonn
+    dims = (48, 2048, 128)
+    layers, net, _ = make_case(oracle, dims, 4, 3, seed=77, hashed=[0], N_build=64)
+    g = _gpu_net(rt, layers, net)
+    g.set_path("layers")
+    sizes = [slonn.slonn_workspace_bytes(g.model, b) for b in (1, 2, 7, 32, 64, 65, 256, 1024, 4096)]
+    assert sizes == sorted(sizes), sizes
+    X = torch.from_numpy(make_queries(dims, 512, seed=9)).cuda()
+    slonn.slonn_profile_begin(16)
+    own = to_numpy_result(g.sparse_forward(X, 0.5))           # 64 tiles of 32 x 32: the output layer splits its reduction
+    assert slonn.slonn_profile_end()["dense"][1] == 1
+    g.workspace(4096)
+    big = to_numpy_result(g.sparse_forward(X, 0.5))
+    assert np.array_equal(own["out"], big["out"]) and np.array_equal(own["argmax"], big["argmax"])
+    ref = net.sparse_forward(X.cpu().numpy(), 0.5)
+    assert_close_rows(own["out"], ref["out"], None, "skinny output layer with split reduction")
+
+
 def test_argument_errors_on_device(rt, oracle):
     import torch
     from paper_2204_08400_amd import slonn
