@@ -344,8 +344,7 @@ int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, cons
   ProfScope prof_(SLONN_PROF_TILES, s);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
   // 128 x 128 tiles with eight wavefronts once they fill the chip (each weight tile is fetched
-  // half as often: C3 batch 1024 190 -> 160 us per layer); 64 x 128 tiles with four, two
-  // workgroups per compute unit, for smaller batches
+  // half as often: C3 batch 1024 190 -> 160 us per layer)
   const bool big = (long)((B + 127) / 128) * ((n + TN - 1) / TN) >= 256;
   const bool wide = (long)((B + 127) / 128) * ((n + 255) / 256) >= 256;
 #define SLONN_LAUNCH_TILES(TQ_, TN_, WP_, NT_)                                                                        \
@@ -358,7 +357,10 @@ int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, cons
                        dim3(NT_), lds, s, X3, Wp, bias, mask, flags, Y, ldy, B, n, d, a);                       \
   }
   if (w_parts == 3) {
-    if (big) SLONN_LAUNCH_TILES(128, 128, 3, 512) else SLONN_LAUNCH_TILES(64, 128, 3, 256)
+    // below that 64 x 64 tiles with four wavefronts: four times as many workgroups (C3 tiles per
+    // step, 64 x 128 against 64 x 64: batch 256 348 -> 213 us, batch 512 351 -> 340, batch 768
+    // 508 -> 456; at batch 1024 the 128 x 128 tiles take 458 us, 64 x 64 tiles 596)
+    if (big) SLONN_LAUNCH_TILES(128, 128, 3, 512) else SLONN_LAUNCH_TILES(64, 64, 3, 256)
   } else {
     // one weight part: twice the node strip per wavefront keeps the LDS reads per MFMA down
     if (wide) SLONN_LAUNCH_TILES(128, 256, 1, 512) else if (big) SLONN_LAUNCH_TILES(128, 128, 1, 512)
@@ -392,7 +394,7 @@ int launch_dense_tiles(const uint16_t* Wp, int w_parts, const float* bias, const
                        dim3(NT_), lds, s, X3, Wp, bias, mask, flags, Y, ldy, B, n, d, a);                       \
   }
   if (w_parts == 3) {
-    if (big) SLONN_LAUNCH_TILES(128, 128, 3, 512) else SLONN_LAUNCH_TILES(64, 128, 3, 256)
+    if (big) SLONN_LAUNCH_TILES(128, 128, 3, 512) else SLONN_LAUNCH_TILES(64, 64, 3, 256)
   } else {
     // one weight part: twice the node strip per wavefront keeps the LDS reads per MFMA down
     if (wide) SLONN_LAUNCH_TILES(128, 256, 1, 512) else if (big) SLONN_LAUNCH_TILES(128, 128, 1, 512)

@@ -604,11 +604,13 @@ namespace {
 // Masked tiles serve 128 queries when their mean list is at least this share of the layer
 // (below it the per-query gather, whose cost grows with batch x budget, is cheaper than the
 // tiles, whose cost per layer is about constant while they fit the chip once: measured
-// break-even on 4096-wide fp32 layers 0.2 at batch 256, 0.12 at 512, 0.1 at 1024).
+// break-even on 4096-wide fp32 layers about 0.15 at batch 256, 0.12 at 512, 0.1 at 1024; at batch
+// 128 it lies near 0.35, and the two launches that find nothing to serve cost every smaller
+// budget 13 us per step: the tiles start at batch 256).
 // bf16 weights (three MFMAs per block; the alternative is the union of 16 queries' rows on the
 // same cores, whose cost follows the union's size)
 constexpr int BF16_TILES_MIN_KEEP_PERMILLE = 100;
-int masked_tiles_min_keep_permille(int B) { return B >= 1024 ? 100 : (B >= 512 ? 120 : 200); }
+int masked_tiles_min_keep_permille(int B) { return B >= 1024 ? 100 : (B >= 512 ? 120 : 150); }
 
 struct PolicyHook {
   const slonn_policy* p = nullptr;
@@ -865,7 +867,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         // on the matrix cores (decided per group on the device); the rest is gathered per query.
         const int32_t* gflag = nullptr;
         const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);   // workgroups of the tile kernel
-        if (L.W3 && mtiles >= 128 && out && !yc && m->path_grouped) {
+        if (L.W3 && B >= 256 && mtiles >= 64 && out && !yc && m->path_grouped) {
           // fp32 layer with split weights: masked tiles on the bf16 matrix cores
           int32_t* flags = nullptr;
           TilesReuse tr;
