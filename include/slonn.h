@@ -236,7 +236,7 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
  * query q / layer l uses keep[q*keep_qstride + l*keep_lstride] (0 strides broadcast;
  * the paper uses one k per query for all layers: keep_lstride = 0).
  * Numerics: hash codes and active sets do not depend on the batch size or the path (the
- * projections are summed in fp64, or for batches from 512 as exact integer sums of fixed-
+ * projections are summed in fp64, or for batches from 256 as exact integer sums of fixed-
  * point digits with every sign certified; only a projection within about 1e-13 of zero can
  * fall either way).  A selected node's output is act(w . x + b) in fp32-class arithmetic:
  * fp32 FMA chains, or - large batches of large layers - exact partial products of bf16 parts

@@ -53,7 +53,8 @@ __global__ void split3_kernel(const float* __restrict__ X, int64_t ldx, int d, u
 }
 
 // One workgroup per query.  The 128 queries of a tile are served by the tile kernel when they
-// list at least min_pairs (query, node) pairs together (every workgroup adds up its tile's list
+// list at least min_per_query (query, node) pairs per query of the tile together (the last tile
+// of a batch may hold fewer than 128 queries; every workgroup adds up its tile's list
 // lengths itself); flags holds that decision once per 16 queries, the unit the per-query gather
 // skips by.  For a served query: mask[q][w] bit j = node 32 w + j is in the query's list and is
 // not a hash node (skip_hslot entry >= 0: its output is its projection, written here from Z when
@@ -65,7 +66,7 @@ __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restric
                                                        const float* __restrict__ Z, int H, int relu,
                                                        float* __restrict__ Y, int ldy,
                                                        uint32_t* __restrict__ mask, int32_t* __restrict__ flags,
-                                                       long long min_pairs, const float* __restrict__ X, int ldx,
+                                                       long long min_per_query, const float* __restrict__ X, int ldx,
                                                        int d, uint16_t* __restrict__ X3) {
   extern __shared__ uint32_t bits[];
   __shared__ int served;
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restric
     long long sum = 0;
     for (int i = tid; i < TM && q0 + i < B; i += 64) sum += cnt[q0 + i];
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-    const int f = sum >= min_pairs ? 1 : 0;
+    const int f = sum >= min_per_query * min(TM, B - q0) ? 1 : 0;
     if (tid == 0) served = f;
     if (q == q0 && tid < TM / 16) flags[q / 16 + tid] = f;
   }
@@ -336,9 +337,9 @@ int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, cons
   {
     ProfScope prof_(SLONN_PROF_SELECT, s);
     // the tile kernel serves 128 queries when they list at least this many pairs together
-    const long long min_pairs = (long long)TM * n * min_keep_permille / 1000;
+    const long long min_per_query = (long long)n * min_keep_permille / 1000;
     hipLaunchKernelGGL(pair_mask_kernel, dim3(B), dim3(256), (size_t)words * 4, s, active, cnt, idx_stride, B, n,
-                       ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, mask, flags, min_pairs, X, ldx, d, X3);
+                       ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, mask, flags, min_per_query, X, ldx, d, X3);
     SLONN_HIP(hipGetLastError());
   }
   ProfScope prof_(SLONN_PROF_TILES, s);

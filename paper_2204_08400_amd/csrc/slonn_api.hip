@@ -42,8 +42,9 @@ namespace {
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 // from this batch on the hash projections run on the int8 matrix cores (below it the fp64 kernels
-// are latency-bound anyway and the slicing pass would not pay)
-constexpr int HASH_INT_MIN_BATCH = 512;
+// are latency-bound anyway and the slicing pass does not pay; C3 hash per step, fp64 against int8:
+// batch 128 49 / 88 us, 192 60 / 91, 256 118 / 94, 384 120 / 105)
+constexpr int HASH_INT_MIN_BATCH = 256;
 
 // up to GATHER_ROW_MAX_BATCH queries the selected rows are fetched by one workgroup each
 // (launch_gather_forward); beyond it large layers are walked in row blocks shared between the
@@ -606,11 +607,13 @@ namespace {
 // tiles, whose cost per layer is about constant while they fit the chip once: measured
 // break-even on 4096-wide fp32 layers about 0.15 at batch 256, 0.12 at 512, 0.1 at 1024; at batch
 // 128 it lies near 0.35, and the two launches that find nothing to serve cost every smaller
-// budget 13 us per step: the tiles start at batch 256).
+// budget 13 us per step: the tiles start at batch 160, where three rows of 64 x 64 tiles cost what
+// they cost at batch 192 and the per-query gather has lost the XCD-aware placement of its row
+// blocks).
 // bf16 weights (three MFMAs per block; the alternative is the union of 16 queries' rows on the
 // same cores, whose cost follows the union's size)
 constexpr int BF16_TILES_MIN_KEEP_PERMILLE = 100;
-int masked_tiles_min_keep_permille(int B) { return B >= 1024 ? 100 : (B >= 512 ? 120 : 150); }
+int masked_tiles_min_keep_permille(int B) { return B >= 1024 ? 100 : (B >= 512 ? 120 : (B >= 256 ? 150 : 200)); }
 
 struct PolicyHook {
   const slonn_policy* p = nullptr;
@@ -867,7 +870,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         // on the matrix cores (decided per group on the device); the rest is gathered per query.
         const int32_t* gflag = nullptr;
         const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);   // workgroups of the tile kernel
-        if (L.W3 && B >= 256 && mtiles >= 64 && out && !yc && m->path_grouped) {
+        if (L.W3 && B >= 160 && mtiles >= 64 && out && !yc && m->path_grouped) {
           // fp32 layer with split weights: masked tiles on the bf16 matrix cores
           int32_t* flags = nullptr;
           TilesReuse tr;
