@@ -3,7 +3,8 @@
 // the first m distinct nodes in rank-major, table-minor order, continuing down the
 // whole-set ranking if the lists run out.
 //
-// Two kernels, both one 256-thread workgroup per query (select_block.h): select_block_kernel
+// Two kernels, both one workgroup per query (select_block.h; 256 threads, 1024 for batches of at
+// most one query per compute unit): select_block_kernel
 // keeps a 4-byte first-occurrence entry per node in LDS; select_wide_kernel, for layers too
 // wide for that (a 100 000-node output layer would need 400 KB), keeps one bit per node
 // plus a small per-round table.  Both can also regroup the finished list by weight-row
@@ -24,7 +25,10 @@ __device__ __forceinline__ int budget_of(float keep, int n) {
 }
 
 constexpr int SEL_NT = 256;      // workgroup size for real batches
-constexpr int SEL_NT_BIG = 1024; // few queries: four times as many slots per round
+constexpr int SEL_NT_BIG = 1024; // up to one query per compute unit: four times as many threads per query
+// (select per step with 256- against 1024-thread workgroups: C3 batch 128 75 / 51 us, batch 256
+// 98 / 76, batch 512 111 / 116; C5 batch 128 407 / 245, batch 256 424 / 309)
+constexpr int SEL_BIG_MAX_BATCH = 256;
 constexpr int WIDE_MU = 4;       // slots per thread per round of the kernel for very wide layers (1024 per round)
 
 // Regroup a finished list by weight-row block (counting sort; the order inside a group does
@@ -277,7 +281,7 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
   const size_t lds_block = ((size_t)n + SelectShared<SEL_NT, BlockMU<SEL_NT>::value>::words_besides_prio) * 4;
   if (lds_block <= (size_t)max_lds) {
     const RowBlocking rbv = rb ? *rb : RowBlocking{};
-    if (B <= 64) {
+    if (B <= SEL_BIG_MAX_BATCH) {
       if (lds_block > 65536)
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
@@ -310,7 +314,7 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
 // the largest budgets (the longest merges) should start first.
 bool select_wants_order(int n, int B, int max_lds, int n_cu) {
   const size_t lds_block = ((size_t)n + SelectShared<SEL_NT, BlockMU<SEL_NT>::value>::words_besides_prio) * 4;
-  if (lds_block > (size_t)max_lds || B <= 64) return false;
+  if (lds_block > (size_t)max_lds || B <= SEL_BIG_MAX_BATCH) return false;
   const size_t per_cu = std::min<size_t>(8, std::max<size_t>(1, ((size_t)160 << 10) / lds_block));
   return (size_t)B > per_cu * (size_t)n_cu;
 }

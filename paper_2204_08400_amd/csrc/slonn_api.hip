@@ -45,6 +45,13 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 // are latency-bound anyway and the slicing pass does not pay; C3 hash per step, fp64 against int8:
 // batch 128 49 / 88 us, 192 60 / 91, 256 118 / 94, 384 120 / 105)
 constexpr int HASH_INT_MIN_BATCH = 256;
+// ... and from batch 64 on where the projection is large (C5, 768 hash rows of 8192 elements, at
+// batch 128: 64 us per layer on the fp64 cores)
+constexpr int HASH_INT_MIN_BATCH_LARGE = 64;
+constexpr long long HASH_INT_LARGE_WORK = 1ll << 29;      // batch x hash rows x row length
+inline bool hash_int_pays(int B, int H, int d) {
+  return B >= HASH_INT_MIN_BATCH || (B >= HASH_INT_MIN_BATCH_LARGE && (long long)B * H * d >= HASH_INT_LARGE_WORK);
+}
 
 // up to GATHER_ROW_MAX_BATCH queries the selected rows are fetched by one workgroup each
 // (launch_gather_forward); beyond it large layers are walked in row blocks shared between the
@@ -114,7 +121,7 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   for (const Layer& l : m->layers) dsplit = std::max(dsplit, dense_split_workspace_bytes(B, l.d_out, l.d_in));
   w->dense_split = dsplit ? take(dsplit) : nullptr;
   size_t hint = 0;
-  if (B >= HASH_INT_MIN_BATCH)
+  if (B >= HASH_INT_MIN_BATCH_LARGE)
     for (const Layer& l : m->layers)
       if (l.Whd) hint = std::max(hint, hash_int_workspace_bytes(B, l.H(), l.d_in));
   w->hash_int = hint ? take(hint) : nullptr;
@@ -783,7 +790,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       // unless the policy kernel needs the projections first)
       HashSplit split;
       const bool policy_here = hook && l == hook->layer;
-      if (L.Whd && w.hash_int && B >= HASH_INT_MIN_BATCH)
+      if (L.Whd && w.hash_int && hash_int_pays(B, L.H(), L.d_in))
         rc = launch_hash_project_int(cur, ldcur, L.Wh, L.Whd, L.ewh, L.bh, z, B, L.H(), L.d_in, m->hash_margin,
                                      w.hash_int, s);
       else
@@ -807,8 +814,10 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
                             reinterpret_cast<uintptr_t>(L.W) % 16 == 0 && reinterpret_cast<uintptr_t>(cur) % 16 == 0;
       // Large batches of a bf16-weight layer: every group of 16 queries is evaluated on the bf16
       // matrix cores; no per-query gather runs, so the lists are not regrouped by row block.
+      // (C5 per step, row-block gather against tiles + unions: batch 64 866 / 2677 us, batch 128
+      // 1391 / 1383, batch 192 1873 / 1441: from batch 160.)
       const long gtiles = (long)((B + 15) / 16) * ((L.d_out + 127) / 128);
-      const bool all_grouped = gtiles >= 1024 && out && !(is_last && Y->val) && m->path_grouped && rows_vec &&
+      const bool all_grouped = B >= 160 && gtiles >= 640 && out && !(is_last && Y->val) && m->path_grouped && rows_vec &&
                                grouped_supported(L.d_out, m->max_lds_bytes) &&
                                grouped_uses_bf16_cores(L.W, L.w_dtype, L.d_in);
       if (!all_grouped && B >= ROW_BLOCK_MIN_BATCH && rows_vec && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20) &&
