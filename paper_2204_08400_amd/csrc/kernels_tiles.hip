@@ -18,8 +18,10 @@
 //   pair_mask_kernel     per 128 queries the decision whether the tile kernel or the per-query
 //                        gather serves them; for served queries one bit per (query, node) pair
 //                        of the active lists and the activations in three parts.
-//   masked_tiles_kernel  128 (or 64) queries x 128 nodes per workgroup, eight (four) wavefronts
-//                        as 2 query halves x 4 (2) node strips; chunks of 32 elements double-
+//   masked_tiles_kernel  128 x 128 (query x node) tiles per workgroup with eight wavefronts as 2
+//                        query halves x 4 node strips (128 x 256 with one weight part), or 64 x
+//                        64 (64 x 128) with four for batches that would not fill the chip with
+//                        the large tiles; chunks of 32 elements double-
 //                        buffered in LDS, the next chunks' global loads in flight during the
 //                        MFMAs; only selected pairs are written.
 #include <algorithm>
