@@ -237,6 +237,28 @@ def test_edge_cases(rt, oracle, path):
                                    slonn.make_output(), None, g.workspace(1))
 
 
+@pytest.mark.parametrize("w_dtype", [wl.W_F32, wl.W_BF16], ids=["f32", "bf16"])
+def test_few_queries_take_a_workgroup_per_row(rt, oracle, w_dtype):
+    """Up to six queries every selected row of 4 KB or more is fetched by a workgroup of its own
+    (no staging in LDS, 4 partial sums per row added in a fixed order); batches 1, 3 and 6, an
+    activated layer with rows of 2048 elements and the 40-node output layer with the identity
+    list, against the oracle; batch 7 takes the other kernels and must agree as well."""
+    from paper_2204_08400_amd import slonn
+    dims = (2048, 2304, 40)
+    layers, net, _ = make_case(oracle, dims, 5, 6, seed=91, hashed=[0], N_build=96, w_dtype=w_dtype,
+                               kind="clip3")
+    g = _gpu_net(rt, layers, net)
+    Xq = make_queries(dims, 7, seed=92, kind="clip3")
+    keep = np.asarray([0.3, 0.0005, 1.0, 0.11, 0.5, 0.25, 0.2], np.float32)
+    for B in (1, 3, 6, 7):
+        ref = net.sparse_forward(Xq[:B], keep[:B])
+        slonn.slonn_profile_begin(16)
+        got = to_numpy_result(g.sparse_forward(Xq[:B], _keep_tensor(keep[:B]), taps=True))
+        prof = slonn.slonn_profile_end()
+        assert prof["gather"][1] == 2 and prof["tiles"][1] == 0 and prof["dense"][1] == 0, prof
+        _say(f"  batch {B}: {compare_sparse(got, ref, layers, f'row kernel batch {B}')}")
+
+
 @pytest.mark.gpu
 def test_hash_node_choice_matches_oracle(rt, oracle):
     """Section 3.4: per-node activation variance on the device against the oracle's float64
