@@ -618,10 +618,13 @@ def test_argument_errors_on_device(rt, oracle):
         slonn.slonn_workspace_bytes(g.model, (1 << 20) + 1)
 
 
-@pytest.mark.parametrize("w_dtype,d,n", [(wl.W_F32, 512, 4096), (wl.W_F32, 544, 4040), (wl.W_F32, 520, 4096),
-                                         (wl.W_BF16, 1024, 4096), (wl.W_BF16, 1032, 4096)],
-                         ids=["f32-tiles", "f32-tiles-ragged", "f32-rows-not-32", "bf16", "bf16-ragged-rows"])
-def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d, n):
+@pytest.mark.parametrize("w_dtype,d,n,B", [(wl.W_F32, 512, 4096, 519), (wl.W_F32, 544, 4040, 519),
+                                           (wl.W_F32, 520, 4096, 519), (wl.W_BF16, 1024, 4096, 519),
+                                           (wl.W_BF16, 1032, 4096, 519), (wl.W_BF16, 1024, 4096, 1031),
+                                           (wl.W_F32, 512, 4096, 200)],
+                         ids=["f32-tiles", "f32-tiles-ragged", "f32-rows-not-32", "bf16", "bf16-ragged-rows",
+                              "bf16-128x128-tiles", "f32-batch-200"])
+def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d, n, B):
     """Large batch on the per-layer path, evaluation across queries on the matrix cores.
     fp32 rows of a multiple of 32 elements: masked 128 x 128 tiles on the bf16 cores (three
     bf16 parts per operand), decided per 128 queries by their mean budget; other fp32 rows:
@@ -633,7 +636,7 @@ def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d, n):
     layers, net, _ = make_case(oracle, dims, 6, 8, seed=61, hashed=[0], cap=1500, N_build=192, kind="clip3",
                                w_dtype=w_dtype)
     g = _gpu_net(rt, layers, net, path="layers")
-    B = 512 + 7                      # ragged last group
+    # (B = 512 + 7 and 1024 + 7: ragged last group; 200: a last tile of 72 queries)
     X = make_queries(dims, B, seed=62, kind="clip3")
     # third case: the first 128 queries with small budgets (their tile stays on the per-query
     # gather), the others large
