@@ -102,6 +102,30 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
   }
 }
 
+// Will the masked tiles serve query q?  The sum pair_mask_kernel forms from the list lengths of
+// the 128 queries of q's tile, formed here from their keep fractions (a list is as long as its
+// budget, or as the K*L hash nodes at its head if those are more).  red: NT / 64 free words of
+// LDS.  Whole workgroup, same answer in every thread.
+template <int NT>
+__device__ __forceinline__ bool tile_served(const RowBlocking& rb, const float* __restrict__ keep, int keep_stride,
+                                            int n, int H, int q, uint32_t* red) {
+  if (rb.served_min_per_query <= 0) return false;
+  const int q0 = q - q % 128, nq = min(128, rb.B - q0);
+  uint32_t mine = 0;
+  for (int i = threadIdx.x; i < nq; i += NT) {
+    const int m = budget_of(keep[(size_t)(q0 + i) * keep_stride], n);
+    mine += (uint32_t)((m == n || m > H) ? m : H);
+  }
+  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mine;
+  __syncthreads();
+  long long sum = 0;
+#pragma unroll
+  for (int w = 0; w < NT / 64; ++w) sum += red[w];
+  return sum >= rb.served_min_per_query * nq;
+}
+
 // A medium batch leaves the hash projection's reduction split in hs.S partial sums per
 // (query, hash row).  Add them in split order, add the bias, and store the projections of
 // query q for this kernel and for the later readers.  Whole workgroup; ends with a barrier.
@@ -156,7 +180,8 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += NT) out[i] = i;
-    if (rb.part_idx) partition_rows<NT>(out, n, rb, q, z, sh.prio);
+    if (rb.part_idx && !tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
+      partition_rows<NT>(out, n, rb, q, z, sh.prio);
     return;
   }
   // The last wavefront forms the keys and fetches the bucket directory (two dependent memory
@@ -175,7 +200,8 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
   __syncthreads();
   select_merge<NT, MU>(L, n, total - H, ids, global_rank, sh, out + H, hskip);
 
-  if (rb.part_idx) partition_rows<NT>(out, total, rb, q, z, sh.prio);
+  if (rb.part_idx && !tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
+    partition_rows<NT>(out, total, rb, q, z, sh.prio);
 }
 
 __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
@@ -215,7 +241,8 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += SEL_NT) out[i] = i;
-    if (rb.part_idx) partition_rows<SEL_NT>(out, n, rb, q, z, sh.tval);
+    if (rb.part_idx && !tile_served<SEL_NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
+      partition_rows<SEL_NT>(out, n, rb, q, z, sh.tval);
     return;
   }
   for (int i = tid; i < words; i += SEL_NT) sh.taken[i] = 0u;
@@ -224,7 +251,8 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   __syncthreads();
   select_block_wide<SEL_NT, WIDE_MU>(z, K, L, n, total - H, dir, ids, global_rank, sh,
                             codes ? codes + (size_t)q * L : nullptr, out + H, H ? hf.hslot : nullptr);
-  if (rb.part_idx) partition_rows<SEL_NT>(out, total, rb, q, z, sh.tval);
+  if (rb.part_idx && !tile_served<SEL_NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
+    partition_rows<SEL_NT>(out, total, rb, q, z, sh.tval);
 }
 
 // Queries in descending order of their budget (256 classes of the keep fraction; the order inside

@@ -835,6 +835,15 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         rb.yc = is_last ? Y->val : nullptr; rb.ldc = Y->stride;
         rb.relu = act == SLONN_ACT_RELU;
       }
+      // fp32 layer with split weights at a batch that fills the tile kernel: masked tiles follow the
+      // select kernel, which then leaves the queries they will serve out of the regrouping
+      const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);   // workgroups of the tile kernel
+      const bool f32_tiles = rb.part_idx && L.W3 && B >= 160 && mtiles >= 64 && out && !(is_last && Y->val) &&
+                             m->path_grouped;
+      if (f32_tiles) {
+        rb.served_min_per_query = (long long)L.d_out * masked_tiles_min_keep_permille(B) / 1000;
+        rb.B = B;
+      }
       HashFirst hf;
       if (m->hash_first) { hf.hnodes = L.hnodes; hf.hslot = L.hslot; }
       // a batch beyond what the device holds at once starts its longest merges first; with one
@@ -878,12 +887,12 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         // Large batches: groups of 16 queries whose lists overlap enough are evaluated together
         // on the matrix cores (decided per group on the device); the rest is gathered per query.
         const int32_t* gflag = nullptr;
-        const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);   // workgroups of the tile kernel
-        if (L.W3 && B >= 160 && mtiles >= 64 && out && !yc && m->path_grouped) {
-          // fp32 layer with split weights: masked tiles on the bf16 matrix cores
+        if (f32_tiles) {
+          // masked tiles on the bf16 matrix cores; a selected hash node of a served query takes its
+          // output from its projection there (the regrouping step does that for the others)
           int32_t* flags = nullptr;
           TilesReuse tr;
-          tr.hslot = rb.hslot;           // outputs of selected hash nodes were written by the regrouping step
+          tr.hslot = rb.hslot; tr.Z = z; tr.H = L.H(); tr.relu = rb.relu;
           rc = launch_masked_tiles(L.W3, 3, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B, L.d_in, L.d_out,
                                    act, &tr, masked_tiles_min_keep_permille(B), w.tiles, &flags, s);
           if (rc) return rc;

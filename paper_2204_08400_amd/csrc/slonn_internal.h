@@ -175,6 +175,11 @@ struct RowBlocking {
   float* y = nullptr;             // [B][ldy] dense outputs (nullable)
   float* yc = nullptr;            // [B][ldc] outputs in selection order (nullable)
   int ldy = 0, ldc = 0, relu = 0;
+  // > 0: the masked tiles follow and serve every tile of 128 queries whose list lengths add up
+  // to at least this much per query (launch_masked_tiles with the same threshold); the queries
+  // of such a tile are not regrouped.  B: the batch (the last tile may be short).
+  long long served_min_per_query = 0;
+  int B = 0;
 };
 constexpr int MAX_ROW_BLOCKS = 1024;
 
