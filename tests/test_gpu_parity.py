@@ -486,24 +486,28 @@ def test_config_c5_full_width_sampled(rt, oracle):
     B = 2048
     cfg, layers, g, net, Xq = _config_case(rt, "C5", 256, B, list_cap=2459)
     keep = wl.keep_uniform(B, cfg.keep_range[0], cfg.keep_range[1], 6)
-    _say("C5 full width: GPU pass")
-    slonn.slonn_profile_begin(64)
-    res = g.sparse_forward(Xq, _keep_tensor(keep), taps=True)
-    prof = slonn.slonn_profile_end()
-    # tiles + unions per hidden layer
-    assert prof["tiles"][1] == len(cfg.hashed_layers) and prof["gather"][1] == len(cfg.hashed_layers), prof
-    # per hidden layer the select kernel, the pair masks of the tiles and the unions; 2048 select
-    # workgroups do not fit the device at once: one more launch orders them by budget
-    assert prof["select"][1] == 3 * len(cfg.hashed_layers) + 1, prof
-    got = to_numpy_result(res)
-    sample = np.asarray([0, 1, 15, 16, 17, 31, 500, 777, 1023, 1024, 1029, 1500, 2032, 2040, 2046, 2047])
-    _say("C5 full width: oracle on the sampled queries")
-    ref = net.sparse_forward(Xq[sample], keep[sample])
-    sub = {"out": got["out"][sample], "argmax": got["argmax"][sample],
-           "taps": {k: [None if t is None else t[sample] for t in v] for k, v in got["taps"].items()}}
-    rep = compare_sparse(sub, ref, layers, "C5 full width")
-    _say(f"  {rep}")
-    assert rep["tainted"] < len(sample)
+    # the timed batch, and a medium one that takes the same kernels in their other shapes: tiles of
+    # 64 x 128, 1024-thread select workgroups, the integer hash below batch 256 (large projections)
+    for b, sample in ((2048, [0, 1, 15, 16, 17, 31, 500, 777, 1023, 1024, 1029, 1500, 2032, 2040, 2046, 2047]),
+                      (192, [0, 1, 17, 63, 64, 100, 127, 128, 150, 190, 191])):
+        sample = np.asarray(sample)
+        _say(f"C5 full width, batch {b}: GPU pass")
+        slonn.slonn_profile_begin(64)
+        res = g.sparse_forward(Xq[:b], _keep_tensor(keep[:b]), taps=True)
+        prof = slonn.slonn_profile_end()
+        # tiles + unions per hidden layer
+        assert prof["tiles"][1] == len(cfg.hashed_layers) and prof["gather"][1] == len(cfg.hashed_layers), prof
+        # per hidden layer the select kernel, the pair masks of the tiles and the unions; 2048 select
+        # workgroups do not fit the device at once: one more launch orders them by budget
+        assert prof["select"][1] == 3 * len(cfg.hashed_layers) + (1 if b == 2048 else 0), prof
+        got = to_numpy_result(res)
+        _say(f"C5 full width, batch {b}: oracle on the sampled queries")
+        ref = net.sparse_forward(Xq[sample], keep[sample])
+        sub = {"out": got["out"][sample], "argmax": got["argmax"][sample],
+               "taps": {k: [None if t is None else t[sample] for t in v] for k, v in got["taps"].items()}}
+        rep = compare_sparse(sub, ref, layers, f"C5 full width batch {b}")
+        _say(f"  {rep}")
+        assert rep["tainted"] < len(sample)
 
 
 @pytest.mark.parametrize("path", ["auto", "layers"])
