@@ -315,6 +315,15 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
       hipLaunchKernelGGL((select_block_kernel<SEL_NT_BIG>), dim3(B), dim3(SEL_NT_BIG), lds_block, s, Z, K, L, n,
                          dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp, order);
+    } else if (B <= 2 * SEL_BIG_MAX_BATCH || lds_block * 5 > ((size_t)160 << 10)) {
+      // up to two queries per compute unit, or maps so large that at most four workgroups share a
+      // unit: 512 threads (select per step with 256 / 512 threads: C3 batch 512 103 / 92 us, batch
+      // 1024 131 / 137; C5 batch 2048 814 / 766)
+      if (lds_block > 65536)
+        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<512>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
+      hipLaunchKernelGGL((select_block_kernel<512>), dim3(B), dim3(512), lds_block, s, Z, K, L, n, dir,
+                         ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp, order);
     } else {
       if (lds_block > 65536)
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT>),
