@@ -247,6 +247,20 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
                          const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
                          void* stream);
 
+/* slonn_sparse_forward for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, results and kernels, but the per-batch workspace is a static device array of
+ * SLONN_STATIC_SCRATCH_BYTES inside the library, one per GPU, held until the process ends.  The
+ * call allocates nothing (no hipMalloc/hipFree, no host allocation).  ECAP when
+ * slonn_workspace_bytes(m, B) exceeds SLONN_STATIC_SCRATCH_BYTES (nothing is enqueued).  All calls
+ * on one GPU share that GPU's array, which keeps whatever the last call left there (every kernel
+ * clears what it needs to start at zero): calls that overlap on one GPU - from different
+ * streams or threads - race; serialise them.                                                  */
+#define SLONN_STATIC_SCRATCH_BYTES (64u << 20)
+int slonn_sparse_forward_static(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
+                                const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
+                                const slonn_debug_taps* taps, void* stream);
+
 /* ---- Choice of k per query (Section 2: ACLO and LCAO; Section 3.2: Confidence LSH tables,
  * latency profiles; Fig. 2 step 2).  Mechanics only: the confidences c(k, x') of the
  * training inputs (Eq. 3) and the latency profile T(k, beta) are supplied by the caller, and

@@ -7,6 +7,12 @@
 
 #include "slonn_internal.h"
 
+// Scratch memory of slonn_sparse_forward_static: one array per device, placed by the loader when the
+// code object reaches that device and held until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; the address kernels may use is what that call returns,
+// looked up once per device with that device current.
+static __device__ __align__(256) unsigned char scratch[SLONN_STATIC_SCRATCH_BYTES];
+
 namespace slonn {
 
 static thread_local char g_err[512] = "";
@@ -26,6 +32,26 @@ struct Profiler {
   size_t used = 0;
 } g_prof;
 }  // namespace
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+}  // namespace
+
+// Device address of the current device's scratch array (looked up on first use per device).
+int static_scratch(void** out) {
+  int dev = 0;
+  SLONN_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) SLONN_FAIL(SLONN_EUNSUPPORTED, "device ordinal %d beyond %d", dev, MAX_DEVICES);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    SLONN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) SLONN_FAIL(SLONN_EHIP, "hipGetSymbolAddress returned a null address for the scratch array");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return SLONN_OK;
+}
 
 ProfScope::ProfScope(int kind, hipStream_t s) : slot(-1), stream(s) {
   if (!g_prof.on || g_prof.used >= g_prof.start.size()) return;
@@ -271,6 +297,12 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
   if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
     m->n_cu = v;
 
+  // the scratch array of the allocation-free entry point: its address on this device, looked up now
+  // so that the entry point itself has nothing left to set up
+  {
+    void* sp = nullptr;
+    if (static_scratch(&sp) != SLONN_OK) return fail(SLONN_EHIP);
+  }
   // library-owned fp32 copies of the FreeHash rows, gathered once (on the device)
   for (Layer& L : m->layers) {
     if (!L.activated()) continue;
@@ -967,6 +999,23 @@ int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slon
                          const slonn_debug_taps* taps, void* workspace, size_t ws_bytes,
                          void* stream) {
   return forward_impl(m, t, X, B, keep, keep_qstride, keep_lstride, Y, taps, workspace, ws_bytes, stream,
+                      nullptr);
+}
+
+int slonn_sparse_forward_static(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
+                                const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
+                                const slonn_debug_taps* taps, void* stream) {
+  if (!m) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  if (B <= 0 || B > SLONN_MAX_BATCH) SLONN_FAIL(SLONN_EINVAL, "B must be in 1 .. %d", SLONN_MAX_BATCH);
+  Workspace w;
+  plan_workspace(m, B, nullptr, &w);
+  if (w.bytes > (size_t)SLONN_STATIC_SCRATCH_BYTES)
+    SLONN_FAIL(SLONN_ECAP, "a batch of %d needs %zu bytes of scratch memory, the static array holds %zu: use "
+               "slonn_sparse_forward with a caller-provided workspace", B, w.bytes, (size_t)SLONN_STATIC_SCRATCH_BYTES);
+  void* sp = nullptr;
+  int rc = static_scratch(&sp);
+  if (rc) return rc;
+  return forward_impl(m, t, X, B, keep, keep_qstride, keep_lstride, Y, taps, sp, SLONN_STATIC_SCRATCH_BYTES, stream,
                       nullptr);
 }
 

@@ -34,7 +34,9 @@ EXPORTS = [
     "slonn_sparse_forward_aclo",
     "slonn_forward_graph_create", "slonn_forward_graph_launch", "slonn_forward_graph_destroy",
     "slonn_activation_variance", "slonn_sample_hash_nodes", "slonn_model_set_hash_margin",
+    "slonn_sparse_forward_static",
 ]
+STATIC_SCRATCH_BYTES = 64 << 20
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused", "tiles")
 PATH_AUTO, PATH_LAYERS, PATH_FUSED = 0, 1, 2
 
@@ -270,6 +272,16 @@ def slonn_sparse_forward(model: Model, tables: Optional[Tables], X: Input, B: in
         C.byref(taps) if taps is not None else None, C.c_void_p(_ptr(workspace)),
         C.c_size_t(workspace.numel() * workspace.element_size() if workspace is not None else 0),
         C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_sparse_forward_static(model: Model, tables: Optional[Tables], X: Input, B: int, keep,
+                                keep_qstride: int, keep_lstride: int, Y: Output, taps: Optional[DebugTaps],
+                                stream=None):
+    """slonn_sparse_forward on the library's static scratch array: the call allocates nothing."""
+    _check(load().slonn_sparse_forward_static(
+        model.h, tables.h if tables is not None else None, C.byref(X), int(B),
+        C.c_void_p(_ptr(keep)), int(keep_qstride), int(keep_lstride), C.byref(Y),
+        C.byref(taps) if taps is not None else None, C.c_void_p(_stream_ptr(stream))))
 
 
 class Policy:
