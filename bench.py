@@ -2,10 +2,14 @@
 """Benchmark of the SLO-NN hot path on one MI355X.
 
 A step is one pass of the whole path (FreeHash projection, key + bucket lookup + merge,
-gathered-row forward, for every layer) over one batch of synthetic queries that already
-sit in HBM.  Workload: the 784-1024-1024-10 fp32 MLP, K=8, L=16 on both hidden layers,
-batch 256, keep fraction 0.25 (the other keep fractions of that workload, and the dense
-MFMA baseline, are timed briefly and reported beside it).  Prints ONE JSON line.
+gathered-row forward, for every layer) over the WHOLE synthetic query set of the workload,
+processed in batches of B (the last batch is the ragged remainder); inputs, weights and tables
+sit in HBM before the timed region starts.  Headline workload: the largest configuration, the
+deep 1024-8192x6-1000 MLP with bf16 weights, K=12 L=64 on six hidden layers, 20 000 queries
+with one keep fraction per query drawn from U[0.02, 0.3], batch 2048.  Beside it, briefly and
+in the same JSON line: the 3072-4096^3-100 fp32 MLP at batch 1024 and the 784-1024^2-10 fp32
+MLP at batch 256 over their keep-fraction sweeps, each with the full network (all nodes) as
+the baseline every speed-up is quoted against.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -16,29 +20,275 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBPS = 8000.0
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+BF16_PEAK_TFLOPS = 2500.0       # dense bf16 MFMA
+FP32_MFMA_PEAK_TFLOPS = 157.3
+KERNEL_OF_KIND = {"fused": "fused_forward_kernel", "tiles": "masked_tiles_kernel", "gather": "gather_blocked_kernel",
+                  "select": "select_block_kernel", "hash": "hash projection kernels", "dense": "dense_layer_kernel",
+                  "ell": "ell_layer_kernel", "finalize": "finalize_kernel"}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+class Workload:
+    """One configuration set up on the device: weights, hash nodes, tables, the query set cut
+    into batches, output buffers and the workspace."""
+
+    def __init__(self, name, B, args, n_queries=0, n_build=0, top_keep=None):
+        import numpy as np
+        import torch
+        from paper_2204_08400_amd import runtime, slonn, workloads as wl
+        self.np, self.torch, self.slonn, self.wl, self.runtime = np, torch, slonn, wl, runtime
+        self.name, self.args = name, args
+        cfg = self.cfg = wl.CONFIGS[name]
+        self.B = B or cfg.batches[-1]
+        dev = self.dev = torch.device("cuda:0")
+        t0 = time.time()
+        layers = self.layers = wl.make_mlp(cfg.dims, seed=0, w_dtype=cfg.w_dtype, last_act=cfg.last_act)
+        self.n_build = n_build or cfg.n_inputs
+        self.nq = n_queries or cfg.n_inputs
+        X_build = wl.make_inputs(cfg, self.n_build, seed=1)
+        self.X_query = wl.make_inputs(cfg, self.nq, seed=2)
+        log(f"{name}: generated weights, {self.n_build} table-training inputs and {self.nq} queries in {time.time() - t0:.1f}s")
+        ell = self.ell = cfg.input_kind == "ell"
+        if ell:     # wide sparse-input model: first layer stored input-major on the device
+            layers[0].W = np.ascontiguousarray(layers[0].W.T)
+        # hash nodes: variance of the full network's activations on the build set (device dense pass)
+        plain = runtime.Network(layers, first_layer_rows_are_inputs=ell)
+        self.xb = self.to_dev(X_build)
+        dn = plain.dense_forward(self.xb, layer_outs=True)
+        keeps = [k for k in cfg.keeps if k < 1.0] + ([cfg.keep_range[1]] if cfg.keep_range else [])
+        top = max(keeps + ([top_keep] if top_keep else []))
+        for l in cfg.hashed_layers:
+            layers[l].K, layers[l].L = cfg.K, cfg.L
+            # lists never need more entries than the largest budget below d_out that will be asked for
+            layers[l].list_cap = min(layers[l].d_out, int(np.ceil(top * layers[l].d_out)) + 1)
+            layers[l].hash_nodes = runtime.hash_nodes_by_variance(dn["layers"][l], cfg.K, cfg.L,
+                                                                  wl.hash_node_draws(cfg.K, cfg.L, seed=3 + l))
+        del plain, dn
+        self.net = runtime.Network(layers, first_layer_rows_are_inputs=ell)
+        t0 = time.time()
+        self.net.build_tables(self.xb)
+        self.net.set_path(args.path)
+        self.net.set_hash_nodes_always_active(args.hash_nodes_always_active)
+        torch.cuda.synchronize()
+        log(f"{name}: tables built on the device in {time.time() - t0:.2f}s")
+
+        xq = self.xq = self.to_dev(self.X_query)
+        B = self.B
+        self.sizes = [min(B, self.nq - s) for s in range(0, self.nq, B)]      # whole query set, ragged tail included
+        self.batches = []
+        for i, nb in enumerate(self.sizes):
+            s = i * B
+            if ell:
+                self.batches.append(slonn.make_input(idx=xq[0][s:s + nb], val=xq[1][s:s + nb], nnz=xq[2][s:s + nb]))
+            else:
+                self.batches.append(slonn.make_input(x=xq[s:s + nb]))
+        n_last = cfg.dims[-1]
+        self.out_arg = torch.empty(B, dtype=torch.int32, device=dev)
+        if layers[-1].K > 0:      # activated output layer: compact (id, value) output, no dense row
+            self._o = (torch.empty((B, n_last), dtype=torch.int32, device=dev),
+                       torch.empty((B, n_last), dtype=torch.float32, device=dev),
+                       torch.empty(B, dtype=torch.int32, device=dev))
+            self.out = slonn.make_output(idx=self._o[0], val=self._o[1], cnt=self._o[2], stride=n_last,
+                                         argmax=self.out_arg)
+        else:
+            self._o = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+            self.out = slonn.make_output(dense=self._o, argmax=self.out_arg)
+        self.yd = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+        self.ws = self.net.workspace(B)
+        self.stream = torch.cuda.current_stream()
+        self.mixed = None
+        if cfg.keep_range:        # one keep fraction per query (mixed SLOs in one batch)
+            self.mixed_host = wl.keep_uniform(self.nq, cfg.keep_range[0], cfg.keep_range[1], seed=6)
+            self.mixed = torch.from_numpy(self.mixed_host).to(dev)
+
+    def to_dev(self, X):
+        torch, np = self.torch, self.np
+        if self.ell:
+            return tuple(torch.from_numpy(np.ascontiguousarray(a)).to(self.dev) for a in X)
+        return torch.from_numpy(X).to(self.dev)
+
+    # ---- one step = the whole query set ----
+    def step(self, keep_t):
+        s, B = self.slonn, self.B
+        for i, nb in enumerate(self.sizes):
+            if self.mixed is not None:
+                s.slonn_sparse_forward(self.net.model, self.net.tables, self.batches[i], nb,
+                                       self.mixed[i * B:i * B + nb], 1, 0, self.out, None, self.ws, self.stream)
+            else:
+                s.slonn_sparse_forward(self.net.model, self.net.tables, self.batches[i], nb, keep_t, 0, 0,
+                                       self.out, None, self.ws, self.stream)
+
+    def dense_step(self):
+        for i, nb in enumerate(self.sizes):
+            self.slonn.slonn_dense_forward(self.net.model, self.batches[i], nb, self.yd, self.out_arg, None,
+                                           self.ws, self.stream)
+
+    def marker(self):
+        """a kernel nothing else here launches, so that a profiler's dispatch list shows where the
+        timed region starts and ends (--markers)"""
+        a = self.torch.ones(64, dtype=self.torch.float32, device=self.dev)
+        self.torch.nextafter(a, a)
+
+    def timed(self, fn, steps, warm, mark=False):
+        """K steps between two synchronisations; returns (seconds, per-step milliseconds).  The
+        slower of the device clock (events on the launch stream) and the host clock counts."""
+        torch = self.torch
+        for _ in range(warm):
+            fn()
+        if mark:
+            self.marker()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        t0 = time.perf_counter()
+        ev[0].record(self.stream)
+        for i in range(steps):
+            fn()
+            ev[i + 1].record(self.stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        if mark:
+            self.marker()
+        per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+        return max(ev[0].elapsed_time(ev[steps]) / 1e3, wall), per
+
+    def keep_tensor(self, keep):
+        return self.torch.full((1,), float(keep if keep is not None else 1.0), dtype=self.torch.float32,
+                               device=self.dev)
+
+    def time_sparse(self, keep, steps, warm, mark=False):
+        kt = self.keep_tensor(keep)
+        return self.timed(lambda: self.step(kt), steps, warm, mark)
+
+    def profile_sparse(self, keep, steps):
+        """Per-kernel-kind durations over `steps` more steps: every launch bracketed by two HIP events
+        on the launch stream inside the library."""
+        kt = self.keep_tensor(keep)
+        per_step = len(self.sizes) * (12 * len(self.layers) + 8)
+        self.slonn.slonn_profile_begin(steps * per_step)
+        for _ in range(steps):
+            self.step(kt)
+        return self.slonn.slonn_profile_end()
+
+    # ---- the method's own work ----
+    def budgets(self, keep, n):
+        """node budgets of the queries in a layer of n nodes (nearest whole node, at least one)"""
+        np = self.np
+        k = self.mixed_host.astype(np.float64) if keep is None else np.full(self.nq, np.float32(keep), np.float64)
+        return np.clip(np.floor(k * n + 0.5), 1, n)
+
+    def gathered_bytes_per_step(self, keep, activated_only=True):
+        """weight bytes the method must evaluate for the whole query set: budget x row bytes for every
+        activated layer (+ the whole matrix per query for layers computed in full, on request)"""
+        tot = 0.0
+        for lay in self.layers:
+            esz = 4 if lay.w_dtype == self.wl.W_F32 else 2
+            if lay.K > 0:
+                tot += float(self.budgets(keep, lay.d_out).sum()) * lay.d_in * esz
+            elif not activated_only:
+                rows = self.cfg.ell_nnz if (self.ell and lay is self.layers[0]) else lay.d_out
+                cols = lay.d_out if (self.ell and lay is self.layers[0]) else lay.d_in
+                tot += float(self.nq) * rows * cols * esz
+        return tot
+
+    def dense_flops_per_query(self):
+        return 2.0 * sum(l.d_in * l.d_out for l in self.layers if not (self.ell and l is self.layers[0]))
+
+
+def load_traffic(key):
+    """HBM bytes per launch and per step from the committed rocprofv3 counter summaries
+    (profiles/hbm_traffic.json; FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size)."""
+    p = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        return json.load(open(p)).get(key)
+    except Exception:
+        return None
+
+
+def roofline_of(w, keep, prof, steps, secs_per_step, traffic_key):
+    """The dominant kernel of the step against the resource that bounds it."""
+    np = w.np
+    per_step_us = {k: v[0] * 1e3 / steps for k, v in prof.items() if v[1]}
+    dom = max(per_step_us, key=per_step_us.get)
+    ms, n = prof[dom]
+    avg_s = ms / 1e3 / n
+    launches_per_step = n / steps
+    gathered = w.gathered_bytes_per_step(keep)
+    tr = load_traffic(traffic_key) or {}
+    tk = (tr.get("kernels") or {}).get(KERNEL_OF_KIND[dom])
+    traffic = int(tk["fetch_bytes_per_launch"] + tk["write_bytes_per_launch"]) if tk else None
+    hbm_step = tr.get("hbm_bytes_per_step")
+    nominal = gathered / secs_per_step / 1e9
+    common = {"kernel": KERNEL_OF_KIND[dom], "avg_launch_us": round(avg_s * 1e6, 2),
+              "launches_per_step": round(launches_per_step, 2), "share_of_step": round(per_step_us[dom] / sum(per_step_us.values()), 3),
+              "traffic": traffic,
+              "gathered_bytes_per_step": int(gathered),
+              "nominal_gathered_GBps": round(nominal, 1),
+              "nominal_gathered_over_hbm_peak": round(nominal / HBM_PEAK_GBPS, 4),
+              "hbm_bytes_per_step_from_counters": hbm_step,
+              "hbm_GBps_from_counters": round(hbm_step / secs_per_step / 1e9, 1) if hbm_step else None,
+              "hbm_frac_from_counters": round(hbm_step / secs_per_step / 1e9 / HBM_PEAK_GBPS, 4) if hbm_step else None,
+              "traffic_source": (f"profiles/hbm_traffic.json[{traffic_key}] (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at this "
+                                 "workload, scaled by a plain copy; not measured in this run)") if tr else None}
+    if dom == "tiles":
+        # masked tiles on the bf16 matrix cores: one launch per activated layer and batch.  The method's
+        # own flops are 2 d per selected (query, node) pair; the kernel issues every pair of its tiles,
+        # and 3 (bf16 weights) or 6 (fp32 weights in three parts) bf16 products per fp32-class product.
+        act = [l for l in w.layers if l.K > 0]
+        own = sum(2.0 * float(w.budgets(keep, l.d_out).sum()) * l.d_in for l in act)
+        issued = sum(2.0 * w.nq * l.d_in * l.d_out * (3 if l.w_dtype == w.wl.W_BF16 else 6) for l in act)
+        own_l, issued_l = own / (n / steps), issued / (n / steps)
+        r = {"bound": "mfma", "achieved": round(own_l / avg_s / 1e12, 2), "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+             "frac": round(own_l / avg_s / 1e12 / BF16_PEAK_TFLOPS, 4),
+             "method_flops_per_launch": int(own_l), "issued_flops_per_launch": int(issued_l),
+             "issued_TFLOPs": round(issued_l / avg_s / 1e12, 1),
+             "issued_frac": round(issued_l / avg_s / 1e12 / BF16_PEAK_TFLOPS, 4),
+             "note": "achieved = the method's own flops (2 d per selected pair) per launch over the mean launch duration; "
+                     "issued = what the tile kernel executes for them: every (query, node) pair of a served 128-query tile, "
+                     "each fp32-class product as 3 (bf16 weights) or 6 (fp32 weights) bf16 MFMA products.  "
+                     "nominal_gathered_GBps is the north-star figure (budget x row bytes over the step time); it exceeds the "
+                     "HBM peak because a weight tile is fetched once per 128 queries, so it is not a roofline fraction"}
+    else:
+        # gather-type kernels: bytes of the rows this kernel kind evaluates per launch
+        per_launch = w.gathered_bytes_per_step(keep, activated_only=(dom != "fused")) / launches_per_step
+        if dom in ("select", "hash", "dense", "finalize", "ell"):
+            per_launch = None
+        ach = per_launch / avg_s / 1e9 if per_launch else None
+        r = {"bound": "hbm", "achieved": round(ach, 1) if ach else None, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+             "frac": round(ach / HBM_PEAK_GBPS, 4) if ach else None,
+             "algorithmic_bytes_per_launch": int(per_launch) if per_launch else None,
+             "note": "achieved = the weight rows the method evaluates per launch (budget x row bytes; whole matrix for layers "
+                     "computed in full) over the mean launch duration.  Where the weights fit the 4 MiB L2 slices / 256 MiB "
+                     "Infinity Cache the rows are served from cache to many queries and the figure is not bounded by the HBM "
+                     "peak: hbm_*_from_counters is what reached HBM"}
+    r.update(common)
+    return r, per_step_us
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--keep", type=float, default=0.25)
-    ap.add_argument("--config", default="C2")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--keep", type=float, default=0.25, help="keep fraction of the headline (configurations with one keep per query ignore it)")
+    ap.add_argument("--config", default="C5")
     ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--queries", type=int, default=0, help="size of the query set (default: the configuration's)")
+    ap.add_argument("--build-inputs", type=int, default=0, help="size of the table-training set (default: the configuration's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="headline only: no keep sweep, no dense baseline, no other workloads")
+    ap.add_argument("--no-others", action="store_true", help="skip the other workloads reported beside the headline")
     ap.add_argument("--path", default="auto", choices=["auto", "layers", "fused"])
     ap.add_argument("--hash-nodes-always-active", action="store_true",
                     help="Section 3.4 variant: hash nodes always computed, never selected (default off)")
     ap.add_argument("--aclo", action="store_true",
                     help="also time the pass with k chosen per query inside it (ACLO, Confidence LSH tables)")
-    ap.add_argument("--build-inputs", type=int, default=0, help="size of the table-training set (default: the config's)")
+    ap.add_argument("--markers", action="store_true",
+                    help="launch a marker kernel (nextafter) right before and after the timed steps, for profilers")
+    ap.add_argument("--no-profile", action="store_true", help="skip the event-instrumented pass (profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, for scaling rocprofv3 byte counters")
     args = ap.parse_args()
@@ -48,120 +298,14 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2204_08400_amd import runtime, slonn, workloads as wl
+    from paper_2204_08400_amd import slonn, workloads as wl
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     slonn.load()
     dev = torch.device("cuda:0")
-    cfg = wl.CONFIGS[args.config]
-    B = args.batch or cfg.batches[-1]
     K, W = args.steps, args.warmup
 
-    # ---- synthetic workload (seeds: weights 0, build set 1, queries 2, hash nodes 3) ----
-    t0 = time.time()
-    layers = wl.make_mlp(cfg.dims, seed=0, w_dtype=cfg.w_dtype, last_act=cfg.last_act)
-    X_build = wl.make_inputs(cfg, args.build_inputs or cfg.n_inputs, seed=1)
-    X_query = wl.make_inputs(cfg, cfg.n_inputs, seed=2)
-    log(f"generated {args.config} in {time.time() - t0:.1f}s")
-
-    # hash nodes: variance of the full network's activations on the build set (device dense pass)
-    ell = cfg.input_kind == "ell"
-    if ell:     # wide sparse-input model: first layer stored input-major on the device
-        layers[0].W = np.ascontiguousarray(layers[0].W.T)
-
-    def to_dev(X):
-        if ell:
-            return tuple(torch.from_numpy(np.ascontiguousarray(a)).to(dev) for a in X)
-        return torch.from_numpy(X).to(dev)
-
-    plain = runtime.Network(layers, first_layer_rows_are_inputs=ell)
-    xb = to_dev(X_build)
-    dn = plain.dense_forward(xb, layer_outs=True)
-    for l in cfg.hashed_layers:
-        layers[l].K, layers[l].L = cfg.K, cfg.L
-        # lists never need more entries than the largest budget below d_out that will be asked for
-        top = max([k for k in cfg.keeps if k < 1.0] + ([cfg.keep_range[1]] if cfg.keep_range else []) + [args.keep])
-        layers[l].list_cap = min(layers[l].d_out, int(np.ceil(top * layers[l].d_out)) + 1)
-        layers[l].hash_nodes = runtime.hash_nodes_by_variance(dn["layers"][l], cfg.K, cfg.L,
-                                                              wl.hash_node_draws(cfg.K, cfg.L, seed=3 + l))
-    del plain, dn
-    net = runtime.Network(layers, first_layer_rows_are_inputs=ell)
-    t0 = time.time()
-    net.build_tables(xb)
-    net.set_path(args.path)
-    net.set_hash_nodes_always_active(args.hash_nodes_always_active)
-    log(f"built tables on the device in {time.time() - t0:.2f}s")
-
-    xq = to_dev(X_query)
-    nq = (xq[0] if ell else xq).shape[0]
-    n_batches = nq // B
-    if ell:
-        batches = [slonn.make_input(idx=xq[0][i * B:(i + 1) * B], val=xq[1][i * B:(i + 1) * B],
-                                    nnz=xq[2][i * B:(i + 1) * B]) for i in range(n_batches)]
-    else:
-        batches = [slonn.make_input(x=xq[i * B:(i + 1) * B]) for i in range(n_batches)]
-    n_last = cfg.dims[-1]
-    out_arg = torch.empty(B, dtype=torch.int32, device=dev)
-    if layers[-1].K > 0:      # activated output layer: compact (id, value) output, no dense row
-        cap = layers[-1].list_cap
-        out_idx = torch.empty((B, n_last), dtype=torch.int32, device=dev)
-        out_val = torch.empty((B, n_last), dtype=torch.float32, device=dev)
-        out_cnt = torch.empty(B, dtype=torch.int32, device=dev)
-        out = slonn.make_output(idx=out_idx, val=out_val, cnt=out_cnt, stride=n_last, argmax=out_arg)
-    else:
-        out_dense = torch.empty((B, n_last), dtype=torch.float32, device=dev)
-        out = slonn.make_output(dense=out_dense, argmax=out_arg)
-    ws = net.workspace(B)
-    stream = torch.cuda.current_stream()
-
-    def run(keep_t, steps, first=0):
-        for i in range(steps):
-            b = (first + i) % n_batches
-            if mixed is not None:      # one keep fraction per query (mixed SLOs in one batch)
-                slonn.slonn_sparse_forward(net.model, net.tables, batches[b], B, mixed[b * B:(b + 1) * B],
-                                           1, 0, out, None, ws, stream)
-            else:
-                slonn.slonn_sparse_forward(net.model, net.tables, batches[b], B, keep_t, 0, 0, out, None,
-                                           ws, stream)
-
-    mixed = None
-    if cfg.keep_range:
-        mixed = torch.from_numpy(wl.keep_uniform(nq, cfg.keep_range[0], cfg.keep_range[1], seed=6)).to(dev)
-
-    def timed(keep, steps, warm):
-        keep_t = torch.full((1,), keep, dtype=torch.float32, device=dev)
-        run(keep_t, warm)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record(stream)
-        run(keep_t, steps, warm)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        return e0.elapsed_time(e1) / 1e3, wall
-
-    def mean_budget(keep, n):
-        """mean node budget of a layer of n nodes (nearest whole node, at least one)"""
-        k = mixed.cpu().numpy().astype(np.float64) if (mixed is not None and keep is None) else \
-            np.asarray([np.float32(keep)], np.float64)
-        return float(np.clip(np.floor(k * n + 0.5), 1, n).mean())
-
-    def gathered_bytes_per_query(keep, activated_only=True):
-        tot = 0.0
-        for lay in layers:
-            esz = 4 if lay.w_dtype == wl.W_F32 else 2
-            if lay.K > 0:
-                tot += mean_budget(keep, lay.d_out) * lay.d_in * esz
-            elif not activated_only:
-                if ell and lay is layers[0]:      # sparse input: one weight row per non-zero
-                    tot += cfg.ell_nnz * lay.d_out * esz
-                else:
-                    tot += lay.d_out * lay.d_in * esz
-        return tot
-
-    head_keep = None if mixed is not None else args.keep
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
         dst = torch.empty_like(src)
@@ -185,133 +329,69 @@ def main():
     del src, dst
     log(f"plain device copy: {copy_gbps:,.0f} GB/s (read + write)")
 
-    # ---- headline: K steps at the chosen keep fraction ----
-    dev_s, wall_s = timed(args.keep, K, W)
-    secs = max(dev_s, wall_s)             # the host loop must keep up: report the slower clock
-    qps = K * B / secs
-    eff_gbps = qps * gathered_bytes_per_query(head_keep) / 1e9
-    log(f"keep {args.keep}: {qps:,.0f} q/s, {secs / K * 1e6:.1f} us/step, effective {eff_gbps:,.0f} GB/s")
+    # ---- headline ----
+    w = Workload(args.config, args.batch, args, n_queries=args.queries, n_build=args.build_inputs, top_keep=args.keep)
+    cfg, B = w.cfg, w.B
+    head_keep = None if w.mixed is not None else args.keep
+    secs, per = w.time_sparse(head_keep, K, W, mark=args.markers)
+    qps = K * w.nq / secs
+    gathered = w.gathered_bytes_per_step(head_keep)
+    eff_gbps = gathered * K / secs / 1e9
+    log(f"{args.config} batch {B}: {qps:,.0f} q/s, {secs / K * 1e3:.3f} ms/step ({len(w.sizes)} batches), "
+        f"nominal {eff_gbps:,.0f} GB/s on gathered bytes")
+    keep_label = head_keep if head_keep is not None else f"per query U[{cfg.keep_range[0]}, {cfg.keep_range[1]}]"
+    head_config = {"workload": f"{args.config}: MLP {'-'.join(map(str, cfg.dims))}, K={cfg.K} L={cfg.L} on "
+                               f"{len(cfg.hashed_layers)} layers", "batch": B, "keep": keep_label,
+                   "queries_per_step": w.nq, "batches_per_step": len(w.sizes), "table_training_inputs": w.n_build,
+                   "path": args.path, "hash_nodes_always_active": bool(args.hash_nodes_always_active)}
+    traffic_key = f"{args.config}_B{B}_keep{head_keep if head_keep is not None else 'mixed'}"
+    extra = {"ms_per_step_median": round(float(np.median(per)), 4),
+             "nominal_gathered_GBps": round(eff_gbps, 1),
+             "measured_copy_GBps": round(copy_gbps, 1)}
+    roofline = None
+    if not args.no_profile:
+        prof = w.profile_sparse(head_keep, K)
+        roofline, per_step_us = roofline_of(w, head_keep, prof, K, secs / K, traffic_key)
+        extra["per_step_us_by_kernel_kind_with_event_overhead"] = {k: round(v, 1) for k, v in per_step_us.items()}
+        extra["avg_launch_us_by_kernel_kind_with_event_overhead"] = \
+            {k: round(v[0] * 1e3 / v[1], 2) for k, v in prof.items() if v[1]}
 
-    # ---- per-kernel durations over the same steps (HIP events on the launch stream) ----
-    keep_t = torch.full((1,), args.keep, dtype=torch.float32, device=dev)
-    slonn.slonn_profile_begin(K * (4 * len(layers) + 4))
-    run(keep_t, K, W)
-    prof = slonn.slonn_profile_end()
-    split_us = {k: (v[0] * 1e3 / max(v[1], 1)) for k, v in prof.items() if v[1]}
-    per_step_us = {k: v[0] * 1e3 / K for k, v in prof.items() if v[1]}
-    # dominant kernel: the one holding most of the step.  Its algorithmic bytes per launch are
-    # the weight rows the method must read: budget x row bytes for each activated layer, the whole
-    # matrix per query for a layer computed in full, summed over the layers that launch covers.
-    bytes_per_step = B * gathered_bytes_per_query(head_keep, activated_only=False)
-    dom = "fused" if prof["fused"][1] else "gather"
-    g_ms, g_n = prof[dom]
-    launches_per_step = g_n / K
-    avg_launch_s = g_ms / 1e3 / g_n
-    if dom == "fused" and launches_per_step == 1:
-        # one kernel per step: the event pair around the K back-to-back launches of the timed
-        # region times that kernel without the per-launch cost of the bracketing events
-        avg_launch_s = min(avg_launch_s, dev_s / K)
-    achieved = (bytes_per_step / launches_per_step) / avg_launch_s / 1e9
-    roofline = {"bound": "hbm", "kernel": ("fused_wide_kernel" if ell else "fused_forward_kernel") if dom == "fused" else "gather_forward_kernel",
-                "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": None, "avg_launch_us": round(avg_launch_s * 1e6, 2),
-                "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step),
-                "note": "algorithmic bytes = the weight rows the method must evaluate (budget x row bytes per "
-                        "activated layer, whole matrix per query for layers computed in full); a fraction above 1 "
-                        "means rows were served to several queries from L2 (traffic = bytes that reached HBM)"}
-    if dom == "gather" and prof["tiles"][1] and prof["tiles"][0] > prof["gather"][0]:
-        # large batches: most of the step is the masked tiles on the bf16 matrix cores, a dense
-        # contraction.  Flops per launch = every (query, node) pair of the layer, 2 d flops each,
-        # times the bf16 products per fp32 product (6 with fp32 weights in three parts, 3 with bf16
-        # weights); the selected pairs are the part of them that is written.
-        t_ms, t_n = prof["tiles"]
-        tile_flops = sum(2.0 * B * lay.d_in * lay.d_out * (3 if lay.w_dtype == wl.W_BF16 else 6)
-                         for lay in layers if lay.K > 0)
-        per_launch = tile_flops / max(1, sum(1 for lay in layers if lay.K > 0))
-        avg_s = t_ms / 1e3 / t_n
-        peak = 2500.0
-        roofline = {"bound": "mfma", "kernel": "masked_tiles_kernel", "achieved": round(per_launch / avg_s / 1e12, 1),
-                    "peak": peak, "unit": "TFLOP/s", "frac": round(per_launch / avg_s / 1e12 / peak, 4),
-                    "traffic": None, "avg_launch_us": round(avg_s * 1e6, 2),
-                    "flops_per_launch": int(per_launch),
-                    "note": "bf16 MFMA flops issued per launch (all pairs of a 128-query tile, fp32 operands as "
-                            "three bf16 parts) over the mean launch duration of the masked tiles; the gathered-bytes "
-                            "figure of the whole step is effective_GBps"}
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            roofline["traffic"] = json.load(open(tpath)).get(f"{args.config}_keep{args.keep}_B{B}")
-        except Exception:
-            pass
+    def sweep_and_dense(wk, steps, warm, keeps):
+        """the keep fractions of a workload and the full network, a few steps each"""
+        res = {"sweep": {}}
+        for keep in keeps:
+            s, _ = wk.time_sparse(keep, steps, warm)
+            q = steps * wk.nq / s
+            res["sweep"][str(keep)] = {"qps": round(q), "ms_per_step": round(s / steps * 1e3, 4),
+                                       "nominal_gathered_GBps": round(wk.gathered_bytes_per_step(keep) * steps / s / 1e9, 1)}
+        dflops = wk.dense_flops_per_query()
+        res["dense_baseline"] = {}
+        for mode, label in ((0, "fp32_mfma"), (1, "bf16_parts_mfma")):
+            if mode and not hasattr(slonn, "slonn_model_set_dense_arithmetic"):
+                continue
+            if hasattr(slonn, "slonn_model_set_dense_arithmetic"):
+                slonn.slonn_model_set_dense_arithmetic(wk.net.model, mode)
+            s, _ = wk.timed(wk.dense_step, steps, warm)
+            res["dense_baseline"][label] = {"qps": round(steps * wk.nq / s), "ms_per_step": round(s / steps * 1e3, 4),
+                                            "TFLOPs": round(dflops * steps * wk.nq / s / 1e12, 2)}
+        if hasattr(slonn, "slonn_model_set_dense_arithmetic"):
+            slonn.slonn_model_set_dense_arithmetic(wk.net.model, 0)
+        best_dense = max(v["qps"] for v in res["dense_baseline"].values())
+        for k, v in res["sweep"].items():
+            v["sparse_over_best_dense"] = round(v["qps"] / best_dense, 3)
+        return res
 
-    extra = {"effective_GBps": round(eff_gbps, 1), "frac_of_hbm_peak": round(eff_gbps / HBM_PEAK_GBPS, 4),
-             "measured_copy_GBps": round(copy_gbps, 1), "frac_of_measured_copy": round(eff_gbps / copy_gbps, 4),
-             "per_step_us_with_event_overhead": {k: round(v, 2) for k, v in per_step_us.items()},
-             "avg_launch_us_with_event_overhead": {k: round(v, 2) for k, v in split_us.items()}}
-
-    # ---- the other keep fractions and the dense baseline, briefly ----
     if not args.no_sweep:
-        sweep = {}
-        for keep in (cfg.keeps if mixed is None else ()):
-            d_s, w_s = timed(keep, 120, 20)
-            s = max(d_s, w_s)
-            q = 120 * B / s
-            sweep[str(keep)] = {"qps": round(q), "effective_GBps": round(q * gathered_bytes_per_query(keep) / 1e9, 1)}
-        extra["sweep"] = sweep
-        yd = torch.empty((B, n_last), dtype=torch.float32, device=dev)
-        torch.cuda.synchronize()
-        for i in range(20):
-            slonn.slonn_dense_forward(net.model, batches[i % n_batches], B, yd, out_arg, None, ws, stream)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for i in range(120):
-            slonn.slonn_dense_forward(net.model, batches[i % n_batches], B, yd, out_arg, None, ws, stream)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        dsec = e0.elapsed_time(e1) / 1e3
-        extra["dense_baseline_qps"] = round(120 * B / dsec)
-        dflops = 2.0 * sum(lay.d_in * lay.d_out for lay in layers if not (ell and lay is layers[0]))
-        extra["dense_baseline_tflops"] = round(dflops * 120 * B / dsec / 1e12, 2)
-        extra["dense_baseline_frac_of_fp32_mfma_peak"] = round(dflops * 120 * B / dsec / 157.3e12, 4)
-
-    # ---- small batches are launch-bound: the same step recorded once and replayed as a HIP graph ----
-    if B <= 64 and mixed is None:
-        keep_g = torch.full((1,), args.keep, dtype=torch.float32, device=dev)
-        graph = slonn.slonn_forward_graph_create(net.model, net.tables, batches[0], B, keep_g, 0, 0, out, ws)
-        for _ in range(20):
-            graph.launch(stream)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record(stream)
-        for _ in range(200):
-            graph.launch(stream)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        g_s = max(e0.elapsed_time(e1) / 1e3, time.perf_counter() - t0)
-        # latency of one step seen from the host: launch, then wait for the result
-        lat = {}
-        for name, fn in (("eager", lambda: run(keep_g, 1)), ("graph", lambda: graph.launch(stream))):
-            ts = []
-            for _ in range(60):
-                torch.cuda.synchronize()
-                t1 = time.perf_counter()
-                fn()
-                torch.cuda.synchronize()
-                ts.append(time.perf_counter() - t1)
-            lat[name] = round(float(np.median(ts[10:])) * 1e6, 2)
-        extra["recorded_step"] = {"us_per_step_back_to_back": round(g_s / 200 * 1e6, 2),
-                                  "qps_back_to_back": round(200 * B / g_s),
-                                  "host_latency_us_median": lat,
-                                  "note": "same batch replayed (weights, tables and access pattern as in the timed region)"}
-        log(f"recorded step: {extra['recorded_step']}")
-        graph.close()
+        keeps = cfg.keeps if w.mixed is None else ()
+        r = sweep_and_dense(w, max(2, min(K, 5)), 1, keeps)
+        extra.update(r)
+        best_dense = max(v["qps"] for v in r["dense_baseline"].values())
+        extra["sparse_over_best_dense"] = round(qps / best_dense, 3)
 
     # ---- k chosen per query inside the pass (ACLO): Confidence LSH tables trained on the build
-    #      set with c(k, x) = -cross-entropy(full prediction, prediction at k) (Eq. 3) ----
-    if args.aclo and mixed is None and not ell and cfg.hashed_layers[0] == 0:
+    #      set with c(k, x) = -cross-entropy(full prediction, prediction at k) (Section 2.1) ----
+    if args.aclo and w.mixed is None and not w.ell and cfg.hashed_layers[0] == 0:
+        net, xb = w.net, w.xb
         grid = sorted(set(float(k) for k in cfg.keeps))
         nb_ = min(xb.shape[0], 8192)
         xb_ = xb[:nb_]
@@ -325,31 +405,22 @@ def main():
         slonn.slonn_policy_train_confidence(pol, codes, conf, nb_)
         # one threshold per query, drawn from the training confidences at the middle k, so that
         # a batch mixes queries that are satisfied early with queries that need more nodes
-        pick = torch.from_numpy(np.random.default_rng(8).integers(0, nb_, nq)).to(dev)
+        pick = torch.from_numpy(np.random.default_rng(8).integers(0, nb_, w.nq)).to(dev)
         thr_all = conf[:, len(grid) // 2][pick].contiguous()
         keep_out = torch.zeros(B, dtype=torch.float32, device=dev)
-
-        def run_aclo(steps, first=0):
-            for i in range(steps):
-                b = (first + i) % n_batches
-                slonn.slonn_sparse_forward_aclo(net.model, net.tables, pol, batches[b], B,
-                                                thr_all[b * B:(b + 1) * B], 1, keep_out, out, None, ws, stream)
-        run_aclo(20)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record(stream)
-        run_aclo(120, 20)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        a_s = max(e0.elapsed_time(e1) / 1e3, time.perf_counter() - t0)
         chosen = []
-        for b in range(min(n_batches, 16)):
-            run_aclo(1, b)
-            chosen.append(keep_out.cpu().numpy().copy())
+
+        def aclo_step(collect=False):
+            for i, nb in enumerate(w.sizes):
+                slonn.slonn_sparse_forward_aclo(net.model, net.tables, pol, w.batches[i], nb,
+                                                thr_all[i * B:i * B + nb], 1, keep_out, w.out, None, w.ws, w.stream)
+                if collect:
+                    chosen.append(keep_out[:nb].cpu().numpy().copy())
+        a_s, _ = w.timed(aclo_step, max(2, min(K, 5)), 1)
+        a_n = max(2, min(K, 5))
+        aclo_step(collect=True)
         chosen = np.concatenate(chosen)
-        extra["aclo"] = {"qps": round(120 * B / a_s), "us_per_step": round(a_s / 120 * 1e6, 2),
-                         "k_grid": grid,
+        extra["aclo"] = {"qps": round(a_n * w.nq / a_s), "ms_per_step": round(a_s / a_n * 1e3, 4), "k_grid": grid,
                          "share_of_queries_per_k": [round(float((chosen == np.float32(k)).mean()), 4) for k in grid],
                          "mean_keep": round(float(chosen.mean()), 4),
                          "confidence": "-cross-entropy(softmax(full), softmax(at k)) on the first "
@@ -358,42 +429,57 @@ def main():
 
     # ---- CPU baseline: the oracle as it stands, on the host cores, bounded sample ----
     cpu = None
-    blob_bytes = slonn.slonn_tables_export_bytes(net.tables)
-    if not args.no_cpu_baseline and blob_bytes > (4 << 30):
-        log(f"CPU baseline skipped: the tables are {blob_bytes / 2**30:.1f} GiB; rerun with --build-inputs 4096")
-    elif not args.no_cpu_baseline:
+    if not args.no_cpu_baseline:
         from oracle import slonn_oracle
-        onet = slonn_oracle.OracleNet(layers, first_layer_rows_are_inputs=ell,
+        net = w.net
+        note = ""
+        blob_bytes = slonn.slonn_tables_export_bytes(net.tables)
+        if blob_bytes > (5 << 30):
+            # the full table set is too large to copy to the host twice: the oracle gets tables trained
+            # (on the device, same kernels) on the first inputs of the same training set
+            nb_small = 1024
+            net_small = w.runtime.Network(w.layers, first_layer_rows_are_inputs=w.ell)
+            net_small.build_tables(w.xb[:nb_small] if not w.ell else tuple(a[:nb_small] for a in w.xb))
+            blob = net_small.export_tables()
+            del net_small
+            note = f", tables trained on the first {nb_small} of the {w.n_build} training inputs ({len(blob) / 2**30:.1f} GiB)"
+        else:
+            blob = net.export_tables()
+        onet = slonn_oracle.OracleNet(w.layers, first_layer_rows_are_inputs=w.ell,
                                       hash_nodes_always_active=args.hash_nodes_always_active)
-        onet.import_tables(net.export_tables())
-        n_s = min(nq, 4096)
-        Xs = tuple(a[:n_s] for a in X_query) if ell else X_query[:n_s]
-        ks = args.keep if mixed is None else mixed[:n_s].cpu().numpy()
-        # passes over the sample until about ten seconds of CPU work have been timed
+        onet.import_tables(blob)
+        del blob
+        big = cfg.dims[1] >= 4096 and len(cfg.dims) > 3
+        n_s = min(w.nq, 512 if big else 4096)
+        Xs = tuple(a[:n_s] for a in w.X_query) if w.ell else w.X_query[:n_s]
+        ks = args.keep if w.mixed is None else w.mixed_host[:n_s]
         done, dt = 0, 0.0
-        while dt < 10.0 and done < 400 * n_s:
+        while dt < 10.0 and done < 400 * n_s:      # passes over the sample until about ten seconds are timed
             t0 = time.perf_counter()
             onet.sparse_forward(Xs, ks, taps=False)
             dt += time.perf_counter() - t0
             done += n_s
-        # the same oracle on one thread, briefly (about three seconds)
-        one = slonn_oracle.OracleNet(layers, threads=1, first_layer_rows_are_inputs=ell,
-                                     hash_nodes_always_active=args.hash_nodes_always_active)
-        one.tables = onet.tables
-        n_1 = min(n_s, 256)
-        X1 = tuple(a[:n_1] for a in Xs) if ell else Xs[:n_1]
-        k1 = ks if np.ndim(ks) == 0 else ks[:n_1]
-        done1, dt1 = 0, 0.0
-        while dt1 < 3.0 and done1 < 400 * n_1:
-            t0 = time.perf_counter()
-            one.sparse_forward(X1, k1, taps=False)
-            dt1 += time.perf_counter() - t0
-            done1 += n_1
-        extra["cpu_baseline_one_thread_qps"] = round(done1 / dt1, 1)
         cpu = {"value": round(done / dt, 1), "unit": "queries/s", "cores": onet.threads, "kind": "oracle",
                "sample": f"first {n_s} queries of the same query set, {done // n_s} passes ({dt:.1f} s of CPU work), "
-                         f"keep {args.keep if mixed is None else 'per query'}, all layers, "
-                         f"{onet.threads} threads over queries"}
+                         f"keep {keep_label}, all layers, {onet.threads} threads over queries{note}"}
+        log(f"CPU oracle: {cpu}")
+        del onet
+
+    # ---- the other workloads, briefly (their own query sets, whole-set steps) ----
+    if not args.no_sweep and not args.no_others and args.config == "C5":
+        others = {}
+        del w
+        torch.cuda.empty_cache()
+        for name, b_, nq_, nb_ in (("C3", 1024, 8192, 8192), ("C2", 256, 0, 0)):
+            wk = Workload(name, b_, args, n_queries=nq_, n_build=nb_)
+            r = sweep_and_dense(wk, 3, 1, wk.cfg.keeps)
+            r["config"] = {"workload": f"{name}: MLP {'-'.join(map(str, wk.cfg.dims))}, K={wk.cfg.K} L={wk.cfg.L}",
+                           "batch": wk.B, "queries_per_step": wk.nq, "table_training_inputs": wk.n_build}
+            others[f"{name}_B{wk.B}"] = r
+            log(f"{name}: {r}")
+            del wk
+            torch.cuda.empty_cache()
+        extra["other_workloads"] = others
 
     line = {
         "metric": "queries/sec and effective HBM GB/s (vs peak) for sparse forward at keep-fraction",
@@ -401,11 +487,7 @@ def main():
         "ms_per_step": round(secs / K * 1e3, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if cfg.w_dtype == wl.W_F32 else "bf16 weights, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"{args.config}: MLP {'-'.join(map(str, cfg.dims))}, K={cfg.K} L={cfg.L} on "
-                               f"{len(cfg.hashed_layers)} hidden layers, {nq} queries", "batch": B,
-                   "keep": args.keep if mixed is None else f"per query U[{cfg.keep_range[0]}, {cfg.keep_range[1]}]",
-                   "queries_per_step": B, "path": args.path,
-                   "hash_nodes_always_active": bool(args.hash_nodes_always_active)},
+        "config": head_config,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     line.update(extra)

@@ -159,6 +159,17 @@ int slonn_model_set_path(slonn_model* m, int path);
  * through the fp64 recomputation: a diagnostic).  EINVAL: null model, margin < 1 or NaN.      */
 int slonn_model_set_hash_margin(slonn_model* m, double margin);
 
+/* Arithmetic of slonn_dense_forward, the all-nodes baseline (Section 3.4, last paragraph).
+ * SLONN_DENSE_FP32_MFMA (default): fp32 operands on the fp32 matrix cores.
+ * SLONN_DENSE_BF16_PARTS: the arithmetic the sparse path uses for large batches of large layers -
+ *   activations (and fp32 weights) as exact sums of three bf16 parts, partial products accumulated in
+ *   fp32 on the bf16 matrix cores - so that sparse and dense passes can be compared like for like.
+ *   Layers or batches that path does not serve (small layers, rows not a multiple of 32 elements, batches
+ *   of only a few tiles) stay on the fp32 cores.  Results agree with the default to fp32 rounding.
+ * EINVAL: null model, unknown mode.                                                          */
+enum { SLONN_DENSE_FP32_MFMA = 0, SLONN_DENSE_BF16_PARTS = 1 };
+int slonn_model_set_dense_arithmetic(slonn_model* m, int mode);
+
 /* Variant of Section 3.4 ("the hash is free"): the K*L FreeHash projections of a layer are
  * the pre-activations of K*L of its own nodes, so those nodes can always be computed at no
  * further cost, and the Node Activator then need not select them.  on != 0: for every

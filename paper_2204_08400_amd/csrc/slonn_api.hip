@@ -442,6 +442,14 @@ int slonn_model_set_hash_margin(slonn_model* m, double margin) {
   return SLONN_OK;
 }
 
+int slonn_model_set_dense_arithmetic(slonn_model* m, int mode) {
+  if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
+  if (mode != SLONN_DENSE_FP32_MFMA && mode != SLONN_DENSE_BF16_PARTS)
+    SLONN_FAIL(SLONN_EINVAL, "unknown dense arithmetic %d", mode);
+  m->dense_arith = mode;
+  return SLONN_OK;
+}
+
 int slonn_model_set_hash_nodes_always_active(slonn_model* m, int on) {
   if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
   m->hash_first = on != 0;
@@ -1126,6 +1134,13 @@ int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float
     if (l == 0 && X->format == SLONN_ELL)
       rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
                             L.d_out, B, L.d_in, L.d_out, L.act, s);
+    else if (m->dense_arith == SLONN_DENSE_BF16_PARTS && w.tiles && (L.W3 || L.w_dtype == SLONN_BF16) &&
+             L.w_layout == SLONN_ROWS_ARE_NODES && L.d_in % 32 == 0 && reinterpret_cast<uintptr_t>(L.W) % 16 == 0 &&
+             (long)((B + 63) / 64) * ((L.d_out + 127) / 128) >= 64 && (size_t)3 * B * L.d_in * 2 <= w.tiles_bytes)
+      // the arithmetic of the masked tiles without a mask: activations (and fp32 weights) as three bf16
+      // parts on the bf16 matrix cores, fp32 accumulation
+      rc = launch_dense_tiles(L.W3 ? L.W3 : static_cast<const uint16_t*>(L.W), L.W3 ? 3 : 1, L.bias, cur, ldcur, out,
+                              L.d_out, B, L.d_in, L.d_out, L.act, w.tiles, s);
     else
       rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, L.d_out, B, L.d_in, L.d_out, L.act,
                               w.dense_split, s);

@@ -67,6 +67,7 @@ struct slonn_model {
   bool path_grouped = true;       // allow the grouped (cross-query) evaluation on the per-layer path
   bool hash_first = false;        // hash nodes always computed, never selected (Section 3.4 variant)
   double hash_margin = 2.0;       // integer hash projections: |z| must exceed this many error bounds
+  int dense_arith = 0;            // slonn_dense_forward: 0 fp32 matrix cores, 1 bf16 parts on the bf16 matrix cores
   int max_lds_bytes = 65536;      // per-workgroup LDS the device grants on request
   int n_cu = 256;
 };

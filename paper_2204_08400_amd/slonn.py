@@ -34,7 +34,7 @@ EXPORTS = [
     "slonn_sparse_forward_aclo",
     "slonn_forward_graph_create", "slonn_forward_graph_launch", "slonn_forward_graph_destroy",
     "slonn_activation_variance", "slonn_sample_hash_nodes", "slonn_model_set_hash_margin",
-    "slonn_sparse_forward_static",
+    "slonn_sparse_forward_static", "slonn_model_set_dense_arithmetic",
 ]
 STATIC_SCRATCH_BYTES = 64 << 20
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused", "tiles")
@@ -183,6 +183,11 @@ def slonn_model_create(layers: Sequence[dict]) -> Model:
 
 def slonn_model_set_path(model: Model, path: int):
     _check(load().slonn_model_set_path(model.h, int(path)))
+
+
+def slonn_model_set_dense_arithmetic(model: Model, mode: int):
+    """0: fp32 matrix cores (default); 1: three bf16 parts on the bf16 matrix cores (see slonn.h)."""
+    _check(load().slonn_model_set_dense_arithmetic(model.h, int(mode)))
 
 
 def slonn_model_set_hash_nodes_always_active(model: Model, on: bool):
