@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 BF16_PEAK_TFLOPS = 2500.0       # dense bf16 MFMA
 FP32_MFMA_PEAK_TFLOPS = 157.3
-KERNEL_OF_KIND = {"fused": "fused_forward_kernel", "tiles": "masked_tiles_kernel", "gather": "gather_blocked_kernel",
+KERNEL_OF_KIND = {"fused": "fused_", "tiles": "masked_tiles_kernel", "gather": "gather_blocked_kernel",
                   "select": "select_block_kernel", "hash": "hash projection kernels", "dense": "dense_layer_kernel",
                   "ell": "ell_layer_kernel", "finalize": "finalize_kernel"}
 
@@ -218,7 +218,8 @@ def roofline_of(w, keep, prof, steps, secs_per_step, traffic_key):
     launches_per_step = n / steps
     gathered = w.gathered_bytes_per_step(keep)
     tr = load_traffic(traffic_key) or {}
-    tk = (tr.get("kernels") or {}).get(KERNEL_OF_KIND[dom])
+    cand = {k: v for k, v in (tr.get("kernels") or {}).items() if k.startswith(KERNEL_OF_KIND[dom])}
+    tk = cand[max(cand, key=lambda k: cand[k]["launches_per_step"])] if cand else None
     traffic = int(tk["fetch_bytes_per_launch"] + tk["write_bytes_per_launch"]) if tk else None
     hbm_step = tr.get("hbm_bytes_per_step")
     nominal = gathered / secs_per_step / 1e9
