@@ -274,7 +274,7 @@ int slonn_sparse_forward_static(const slonn_model* m, const slonn_tables* t, con
 
 /* ---- Choice of k per query (Section 2: ACLO and LCAO; Section 3.2: Confidence LSH tables,
  * latency profiles; Fig. 2 step 2).  Mechanics only: the confidences c(k, x') of the
- * training inputs (Eq. 3) and the latency profile T(k, beta) are supplied by the caller, and
+ * training inputs (the confidence definition of Section 2.1, the first equation) and the latency profile T(k, beta) are supplied by the caller, and
  * an accuracy target reaches the library as the confidence threshold it was calibrated to.
  *
  * A policy holds an ascending grid k_0 < ... < k_{G-1} of keep fractions (HOST, values in

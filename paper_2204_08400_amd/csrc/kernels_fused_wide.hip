@@ -162,10 +162,13 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
   const int n1 = a.n1, n2 = a.n2;
 
   // ---- sparse input row into LDS ----
-  const int c = min(a.nnz[q], a.ell_stride);
+  // (count clamped to the row's slots; an entry whose column lies outside [0, d0) contributes nothing)
+  const int c = min(max(a.nnz[q], 0), a.ell_stride);
   for (int t = tid; t < c; t += NT) {
-    s_idx[t] = a.idx[(size_t)q * a.ell_stride + t];
-    s_val[t] = a.val[(size_t)q * a.ell_stride + t];
+    const int i = a.idx[(size_t)q * a.ell_stride + t];
+    const bool ok = (unsigned)i < (unsigned)a.d0;
+    s_idx[t] = ok ? i : 0;
+    s_val[t] = ok ? a.val[(size_t)q * a.ell_stride + t] : 0.0f;
   }
   __syncthreads();
 

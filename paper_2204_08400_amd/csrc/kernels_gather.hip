@@ -350,13 +350,17 @@ __global__ __launch_bounds__(256) void ell_layer_kernel(
   extern __shared__ __align__(16) unsigned char ell_smem[];
   using C = Chunk<WDT>;
   const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int c = nnz[q];
+  // the row's entry count and columns live in device memory the host cannot check: the count is
+  // clamped to the row's slots, an entry whose column lies outside [0, d) contributes nothing
+  const int c = min(max(nnz[q], 0), ell_stride);
   int32_t* s_idx = reinterpret_cast<int32_t*>(ell_smem);
   float* s_val = reinterpret_cast<float*>(s_idx + ell_stride);
   float* part = s_val + ell_stride;                       // [4][64]
   for (int t = tid; t < c; t += 256) {
-    s_idx[t] = idx[(size_t)q * ell_stride + t];
-    s_val[t] = val[(size_t)q * ell_stride + t];
+    const int i = idx[(size_t)q * ell_stride + t];
+    const bool ok = (unsigned)i < (unsigned)d;
+    s_idx[t] = ok ? i : 0;
+    s_val[t] = ok ? val[(size_t)q * ell_stride + t] : 0.0f;
   }
   __syncthreads();
   const int j = blockIdx.y * 64 + lane;

@@ -277,9 +277,29 @@ int hash_split_factor(int B, int H, int d) {
   return S >= 2 ? S : 1;
 }
 
+namespace {
+int launch_hash_project_chunk(const float* X, int ldx, const float* Wh, const float* bh, float* Z, int B,
+                              int H, int d, void* split_scratch, HashSplit* pending, hipStream_t s);
+}
+
 int launch_hash_project(const float* X, int ldx, const float* Wh, const float* bh, float* Z, int B,
                         int H, int d, void* split_scratch, HashSplit* pending, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_HASH, s);
+  // the batch runs along the grid's y dimension (limit 65535) in tiles of at least 16 queries, one
+  // query per y step for the smallest batches: chunks of 2^19 queries stay within it
+  constexpr int CHUNK = 1 << 19;
+  for (int q0 = 0; q0 < B; q0 += CHUNK) {
+    const int nb = std::min(CHUNK, B - q0);
+    const int rc = launch_hash_project_chunk(X + (size_t)q0 * ldx, ldx, Wh, bh, Z + (size_t)q0 * H, nb, H, d,
+                                             split_scratch, B <= CHUNK ? pending : nullptr, s);
+    if (rc) return rc;
+  }
+  return SLONN_OK;
+}
+
+namespace {
+int launch_hash_project_chunk(const float* X, int ldx, const float* Wh, const float* bh, float* Z, int B,
+                              int H, int d, void* split_scratch, HashSplit* pending, hipStream_t s) {
   const bool vec = (d % 4 == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
                    (reinterpret_cast<uintptr_t>(Wh) % 16 == 0);
   const int S = (vec && split_scratch) ? hash_split_factor(B, H, d) : 1;
@@ -352,6 +372,7 @@ int launch_hash_project(const float* X, int ldx, const float* Wh, const float* b
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }
+}  // namespace
 
 // FreeHash rows are borrowed from the layer itself (Def. 2): copy them once into one contiguous
 // fp32 matrix so that the projection reads a dense operand.

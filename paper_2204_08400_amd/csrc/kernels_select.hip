@@ -289,8 +289,8 @@ __global__ __launch_bounds__(1024) void order_by_budget_kernel(const float* __re
 
 __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t* __restrict__ cnt,
                                  int n, int B) {
-  const int q = blockIdx.y;
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int q = blockIdx.x;          // the batch (up to 2^20) in the grid's x dimension, whose limit is 2^31 - 1
+  const int i = blockIdx.y * blockDim.x + threadIdx.x;
   if (q >= B) return;
   if (idx && i < n) idx[(size_t)q * stride + i] = i;
   if (i == 0 && cnt) cnt[q] = n;
@@ -368,7 +368,9 @@ bool select_fills_row_blocks(int n, int max_lds) {
 }
 
 int launch_fill_iota(int32_t* idx, int stride, int32_t* cnt, int n, int B, hipStream_t s) {
-  dim3 grid(idx ? (n + 255) / 256 : 1, B);
+  const int chunks = idx ? (n + 255) / 256 : 1;
+  if (chunks > 65535) SLONN_FAIL(SLONN_EUNSUPPORTED, "compact output of a layer with %d nodes is too wide", n);
+  dim3 grid(B, chunks);
   hipLaunchKernelGGL(fill_iota_kernel, grid, dim3(256), 0, s, idx, stride, cnt, n, B);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;

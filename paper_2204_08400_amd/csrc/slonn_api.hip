@@ -297,6 +297,12 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
   if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
     m->n_cu = v;
 
+  // The caller may have filled W and bias on any stream; the set-up kernels below run on the default
+  // stream.  One device-wide synchronisation first, so that they read what the caller wrote.
+  if ((e = hipDeviceSynchronize()) != hipSuccess) {
+    set_error("hipDeviceSynchronize failed: %s", hipGetErrorString(e));
+    return fail(SLONN_EHIP);
+  }
   // the scratch array of the allocation-free entry point: its address on this device, looked up now
   // so that the entry point itself has nothing left to set up
   {
@@ -709,7 +715,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
     const Layer& O = m->layers[1];
     const TableSet* ts = t->for_layer(1);
     FusedWideArgs a{};
-    a.W0 = A.W; a.b0 = A.bias; a.w0_dtype = A.w_dtype; a.act0 = A.act; a.n1 = A.d_out;
+    a.W0 = A.W; a.b0 = A.bias; a.w0_dtype = A.w_dtype; a.act0 = A.act; a.d0 = A.d_in; a.n1 = A.d_out;
     a.n1p = (A.d_out + 3) & ~3;
     a.ccp = 1;
     while (a.ccp * 4 < A.d_out) a.ccp *= 2;

@@ -145,7 +145,7 @@ struct FusedWideArgs {
   // hidden layer
   const void* W0; const float* b0;
   const int32_t* idx; const float* val; const int32_t* nnz;
-  int w0_dtype, act0, n1, n1p, ccp, ell_stride, ellp;
+  int w0_dtype, act0, d0, n1, n1p, ccp, ell_stride, ellp;
   // output layer and its Node Activator
   const void* W1; const float* b1; const float* Wh; const float* bh;
   const uint32_t* dir; const int32_t* ids; const int32_t* global_rank;

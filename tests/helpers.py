@@ -40,8 +40,11 @@ def make_queries(dims, N, seed, kind="u01", ell_nnz=0):
     return wl.inputs_normal_clipped(N, dims[0], seed, 3.0 if kind == "clip3" else None)
 
 
-def assert_close_rows(got: np.ndarray, ref: np.ndarray, rows=None, what=""):
-    """Per query: max|g-o| <= tol*max|o| and element-wise |g-o| <= tol*|o| + 1e-6*max|o|."""
+def assert_close_rows(got: np.ndarray, ref: np.ndarray, rows=None, what="", depth=1):
+    """Per query: max|g-o| <= tol*max|o| and element-wise |g-o| <= tol*|o| + depth*1e-6*max|o|.
+    depth = number of layers whose fp32 rounding the values carry (1 for a first layer): an output
+    near zero is a cancellation of terms of the size of max|o|, so its error does not shrink with
+    it, and a layer's inputs carry the rounding of every layer before it."""
     if rows is not None:
         got, ref = got[rows], ref[rows]
     if ref.size == 0:
@@ -50,19 +53,22 @@ def assert_close_rows(got: np.ndarray, ref: np.ndarray, rows=None, what=""):
     err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
     worst = float((err / scale).max())
     assert worst <= REL_TOL, f"{what}: max error {worst:.3e} of the row maximum"
-    bound = REL_TOL * np.abs(ref) + 1e-6 * scale
+    bound = REL_TOL * np.abs(ref) + depth * 1e-6 * scale
     bad = err > bound
-    assert not bad.any(), f"{what}: {int(bad.sum())} elements beyond the element-wise bound"
+    assert not bad.any(), (f"{what}: {int(bad.sum())} elements beyond the element-wise bound "
+                           f"(worst error / bound {float((err / bound).max()):.2f})")
     return worst
 
 
-def compare_sparse(res_gpu: dict, res_ref: dict, layers, what=""):
+def compare_sparse(res_gpu: dict, res_ref: dict, layers, what="", max_tainted=None):
     """Compare a GPU sparse forward (with taps, as numpy) with the oracle's.
 
     A query is *tainted* from the first layer on where one of its hash projections
     lies within 1e-6 of zero (its key then depends on summation order); tainted
     queries are set aside and counted, everything else must agree: codes and active
-    lists bit for bit, outputs to REL_TOL, argmax exactly.  Returns a report dict.
+    lists bit for bit, outputs to REL_TOL, argmax exactly.  At most max_tainted queries may be
+    set aside (default: 2, or 1 % of the queries if that is more; a test that plants ties says
+    how many it expects).  Returns a report dict.
     """
     N = res_ref["out"].shape[0]
     tainted = np.zeros(N, bool)
@@ -89,7 +95,8 @@ def compare_sparse(res_gpu: dict, res_ref: dict, layers, what=""):
                                        err_msg=f"{what} layer {l}: hash projections")
         ok = ~tainted
         rep["max_rel_err"] = max(rep["max_rel_err"],
-                                 assert_close_rows(g["out"][l], ref["out"], ok, f"{what} layer {l} output"))
+                                 assert_close_rows(g["out"][l], ref["out"], ok, f"{what} layer {l} output",
+                                                   depth=l + 1))
         # dropped nodes are exactly +0 on both sides
         if lay.act == wl.ACT_RELU:
             assert not np.signbit(g["out"][l]).any(), f"{what} layer {l}: negative zero or value after ReLU"
@@ -100,8 +107,10 @@ def compare_sparse(res_gpu: dict, res_ref: dict, layers, what=""):
                 assert not g["out"][l][q, mask].any(), f"{what} layer {l} query {q}: dropped node not zero"
     ok = ~tainted
     assert np.array_equal(res_gpu["argmax"][ok], res_ref["argmax"][ok]), f"{what}: argmax differs"
-    assert_close_rows(res_gpu["out"], res_ref["out"], ok, f"{what} final output")
+    assert_close_rows(res_gpu["out"], res_ref["out"], ok, f"{what} final output", depth=len(layers))
     rep["tainted"] = int(tainted.sum())
+    limit = max(2, -(-N // 100)) if max_tainted is None else max_tainted
+    assert rep["tainted"] <= limit, f"{what}: {rep['tainted']} of {N} queries set aside as ties (limit {limit})"
     return rep
 
 

@@ -289,6 +289,8 @@ BUILD_CASES = [
     dict(dims=(100, 300, 260, 37), K=4, L=6, cap=200, N=500, hashed=None, last_act=wl.ACT_NONE),
     dict(dims=(48, 10000, 16), K=5, L=4, cap=400, N=300, hashed=[0], last_act=wl.ACT_NONE),       # wide ReLU layer
     dict(dims=(48, 128, 12000), K=6, L=5, cap=300, N=300, hashed=[1], last_act=wl.ACT_SOFTMAX),   # wide softmax layer
+    # the width of the extreme-classification output layers (Table 1): 100 000 softmax nodes, few inputs
+    dict(dims=(64, 128, 100000), K=5, L=3, cap=600, N=96, hashed=[1], last_act=wl.ACT_SOFTMAX),
 ]
 
 
@@ -433,12 +435,15 @@ def test_config_c3_shape_sampled(rt, oracle):
 
 @pytest.mark.timeout(600)
 def test_config_c3_timed_batch_sampled(rt, oracle):
-    """C3 at the batch bench.py times (1024 queries, keep 0.25, path auto: row-block gather plus
-    grouped evaluation on the fp32 matrix cores); the oracle computes a sample of the queries."""
+    """C3 at the batch bench.py times (1024 queries, path auto: integer hash, select, then per 128
+    queries either the masked tiles on the bf16 matrix cores - keep 0.1 and above - or the row-block
+    gather), over the keep sweep; the oracle computes the first and the last query of every group
+    of 16 (128 queries: both sides of every 16- and 128-query boundary of the tiles and unions)."""
     from paper_2204_08400_amd import slonn
     B = 1024
     cfg, layers, g, net, Xq = _config_case(rt, "C3", 4096, B, list_cap=2049)
-    for keep in (0.25, 0.05):
+    sample = np.asarray([q for q in range(B) if q % 16 in (0, 15)])
+    for keep in (0.05, 0.1, 0.25, 0.5):
         _say(f"C3 batch 1024 keep={keep}: GPU pass")
         slonn.slonn_profile_begin(64)
         res = g.sparse_forward(Xq, keep, taps=True)
@@ -447,7 +452,7 @@ def test_config_c3_timed_batch_sampled(rt, oracle):
         assert prof["tiles"][1] == len(cfg.hashed_layers) and prof["gather"][1] == len(cfg.hashed_layers), prof
         assert prof["dense"][1] == 1, prof
         got = to_numpy_result(res)
-        sample = np.asarray([0, 1, 15, 16, 17, 100, 511, 512, 513, 800, 1008, 1022, 1023])
+        _say(f"C3 batch 1024 keep={keep}: oracle on {len(sample)} sampled queries")
         ref = net.sparse_forward(Xq[sample], keep)
         sub = {"out": got["out"][sample], "argmax": got["argmax"][sample],
                "taps": {k: [None if t is None else t[sample] for t in v] for k, v in got["taps"].items()}}
@@ -488,9 +493,10 @@ def test_config_c5_full_width_sampled(rt, oracle):
     keep = wl.keep_uniform(B, cfg.keep_range[0], cfg.keep_range[1], 6)
     # the timed batch, and a medium one that takes the same kernels in their other shapes: tiles of
     # 64 x 128, 1024-thread select workgroups, the integer hash below batch 256 (large projections)
-    for b, sample in ((2048, [0, 1, 15, 16, 17, 31, 500, 777, 1023, 1024, 1029, 1500, 2032, 2040, 2046, 2047]),
-                      (192, [0, 1, 17, 63, 64, 100, 127, 128, 150, 190, 191])):
-        sample = np.asarray(sample)
+    # (sampled: the first and the last query of every group of 16, i.e. both sides of every 16- and
+    # 128-query boundary of the unions and tiles)
+    for b in (2048, 192):
+        sample = np.asarray([q for q in range(b) if q % 16 in (0, 15)])
         _say(f"C5 full width, batch {b}: GPU pass")
         slonn.slonn_profile_begin(64)
         res = g.sparse_forward(Xq[:b], _keep_tensor(keep[:b]), taps=True)
@@ -505,17 +511,18 @@ def test_config_c5_full_width_sampled(rt, oracle):
         ref = net.sparse_forward(Xq[sample], keep[sample])
         sub = {"out": got["out"][sample], "argmax": got["argmax"][sample],
                "taps": {k: [None if t is None else t[sample] for t in v] for k, v in got["taps"].items()}}
-        rep = compare_sparse(sub, ref, layers, f"C5 full width batch {b}")
+        # six sparse layers deep the projections are of order 1e-3 (every layer keeps 2-30 % of its
+        # nodes), so the absolute 1e-6 tie zone catches a few per cent of the queries here
+        rep = compare_sparse(sub, ref, layers, f"C5 full width batch {b}", max_tainted=len(sample) // 10)
         _say(f"  {rep}")
-        assert rep["tainted"] < len(sample)
 
 
 @pytest.mark.parametrize("path", ["auto", "layers"])
 def test_config_c4_shape(rt, oracle, path):
     """Wiki10/Delicious-shaped model at its real width: 100 000 sparse features (100
     non-zeros) -> 128 -> 100 000 softmax outputs, K=12 L=50 on the output layer, keep
-    0.005 (500 nodes), batch 128.  Tables come from the oracle on a 256-input build set
-    (the device build does not cover layers this wide)."""
+    0.005 (500 nodes), batch 128.  Tables come from the oracle on a 256-input build set (the
+    device build of a layer this wide is compared with the oracle's in test_build_tables_matches_oracle)."""
     import copy
     cfg = wl.CONFIGS["C4"]
     layers, net, _ = make_case(oracle, cfg.dims, cfg.K, cfg.L, seed=0, hashed=[1], cap=600,
@@ -534,7 +541,8 @@ def test_config_c4_shape(rt, oracle, path):
     _say(f"C4 sparse forward path={path}")
     ref = net.sparse_forward(X, 0.005)
     got = to_numpy_result(g.sparse_forward(X, 0.005, taps=True, compact=True))
-    rep = compare_sparse(got, ref, layers, "C4")
+    # 600 projections per query on logits of order 0.1: the absolute 1e-6 tie zone takes a few queries
+    rep = compare_sparse(got, ref, layers, "C4", max_tainted=6)
     _say(f"  {rep}")
     ok = ~ref["layers"][1]["tie"]
     assert (got["cnt"][ok] == 500).all()
@@ -1013,3 +1021,38 @@ def test_maximum_batch(rt, oracle, path):
     assert np.array_equal(got["argmax"][ok], ref["argmax"][ok])
     assert_close_rows(got["out"], ref["out"], ok, "maximum batch")
     assert ok.sum() > 0.9 * B
+    if path == "layers":
+        # compact output of a last layer without a Node Activator: every node, ascending, for all 2^20
+        # queries (the batch runs along the grid's x dimension there)
+        _say("maximum batch: compact output")
+        r = to_numpy_result(g.sparse_forward(X, 0.25, compact=True))
+        assert (r["cnt"] == dims[-1]).all()
+        assert (r["idx"] == np.arange(dims[-1], dtype=np.int32)[None, :]).all()
+        assert_close_rows(r["out"], ref["out"], ok, "maximum batch, compact call")
+
+
+def test_maximum_batch_wide_hash(rt, oracle):
+    """2^20 queries against 128 hash rows: every tile shape of the batch-wide projection kernels puts
+    more than 65 535 tiles of queries along the batch, which the launcher cuts into chunks."""
+    dims = (16, 160, 4)
+    layers, net, _ = make_case(oracle, dims, 4, 32, seed=123, hashed=[0], N_build=64)
+    g = _gpu_net(rt, layers, net, path="layers")
+    B = 1 << 20
+    X = make_queries(dims, B, seed=124)
+    _say("maximum batch, 128 hash rows: select on the device")
+    sel = g.select(0, X, 0.05)
+    codes = sel["codes"].cpu().numpy().view(np.uint32)
+    z = sel["z"].cpu().numpy()
+    # the oracle on a sample of the queries spread over the whole batch, both chunks included
+    pick = np.concatenate([np.arange(0, B, 4099), np.arange(B - 64, B), np.arange((1 << 19) - 32, (1 << 19) + 32)])
+    Z = oracle.hash_project(layers[0], X[pick])
+    keys, tie = oracle.keys_from_z(Z, 4, 32)
+    okq = ~tie
+    assert np.array_equal(codes[pick][okq], keys[okq])
+    np.testing.assert_allclose(z[pick], Z, rtol=1e-6, atol=1e-6 * float(np.abs(Z).max()))
+    active, cnt = net.tables[0].select(keys, np.float32(0.05))
+    got_a = sel["active"].cpu().numpy()[pick]
+    got_c = sel["cnt"].cpu().numpy()[pick]
+    assert np.array_equal(got_c[okq], cnt[okq])
+    m = int(cnt[0])
+    assert np.array_equal(got_a[okq, :m], active[okq, :m])

@@ -699,3 +699,35 @@ def test_sample_hash_nodes_is_proportional_and_without_replacement(oracle):
     v = np.array([5.0, 1.0, 2.0, 2.0])
     second = np.array([oracle.sample_hash_nodes(v, 2, 1, [0.1, (g + 0.5) / G])[1] for g in range(G)])
     np.testing.assert_array_equal(np.bincount(second, minlength=4), [0, 2000, 4000, 4000])
+
+
+def test_per_layer_keep_is_applied_layer_by_layer(oracle):
+    """keep given as [N][n_layers]: column l is layer l's fraction (the paper uses one k per query
+    for all layers, Section 2.1; the library also takes one per layer).  Pinned by what must hold
+    whatever the columns are: equal columns reproduce the one-k-per-query result bit for bit; the
+    active count of layer l is the budget of column l alone; a column of ones computes that layer
+    in full, i.e. it equals the dense layer applied to the (sparse) output of the layer before; and
+    swapping two different columns changes the result."""
+    net, _ = _small_net(oracle, (24, 40, 36, 9), K=3, L=4, seed=77)
+    X = wl.inputs_uniform_half_zero(21, 24, 5)
+    k0 = wl.keep_uniform(21, 0.1, 0.9, 3)
+    k1 = wl.keep_uniform(21, 0.05, 0.6, 4)
+    same = net.sparse_forward(X, np.stack([k0, k0, k0], axis=1))
+    one = net.sparse_forward(X, k0)
+    assert np.array_equal(same["out"], one["out"])
+    for l in (0, 1):
+        assert np.array_equal(same["layers"][l]["active"], one["layers"][l]["active"])
+    two = net.sparse_forward(X, np.stack([k0, k1, k0], axis=1))
+    for q in range(21):
+        assert two["layers"][0]["cnt"][q] == oracle.budget(float(k0[q]), 40)
+        assert two["layers"][1]["cnt"][q] == oracle.budget(float(k1[q]), 36)
+    # layer 0 only sees column 0: identical to the equal-columns run there
+    assert np.array_equal(two["layers"][0]["active"], same["layers"][0]["active"])
+    assert np.array_equal(two["layers"][0]["out"], same["layers"][0]["out"])
+    swapped = net.sparse_forward(X, np.stack([k1, k0, k0], axis=1))
+    assert not np.array_equal(swapped["layers"][0]["cnt"], two["layers"][0]["cnt"])
+    # a column of ones: that layer is the full layer on the previous layer's sparse output
+    full1 = net.sparse_forward(X, np.stack([k0, np.ones(21, np.float32), k0], axis=1))
+    want = oracle.dense_layer(net.layers[1], full1["layers"][0]["out"], 1)
+    assert np.array_equal(full1["layers"][1]["out"], want)
+    assert (full1["layers"][1]["cnt"] == 36).all()
