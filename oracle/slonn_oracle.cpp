@@ -220,6 +220,43 @@ void* so_tables_build(int n, int K, int L, int list_cap, const uint32_t* keys, c
 
 void so_tables_free(void* h) { delete static_cast<Tables*>(h); }
 
+// Online refresh of a Node Activator (Section 3.2: the tables may be trained before or after
+// deployment; Section 6 names refreshing them as data drifts): Alg. 1 goes on where it stopped.
+// The N new inputs (their keys and the layer's activations for them, in order) are added to the
+// NodeScore of the buckets they fall into and to the whole-set sums, continuing every running
+// sum in input order; the buckets they touched and the whole-set ranking are sorted again.
+// Needs tables that kept their NodeScore (keep_scores).  Returns 0, or -1 without that state.
+int so_tables_refresh(void* h, const uint32_t* keys, const float* act, int64_t N) {
+  Tables* t = static_cast<Tables*>(h);
+  if (!t->keep_scores) return -1;
+  const int n = t->n, L = t->L;
+  for (int b = 0; b < L; ++b) {
+    auto& sc = t->score[b];
+    std::vector<uint32_t> touched;
+    for (int64_t x = 0; x < N; ++x) {
+      const uint32_t key = keys[x * L + b];
+      auto it = sc.find(key);
+      if (it == sc.end()) it = sc.emplace(key, std::vector<double>(n, 0.0)).first;
+      std::vector<double>& v = it->second;
+      const float* a = act + x * n;
+      for (int j = 0; j < n; ++j) v[j] += static_cast<double>(a[j]);
+      t->count[b][key] += 1;
+      touched.push_back(key);
+    }
+    for (uint32_t key : touched) t->rank[b][key] = rank_positive(sc[key], t->list_cap);
+  }
+  for (int64_t x = 0; x < N; ++x)
+    for (int j = 0; j < n; ++j) t->global_score[j] += static_cast<double>(act[x * n + j]);
+  for (int j = 0; j < n; ++j) t->global_rank[j] = j;
+  const std::vector<double>& g = t->global_score;
+  std::sort(t->global_rank.begin(), t->global_rank.end(), [&](int32_t a, int32_t b) {
+    if (g[a] != g[b]) return g[a] > g[b];
+    return a < b;
+  });
+  t->N += N;
+  return 0;
+}
+
 // Tables from explicit lists (used to load a table set built elsewhere): dir has
 // L*(2^K+1) offsets into ids, table-major.
 void* so_tables_from_lists(int n, int K, int L, int list_cap, const uint32_t* dir, const int32_t* ids,

@@ -140,6 +140,14 @@ class Tables:
         h = lib().so_tables_from_lists(n, K, L, list_cap, _p(dir_), _p(ids), _p(gr))
         return cls(h, n, K, L, list_cap)
 
+    def refresh(self, keys, act):
+        """Alg. 1 continued on more training inputs (their keys [N][L], the layer's activations
+        [N][n]); needs tables built with keep_scores."""
+        keys = np.ascontiguousarray(keys, np.uint32)
+        act = _f32(act)
+        if lib().so_tables_refresh(self.h, _p(keys), _p(act), C.c_int64(act.shape[0])) != 0:
+            raise ValueError("these tables did not keep their NodeScore sums")
+
     def bucket(self, b, key):
         buf = np.empty(self.n, np.int32)
         ln = lib().so_tables_bucket(self.h, b, C.c_uint32(int(key)), _p(buf), self.n)
@@ -365,6 +373,23 @@ class OracleNet:
                 act = dense_layer(layer, cur, self.threads)
                 self.tables[l] = Tables.build(layer.d_out, layer.K, layer.L, layer.list_cap, keys, act,
                                               keep_scores, self.threads)
+                cur = act
+            elif l == 0 and isinstance(cur, tuple):
+                cur = self._first(cur)
+            else:
+                cur = dense_layer(layer, cur, self.threads)
+        return self.tables
+
+    def refresh_tables(self, X_new):
+        """Online refresh: every Node Activator continues Alg. 1 on the inputs X_new (Input_l is
+        again the full network's input to layer l).  Tables must have been built with keep_scores."""
+        cur = X_new
+        for l, layer in enumerate(self.layers):
+            if layer.K > 0 and layer.L > 0:
+                Z = hash_project(layer, cur, self.threads)
+                keys, _ = keys_from_z(Z, layer.K, layer.L)
+                act = dense_layer(layer, cur, self.threads)
+                self.tables[l].refresh(keys, act)
                 cur = act
             elif l == 0 and isinstance(cur, tuple):
                 cur = self._first(cur)

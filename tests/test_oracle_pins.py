@@ -731,3 +731,72 @@ def test_per_layer_keep_is_applied_layer_by_layer(oracle):
     want = oracle.dense_layer(net.layers[1], full1["layers"][0]["out"], 1)
     assert np.array_equal(full1["layers"][1]["out"], want)
     assert (full1["layers"][1]["cnt"] == 36).all()
+
+
+def test_refresh_equals_alg1_on_the_concatenated_set(oracle):
+    """Online refresh continues Alg. 1: tables trained on A and refreshed with B must be the
+    tables Alg. 1 gives on A followed by B - same NodeScore sums to the last bit (every running
+    sum is continued in input order), same lists, same whole-set ranking, same bucket counts -
+    also when B opens buckets A never hit, and over two refreshes in a row."""
+    dims = (18, 30, 26, 7)
+    for K, L, cap in ((3, 4, None), (4, 2, 9)):
+        net_a, Xa = _small_net(oracle, dims, K=K, L=L, seed=91, cap=cap, N_build=40)
+        Xb = wl.inputs_uniform_half_zero(33, dims[0], 501)
+        Xc = wl.inputs_uniform_half_zero(5, dims[0], 502)
+        net_a.refresh_tables(Xb)
+        net_a.refresh_tables(Xc)
+        full = oracle.OracleNet(net_a.layers, threads=2)
+        full.build_tables(np.concatenate([Xa, Xb, Xc]), keep_scores=True)
+        opened = 0
+        for l in (0, 1):
+            ta, tf = net_a.tables[l], full.tables[l]
+            for b in range(L):
+                for key in range(1 << K):
+                    assert ta.bucket_count(b, key) == tf.bucket_count(b, key)
+                    assert ta.bucket(b, key).tolist() == tf.bucket(b, key).tolist()
+                    sa, sf = ta.bucket_scores(b, key), tf.bucket_scores(b, key)
+                    assert (sa is None) == (sf is None)
+                    if sa is not None:
+                        assert np.array_equal(sa, sf)
+            ga, sa = ta.global_rank()
+            gf, sf = tf.global_rank()
+            assert ga.tolist() == gf.tolist() and np.array_equal(sa, sf)
+        # the refresh really changed something: the tables differ from those trained on A alone
+        only_a = oracle.OracleNet(net_a.layers, threads=2)
+        only_a.build_tables(Xa, keep_scores=True)
+        differ = any(only_a.tables[0].bucket(b, key).tolist() != net_a.tables[0].bucket(b, key).tolist()
+                     for b in range(L) for key in range(1 << K))
+        assert differ
+    # tables without their sums cannot be refreshed
+    lean, Xa = _small_net(oracle, dims, K=3, L=4, seed=91, N_build=40, keep_scores=False)
+    with pytest.raises(ValueError):
+        lean.refresh_tables(Xa[:3])
+
+
+def test_refresh_worked_example(oracle):
+    """The hand-worked example's tables refreshed with its first query as a fifth training input
+    q = (.75, .25): keys (3, 2), activations (.75, .25, .25, .5, 0, .25).  By hand:
+    T0[3] = (2, .5, 1, 1.5, 0, .25) + a = (2.75, .75, 1.25, 2, 0, .5) -> [0, 3, 2, 1, 5];
+    T1[2] = (1.5, 0, .25, 1.5, 0, 1) + a = (2.25, .25, .5, 2, 0, 1.25) -> [0, 3, 5, 2, 1];
+    Global = (2.5, 1.5, 1.25, 2, 1.25, 1.25) + a = (3.25, 1.75, 1.5, 2.5, 1.25, 1.5) -> [0, 3, 1, 2, 5, 4]
+    (nodes 2 and 5 tie at 1.5: lower id first); every other bucket is untouched."""
+    with open(GOLD) as f:
+        gold = json.load(f)
+    lay = wl.LayerData(2, 6, wl.ACT_RELU, wl.W_F32, np.asarray(gold["W"], np.float32),
+                       np.asarray(gold["bias"], np.float32), 2, 2, 6, np.asarray(gold["hash_nodes"], np.int32))
+    net = oracle.OracleNet([lay], threads=1)
+    net.build_tables(np.asarray(gold["build"], np.float32), keep_scores=True)
+    before = {(b, k): net.tables[0].bucket(b, k).tolist() for b in range(2) for k in range(4)}
+    net.refresh_tables(np.asarray([[0.75, 0.25]], np.float32))
+    t = net.tables[0]
+    assert t.bucket(0, 3).tolist() == [0, 3, 2, 1, 5]
+    assert t.bucket_scores(0, 3).tolist() == [2.75, 0.75, 1.25, 2.0, 0.0, 0.5]
+    assert t.bucket(1, 2).tolist() == [0, 3, 5, 2, 1]
+    assert t.bucket_scores(1, 2).tolist() == [2.25, 0.25, 0.5, 2.0, 0.0, 1.25]
+    gr, gs = t.global_rank()
+    assert gs.tolist() == [3.25, 1.75, 1.5, 2.5, 1.25, 1.5]
+    assert gr.tolist() == [0, 3, 1, 2, 5, 4]
+    for (b, k), lst in before.items():
+        if (b, k) not in ((0, 3), (1, 2)):
+            assert t.bucket(b, k).tolist() == lst
+    assert t.bucket_count(0, 3) == 3 and t.bucket_count(1, 2) == 3
