@@ -202,6 +202,19 @@ int slonn_model_set_hash_nodes_always_active(slonn_model* m, int on);
 int slonn_activation_variance(const float* A, int64_t N, int n, int64_t lda, double* var_out, void* stream);
 int slonn_sample_hash_nodes(const double* variance, int n, int K, int L, const double* u,
                             int32_t* hash_nodes_out);
+/* The same draws on the device, so that variance (as slonn_activation_variance leaves it), draws
+ * and ids never visit the host: variance [n], u [K*L] and hash_nodes_out [K*L] are DEVICE arrays;
+ * asynchronous on `stream`.  Same ids as slonn_sample_hash_nodes, id for id (the running sums are
+ * formed in the same order).  EUNSUPPORTED: n above 2^20.  (slonn_model_create takes hash_nodes
+ * from the host: copy the K*L ids back once.)                                               */
+int slonn_sample_hash_nodes_device(const double* variance, int n, int K, int L, const double* u,
+                                   int32_t* hash_nodes_out, void* stream);
+
+/* Online refresh (Section 3.2: the tables can be trained before or after deployment; Section 6:
+ * refreshed as the data drifts).  on != 0, set before slonn_build_tables: the tables keep their
+ * NodeScore sums on the device (L * 2^K * n doubles per activated layer, plus the whole-set sums),
+ * which slonn_tables_refresh needs.  Default off.  EINVAL: null model.                        */
+int slonn_model_set_tables_refreshable(slonn_model* m, int on);
 
 /* Alg. 1 for every activated layer, on the device.  X_build holds N training inputs
  * (device).  Input_l is the full network's output of layer l-1 on X_build; the
@@ -209,10 +222,23 @@ int slonn_sample_hash_nodes(const double* variance, int n, int K, int L, const d
  * positive-score nodes sorted from the highest sum to the lowest (ties: lower id),
  * at most list_cap of them; the sums over all N inputs give the fallback ranking.
  * Allocates temporary device memory, synchronises `stream`, returns owned tables.
- * N <= SLONN_MAX_BATCH.  EUNSUPPORTED: an activated layer wider than 8192 nodes whose
- * list_cap also exceeds 8192 (wide layers rank only the head of each bucket).        */
+ * N <= SLONN_MAX_BATCH.  Everything runs on the device (layers up to 8192 nodes sort each
+ * bucket in LDS; wider layers rank the head of a bucket through a score threshold, or sort
+ * whole buckets when lists longer than 8192 ids are asked for or sums are equal in masses).
+ * ENOMEM: the NodeScore sums of refreshable tables do not fit.                       */
 int slonn_build_tables(const slonn_model* m, const slonn_input* X_build, int64_t N, void* stream,
                        slonn_tables** out);
+
+/* Alg. 1 continued on N more training inputs X_new (device): they are added to the NodeScore
+ * sums of the buckets they fall into and to the whole-set sums, every running sum continued in
+ * input order; the buckets they touched and the whole-set ranking are sorted again, the other
+ * lists are kept.  Afterwards the tables are, bit for bit, those slonn_build_tables gives on all
+ * inputs seen so far in the order they arrived.  Synchronises `stream`; replaces the tables'
+ * device arrays, so no select / forward call on these tables may be in flight.
+ * EUNSUPPORTED: tables without NodeScore sums (trained without
+ * slonn_model_set_tables_refreshable, or imported).  After any other failure discard the tables. */
+int slonn_tables_refresh(const slonn_model* m, slonn_tables* t, const slonn_input* X_new, int64_t N,
+                         void* stream);
 
 /* Table blob (host memory, little endian, all fields 4 bytes wide):
  *   u32 magic, u32 version, u32 n_sets, u32 0

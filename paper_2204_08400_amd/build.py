@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslonn.so")
 SOURCES = ["slonn_api.hip", "kernels_hash.hip", "kernels_select.hip", "kernels_gather.hip",
            "kernels_dense.hip", "kernels_build.hip", "kernels_fused.hip", "kernels_grouped.hip", "kernels_policy.hip", "kernels_fused_wide.hip",
-           "kernels_variance.hip", "kernels_tiles.hip", "kernels_hash_int.hip"]
+           "kernels_variance.hip", "kernels_tiles.hip", "kernels_hash_int.hip", "kernels_rank_sort.hip"]
 
 
 def hipcc() -> str:

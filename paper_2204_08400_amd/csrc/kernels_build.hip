@@ -26,16 +26,19 @@ __global__ void keys_kernel(const float* __restrict__ Z, int K, int L, int64_t N
   keys[e] = key;
 }
 
-// NodeScore[key][j] = sum of act[x][j] over the bucket's members, in order
+// NodeScore[key][j] = sum of act[x][j] over the bucket's members, in order.  accumulate != 0
+// (online refresh): the sums continue from the kept NodeScore, and buckets without new members
+// are left as they are (npos[key] must have been cleared for the others).
 __global__ void node_score_kernel(const float* __restrict__ act, int n, const uint32_t* __restrict__ start,
                                   const uint32_t* __restrict__ members, double* __restrict__ score,
-                                  uint32_t* __restrict__ npos) {
+                                  uint32_t* __restrict__ npos, int accumulate) {
   const int key = blockIdx.y;
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
-  double s = 0.0;
   uint32_t i = start[key];
   const uint32_t end = start[key + 1];
+  if (accumulate && i == end) return;
+  double s = accumulate ? score[(size_t)key * n + j] : 0.0;
   for (; i + 8 <= end; i += 8) {        // eight loads in flight, added in input order
     float v[8];
 #pragma unroll
@@ -49,10 +52,10 @@ __global__ void node_score_kernel(const float* __restrict__ act, int n, const ui
 }
 
 __global__ void total_score_kernel(const float* __restrict__ act, int n, int64_t N,
-                                   double* __restrict__ score) {
+                                   double* __restrict__ score, int accumulate) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
-  double s = 0.0;
+  double s = accumulate ? score[j] : 0.0;
   int64_t x = 0;
   for (; x + 8 <= N; x += 8) {          // eight loads in flight, added in input order
     float v[8];
@@ -121,16 +124,19 @@ __device__ __forceinline__ bool pair_before(double sa, int a, double sb, int b) 
 // Bitonic sort of one bucket's (score, node id) pairs in LDS (12 bytes per node: P doubles,
 // then P ids).  positive_only: nodes with a sum <= 0 are left out.  Writes the first
 // out_len[bucket] ids at out + out_off[bucket].
+// members (nullable): start offsets of the buckets' new member lists; a bucket without new members
+// (members[bucket] == members[bucket + 1]) is skipped (online refresh copies its old list instead).
 __global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ score, int n, int P,
                                                   int positive_only, const uint32_t* __restrict__ out_off,
                                                   const uint32_t* __restrict__ out_len,
-                                                  int32_t* __restrict__ out) {
+                                                  int32_t* __restrict__ out, const uint32_t* __restrict__ members) {
   extern __shared__ __align__(16) unsigned char rank_smem[];
   double* key = reinterpret_cast<double*>(rank_smem);
   int32_t* ids = reinterpret_cast<int32_t*>(key + P);
   const int bucket = blockIdx.x;
   const uint32_t len = out_len[bucket];
   if (len == 0) return;
+  if (members && members[bucket] == members[bucket + 1]) return;
   const double* sc = score + (size_t)bucket * n;
   for (int i = threadIdx.x; i < P; i += 256) {
     int v = -1;
@@ -184,13 +190,15 @@ __device__ __forceinline__ int block_count_ge(const double* sc, int n, double th
 __global__ __launch_bounds__(256) void rank_wide_kernel(const double* __restrict__ score, int n,
                                                        const uint32_t* __restrict__ out_off,
                                                        const uint32_t* __restrict__ out_len,
-                                                       int32_t* __restrict__ out, int* __restrict__ fail) {
+                                                       int32_t* __restrict__ out, int* __restrict__ fail,
+                                                       const uint32_t* __restrict__ members) {
   __shared__ double samp[SAMPLE];          // 32 KB, reused as the candidate id buffer
   __shared__ int red[8];
   int32_t* ids = reinterpret_cast<int32_t*>(samp);
   const int bucket = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int len = (int)out_len[bucket];
   if (len == 0) return;
+  if (members && members[bucket] == members[bucket + 1]) return;
   const double* sc = score + (size_t)bucket * n;
 
   // threshold: start from the sample value whose rank predicts about four times len candidates
@@ -267,11 +275,32 @@ __global__ __launch_bounds__(256) void rank_wide_kernel(const double* __restrict
   for (int i = tid; i < len; i += 256) dst[i] = ids[i];
 }
 
+// buckets that received new members start again from no positive node (online refresh)
+__global__ void clear_touched_npos_kernel(const uint32_t* __restrict__ start, int nb, uint32_t* __restrict__ npos) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < nb && start[k] != start[k + 1]) npos[k] = 0u;
+}
+
+// Online refresh: a bucket without new members keeps its list; it moves to its new place in the
+// id array (old_dir: the table's old directory row; its length has not changed).
+__global__ __launch_bounds__(256) void copy_untouched_lists_kernel(const uint32_t* __restrict__ start,
+                                                                  const uint32_t* __restrict__ old_dir,
+                                                                  const int32_t* __restrict__ old_ids,
+                                                                  const uint32_t* __restrict__ off,
+                                                                  const uint32_t* __restrict__ len,
+                                                                  int32_t* __restrict__ out) {
+  const int bucket = blockIdx.x;
+  if (start[bucket] != start[bucket + 1]) return;
+  const uint32_t l = len[bucket], from = old_dir[bucket], to = off[bucket];
+  for (uint32_t i = threadIdx.x; i < l; i += 256) out[to + i] = old_ids[from + i];
+}
+
 template <class T>
 struct DevBuf {
   T* p = nullptr;
   ~DevBuf() { if (p) (void)hipFree(p); }
   hipError_t alloc(size_t count) { return hipMalloc(&p, std::max<size_t>(count, 1) * sizeof(T)); }
+  T* release() { T* q = p; p = nullptr; return q; }
 };
 
 }  // namespace
@@ -280,7 +309,11 @@ void free_table_set(TableSet* ts) {
   if (ts->d_dir) (void)hipFree(ts->d_dir);
   if (ts->d_ids) (void)hipFree(ts->d_ids);
   if (ts->d_global_rank) (void)hipFree(ts->d_global_rank);
+  if (ts->d_score) (void)hipFree(ts->d_score);
+  if (ts->d_global_score) (void)hipFree(ts->d_global_score);
+  if (ts->d_npos) (void)hipFree(ts->d_npos);
   ts->d_dir = nullptr; ts->d_ids = nullptr; ts->d_global_rank = nullptr;
+  ts->d_score = nullptr; ts->d_global_score = nullptr; ts->d_npos = nullptr;
 }
 
 int upload_table_set(TableSet* ts, const int32_t* d_ids_src) {
@@ -298,35 +331,47 @@ int upload_table_set(TableSet* ts, const int32_t* d_ids_src) {
   return SLONN_OK;
 }
 
+// Alg. 1 for one layer on N training inputs X_l (act: the layer's own output for them).
+// refresh == false: from nothing.  refresh == true: ts holds the NodeScore sums of the inputs seen
+// so far (tables trained with slonn_model_set_tables_refreshable); the new inputs are added to
+// the buckets they hit and to the whole-set sums, every running sum continued in input order, the
+// touched buckets and the whole-set ranking are sorted again, the other lists are copied.
 int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_t N, const float* act,
-                       TableSet* ts, hipStream_t s) {
+                       TableSet* ts, bool refresh, hipStream_t s) {
   const Layer& Ly = m->layers[layer];
   const int n = Ly.d_out, K = Ly.K, L = Ly.L, H = Ly.H();
   const bool wide = n > SORT_MAX;
-  if (wide && std::min(Ly.list_cap, n) > SORT_MAX)
-    SLONN_FAIL(SLONN_EUNSUPPORTED, "build: layer %d has %d nodes; lists of wide layers hold at most %d ids",
-               layer, n, SORT_MAX);
   if (N <= 0 || N > 0x7FFFFFFF) SLONN_FAIL(SLONN_EINVAL, "build: bad training-set size");
   const int nb = 1 << K;
   int P = 1;
   while (P < n) P <<= 1;
   if (P < 2) P = 2;
   const int cap = std::min(Ly.list_cap, n);
+  // wide layers rank the head of each bucket through a threshold when the lists are short enough
+  // for an LDS sort of the candidates, otherwise (and when masses of equal sums defeat the
+  // threshold) through a radix sort of the whole bucket
+  bool use_sort = wide && cap > SORT_MAX;
   const size_t rank_lds = (size_t)P * 12;           // (score, id) pairs of the LDS sort
   if (!wide && rank_lds > 65536)
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)rank_lds));
+  const bool keep = refresh || m->tables_refreshable;
+  if (refresh && (!ts->d_score || !ts->d_npos || !ts->d_global_score))
+    SLONN_FAIL(SLONN_EUNSUPPORTED, "refresh: the tables of layer %d hold no NodeScore sums", layer);
 
-  ts->layer = layer; ts->K = K; ts->L = L; ts->n = n; ts->list_cap = Ly.list_cap;
-  ts->dir.assign((size_t)L * (nb + 1), 0);
-  ts->ids.clear();
-  ts->global_rank.assign(n, 0);
+  if (!refresh) {
+    ts->layer = layer; ts->K = K; ts->L = L; ts->n = n; ts->list_cap = Ly.list_cap;
+    ts->dir.assign((size_t)L * (nb + 1), 0);
+    ts->ids.clear();
+    ts->global_rank.assign(n, 0);
+    ts->nonempty = 0;
+  }
 
   DevBuf<float> Z;
-  DevBuf<uint32_t> keys, hist, start, cursor, members, npos, off, len, dir, base;
+  DevBuf<uint32_t> keys, hist, start, cursor, members, npos_tmp, off, len, dir, base;
   DevBuf<unsigned long long> nonempty;
-  DevBuf<double> score;
-  DevBuf<int32_t> out;
+  DevBuf<double> score_tmp, gscore_tmp;
+  DevBuf<int32_t> out, gr;
   DevBuf<int> fail;
   SLONN_HIP(fail.alloc(1));
   SLONN_HIP(hipMemsetAsync(fail.p, 0, sizeof(int), s));
@@ -336,13 +381,33 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
   SLONN_HIP(start.alloc((size_t)L * (nb + 1)));
   SLONN_HIP(cursor.alloc((size_t)L * nb));
   SLONN_HIP(members.alloc((size_t)L * N));
-  SLONN_HIP(npos.alloc((size_t)L * nb));
   SLONN_HIP(off.alloc(nb));
   SLONN_HIP(len.alloc(nb));
   SLONN_HIP(dir.alloc((size_t)L * (nb + 1)));
   SLONN_HIP(base.alloc(1));
   SLONN_HIP(nonempty.alloc(1));
-  SLONN_HIP(score.alloc((size_t)nb * n));
+  SLONN_HIP(gr.alloc(n));
+  double* score = nullptr;       // [L][nb][n] when kept, else [nb][n] reused by every table
+  uint32_t* npos = nullptr;      // [L][nb]
+  double* gscore = nullptr;      // [n]
+  if (keep) {
+    if (!refresh) {
+      hipError_t e = hipMalloc(&ts->d_score, (size_t)L * nb * n * sizeof(double));
+      if (e == hipSuccess) e = hipMalloc(&ts->d_npos, (size_t)L * nb * 4);
+      if (e == hipSuccess) e = hipMalloc(&ts->d_global_score, (size_t)n * sizeof(double));
+      if (e != hipSuccess) {
+        (void)hipGetLastError();
+        SLONN_FAIL(SLONN_ENOMEM, "build: layer %d: the NodeScore sums kept for online refresh need %zu bytes", layer,
+                   (size_t)L * nb * n * sizeof(double));
+      }
+    }
+    score = ts->d_score; npos = ts->d_npos; gscore = ts->d_global_score;
+  } else {
+    SLONN_HIP(score_tmp.alloc((size_t)nb * n));
+    SLONN_HIP(npos_tmp.alloc((size_t)L * nb));
+    SLONN_HIP(gscore_tmp.alloc(n));
+    score = score_tmp.p; npos = npos_tmp.p; gscore = gscore_tmp.p;
+  }
 
   int rc = launch_hash_project(X_l, Ly.d_in, Ly.Wh, Ly.bh, Z.p, (int)N, H, Ly.d_in, nullptr, nullptr, s);
   if (rc) return rc;
@@ -352,8 +417,6 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
 
   // bucket member lists of all L tables at once
   SLONN_HIP(hipMemsetAsync(hist.p, 0, (size_t)L * nb * 4, s));
-  SLONN_HIP(hipMemsetAsync(npos.p, 0, (size_t)L * nb * 4, s));
-  SLONN_HIP(hipMemsetAsync(base.p, 0, 4, s));
   SLONN_HIP(hipMemsetAsync(nonempty.p, 0, 8, s));
   hipLaunchKernelGGL(bucket_hist_kernel, dim3((unsigned)((tot_keys + 255) / 256)), dim3(256), 0, s, keys.p, N, L, nb,
                      hist.p);
@@ -366,65 +429,107 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
   hipLaunchKernelGGL(count_nonempty_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, s, hist.p, cells,
                      nonempty.p);
   SLONN_HIP(hipGetLastError());
-  // every non-empty bucket keeps at most cap ids: size the id array once, for all tables
+  // every bucket with a list keeps at most cap ids: size the id array once, for all tables (after a
+  // refresh: the buckets that had a list before plus the buckets the new inputs hit)
   unsigned long long h_nonempty = 0;
   SLONN_HIP(hipMemcpyAsync(&h_nonempty, nonempty.p, 8, hipMemcpyDeviceToHost, s));
   SLONN_HIP(hipStreamSynchronize(s));
-  const unsigned long long id_bound = h_nonempty * (unsigned long long)cap;
+  const unsigned long long id_bound =
+      std::min<unsigned long long>(h_nonempty + (refresh ? ts->nonempty : 0), (unsigned long long)cells) *
+      (unsigned long long)cap;
   if (id_bound > 0xFFFFFFFFull)
     SLONN_FAIL(SLONN_EUNSUPPORTED, "build: layer %d: up to %llu list entries do not fit 32-bit offsets", layer,
                id_bound);
   SLONN_HIP(out.alloc((size_t)id_bound));
 
   // per table: NodeScore sums, list lengths and places, ranking -- no host round trip
-  for (int b = 0; b < L; ++b) {
-    const uint32_t* st = start.p + (size_t)b * (nb + 1);
-    hipLaunchKernelGGL(node_score_kernel, dim3((n + 255) / 256, nb), dim3(256), 0, s, act, n, st,
-                       members.p + (size_t)b * N, score.p, npos.p + (size_t)b * nb);
-    SLONN_HIP(hipGetLastError());
-    hipLaunchKernelGGL(layout_kernel, dim3(1), dim3(256), 0, s, npos.p + (size_t)b * nb, nb, (uint32_t)cap, base.p,
-                       off.p, len.p, dir.p + (size_t)b * (nb + 1));
-    SLONN_HIP(hipGetLastError());
-    if (wide)
-      hipLaunchKernelGGL(rank_wide_kernel, dim3(nb), dim3(256), 0, s, score.p, n, off.p, len.p, out.p, fail.p);
-    else
-      hipLaunchKernelGGL(rank_kernel, dim3(nb), dim3(256), rank_lds, s, score.p, n, P, 1, off.p, len.p, out.p);
-    SLONN_HIP(hipGetLastError());
+  auto run_tables = [&](bool sums, bool by_sort) -> int {
+    SLONN_HIP(hipMemsetAsync(base.p, 0, 4, s));
+    if (sums && !refresh) SLONN_HIP(hipMemsetAsync(npos, 0, (size_t)L * nb * 4, s));
+    for (int b = 0; b < L; ++b) {
+      const uint32_t* st = start.p + (size_t)b * (nb + 1);
+      double* sc = keep ? score + (size_t)b * nb * n : score;
+      uint32_t* np_b = npos + (size_t)b * nb;
+      if (sums) {
+        if (refresh) {
+          hipLaunchKernelGGL(clear_touched_npos_kernel, dim3((nb + 255) / 256), dim3(256), 0, s, st, nb, np_b);
+          SLONN_HIP(hipGetLastError());
+        }
+        hipLaunchKernelGGL(node_score_kernel, dim3((n + 255) / 256, nb), dim3(256), 0, s, act, n, st,
+                           members.p + (size_t)b * N, sc, np_b, refresh ? 1 : 0);
+        SLONN_HIP(hipGetLastError());
+      }
+      hipLaunchKernelGGL(layout_kernel, dim3(1), dim3(256), 0, s, np_b, nb, (uint32_t)cap, base.p, off.p, len.p,
+                         dir.p + (size_t)b * (nb + 1));
+      SLONN_HIP(hipGetLastError());
+      const uint32_t* only = refresh ? st : nullptr;      // a refresh ranks the buckets with new members
+      if (by_sort) {
+        const int rc2 = rank_by_sort(sc, n, nb, off.p, len.p, only, out.p, s);
+        if (rc2) return rc2;
+      } else if (wide) {
+        hipLaunchKernelGGL(rank_wide_kernel, dim3(nb), dim3(256), 0, s, sc, n, off.p, len.p, out.p, fail.p, only);
+      } else {
+        hipLaunchKernelGGL(rank_kernel, dim3(nb), dim3(256), rank_lds, s, sc, n, P, 1, off.p, len.p, out.p, only);
+      }
+      SLONN_HIP(hipGetLastError());
+      if (refresh) {
+        hipLaunchKernelGGL(copy_untouched_lists_kernel, dim3(nb), dim3(256), 0, s, st,
+                           ts->d_dir + (size_t)b * (nb + 1), ts->d_ids, off.p, len.p, out.p);
+        SLONN_HIP(hipGetLastError());
+      }
+    }
+    return SLONN_OK;
+  };
+  rc = run_tables(true, use_sort);
+  if (rc) return rc;
+  if (wide && !use_sort) {
+    int h_fail = 0;
+    SLONN_HIP(hipMemcpyAsync(&h_fail, fail.p, sizeof(int), hipMemcpyDeviceToHost, s));
+    SLONN_HIP(hipStreamSynchronize(s));
+    if (h_fail) {
+      // some bucket holds so many exactly equal sums that no threshold isolates the head of its
+      // list: rank every bucket by a full sort instead (equal sums fall in ascending id order).
+      // Kept sums are final already; sums in the per-table buffer are formed again.
+      use_sort = true;
+      rc = run_tables(!keep, true);
+      if (rc) return rc;
+    }
   }
   uint32_t h_total = 0;
+  std::vector<uint32_t> h_dir((size_t)L * (nb + 1));
   SLONN_HIP(hipMemcpyAsync(&h_total, base.p, 4, hipMemcpyDeviceToHost, s));
-  SLONN_HIP(hipMemcpyAsync(ts->dir.data(), dir.p, (size_t)L * (nb + 1) * 4, hipMemcpyDeviceToHost, s));
-  SLONN_HIP(hipStreamSynchronize(s));
-  ts->n_ids = h_total;                          // the lists stay on the device (export copies them out)
+  SLONN_HIP(hipMemcpyAsync(h_dir.data(), dir.p, (size_t)L * (nb + 1) * 4, hipMemcpyDeviceToHost, s));
 
   // whole-set ranking: every node, zero sums included
-  hipLaunchKernelGGL(total_score_kernel, dim3((n + 255) / 256), dim3(256), 0, s, act, n, N, score.p);
+  hipLaunchKernelGGL(total_score_kernel, dim3((n + 255) / 256), dim3(256), 0, s, act, n, N, gscore, refresh ? 1 : 0);
   SLONN_HIP(hipGetLastError());
-  if (wide) {
-    // one ranking of all n nodes per layer: sorted on the host with the same comparison
-    int h_fail = 0;
-    std::vector<double> h_score(n);
-    SLONN_HIP(hipMemcpyAsync(&h_fail, fail.p, sizeof(int), hipMemcpyDeviceToHost, s));
-    SLONN_HIP(hipMemcpyAsync(h_score.data(), score.p, (size_t)n * 8, hipMemcpyDeviceToHost, s));
-    SLONN_HIP(hipStreamSynchronize(s));
-    if (h_fail)
-      SLONN_FAIL(SLONN_EUNSUPPORTED, "build: layer %d: a bucket has too many equal activation sums to rank", layer);
-    for (int j = 0; j < n; ++j) ts->global_rank[j] = j;
-    std::sort(ts->global_rank.begin(), ts->global_rank.end(), [&](int32_t a, int32_t b) {
-      if (h_score[a] != h_score[b]) return h_score[a] > h_score[b];
-      return a < b;
-    });
-    return upload_table_set(ts, out.p);
-  }
   const uint32_t zero = 0, all = (uint32_t)n;
   SLONN_HIP(hipMemcpyAsync(off.p, &zero, 4, hipMemcpyHostToDevice, s));
   SLONN_HIP(hipMemcpyAsync(len.p, &all, 4, hipMemcpyHostToDevice, s));
-  DevBuf<int32_t> gr;
-  SLONN_HIP(gr.alloc(n));
-  hipLaunchKernelGGL(rank_kernel, dim3(1), dim3(256), rank_lds, s, score.p, n, P, 0, off.p, len.p, gr.p);
-  SLONN_HIP(hipGetLastError());
-  SLONN_HIP(hipMemcpyAsync(ts->global_rank.data(), gr.p, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+  if (wide) {
+    rc = rank_by_sort(gscore, n, 1, off.p, len.p, nullptr, gr.p, s);
+    if (rc) return rc;
+  } else {
+    hipLaunchKernelGGL(rank_kernel, dim3(1), dim3(256), rank_lds, s, gscore, n, P, 0, off.p, len.p, gr.p, nullptr);
+    SLONN_HIP(hipGetLastError());
+  }
+  std::vector<int32_t> h_gr(n);
+  SLONN_HIP(hipMemcpyAsync(h_gr.data(), gr.p, (size_t)n * 4, hipMemcpyDeviceToHost, s));
   SLONN_HIP(hipStreamSynchronize(s));
+
+  // publish: directory, lists (they stay on the device; export copies them out), ranking
+  ts->dir.swap(h_dir);
+  ts->global_rank.swap(h_gr);
+  ts->n_ids = h_total;
+  ts->nonempty = 0;
+  for (int b = 0; b < L; ++b)
+    for (int k = 0; k < nb; ++k)
+      if (ts->dir[(size_t)b * (nb + 1) + k + 1] > ts->dir[(size_t)b * (nb + 1) + k]) ++ts->nonempty;
+  ts->n_trained += N;
+  if (ts->d_dir) (void)hipFree(ts->d_dir);
+  if (ts->d_ids) (void)hipFree(ts->d_ids);
+  if (ts->d_global_rank) (void)hipFree(ts->d_global_rank);
+  ts->d_dir = nullptr; ts->d_ids = nullptr; ts->d_global_rank = nullptr;
   return upload_table_set(ts, out.p);
 }
 
@@ -432,67 +537,71 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
 
 using namespace slonn;
 
-extern "C" int slonn_build_tables(const slonn_model* m, const slonn_input* X_build, int64_t N, void* stream,
-                                  slonn_tables** out) {
-  if (!out) SLONN_FAIL(SLONN_EINVAL, "out is null");
-  *out = nullptr;
-  if (!m || !X_build) SLONN_FAIL(SLONN_EINVAL, "null argument");
+namespace slonn {
+namespace {
+
+int check_training_input(const slonn_model* m, const slonn_input* X, int64_t N) {
+  if (!m || !X) SLONN_FAIL(SLONN_EINVAL, "null argument");
   if (N <= 0 || N > SLONN_MAX_BATCH) SLONN_FAIL(SLONN_EINVAL, "N must be in 1 .. %d", SLONN_MAX_BATCH);
-  if (X_build->format == SLONN_DENSE) {
-    if (!X_build->x) SLONN_FAIL(SLONN_EINVAL, "dense input pointer is null");
+  if (X->format == SLONN_DENSE) {
+    if (!X->x) SLONN_FAIL(SLONN_EINVAL, "dense input pointer is null");
     if (m->layers[0].w_layout != SLONN_ROWS_ARE_NODES)
       SLONN_FAIL(SLONN_EUNSUPPORTED, "dense input needs a node-major first layer");
-  } else if (X_build->format == SLONN_ELL) {
-    if (!X_build->idx || !X_build->val || !X_build->nnz || X_build->ell_stride <= 0)
+  } else if (X->format == SLONN_ELL) {
+    if (!X->idx || !X->val || !X->nnz || X->ell_stride <= 0)
       SLONN_FAIL(SLONN_EINVAL, "ELL input needs idx, val, nnz and a positive ell_stride");
     if (m->layers[0].activated())
       SLONN_FAIL(SLONN_EUNSUPPORTED, "a Node Activator on a sparse-input first layer is not supported");
   } else {
-    SLONN_FAIL(SLONN_EINVAL, "unknown input format %d", X_build->format);
+    SLONN_FAIL(SLONN_EINVAL, "unknown input format %d", X->format);
   }
-  for (const Layer& L : m->layers)
-    if (L.activated() && L.d_out > SORT_MAX && std::min(L.list_cap, L.d_out) > SORT_MAX)
-      SLONN_FAIL(SLONN_EUNSUPPORTED,
-                 "build: an activated layer has %d nodes; layers wider than %d need list_cap <= %d", L.d_out,
-                 SORT_MAX, SORT_MAX);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  slonn_tables* t = new (std::nothrow) slonn_tables;
-  if (!t) SLONN_FAIL(SLONN_ENOMEM, "out of host memory");
-  t->model = m;
-  auto fail = [&](int code) {
-    slonn_tables_destroy(t);
-    return code;
-  };
+  return SLONN_OK;
+}
 
+// The full network on the training inputs, layer by layer (Input_l is the full network's output
+// of layer l-1); every activated layer trains (refresh == false) or refreshes its tables.
+int train_tables(const slonn_model* m, slonn_tables* t, const slonn_input* X, int64_t N, bool refresh,
+                 hipStream_t s) {
   const int nl = (int)m->layers.size();
   int last_needed = -1;
   for (int l = 0; l < nl; ++l)
     if (m->layers[l].activated()) last_needed = l;
-  float* prev = nullptr;   // Input_l: the full network's output of layer l-1
-  const float* cur = X_build->x;
+  float* prev = nullptr;
+  const float* cur = X->x;
   int rc = SLONN_OK;
   for (int l = 0; l <= last_needed && rc == SLONN_OK; ++l) {
     const Layer& L = m->layers[l];
     float* act = nullptr;
     hipError_t e = hipMalloc(&act, (size_t)N * L.d_out * 4);
     if (e != hipSuccess) {
+      (void)hipGetLastError();
       set_error("build: cannot allocate %zu bytes for layer %d activations", (size_t)N * L.d_out * 4, l);
       rc = SLONN_ENOMEM;
       break;
     }
-    if (l == 0 && X_build->format == SLONN_ELL)
-      rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X_build->idx, X_build->val, X_build->nnz,
-                            X_build->ell_stride, act, L.d_out, (int)N, L.d_in, L.d_out, L.act, s);
+    if (l == 0 && X->format == SLONN_ELL)
+      rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, act,
+                            L.d_out, (int)N, L.d_in, L.d_out, L.act, s);
     else
+      // (refreshable tables: one kernel shape for every training-set size, so that an input's
+      // activations - and with them every NodeScore sum - are the same whether it arrives in the
+      // first training set or in a later refresh)
       rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, L.d_in, act, L.d_out, (int)N, L.d_in, L.d_out,
-                              L.act, nullptr, s);
+                              L.act, nullptr, s, refresh || m->tables_refreshable);
     if (rc == SLONN_OK && L.act == SLONN_ACT_SOFTMAX)
       rc = launch_finalize(act, L.d_out, L.d_out, nullptr, nullptr, 0, nullptr, 0, 1, nullptr, (int)N, s);
     if (rc == SLONN_OK && L.activated()) {
-      TableSet ts;
-      rc = build_layer_tables(m, l, cur, N, act, &ts, s);
-      if (rc == SLONN_OK) t->sets.push_back(std::move(ts));
-      else free_table_set(&ts);
+      if (refresh) {
+        TableSet* ts = nullptr;
+        for (TableSet& c : t->sets)
+          if (c.layer == l) ts = &c;
+        rc = build_layer_tables(m, l, cur, N, act, ts, true, s);
+      } else {
+        TableSet ts;
+        rc = build_layer_tables(m, l, cur, N, act, &ts, false, s);
+        if (rc == SLONN_OK) t->sets.push_back(std::move(ts));
+        else free_table_set(&ts);
+      }
     }
     if (hipStreamSynchronize(s) != hipSuccess && rc == SLONN_OK) {
       set_error("build: stream synchronisation failed at layer %d", l);
@@ -503,7 +612,46 @@ extern "C" int slonn_build_tables(const slonn_model* m, const slonn_input* X_bui
     cur = act;
   }
   if (prev) (void)hipFree(prev);
-  if (rc != SLONN_OK) return fail(rc);
+  return rc;
+}
+
+}  // namespace
+}  // namespace slonn
+
+extern "C" int slonn_build_tables(const slonn_model* m, const slonn_input* X_build, int64_t N, void* stream,
+                                  slonn_tables** out) {
+  if (!out) SLONN_FAIL(SLONN_EINVAL, "out is null");
+  *out = nullptr;
+  int rc = check_training_input(m, X_build, N);
+  if (rc) return rc;
+  slonn_tables* t = new (std::nothrow) slonn_tables;
+  if (!t) SLONN_FAIL(SLONN_ENOMEM, "out of host memory");
+  t->model = m;
+  rc = train_tables(m, t, X_build, N, false, static_cast<hipStream_t>(stream));
+  if (rc != SLONN_OK) {
+    slonn_tables_destroy(t);
+    return rc;
+  }
   *out = t;
   return SLONN_OK;
+}
+
+extern "C" int slonn_tables_refresh(const slonn_model* m, slonn_tables* t, const slonn_input* X_new, int64_t N,
+                                    void* stream) {
+  if (!t) SLONN_FAIL(SLONN_EINVAL, "tables are null");
+  int rc = check_training_input(m, X_new, N);
+  if (rc) return rc;
+  if (t->model != m) SLONN_FAIL(SLONN_EINVAL, "tables belong to another model");
+  for (size_t l = 0; l < m->layers.size(); ++l)
+    if (m->layers[l].activated()) {
+      const TableSet* ts = t->for_layer((int)l);
+      if (!ts || !ts->d_score || !ts->d_npos || !ts->d_global_score)
+        SLONN_FAIL(SLONN_EUNSUPPORTED, "refresh: the tables of layer %zu hold no NodeScore sums (train them after "
+                   "slonn_model_set_tables_refreshable; imported tables carry none)", l);
+      if (ts->n_trained + N > SLONN_MAX_BATCH * 64ll)
+        SLONN_FAIL(SLONN_EUNSUPPORTED, "refresh: more than %lld training inputs in all", SLONN_MAX_BATCH * 64ll);
+    }
+  // A failure part-way leaves the earlier layers refreshed and the later ones not: the caller
+  // should then discard the tables.
+  return train_tables(m, t, X_new, N, true, static_cast<hipStream_t>(stream));
 }

@@ -282,16 +282,19 @@ size_t dense_split_workspace_bytes(int B, int n, int d) {
 }
 
 int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
-                       float* Y, int ldy, int B, int d, int n, int act, void* split_scratch, hipStream_t s) {
+                       float* Y, int ldy, int B, int d, int n, int act, void* split_scratch, hipStream_t s,
+                       bool batch_invariant) {
   ProfScope prof_(SLONN_PROF_DENSE, s);
   if (B <= 0) return SLONN_OK;
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
   const int vecx = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);
   const int vecw = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(W) % 16 == 0);
   const long big_tiles = (long)((B + 127) / 128) * ((n + 127) / 128);
-  const bool big = big_tiles >= 512;
+  // batch_invariant: one kernel shape whatever the batch, so that a query's outputs do not depend on
+  // how many queries travel with it (every shape sums a row's products in its own order)
+  const bool big = big_tiles >= 512 && !batch_invariant;
   const long tiles64 = (long)((B + 63) / 64) * ((n + 63) / 64);
-  if (tiles64 < 256 && dense_small_supported(W, w_dtype, X, ldx, d)) {
+  if (!batch_invariant && tiles64 < 256 && dense_small_supported(W, w_dtype, X, ldx, d)) {
     const bool few = (long)((n + 31) / 32) * ((B + 31) / 32) < 512 && d >= 1024;
     // a handful of tiles (a skinny output layer): the reduction is split over workgroups as well,
     // a second kernel adds the slices in order

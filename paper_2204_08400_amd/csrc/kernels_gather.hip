@@ -448,7 +448,13 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
   const bool vec = (d % chunk == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(W) % 16 == 0) &&
                    (reinterpret_cast<uintptr_t>(X) % 16 == 0);
   const size_t lds = ((size_t)d + 8) * sizeof(float);
-  if (lds > 65536) SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
+  if (lds > ((size_t)160 << 10))
+    SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
+  // beyond 64 KB a kernel has to be granted its dynamic LDS explicitly
+  auto grant = [&](const void* fn) -> int {
+    if (lds > 65536) SLONN_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    return SLONN_OK;
+  };
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
   // few queries, or few rows each (a skinny layer computed in full): the 64-row chunks of the
   // general kernel would leave most of the chip idle; long rows: one wavefront per row
@@ -469,6 +475,9 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
     int chunks = (max_rows + ROWS_PER_WAVE_BLOCK - 1) / ROWS_PER_WAVE_BLOCK;
     chunks = std::min(chunks, std::max(4, 4096 / B));
     dim3 grid(B, chunks);
+    if (int g = grant(w_dtype == SLONN_F32 ? reinterpret_cast<const void*>(gather_wave_kernel<SLONN_F32>)
+                                           : reinterpret_cast<const void*>(gather_wave_kernel<SLONN_BF16>)))
+      return g;
     if (w_dtype == SLONN_F32)
       hipLaunchKernelGGL((gather_wave_kernel<SLONN_F32>), grid, dim3(256), lds, s, W, bias, X, ldx, active,
                          cnt, idx_stride, Y, ldy, yc, ldc, d, n, a, (int)grid.y);
@@ -484,12 +493,13 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
   if (chunks > want) chunks = want;
   dim3 grid(B, chunks);
 #define SLONN_LAUNCH_GATHER(WDT, VEC)                                                              \
+  if (int g = grant(reinterpret_cast<const void*>(gather_forward_kernel<WDT, VEC>))) return g;     \
   hipLaunchKernelGGL((gather_forward_kernel<WDT, VEC>), grid, dim3(256), lds, s, W, bias, X, ldx,  \
                      active, cnt, idx_stride, Y, ldy, yc, ldc, d, n, a, (int)grid.y)
   if (w_dtype == SLONN_F32) {
-    if (vec) SLONN_LAUNCH_GATHER(SLONN_F32, true); else SLONN_LAUNCH_GATHER(SLONN_F32, false);
+    if (vec) { SLONN_LAUNCH_GATHER(SLONN_F32, true); } else { SLONN_LAUNCH_GATHER(SLONN_F32, false); }
   } else {
-    if (vec) SLONN_LAUNCH_GATHER(SLONN_BF16, true); else SLONN_LAUNCH_GATHER(SLONN_BF16, false);
+    if (vec) { SLONN_LAUNCH_GATHER(SLONN_BF16, true); } else { SLONN_LAUNCH_GATHER(SLONN_BF16, false); }
   }
 #undef SLONN_LAUNCH_GATHER
   SLONN_HIP(hipGetLastError());
@@ -502,7 +512,12 @@ int launch_gather_blocked(const void* W, int w_dtype, const float* bias, const f
   ProfScope prof_(SLONN_PROF_GATHER, s);
   if (B <= 0) return SLONN_OK;
   const size_t lds = ((size_t)d + 8) * sizeof(float);
-  if (lds > 65536) SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
+  if (lds > ((size_t)160 << 10))
+    SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
+  if (lds > 65536)
+    SLONN_HIP(hipFuncSetAttribute(w_dtype == SLONN_F32 ? reinterpret_cast<const void*>(gather_blocked_kernel<SLONN_F32>)
+                                                       : reinterpret_cast<const void*>(gather_blocked_kernel<SLONN_BF16>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const int by_xcd = B <= 128;
   dim3 grid((unsigned)(by_xcd ? 8 * ((rb.nblk + 7) / 8) : rb.nblk) * B);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;

@@ -448,6 +448,12 @@ int slonn_model_set_hash_margin(slonn_model* m, double margin) {
   return SLONN_OK;
 }
 
+int slonn_model_set_tables_refreshable(slonn_model* m, int on) {
+  if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
+  m->tables_refreshable = on != 0;
+  return SLONN_OK;
+}
+
 int slonn_model_set_dense_arithmetic(slonn_model* m, int mode) {
   if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
   if (mode != SLONN_DENSE_FP32_MFMA && mode != SLONN_DENSE_BF16_PARTS)

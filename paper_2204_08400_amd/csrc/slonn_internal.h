@@ -57,6 +57,12 @@ struct TableSet {                 // Node Importance tables of one layer
   uint32_t* d_dir = nullptr;      // device copies
   int32_t* d_ids = nullptr;
   int32_t* d_global_rank = nullptr;
+  // NodeScore state kept for online refresh (tables trained with slonn_model_set_tables_refreshable)
+  double* d_score = nullptr;         // [L][2^K][n] NodeScore sums
+  double* d_global_score = nullptr;  // [n] sums over all training inputs
+  uint32_t* d_npos = nullptr;        // [L][2^K] nodes with a positive sum per bucket
+  unsigned long long nonempty = 0;   // buckets that hold a list
+  long long n_trained = 0;           // training inputs seen so far
 };
 
 }  // namespace slonn
@@ -67,6 +73,7 @@ struct slonn_model {
   bool path_grouped = true;       // allow the grouped (cross-query) evaluation on the per-layer path
   bool hash_first = false;        // hash nodes always computed, never selected (Section 3.4 variant)
   double hash_margin = 2.0;       // integer hash projections: |z| must exceed this many error bounds
+  bool tables_refreshable = false; // slonn_build_tables keeps the NodeScore sums for slonn_tables_refresh
   int dense_arith = 0;            // slonn_dense_forward: 0 fp32 matrix cores, 1 bf16 parts on the bf16 matrix cores
   int max_lds_bytes = 65536;      // per-workgroup LDS the device grants on request
   int n_cu = 256;
@@ -322,7 +329,8 @@ int launch_finalize(float* Y, int ldy, int n, const int32_t* active, const int32
 // dense_split_workspace_bytes(B, n, d) bytes; with it a problem of only a few tiles (a skinny
 // output layer) splits its reduction over more workgroups.
 int launch_dense_layer(const void* W, int w_dtype, const float* bias, const float* X, int ldx,
-                       float* Y, int ldy, int B, int d, int n, int act, void* split_scratch, hipStream_t s);
+                       float* Y, int ldy, int B, int d, int n, int act, void* split_scratch, hipStream_t s,
+                       bool batch_invariant = false);
 size_t dense_split_workspace_bytes(int B, int n, int d);
 
 // true when a problem of fewer than 256 tiles of 64x64 can take the small-shape MFMA kernel
@@ -345,7 +353,13 @@ int launch_fill_iota(int32_t* idx, int stride, int32_t* cnt, int n, int B, hipSt
 
 // Alg. 1 on the device for one layer; fills ts (host + device copies).
 int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_t N, const float* act,
-                       TableSet* ts, hipStream_t s);
+                       TableSet* ts, bool refresh, hipStream_t s);
+// Ranking by a full sort, for what the LDS sorts of the table build do not cover: for every
+// segment seg < segs (score + seg * n, n sums each) with len[seg] > 0 (and, when only is given,
+// only[seg] != only[seg + 1]) the len[seg] best node ids by (sum descending, id ascending) go to
+// out + off[seg].  Allocates temporary device memory.
+int rank_by_sort(const double* score, int n, int segs, const uint32_t* off, const uint32_t* len,
+                 const uint32_t* only, int32_t* out, hipStream_t s);
 // device copies from the host vectors; the lists come from d_ids_src (device, ts->n_ids
 // entries) when given, else from ts->ids
 int upload_table_set(TableSet* ts, const int32_t* d_ids_src = nullptr);

@@ -24,7 +24,10 @@ def hash_nodes_by_variance(acts: torch.Tensor, K: int, L: int, u: np.ndarray) ->
     (device tensor): variance on the device, the draws u consumed by the library's sampler."""
     var = torch.empty(acts.shape[1], dtype=torch.float64, device=acts.device)
     slonn.slonn_activation_variance(acts, var)
-    return slonn.slonn_sample_hash_nodes(var.cpu().numpy(), K, L, u)
+    ud = torch.from_numpy(np.ascontiguousarray(u, np.float64)).to(acts.device)
+    out = torch.empty(K * L, dtype=torch.int32, device=acts.device)
+    slonn.slonn_sample_hash_nodes_device(var, K, L, ud, out)
+    return out.cpu().numpy()          # model creation takes the ids from the host
 
 
 class Network:
@@ -85,6 +88,15 @@ class Network:
     def build_tables(self, X_build):
         inp = self.to_input(X_build)
         self.tables = slonn.slonn_build_tables(self.model, inp, self.batch_of(inp))
+        return self.tables
+
+    def set_tables_refreshable(self, on: bool):
+        """Before build_tables: keep the NodeScore sums so that refresh_tables can continue Alg. 1."""
+        slonn.slonn_model_set_tables_refreshable(self.model, on)
+
+    def refresh_tables(self, X_new):
+        inp = self.to_input(X_new)
+        slonn.slonn_tables_refresh(self.model, self.tables, inp, self.batch_of(inp))
         return self.tables
 
     def import_tables(self, blob: bytes):

@@ -35,6 +35,7 @@ EXPORTS = [
     "slonn_forward_graph_create", "slonn_forward_graph_launch", "slonn_forward_graph_destroy",
     "slonn_activation_variance", "slonn_sample_hash_nodes", "slonn_model_set_hash_margin",
     "slonn_sparse_forward_static", "slonn_model_set_dense_arithmetic",
+    "slonn_sample_hash_nodes_device", "slonn_model_set_tables_refreshable", "slonn_tables_refresh",
 ]
 STATIC_SCRATCH_BYTES = 64 << 20
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused", "tiles")
@@ -201,6 +202,16 @@ def slonn_build_tables(model: Model, X_build: Input, N: int, stream=None) -> Tab
     return Tables(model, h)
 
 
+def slonn_model_set_tables_refreshable(model: Model, on: bool):
+    _check(load().slonn_model_set_tables_refreshable(model.h, int(bool(on))))
+
+
+def slonn_tables_refresh(model: Model, tables: Tables, X_new: Input, N: int, stream=None):
+    """Alg. 1 continued on N more training inputs (tables trained as refreshable)."""
+    _check(load().slonn_tables_refresh(model.h, tables.h, C.byref(X_new), C.c_int64(N),
+                                       C.c_void_p(_stream_ptr(stream))))
+
+
 def slonn_tables_export_bytes(tables: Tables) -> int:
     """size of the blob slonn_tables_export would write"""
     n = C.c_size_t(0)
@@ -360,6 +371,13 @@ def slonn_activation_variance(A, var_out, stream=None):
     _check(load().slonn_activation_variance(C.c_void_p(A.data_ptr()), C.c_int64(A.shape[0]), int(A.shape[1]),
                                             C.c_int64(A.stride(0)), C.c_void_p(_ptr(var_out)),
                                             C.c_void_p(_stream_ptr(stream))))
+
+
+def slonn_sample_hash_nodes_device(variance, K: int, L: int, u, out, stream=None):
+    """variance: device float64 [n]; u: device float64 [K*L]; out: device int32 [K*L]."""
+    _check(load().slonn_sample_hash_nodes_device(C.c_void_p(_ptr(variance)), int(variance.numel()), int(K), int(L),
+                                                 C.c_void_p(_ptr(u)), C.c_void_p(_ptr(out)),
+                                                 C.c_void_p(_stream_ptr(stream))))
 
 
 def slonn_sample_hash_nodes(variance: np.ndarray, K: int, L: int, u: np.ndarray) -> np.ndarray:

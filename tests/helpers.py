@@ -10,9 +10,17 @@ REL_TOL = 1e-4          # fp32 outputs, relative to the largest output of the qu
 
 
 def make_case(oracle, dims, K, L, seed, hashed=None, cap=None, N_build=256, w_dtype=wl.W_F32,
-              last_act=wl.ACT_NONE, kind="u01", ell_nnz=0, threads=None):
-    """Layers with variance-sampled hash nodes, the oracle net with tables built."""
+              last_act=wl.ACT_NONE, kind="u01", ell_nnz=0, threads=None, repeat_rows=0, keep_scores=False):
+    """Layers with variance-sampled hash nodes, the oracle net with tables built.  repeat_rows = p > 0:
+    the rows (and biases) of every activated layer repeat with period p, so that masses of nodes have
+    exactly equal activations."""
     layers = wl.make_mlp(dims, seed=seed, w_dtype=w_dtype, last_act=last_act)
+    if repeat_rows:
+        for l in (range(len(layers) - 1) if hashed is None else hashed):
+            lay = layers[l]
+            src = np.arange(lay.d_out) % repeat_rows
+            lay.W = np.ascontiguousarray(lay.W[src])
+            lay.bias = np.ascontiguousarray(lay.bias[src])
     hashed = list(range(len(layers) - 1)) if hashed is None else list(hashed)
     if ell_nnz:
         Xb = wl.inputs_ell(N_build, dims[0], ell_nnz, seed + 1)
@@ -28,7 +36,7 @@ def make_case(oracle, dims, K, L, seed, hashed=None, cap=None, N_build=256, w_dt
         lay.list_cap = lay.d_out if cap is None else cap
         lay.hash_nodes = oracle.sample_hash_nodes(oracle.activation_variance(dense[l]), K, L,
                                                   wl.hash_node_draws(K, L, seed + 3 + l))
-    net.build_tables(Xb)
+    net.build_tables(Xb, keep_scores=keep_scores)
     return layers, net, Xb
 
 

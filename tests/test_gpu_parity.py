@@ -285,12 +285,51 @@ def test_hash_node_choice_matches_oracle(rt, oracle):
             assert rt.hash_nodes_by_variance(view, K, L, u).tolist() == oracle.sample_hash_nodes(want, K, L, u).tolist()
 
 
+def test_device_hash_node_draws_match_oracle(rt, oracle):
+    """The variance-proportional draws on the device (one wavefront, running sums in node order)
+    against the oracle's, id for id, on the same variances: ragged layer widths, more draws than
+    nodes with variance (the rest come lowest id first), negative / infinite / NaN entries (count
+    as zero), a draw target in the last chunk, and the library's host sampler beside both."""
+    import torch
+    from paper_2204_08400_amd import slonn
+    rng = np.random.default_rng(5)
+    cases = []
+    for n, K, L in [(70, 4, 8), (64, 2, 3), (1000, 6, 10), (129, 8, 16), (8192, 12, 64), (5, 1, 5), (100003, 4, 6)]:
+        v = rng.random(n) ** 3
+        v[::5] = 0.0
+        cases.append((v, K, L, f"n={n}"))
+    v = np.zeros(90); v[[3, 17, 80]] = [2.0, 1.0, 0.5]
+    cases.append((v, 3, 4, "three nodes with variance, twelve draws"))
+    v = rng.random(200); v[5] = np.nan; v[6] = np.inf; v[7] = -np.inf; v[8] = -3.0
+    cases.append((v, 5, 6, "non-finite and negative entries"))
+    v = np.zeros(300); v[299] = 1.0
+    cases.append((v, 2, 2, "all variance on the last node"))
+    cases.append((np.zeros(77), 3, 5, "no variance at all"))
+    for v, K, L, what in cases:
+        _say(f"device hash-node draws: {what} K={K} L={L}")
+        u = wl.hash_node_draws(K, L, seed=len(v))
+        want = oracle.sample_hash_nodes(v, K, L, u)
+        vd = torch.from_numpy(v).cuda()
+        ud = torch.from_numpy(u).cuda()
+        out = torch.full((K * L,), -1, dtype=torch.int32, device="cuda")
+        slonn.slonn_sample_hash_nodes_device(vd, K, L, ud, out)
+        got = out.cpu().numpy()
+        assert got.tolist() == want.tolist(), what
+        assert slonn.slonn_sample_hash_nodes(v, K, L, u).tolist() == want.tolist(), what
+        assert len(set(got.tolist())) == K * L
+
+
 BUILD_CASES = [
     dict(dims=(100, 300, 260, 37), K=4, L=6, cap=200, N=500, hashed=None, last_act=wl.ACT_NONE),
     dict(dims=(48, 10000, 16), K=5, L=4, cap=400, N=300, hashed=[0], last_act=wl.ACT_NONE),       # wide ReLU layer
     dict(dims=(48, 128, 12000), K=6, L=5, cap=300, N=300, hashed=[1], last_act=wl.ACT_SOFTMAX),   # wide softmax layer
     # the width of the extreme-classification output layers (Table 1): 100 000 softmax nodes, few inputs
     dict(dims=(64, 128, 100000), K=5, L=3, cap=600, N=96, hashed=[1], last_act=wl.ACT_SOFTMAX),
+    # lists longer than the LDS sort holds on a layer wider than it: whole buckets are radix-sorted
+    dict(dims=(48, 128, 12000), K=4, L=3, cap=10000, N=200, hashed=[1], last_act=wl.ACT_SOFTMAX),
+    # masses of exactly equal sums (the layer's rows repeat with period 2): no threshold isolates the
+    # head of a list, every bucket falls back to the full sort; equal sums rank by ascending id
+    dict(dims=(32, 20000, 8), K=3, L=2, cap=500, N=120, hashed=[0], last_act=wl.ACT_NONE, repeat_rows=2),
 ]
 
 
@@ -301,7 +340,7 @@ def test_build_tables_matches_oracle(rt, oracle, case):
     built on either side give the same selection when both sides load the same blob."""
     dims = case["dims"]
     layers, net, Xb = make_case(oracle, dims, case["K"], case["L"], seed=17, cap=case["cap"], N_build=case["N"],
-                                hashed=case["hashed"], last_act=case["last_act"])
+                                hashed=case["hashed"], last_act=case["last_act"], repeat_rows=case.get("repeat_rows", 0))
     hashed = [l for l, lay in enumerate(layers) if lay.K > 0]
     g = rt.Network(layers)
     _say(f"device build {dims}")
@@ -343,6 +382,75 @@ def test_build_tables_matches_oracle(rt, oracle, case):
     g2 = rt.Network(layers)
     g2.build_tables(Xb)
     assert g2.export_tables() == blob
+
+
+@pytest.mark.parametrize("case", [
+    dict(dims=(60, 200, 150, 9), K=4, L=5, cap=None, hashed=None, last_act=wl.ACT_NONE),
+    dict(dims=(40, 96, 9000), K=3, L=3, cap=300, hashed=[1], last_act=wl.ACT_SOFTMAX),       # wide layer
+], ids=["two-hidden", "wide-softmax"])
+def test_tables_refresh_matches_oracle_and_full_build(rt, oracle, case):
+    """Online refresh (Alg. 1 continued): tables trained on A on the device and refreshed with B,
+    then C, must be bit for bit the tables the device trains on A + B + C at once, and match the
+    oracle's refreshed tables under the same rules as a build (swaps only among sums equal to 1e-5);
+    the forward pass on the refreshed tables agrees with the oracle on the same blob."""
+    from paper_2204_08400_amd import slonn
+    dims = case["dims"]
+    layers, net, Xa = make_case(oracle, dims, case["K"], case["L"], seed=29, cap=case["cap"], N_build=150,
+                                hashed=case["hashed"], last_act=case["last_act"], keep_scores=True)
+    hashed = [l for l, lay in enumerate(layers) if lay.K > 0]
+    Xb = make_queries(dims, 90, seed=301)
+    Xc = make_queries(dims, 7, seed=302)
+    g = rt.Network(layers)
+    g.set_tables_refreshable(True)
+    _say(f"refresh {dims}: device build on A, refresh with B and C")
+    g.build_tables(Xa)
+    only_a = g.export_tables()
+    g.refresh_tables(Xb)
+    g.refresh_tables(Xc)
+    blob = g.export_tables()
+    assert blob != only_a
+    g_full = rt.Network(layers)
+    g_full.set_tables_refreshable(True)
+    g_full.build_tables(np.concatenate([Xa, Xb, Xc]))
+    assert g_full.export_tables() == blob, "refreshed tables differ from a build on all inputs"
+    # the oracle's refresh
+    net.refresh_tables(Xb)
+    net.refresh_tables(Xc)
+    net_g = oracle.OracleNet(layers)
+    net_g.import_tables(blob)
+    for l in hashed:
+        tg, ts = net_g.tables[l], net.tables[l]
+        swaps = mism = 0
+        for b in range(layers[l].L):
+            for key in range(1 << layers[l].K):
+                lg, ls = tg.bucket(b, key), ts.bucket(b, key)
+                if ls.size == 0 and lg.size == 0:
+                    continue
+                sc = ts.bucket_scores(b, key)
+                if sc is None or lg.size != ls.size:
+                    mism += 1
+                    continue
+                for a, c in zip(lg, ls):
+                    if a != c:
+                        swaps += 1
+                        assert abs(sc[a] - sc[c]) <= 1e-5 * max(abs(sc[a]), abs(sc[c])), (l, b, key, a, c)
+        _say(f"layer {l}: {swaps} rank swaps among near-equal sums, {mism} buckets with different membership")
+        assert mism <= (2 if l > hashed[0] else 0)
+        gg, _ = tg.global_rank()
+        gs, ss = ts.global_rank()
+        for a, c in zip(gg, gs):
+            if a != c:
+                assert abs(ss[a] - ss[c]) <= 1e-5 * max(abs(ss[a]), abs(ss[c]), 1e-30)
+    X = make_queries(dims, 48, seed=9)
+    ref = net_g.sparse_forward(X, 0.05)
+    got = to_numpy_result(g.sparse_forward(X, 0.05, taps=True))
+    compare_sparse(got, ref, layers, "refreshed tables")
+    # tables that kept no sums refuse
+    g2 = rt.Network(layers)
+    g2.build_tables(Xa)
+    with pytest.raises(slonn.SlonnError) as e:
+        g2.refresh_tables(Xb)
+    assert e.value.code == -4
 
 
 # --------------------------------------------------------------------------- #
