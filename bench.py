@@ -87,19 +87,28 @@ class Workload:
             else:
                 self.batches.append(slonn.make_input(x=xq[s:s + nb]))
         n_last = cfg.dims[-1]
-        self.out_arg = torch.empty(B, dtype=torch.int32, device=dev)
-        if layers[-1].K > 0:      # activated output layer: compact (id, value) output, no dense row
-            self._o = (torch.empty((B, n_last), dtype=torch.int32, device=dev),
-                       torch.empty((B, n_last), dtype=torch.float32, device=dev),
-                       torch.empty(B, dtype=torch.int32, device=dev))
-            self.out = slonn.make_output(idx=self._o[0], val=self._o[1], cnt=self._o[2], stride=n_last,
-                                         argmax=self.out_arg)
-        else:
-            self._o = torch.empty((B, n_last), dtype=torch.float32, device=dev)
-            self.out = slonn.make_output(dense=self._o, argmax=self.out_arg)
-        self.yd = torch.empty((B, n_last), dtype=torch.float32, device=dev)
-        self.ws = self.net.workspace(B)
+        # Lanes: consecutive batches of a step go to HIP streams in turn (default priority), each with
+        # its own workspace and output buffers, so that the launch- and latency-bound kernels of one
+        # batch (hash, select) run beside the matrix-core kernels of another.  Lane 0 is the current stream.
         self.stream = torch.cuda.current_stream()
+        self.lanes = []
+        ws_bytes = slonn.slonn_workspace_bytes(self.net.model, B)
+        for i in range(max(1, args.streams)):
+            lane = {"stream": self.stream if i == 0 else torch.cuda.Stream(device=dev),
+                    "ws": torch.empty(ws_bytes, dtype=torch.uint8, device=dev),
+                    "arg": torch.empty(B, dtype=torch.int32, device=dev),
+                    "yd": torch.empty((B, n_last), dtype=torch.float32, device=dev)}
+            if layers[-1].K > 0:      # activated output layer: compact (id, value) output, no dense row
+                lane["o"] = (torch.empty((B, n_last), dtype=torch.int32, device=dev),
+                             torch.empty((B, n_last), dtype=torch.float32, device=dev),
+                             torch.empty(B, dtype=torch.int32, device=dev))
+                lane["out"] = slonn.make_output(idx=lane["o"][0], val=lane["o"][1], cnt=lane["o"][2], stride=n_last,
+                                                argmax=lane["arg"])
+            else:
+                lane["o"] = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+                lane["out"] = slonn.make_output(dense=lane["o"], argmax=lane["arg"])
+            self.lanes.append(lane)
+        self.out, self.ws, self.out_arg = self.lanes[0]["out"], self.lanes[0]["ws"], self.lanes[0]["arg"]
         self.mixed = None
         if cfg.keep_range:        # one keep fraction per query (mixed SLOs in one batch)
             self.mixed_host = wl.keep_uniform(self.nq, cfg.keep_range[0], cfg.keep_range[1], seed=6)
@@ -112,20 +121,35 @@ class Workload:
         return torch.from_numpy(X).to(self.dev)
 
     # ---- one step = the whole query set ----
-    def step(self, keep_t):
+    def _fork(self, lanes):
+        for ln in lanes[1:]:
+            ln["stream"].wait_stream(self.stream)
+
+    def _join(self, lanes):
+        for ln in lanes[1:]:
+            self.stream.wait_stream(ln["stream"])
+
+    def step(self, keep_t, one_lane=False):
         s, B = self.slonn, self.B
+        lanes = self.lanes[:1] if one_lane else self.lanes
+        self._fork(lanes)
         for i, nb in enumerate(self.sizes):
+            ln = lanes[i % len(lanes)]
             if self.mixed is not None:
                 s.slonn_sparse_forward(self.net.model, self.net.tables, self.batches[i], nb,
-                                       self.mixed[i * B:i * B + nb], 1, 0, self.out, None, self.ws, self.stream)
+                                       self.mixed[i * B:i * B + nb], 1, 0, ln["out"], None, ln["ws"], ln["stream"])
             else:
                 s.slonn_sparse_forward(self.net.model, self.net.tables, self.batches[i], nb, keep_t, 0, 0,
-                                       self.out, None, self.ws, self.stream)
+                                       ln["out"], None, ln["ws"], ln["stream"])
+        self._join(lanes)
 
     def dense_step(self):
+        self._fork(self.lanes)
         for i, nb in enumerate(self.sizes):
-            self.slonn.slonn_dense_forward(self.net.model, self.batches[i], nb, self.yd, self.out_arg, None,
-                                           self.ws, self.stream)
+            ln = self.lanes[i % len(self.lanes)]
+            self.slonn.slonn_dense_forward(self.net.model, self.batches[i], nb, ln["yd"], ln["arg"], None,
+                                           ln["ws"], ln["stream"])
+        self._join(self.lanes)
 
     def marker(self):
         """a kernel nothing else here launches, so that a profiler's dispatch list shows where the
@@ -170,7 +194,7 @@ class Workload:
         per_step = len(self.sizes) * (12 * len(self.layers) + 8)
         self.slonn.slonn_profile_begin(steps * per_step)
         for _ in range(steps):
-            self.step(kt)
+            self.step(kt, one_lane=True)       # one stream: a kernel's duration without a neighbour on the chip
         return self.slonn.slonn_profile_end()
 
     # ---- the method's own work ----
@@ -287,6 +311,8 @@ def main():
                     help="Section 3.4 variant: hash nodes always computed, never selected (default off)")
     ap.add_argument("--aclo", action="store_true",
                     help="also time the pass with k chosen per query inside it (ACLO, Confidence LSH tables)")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="HIP streams the batches of a step are dealt to in turn (each with its own workspace)")
     ap.add_argument("--markers", action="store_true",
                     help="launch a marker kernel (nextafter) right before and after the timed steps, for profilers")
     ap.add_argument("--no-profile", action="store_true", help="skip the event-instrumented pass (profiler runs)")
@@ -344,6 +370,7 @@ def main():
     head_config = {"workload": f"{args.config}: MLP {'-'.join(map(str, cfg.dims))}, K={cfg.K} L={cfg.L} on "
                                f"{len(cfg.hashed_layers)} layers", "batch": B, "keep": keep_label,
                    "queries_per_step": w.nq, "batches_per_step": len(w.sizes), "table_training_inputs": w.n_build,
+                   "streams": max(1, args.streams),
                    "path": args.path, "hash_nodes_always_active": bool(args.hash_nodes_always_active)}
     traffic_key = f"{args.config}_B{B}_keep{head_keep if head_keep is not None else 'mixed'}"
     extra = {"ms_per_step_median": round(float(np.median(per)), 4),
