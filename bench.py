@@ -49,8 +49,13 @@ class Workload:
         layers = self.layers = wl.make_mlp(cfg.dims, seed=0, w_dtype=cfg.w_dtype, last_act=cfg.last_act)
         self.n_build = n_build or cfg.n_inputs
         self.nq = n_queries or cfg.n_inputs
-        X_build = wl.make_inputs(cfg, self.n_build, seed=1)
-        self.X_query = wl.make_inputs(cfg, self.nq, seed=2)
+        if args.input_clusters > 0 and cfg.input_kind != "ell":
+            # not a benchmark configuration: inputs with class structure, for --cluster-by-key
+            X_build = wl.inputs_clustered(self.n_build, cfg.dims[0], 1, args.input_clusters)
+            self.X_query = wl.inputs_clustered(self.nq, cfg.dims[0], 2, args.input_clusters)
+        else:
+            X_build = wl.make_inputs(cfg, self.n_build, seed=1)
+            self.X_query = wl.make_inputs(cfg, self.nq, seed=2)
         log(f"{name}: generated weights, {self.n_build} table-training inputs and {self.nq} queries in {time.time() - t0:.1f}s")
         ell = self.ell = cfg.input_kind == "ell"
         if ell:     # wide sparse-input model: first layer stored input-major on the device
@@ -311,6 +316,11 @@ def main():
                     help="Section 3.4 variant: hash nodes always computed, never selected (default off)")
     ap.add_argument("--aclo", action="store_true",
                     help="also time the pass with k chosen per query inside it (ACLO, Confidence LSH tables)")
+    ap.add_argument("--cluster-by-key", action="store_true",
+                    help="Section 6 (future work): also order each batch by its first-layer LSH keys before the pass; "
+                         "reports the union of 16 / 128 queries' active rows over one list, and the rate, both ways")
+    ap.add_argument("--input-clusters", type=int, default=0,
+                    help="inputs with class structure instead of the configuration's (study of --cluster-by-key only)")
     ap.add_argument("--streams", type=int, default=2,
                     help="HIP streams the batches of a step are dealt to in turn (each with its own workspace)")
     ap.add_argument("--markers", action="store_true",
@@ -454,6 +464,44 @@ def main():
                          "confidence": "-cross-entropy(softmax(full), softmax(at k)) on the first "
                                        f"{nb_} build inputs; per-query thresholds drawn from those at k = {grid[len(grid) // 2]}"}
         log(f"ACLO: {extra['aclo']}")
+
+    # ---- batches ordered by LSH key (Section 6 names clustering a batch into micro-batches as future
+    #      work): queries whose first-layer keys agree share the heads of their ranked lists, so groups
+    #      of neighbours in that order select overlapping rows.  The keys come from slonn_select; the
+    #      reordering of the query rows is a device gather outside the library. ----
+    if args.cluster_by_key and w.mixed is None and not w.ell:
+        net = w.net
+        l0 = cfg.hashed_layers[0]
+        nb0 = w.sizes[0]
+        xb0 = w.xq[:nb0]
+        if l0 > 0:
+            xb0 = net.dense_forward(xb0, layer_outs=True)["layers"][l0 - 1]
+        codes = net.select(l0, xb0, head_keep)["codes"].cpu().numpy().view(np.uint32)
+        order = np.lexsort(codes.T[::-1])             # by table 0's key, then table 1's, ...
+        res = {}
+        for label, perm in (("arrival_order", np.arange(nb0)), ("ordered_by_first_layer_keys", order)):
+            xq_p = w.xq[:nb0][torch.from_numpy(perm).to(dev)].contiguous()
+            r = net.sparse_forward(xq_p, head_keep, taps=True)
+            stats = {}
+            for l in cfg.hashed_layers:
+                act = r["taps"]["active"][l].cpu().numpy()
+                cnt = r["taps"]["cnt"][l].cpu().numpy()
+                for gsz in (16, 128):
+                    ratios = []
+                    for g0 in range(0, nb0 - gsz + 1, gsz):
+                        u = np.unique(np.concatenate([act[q, :cnt[q]] for q in range(g0, g0 + gsz)])).size
+                        ratios.append(u / cnt[g0:g0 + gsz].mean())
+                    stats[f"layer{l}_union_of_{gsz}_over_one_list"] = round(float(np.mean(ratios)), 3)
+            inp = slonn.make_input(x=xq_p)
+            kt = w.keep_tensor(head_keep)
+
+            def one():
+                slonn.slonn_sparse_forward(net.model, net.tables, inp, nb0, kt, 0, 0, w.out, None, w.ws, w.stream)
+            s_, _ = w.timed(one, 30, 5)
+            stats["us_per_batch"] = round(s_ / 30 * 1e6, 1)
+            res[label] = stats
+        extra["cluster_by_key"] = res
+        log(f"cluster by key: {res}")
 
     # ---- CPU baseline: the oracle as it stands, on the host cores, bounded sample ----
     cpu = None

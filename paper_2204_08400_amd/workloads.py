@@ -209,6 +209,20 @@ CONFIGS = {
 }
 
 
+def inputs_clustered(N: int, d: int, seed: int, n_clusters: int, spread: float = 0.3,
+                     clip: Optional[float] = 3.0) -> np.ndarray:
+    """Inputs with class structure (not one of the benchmark configurations; for the study of
+    batches ordered by LSH key): ``n_clusters`` centres drawn N(0,1) once (seed-independent
+    stream), each input = its centre + ``spread`` * N(0,1), the centre picked uniformly at random
+    per input, arrival order random."""
+    centres = _fill(normal01, 12345, 8, n_clusters * d, np.float64).reshape(n_clusters, d)
+    which = (random_u64(seed, 9, 0, N) % _U64(n_clusters)).astype(np.int64)
+    x = centres[which] + spread * _fill(normal01, seed, 3, N * d, np.float64).reshape(N, d)
+    if clip is not None:
+        x = np.clip(x, -clip, clip)
+    return x.astype(np.float32)
+
+
 def make_inputs(cfg: Config, N: int, seed: int):
     d = cfg.dims[0]
     if cfg.input_kind == "u01_half_zero":
