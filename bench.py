@@ -81,16 +81,10 @@ class Workload:
         torch.cuda.synchronize()
         log(f"{name}: tables built on the device in {time.time() - t0:.2f}s")
 
-        xq = self.xq = self.to_dev(self.X_query)
+        self.xq = self.to_dev(self.X_query)
+        self.nq_all = self.nq
+        self.set_batch(self.B, self.nq)
         B = self.B
-        self.sizes = [min(B, self.nq - s) for s in range(0, self.nq, B)]      # whole query set, ragged tail included
-        self.batches = []
-        for i, nb in enumerate(self.sizes):
-            s = i * B
-            if ell:
-                self.batches.append(slonn.make_input(idx=xq[0][s:s + nb], val=xq[1][s:s + nb], nnz=xq[2][s:s + nb]))
-            else:
-                self.batches.append(slonn.make_input(x=xq[s:s + nb]))
         n_last = cfg.dims[-1]
         # Lanes: consecutive batches of a step go to HIP streams in turn (default priority), each with
         # its own workspace and output buffers, so that the launch- and latency-bound kernels of one
@@ -119,6 +113,22 @@ class Workload:
             self.mixed_host = wl.keep_uniform(self.nq, cfg.keep_range[0], cfg.keep_range[1], seed=6)
             self.mixed = torch.from_numpy(self.mixed_host).to(dev)
 
+    def set_batch(self, B, nq=0):
+        """the query set (its first nq queries) cut into batches of B, ragged tail included; buffers and
+        workspace are sized for the batch the workload was created with, so B may only shrink"""
+        slonn, xq = self.slonn, self.xq
+        assert B <= self.B
+        self.batch = B
+        self.nq = min(nq or self.nq_all, self.nq_all)
+        self.sizes = [min(B, self.nq - s) for s in range(0, self.nq, B)]
+        self.batches = []
+        for i, nb in enumerate(self.sizes):
+            s = i * B
+            if self.ell:
+                self.batches.append(slonn.make_input(idx=xq[0][s:s + nb], val=xq[1][s:s + nb], nnz=xq[2][s:s + nb]))
+            else:
+                self.batches.append(slonn.make_input(x=xq[s:s + nb]))
+
     def to_dev(self, X):
         torch, np = self.torch, self.np
         if self.ell:
@@ -135,7 +145,7 @@ class Workload:
             self.stream.wait_stream(ln["stream"])
 
     def step(self, keep_t, one_lane=False):
-        s, B = self.slonn, self.B
+        s, B = self.slonn, self.batch
         lanes = self.lanes[:1] if one_lane else self.lanes
         self._fork(lanes)
         for i, nb in enumerate(self.sizes):
@@ -206,7 +216,7 @@ class Workload:
     def budgets(self, keep, n):
         """node budgets of the queries in a layer of n nodes (nearest whole node, at least one)"""
         np = self.np
-        k = self.mixed_host.astype(np.float64) if keep is None else np.full(self.nq, np.float32(keep), np.float64)
+        k = self.mixed_host[:self.nq].astype(np.float64) if keep is None else np.full(self.nq, np.float32(keep), np.float64)
         return np.clip(np.floor(k * n + 0.5), 1, n)
 
     def gathered_bytes_per_step(self, keep, activated_only=True):
@@ -414,6 +424,14 @@ def main():
                                             "TFLOPs": round(dflops * steps * wk.nq / s / 1e12, 2)}
         if hasattr(slonn, "slonn_model_set_dense_arithmetic"):
             slonn.slonn_model_set_dense_arithmetic(wk.net.model, 0)
+        if wk.batch <= 64 and 1.0 not in keeps and wk.mixed is None:
+            # small batches: the full network is also run through the sparse path's own kernels with every
+            # node active (keep 1.0: no table access, rows spread over all compute units), the "all nodes
+            # computed" case of Section 3.4; a matrix-core GEMM has little to offer a handful of queries
+            s, _ = wk.time_sparse(1.0, steps, warm)
+            res["dense_baseline"]["all_nodes_through_the_gather_kernels"] = {
+                "qps": round(steps * wk.nq / s), "ms_per_step": round(s / steps * 1e3, 4),
+                "TFLOPs": round(dflops * steps * wk.nq / s / 1e12, 2)}
         best_dense = max(v["qps"] for v in res["dense_baseline"].values())
         for k, v in res["sweep"].items():
             v["sparse_over_best_dense"] = round(v["qps"] / best_dense, 3)
@@ -546,13 +564,18 @@ def main():
         others = {}
         del w
         torch.cuda.empty_cache()
-        for name, b_, nq_, nb_ in (("C3", 1024, 8192, 8192), ("C2", 256, 0, 0)):
-            wk = Workload(name, b_, args, n_queries=nq_, n_build=nb_)
-            r = sweep_and_dense(wk, 3, 1, wk.cfg.keeps)
-            r["config"] = {"workload": f"{name}: MLP {'-'.join(map(str, wk.cfg.dims))}, K={wk.cfg.K} L={wk.cfg.L}",
-                           "batch": wk.B, "queries_per_step": wk.nq, "table_training_inputs": wk.n_build}
-            others[f"{name}_B{wk.B}"] = r
-            log(f"{name}: {r}")
+        # (name, batch sizes with the queries per step at each, query set, table-training inputs)
+        for name, shapes, nq_, nb_ in (("C3", ((1024, 8192), (32, 2048), (1, 256)), 8192, 8192),
+                                       ("C2", ((256, 0),), 0, 0), ("C4", ((128, 0),), 0, 0), ("C1", ((64, 0), (1, 64)), 0, 0)):
+            wk = Workload(name, shapes[0][0], args, n_queries=nq_, n_build=nb_)
+            for b_, q_ in shapes:
+                wk.set_batch(b_, q_)
+                r = sweep_and_dense(wk, 3, 1, wk.cfg.keeps)
+                r["config"] = {"workload": f"{name}: MLP {'-'.join(map(str, wk.cfg.dims))}, K={wk.cfg.K} L={wk.cfg.L}",
+                               "batch": b_, "queries_per_step": wk.nq, "table_training_inputs": wk.n_build,
+                               "streams": max(1, args.streams)}
+                others[f"{name}_B{b_}"] = r
+                log(f"{name} batch {b_}: {r}")
             del wk
             torch.cuda.empty_cache()
         extra["other_workloads"] = others
