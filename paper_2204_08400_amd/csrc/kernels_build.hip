@@ -281,18 +281,29 @@ __global__ void clear_touched_npos_kernel(const uint32_t* __restrict__ start, in
   if (k < nb && start[k] != start[k + 1]) npos[k] = 0u;
 }
 
+// 4-byte ids <-> the 2-byte ids that layers of up to 65 536 nodes store
+__global__ void narrow_ids_kernel(const int32_t* __restrict__ src, uint16_t* __restrict__ dst, size_t count) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) dst[i] = (uint16_t)src[i];
+}
+__global__ void widen_ids_kernel(const uint16_t* __restrict__ src, int32_t* __restrict__ dst, size_t count) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) dst[i] = (int32_t)src[i];
+}
+
 // Online refresh: a bucket without new members keeps its list; it moves to its new place in the
 // id array (old_dir: the table's old directory row; its length has not changed).
+template <typename IdT>
 __global__ __launch_bounds__(256) void copy_untouched_lists_kernel(const uint32_t* __restrict__ start,
                                                                   const uint32_t* __restrict__ old_dir,
-                                                                  const int32_t* __restrict__ old_ids,
+                                                                  const IdT* __restrict__ old_ids,
                                                                   const uint32_t* __restrict__ off,
                                                                   const uint32_t* __restrict__ len,
                                                                   int32_t* __restrict__ out) {
   const int bucket = blockIdx.x;
   if (start[bucket] != start[bucket + 1]) return;
   const uint32_t l = len[bucket], from = old_dir[bucket], to = off[bucket];
-  for (uint32_t i = threadIdx.x; i < l; i += 256) out[to + i] = old_ids[from + i];
+  for (uint32_t i = threadIdx.x; i < l; i += 256) out[to + i] = (int32_t)old_ids[from + i];
 }
 
 template <class T>
@@ -318,16 +329,49 @@ void free_table_set(TableSet* ts) {
 
 int upload_table_set(TableSet* ts, const int32_t* d_ids_src) {
   if (!d_ids_src) ts->n_ids = ts->ids.size();
+  // layers of up to 65 536 nodes keep their lists as 2-byte ids: half the table memory and half
+  // the bytes a query's merge reads
+  ts->narrow = ts->n <= 65536;
   SLONN_HIP(hipMalloc(&ts->d_dir, std::max<size_t>(ts->dir.size(), 1) * 4));
-  SLONN_HIP(hipMalloc(&ts->d_ids, std::max<size_t>(ts->n_ids, 1) * 4));
+  SLONN_HIP(hipMalloc(&ts->d_ids, std::max<size_t>(ts->n_ids, 1) * (ts->narrow ? 2 : 4)));
   SLONN_HIP(hipMalloc(&ts->d_global_rank, std::max<size_t>(ts->global_rank.size(), 1) * 4));
   SLONN_HIP(hipMemcpy(ts->d_dir, ts->dir.data(), ts->dir.size() * 4, hipMemcpyHostToDevice));
-  if (ts->n_ids)
+  if (ts->n_ids && !ts->narrow) {
     SLONN_HIP(hipMemcpy(ts->d_ids, d_ids_src ? d_ids_src : ts->ids.data(), ts->n_ids * 4,
                         d_ids_src ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice));
+  } else if (ts->n_ids && d_ids_src) {
+    hipLaunchKernelGGL(narrow_ids_kernel, dim3((unsigned)((ts->n_ids + 255) / 256)), dim3(256), 0, nullptr, d_ids_src,
+                       static_cast<uint16_t*>(ts->d_ids), ts->n_ids);
+    SLONN_HIP(hipGetLastError());
+    SLONN_HIP(hipStreamSynchronize(nullptr));
+  } else if (ts->n_ids) {
+    std::vector<uint16_t> small(ts->n_ids);
+    for (size_t i = 0; i < ts->n_ids; ++i) small[i] = (uint16_t)ts->ids[i];
+    SLONN_HIP(hipMemcpy(ts->d_ids, small.data(), ts->n_ids * 2, hipMemcpyHostToDevice));
+  }
   std::vector<int32_t>().swap(ts->ids);        // the lists live on the device from here on
   SLONN_HIP(hipMemcpy(ts->d_global_rank, ts->global_rank.data(), ts->global_rank.size() * 4,
                       hipMemcpyHostToDevice));
+  return SLONN_OK;
+}
+
+int download_ids(const TableSet* ts, int32_t* host_out) {
+  if (!ts->n_ids) return SLONN_OK;
+  if (!ts->narrow) {
+    SLONN_HIP(hipMemcpy(host_out, ts->d_ids, ts->n_ids * 4, hipMemcpyDeviceToHost));
+    return SLONN_OK;
+  }
+  // widened on the device through a staging buffer, 64 Mi ids at a time
+  const size_t step = std::min<size_t>(ts->n_ids, (size_t)64 << 20);
+  DevBuf<int32_t> stage;
+  SLONN_HIP(stage.alloc(step));
+  const uint16_t* src = static_cast<const uint16_t*>(ts->d_ids);
+  for (size_t at = 0; at < ts->n_ids; at += step) {
+    const size_t c = std::min(step, ts->n_ids - at);
+    hipLaunchKernelGGL(widen_ids_kernel, dim3((unsigned)((c + 255) / 256)), dim3(256), 0, nullptr, src + at, stage.p, c);
+    SLONN_HIP(hipGetLastError());
+    SLONN_HIP(hipMemcpy(host_out + at, stage.p, c * 4, hipMemcpyDeviceToHost));
+  }
   return SLONN_OK;
 }
 
@@ -473,8 +517,14 @@ int build_layer_tables(const slonn_model* m, int layer, const float* X_l, int64_
       }
       SLONN_HIP(hipGetLastError());
       if (refresh) {
-        hipLaunchKernelGGL(copy_untouched_lists_kernel, dim3(nb), dim3(256), 0, s, st,
-                           ts->d_dir + (size_t)b * (nb + 1), ts->d_ids, off.p, len.p, out.p);
+        if (ts->narrow)
+          hipLaunchKernelGGL(copy_untouched_lists_kernel<uint16_t>, dim3(nb), dim3(256), 0, s, st,
+                             ts->d_dir + (size_t)b * (nb + 1), static_cast<const uint16_t*>(ts->d_ids), off.p, len.p,
+                             out.p);
+        else
+          hipLaunchKernelGGL(copy_untouched_lists_kernel<int32_t>, dim3(nb), dim3(256), 0, s, st,
+                             ts->d_dir + (size_t)b * (nb + 1), static_cast<const int32_t*>(ts->d_ids), off.p, len.p,
+                             out.p);
         SLONN_HIP(hipGetLastError());
       }
     }

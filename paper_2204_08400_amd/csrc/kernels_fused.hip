@@ -339,8 +339,16 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
       if (wave == 0 && lane == 0 && Ly.tap_cnt) Ly.tap_cnt[q] = Hf + msel;
       if (m < n) {
         // ---- keys, bucket lookup, merge: first msel distinct nodes in slot order ----
-        select_block<NT>(zs, Ly.K, Ly.L, n, msel, Ly.dir, Ly.ids, Ly.global_rank, sh,
-                         Ly.tap_codes ? Ly.tap_codes + (size_t)q * Ly.L : nullptr, alist, Hf ? hmap : nullptr);
+        if (Ly.ids_narrow)
+          select_block<NT, SELECT_MU, uint16_t>(zs, Ly.K, Ly.L, n, msel, Ly.dir, static_cast<const uint16_t*>(Ly.ids),
+                                                Ly.global_rank, sh,
+                                                Ly.tap_codes ? Ly.tap_codes + (size_t)q * Ly.L : nullptr, alist,
+                                                Hf ? hmap : nullptr);
+        else
+          select_block<NT, SELECT_MU, int32_t>(zs, Ly.K, Ly.L, n, msel, Ly.dir, static_cast<const int32_t*>(Ly.ids),
+                                               Ly.global_rank, sh,
+                                               Ly.tap_codes ? Ly.tap_codes + (size_t)q * Ly.L : nullptr, alist,
+                                               Hf ? hmap : nullptr);
         list = alist;
         if (Ly.tap_idx) {
           for (int i = tid; i < Hf; i += NT) Ly.tap_idx[(size_t)q * n + i] = Ly.hnodes[i];

@@ -276,9 +276,16 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
     for (int i = tid; i < n2; i += NT) list[i] = i;
   } else {
     for (int h = tid; h < Hf; h += NT) list[h] = a.hnodes[h];
-    select_block_wide<NT>(zs, a.K, a.L, n2, total - Hf, a.dir, a.ids, a.global_rank, sh,
-                          a.tap_codes ? a.tap_codes + (size_t)q * a.L : nullptr, list + Hf,
-                          Hf ? a.hslot : nullptr);
+    if (a.ids_narrow)
+      select_block_wide<NT, SELECT_MU, uint16_t>(zs, a.K, a.L, n2, total - Hf, a.dir, static_cast<const uint16_t*>(a.ids),
+                                                 a.global_rank, sh,
+                                                 a.tap_codes ? a.tap_codes + (size_t)q * a.L : nullptr, list + Hf,
+                                                 Hf ? a.hslot : nullptr);
+    else
+      select_block_wide<NT, SELECT_MU, int32_t>(zs, a.K, a.L, n2, total - Hf, a.dir, static_cast<const int32_t*>(a.ids),
+                                                a.global_rank, sh,
+                                                a.tap_codes ? a.tap_codes + (size_t)q * a.L : nullptr, list + Hf,
+                                                Hf ? a.hslot : nullptr);
   }
   __syncthreads();          // the list (global memory) is complete and visible to the workgroup
 

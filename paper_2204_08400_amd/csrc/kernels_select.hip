@@ -145,10 +145,10 @@ __device__ __forceinline__ void sum_split_projections(const HashSplit& hs, int q
 template <int NT>
 struct BlockMU { static constexpr int value = 4096 / NT; };
 
-template <int NT>
+template <int NT, typename IdT>
 __global__ __launch_bounds__(NT) void select_block_kernel(
     const float* Z, int K, int L, int n, const uint32_t* __restrict__ dir,
-    const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
+    const IdT* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
     float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf, HashSplit hsp,
@@ -198,15 +198,16 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
     for (int h = tid; h < H; h += NI) out[h] = hf.hnodes[h];
   }
   __syncthreads();
-  select_merge<NT, MU>(L, n, total - H, ids, global_rank, sh, out + H, hskip);
+  select_merge<NT, MU, IdT>(L, n, total - H, ids, global_rank, sh, out + H, hskip);
 
   if (rb.part_idx && !tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
     partition_rows<NT>(out, total, rb, q, z, sh.prio);
 }
 
+template <typename IdT>
 __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
     const float* Z, int K, int L, int n, const uint32_t* __restrict__ dir,
-    const int32_t* __restrict__ ids, const int32_t* __restrict__ global_rank,
+    const IdT* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
     int32_t* __restrict__ active, int32_t* __restrict__ cnt, int idx_stride,
     float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf, HashSplit hsp,
@@ -249,7 +250,7 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   for (int i = tid; i < SelectWideTable<SEL_NT, WIDE_MU>::entries; i += SEL_NT) { sh.tkey[i] = -1; sh.tval[i] = 0xFFFFFFFFu; }
   for (int h = tid; h < H; h += SEL_NT) out[h] = hf.hnodes[h];
   __syncthreads();
-  select_block_wide<SEL_NT, WIDE_MU>(z, K, L, n, total - H, dir, ids, global_rank, sh,
+  select_block_wide<SEL_NT, WIDE_MU, IdT>(z, K, L, n, total - H, dir, ids, global_rank, sh,
                             codes ? codes + (size_t)q * L : nullptr, out + H, H ? hf.hslot : nullptr);
   if (rb.part_idx && !tile_served<SEL_NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
     partition_rows<SEL_NT>(out, total, rb, q, z, sh.tval);
@@ -298,37 +299,36 @@ __global__ void fill_iota_kernel(int32_t* __restrict__ idx, int stride, int32_t*
 
 }  // namespace
 
-int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,
-                  const int32_t* global_rank, const float* keep, int keep_stride, int B,
-                  uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
-                  int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first,
-                  const HashSplit* split, const int32_t* order, hipStream_t s) {
-  ProfScope prof_(SLONN_PROF_SELECT, s);
-  const HashFirst hf = hash_first ? *hash_first : HashFirst{};
-  const HashSplit hsp = split ? *split : HashSplit{};
+namespace {
+template <typename IdT>
+int launch_select_t(const float* Z, int K, int L, int n, const uint32_t* dir, const IdT* ids,
+                    const int32_t* global_rank, const float* keep, int keep_stride, int B,
+                    uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
+                    int ldy, int max_lds, const RowBlocking* rb, const HashFirst& hf, const HashSplit& hsp,
+                    const int32_t* order, hipStream_t s) {
   const size_t lds_block = ((size_t)n + SelectShared<SEL_NT, BlockMU<SEL_NT>::value>::words_besides_prio) * 4;
   if (lds_block <= (size_t)max_lds) {
     const RowBlocking rbv = rb ? *rb : RowBlocking{};
     if (B <= SEL_BIG_MAX_BATCH) {
       if (lds_block > 65536)
-        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG>),
+        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG, IdT>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
-      hipLaunchKernelGGL((select_block_kernel<SEL_NT_BIG>), dim3(B), dim3(SEL_NT_BIG), lds_block, s, Z, K, L, n,
+      hipLaunchKernelGGL((select_block_kernel<SEL_NT_BIG, IdT>), dim3(B), dim3(SEL_NT_BIG), lds_block, s, Z, K, L, n,
                          dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp, order);
     } else if (B <= 2 * SEL_BIG_MAX_BATCH || lds_block * 5 > ((size_t)160 << 10)) {
       // up to two queries per compute unit, or maps so large that at most four workgroups share a
       // unit: 512 threads (select per step with 256 / 512 threads: C3 batch 512 103 / 92 us, batch
       // 1024 131 / 137; C5 batch 2048 814 / 766)
       if (lds_block > 65536)
-        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<512>),
+        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<512, IdT>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
-      hipLaunchKernelGGL((select_block_kernel<512>), dim3(B), dim3(512), lds_block, s, Z, K, L, n, dir,
+      hipLaunchKernelGGL((select_block_kernel<512, IdT>), dim3(B), dim3(512), lds_block, s, Z, K, L, n, dir,
                          ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp, order);
     } else {
       if (lds_block > 65536)
-        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT>),
+        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT, IdT>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));
-      hipLaunchKernelGGL((select_block_kernel<SEL_NT>), dim3(B), dim3(SEL_NT), lds_block, s, Z, K, L, n, dir,
+      hipLaunchKernelGGL((select_block_kernel<SEL_NT, IdT>), dim3(B), dim3(SEL_NT), lds_block, s, Z, K, L, n, dir,
                          ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp, order);
     }
     SLONN_HIP(hipGetLastError());
@@ -339,12 +339,28 @@ int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, cons
     SLONN_FAIL(SLONN_EUNSUPPORTED, "select: layer with %d nodes needs %zu bytes of LDS, device grants %d",
                n, lds, max_lds);
   if (lds > 65536)
-    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_wide_kernel),
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_wide_kernel<IdT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(select_wide_kernel, dim3(B), dim3(SEL_NT), lds, s, Z, K, L, n, dir, ids, global_rank,
+  hipLaunchKernelGGL(select_wide_kernel<IdT>, dim3(B), dim3(SEL_NT), lds, s, Z, K, L, n, dir, ids, global_rank,
                      keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rb ? *rb : RowBlocking{}, hf, hsp, order);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
+}
+}  // namespace
+
+int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const void* ids, bool ids_narrow,
+                  const int32_t* global_rank, const float* keep, int keep_stride, int B,
+                  uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
+                  int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first,
+                  const HashSplit* split, const int32_t* order, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_SELECT, s);
+  const HashFirst hf = hash_first ? *hash_first : HashFirst{};
+  const HashSplit hsp = split ? *split : HashSplit{};
+  if (ids_narrow)
+    return launch_select_t(Z, K, L, n, dir, static_cast<const uint16_t*>(ids), global_rank, keep, keep_stride, B, codes,
+                           active, cnt, idx_stride, yzero, ldy, max_lds, rb, hf, hsp, order, s);
+  return launch_select_t(Z, K, L, n, dir, static_cast<const int32_t*>(ids), global_rank, keep, keep_stride, B, codes,
+                         active, cnt, idx_stride, yzero, ldy, max_lds, rb, hf, hsp, order, s);
 }
 
 // More queries than workgroups of the select kernel fit on the device at once: the queries with

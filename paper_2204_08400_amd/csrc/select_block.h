@@ -58,8 +58,9 @@ __device__ __forceinline__ void select_keys(const float* z, int K, int L_, const
 // hskip (nullable, LDS or global, [n]): nodes with an entry >= 0 are passed over wherever
 // they turn up (the variant of Section 3.4 in which hash nodes are computed anyway and the
 // Node Activator never selects them); the caller keeps m <= n minus their number.
-template <int NT, int MU = SELECT_MU>
-__device__ __forceinline__ void select_merge(int L_, int n, int m, const int32_t* __restrict__ ids,
+// IdT: the type the lists are stored in (uint16_t for layers of up to 65 536 nodes, else int32_t)
+template <int NT, int MU = SELECT_MU, typename IdT = int32_t>
+__device__ __forceinline__ void select_merge(int L_, int n, int m, const IdT* __restrict__ ids,
                                              const int32_t* __restrict__ global_rank,
                                              const SelectShared<NT, MU>& sh, int32_t* out,
                                              const int16_t* hskip = nullptr) {
@@ -94,7 +95,7 @@ __device__ __forceinline__ void select_merge(int L_, int n, int m, const int32_t
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
       valid[u] = u < per && slot0 + u < nslots && r < sh.s_len[b];
-      node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
+      node[u] = valid[u] ? (int)ids[sh.s_off[b] + r] : -1;
       if (++b == L) { b = 0; ++r; }
     }
     if (hskip) {
@@ -172,16 +173,16 @@ __device__ __forceinline__ void select_merge(int L_, int n, int m, const int32_t
 // Keys by the first wavefront, then the merge: for callers whose projections are only ready
 // now.  prio[0..n) must hold 0xFFFFFFFF and be visible to all threads (caller clears it and
 // synchronises).
-template <int NT, int MU = SELECT_MU>
+template <int NT, int MU = SELECT_MU, typename IdT = int32_t>
 __device__ __forceinline__ void select_block(const float* z, int K, int L_, int n, int m,
                                              const uint32_t* __restrict__ dir,
-                                             const int32_t* __restrict__ ids,
+                                             const IdT* __restrict__ ids,
                                              const int32_t* __restrict__ global_rank,
                                              const SelectShared<NT, MU>& sh, uint32_t* codes_row,
                                              int32_t* out, const int16_t* hskip = nullptr) {
   if (threadIdx.x < 64) select_keys<NT, MU>(z, K, L_, dir, sh, codes_row);
   __syncthreads();
-  select_merge<NT, MU>(L_, n, m, ids, global_rank, sh, out, hskip);
+  select_merge<NT, MU, IdT>(L_, n, m, ids, global_rank, sh, out, hskip);
 }
 
 // Same query for layers too wide for a 4-byte map entry per node (hundreds of thousands of
@@ -212,10 +213,10 @@ struct SelectSharedWide {
 // taken[] must be zero and tkey[] = -1, tval[] = 0xFFFFFFFF on entry (caller + barrier).
 // Slots, rounds and compaction as in select_merge (a thread takes consecutive slots; positions
 // from one count per thread); a third barrier per round lets the round table be emptied.
-template <int NT, int MU = SELECT_MU>
+template <int NT, int MU = SELECT_MU, typename IdT = int32_t>
 __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_, int n, int m,
                                                   const uint32_t* __restrict__ dir,
-                                                  const int32_t* __restrict__ ids,
+                                                  const IdT* __restrict__ ids,
                                                   const int32_t* __restrict__ global_rank,
                                                   const SelectSharedWide<NT, MU>& sh, uint32_t* codes_row,
                                                   int32_t* out, const int16_t* hskip = nullptr) {
@@ -264,7 +265,7 @@ __device__ __forceinline__ void select_block_wide(const float* z, int K, int L_,
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
       valid[u] = u < per && base + rel0 + u < nslots && r < sh.s_len[b];
-      node[u] = valid[u] ? ids[sh.s_off[b] + r] : -1;
+      node[u] = valid[u] ? (int)ids[sh.s_off[b] + r] : -1;
       cell[u] = 0;
       if (++b == L) { b = 0; ++r; }
     }

@@ -527,7 +527,8 @@ int slonn_tables_export(const slonn_tables* t, void* host_buf, size_t* bytes) {
     put(L.hash_nodes.data(), 4 * L.hash_nodes.size());
     put(s.dir.data(), 4 * s.dir.size());
     if (s.n_ids) {                              // the lists are held on the device only
-      SLONN_HIP(hipMemcpy(p, s.d_ids, 4 * s.n_ids, hipMemcpyDeviceToHost));
+      const int rc = download_ids(&s, reinterpret_cast<int32_t*>(p));
+      if (rc) return rc;
       p += 4 * s.n_ids;
     }
     put(s.global_rank.data(), 4 * s.global_rank.size());
@@ -651,7 +652,7 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
   if (rc) return rc;
   HashFirst hf;
   if (m->hash_first) { hf.hnodes = L.hnodes; hf.hslot = L.hslot; }
-  return launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank, keep, keep_stride,
+  return launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->narrow, ts->d_global_rank, keep, keep_stride,
                        B, codes_out, active_idx, active_cnt, idx_stride, nullptr, 0, m->max_lds_bytes,
                        nullptr, m->hash_first ? &hf : nullptr, nullptr, nullptr, s);
 }
@@ -729,7 +730,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
     a.ellp = (X->ell_stride + 3) & ~3;
     a.W1 = O.W; a.b1 = O.bias; a.w1_dtype = O.w_dtype; a.act1 = O.act; a.n2 = O.d_out;
     a.Wh = O.Wh; a.bh = O.bh; a.K = O.K; a.L = O.L; a.Hp = (O.H() + 3) & ~3;
-    a.dir = ts->d_dir; a.ids = ts->d_ids; a.global_rank = ts->d_global_rank;
+    a.dir = ts->d_dir; a.ids = ts->d_ids; a.ids_narrow = ts->narrow ? 1 : 0; a.global_rank = ts->d_global_rank;
     a.hnodes = O.hnodes; a.hslot = O.hslot; a.hash_first = m->hash_first ? 1 : 0;
     a.keep = keep + (size_t)1 * keep_lstride; a.keep_qstride = keep_qstride;
     int32_t* tap_idx = taps && taps->active_idx ? taps->active_idx[1] : nullptr;
@@ -778,7 +779,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       f.d_in = L.d_in; f.d_out = L.d_out; f.act = L.act; f.w_dtype = L.w_dtype; f.K = L.K; f.L = L.L;
       if (L.activated()) {
         const TableSet* ts = t->for_layer(l);
-        f.dir = ts->d_dir; f.ids = ts->d_ids; f.global_rank = ts->d_global_rank;
+        f.dir = ts->d_dir; f.ids = ts->d_ids; f.ids_narrow = ts->narrow ? 1 : 0; f.global_rank = ts->d_global_rank;
         a.max_H = std::max(a.max_H, L.H());
         a.max_na = std::max(a.max_na, L.d_out);
       }
@@ -909,7 +910,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         }
         order = w.order;
       }
-      rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->d_global_rank,
+      rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->narrow, ts->d_global_rank,
                          keep + (size_t)l * keep_lstride, keep_qstride, B, codes, aidx, acnt, astride, out,
                          ldo, m->max_lds_bytes, rb.part_idx ? &rb : nullptr, m->hash_first ? &hf : nullptr,
                          split.part ? &split : nullptr, order, s);

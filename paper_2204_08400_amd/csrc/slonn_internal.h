@@ -55,7 +55,8 @@ struct TableSet {                 // Node Importance tables of one layer
   std::vector<int32_t> global_rank;
   size_t n_ids = 0;               // list entries held in d_ids
   uint32_t* d_dir = nullptr;      // device copies
-  int32_t* d_ids = nullptr;
+  void* d_ids = nullptr;          // the lists: uint16_t entries when narrow, else int32_t
+  bool narrow = false;            // layers of up to 65 536 nodes store 2-byte node ids
   int32_t* d_global_rank = nullptr;
   // NodeScore state kept for online refresh (tables trained with slonn_model_set_tables_refreshable)
   double* d_score = nullptr;         // [L][2^K][n] NodeScore sums
@@ -123,14 +124,14 @@ struct FusedLayer {
   const int16_t* hslot;
   const int32_t* hnodes;
   const uint32_t* dir;
-  const int32_t* ids;
+  const void* ids;                 // uint16_t entries when ids_narrow, else int32_t
   const int32_t* global_rank;
   uint32_t* tap_codes;
   float* tap_z;
   int32_t* tap_idx;
   int32_t* tap_cnt;
   float* tap_out;
-  int d_in, d_out, act, w_dtype, K, L;
+  int d_in, d_out, act, w_dtype, K, L, ids_narrow;
 };
 struct FusedArgs {
   FusedLayer layer[FUSED_MAX_LAYERS];
@@ -155,9 +156,9 @@ struct FusedWideArgs {
   int w0_dtype, act0, d0, n1, n1p, ccp, ell_stride, ellp;
   // output layer and its Node Activator
   const void* W1; const float* b1; const float* Wh; const float* bh;
-  const uint32_t* dir; const int32_t* ids; const int32_t* global_rank;
+  const uint32_t* dir; const void* ids; const int32_t* global_rank;
   const int32_t* hnodes; const int16_t* hslot;
-  int w1_dtype, act1, n2, K, L, Hp, hash_first;
+  int w1_dtype, act1, n2, K, L, Hp, hash_first, ids_narrow;
   const float* keep; int keep_qstride;
   // outputs (list, vals, cnt always; dense, argmax and the taps nullable)
   int32_t* list; int list_stride;
@@ -235,7 +236,8 @@ int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8
                             hipStream_t s);
 
 // keys + bucket lookup + merge for one layer.  yzero (nullable): [B][ldy] rows to clear.
-int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const int32_t* ids,
+// ids: the lists, uint16_t entries when ids_narrow, else int32_t
+int launch_select(const float* Z, int K, int L, int n, const uint32_t* dir, const void* ids, bool ids_narrow,
                   const int32_t* global_rank, const float* keep, int keep_stride, int B,
                   uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
                   int ldy, int max_lds, const RowBlocking* rb, const HashFirst* hash_first,
@@ -363,6 +365,8 @@ int rank_by_sort(const double* score, int n, int segs, const uint32_t* off, cons
 // device copies from the host vectors; the lists come from d_ids_src (device, ts->n_ids
 // entries) when given, else from ts->ids
 int upload_table_set(TableSet* ts, const int32_t* d_ids_src = nullptr);
+// the lists of a table set as 4-byte ids in host memory (ts->n_ids of them)
+int download_ids(const TableSet* ts, int32_t* host_out);
 void free_table_set(TableSet* ts);
 
 }  // namespace slonn
