@@ -144,13 +144,13 @@ class Workload:
         for ln in lanes[1:]:
             self.stream.wait_stream(ln["stream"])
 
-    def step(self, keep_t, one_lane=False):
+    def step(self, keep_t, one_lane=False, uniform=False):
         s, B = self.slonn, self.batch
         lanes = self.lanes[:1] if one_lane else self.lanes
         self._fork(lanes)
         for i, nb in enumerate(self.sizes):
             ln = lanes[i % len(lanes)]
-            if self.mixed is not None:
+            if self.mixed is not None and not uniform:
                 s.slonn_sparse_forward(self.net.model, self.net.tables, self.batches[i], nb,
                                        self.mixed[i * B:i * B + nb], 1, 0, ln["out"], None, ln["ws"], ln["stream"])
             else:
@@ -198,9 +198,9 @@ class Workload:
         return self.torch.full((1,), float(keep if keep is not None else 1.0), dtype=self.torch.float32,
                                device=self.dev)
 
-    def time_sparse(self, keep, steps, warm, mark=False):
+    def time_sparse(self, keep, steps, warm, mark=False, uniform=False):
         kt = self.keep_tensor(keep)
-        return self.timed(lambda: self.step(kt), steps, warm, mark)
+        return self.timed(lambda: self.step(kt, uniform=uniform), steps, warm, mark)
 
     def profile_sparse(self, keep, steps):
         """Per-kernel-kind durations over `steps` more steps: every launch bracketed by two HIP events
@@ -424,11 +424,11 @@ def main():
                                             "TFLOPs": round(dflops * steps * wk.nq / s / 1e12, 2)}
         if hasattr(slonn, "slonn_model_set_dense_arithmetic"):
             slonn.slonn_model_set_dense_arithmetic(wk.net.model, 0)
-        if wk.batch <= 64 and 1.0 not in keeps and wk.mixed is None:
+        if wk.batch <= 64 and 1.0 not in keeps:
             # small batches: the full network is also run through the sparse path's own kernels with every
             # node active (keep 1.0: no table access, rows spread over all compute units), the "all nodes
             # computed" case of Section 3.4; a matrix-core GEMM has little to offer a handful of queries
-            s, _ = wk.time_sparse(1.0, steps, warm)
+            s, _ = wk.time_sparse(1.0, steps, warm, uniform=True)
             res["dense_baseline"]["all_nodes_through_the_gather_kernels"] = {
                 "qps": round(steps * wk.nq / s), "ms_per_step": round(s / steps * 1e3, 4),
                 "TFLOPs": round(dflops * steps * wk.nq / s / 1e12, 2)}
@@ -562,6 +562,19 @@ def main():
     # ---- the other workloads, briefly (their own query sets, whole-set steps) ----
     if not args.no_sweep and not args.no_others and args.config == "C5":
         others = {}
+        # the headline model at small batches (the paper serves one query at a time, Section 4)
+        for b_, q_ in ((32, 1024), (8, 256), (1, 64)):
+            w.set_batch(b_, q_)
+            r = sweep_and_dense(w, 3, 1, ())
+            s_, _ = w.time_sparse(None, 3, 1)
+            best = max(v["qps"] for v in r["dense_baseline"].values())
+            r["sparse"] = {"qps": round(3 * w.nq / s_), "ms_per_step": round(s_ / 3 * 1e3, 4),
+                           "nominal_gathered_GBps": round(w.gathered_bytes_per_step(None) * 3 / s_ / 1e9, 1),
+                           "sparse_over_best_dense": round(3 * w.nq / s_ / best, 3)}
+            r["config"] = {"workload": head_config["workload"], "batch": b_, "keep": keep_label,
+                           "queries_per_step": w.nq, "streams": max(1, args.streams)}
+            others[f"{args.config}_B{b_}"] = r
+            log(f"{args.config} batch {b_}: {r}")
         del w
         torch.cuda.empty_cache()
         # (name, batch sizes with the queries per step at each, query set, table-training inputs)
