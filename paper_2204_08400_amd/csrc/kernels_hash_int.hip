@@ -163,12 +163,14 @@ template <int HH, int WQ, int WH>
 __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __restrict__ Xd,
                                                             const int8_t* __restrict__ Wd,
                                                             double* __restrict__ part, int B, int H, int d,
-                                                            int nslices) {
+                                                            int nslices, int xcd_sx) {
   extern __shared__ u32x4 hash_lds[];       // two buffers of [HQ rows of X | HH rows of W][HROW]
   constexpr int BUF = (HQ + HH) * HROW;
   constexpr int TOTAL = (HQ + HH) * HPIECES;         // pieces per chunk
   constexpr int PER = (TOTAL + 511) / 512;           // per thread (the last one partly repeated)
-  const int q0 = blockIdx.y * HQ, h0 = blockIdx.x * HH;
+  int tile_h, tile_q;                       // the workgroups of one XCD take a compact block of tiles
+  xcd_tile(blockIdx.x, blockIdx.y, gridDim.x, gridDim.y, xcd_sx, tile_h, tile_q);
+  const int q0 = tile_q * HQ, h0 = tile_h * HH;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   constexpr int NBQ = HQ / (16 * WQ), NBH = HH / (16 * WH);   // 16 x 16 blocks per wavefront
   static_assert(WQ * WH == 8 && HQ % (16 * WQ) == 0 && HH % (16 * WH) == 0, "wavefront grid must cover the tile");
@@ -374,23 +376,30 @@ __global__ __launch_bounds__(256) void hash_int_finish_kernel(const double* __re
 int hash_int_digits() { return DIGITS; }
 
 bool hash_int_supported(int d, int max_lds) {      // (d <= 16384: the slicing kernel holds a row in registers)
-  return d % 64 == 0 && d <= 16384 && (size_t)2 * (HQ + 64) * HROW * 16 <= (size_t)max_lds;
+  return d % 64 == 0 && d <= 16384 && (size_t)2 * (HQ + 96) * HROW * 16 <= (size_t)max_lds;
 }
 
-// Tile height (64 or 48 hash rows) and slices of the reduction dimension: the pair that fills one
+// Tile height (96, 64 or 48 hash rows) and slices of the reduction dimension: the pair that fills one
 // round of workgroups best (one workgroup per compute unit: the two tile buffers take most of
 // its LDS), slices of at least 8 chunks.
 void hash_int_plan(int B, int H, int d, int* hh_out, int* s_out) {
   const int nchunks = d / 64;
   int best_hh = 64, best_s = 1;
   long best_fill = -1;
-  for (int hh : {64, 48}) {
+  for (int hh : {96, 64, 48}) {
+    // (the tall tile only where it wastes next to no rows: C5's 768 hash rows are 8 tiles of 96 - tiles
+    // 107 -> 92 us; on C3's 320 rows it would pad to 384 and slice the reduction eightfold - 46.6 -> 48.6 us)
+    if (hh == 96 && (long)((H + 95) / 96) * 96 * 100 > (long)H * 105) continue;
     const int tiles = ((B + HQ - 1) / HQ) * ((H + hh - 1) / hh);
     int S = 1;
     while (tiles * S * 2 <= 256 && S * 2 <= 8 && nchunks / (S * 2) >= 8) S *= 2;
-    // useful work per slot of the rounds the grid takes (rows beyond H are wasted work)
+    // useful work per slot of the rounds the grid takes (rows beyond H are wasted work), times how
+    // far the tile's LDS traffic lets the matrix cores run: per chunk a 128 x 96 tile reads 20
+    // operand fragments per wavefront for 60 MFMAs (the cores are the limit), 128 x 64 reads 16 for
+    // 40 (about even), 128 x 48 with eight query strips reads 16 for 30 (LDS-bound at 0.7)
     const long rounds = (tiles * S + 255) / 256;
-    const long fill = (long)H * 1000 / ((H + hh - 1) / hh * hh) * (tiles * S) / (rounds * 256);
+    const long eff = hh == 96 ? 100 : (hh == 64 ? 92 : 70);
+    const long fill = (long)H * 1000 / ((H + hh - 1) / hh * hh) * (tiles * S) / (rounds * 256) * eff;
     if (fill > best_fill) { best_fill = fill; best_hh = hh; best_s = S; }
   }
   *hh_out = best_hh;
@@ -422,19 +431,29 @@ int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8
   if (rc) return rc;
   int hh = 64, S = 1;
   hash_int_plan(B, H, d, &hh, &S);
-  if (hh == 64) {
+  // XCD-aware tile order: per XCD the fewest bytes of digits (a tile of hash rows against a tile of queries)
+  const int nx = (H + hh - 1) / hh, ny = (B + HQ - 1) / HQ;
+  const int sx = xcd_split(nx, ny, (double)hh * DIGITS * d / S, (double)HQ * DIGITS * d / S);
+  if (hh == 96) {
+    constexpr size_t lds = (size_t)2 * (HQ + 96) * HROW * 16;
+    static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel<96, 4, 2>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((hash_int_tiles_kernel<96, 4, 2>), dim3((H + 95) / 96, (B + HQ - 1) / HQ, S), dim3(512), lds, s,
+                       Xd, Wd, part, B, H, d, S, sx);
+  } else if (hh == 64) {
     constexpr size_t lds = (size_t)2 * (HQ + 64) * HROW * 16;
     static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel<64, 4, 2>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((hash_int_tiles_kernel<64, 4, 2>), dim3((H + 63) / 64, (B + HQ - 1) / HQ, S), dim3(512), lds, s,
-                       Xd, Wd, part, B, H, d, S);
+                       Xd, Wd, part, B, H, d, S, sx);
   } else {
     constexpr size_t lds = (size_t)2 * (HQ + 48) * HROW * 16;
     SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(hash_int_tiles_kernel<48, 8, 1>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((hash_int_tiles_kernel<48, 8, 1>), dim3((H + 47) / 48, (B + HQ - 1) / HQ, S), dim3(512), lds, s,
-                       Xd, Wd, part, B, H, d, S);
+                       Xd, Wd, part, B, H, d, S, sx);
   }
   SLONN_HIP(hipGetLastError());
   hipLaunchKernelGGL(hash_int_finish_kernel, dim3((unsigned)(((size_t)B * H + 255) / 256)), dim3(256), 0, s, part, S,

@@ -210,6 +210,33 @@ struct HashSplit {
   float* Z = nullptr;
 };
 
+// Tile kernels and the eight XCDs.  Workgroups are dealt to the XCDs in turn by their linear id,
+// and each XCD has an L2 of its own: the workgroups of one XCD should share operand tiles.  For an
+// nx x ny grid of tiles (x: tiles of the first operand, y: of the second) the XCDs are laid out
+// sx x (8 / sx) over the grid and every XCD takes a compact block of nx / sx by ny / (8 / sx) tiles.
+// xcd_split picks sx (0: leave the grid as it is) from the bytes of one tile of either operand.
+inline int xcd_split(int nx, int ny, double x_tile_bytes, double y_tile_bytes) {
+  int best = 0;
+  double best_cost = 0.0;
+  for (int sx = 1; sx <= 8; sx *= 2) {
+    const int sy = 8 / sx;
+    if (nx % sx != 0 || ny % sy != 0) continue;
+    const double cost = (double)(nx / sx) * x_tile_bytes + (double)(ny / sy) * y_tile_bytes;
+    if (best == 0 || cost < best_cost) { best = sx; best_cost = cost; }
+  }
+  return best;
+}
+#if defined(__HIPCC__)
+__device__ __forceinline__ void xcd_tile(int bx, int by, int nx, int ny, int sx, int& tx, int& ty) {
+  if (sx == 0) { tx = bx; ty = by; return; }
+  const int sy = 8 / sx;
+  const int w = bx + nx * by, xcd = w & 7, slot = w >> 3;
+  const int rx = nx / sx, ry = ny / sy;
+  tx = (xcd % sx) * rx + slot % rx;
+  ty = (xcd / sx) * ry + slot / rx;
+}
+#endif
+
 // ---- kernel launchers (each validates nothing: callers have checked shapes) ----
 
 // Z[q][h] = Wh[h] . X[q] + bh[h], fp64 accumulation, rounded once to fp32.
