@@ -133,6 +133,34 @@ def test_dense_forward_matches_oracle(rt, oracle):
         assert np.array_equal(got["argmax"].cpu().numpy(), oracle.argmax(ref[-1]))
 
 
+@pytest.mark.parametrize("w_dtype", [wl.W_F32, wl.W_BF16], ids=["f32", "bf16"])
+def test_dense_forward_in_bf16_parts_matches_oracle(rt, oracle, w_dtype):
+    """The full network in the sparse path's large-batch arithmetic (operands as three bf16 parts on
+    the bf16 matrix cores, slonn_model_set_dense_arithmetic) against the oracle's dense network, and
+    that the unmasked tiles really ran for the large layers."""
+    from paper_2204_08400_amd import slonn
+    dims = (512, 2048, 2048, 16)
+    layers, net, _ = make_case(oracle, dims, 4, 6, seed=41, kind="clip3", N_build=64, w_dtype=w_dtype)
+    g = _gpu_net(rt, layers, net)
+    X = make_queries(dims, 300, seed=42, kind="clip3")       # a ragged batch: 4 tiles of 64 and 44 queries
+    ref = net.dense_forward(X)
+    slonn.slonn_model_set_dense_arithmetic(g.model, 1)
+    slonn.slonn_profile_begin(16)
+    got = g.dense_forward(X, layer_outs=True)
+    prof = slonn.slonn_profile_end()
+    assert prof["dense"][1] == len(layers), prof
+    for l in range(len(layers)):
+        assert_close_rows(got["layers"][l].cpu().numpy(), ref[l], None, f"dense in bf16 parts, layer {l}", depth=l + 1)
+    assert np.array_equal(got["argmax"].cpu().numpy(), oracle.argmax(ref[-1]))
+    # against the default arithmetic: the same results to fp32 rounding, not the same bits
+    slonn.slonn_model_set_dense_arithmetic(g.model, 0)
+    plain = g.dense_forward(X, layer_outs=True)
+    assert_close_rows(got["layers"][1].cpu().numpy(), plain["layers"][1].cpu().numpy(), None, "bf16 parts vs fp32 cores", depth=2)
+    assert not np.array_equal(got["layers"][1].cpu().numpy(), plain["layers"][1].cpu().numpy())
+    with pytest.raises(slonn.SlonnError):
+        slonn.slonn_model_set_dense_arithmetic(g.model, 7)
+
+
 def test_keep_one_equals_dense_path(rt, oracle):
     dims = (100, 300, 260, 37)
     layers, net, _ = make_case(oracle, dims, 4, 6, seed=17)

@@ -100,7 +100,21 @@ def test_null_handles_are_rejected(slonn):
     assert lib.slonn_policy_keep_lcao(None, 1, None, 0, None, 0, None, 0, None, None, None, None) == slonn.EINVAL
     assert lib.slonn_sparse_forward_aclo(None, None, None, None, 1, None, 0, None, None, None, None,
                                          C.c_size_t(0), None) == slonn.EINVAL
+    assert lib.slonn_sparse_forward_static(None, None, None, 1, None, 0, 0, None, None, None) == slonn.EINVAL
+    assert lib.slonn_model_set_dense_arithmetic(None, 1) == slonn.EINVAL
+    assert lib.slonn_model_set_tables_refreshable(None, 1) == slonn.EINVAL
+    assert lib.slonn_tables_refresh(None, None, None, C.c_int64(1), None) == slonn.EINVAL
+    assert lib.slonn_sample_hash_nodes_device(None, 8, 1, 1, None, None, None) == slonn.EINVAL
     assert slonn.load().slonn_last_error()
+
+
+def test_device_sampler_rejects_before_touching_the_device(slonn):
+    """argument checks of slonn_sample_hash_nodes_device run on the host (pointers are never read)"""
+    lib = slonn.load()
+    p = C.c_void_p(0x1000)
+    assert lib.slonn_sample_hash_nodes_device(p, 8, 3, 3, p, p, None) == slonn.EINVAL           # K*L > n
+    assert lib.slonn_sample_hash_nodes_device(p, 0, 1, 1, p, p, None) == slonn.EINVAL
+    assert lib.slonn_sample_hash_nodes_device(p, (1 << 20) + 1, 1, 1, p, p, None) == -4          # beyond 2^20 nodes
 
 
 def test_binding_fails_loudly_without_library(slonn, monkeypatch, tmp_path):
