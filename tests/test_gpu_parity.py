@@ -1192,3 +1192,49 @@ def test_maximum_batch_wide_hash(rt, oracle):
     assert np.array_equal(got_c[okq], cnt[okq])
     m = int(cnt[0])
     assert np.array_equal(got_a[okq, :m], active[okq, :m])
+
+
+def test_two_streams_with_their_own_workspaces_do_not_interfere(rt, oracle):
+    """bench.py deals the batches of a step to two HIP streams, each with its own workspace and output
+    buffers.  Calls in flight on both streams at once must give, bit for bit, what the same calls
+    give one after the other (the library keeps no per-call state outside the workspace), on the
+    per-layer path (workspace in use) and on the whole-network kernel."""
+    import torch
+    from paper_2204_08400_amd import slonn
+    B, rounds = 96, 6
+    keep = torch.full((1,), 0.2, dtype=torch.float32, device="cuda")
+    for path, dims in (("layers", (512, 4096, 520, 10)), ("fused", (256, 1024, 512, 10))):
+        layers, net, _ = make_case(oracle, dims, 6, 12, seed=31, kind="clip3", N_build=128)
+        Xs = [torch.from_numpy(make_queries(dims, B, seed=700 + i, kind="clip3")).cuda() for i in range(2 * rounds)]
+        g = _gpu_net(rt, layers, net, path=path)
+        nbytes = slonn.slonn_workspace_bytes(g.model, B)
+        lanes = []
+        for s in (torch.cuda.current_stream(), torch.cuda.Stream()):
+            lanes.append(dict(stream=s, ws=torch.empty(nbytes, dtype=torch.uint8, device="cuda")))
+        # one after the other on one stream
+        want = []
+        for x in Xs:
+            y = torch.empty((B, dims[-1]), dtype=torch.float32, device="cuda")
+            a = torch.empty(B, dtype=torch.int32, device="cuda")
+            slonn.slonn_sparse_forward(g.model, g.tables, slonn.make_input(x=x), B, keep, 0, 0,
+                                       slonn.make_output(dense=y, argmax=a), None, lanes[0]["ws"], lanes[0]["stream"])
+            want.append((y, a))
+        torch.cuda.synchronize()
+        # the same calls dealt to the two streams in turn, nothing waited for in between
+        _say(f"two streams, path={path}")
+        got = []
+        lanes[1]["stream"].wait_stream(lanes[0]["stream"])
+        for i, x in enumerate(Xs):
+            ln = lanes[i % 2]
+            y = torch.empty((B, dims[-1]), dtype=torch.float32, device="cuda")
+            a = torch.empty(B, dtype=torch.int32, device="cuda")
+            slonn.slonn_sparse_forward(g.model, g.tables, slonn.make_input(x=x), B, keep, 0, 0,
+                                       slonn.make_output(dense=y, argmax=a), None, ln["ws"], ln["stream"])
+            got.append((y, a))
+        torch.cuda.synchronize()
+        for i, ((y, a), (yw, aw)) in enumerate(zip(got, want)):
+            assert torch.equal(y, yw) and torch.equal(a, aw), f"path {path}: call {i} differs when two streams overlap"
+        # and the oracle agrees with one of them
+        ref = net.sparse_forward(Xs[3].cpu().numpy(), 0.2)
+        assert_close_rows(got[3][0].cpu().numpy(), ref["out"], None, "two streams vs oracle",
+                          depth=len(layers))
