@@ -103,9 +103,10 @@ __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restric
     }
     atomicOr(&bits[node >> 5], 1u << (node & 31));
   }
-  // eight elements per thread: two 16-byte loads, three 16-byte stores (d is a multiple of 32)
+  // eight elements per thread: two 16-byte loads, three 16-byte stores (d is a multiple of 32);
+  // no X3: the tile kernel splits the fp32 activations itself
   const bool vec = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);
-  for (int g8 = tid; g8 < (d >> 3); g8 += 256) {
+  for (int g8 = tid; X3 && g8 < (d >> 3); g8 += 256) {
     float xv[8];
     const float* xp = X + (size_t)q * ldx + 8 * g8;
     if (vec) {
@@ -151,6 +152,33 @@ __device__ __forceinline__ void lds_only_barrier() {
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// Eight consecutive fp32 numbers (a, b: their bits) as three pieces of eight bf16 numbers each:
+// the leading 8 significand bits, the next 8, the last 8 (the arithmetic of split3_kernel).
+// Two neighbouring elements (their bits) -> one 32-bit word of each part.
+__device__ __forceinline__ void split_pair(uint32_t x0, uint32_t x1, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
+  const uint32_t x[2] = {x0, x1};
+  uint32_t r1[2], r2[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const float f1 = __uint_as_float(x[e]) - __uint_as_float(x[e] & 0xFFFF0000u);      // exact
+    r1[e] = __float_as_uint(f1);
+    const float f2 = f1 - __uint_as_float(r1[e] & 0xFFFF0000u);                         // exact, at most 8 bits left
+    r2[e] = __float_as_uint(f2);
+  }
+  hi = (x[0] >> 16) | (x[1] & 0xFFFF0000u);
+  mid = (r1[0] >> 16) | (r1[1] & 0xFFFF0000u);
+  lo = (r2[0] >> 16) | (r2[1] & 0xFFFF0000u);
+}
+__device__ __forceinline__ void split8(u32x4 a, u32x4 b, u32x4& hi, u32x4& mid, u32x4& lo) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const u32x4 v = j < 2 ? a : b;
+    uint32_t h, m, l;
+    split_pair(v[(2 * j) & 3], v[(2 * j + 1) & 3], h, m, l);
+    hi[j] = h; mid[j] = m; lo[j] = l;
+  }
+}
+
 // X3: activation rows in three interleaved bf16 parts (see above).  Wp: weight rows, for WP = 3 in
 // the same three-part layout, for WP = 1 plain bf16 rows (bf16 weights: w x_hi, w x_mid, w x_lo
 // are each exact in fp32, three MFMAs per block).  d a multiple of 32.
@@ -158,9 +186,14 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // operand with the eight elements 8 (l / 16) .. + 7 of the step; register v of lane l holds
 // D[4 (l / 16) + v][l % 16], rows from the first operand (here: nodes), columns from the second
 // (queries).
-// TQ queries x TNN nodes per tile; WP weight parts; NT threads (wavefronts in 2 x NT / 128: query halves x node strips)
-template <int TQ, int TNN, int WP, int NT>
+// TQ queries x TNN nodes per tile; WP weight parts; NT threads (wavefronts in 2 x NT / 128: query halves x node strips).
+// XF: the activations come as fp32 rows Xf (16-byte aligned, ldx a multiple of 4) and are split
+// into their three parts on the way from registers to LDS (44 vector instructions per thread and
+// chunk in the shadow of 48 or 96 MFMAs), so that no three-part copy of them passes through HBM;
+// otherwise X3 holds that copy.
+template <int TQ, int TNN, int WP, int NT, bool XF>
 __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __restrict__ X3,
+                                                          const float* __restrict__ Xf, int ldx,
                                                           const uint16_t* __restrict__ Wp,
                                                           const float* __restrict__ bias,
                                                           const uint32_t* __restrict__ mask,
@@ -172,7 +205,10 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
   constexpr int ROWX = PX + 1, ROWW = PW + 1;   // LDS rows, padded by one piece (208 / 80 bytes stagger the banks)
   constexpr int BUF16 = TQ * ROWX + TNN * ROWW;
   constexpr int QB = TQ / 32;              // 16-query blocks per wavefront
-  constexpr int XP = TQ * PX / NT;         // X pieces per thread and chunk
+  constexpr int XG = TQ * 4 / NT;          // XF: groups of eight fp32 activations per thread and chunk
+  constexpr int XP = XF ? 2 * XG : TQ * PX / NT;   // 16-byte pieces of activations loaded per thread and chunk
+  constexpr int XSTEP = XF ? 8 : PX;       // pieces per row and chunk in global memory
+  static_assert(TQ * 4 % NT == 0, "activation groups must divide evenly");
   constexpr int WT = TNN * PW / NT;         // W pieces per thread and chunk
   constexpr int WN = NT / 128;             // node strips (wavefronts along the nodes)
   constexpr int NB = TNN / (16 * WN);       // 16-node blocks per wavefront
@@ -187,11 +223,22 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
   const u32x4* xsrc[XP];
   const u32x4* wsrc[WT];
   int dstx[XP], dstw[WT];
+  if constexpr (XF) {
 #pragma unroll
-  for (int i = 0; i < XP; ++i) {
-    const int idx = tid + NT * i, row = idx / PX, piece = idx % PX;
-    xsrc[i] = reinterpret_cast<const u32x4*>(X3 + (size_t)min(m0 + row, B - 1) * 3 * d) + piece;
-    dstx[i] = row * ROWX + piece;
+    for (int g = 0; g < XG; ++g) {
+      const int idx = tid + NT * g, row = idx / 4, grp = idx % 4;
+      xsrc[2 * g] = reinterpret_cast<const u32x4*>(Xf + (size_t)min(m0 + row, B - 1) * ldx) + 2 * grp;
+      xsrc[2 * g + 1] = xsrc[2 * g] + 1;
+      dstx[2 * g] = row * ROWX + 3 * grp;
+      dstx[2 * g + 1] = 0;               // (unused)
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+      const int idx = tid + NT * i, row = idx / PX, piece = idx % PX;
+      xsrc[i] = reinterpret_cast<const u32x4*>(X3 + (size_t)min(m0 + row, B - 1) * 3 * d) + piece;
+      dstx[i] = row * ROWX + piece;
+    }
   }
 #pragma unroll
   for (int i = 0; i < WT; ++i) {
@@ -210,18 +257,28 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
 #define SLONN_TILES_LOAD(RX, RW, CHUNK)                                            \
   {                                                                               \
     const size_t c_ = (size_t)min((CHUNK), last);                                 \
-    _Pragma("unroll") for (int i = 0; i < XP; ++i) RX[i] = xsrc[i][c_ * PX];      \
+    _Pragma("unroll") for (int i = 0; i < XP; ++i) RX[i] = xsrc[i][c_ * XSTEP];   \
     _Pragma("unroll") for (int i = 0; i < WT; ++i) RW[i] = wsrc[i][c_ * PW];      \
   }
-#define SLONN_TILES_STORE(BUF, RX, RW)                                             \
+#define SLONN_TILES_STORE(BUF, RX, RW, SP)                                         \
   {                                                                               \
     u32x4* buf_ = tiles_lds + (BUF) * BUF16;                                      \
-    _Pragma("unroll") for (int i = 0; i < XP; ++i) buf_[dstx[i]] = RX[i];         \
+    if constexpr (XF) {                                                           \
+      _Pragma("unroll") for (int g = 0; g < XG; ++g)                              \
+        _Pragma("unroll") for (int p = 0; p < 3; ++p) buf_[dstx[2 * g] + p] = SP[g][p]; \
+    } else {                                                                      \
+      _Pragma("unroll") for (int i = 0; i < XP; ++i) buf_[dstx[i]] = RX[i];       \
+    }                                                                             \
     _Pragma("unroll") for (int i = 0; i < WT; ++i) buf_[dstw[i]] = RW[i];         \
   }
+  u32x4 sp[XG][3];                         // XF: the three parts of the chunk that moves to LDS next
   SLONN_TILES_LOAD(r0x, r0w, 0);
   SLONN_TILES_LOAD(r1x, r1w, 1);
-  SLONN_TILES_STORE(0, r0x, r0w);
+  if constexpr (XF) {
+#pragma unroll
+    for (int g = 0; g < XG; ++g) split8(r0x[2 * g], r0x[2 * g + 1], sp[g][0], sp[g][1], sp[g][2]);
+  }
+  SLONN_TILES_STORE(0, r0x, r0w, sp);
   SLONN_TILES_LOAD(r0x, r0w, 2);
   lds_only_barrier();
   // now: LDS buffer 0 holds chunk 0, r1 chunk 1, r0 chunk 2
@@ -232,7 +289,10 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
 #pragma unroll
     for (int b = 0; b < QB; ++b) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  auto multiply = [&](int buf) {
+  // (XF: between the MFMAs the registers RX of the chunk that moves to LDS next are split into
+  // sp, a few instructions after every query block, so that the vector instructions run in the
+  // shadow of the MFMAs instead of in one run between two chunks)
+  auto multiply = [&](int buf, const u32x4 (&RX)[XP]) {
     const u32x4* Xs = tiles_lds + buf * BUF16;
     const u32x4* Ws = Xs + TQ * ROWX;
     bf16x8 xb[QB][3];
@@ -240,6 +300,9 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
     for (int b = 0; b < QB; ++b)
 #pragma unroll
       for (int p = 0; p < 3; ++p) xb[b][p] = as_bf16x8(Xs[(wq * (TQ / 2) + b * 16 + r) * ROWX + kg * 3 + p]);
+    constexpr int PAIRS = 4 / NB;          // XF: pairs of elements split per node block (NB is 2 or 4)
+    static_assert(!XF || ((NB == 2 || NB == 4) && (QB == 2 || QB == 4)), "the split is spread over the blocks");
+    uint32_t f1[XG][PAIRS][2], f2[XG][PAIRS][2];
 #pragma unroll
     for (int a = 0; a < NB; ++a) {
       bf16x8 wa[WP];
@@ -261,21 +324,51 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
           v = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[0], xb[b][0], v, 0, 0, 0);
         }
         acc[a][b] = v;
+        if constexpr (XF) {
+          // a quarter (QB = 4) or a half (QB = 2) of the split of this node block's share of the
+          // elements; the scheduler may not move vector instructions or MFMAs past this point, so
+          // the split's instructions stay in the shadow of the MFMAs around them
+          constexpr int SPB = 4 / QB;      // stages per query block
+#pragma unroll
+          for (int st = b * SPB; st < (b + 1) * SPB; ++st)
+#pragma unroll
+            for (int g = 0; g < XG; ++g)
+#pragma unroll
+              for (int jj = 0; jj < PAIRS; ++jj) {
+                const int j = a * PAIRS + jj;      // elements 2 j, 2 j + 1 of the group of eight
+                const uint32_t x0 = RX[2 * g + (j >> 1)][(2 * j) & 3], x1 = RX[2 * g + (j >> 1)][(2 * j + 1) & 3];
+                uint32_t(&t1)[2] = f1[g][jj];
+                uint32_t(&t2)[2] = f2[g][jj];
+                if (st == 0) {
+                  t1[0] = __float_as_uint(__uint_as_float(x0) - __uint_as_float(x0 & 0xFFFF0000u));   // exact
+                  t1[1] = __float_as_uint(__uint_as_float(x1) - __uint_as_float(x1 & 0xFFFF0000u));
+                } else if (st == 1) {
+                  t2[0] = __float_as_uint(__uint_as_float(t1[0]) - __uint_as_float(t1[0] & 0xFFFF0000u));   // exact
+                  t2[1] = __float_as_uint(__uint_as_float(t1[1]) - __uint_as_float(t1[1] & 0xFFFF0000u));
+                } else if (st == 2) {
+                  sp[g][0][j] = (x0 >> 16) | (x1 & 0xFFFF0000u);
+                  sp[g][1][j] = (t1[0] >> 16) | (t1[1] & 0xFFFF0000u);
+                } else {
+                  sp[g][2][j] = (t2[0] >> 16) | (t2[1] & 0xFFFF0000u);
+                }
+              }
+          __builtin_amdgcn_sched_barrier(0x0004 | 0x0010 | 0x0080);   // scalar, memory and LDS instructions may cross
+        }
       }
     }
   };
   int c = 0;
   for (; c + 2 <= nchunks; c += 2) {       // chunks c (buffer 0) and c + 1 (buffer 1)
-    multiply(0);
-    SLONN_TILES_STORE(1, r1x, r1w);        // chunk c + 1
+    multiply(0, r1x);
+    SLONN_TILES_STORE(1, r1x, r1w, sp);    // chunk c + 1
     SLONN_TILES_LOAD(r1x, r1w, c + 3);
     lds_only_barrier();
-    multiply(1);
-    SLONN_TILES_STORE(0, r0x, r0w);        // chunk c + 2
+    multiply(1, r0x);
+    SLONN_TILES_STORE(0, r0x, r0w, sp);    // chunk c + 2
     SLONN_TILES_LOAD(r0x, r0w, c + 4);
     lds_only_barrier();
   }
-  if (c < nchunks) multiply(0);            // an odd number of chunks
+  if (c < nchunks) multiply(0, r1x);       // an odd number of chunks
 #undef SLONN_TILES_LOAD
 #undef SLONN_TILES_STORE
 
@@ -324,6 +417,57 @@ int launch_split3(const float* X, int64_t ldx, int64_t rows, int d, uint16_t* ou
   return SLONN_OK;
 }
 
+namespace {
+
+// The tile shape for a batch and a layer, and the launch.  X3 == nullptr: the kernel splits the
+// fp32 activations X itself.
+template <int TQ_, int TN_, int WP_, int NT_>
+int launch_tiles_shape(const uint16_t* X3, const float* X, int ldx, const uint16_t* Wp, const float* bias,
+                       const uint32_t* mask, const int32_t* flags, float* Y, int ldy, int B, int n, int d, int a,
+                       hipStream_t s) {
+  constexpr size_t lds = tiles_lds_bytes<TQ_, TN_, WP_>();
+  static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");
+  const dim3 grid((n + TN_ - 1) / TN_, (B + TQ_ - 1) / TQ_);
+  if (X3) {
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, TN_, WP_, NT_, false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, TN_, WP_, NT_, false>), grid, dim3(NT_), lds, s, X3, X, ldx, Wp, bias,
+                       mask, flags, Y, ldy, B, n, d, a);
+  } else {
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, TN_, WP_, NT_, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, TN_, WP_, NT_, true>), grid, dim3(NT_), lds, s, X3, X, ldx, Wp, bias,
+                       mask, flags, Y, ldy, B, n, d, a);
+  }
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
+int launch_tiles(const uint16_t* X3, const float* X, int ldx, const uint16_t* Wp, int w_parts, const float* bias,
+                 const uint32_t* mask, const int32_t* flags, float* Y, int ldy, int B, int n, int d, int a,
+                 hipStream_t s) {
+  // 128 x 128 tiles with eight wavefronts once they fill the chip (each weight tile is fetched
+  // half as often: C3 batch 1024 190 -> 160 us per layer)
+  const bool big = (long)((B + 127) / 128) * ((n + TN - 1) / TN) >= 256;
+  const bool wide = (long)((B + 127) / 128) * ((n + 255) / 256) >= 256;
+  if (w_parts == 3) {
+    // below that 64 x 64 tiles with four wavefronts: four times as many workgroups (C3 tiles per
+    // step, 64 x 128 against 64 x 64: batch 256 348 -> 213 us, batch 512 351 -> 340, batch 768
+    // 508 -> 456; at batch 1024 the 128 x 128 tiles take 458 us, 64 x 64 tiles 596)
+    if (big) return launch_tiles_shape<128, 128, 3, 512>(X3, X, ldx, Wp, bias, mask, flags, Y, ldy, B, n, d, a, s);
+    return launch_tiles_shape<64, 64, 3, 256>(X3, X, ldx, Wp, bias, mask, flags, Y, ldy, B, n, d, a, s);
+  }
+  // one weight part: twice the node strip per wavefront keeps the LDS reads per MFMA down
+  if (wide) return launch_tiles_shape<128, 256, 1, 512>(X3, X, ldx, Wp, bias, mask, flags, Y, ldy, B, n, d, a, s);
+  if (big) return launch_tiles_shape<128, 128, 1, 512>(X3, X, ldx, Wp, bias, mask, flags, Y, ldy, B, n, d, a, s);
+  return launch_tiles_shape<64, 128, 1, 256>(X3, X, ldx, Wp, bias, mask, flags, Y, ldy, B, n, d, a, s);
+}
+
+// fp32 rows the tile kernel can fetch in 16-byte pieces
+bool rows_aligned(const float* X, int ldx) { return ldx % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0; }
+
+}  // namespace
+
 int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx,
                         const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d,
                         int n, int act, const TilesReuse* reuse, int min_keep_permille, void* scratch,
@@ -334,7 +478,10 @@ int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, cons
   const size_t flag_bytes = ((size_t)(B / 16 + TM / 16 + 1) * 4 + 255) / 256 * 256;
   uint32_t* mask = static_cast<uint32_t*>(scratch);
   int32_t* flags = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + mask_bytes);
-  uint16_t* X3 = reinterpret_cast<uint16_t*>(static_cast<char*>(scratch) + mask_bytes + flag_bytes);
+  // (activations the kernel cannot fetch in 16-byte pieces are split into a copy first)
+  uint16_t* X3 = rows_aligned(X, ldx)
+                     ? nullptr
+                     : reinterpret_cast<uint16_t*>(static_cast<char*>(scratch) + mask_bytes + flag_bytes);
   *flags_out = flags;
   {
     ProfScope prof_(SLONN_PROF_SELECT, s);
@@ -346,66 +493,23 @@ int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, cons
   }
   ProfScope prof_(SLONN_PROF_TILES, s);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
-  // 128 x 128 tiles with eight wavefronts once they fill the chip (each weight tile is fetched
-  // half as often: C3 batch 1024 190 -> 160 us per layer)
-  const bool big = (long)((B + 127) / 128) * ((n + TN - 1) / TN) >= 256;
-  const bool wide = (long)((B + 127) / 128) * ((n + 255) / 256) >= 256;
-#define SLONN_LAUNCH_TILES(TQ_, TN_, WP_, NT_)                                                                        \
-  {                                                                                                             \
-    constexpr size_t lds = tiles_lds_bytes<TQ_, TN_, WP_>();                                                         \
-    static_assert(lds <= 160 * 1024, "two tile buffers must fit the LDS of a compute unit");                   \
-    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, TN_, WP_, NT_>),            \
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                       \
-    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, TN_, WP_, NT_>), dim3((n + TN_ - 1) / TN_, (B + TQ_ - 1) / TQ_),      \
-                       dim3(NT_), lds, s, X3, Wp, bias, mask, flags, Y, ldy, B, n, d, a);                       \
-  }
-  if (w_parts == 3) {
-    // below that 64 x 64 tiles with four wavefronts: four times as many workgroups (C3 tiles per
-    // step, 64 x 128 against 64 x 64: batch 256 348 -> 213 us, batch 512 351 -> 340, batch 768
-    // 508 -> 456; at batch 1024 the 128 x 128 tiles take 458 us, 64 x 64 tiles 596)
-    if (big) SLONN_LAUNCH_TILES(128, 128, 3, 512) else SLONN_LAUNCH_TILES(64, 64, 3, 256)
-  } else {
-    // one weight part: twice the node strip per wavefront keeps the LDS reads per MFMA down
-    if (wide) SLONN_LAUNCH_TILES(128, 256, 1, 512) else if (big) SLONN_LAUNCH_TILES(128, 128, 1, 512)
-    else SLONN_LAUNCH_TILES(64, 128, 1, 256)
-  }
-#undef SLONN_LAUNCH_TILES
-  SLONN_HIP(hipGetLastError());
-  return SLONN_OK;
+  return launch_tiles(X3, X, ldx, Wp, w_parts, bias, mask, flags, Y, ldy, B, n, d, a, s);
 }
 
 // A layer computed in full for a large batch through the same tiles (no mask, every query
 // served): bf16 weights as they are (w_parts 1) or fp32 weights in three parts (w_parts 3).
-// scratch: 3 * B * d * 2 bytes for the split activations.
+// scratch: 3 * B * d * 2 bytes (used for a three-part copy of activations that are not 16-byte aligned).
 int launch_dense_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx, float* Y,
                        int ldy, int B, int d, int n, int act, void* scratch, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_DENSE, s);
-  uint16_t* X3 = static_cast<uint16_t*>(scratch);
-  int rc = launch_split3(X, ldx, B, d, X3, s);
-  if (rc) return rc;
+  uint16_t* X3 = nullptr;
+  if (!rows_aligned(X, ldx)) {
+    X3 = static_cast<uint16_t*>(scratch);
+    const int rc = launch_split3(X, ldx, B, d, X3, s);
+    if (rc) return rc;
+  }
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
-  const uint32_t* mask = nullptr;
-  const int32_t* flags = nullptr;
-  const bool big = (long)((B + 127) / 128) * ((n + TN - 1) / TN) >= 256;
-  const bool wide = (long)((B + 127) / 128) * ((n + 255) / 256) >= 256;
-#define SLONN_LAUNCH_TILES(TQ_, TN_, WP_, NT_)                                                                        \
-  {                                                                                                             \
-    constexpr size_t lds = tiles_lds_bytes<TQ_, TN_, WP_>();                                                         \
-    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(masked_tiles_kernel<TQ_, TN_, WP_, NT_>),            \
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                       \
-    hipLaunchKernelGGL((masked_tiles_kernel<TQ_, TN_, WP_, NT_>), dim3((n + TN_ - 1) / TN_, (B + TQ_ - 1) / TQ_),      \
-                       dim3(NT_), lds, s, X3, Wp, bias, mask, flags, Y, ldy, B, n, d, a);                       \
-  }
-  if (w_parts == 3) {
-    if (big) SLONN_LAUNCH_TILES(128, 128, 3, 512) else SLONN_LAUNCH_TILES(64, 64, 3, 256)
-  } else {
-    // one weight part: twice the node strip per wavefront keeps the LDS reads per MFMA down
-    if (wide) SLONN_LAUNCH_TILES(128, 256, 1, 512) else if (big) SLONN_LAUNCH_TILES(128, 128, 1, 512)
-    else SLONN_LAUNCH_TILES(64, 128, 1, 256)
-  }
-#undef SLONN_LAUNCH_TILES
-  SLONN_HIP(hipGetLastError());
-  return SLONN_OK;
+  return launch_tiles(X3, X, ldx, Wp, w_parts, bias, nullptr, nullptr, Y, ldy, B, n, d, a, s);
 }
 
 }  // namespace slonn
