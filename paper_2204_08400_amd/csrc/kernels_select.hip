@@ -126,6 +126,33 @@ __device__ __forceinline__ bool tile_served(const RowBlocking& rb, const float* 
   return sum >= rb.served_min_per_query * nq;
 }
 
+// What the tile kernel reads about query q (RowBlocking::mask): for a query of a served tile one
+// bit per node of its finished list out[0 .. total) (all: the whole layer), and from the tile's
+// first query the tile's decision for each of its eight groups of 16 queries.  bits: (n + 31) / 32
+// free words of LDS.  Whole workgroup.
+template <int NT>
+__device__ __forceinline__ void write_pair_mask(const RowBlocking& rb, int q, bool served, const int32_t* out,
+                                                int total, int n, bool all, uint32_t* bits) {
+  const int tid = threadIdx.x, words = (n + 31) >> 5;
+  if (q % 128 == 0 && tid < 8) rb.flags[q / 16 + tid] = served ? 1 : 0;
+  if (!served) return;
+  uint32_t* row = rb.mask + (size_t)q * words;
+  if (all) {
+    for (int i = tid; i < words; i += NT)
+      row[i] = (i == words - 1 && (n & 31)) ? ((1u << (n & 31)) - 1u) : 0xFFFFFFFFu;
+    return;
+  }
+  __syncthreads();        // the list is complete, the LDS words are free
+  for (int i = tid; i < words; i += NT) bits[i] = 0u;
+  __syncthreads();
+  for (int t = tid; t < total; t += NT) {
+    const int node = out[t];
+    atomicOr(&bits[node >> 5], 1u << (node & 31));
+  }
+  __syncthreads();
+  for (int i = tid; i < words; i += NT) row[i] = bits[i];
+}
+
 // A medium batch leaves the hash projection's reduction split in hs.S partial sums per
 // (query, hash row).  Add them in split order, add the bias, and store the projections of
 // query q for this kernel and for the later readers.  Whole workgroup; ends with a barrier.
@@ -180,8 +207,9 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += NT) out[i] = i;
-    if (rb.part_idx && !tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
-      partition_rows<NT>(out, n, rb, q, z, sh.prio);
+    const bool served = tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
+    if (rb.mask) write_pair_mask<NT>(rb, q, served, out, n, n, true, sh.prio);
+    if (rb.part_idx && !served) partition_rows<NT>(out, n, rb, q, z, sh.prio);
     return;
   }
   // The last wavefront forms the keys and fetches the bucket directory (two dependent memory
@@ -200,8 +228,9 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
   __syncthreads();
   select_merge<NT, MU, IdT>(L, n, total - H, ids, global_rank, sh, out + H, hskip);
 
-  if (rb.part_idx && !tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
-    partition_rows<NT>(out, total, rb, q, z, sh.prio);
+  const bool served = tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
+  if (rb.mask) write_pair_mask<NT>(rb, q, served, out, total, n, false, sh.prio);
+  if (rb.part_idx && !served) partition_rows<NT>(out, total, rb, q, z, sh.prio);
 }
 
 template <typename IdT>
@@ -242,8 +271,9 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += SEL_NT) out[i] = i;
-    if (rb.part_idx && !tile_served<SEL_NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
-      partition_rows<SEL_NT>(out, n, rb, q, z, sh.tval);
+    const bool served = tile_served<SEL_NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
+    if (rb.mask) write_pair_mask<SEL_NT>(rb, q, served, out, n, n, true, sh.taken);
+    if (rb.part_idx && !served) partition_rows<SEL_NT>(out, n, rb, q, z, sh.tval);
     return;
   }
   for (int i = tid; i < words; i += SEL_NT) sh.taken[i] = 0u;
@@ -252,8 +282,9 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   __syncthreads();
   select_block_wide<SEL_NT, WIDE_MU, IdT>(z, K, L, n, total - H, dir, ids, global_rank, sh,
                             codes ? codes + (size_t)q * L : nullptr, out + H, H ? hf.hslot : nullptr);
-  if (rb.part_idx && !tile_served<SEL_NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt)))
-    partition_rows<SEL_NT>(out, total, rb, q, z, sh.tval);
+  const bool served = tile_served<SEL_NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
+  if (rb.mask) write_pair_mask<SEL_NT>(rb, q, served, out, total, n, false, sh.taken);
+  if (rb.part_idx && !served) partition_rows<SEL_NT>(out, total, rb, q, z, sh.tval);
 }
 
 // Queries in descending order of their budget (256 classes of the keep fraction; the order inside

@@ -58,15 +58,14 @@ __global__ void split3_kernel(const float* __restrict__ X, int64_t ldx, int d, u
 // list at least min_per_query (query, node) pairs per query of the tile together (the last tile
 // of a batch may hold fewer than 128 queries; every workgroup adds up its tile's list
 // lengths itself); flags holds that decision once per 16 queries, the unit the per-query gather
-// skips by.  For a served query: mask[q][w] bit j = node 32 w + j is in the query's list and is
-// not a hash node (skip_hslot entry >= 0: its output is its projection, written here from Z when
-// Z is given, else already written by the caller), and X3 row q = the activations in three
-// bf16 parts.
+// skips by.  For a served query: mask[q][w] bit j = node 32 w + j is in the query's list (a
+// selected hash node too: inside a tile its pair costs nothing extra, so its projection is not
+// reused there), and, where X3 is given, X3 row q = the activations in three bf16 parts.  The
+// select kernel writes the same masks and flags itself when it is told to (RowBlocking::mask);
+// this kernel serves the callers that did not, or whose activations need the three-part copy.
 __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restrict__ active,
                                                        const int32_t* __restrict__ cnt, int idx_stride, int B,
-                                                       int n, const int16_t* __restrict__ skip_hslot,
-                                                       const float* __restrict__ Z, int H, int relu,
-                                                       float* __restrict__ Y, int ldy,
+                                                       int n,
                                                        uint32_t* __restrict__ mask, int32_t* __restrict__ flags,
                                                        long long min_per_query, const float* __restrict__ X, int ldx,
                                                        int d, uint16_t* __restrict__ X3) {
@@ -90,17 +89,6 @@ __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restric
   const int32_t* list = active + (size_t)q * idx_stride;
   for (int t = tid; t < c; t += 256) {
     const int node = list[t];
-    if (skip_hslot) {
-      const int hs = skip_hslot[node];
-      if (hs >= 0) {                     // a selected hash node: its output is its projection
-        if (Z) {
-          float v = Z[(size_t)q * H + hs];
-          if (relu && !(v > 0.0f)) v = 0.0f;
-          Y[(size_t)q * ldy + node] = v;
-        }
-        continue;
-      }
-    }
     atomicOr(&bits[node >> 5], 1u << (node & 31));
   }
   // eight elements per thread: two 16-byte loads, three 16-byte stores (d is a multiple of 32);
@@ -468,27 +456,34 @@ bool rows_aligned(const float* X, int ldx) { return ldx % 4 == 0 && reinterpret_
 
 }  // namespace
 
+void masked_tiles_buffers(void* scratch, int B, int n, uint32_t** mask, int32_t** flags) {
+  const size_t mask_bytes = ((size_t)B * ((n + 31) / 32) * 4 + 255) / 256 * 256;
+  *mask = static_cast<uint32_t*>(scratch);
+  *flags = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + mask_bytes);
+}
+
+// mask_ready: the select kernel has written the masks and flags already (same threshold)
 int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx,
                         const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d,
-                        int n, int act, const TilesReuse* reuse, int min_keep_permille, void* scratch,
+                        int n, int act, bool mask_ready, int min_keep_permille, void* scratch,
                         int32_t** flags_out, hipStream_t s) {
-  const TilesReuse ru = reuse ? *reuse : TilesReuse{};
   const int words = (n + 31) / 32;
   const size_t mask_bytes = ((size_t)B * words * 4 + 255) / 256 * 256;
   const size_t flag_bytes = ((size_t)(B / 16 + TM / 16 + 1) * 4 + 255) / 256 * 256;
-  uint32_t* mask = static_cast<uint32_t*>(scratch);
-  int32_t* flags = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + mask_bytes);
+  uint32_t* mask = nullptr;
+  int32_t* flags = nullptr;
+  masked_tiles_buffers(scratch, B, n, &mask, &flags);
   // (activations the kernel cannot fetch in 16-byte pieces are split into a copy first)
   uint16_t* X3 = rows_aligned(X, ldx)
                      ? nullptr
                      : reinterpret_cast<uint16_t*>(static_cast<char*>(scratch) + mask_bytes + flag_bytes);
   *flags_out = flags;
-  {
+  if (!mask_ready || X3) {
     ProfScope prof_(SLONN_PROF_SELECT, s);
     // the tile kernel serves 128 queries when they list at least this many pairs together
     const long long min_per_query = (long long)n * min_keep_permille / 1000;
     hipLaunchKernelGGL(pair_mask_kernel, dim3(B), dim3(256), (size_t)words * 4, s, active, cnt, idx_stride, B, n,
-                       ru.hslot, ru.Z, ru.H, ru.relu, Y, ldy, mask, flags, min_per_query, X, ldx, d, X3);
+                       mask, flags, min_per_query, X, ldx, d, X3);
     SLONN_HIP(hipGetLastError());
   }
   ProfScope prof_(SLONN_PROF_TILES, s);

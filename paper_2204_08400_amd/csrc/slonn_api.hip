@@ -893,9 +893,15 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);   // workgroups of the tile kernel
       const bool f32_tiles = rb.part_idx && L.W3 && B >= 160 && mtiles >= 64 && out && !(is_last && Y->val) &&
                              m->path_grouped;
-      if (f32_tiles) {
-        rb.served_min_per_query = (long long)L.d_out * masked_tiles_min_keep_permille(B) / 1000;
+      // (bf16-weight layers: tiles of 128 queries with large budgets go to the masked tiles, the others
+      // to the unions of 16)
+      const bool bf16_tiles = all_grouped && mtiles >= 128 && masked_tiles_supported(L.d_in, L.d_out, m->max_lds_bytes);
+      if ((f32_tiles || bf16_tiles) && w.tiles) {
+        // the select kernel decides per tile like the tile launcher would and writes the pair masks
+        const int permille = f32_tiles ? masked_tiles_min_keep_permille(B) : BF16_TILES_MIN_KEEP_PERMILLE;
+        rb.served_min_per_query = (long long)L.d_out * permille / 1000;
         rb.B = B;
+        masked_tiles_buffers(w.tiles, B, L.d_out, &rb.mask, &rb.flags);
       }
       HashFirst hf;
       if (m->hash_first) { hf.hnodes = L.hnodes; hf.hslot = L.hslot; }
@@ -912,7 +918,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       }
       rc = launch_select(z, L.K, L.L, L.d_out, ts->d_dir, ts->d_ids, ts->narrow, ts->d_global_rank,
                          keep + (size_t)l * keep_lstride, keep_qstride, B, codes, aidx, acnt, astride, out,
-                         ldo, m->max_lds_bytes, rb.part_idx ? &rb : nullptr, m->hash_first ? &hf : nullptr,
+                         ldo, m->max_lds_bytes, (rb.part_idx || rb.mask) ? &rb : nullptr, m->hash_first ? &hf : nullptr,
                          split.part ? &split : nullptr, order, s);
       if (rc) return rc;
       act_list = aidx; act_cnt = acnt; act_stride = astride;
@@ -922,14 +928,11 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         reuse.hslot = L.hslot; reuse.Z = z; reuse.H = L.H(); reuse.relu = act == SLONN_ACT_RELU;
         // tiles of 128 queries with large budgets: masked dense tiles; the others: unions of 16
         const int32_t* served = nullptr;
-        const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);
-        if (mtiles >= 128 && masked_tiles_supported(L.d_in, L.d_out, m->max_lds_bytes)) {
-          TilesReuse tr;
-          tr.hslot = L.hslot; tr.Z = z; tr.H = L.H(); tr.relu = reuse.relu;
+        if (bf16_tiles) {
           int32_t* tflags = nullptr;
           rc = launch_masked_tiles(static_cast<const uint16_t*>(L.W), 1, L.bias, cur, ldcur, aidx, acnt, astride, out,
-                                   ldo, B, L.d_in, L.d_out, act, &tr, BF16_TILES_MIN_KEEP_PERMILLE, w.tiles, &tflags,
-                                   s);
+                                   ldo, B, L.d_in, L.d_out, act, rb.mask != nullptr, BF16_TILES_MIN_KEEP_PERMILLE,
+                                   w.tiles, &tflags, s);
           if (rc) return rc;
           served = tflags;
         }
@@ -941,13 +944,11 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         // on the matrix cores (decided per group on the device); the rest is gathered per query.
         const int32_t* gflag = nullptr;
         if (f32_tiles) {
-          // masked tiles on the bf16 matrix cores; a selected hash node of a served query takes its
-          // output from its projection there (the regrouping step does that for the others)
+          // masked tiles on the bf16 matrix cores (a selected hash node of a served query is computed
+          // there like any other pair; the regrouping step reuses the projections for the others)
           int32_t* flags = nullptr;
-          TilesReuse tr;
-          tr.hslot = rb.hslot; tr.Z = z; tr.H = L.H(); tr.relu = rb.relu;
           rc = launch_masked_tiles(L.W3, 3, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B, L.d_in, L.d_out,
-                                   act, &tr, masked_tiles_min_keep_permille(B), w.tiles, &flags, s);
+                                   act, rb.mask != nullptr, masked_tiles_min_keep_permille(B), w.tiles, &flags, s);
           if (rc) return rc;
           gflag = flags;
         } else if (gtiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {

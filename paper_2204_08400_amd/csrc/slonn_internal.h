@@ -189,6 +189,11 @@ struct RowBlocking {
   // of such a tile are not regrouped.  B: the batch (the last tile may be short).
   long long served_min_per_query = 0;
   int B = 0;
+  // mask != nullptr: the select kernel itself writes what the tile kernel reads -- for a query of
+  // a served tile one bit per node of its list (mask[q][(n + 31) / 32]), and per tile the decision
+  // (flags[q / 16 .. + 7] for the tile's first query q) -- so that no pass over the lists follows.
+  uint32_t* mask = nullptr;
+  int32_t* flags = nullptr;
 };
 constexpr int MAX_ROW_BLOCKS = 1024;
 
@@ -322,19 +327,16 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
 // where they did (mean list at least min_keep_permille / 1000 of the layer).  reuse (nullable):
 // nodes with an hslot entry >= 0 are left out; with Z their outputs act(Z) are written for the
 // served queries.  scratch: masked_tiles_workspace_bytes(B, n, d) bytes.
-struct TilesReuse {
-  const int16_t* hslot = nullptr;
-  const float* Z = nullptr;      // [B][H] projections
-  int H = 0, relu = 0;
-};
 bool masked_tiles_supported(int d, int n, int max_lds);
 size_t masked_tiles_workspace_bytes(int B, int n, int d);
+// where in that scratch the pair masks [B][(n + 31) / 32] and the per-16-queries flags live
+void masked_tiles_buffers(void* scratch, int B, int n, uint32_t** mask, int32_t** flags);
 int launch_split3(const float* X, int64_t ldx, int64_t rows, int d, uint16_t* out, hipStream_t s);
 int launch_dense_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx, float* Y,
                        int ldy, int B, int d, int n, int act, void* scratch, hipStream_t s);
 int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx,
                         const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d,
-                        int n, int act, const TilesReuse* reuse, int min_keep_permille, void* scratch,
+                        int n, int act, bool mask_ready, int min_keep_permille, void* scratch,
                         int32_t** flags_out, hipStream_t s);
 
 // y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).
