@@ -245,19 +245,27 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
   };
 
   // chunk c is multiplied out of buffer (c - c_begin) % 2 while chunk c + 1 moves from registers into
-  // the other buffer and chunk c + 2 is on its way from L2; one LDS-only barrier per chunk
+  // the other buffer and chunks c + 2 and c + 3 are on their way from L2 or HBM (two register sets: a
+  // load has two chunks' worth of MFMAs to arrive); one LDS-only barrier per chunk
   if (c_begin < c_end) {
+    u32x4 r1[PER];
     SLONN_HASH_LOAD(r0, c_begin);
+    SLONN_HASH_LOAD(r1, c_begin + 1);
     SLONN_HASH_STORE(0, r0);
-    SLONN_HASH_LOAD(r0, c_begin + 1);
+    SLONN_HASH_LOAD(r0, c_begin + 2);
     lds_only_barrier();
-    for (int c = c_begin; c < c_end; ++c) {
-      const int cur = (c - c_begin) & 1;
-      multiply(cur);
-      SLONN_HASH_STORE(cur ^ 1, r0);
-      SLONN_HASH_LOAD(r0, c + 2);
+    int c = c_begin;
+    for (; c + 2 <= c_end; c += 2) {
+      multiply(0);
+      SLONN_HASH_STORE(1, r1);             // chunk c + 1
+      SLONN_HASH_LOAD(r1, c + 3);
+      lds_only_barrier();
+      multiply(1);
+      SLONN_HASH_STORE(0, r0);             // chunk c + 2
+      SLONN_HASH_LOAD(r0, c + 4);
       lds_only_barrier();
     }
+    if (c < c_end) multiply(0);            // an odd number of chunks
   }
 #undef SLONN_HASH_LOAD
 #undef SLONN_HASH_STORE
