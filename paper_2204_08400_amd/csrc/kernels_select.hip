@@ -172,8 +172,12 @@ __device__ __forceinline__ void sum_split_projections(const HashSplit& hs, int q
 template <int NT>
 struct BlockMU { static constexpr int value = 4096 / NT; };
 
+// (second launch bound: eight wavefronts per SIMD for the 512-thread workgroups of large batches --
+// the kernel waits on memory round trips, and with the 106 scalar registers it would otherwise take
+// only seven fit, i.e. three workgroups per compute unit instead of four.  The other sizes run one
+// workgroup per compute unit or are bound by their vector registers: no point in spilling scalars.)
 template <int NT, typename IdT>
-__global__ __launch_bounds__(NT) void select_block_kernel(
+__global__ __launch_bounds__(NT, NT == 512 ? 8 : 4) void select_block_kernel(
     const float* Z, int K, int L, int n, const uint32_t* __restrict__ dir,
     const IdT* __restrict__ ids, const int32_t* __restrict__ global_rank,
     const float* __restrict__ keep, int keep_stride, uint32_t* __restrict__ codes,
@@ -190,46 +194,53 @@ __global__ __launch_bounds__(NT) void select_block_kernel(
   sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + MU * (NT / 64));
 
   const int q = order ? order[blockIdx.x] : (int)blockIdx.x, tid = threadIdx.x;
-  const int m = budget_of(keep[(size_t)q * keep_stride], n);
+  const float keep_q = keep[(size_t)q * keep_stride];      // on its way while the keys form
   int32_t* out = active + (size_t)q * idx_stride;
   const float* z = Z + (size_t)q * K * L;
   sum_split_projections<NT>(hsp, q, K * L);
+  // The last wavefront forms the keys and fetches the bucket directory (two dependent memory
+  // round trips) right away; the others find the budget, clear the output row and the maps.
+  uint32_t* codes_row = codes ? codes + (size_t)q * L : nullptr;
+  constexpr int NI = NT - 64;          // threads that clear
+  if (tid >= NI) select_keys<NT, MU>(z, K, L, dir, sh, codes_row);
+  const int m = budget_of(keep_q, n);
   float* y = yzero ? yzero + (size_t)q * ldy : nullptr;
   const int H = hf.hnodes ? K * L : 0;          // hash nodes in front of the list (Section 3.4 variant)
   const int total = (m == n || m > H) ? m : H;
+  const int words = (n + 31) >> 5;
   if (tid == 0) cnt[q] = total;
-  if (m == n) {   // the layer is computed in full: ascending ids, no table access
+  if (m == n) {   // the layer is computed in full: ascending ids, no table access (the keys are written as codes)
     if (y)
       for (int i = tid; i < n; i += NT) y[i] = 0.0f;
-    if (codes && tid < L) {
-      uint32_t key = 0;
-      for (int j = 0; j < K; ++j) key |= (z[tid * K + j] > 0.0f ? 1u : 0u) << j;
-      codes[(size_t)q * L + tid] = key;
-    }
     for (int i = tid; i < n; i += NT) out[i] = i;
     const bool served = tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
     if (rb.mask) write_pair_mask<NT>(rb, q, served, out, n, n, true, sh.prio);
     if (rb.part_idx && !served) partition_rows<NT>(out, n, rb, q, z, sh.prio);
     return;
   }
-  // The last wavefront forms the keys and fetches the bucket directory (two dependent memory
-  // round trips) while the others clear the output row and the map.
-  uint32_t* codes_row = codes ? codes + (size_t)q * L : nullptr;
   const int16_t* hskip = H ? hf.hslot : nullptr;
-  constexpr int NI = NT - 64;          // threads that clear
-  if (tid >= NI) {
-    select_keys<NT, MU>(z, K, L, dir, sh, codes_row);
-  } else {
+  // (with pair masks asked for, the merge sets one bit per chosen node as it goes)
+  sh.bits = rb.mask ? sh.s_misc + 4 : nullptr;
+  if (tid < NI) {
     if (y)
       for (int i = tid; i < n; i += NI) y[i] = 0.0f;
     for (int i = tid; i < n; i += NI) sh.prio[i] = 0xFFFFFFFFu;
+    if (sh.bits)
+      for (int i = tid; i < words; i += NI) sh.bits[i] = 0u;
     for (int h = tid; h < H; h += NI) out[h] = hf.hnodes[h];
   }
+  // (the tile's decision while the keys are on their way; its barriers also end the clearing)
+  const bool served = tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
   __syncthreads();
+  if (sh.bits)
+    for (int h = tid; h < H; h += NT) atomicOr(&sh.bits[hf.hnodes[h] >> 5], 1u << (hf.hnodes[h] & 31));
   select_merge<NT, MU, IdT>(L, n, total - H, ids, global_rank, sh, out + H, hskip);
 
-  const bool served = tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
-  if (rb.mask) write_pair_mask<NT>(rb, q, served, out, total, n, false, sh.prio);
+  if (rb.mask) {      // (select_merge ends with a barrier: every bit is set)
+    if (q % 128 == 0 && tid < 8) rb.flags[q / 16 + tid] = served ? 1 : 0;
+    if (served)
+      for (int i = tid; i < words; i += NT) rb.mask[(size_t)q * words + i] = sh.bits[i];
+  }
   if (rb.part_idx && !served) partition_rows<NT>(out, total, rb, q, z, sh.prio);
 }
 
@@ -337,9 +348,11 @@ int launch_select_t(const float* Z, int K, int L, int n, const uint32_t* dir, co
                     uint32_t* codes, int32_t* active, int32_t* cnt, int idx_stride, float* yzero,
                     int ldy, int max_lds, const RowBlocking* rb, const HashFirst& hf, const HashSplit& hsp,
                     const int32_t* order, hipStream_t s) {
-  const size_t lds_block = ((size_t)n + SelectShared<SEL_NT, BlockMU<SEL_NT>::value>::words_besides_prio) * 4;
+  const RowBlocking rbv = rb ? *rb : RowBlocking{};
+  // (one more bit per node where the kernel also writes the tile kernel's pair masks)
+  const size_t lds_block = ((size_t)n + SelectShared<SEL_NT, BlockMU<SEL_NT>::value>::words_besides_prio +
+                            (rbv.mask ? (size_t)(n + 31) / 32 : 0)) * 4;
   if (lds_block <= (size_t)max_lds) {
-    const RowBlocking rbv = rb ? *rb : RowBlocking{};
     if (B <= SEL_BIG_MAX_BATCH) {
       if (lds_block > 65536)
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG, IdT>),

@@ -25,6 +25,7 @@ struct SelectShared {            // LDS regions the caller carves out
   uint32_t* s_len;               // [64] list lengths
   int* wave_cnt;                 // [MU * NT/64], the first NT/64 in use
   uint32_t* s_misc;              // [4]
+  uint32_t* bits = nullptr;      // [(n + 31) / 32] optional: one bit per chosen node (select_merge)
   static constexpr int words_besides_prio = 64 + 64 + MU * (NT / 64) + 4;
 };
 
@@ -52,12 +53,21 @@ __device__ __forceinline__ void select_keys(const float* z, int K, int L_, const
   if (lane == 0) sh.s_misc[0] = len;
 }
 
+// Barrier that orders LDS traffic only: global loads issued before it stay in flight across it
+// (__syncthreads would wait for them as well).
+__device__ __forceinline__ void select_lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // The merge, by the whole workgroup, after select_keys and a barrier.  prio[0..n) must hold
 // 0xFFFFFFFF and be visible to all threads.  On return (all threads, after a barrier)
 // out[0..m) holds the chosen ids in selection order.  0 <= m < n.
 // hskip (nullable, LDS or global, [n]): nodes with an entry >= 0 are passed over wherever
 // they turn up (the variant of Section 3.4 in which hash nodes are computed anyway and the
 // Node Activator never selects them); the caller keeps m <= n minus their number.
+// sh.bits (nullable, LDS, zeroed by the caller): receives one bit per chosen node.
 // IdT: the type the lists are stored in (uint16_t for layers of up to 65 536 nodes, else int32_t)
 template <int NT, int MU = SELECT_MU, typename IdT = int32_t>
 __device__ __forceinline__ void select_merge(int L_, int n, int m, const IdT* __restrict__ ids,
@@ -74,6 +84,8 @@ __device__ __forceinline__ void select_merge(int L_, int n, int m, const IdT* __
   // A thread takes `per` consecutive slots (consecutive tables of one rank), so that positions
   // in slot order follow from one count per thread, and the lanes of a wavefront that read
   // the same table read consecutive ranks of it.
+  // (Asking for the ids of round r + 1 before round r is worked through was tried: a query that
+  // ends with round r has asked in vain, and most do -- slower on every workload.)
   const uint32_t L = (uint32_t)L_;
   const uint32_t nslots = sh.s_misc[0] * L;            // <= n * 64 < 2^32
   int per = (12 * m + NT - 1) / NT;
@@ -82,35 +94,43 @@ __device__ __forceinline__ void select_merge(int L_, int n, int m, const IdT* __
   // slot / L without a division per thread: the round's first slot is divided once, the offset
   // inside the round (below 16384) by multiplication with ceil(2^20 / L)
   static_assert(MU * NT + 64 <= 16384, "round too large for the multiplicative division");
-  static_assert(MU <= 32, "a thread's first occurrences are kept in a 32-bit mask");
+  static_assert(MU <= 32, "a thread's slots of a round are kept in 32-bit masks");
   const uint32_t magic = ((1u << 20) + L - 1) / L;
-  for (uint32_t base = 0; base < nslots && count < m; base += NT * per) {
+  // this thread's slots of the round that starts at slot `base`: ids requested, mask of the slots that exist
+  auto request = [&](uint32_t base, int (&node)[MU]) -> uint32_t {
+    uint32_t have = 0;
+    if (base >= nslots) return have;
     const uint32_t r_base = base / L, rem_base = base - r_base * L;
     const uint32_t slot0 = base + tid * per;
     const uint32_t off = rem_base + tid * per;
     const uint32_t dr = (uint32_t)(((unsigned long long)off * magic) >> 20);
     uint32_t r = r_base + dr, b = off - dr * L;
-    int node[MU];
-    bool valid[MU];
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
-      valid[u] = u < per && slot0 + u < nslots && r < sh.s_len[b];
-      node[u] = valid[u] ? (int)ids[sh.s_off[b] + r] : -1;
+      const bool v = u < per && slot0 + u < nslots && r < sh.s_len[b];
+      node[u] = v ? (int)ids[sh.s_off[b] + r] : -1;
+      have |= (v ? 1u : 0u) << u;
       if (++b == L) { b = 0; ++r; }
     }
+    return have;
+  };
+  int node[MU];
+  for (uint32_t base = 0; base < nslots && count < m; base += NT * per) {
+    const uint32_t slot0 = base + tid * per;
+    uint32_t valid = request(base, node);
     if (hskip) {
 #pragma unroll
       for (int u = 0; u < MU; ++u)
-        if (valid[u] && hskip[node[u]] >= 0) valid[u] = false;
+        if (((valid >> u) & 1u) && hskip[node[u]] >= 0) valid &= ~(1u << u);
     }
 #pragma unroll
     for (int u = 0; u < MU; ++u)
-      if (valid[u]) atomicMin(&sh.prio[node[u]], slot0 + u);
-    __syncthreads();
+      if ((valid >> u) & 1u) atomicMin(&sh.prio[node[u]], slot0 + u);
+    select_lds_barrier();
     uint32_t firsts = 0;
 #pragma unroll
     for (int u = 0; u < MU; ++u)
-      if (valid[u] && sh.prio[node[u]] == slot0 + u) firsts |= 1u << u;
+      if (((valid >> u) & 1u) && sh.prio[node[u]] == slot0 + u) firsts |= 1u << u;
     // first occurrences in the lanes below this one and in the wavefront, from one ballot per
     // bit of the thread's count
     const int mine = __popc(firsts);
@@ -122,7 +142,7 @@ __device__ __forceinline__ void select_merge(int L_, int n, int m, const IdT* __
       in_wave += __popcll(has) << bit;
     }
     if (lane == 0) sh.wave_cnt[wave] = in_wave;
-    __syncthreads();
+    select_lds_barrier();
     // (the next write of wave_cnt comes after the next round's first barrier: no barrier here)
     int total = 0;
 #pragma unroll
@@ -135,21 +155,24 @@ __device__ __forceinline__ void select_merge(int L_, int n, int m, const IdT* __
 #pragma unroll
     for (int u = 0; u < MU; ++u) {
       if ((firsts >> u) & 1u) {
-        if (pos < m) out[pos] = node[u];
+        if (pos < m) {
+          out[pos] = node[u];
+          if (sh.bits) atomicOr(&sh.bits[node[u] >> 5], 1u << (node[u] & 31));
+        }
         ++pos;
       }
     }
     count += total;
   }
-  __syncthreads();        // the last round's counts have been read
+  __syncthreads();        // the last round's counts have been read; the list so far is visible
   // the lists ran out: continue down the whole-set ranking (a permutation: no duplicates)
   for (int base = 0; base < n && count < m; base += NT) {
     const int i = base + tid;
-    int node = -1;
+    int cand = -1;
     bool first = false;
     if (i < n) {
-      node = global_rank[i];
-      first = sh.prio[node] == 0xFFFFFFFFu && !(hskip && hskip[node] >= 0);
+      cand = global_rank[i];
+      first = sh.prio[cand] == 0xFFFFFFFFu && !(hskip && hskip[cand] >= 0);
     }
     const unsigned long long votes = __ballot(first);
     if (lane == 0) sh.wave_cnt[wave] = __popcll(votes);
@@ -163,7 +186,10 @@ __device__ __forceinline__ void select_merge(int L_, int n, int m, const IdT* __
     }
     if (first) {
       const int pos = count + before + __popcll(votes & below);
-      if (pos < m) out[pos] = node;
+      if (pos < m) {
+        out[pos] = cand;
+        if (sh.bits) atomicOr(&sh.bits[cand >> 5], 1u << (cand & 31));
+      }
     }
     count += total;
     __syncthreads();
