@@ -55,11 +55,14 @@ constexpr int HPIECES = 4 * DIGITS;  // 16-byte pieces per row and chunk of 64 e
 constexpr int HROW = HPIECES + 1;    // LDS row in pieces (272 bytes: staggers the banks)
 constexpr int BAD_ROW = INT_MIN;   // exponent entry of a row with a non-finite element
 
-// One workgroup per row; a thread holds up to four groups of sixteen consecutive elements in
-// registers (d <= 16384), so the row is read once: maximum, exponent, digits.
+// One workgroup per row; a thread holds up to MAXG groups of sixteen consecutive elements in
+// registers (d <= 4096 MAXG), so the row is read once: maximum, exponent, digits.  (One group for
+// rows of up to 4096 elements: 32 vector registers instead of 78, C3 batch 1024 14.9 -> 10.4 us.
+// Two groups for rows of 8192 were slower than four -- 45.7 against 39.6 us on C5: with eight
+// workgroups per compute unit all 2048 rows load at once and then store at once.)
+template <int MAXG>
 __global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restrict__ X, int64_t ldx, int d,
                                                     int8_t* __restrict__ out, int32_t* __restrict__ expo) {
-  constexpr int MAXG = 4;
   __shared__ float red[4];
   __shared__ int s_e;
   const int64_t row = blockIdx.x;
@@ -421,7 +424,10 @@ size_t hash_int_workspace_bytes(int B, int H, int d) {
 }
 
 int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s) {
-  hipLaunchKernelGGL(slice_digits_kernel, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo);
+  if (d <= 4096)
+    hipLaunchKernelGGL(slice_digits_kernel<1>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo);
+  else
+    hipLaunchKernelGGL(slice_digits_kernel<4>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }
