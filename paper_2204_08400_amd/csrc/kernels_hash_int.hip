@@ -13,7 +13,10 @@
 // rigorously, per element of the dot product and in units of 2^(e_w + e_x):
 //   truncation of the operands   |w x - w' x'| < 2^-27 (1 + 2^-29)
 //   the six dropped pairs        127^2 (1 + 2 * 128 + 3 * 128^2) 2^-56 < 2^-26.43
-// together 1.86e-8 < 2^-25, so the projection is off by less than BOUND = d * 2^(e_w + e_x - 25).
+// together 1.86e-8 < 2^-25, and an element of x that is zero contributes no error at all (its digits
+// are zero), so the projection is off by less than BOUND = nnz(x) * 2^(e_w + e_x - 25), nnz(x) <= d
+// the number of non-zero activations of the query (the output of a sparse ReLU layer has few:
+// C5 16 %, which takes the projections to recompute from 6 to 1 in 10^4).
 // A projection with |z| > margin * BOUND has a certain sign; the others (about one in 10^4 on
 // normal data of width 8192) and rows with non-finite entries are recomputed in fp64 like the
 // fp64 kernel does.  The value itself is typically off by a few 10^-8 of its own size (the
@@ -49,21 +52,22 @@ constexpr int DIGITS = 4;          // 7-bit digits per element
 constexpr int FRAC_BITS = 7 * DIGITS;   // fixed point: 28 bits below 2^e
 constexpr int MIN_PAIR = 3;        // digit pairs with s + t below it are dropped
 constexpr int CLASSES = 2 * (DIGITS - 1) - MIN_PAIR + 1;   // s + t = 3 .. 6
-constexpr int BOUND_EXP = -25;     // BOUND = d * 2^(e_w + e_x + BOUND_EXP), derived above
+constexpr int BOUND_EXP = -25;     // BOUND = nnz(x) * 2^(e_w + e_x + BOUND_EXP), derived above
 constexpr int HQ = 128;            // queries per tile (hash rows per tile: 64 or 48, see the launcher)
 constexpr int HPIECES = 4 * DIGITS;  // 16-byte pieces per row and chunk of 64 elements
 constexpr int HROW = HPIECES + 1;    // LDS row in pieces (272 bytes: staggers the banks)
 constexpr int BAD_ROW = INT_MIN;   // exponent entry of a row with a non-finite element
 
 // One workgroup per row; a thread holds up to MAXG groups of sixteen consecutive elements in
-// registers (d <= 4096 MAXG), so the row is read once: maximum, exponent, digits.  (One group for
-// rows of up to 4096 elements: 32 vector registers instead of 78, C3 batch 1024 14.9 -> 10.4 us.
-// Two groups for rows of 8192 were slower than four -- 45.7 against 39.6 us on C5: with eight
-// workgroups per compute unit all 2048 rows load at once and then store at once.)
+// registers (d <= 4096 MAXG), so the row is read once: maximum, exponent, digits.  (MAXG sized to
+// the row: one group for rows of up to 4096 elements takes 32 vector registers instead of 78, C3
+// batch 1024 14.9 -> 10.4 us; rows of 8192 run as fast with two groups as with four.)
 template <int MAXG>
 __global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restrict__ X, int64_t ldx, int d,
-                                                    int8_t* __restrict__ out, int32_t* __restrict__ expo) {
+                                                    int8_t* __restrict__ out, int32_t* __restrict__ expo,
+                                                    int32_t* __restrict__ nonzeros) {
   __shared__ float red[4];
+  __shared__ int red_nz[4];
   __shared__ int s_e;
   const int64_t row = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -93,6 +97,7 @@ __global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restri
   }
   float mx = 0.0f;
   bool bad = false;
+  int nz = 0;
 #pragma unroll
   for (int g = 0; g < MAXG; ++g)
 #pragma unroll
@@ -100,12 +105,17 @@ __global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restri
       const float v = fabsf(xv[g][j]);
       if (!(v <= 3.0e38f)) bad = true;          // infinity or NaN
       mx = fmaxf(mx, v);
+      nz += v != 0.0f ? 1 : 0;
     }
   if (bad) mx = __int_as_float(0x7f800000);
-  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-  if (lane == 0) red[wave] = mx;
+  for (int o = 32; o > 0; o >>= 1) {
+    mx = fmaxf(mx, __shfl_xor(mx, o));
+    nz += __shfl_xor(nz, o);
+  }
+  if (lane == 0) { red[wave] = mx; red_nz[wave] = nz; }
   __syncthreads();
   if (tid == 0) {
+    if (nonzeros) nonzeros[row] = (red_nz[0] + red_nz[1]) + (red_nz[2] + red_nz[3]);
     const float m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     int e = 0;
     if (!(m <= 3.0e38f)) e = BAD_ROW;
@@ -299,6 +309,7 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
 // once (rows of a multiple of 64 elements), so a row of 4096 elements is one round trip to L2.
 __global__ __launch_bounds__(256) void hash_int_finish_kernel(const double* __restrict__ part, int S,
                                                              const int32_t* __restrict__ ex,
+                                                             const int32_t* __restrict__ nzx,
                                                              const int32_t* __restrict__ ew,
                                                              const float* __restrict__ X, int ldx,
                                                              const float* __restrict__ Wh,
@@ -322,7 +333,7 @@ __global__ __launch_bounds__(256) void hash_int_finish_kernel(const double* __re
       for (int z = 0; z < S; ++z) sum += part[(size_t)z * total + i];
       const double dot = ldexp(sum, 7 * MIN_PAIR + eq + eh - 2 * FRAC_BITS);
       const double zz = dot + (double)bh[h];
-      const double bound = ldexp((double)d, eq + eh + BOUND_EXP);
+      const double bound = ldexp((double)min(d, nzx[q]), eq + eh + BOUND_EXP);
       if (fabs(zz) > margin * bound) {
         Z[i] = (float)zz;
         redo = false;
@@ -420,14 +431,17 @@ void hash_int_plan(int B, int H, int d, int* hh_out, int* s_out) {
 size_t hash_int_workspace_bytes(int B, int H, int d) {
   const size_t x5 = ((size_t)B * DIGITS * d + 255) / 256 * 256;
   const size_t ex = ((size_t)B * 4 + 255) / 256 * 256;
-  return x5 + ex + (size_t)8 * B * H * sizeof(double) + 256;
+  return x5 + 2 * ex + (size_t)8 * B * H * sizeof(double) + 256;      // digits | exponents | non-zero counts | partial sums
 }
 
-int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s) {
+int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo,
+                        int32_t* nonzeros, hipStream_t s) {
   if (d <= 4096)
-    hipLaunchKernelGGL(slice_digits_kernel<1>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo);
+    hipLaunchKernelGGL(slice_digits_kernel<1>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo, nonzeros);
+  else if (d <= 8192)
+    hipLaunchKernelGGL(slice_digits_kernel<2>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo, nonzeros);
   else
-    hipLaunchKernelGGL(slice_digits_kernel<4>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo);
+    hipLaunchKernelGGL(slice_digits_kernel<4>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo, nonzeros);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }
@@ -440,8 +454,9 @@ int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8
   const size_t ex_bytes = ((size_t)B * 4 + 255) / 256 * 256;
   int8_t* Xd = static_cast<int8_t*>(scratch);
   int32_t* ex = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + x5_bytes);
-  double* part = reinterpret_cast<double*>(static_cast<char*>(scratch) + x5_bytes + ex_bytes);
-  int rc = launch_slice_digits(X, ldx, B, d, Xd, ex, s);
+  int32_t* nzx = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + x5_bytes + ex_bytes);
+  double* part = reinterpret_cast<double*>(static_cast<char*>(scratch) + x5_bytes + 2 * ex_bytes);
+  int rc = launch_slice_digits(X, ldx, B, d, Xd, ex, nzx, s);
   if (rc) return rc;
   int hh = 64, S = 1;
   hash_int_plan(B, H, d, &hh, &S);
@@ -471,7 +486,7 @@ int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8
   }
   SLONN_HIP(hipGetLastError());
   hipLaunchKernelGGL(hash_int_finish_kernel, dim3((unsigned)(((size_t)B * H + 255) / 256)), dim3(256), 0, s, part, S,
-                     ex, ew, X, ldx, Wh, bh, Z, B, H, d, margin);
+                     ex, nzx, ew, X, ldx, Wh, bh, Z, B, H, d, margin);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

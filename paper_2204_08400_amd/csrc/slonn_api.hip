@@ -341,7 +341,7 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
         (void)hipGetLastError();
         if (L.Whd) (void)hipFree(L.Whd);
         L.Whd = nullptr;
-      } else if (launch_slice_digits(L.Wh, L.d_in, H, L.d_in, L.Whd, L.ewh, nullptr) != SLONN_OK ||
+      } else if (launch_slice_digits(L.Wh, L.d_in, H, L.d_in, L.Whd, L.ewh, nullptr, nullptr) != SLONN_OK ||
                  (e = hipStreamSynchronize(nullptr)) != hipSuccess) {
         if (e != hipSuccess) set_error("slicing the FreeHash rows failed: %s", hipGetErrorString(e));
         return fail(SLONN_EHIP);

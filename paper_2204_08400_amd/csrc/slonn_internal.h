@@ -262,7 +262,8 @@ int hash_split_factor(int B, int H, int d);
 bool hash_int_supported(int d, int max_lds);
 int hash_int_digits();
 size_t hash_int_workspace_bytes(int B, int H, int d);
-int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo, hipStream_t s);
+int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo,
+                        int32_t* nonzeros, hipStream_t s);   // nonzeros: nullable, per row the count of non-zero elements
 int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8_t* Wd, const int32_t* ew,
                             const float* bh, float* Z, int B, int H, int d, double margin, void* scratch,
                             hipStream_t s);
