@@ -17,7 +17,8 @@
 //                        creation, activations once per layer call.
 //   pair_mask_kernel     per 128 queries the decision whether the tile kernel or the per-query
 //                        gather serves them; for served queries one bit per (query, node) pair
-//                        of the active lists and the activations in three parts.
+//                        of the active lists (the select kernel does the same on its own when
+//                        asked to; this kernel serves the callers that did not ask).
 //   masked_tiles_kernel  128 x 128 (query x node) tiles per workgroup with eight wavefronts as 2
 //                        query halves x 4 node strips (128 x 256 with one weight part), or 64 x
 //                        64 (64 x 128) with four for batches that would not fill the chip with
@@ -60,15 +61,12 @@ __global__ void split3_kernel(const float* __restrict__ X, int64_t ldx, int d, u
 // lengths itself); flags holds that decision once per 16 queries, the unit the per-query gather
 // skips by.  For a served query: mask[q][w] bit j = node 32 w + j is in the query's list (a
 // selected hash node too: inside a tile its pair costs nothing extra, so its projection is not
-// reused there), and, where X3 is given, X3 row q = the activations in three bf16 parts.  The
-// select kernel writes the same masks and flags itself when it is told to (RowBlocking::mask);
-// this kernel serves the callers that did not, or whose activations need the three-part copy.
+// reused there).  The select kernel writes the same masks and flags itself when it is told to
+// (RowBlocking::mask); this kernel serves the callers that did not.
 __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restrict__ active,
                                                        const int32_t* __restrict__ cnt, int idx_stride, int B,
-                                                       int n,
-                                                       uint32_t* __restrict__ mask, int32_t* __restrict__ flags,
-                                                       long long min_per_query, const float* __restrict__ X, int ldx,
-                                                       int d, uint16_t* __restrict__ X3) {
+                                                       int n, uint32_t* __restrict__ mask,
+                                                       int32_t* __restrict__ flags, long long min_per_query) {
   extern __shared__ uint32_t bits[];
   __shared__ int served;
   const int q = blockIdx.x, tid = threadIdx.x;
@@ -90,41 +88,6 @@ __global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restric
   for (int t = tid; t < c; t += 256) {
     const int node = list[t];
     atomicOr(&bits[node >> 5], 1u << (node & 31));
-  }
-  // eight elements per thread: two 16-byte loads, three 16-byte stores (d is a multiple of 32);
-  // no X3: the tile kernel splits the fp32 activations itself
-  const bool vec = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);
-  for (int g8 = tid; X3 && g8 < (d >> 3); g8 += 256) {
-    float xv[8];
-    const float* xp = X + (size_t)q * ldx + 8 * g8;
-    if (vec) {
-      const float4 a = *reinterpret_cast<const float4*>(xp), b = *reinterpret_cast<const float4*>(xp + 4);
-      xv[0] = a.x; xv[1] = a.y; xv[2] = a.z; xv[3] = a.w; xv[4] = b.x; xv[5] = b.y; xv[6] = b.z; xv[7] = b.w;
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) xv[e] = xp[e];
-    }
-    uint32_t hi[4], mid[4], lo[4];
-#pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-      uint32_t h2[2], m2[2], l2[2];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const float x = xv[e + j];
-        const uint32_t hb = __float_as_uint(x) & 0xFFFF0000u;
-        const float r1 = x - __uint_as_float(hb);
-        const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
-        const float r2 = r1 - __uint_as_float(mb);
-        h2[j] = hb >> 16; m2[j] = mb >> 16; l2[j] = __float_as_uint(r2) >> 16;
-      }
-      hi[e >> 1] = h2[0] | (h2[1] << 16);
-      mid[e >> 1] = m2[0] | (m2[1] << 16);
-      lo[e >> 1] = l2[0] | (l2[1] << 16);
-    }
-    u32x4* o = reinterpret_cast<u32x4*>(X3 + (size_t)q * 3 * d + (size_t)g8 * 24);
-    o[0] = (u32x4){hi[0], hi[1], hi[2], hi[3]};
-    o[1] = (u32x4){mid[0], mid[1], mid[2], mid[3]};
-    o[2] = (u32x4){lo[0], lo[1], lo[2], lo[3]};
   }
   __syncthreads();
   for (int i = tid; i < words; i += 256) mask[(size_t)q * words + i] = bits[i];
@@ -393,6 +356,8 @@ bool masked_tiles_supported(int d, int n, int max_lds) {
   return d % 32 == 0 && (size_t)((n + 31) / 32) * 4 <= (size_t)max_lds && tiles_lds_bytes<128, 128, 3>() <= (size_t)max_lds;
 }
 
+// (pair masks, flags, and room for a three-part copy of the activations, which launch_dense_tiles
+// makes of rows that are not 16-byte aligned)
 size_t masked_tiles_workspace_bytes(int B, int n, int d) {
   const size_t mask = ((size_t)B * ((n + 31) / 32) * 4 + 255) / 256 * 256;
   const size_t flags = ((size_t)(B / 16 + TM / 16 + 1) * 4 + 255) / 256 * 256;
@@ -462,33 +427,29 @@ void masked_tiles_buffers(void* scratch, int B, int n, uint32_t** mask, int32_t*
   *flags = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + mask_bytes);
 }
 
-// mask_ready: the select kernel has written the masks and flags already (same threshold)
+// mask_ready: the select kernel has written the masks and flags already (same threshold).
+// X: fp32 rows the kernel fetches in 16-byte pieces (16-byte aligned, ldx a multiple of 4).
 int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx,
                         const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d,
                         int n, int act, bool mask_ready, int min_keep_permille, void* scratch,
                         int32_t** flags_out, hipStream_t s) {
+  if (!rows_aligned(X, ldx)) SLONN_FAIL(SLONN_EINVAL, "masked tiles: activations must be 16-byte aligned rows");
   const int words = (n + 31) / 32;
-  const size_t mask_bytes = ((size_t)B * words * 4 + 255) / 256 * 256;
-  const size_t flag_bytes = ((size_t)(B / 16 + TM / 16 + 1) * 4 + 255) / 256 * 256;
   uint32_t* mask = nullptr;
   int32_t* flags = nullptr;
   masked_tiles_buffers(scratch, B, n, &mask, &flags);
-  // (activations the kernel cannot fetch in 16-byte pieces are split into a copy first)
-  uint16_t* X3 = rows_aligned(X, ldx)
-                     ? nullptr
-                     : reinterpret_cast<uint16_t*>(static_cast<char*>(scratch) + mask_bytes + flag_bytes);
   *flags_out = flags;
-  if (!mask_ready || X3) {
+  if (!mask_ready) {
     ProfScope prof_(SLONN_PROF_SELECT, s);
     // the tile kernel serves 128 queries when they list at least this many pairs together
     const long long min_per_query = (long long)n * min_keep_permille / 1000;
     hipLaunchKernelGGL(pair_mask_kernel, dim3(B), dim3(256), (size_t)words * 4, s, active, cnt, idx_stride, B, n,
-                       mask, flags, min_per_query, X, ldx, d, X3);
+                       mask, flags, min_per_query);
     SLONN_HIP(hipGetLastError());
   }
   ProfScope prof_(SLONN_PROF_TILES, s);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
-  return launch_tiles(X3, X, ldx, Wp, w_parts, bias, mask, flags, Y, ldy, B, n, d, a, s);
+  return launch_tiles(nullptr, X, ldx, Wp, w_parts, bias, mask, flags, Y, ldy, B, n, d, a, s);
 }
 
 // A layer computed in full for a large batch through the same tiles (no mask, every query

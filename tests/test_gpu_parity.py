@@ -152,6 +152,16 @@ def test_dense_forward_in_bf16_parts_matches_oracle(rt, oracle, w_dtype):
     for l in range(len(layers)):
         assert_close_rows(got["layers"][l].cpu().numpy(), ref[l], None, f"dense in bf16 parts, layer {l}", depth=l + 1)
     assert np.array_equal(got["argmax"].cpu().numpy(), oracle.argmax(ref[-1]))
+    # input rows that are not 16-byte aligned: the tile kernel cannot fetch them in 16-byte pieces, a
+    # three-part copy is made first (split3_kernel) -- the same arithmetic, so the same bits
+    import torch
+    buf = torch.empty(X.size + 1, dtype=torch.float32, device="cuda:0")
+    xm = buf[1:].view(X.shape[0], X.shape[1])
+    xm.copy_(torch.from_numpy(np.ascontiguousarray(X, np.float32)))
+    assert xm.data_ptr() % 16 == 4
+    off = g.dense_forward(xm, layer_outs=True)
+    for l in range(len(layers)):
+        assert torch.equal(off["layers"][l], got["layers"][l]), f"layer {l}: misaligned input rows"
     # against the default arithmetic: the same results to fp32 rounding, not the same bits
     slonn.slonn_model_set_dense_arithmetic(g.model, 0)
     plain = g.dense_forward(X, layer_outs=True)
