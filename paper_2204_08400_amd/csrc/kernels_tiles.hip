@@ -15,10 +15,13 @@
 //                        of part p of row i at i * 3 d + (k / 8) * 24 + 8 p + k % 8, so a row's
 //                        chunk of 32 elements is 192 contiguous bytes.  Weights once at model
 //                        creation, activations once per layer call.
-//   pair_mask_kernel     per 128 queries the decision whether the tile kernel or the per-query
-//                        gather serves them; for served queries one bit per (query, node) pair
-//                        of the active lists (the select kernel does the same on its own when
-//                        asked to; this kernel serves the callers that did not ask).
+//   (the select kernel)  per 128 queries the decision whether the tile kernel or the per-query
+//                        gather serves them (the queries must list at least a threshold of
+//                        (query, node) pairs per query together), once per 16 queries, the unit
+//                        the other paths skip by; for served queries one bit per (query, node)
+//                        pair of the active lists (RowBlocking::mask, kernels_select.hip).  A
+//                        selected hash node has its bit too: inside a tile its pair costs
+//                        nothing extra, so its projection is not reused there.
 //   masked_tiles_kernel  128 x 128 (query x node) tiles per workgroup with eight wavefronts as 2
 //                        query halves x 4 node strips (128 x 256 with one weight part), or 64 x
 //                        64 (64 x 128) with four for batches that would not fill the chip with
@@ -53,44 +56,6 @@ __global__ void split3_kernel(const float* __restrict__ X, int64_t ldx, int d, u
   out[at] = (uint16_t)(hb >> 16);
   out[at + 8] = (uint16_t)(mb >> 16);
   out[at + 16] = (uint16_t)(__float_as_uint(r2) >> 16);
-}
-
-// One workgroup per query.  The 128 queries of a tile are served by the tile kernel when they
-// list at least min_per_query (query, node) pairs per query of the tile together (the last tile
-// of a batch may hold fewer than 128 queries; every workgroup adds up its tile's list
-// lengths itself); flags holds that decision once per 16 queries, the unit the per-query gather
-// skips by.  For a served query: mask[q][w] bit j = node 32 w + j is in the query's list (a
-// selected hash node too: inside a tile its pair costs nothing extra, so its projection is not
-// reused there).  The select kernel writes the same masks and flags itself when it is told to
-// (RowBlocking::mask); this kernel serves the callers that did not.
-__global__ __launch_bounds__(256) void pair_mask_kernel(const int32_t* __restrict__ active,
-                                                       const int32_t* __restrict__ cnt, int idx_stride, int B,
-                                                       int n, uint32_t* __restrict__ mask,
-                                                       int32_t* __restrict__ flags, long long min_per_query) {
-  extern __shared__ uint32_t bits[];
-  __shared__ int served;
-  const int q = blockIdx.x, tid = threadIdx.x;
-  const int words = (n + 31) >> 5;
-  if (tid < 64) {
-    const int q0 = q - q % TM;
-    long long sum = 0;
-    for (int i = tid; i < TM && q0 + i < B; i += 64) sum += cnt[q0 + i];
-    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-    const int f = sum >= min_per_query * min(TM, B - q0) ? 1 : 0;
-    if (tid == 0) served = f;
-    if (q == q0 && tid < TM / 16) flags[q / 16 + tid] = f;
-  }
-  for (int i = tid; i < words; i += 256) bits[i] = 0u;
-  __syncthreads();
-  if (!served) return;
-  const int c = cnt[q];
-  const int32_t* list = active + (size_t)q * idx_stride;
-  for (int t = tid; t < c; t += 256) {
-    const int node = list[t];
-    atomicOr(&bits[node >> 5], 1u << (node & 31));
-  }
-  __syncthreads();
-  for (int i = tid; i < words; i += 256) mask[(size_t)q * words + i] = bits[i];
 }
 
 // Barrier that orders LDS traffic only: global loads issued before it stay in flight across it
@@ -427,26 +392,16 @@ void masked_tiles_buffers(void* scratch, int B, int n, uint32_t** mask, int32_t*
   *flags = reinterpret_cast<int32_t*>(static_cast<char*>(scratch) + mask_bytes);
 }
 
-// mask_ready: the select kernel has written the masks and flags already (same threshold).
-// X: fp32 rows the kernel fetches in 16-byte pieces (16-byte aligned, ldx a multiple of 4).
-int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx,
-                        const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d,
-                        int n, int act, bool mask_ready, int min_keep_permille, void* scratch,
-                        int32_t** flags_out, hipStream_t s) {
+// The select kernel has written the pair masks and the per-tile decisions into scratch
+// (masked_tiles_buffers).  X: fp32 rows the kernel fetches in 16-byte pieces (16-byte aligned, ldx a
+// multiple of 4).
+int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx, float* Y,
+                        int ldy, int B, int d, int n, int act, void* scratch, int32_t** flags_out, hipStream_t s) {
   if (!rows_aligned(X, ldx)) SLONN_FAIL(SLONN_EINVAL, "masked tiles: activations must be 16-byte aligned rows");
-  const int words = (n + 31) / 32;
   uint32_t* mask = nullptr;
   int32_t* flags = nullptr;
   masked_tiles_buffers(scratch, B, n, &mask, &flags);
   *flags_out = flags;
-  if (!mask_ready) {
-    ProfScope prof_(SLONN_PROF_SELECT, s);
-    // the tile kernel serves 128 queries when they list at least this many pairs together
-    const long long min_per_query = (long long)n * min_keep_permille / 1000;
-    hipLaunchKernelGGL(pair_mask_kernel, dim3(B), dim3(256), (size_t)words * 4, s, active, cnt, idx_stride, B, n,
-                       mask, flags, min_per_query);
-    SLONN_HIP(hipGetLastError());
-  }
   ProfScope prof_(SLONN_PROF_TILES, s);
   const int a = (act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
   return launch_tiles(nullptr, X, ldx, Wp, w_parts, bias, mask, flags, Y, ldy, B, n, d, a, s);

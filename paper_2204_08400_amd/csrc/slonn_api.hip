@@ -891,13 +891,14 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       // fp32 layer with split weights at a batch that fills the tile kernel: masked tiles follow the
       // select kernel, which then leaves the queries they will serve out of the regrouping
       const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);   // workgroups of the tile kernel
-      const bool f32_tiles = rb.part_idx && L.W3 && B >= 160 && mtiles >= 64 && out && !(is_last && Y->val) &&
-                             m->path_grouped;
+      const bool f32_tiles = rb.part_idx && L.W3 && w.tiles && B >= 160 && mtiles >= 64 && out &&
+                             !(is_last && Y->val) && m->path_grouped;
       // (bf16-weight layers: tiles of 128 queries with large budgets go to the masked tiles, the others
       // to the unions of 16)
-      const bool bf16_tiles = all_grouped && mtiles >= 128 && masked_tiles_supported(L.d_in, L.d_out, m->max_lds_bytes);
-      if ((f32_tiles || bf16_tiles) && w.tiles) {
-        // the select kernel decides per tile like the tile launcher would and writes the pair masks
+      const bool bf16_tiles = all_grouped && w.tiles && mtiles >= 128 &&
+                              masked_tiles_supported(L.d_in, L.d_out, m->max_lds_bytes);
+      if (f32_tiles || bf16_tiles) {
+        // the select kernel decides per tile of 128 queries and writes the pair masks of the served ones
         const int permille = f32_tiles ? masked_tiles_min_keep_permille(B) : BF16_TILES_MIN_KEEP_PERMILLE;
         rb.served_min_per_query = (long long)L.d_out * permille / 1000;
         rb.B = B;
@@ -930,9 +931,8 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         const int32_t* served = nullptr;
         if (bf16_tiles) {
           int32_t* tflags = nullptr;
-          rc = launch_masked_tiles(static_cast<const uint16_t*>(L.W), 1, L.bias, cur, ldcur, aidx, acnt, astride, out,
-                                   ldo, B, L.d_in, L.d_out, act, rb.mask != nullptr, BF16_TILES_MIN_KEEP_PERMILLE,
-                                   w.tiles, &tflags, s);
+          rc = launch_masked_tiles(static_cast<const uint16_t*>(L.W), 1, L.bias, cur, ldcur, out, ldo, B, L.d_in,
+                                   L.d_out, act, w.tiles, &tflags, s);
           if (rc) return rc;
           served = tflags;
         }
@@ -947,8 +947,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
           // masked tiles on the bf16 matrix cores (a selected hash node of a served query is computed
           // there like any other pair; the regrouping step reuses the projections for the others)
           int32_t* flags = nullptr;
-          rc = launch_masked_tiles(L.W3, 3, L.bias, cur, ldcur, aidx, acnt, astride, out, ldo, B, L.d_in, L.d_out,
-                                   act, rb.mask != nullptr, masked_tiles_min_keep_permille(B), w.tiles, &flags, s);
+          rc = launch_masked_tiles(L.W3, 3, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out, act, w.tiles, &flags, s);
           if (rc) return rc;
           gflag = flags;
         } else if (gtiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {

@@ -324,10 +324,9 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
 // Large batches of a large layer: the selected (query, node) pairs evaluated as masked dense
 // tiles on the bf16 matrix cores (activations as three bf16 parts).  Wp: w_parts == 3: fp32
 // weights through launch_split3; w_parts == 1: the layer's own bf16 rows.  Per 128 queries the
-// device decides whether the tiles serve them: *flags_out (device, one per 16 queries) is 1
-// where they did (mean list at least min_keep_permille / 1000 of the layer).  reuse (nullable):
-// nodes with an hslot entry >= 0 are left out; with Z their outputs act(Z) are written for the
-// served queries.  scratch: masked_tiles_workspace_bytes(B, n, d) bytes.
+// select kernel has decided whether the tiles serve them (RowBlocking::mask, ::flags, placed in
+// scratch by masked_tiles_buffers): *flags_out (device, one per 16 queries) is 1 where they do.
+// X: 16-byte aligned fp32 rows.  scratch: masked_tiles_workspace_bytes(B, n, d) bytes.
 bool masked_tiles_supported(int d, int n, int max_lds);
 size_t masked_tiles_workspace_bytes(int B, int n, int d);
 // where in that scratch the pair masks [B][(n + 31) / 32] and the per-16-queries flags live
@@ -335,10 +334,8 @@ void masked_tiles_buffers(void* scratch, int B, int n, uint32_t** mask, int32_t*
 int launch_split3(const float* X, int64_t ldx, int64_t rows, int d, uint16_t* out, hipStream_t s);
 int launch_dense_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx, float* Y,
                        int ldy, int B, int d, int n, int act, void* scratch, hipStream_t s);
-int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx,
-                        const int32_t* active, const int32_t* cnt, int idx_stride, float* Y, int ldy, int B, int d,
-                        int n, int act, bool mask_ready, int min_keep_permille, void* scratch,
-                        int32_t** flags_out, hipStream_t s);
+int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx, float* Y,
+                        int ldy, int B, int d, int n, int act, void* scratch, int32_t** flags_out, hipStream_t s);
 
 // y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).
 // yc (nullable) receives the values in list order.
