@@ -448,8 +448,13 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
   const bool vec = (d % chunk == 0) && (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(W) % 16 == 0) &&
                    (reinterpret_cast<uintptr_t>(X) % 16 == 0);
   const size_t lds = ((size_t)d + 8) * sizeof(float);
-  if (lds > ((size_t)160 << 10))
-    SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer", d);
+  // rows too long for the query vector to be staged in LDS (beyond 40 952 inputs): the kernel that
+  // reads the vector from global memory, whatever the batch
+  const bool too_long = lds > ((size_t)160 << 10);
+  const bool row_ok = vec && (size_t)d * esz >= 4096 && max_rows <= idx_stride_or(active, idx_stride, n);
+  if (too_long && (!row_ok || B > 65535))
+    SLONN_FAIL(SLONN_EUNSUPPORTED, "gather: d_in %d does not fit the LDS staging buffer%s", d,
+               row_ok ? " and the batch is beyond 65535" : " and the rows are not 16-byte aligned");
   // beyond 64 KB a kernel has to be granted its dynamic LDS explicitly
   auto grant = [&](const void* fn) -> int {
     if (lds > 65536) SLONN_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -459,7 +464,7 @@ int launch_gather_forward(const void* W, int w_dtype, const float* bias, const f
   // few queries, or few rows each (a skinny layer computed in full): the 64-row chunks of the
   // general kernel would leave most of the chip idle; long rows: one wavefront per row
   const long coarse_wgs = (long)B * ((max_rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
-  if (vec && B <= GATHER_ROW_MAX_BATCH && (size_t)d * esz >= 4096 && max_rows <= idx_stride_or(active, idx_stride, n)) {
+  if (row_ok && (B <= GATHER_ROW_MAX_BATCH || too_long)) {
     // one workgroup per list entry (at most 2048 per query, strided beyond)
     dim3 grid(std::min(max_rows, 2048), B);
     if (w_dtype == SLONN_F32)

@@ -102,8 +102,8 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
   }
 }
 
-// Will the masked tiles serve query q?  The sum pair_mask_kernel forms from the list lengths of
-// the 128 queries of q's tile, formed here from their keep fractions (a list is as long as its
+// Will the masked tiles serve query q?  The sum of the list lengths of the 128 queries of q's
+// tile against the threshold, formed from their keep fractions (a list is as long as its
 // budget, or as the K*L hash nodes at its head if those are more).  red: NT / 64 free words of
 // LDS.  Whole workgroup, same answer in every thread.
 template <int NT>

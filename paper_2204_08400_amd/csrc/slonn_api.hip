@@ -873,8 +873,9 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       const bool all_grouped = B >= 160 && gtiles >= 640 && out && !(is_last && Y->val) && m->path_grouped && rows_vec &&
                                grouped_supported(L.d_out, m->max_lds_bytes) &&
                                grouped_uses_bf16_cores(L.W, L.w_dtype, L.d_in);
+      // (the row-block gather stages a query's activations in LDS: up to 40 952 inputs)
       if (!all_grouped && B >= ROW_BLOCK_MIN_BATCH && rows_vec && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20) &&
-          select_fills_row_blocks(L.d_out, m->max_lds_bytes)) {
+          ((size_t)L.d_in + 8) * 4 <= ((size_t)160 << 10) && select_fills_row_blocks(L.d_out, m->max_lds_bytes)) {
         int rpb = 16;
         while ((size_t)rpb * 2 * row_bytes <= ((size_t)2 << 20)) rpb *= 2;
         while ((L.d_out + rpb - 1) / rpb > MAX_ROW_BLOCKS) rpb *= 2;

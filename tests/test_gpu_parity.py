@@ -890,11 +890,39 @@ def test_selected_hash_nodes_reuse_their_projection(rt, oracle, path):
         assert reused > 0
 
 
+def test_masked_tiles_behind_the_wide_select_kernel(rt, oracle):
+    """A bf16 layer too wide for the select kernel's per-node LDS map (50 000 nodes: the bitmap
+    variant runs) at a batch that takes the masked tiles: the bitmap kernel writes the tiles' pair
+    masks from its finished lists.  Keep 0.15 serves every tile, keep 0.03 none (unions of 16)."""
+    from paper_2204_08400_amd import slonn
+    dims = (256, 50000, 16)
+    layers, net, _ = make_case(oracle, dims, 8, 10, seed=91, hashed=[0], cap=8000, N_build=96, kind="clip3",
+                               w_dtype=wl.W_BF16)
+    g = _gpu_net(rt, layers, net, path="layers")
+    B = 256
+    X = make_queries(dims, B, seed=92, kind="clip3")
+    for keep, tiles in ((0.15, 1), (0.03, 0)):
+        _say(f"wide select + masked tiles, keep {keep}")
+        ref = net.sparse_forward(X, keep)
+        slonn.slonn_profile_begin(16)
+        res = g.sparse_forward(X, keep, taps=True)
+        prof = slonn.slonn_profile_end()
+        got = to_numpy_result(res)
+        _say(f"  {compare_sparse(got, ref, layers, 'wide select + tiles')}")
+        # the tile kernel is launched either way (unserved tiles leave at once) and the unions follow;
+        # the output layer's 50 000-element rows do not fit the LDS staging of the gather kernels: it
+        # takes the kernel that reads the activations from global memory
+        assert prof["tiles"][1] == 1 and prof["gather"][1] == 2, prof
+
+
 HASH_FIRST_CASES = [
     # small layers (fused eligible), a row-block layer, a bf16 net, a wide activated output layer
     dict(dims=(96, 1000, 640, 12), K=6, L=10, kind="u01", B=67, last_act=wl.ACT_SOFTMAX),
     dict(dims=(640, 1536, 40), K=5, L=8, kind="u01", B=48, hashed=[0], cap=800),
     dict(dims=(128, 768, 512, 10), K=4, L=16, kind="clip3", B=130, w_dtype=wl.W_BF16),
+    # a batch and a layer that take the masked tiles: the hash nodes at the head of the lists get
+    # their bits in the pair masks of the served tiles
+    dict(dims=(640, 4096, 40), K=5, L=8, kind="u01", B=192, hashed=[0], cap=1400),
 ]
 
 
@@ -904,6 +932,8 @@ def test_hash_nodes_always_active_matches_oracle(rt, oracle, case, path):
     """Section 3.4 variant: hash nodes head every active list and are never selected;
     budgets below K*L give exactly the hash nodes."""
     dims = case["dims"]
+    if path == "fused" and not _fused_ok(case):
+        pytest.skip("model does not qualify for the whole-network kernel")
     layers, net, _ = make_case(oracle, dims, case["K"], case["L"], seed=81, hashed=case.get("hashed"),
                                cap=case.get("cap"), N_build=200, kind=case["kind"],
                                w_dtype=case.get("w_dtype", wl.W_F32), last_act=case.get("last_act", wl.ACT_NONE))
