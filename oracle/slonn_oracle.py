@@ -120,7 +120,7 @@ class Tables:
         self.n, self.K, self.L, self.list_cap = n, K, L, list_cap
 
     def __del__(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and lib is not None:       # (module globals are gone at interpreter exit)
             lib().so_tables_free(self.h)
             self.h = None
 

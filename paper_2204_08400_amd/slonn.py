@@ -147,7 +147,7 @@ class Model:
         self.h = h
 
     def close(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and load is not None:      # (module globals are gone at interpreter exit)
             load().slonn_model_destroy(self.h)
             self.h = None
 
@@ -159,7 +159,7 @@ class Tables:
         self.model, self.h = model, handle
 
     def close(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and load is not None:
             load().slonn_tables_destroy(self.h)
             self.h = None
 
@@ -310,7 +310,7 @@ class Policy:
         self.h, self.K, self.L, self.G = h, int(K), int(L), len(k_grid)
 
     def close(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and load is not None:
             load().slonn_policy_destroy(self.h)
             self.h = None
 
@@ -403,7 +403,7 @@ class ForwardGraph:
         _check(load().slonn_forward_graph_launch(self.h, C.c_void_p(_stream_ptr(stream))))
 
     def close(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and load is not None:
             load().slonn_forward_graph_destroy(self.h)
             self.h = None
 
