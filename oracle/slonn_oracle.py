@@ -283,7 +283,7 @@ class ConfidenceTables:
         self.h = C.c_void_p(lib().so_conf_build(K, L, self.G, _p(keys), _p(conf), C.c_int64(keys.shape[0])))
 
     def __del__(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and lib is not None:
             lib().so_conf_free(self.h)
             self.h = None
 
