@@ -118,7 +118,12 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
                                                           int act) {
   extern __shared__ u32x4 tiles_lds[];     // two buffers of [TQ rows of X | TNN rows of W]
   constexpr int PX = PIECES, PW = 4 * WP;  // 16-byte pieces per row and chunk of 32 elements
-  constexpr int ROWX = PX + 1, ROWW = PW + 1;   // LDS rows, padded by one piece (208 / 80 bytes stagger the banks)
+  // LDS rows padded by two pieces: 14 (6) pieces per row.  A wavefront's fragment read -- lane (r, kg) takes
+  // piece r * ROW + kg * parts + p -- then costs 4 LDS cycles, the full 256 bytes per cycle; with one
+  // piece of padding (odd row lengths) or none it costs 8, and the kernel was bound by its LDS
+  // traffic (measured per wavefront instruction with every row length from 9 to 34: the lengths
+  // that are 2 modulo 4 are the conflict-free ones).
+  constexpr int ROWX = PX + 2, ROWW = PW + 2;
   constexpr int BUF16 = TQ * ROWX + TNN * ROWW;
   constexpr int QB = TQ / 32;              // 16-query blocks per wavefront
   constexpr int XG = TQ * 4 / NT;          // XF: groups of eight fp32 activations per thread and chunk
@@ -313,7 +318,7 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
 }
 
 template <int TQ, int TNN, int WP>
-constexpr size_t tiles_lds_bytes() { return (size_t)2 * (TQ * (PIECES + 1) + TNN * (4 * WP + 1)) * 16; }
+constexpr size_t tiles_lds_bytes() { return (size_t)2 * (TQ * (PIECES + 2) + TNN * (4 * WP + 2)) * 16; }
 
 }  // namespace
 
