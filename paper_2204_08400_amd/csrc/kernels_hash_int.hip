@@ -55,7 +55,12 @@ constexpr int CLASSES = 2 * (DIGITS - 1) - MIN_PAIR + 1;   // s + t = 3 .. 6
 constexpr int BOUND_EXP = -25;     // BOUND = nnz(x) * 2^(e_w + e_x + BOUND_EXP), derived above
 constexpr int HQ = 128;            // queries per tile (hash rows per tile: 64 or 48, see the launcher)
 constexpr int HPIECES = 4 * DIGITS;  // 16-byte pieces per row and chunk of 64 elements
-constexpr int HROW = HPIECES + 1;    // LDS row in pieces (272 bytes: staggers the banks)
+// LDS row: 18 pieces, the chunk's pieces in digit-major order (piece 4 * digit + group): a wavefront's
+// fragment read -- lane (r, kg) takes piece r * HROW + 4 * digit + kg -- then costs 4 LDS cycles, the full
+// 256 bytes per cycle.  In the order of global memory (4 * group + digit) no row length from 16 to 40
+// gets below 8 cycles, and the kernel was bound by its LDS traffic.
+constexpr int HROW = HPIECES + 2;
+__host__ __device__ constexpr int hash_lds_col(int piece) { return (piece % DIGITS) * 4 + piece / DIGITS; }
 constexpr int BAD_ROW = INT_MIN;   // exponent entry of a row with a non-finite element
 
 // One workgroup per row; a thread holds up to MAXG groups of sixteen consecutive elements in
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
     const int8_t* base = isx ? Xd + (size_t)min(q0 + row, B - 1) * DIGITS * d
                              : Wd + (size_t)min(h0 + row, H - 1) * DIGITS * d;
     src[i] = reinterpret_cast<const u32x4*>(base) + piece;
-    dst[i] = (isx ? row : HQ + row) * HROW + piece;
+    dst[i] = (isx ? row : HQ + row) * HROW + hash_lds_col(piece);
   }
   // this workgroup's chunks of 64 elements
   const int nchunks = d / 64;
@@ -232,18 +237,19 @@ __global__ __launch_bounds__(512) void hash_int_tiles_kernel(const int8_t* __res
     const u32x4* Xs = hash_lds + buf * BUF;
     const u32x4* Ws = Xs + HQ * HROW;
     // An MFMA consumes the whole chunk of 64 elements: lane (r, kg) supplies the 16 elements of
-    // group kg, i.e. piece kg * DIGITS + digit of its row.  One MFMA per digit pair and block.
+    // group kg, i.e. piece kg * DIGITS + digit of its row (at 4 * digit + kg of the LDS row).  One MFMA per
+    // digit pair and block.
     i32x4 xd[NBQ][DIGITS];
 #pragma unroll
     for (int b = 0; b < NBQ; ++b)
 #pragma unroll
       for (int t = 0; t < DIGITS; ++t)
-        xd[b][t] = as_i32x4(Xs[(wq * 16 * NBQ + b * 16 + r) * HROW + kg * DIGITS + t]);
+        xd[b][t] = as_i32x4(Xs[(wq * 16 * NBQ + b * 16 + r) * HROW + 4 * t + kg]);
 #pragma unroll
     for (int s = 0; s < DIGITS; ++s) {
       i32x4 wd[NBH];
 #pragma unroll
-      for (int a = 0; a < NBH; ++a) wd[a] = as_i32x4(Ws[(wh * 16 * NBH + a * 16 + r) * HROW + kg * DIGITS + s]);
+      for (int a = 0; a < NBH; ++a) wd[a] = as_i32x4(Ws[(wh * 16 * NBH + a * 16 + r) * HROW + 4 * s + kg]);
 #pragma unroll
       for (int t = 0; t < DIGITS; ++t) {
         if (s + t < MIN_PAIR) continue;
