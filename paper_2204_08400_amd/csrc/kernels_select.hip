@@ -104,26 +104,21 @@ __device__ __forceinline__ void partition_rows(const int32_t* out, int m, const 
 
 // Will the masked tiles serve query q?  The sum of the list lengths of the 128 queries of q's
 // tile against the threshold, formed from their keep fractions (a list is as long as its
-// budget, or as the K*L hash nodes at its head if those are more).  red: NT / 64 free words of
-// LDS.  Whole workgroup, same answer in every thread.
-template <int NT>
+// budget, or as the K*L hash nodes at its head if those are more).  Every wavefront forms the sum
+// for itself (two keep fractions per lane, one reduction over the lanes): no barrier, the same
+// answer in every thread of the workgroup.
 __device__ __forceinline__ bool tile_served(const RowBlocking& rb, const float* __restrict__ keep, int keep_stride,
-                                            int n, int H, int q, uint32_t* red) {
+                                            int n, int H, int q) {
   if (rb.served_min_per_query <= 0) return false;
   const int q0 = q - q % 128, nq = min(128, rb.B - q0);
+  const int lane = threadIdx.x & 63;
   uint32_t mine = 0;
-  for (int i = threadIdx.x; i < nq; i += NT) {
+  for (int i = lane; i < nq; i += 64) {
     const int m = budget_of(keep[(size_t)(q0 + i) * keep_stride], n);
     mine += (uint32_t)((m == n || m > H) ? m : H);
   }
   for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mine;
-  __syncthreads();
-  long long sum = 0;
-#pragma unroll
-  for (int w = 0; w < NT / 64; ++w) sum += red[w];
-  return sum >= rb.served_min_per_query * nq;
+  return (long long)mine >= rb.served_min_per_query * nq;
 }
 
 // What the tile kernel reads about query q (RowBlocking::mask): for a query of a served tile one
@@ -209,11 +204,14 @@ __global__ __launch_bounds__(NT, NT == 512 ? 8 : 4) void select_block_kernel(
   const int total = (m == n || m > H) ? m : H;
   const int words = (n + 31) >> 5;
   if (tid == 0) cnt[q] = total;
+  // (the tile kernel writes every element of the output rows of the queries it serves, zeros for the
+  // nodes that were not selected: those rows are not cleared here)
+  const bool served = tile_served(rb, keep, keep_stride, n, H, q);
+  if (served && rb.mask) y = nullptr;
   if (m == n) {   // the layer is computed in full: ascending ids, no table access (the keys are written as codes)
     if (y)
       for (int i = tid; i < n; i += NT) y[i] = 0.0f;
     for (int i = tid; i < n; i += NT) out[i] = i;
-    const bool served = tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
     if (rb.mask) write_pair_mask<NT>(rb, q, served, out, n, n, true, sh.prio);
     if (rb.part_idx && !served) partition_rows<NT>(out, n, rb, q, z, sh.prio);
     return;
@@ -229,8 +227,6 @@ __global__ __launch_bounds__(NT, NT == 512 ? 8 : 4) void select_block_kernel(
       for (int i = tid; i < words; i += NI) sh.bits[i] = 0u;
     for (int h = tid; h < H; h += NI) out[h] = hf.hnodes[h];
   }
-  // (the tile's decision while the keys are on their way; its barriers also end the clearing)
-  const bool served = tile_served<NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
   __syncthreads();
   if (sh.bits)
     for (int h = tid; h < H; h += NT) atomicOr(&sh.bits[hf.hnodes[h] >> 5], 1u << (hf.hnodes[h] & 31));
@@ -268,11 +264,13 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   int32_t* out = active + (size_t)q * idx_stride;
   const float* z = Z + (size_t)q * K * L;
   sum_split_projections<SEL_NT>(hsp, q, K * L);
-  if (yzero) {
+  const int H = hf.hnodes ? K * L : 0;
+  // (the tile kernel writes every element of the output rows of the queries it serves: not cleared here)
+  const bool served = tile_served(rb, keep, keep_stride, n, H, q);
+  if (yzero && !(served && rb.mask)) {
     float* y = yzero + (size_t)q * ldy;
     for (int i = tid; i < n; i += SEL_NT) y[i] = 0.0f;
   }
-  const int H = hf.hnodes ? K * L : 0;
   const int total = (m == n || m > H) ? m : H;
   if (tid == 0) cnt[q] = total;
   if (m == n) {
@@ -282,7 +280,6 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
       codes[(size_t)q * L + tid] = key;
     }
     for (int i = tid; i < n; i += SEL_NT) out[i] = i;
-    const bool served = tile_served<SEL_NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
     if (rb.mask) write_pair_mask<SEL_NT>(rb, q, served, out, n, n, true, sh.taken);
     if (rb.part_idx && !served) partition_rows<SEL_NT>(out, n, rb, q, z, sh.tval);
     return;
@@ -293,7 +290,6 @@ __global__ __launch_bounds__(SEL_NT) void select_wide_kernel(
   __syncthreads();
   select_block_wide<SEL_NT, WIDE_MU, IdT>(z, K, L, n, total - H, dir, ids, global_rank, sh,
                             codes ? codes + (size_t)q * L : nullptr, out + H, H ? hf.hslot : nullptr);
-  const bool served = tile_served<SEL_NT>(rb, keep, keep_stride, n, H, q, reinterpret_cast<uint32_t*>(sh.wave_cnt));
   if (rb.mask) write_pair_mask<SEL_NT>(rb, q, served, out, total, n, false, sh.taken);
   if (rb.part_idx && !served) partition_rows<SEL_NT>(out, total, rb, q, z, sh.tval);
 }

@@ -293,8 +293,12 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
 #undef SLONN_TILES_LOAD
 #undef SLONN_TILES_STORE
 
-  // register v of block (a, b): node n0 + 16 NB wn + 16 a + 4 kg + v, query m0 + (TQ / 2) wq + 16 b + r
+  // register v of block (a, b): node n0 + 16 NB wn + 16 a + 4 kg + v, query m0 + (TQ / 2) wq + 16 b + r.
+  // Every element of the tile is written: the result for a selected pair, zero for the others (the
+  // select kernel does not clear the output rows of the queries the tiles serve) -- four nodes of
+  // one query as one 16-byte store where the row allows it.
   const int words = (n + 31) >> 5;
+  const bool vec_out = (ldy % 4 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
 #pragma unroll
   for (int b = 0; b < QB; ++b) {
     const int q = m0 + wq * (TQ / 2) + b * 16 + r;
@@ -303,15 +307,25 @@ __global__ __launch_bounds__(NT) void masked_tiles_kernel(const uint16_t* __rest
     for (int a = 0; a < NB; ++a) {
       const int node = n0 + wn * 16 * NB + a * 16 + 4 * kg; // a multiple of 4: its four bits share a word
       if (node >= n) continue;
-      // (no mask: a layer computed in full, every pair is written)
+      // (no mask: a layer computed in full, every pair counts)
       const uint32_t four = mask ? (mask[(size_t)q * words + (node >> 5)] >> (node & 31)) & 0xFu : 0xFu;
+      float zv[4];
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
+        float z = 0.0f;
         if (((four >> v) & 1u) && node + v < n) {
-          float z = acc[a][b][v] + bias[node + v];
+          z = acc[a][b][v] + bias[node + v];
           if (act == SLONN_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-          Y[(size_t)q * ldy + node + v] = z;
         }
+        zv[v] = z;
+      }
+      float* yp = Y + (size_t)q * ldy + node;
+      if (vec_out && node + 3 < n) {
+        *reinterpret_cast<float4*>(yp) = make_float4(zv[0], zv[1], zv[2], zv[3]);
+      } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (node + v < n) yp[v] = zv[v];
       }
     }
   }
