@@ -21,7 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
-BF16_PEAK_TFLOPS = 2500.0       # dense bf16 MFMA
+F16_PEAK_TFLOPS = 2500.0        # dense fp16 (and bf16) MFMA
 FP32_MFMA_PEAK_TFLOPS = 157.3
 KERNEL_OF_KIND = {"fused": "fused_", "tiles": "masked_tiles_kernel", "gather": "gather_blocked_kernel",
                   "select": "select_block_kernel", "hash": "hash projection kernels", "dense": "dense_layer_kernel",
@@ -274,21 +274,21 @@ def roofline_of(w, keep, prof, steps, secs_per_step, traffic_key):
               "traffic_source": (f"profiles/hbm_traffic.json[{traffic_key}] (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at this "
                                  "workload, scaled by a plain copy; not measured in this run)") if tr else None}
     if dom == "tiles":
-        # masked tiles on the bf16 matrix cores: one launch per activated layer and batch.  The method's
+        # masked tiles on the fp16 matrix cores: one launch per activated layer and batch.  The method's
         # own flops are 2 d per selected (query, node) pair; the kernel issues every pair of its tiles,
-        # and 3 (bf16 weights) or 6 (fp32 weights in three parts) bf16 products per fp32-class product.
+        # and 2 (bf16 weights) or 3 (fp32 weights in two parts) fp16 products per fp32-class product.
         act = [l for l in w.layers if l.K > 0]
         own = sum(2.0 * float(w.budgets(keep, l.d_out).sum()) * l.d_in for l in act)
-        issued = sum(2.0 * w.nq * l.d_in * l.d_out * (3 if l.w_dtype == w.wl.W_BF16 else 6) for l in act)
+        issued = sum(2.0 * w.nq * l.d_in * l.d_out * (2 if l.w_dtype == w.wl.W_BF16 else 3) for l in act)
         own_l, issued_l = own / (n / steps), issued / (n / steps)
-        r = {"bound": "mfma", "achieved": round(own_l / avg_s / 1e12, 2), "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-             "frac": round(own_l / avg_s / 1e12 / BF16_PEAK_TFLOPS, 4),
+        r = {"bound": "mfma", "achieved": round(own_l / avg_s / 1e12, 2), "peak": F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+             "frac": round(own_l / avg_s / 1e12 / F16_PEAK_TFLOPS, 4),
              "method_flops_per_launch": int(own_l), "issued_flops_per_launch": int(issued_l),
              "issued_TFLOPs": round(issued_l / avg_s / 1e12, 1),
-             "issued_frac": round(issued_l / avg_s / 1e12 / BF16_PEAK_TFLOPS, 4),
+             "issued_frac": round(issued_l / avg_s / 1e12 / F16_PEAK_TFLOPS, 4),
              "note": "achieved = the method's own flops (2 d per selected pair) per launch over the mean launch duration; "
                      "issued = what the tile kernel executes for them: every (query, node) pair of a served 128-query tile, "
-                     "each fp32-class product as 3 (bf16 weights) or 6 (fp32 weights) bf16 MFMA products.  "
+                     "each fp32-class product as 2 (bf16 weights) or 3 (fp32 weights) fp16 MFMA products.  "
                      "nominal_gathered_GBps is the north-star figure (budget x row bytes over the step time); it exceeds the "
                      "HBM peak because a weight tile is fetched once per 128 queries, so it is not a roofline fraction"}
     else:
@@ -414,7 +414,7 @@ def main():
                                        "nominal_gathered_GBps": round(wk.gathered_bytes_per_step(keep) * steps / s / 1e9, 1)}
         dflops = wk.dense_flops_per_query()
         res["dense_baseline"] = {}
-        for mode, label in ((0, "fp32_mfma"), (1, "bf16_parts_mfma")):
+        for mode, label in ((0, "fp32_mfma"), (1, "f16_parts_mfma")):
             if mode and not hasattr(slonn, "slonn_model_set_dense_arithmetic"):
                 continue
             if hasattr(slonn, "slonn_model_set_dense_arithmetic"):

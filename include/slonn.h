@@ -161,13 +161,14 @@ int slonn_model_set_hash_margin(slonn_model* m, double margin);
 
 /* Arithmetic of slonn_dense_forward, the all-nodes baseline (Section 3.4, last paragraph).
  * SLONN_DENSE_FP32_MFMA (default): fp32 operands on the fp32 matrix cores.
- * SLONN_DENSE_BF16_PARTS: the arithmetic the sparse path uses for large batches of large layers -
- *   activations (and fp32 weights) as exact sums of three bf16 parts, partial products accumulated in
- *   fp32 on the bf16 matrix cores - so that sparse and dense passes can be compared like for like.
+ * SLONN_DENSE_F16_PARTS: the arithmetic the sparse path uses for large batches of large layers -
+ *   rows scaled by powers of two, activations (and fp32 weights) as sums of two fp16 parts (22
+ *   significand bits; bf16 weights are one part, exactly), partial products accumulated in fp32 on
+ *   the fp16 matrix cores - so that sparse and dense passes can be compared like for like.
  *   Layers or batches that path does not serve (small layers, rows not a multiple of 32 elements, batches
  *   of only a few tiles) stay on the fp32 cores.  Results agree with the default to fp32 rounding.
  * EINVAL: null model, unknown mode.                                                          */
-enum { SLONN_DENSE_FP32_MFMA = 0, SLONN_DENSE_BF16_PARTS = 1 };
+enum { SLONN_DENSE_FP32_MFMA = 0, SLONN_DENSE_F16_PARTS = 1 };
 int slonn_model_set_dense_arithmetic(slonn_model* m, int mode);
 
 /* Variant of Section 3.4 ("the hash is free"): the K*L FreeHash projections of a layer are
@@ -276,8 +277,9 @@ int slonn_select(const slonn_model* m, const slonn_tables* t, int layer, const f
  * projections are summed in fp64, or for batches from 256 as exact integer sums of fixed-
  * point digits with every sign certified; only a projection within about 1e-13 of zero can
  * fall either way).  A selected node's output is act(w . x + b) in fp32-class arithmetic:
- * fp32 FMA chains, or - large batches of large layers - exact partial products of bf16 parts
- * of the operands accumulated in fp32 on the matrix cores; the summation order differs
+ * fp32 FMA chains, or - large batches of large layers - exact partial products of fp16 parts
+ * of the operands (rows scaled by powers of two, 22 significand bits per operand, bf16 weights
+ * exactly) accumulated in fp32 on the matrix cores; the summation order differs
  * between paths and batch sizes, results agree to fp32 rounding.                     */
 int slonn_sparse_forward(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
                          const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,

@@ -440,6 +440,11 @@ size_t hash_int_workspace_bytes(int B, int H, int d) {
   return x5 + 2 * ex + (size_t)8 * B * H * sizeof(double) + 256;      // digits | exponents | non-zero counts | partial sums
 }
 
+const int32_t* hash_int_row_exponents(const void* scratch, int B, int d) {
+  const size_t x5_bytes = ((size_t)B * DIGITS * d + 255) / 256 * 256;
+  return reinterpret_cast<const int32_t*>(static_cast<const char*>(scratch) + x5_bytes);
+}
+
 int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo,
                         int32_t* nonzeros, hipStream_t s) {
   if (d <= 4096)

@@ -134,12 +134,8 @@ void plan_workspace(const slonn_model* m, int B, char* base, Workspace* w) {
   w->grouped = take(grouped_workspace_bytes(B, std::max(max_na, 1), d_bf16));
   size_t tiles_bytes = 0;
   for (const Layer& l : m->layers)
-    if (l.activated() && (l.W3 || l.w_dtype == SLONN_BF16) && masked_tiles_supported(l.d_in, l.d_out, m->max_lds_bytes))
+    if (l.Wt && (l.activated() || B >= 256))   // (a layer computed in full goes through the tiles from batch 256)
       tiles_bytes = std::max(tiles_bytes, masked_tiles_workspace_bytes(B, l.d_out, l.d_in));
-  // (a bf16 layer computed in full uses the same buffer for its split activations)
-  for (const Layer& l : m->layers)
-    if (!l.activated() && l.w_dtype == SLONN_BF16 && l.d_in % 32 == 0 && B >= 256)
-      tiles_bytes = std::max(tiles_bytes, (size_t)3 * B * l.d_in * 2 + 256);
   w->tiles = tiles_bytes ? take(tiles_bytes) : nullptr;
   w->tiles_bytes = tiles_bytes;
   w->hash_split = take(hash_split_workspace_bytes());
@@ -347,20 +343,29 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
         return fail(SLONN_EHIP);
       }
     }
-    // Large fp32 layers (the ones the forward pass walks in row blocks): the weights once more as
-    // three bf16 parts, for the masked tiles that serve large batches on the bf16 matrix cores.
-    // Without the memory for it large batches stay on the other paths.
-    const size_t row_bytes = (size_t)L.d_in * 4;
-    if (L.w_dtype == SLONN_F32 && masked_tiles_supported(L.d_in, L.d_out, m->max_lds_bytes) &&
-        reinterpret_cast<uintptr_t>(L.W) % 16 == 0 && L.w_layout == SLONN_ROWS_ARE_NODES && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20)) {
-      if (hipMalloc(&L.W3, (size_t)3 * L.d_out * L.d_in * 2) != hipSuccess) {
-        (void)hipGetLastError();
-        L.W3 = nullptr;
-      } else if (launch_split3(static_cast<const float*>(L.W), L.d_in, L.d_out, L.d_in, L.W3, nullptr) != SLONN_OK ||
-                 (e = hipStreamSynchronize(nullptr)) != hipSuccess) {
-        if (e != hipSuccess) set_error("splitting the weights failed: %s", hipGetErrorString(e));
-        return fail(SLONN_EHIP);
-      }
+  }
+  // Large layers: the weights once more as scaled fp16 parts (fp32 weights: two, bf16 weights:
+  // one, the same bytes again) for the tiles that serve large batches on the fp16 matrix cores --
+  // activated fp32 layers of the size the forward pass walks in row blocks, and bf16 layers.
+  // Without the memory for it large batches stay on the other paths.
+  for (Layer& L : m->layers) {
+    const size_t row_bytes = (size_t)L.d_in * (L.w_dtype == SLONN_F32 ? 4 : 2);
+    const bool wanted = L.w_dtype == SLONN_F32 ? (L.activated() && row_bytes >= 2048 && row_bytes * L.d_out > ((size_t)3 << 20))
+                                               : true;
+    if (!wanted || !masked_tiles_supported(L.d_in, L.d_out, m->max_lds_bytes) ||
+        reinterpret_cast<uintptr_t>(L.W) % 16 != 0 || L.w_layout != SLONN_ROWS_ARE_NODES)
+      continue;
+    if (hipMalloc(&L.Wt, tile_weights_bytes(L.w_dtype, L.d_out, L.d_in)) != hipSuccess ||
+        hipMalloc(&L.wt_exp, (size_t)L.d_out * 4) != hipSuccess) {
+      (void)hipGetLastError();
+      if (L.Wt) (void)hipFree(L.Wt);
+      L.Wt = nullptr;
+    } else if (launch_split_weights(L.W, L.w_dtype, L.d_out, L.d_in, L.Wt, L.wt_exp, nullptr) != SLONN_OK ||
+               (e = hipStreamSynchronize(nullptr)) != hipSuccess) {
+      if (e != hipSuccess) set_error("splitting the weights failed: %s", hipGetErrorString(e));
+      return fail(SLONN_EHIP);
+    } else {
+      L.wt_parts = L.w_dtype == SLONN_F32 ? 2 : 1;
     }
   }
   *out = m;
@@ -456,7 +461,7 @@ int slonn_model_set_tables_refreshable(slonn_model* m, int on) {
 
 int slonn_model_set_dense_arithmetic(slonn_model* m, int mode) {
   if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
-  if (mode != SLONN_DENSE_FP32_MFMA && mode != SLONN_DENSE_BF16_PARTS)
+  if (mode != SLONN_DENSE_FP32_MFMA && mode != SLONN_DENSE_F16_PARTS)
     SLONN_FAIL(SLONN_EINVAL, "unknown dense arithmetic %d", mode);
   m->dense_arith = mode;
   return SLONN_OK;
@@ -475,7 +480,8 @@ int slonn_model_destroy(slonn_model* m) {
     if (L.bh) (void)hipFree(L.bh);
     if (L.hslot) (void)hipFree(L.hslot);
     if (L.hnodes) (void)hipFree(L.hnodes);
-    if (L.W3) (void)hipFree(L.W3);
+    if (L.Wt) (void)hipFree(L.Wt);
+    if (L.wt_exp) (void)hipFree(L.wt_exp);
     if (L.Whd) (void)hipFree(L.Whd);
     if (L.ewh) (void)hipFree(L.ewh);
   }
@@ -843,10 +849,12 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       // unless the policy kernel needs the projections first)
       HashSplit split;
       const bool policy_here = hook && l == hook->layer;
-      if (L.Whd && w.hash_int && hash_int_pays(B, L.H(), L.d_in))
+      const int32_t* cur_exp = nullptr;    // exponents of the rows of cur, where the hash has found them
+      if (L.Whd && w.hash_int && hash_int_pays(B, L.H(), L.d_in)) {
         rc = launch_hash_project_int(cur, ldcur, L.Wh, L.Whd, L.ewh, L.bh, z, B, L.H(), L.d_in, m->hash_margin,
                                      w.hash_int, s);
-      else
+        cur_exp = hash_int_row_exponents(w.hash_int, B, L.d_in);
+      } else
         rc = launch_hash_project(cur, ldcur, L.Wh, L.bh, z, B, L.H(), L.d_in, w.hash_split,
                                  policy_here ? nullptr : &split, s);
       if (rc) return rc;
@@ -892,12 +900,11 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       // fp32 layer with split weights at a batch that fills the tile kernel: masked tiles follow the
       // select kernel, which then leaves the queries they will serve out of the regrouping
       const long mtiles = (long)((B + 63) / 64) * ((L.d_out + 127) / 128);   // workgroups of the tile kernel
-      const bool f32_tiles = rb.part_idx && L.W3 && w.tiles && B >= 160 && mtiles >= 64 && out &&
+      const bool f32_tiles = rb.part_idx && L.w_dtype == SLONN_F32 && L.Wt && w.tiles && B >= 160 && mtiles >= 64 && out &&
                              !(is_last && Y->val) && m->path_grouped;
       // (bf16-weight layers: tiles of 128 queries with large budgets go to the masked tiles, the others
       // to the unions of 16)
-      const bool bf16_tiles = all_grouped && w.tiles && mtiles >= 128 &&
-                              masked_tiles_supported(L.d_in, L.d_out, m->max_lds_bytes);
+      const bool bf16_tiles = all_grouped && L.Wt && w.tiles && mtiles >= 128;
       if (f32_tiles || bf16_tiles) {
         // the select kernel decides per tile of 128 queries and writes the pair masks of the served ones
         const int permille = f32_tiles ? masked_tiles_min_keep_permille(B) : BF16_TILES_MIN_KEEP_PERMILLE;
@@ -932,7 +939,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         const int32_t* served = nullptr;
         if (bf16_tiles) {
           int32_t* tflags = nullptr;
-          rc = launch_masked_tiles(static_cast<const uint16_t*>(L.W), 1, L.bias, cur, ldcur, out, ldo, B, L.d_in,
+          rc = launch_masked_tiles(L.Wt, L.wt_parts, L.wt_exp, L.bias, cur, ldcur, cur_exp, out, ldo, B, L.d_in,
                                    L.d_out, act, w.tiles, &tflags, s);
           if (rc) return rc;
           served = tflags;
@@ -945,10 +952,11 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
         // on the matrix cores (decided per group on the device); the rest is gathered per query.
         const int32_t* gflag = nullptr;
         if (f32_tiles) {
-          // masked tiles on the bf16 matrix cores (a selected hash node of a served query is computed
+          // masked tiles on the fp16 matrix cores (a selected hash node of a served query is computed
           // there like any other pair; the regrouping step reuses the projections for the others)
           int32_t* flags = nullptr;
-          rc = launch_masked_tiles(L.W3, 3, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out, act, w.tiles, &flags, s);
+          rc = launch_masked_tiles(L.Wt, L.wt_parts, L.wt_exp, L.bias, cur, ldcur, cur_exp, out, ldo, B, L.d_in, L.d_out,
+                                   act, w.tiles, &flags, s);
           if (rc) return rc;
           gflag = flags;
         } else if (gtiles >= 1024 && out && !yc && m->path_grouped && grouped_supported(L.d_out, m->max_lds_bytes)) {
@@ -975,12 +983,12 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
                             ldo, B, L.d_in, L.d_out, act, s);
       if (rc) return rc;
-    } else if (w.tiles && L.w_dtype == SLONN_BF16 && L.d_in % 32 == 0 && reinterpret_cast<uintptr_t>(L.W) % 16 == 0 &&
-               (long)((B + 63) / 64) * ((L.d_out + 127) / 128) >= 128 && (size_t)3 * B * L.d_in * 2 <= w.tiles_bytes) {
+    } else if (w.tiles && L.w_dtype == SLONN_BF16 && L.Wt && (long)((B + 63) / 64) * ((L.d_out + 127) / 128) >= 128 &&
+               masked_tiles_workspace_bytes(B, L.d_out, L.d_in) <= w.tiles_bytes) {
       // a bf16-weight layer computed in full for a large batch: the tiles of the masked evaluation
-      // without a mask, on the bf16 matrix cores (three parts of the activations, fp32 accuracy)
-      rc = launch_dense_tiles(static_cast<const uint16_t*>(L.W), 1, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out,
-                              act, w.tiles, s);
+      // without a mask, on the fp16 matrix cores (two parts of the activations, fp32 accuracy)
+      rc = launch_dense_tiles(L.Wt, L.wt_parts, L.wt_exp, L.bias, cur, ldcur, out, ldo, B, L.d_in, L.d_out, act, w.tiles,
+                              s);
       if (rc) return rc;
     } else if ((size_t)((B + 63) / 64) * ((L.d_out + 63) / 64) >= 256 ||
                ((size_t)((B + 31) / 32) * ((L.d_out + 31) / 32) >= 64 &&
@@ -1148,13 +1156,13 @@ int slonn_dense_forward(const slonn_model* m, const slonn_input* X, int B, float
     if (l == 0 && X->format == SLONN_ELL)
       rc = launch_ell_layer(L.W, L.w_dtype, L.w_layout, L.bias, X->idx, X->val, X->nnz, X->ell_stride, out,
                             L.d_out, B, L.d_in, L.d_out, L.act, s);
-    else if (m->dense_arith == SLONN_DENSE_BF16_PARTS && w.tiles && (L.W3 || L.w_dtype == SLONN_BF16) &&
-             L.w_layout == SLONN_ROWS_ARE_NODES && L.d_in % 32 == 0 && reinterpret_cast<uintptr_t>(L.W) % 16 == 0 &&
-             (long)((B + 63) / 64) * ((L.d_out + 127) / 128) >= 64 && (size_t)3 * B * L.d_in * 2 <= w.tiles_bytes)
-      // the arithmetic of the masked tiles without a mask: activations (and fp32 weights) as three bf16
-      // parts on the bf16 matrix cores, fp32 accumulation
-      rc = launch_dense_tiles(L.W3 ? L.W3 : static_cast<const uint16_t*>(L.W), L.W3 ? 3 : 1, L.bias, cur, ldcur, out,
-                              L.d_out, B, L.d_in, L.d_out, L.act, w.tiles, s);
+    else if (m->dense_arith == SLONN_DENSE_F16_PARTS && w.tiles && L.Wt &&
+             (long)((B + 63) / 64) * ((L.d_out + 127) / 128) >= 64 &&
+             masked_tiles_workspace_bytes(B, L.d_out, L.d_in) <= w.tiles_bytes)
+      // the arithmetic of the masked tiles without a mask: activations (and fp32 weights) as two fp16
+      // parts on the fp16 matrix cores, fp32 accumulation
+      rc = launch_dense_tiles(L.Wt, L.wt_parts, L.wt_exp, L.bias, cur, ldcur, out, L.d_out, B, L.d_in, L.d_out, L.act,
+                              w.tiles, s);
     else
       rc = launch_dense_layer(L.W, L.w_dtype, L.bias, cur, ldcur, out, L.d_out, B, L.d_in, L.d_out, L.act,
                               w.dense_split, s);

@@ -41,7 +41,9 @@ struct Layer {
   float* bh = nullptr;           // [H]
   int16_t* hslot = nullptr;      // [d_out] device: index of the node among the hash rows, or -1
   int32_t* hnodes = nullptr;     // [H] device copy of hash_nodes
-  uint16_t* W3 = nullptr;        // large fp32 layers: the weights as three interleaved bf16 parts [d_out][3 d_in]
+  uint16_t* Wt = nullptr;        // large layers: the weights as scaled fp16 parts for the tile kernel [d_out][wt_parts d_in]
+  int32_t* wt_exp = nullptr;     // [d_out] the rows' exponents
+  int wt_parts = 0;              // 2 (fp32 weights) or 1 (bf16 weights)
   int8_t* Whd = nullptr;         // the FreeHash rows as interleaved 7-bit digits [H][hash_int_digits() * d_in] (int8 cores)
   int32_t* ewh = nullptr;        // [H] their fixed-point exponents
   int H() const { return K * L; }
@@ -75,7 +77,7 @@ struct slonn_model {
   bool hash_first = false;        // hash nodes always computed, never selected (Section 3.4 variant)
   double hash_margin = 2.0;       // integer hash projections: |z| must exceed this many error bounds
   bool tables_refreshable = false; // slonn_build_tables keeps the NodeScore sums for slonn_tables_refresh
-  int dense_arith = 0;            // slonn_dense_forward: 0 fp32 matrix cores, 1 bf16 parts on the bf16 matrix cores
+  int dense_arith = 0;            // slonn_dense_forward: 0 fp32 matrix cores, 1 fp16 parts on the fp16 matrix cores
   int max_lds_bytes = 65536;      // per-workgroup LDS the device grants on request
   int n_cu = 256;
 };
@@ -267,6 +269,9 @@ int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t
 int launch_hash_project_int(const float* X, int ldx, const float* Wh, const int8_t* Wd, const int32_t* ew,
                             const float* bh, float* Z, int B, int H, int d, double margin, void* scratch,
                             hipStream_t s);
+// after launch_hash_project_int: the exponents of the rows of X it left in its scratch (largest magnitude of
+// row q below 2^e[q], INT_MIN for a row with a non-finite element)
+const int32_t* hash_int_row_exponents(const void* scratch, int B, int d);
 
 // keys + bucket lookup + merge for one layer.  yzero (nullable): [B][ldy] rows to clear.
 // ids: the lists, uint16_t entries when ids_narrow, else int32_t
@@ -322,20 +327,26 @@ int launch_gather_grouped(const void* W, int w_dtype, const float* bias, const f
                           void* scratch, int max_lds, int32_t** gflag_out, hipStream_t s);
 
 // Large batches of a large layer: the selected (query, node) pairs evaluated as masked dense
-// tiles on the bf16 matrix cores (activations as three bf16 parts).  Wp: w_parts == 3: fp32
-// weights through launch_split3; w_parts == 1: the layer's own bf16 rows.  Per 128 queries the
-// select kernel has decided whether the tiles serve them (RowBlocking::mask, ::flags, placed in
-// scratch by masked_tiles_buffers): *flags_out (device, one per 16 queries) is 1 where they do.
-// X: 16-byte aligned fp32 rows.  scratch: masked_tiles_workspace_bytes(B, n, d) bytes.
+// tiles on the fp16 matrix cores (rows scaled by powers of two, activations and fp32 weights as
+// two fp16 parts, bf16 weights as one).  Wp, wexp: the weights through launch_split_weights
+// (tile_weights_bytes(w_dtype, n, d) bytes, n exponents), w_parts 2 for fp32 weights, 1 for bf16.
+// Per 128 queries the select kernel has decided whether the tiles serve them (RowBlocking::mask,
+// ::flags, placed in scratch by masked_tiles_buffers): *flags_out (device, one per 16 queries) is
+// 1 where they do.  X: 16-byte aligned fp32 rows; xexp (nullable, device): their exponents
+// (largest magnitude of row q below 2^xexp[q], INT_MIN for a row with a non-finite element)
+// where a kernel before this one has found them.  scratch: masked_tiles_workspace_bytes(B, n, d)
+// bytes.
 bool masked_tiles_supported(int d, int n, int max_lds);
 size_t masked_tiles_workspace_bytes(int B, int n, int d);
 // where in that scratch the pair masks [B][(n + 31) / 32] and the per-16-queries flags live
 void masked_tiles_buffers(void* scratch, int B, int n, uint32_t** mask, int32_t** flags);
-int launch_split3(const float* X, int64_t ldx, int64_t rows, int d, uint16_t* out, hipStream_t s);
-int launch_dense_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx, float* Y,
-                       int ldy, int B, int d, int n, int act, void* scratch, hipStream_t s);
-int launch_masked_tiles(const uint16_t* Wp, int w_parts, const float* bias, const float* X, int ldx, float* Y,
-                        int ldy, int B, int d, int n, int act, void* scratch, int32_t** flags_out, hipStream_t s);
+size_t tile_weights_bytes(int w_dtype, int n, int d);
+int launch_split_weights(const void* W, int w_dtype, int n, int d, uint16_t* out, int32_t* wexp, hipStream_t s);
+int launch_dense_tiles(const uint16_t* Wp, int w_parts, const int32_t* wexp, const float* bias, const float* X, int ldx,
+                       float* Y, int ldy, int B, int d, int n, int act, void* scratch, hipStream_t s);
+int launch_masked_tiles(const uint16_t* Wp, int w_parts, const int32_t* wexp, const float* bias, const float* X, int ldx,
+                        const int32_t* xexp, float* Y, int ldy, int B, int d, int n, int act, void* scratch,
+                        int32_t** flags_out, hipStream_t s);
 
 // y[q][j] = act(W[j] . X[q] + b[j]) for the listed rows (active == nullptr: all n rows).
 // yc (nullable) receives the values in list order.

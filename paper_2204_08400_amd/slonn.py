@@ -187,7 +187,7 @@ def slonn_model_set_path(model: Model, path: int):
 
 
 def slonn_model_set_dense_arithmetic(model: Model, mode: int):
-    """0: fp32 matrix cores (default); 1: three bf16 parts on the bf16 matrix cores (see slonn.h)."""
+    """0: fp32 matrix cores (default); 1: two fp16 parts on the fp16 matrix cores (see slonn.h)."""
     _check(load().slonn_model_set_dense_arithmetic(model.h, int(mode)))
 
 

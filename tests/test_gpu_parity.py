@@ -134,9 +134,9 @@ def test_dense_forward_matches_oracle(rt, oracle):
 
 
 @pytest.mark.parametrize("w_dtype", [wl.W_F32, wl.W_BF16], ids=["f32", "bf16"])
-def test_dense_forward_in_bf16_parts_matches_oracle(rt, oracle, w_dtype):
-    """The full network in the sparse path's large-batch arithmetic (operands as three bf16 parts on
-    the bf16 matrix cores, slonn_model_set_dense_arithmetic) against the oracle's dense network, and
+def test_dense_forward_in_f16_parts_matches_oracle(rt, oracle, w_dtype):
+    """The full network in the sparse path's large-batch arithmetic (scaled operands as two fp16 parts
+    on the fp16 matrix cores, slonn_model_set_dense_arithmetic) against the oracle's dense network, and
     that the unmasked tiles really ran for the large layers."""
     from paper_2204_08400_amd import slonn
     dims = (512, 2048, 2048, 16)
@@ -150,10 +150,10 @@ def test_dense_forward_in_bf16_parts_matches_oracle(rt, oracle, w_dtype):
     prof = slonn.slonn_profile_end()
     assert prof["dense"][1] == len(layers), prof
     for l in range(len(layers)):
-        assert_close_rows(got["layers"][l].cpu().numpy(), ref[l], None, f"dense in bf16 parts, layer {l}", depth=l + 1)
+        assert_close_rows(got["layers"][l].cpu().numpy(), ref[l], None, f"dense in f16 parts, layer {l}", depth=l + 1)
     assert np.array_equal(got["argmax"].cpu().numpy(), oracle.argmax(ref[-1]))
     # input rows that are not 16-byte aligned: the tile kernel cannot fetch them in 16-byte pieces, a
-    # three-part copy is made first (split3_kernel) -- the same arithmetic, so the same bits
+    # two-part copy is made first (split_rows_kernel) -- the same arithmetic, so the same bits
     import torch
     buf = torch.empty(X.size + 1, dtype=torch.float32, device="cuda:0")
     xm = buf[1:].view(X.shape[0], X.shape[1])
@@ -165,10 +165,60 @@ def test_dense_forward_in_bf16_parts_matches_oracle(rt, oracle, w_dtype):
     # against the default arithmetic: the same results to fp32 rounding, not the same bits
     slonn.slonn_model_set_dense_arithmetic(g.model, 0)
     plain = g.dense_forward(X, layer_outs=True)
-    assert_close_rows(got["layers"][1].cpu().numpy(), plain["layers"][1].cpu().numpy(), None, "bf16 parts vs fp32 cores", depth=2)
+    assert_close_rows(got["layers"][1].cpu().numpy(), plain["layers"][1].cpu().numpy(), None, "f16 parts vs fp32 cores", depth=2)
     assert not np.array_equal(got["layers"][1].cpu().numpy(), plain["layers"][1].cpu().numpy())
     with pytest.raises(slonn.SlonnError):
         slonn.slonn_model_set_dense_arithmetic(g.model, 7)
+
+
+@pytest.mark.parametrize("w_dtype", [wl.W_F32, wl.W_BF16], ids=["f32", "bf16"])
+def test_tile_arithmetic_is_fp32_class_over_a_wide_dynamic_range(rt, oracle, w_dtype):
+    """The tile kernel scales every row by a power of two and carries operands as two fp16 parts.
+    Rows of the weights spread over 2^-25 .. 2^25 and the queries over 2^-30 .. 2^30, so that the
+    second layer's inputs span 2^50 within one row; a row of zeros; a row with a single non-zero element.  Against
+    the oracle's fp64 network the error must stay within the parity bound, and on the first layer
+    within that of a plain fp32 evaluation of the same dot products (one fp32 multiply and one fp32
+    add per element, in order)."""
+    from paper_2204_08400_amd import slonn
+    dims = (1024, 2048, 2048, 24)
+    layers = wl.make_mlp(dims, seed=51, w_dtype=w_dtype)
+    rng = np.random.default_rng(52)                     # (exponents only: no arithmetic of the method)
+    for l, lay in enumerate(layers[:2]):
+        k = rng.integers(-25, 26, size=lay.d_out).astype(np.float64)
+        w = wl.bf16_bits_to_f32(lay.W) if w_dtype == wl.W_BF16 else lay.W
+        w = (w.astype(np.float64) * np.exp2(k)[:, None]).astype(np.float32)      # exact: powers of two
+        lay.W = wl.f32_to_bf16_bits(w) if w_dtype == wl.W_BF16 else w
+        lay.bias = (lay.bias.astype(np.float64) * np.exp2(k)).astype(np.float32)
+        if w_dtype == wl.W_F32:       # (fp32 layers get their tile weights when they are activated layers)
+            lay.K, lay.L, lay.list_cap = 4, 6, lay.d_out
+            lay.hash_nodes = np.arange(24, dtype=np.int32)
+    X = make_queries(dims, 300, seed=53, kind="clip3")
+    X = (X.astype(np.float64) * np.exp2(rng.integers(-30, 31, size=300).astype(np.float64))[:, None]).astype(np.float32)
+    X[7] = 0.0
+    X[11] = 0.0
+    X[11, 333] = -1.5e-12
+    net = oracle.OracleNet(layers)
+    g = rt.Network(layers)
+    ref = net.dense_forward(X)
+    slonn.slonn_model_set_dense_arithmetic(g.model, 1)
+    slonn.slonn_profile_begin(16)
+    got = g.dense_forward(X, layer_outs=True)
+    prof = slonn.slonn_profile_end()
+    assert prof["dense"][1] == len(layers), prof         # every layer through the tiles
+    worst = [assert_close_rows(got["layers"][l].cpu().numpy(), ref[l], None, f"wide range, layer {l}", depth=l + 1)
+             for l in range(len(layers))]
+    assert np.array_equal(got["argmax"].cpu().numpy(), oracle.argmax(ref[-1]))
+    lay = layers[0]
+    w32 = wl.bf16_bits_to_f32(lay.W) if w_dtype == wl.W_BF16 else lay.W
+    plain = np.zeros((X.shape[0], lay.d_out), np.float32)
+    wt = np.ascontiguousarray(w32.T)
+    for k in range(lay.d_in):                                            # fp32 products, fp32 sums, in order
+        plain += X[:, k:k + 1] * wt[k][None, :]
+    plain = np.maximum(plain + lay.bias, np.float32(0.0))
+    scale = np.maximum(np.abs(ref[0]).max(axis=1, keepdims=True), 1e-300)
+    err_plain = float((np.abs(plain.astype(np.float64) - ref[0]) / scale).max())
+    _say(f"  wide range {('f32', 'bf16')[w_dtype == wl.W_BF16]}: tiles {worst} of the row maximum, plain fp32 {err_plain:.3e}")
+    assert worst[0] <= err_plain, (worst[0], err_plain)
 
 
 def test_keep_one_equals_dense_path(rt, oracle):
@@ -582,7 +632,7 @@ def test_config_c3_shape_sampled(rt, oracle):
 @pytest.mark.timeout(600)
 def test_config_c3_timed_batch_sampled(rt, oracle):
     """C3 at the batch bench.py times (1024 queries, path auto: integer hash, select, then per 128
-    queries either the masked tiles on the bf16 matrix cores - keep 0.1 and above - or the row-block
+    queries either the masked tiles on the fp16 matrix cores - keep 0.1 and above - or the row-block
     gather), over the keep sweep; the oracle computes the first and the last query of every group
     of 16 (128 queries: both sides of every 16- and 128-query boundary of the tiles and unions)."""
     from paper_2204_08400_amd import slonn
@@ -629,7 +679,7 @@ def test_config_c5_shape_sampled(rt, oracle):
 def test_config_c5_full_width_sampled(rt, oracle):
     """C5 at its real shape (1024-[8192]x6-1000, bf16 weights, K=12 L=64, batch 2048, per-query
     keep ~ U[0.02, 0.3]) in the launch configuration bench.py times (path auto: per-layer path,
-    masked tiles on the bf16 matrix cores for the 128-query tiles with large budgets, unions of
+    masked tiles on the fp16 matrix cores for the 128-query tiles with large budgets, unions of
     16 queries for the others).  Tables are built on the
     device from 256 inputs to keep the blob the oracle loads near 1 GB; the oracle then computes
     a sample of queries one by one."""
@@ -784,8 +834,8 @@ def test_argument_errors_on_device(rt, oracle):
                               "bf16-128x128-tiles", "f32-batch-200"])
 def test_grouped_evaluation_matches_oracle(rt, oracle, w_dtype, d, n, B):
     """Large batch on the per-layer path, evaluation across queries on the matrix cores.
-    fp32 rows of a multiple of 32 elements: masked 128 x 128 tiles on the bf16 cores (three
-    bf16 parts per operand), decided per 128 queries by their mean budget; other fp32 rows:
+    fp32 rows of a multiple of 32 elements: masked 128 x 128 tiles on the fp16 cores (two
+    fp16 parts per operand), decided per 128 queries by their mean budget; other fp32 rows:
     groups of 16 queries whose lists overlap, union of rows on the fp32 cores; bf16 weights:
     every group of 16 on the bf16 cores.  The rest stays on the per-query gather.  Same results
     either way."""
