@@ -26,7 +26,7 @@
 // from its projection).  A fifth digit and the pairs down to s + t = 3 of five (19 MFMAs per
 // block instead of 10) tightened BOUND by 2^8 and took twice the time.
 //
-//   slice_digits_kernel   one workgroup per row: row maximum -> e, four int8 digits per element,
+//   slice_digits_kernel   a row at a time per workgroup: row maximum -> e, four int8 digits per element,
 //                         interleaved per 16 elements (element k, digit s of row i at
 //                         i * 4 d + (k / 16) * 64 + 16 s + k % 16).
 //   hash_int_tiles_kernel 128 queries x 64 hash rows per workgroup and slice of the reduction
@@ -63,108 +63,125 @@ constexpr int HROW = HPIECES + 2;
 __host__ __device__ constexpr int hash_lds_col(int piece) { return (piece % DIGITS) * 4 + piece / DIGITS; }
 constexpr int BAD_ROW = INT_MIN;   // exponent entry of a row with a non-finite element
 
-// One workgroup per row; a thread holds up to MAXG groups of sixteen consecutive elements in
-// registers (d <= 4096 MAXG), so the row is read once: maximum, exponent, digits.  (MAXG sized to
-// the row: one group for rows of up to 4096 elements takes 32 vector registers instead of 78, C3
-// batch 1024 14.9 -> 10.4 us; rows of 8192 run as fast with two groups as with four.)
-template <int MAXG>
-__global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restrict__ X, int64_t ldx, int d,
-                                                    int8_t* __restrict__ out, int32_t* __restrict__ expo,
-                                                    int32_t* __restrict__ nonzeros) {
-  __shared__ float red[4];
-  __shared__ int red_nz[4];
-  __shared__ int s_e;
-  const int64_t row = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float* x = X + row * ldx;
-  const bool vec = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);
-  const int ngroups = d >> 4;                  // d is a multiple of 64
-  float xv[MAXG][16];
-#pragma unroll
-  for (int g = 0; g < MAXG; ++g) {
-    const int g16 = tid + 256 * g;
-    if (g16 < ngroups) {
-      const float* xp = x + 16 * g16;
-      if (vec) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float4 v = reinterpret_cast<const float4*>(xp)[j];
-          xv[g][4 * j] = v.x; xv[g][4 * j + 1] = v.y; xv[g][4 * j + 2] = v.z; xv[g][4 * j + 3] = v.w;
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 16; ++j) xv[g][j] = xp[j];
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 16; ++j) xv[g][j] = 0.0f;
-    }
-  }
-  float mx = 0.0f;
-  bool bad = false;
-  int nz = 0;
-#pragma unroll
-  for (int g = 0; g < MAXG; ++g)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const float v = fabsf(xv[g][j]);
-      if (!(v <= 3.0e38f)) bad = true;          // infinity or NaN
-      mx = fmaxf(mx, v);
-      nz += v != 0.0f ? 1 : 0;
-    }
-  if (bad) mx = __int_as_float(0x7f800000);
-  for (int o = 32; o > 0; o >>= 1) {
-    mx = fmaxf(mx, __shfl_xor(mx, o));
-    nz += __shfl_xor(nz, o);
-  }
-  if (lane == 0) { red[wave] = mx; red_nz[wave] = nz; }
-  __syncthreads();
-  if (tid == 0) {
-    if (nonzeros) nonzeros[row] = (red_nz[0] + red_nz[1]) + (red_nz[2] + red_nz[3]);
-    const float m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    int e = 0;
-    if (!(m <= 3.0e38f)) e = BAD_ROW;
-    else if (m > 0.0f) (void)frexpf(m, &e);   // m = f * 2^e with f in [0.5, 1): |x| < 2^e
-    s_e = e;
-    expo[row] = e;
-  }
-  __syncthreads();
-  const int e = s_e;
-  int8_t* o = out + (size_t)row * DIGITS * d;
-  const double scale = e == BAD_ROW ? 0.0 : ldexp(1.0, FRAC_BITS - e);
-  // per group of sixteen elements one 16-byte store per digit
-#pragma unroll
-  for (int g = 0; g < MAXG; ++g) {
-    const int g16 = tid + 256 * g;
-    if (g16 >= ngroups) break;
-    uint32_t packed[DIGITS][4];
-#pragma unroll
-    for (int s = 0; s < DIGITS; ++s)
-#pragma unroll
-      for (int w = 0; w < 4; ++w) packed[s][w] = 0u;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const double sv = (double)xv[g][j] * scale;          // exact: a power of two times an fp32 number
-      const int V = e == BAD_ROW ? 0 : (int)sv;            // truncation towards zero, |V| < 2^28
-      const uint32_t a = (uint32_t)(V < 0 ? -V : V);
-#pragma unroll
-      for (int s = 0; s < DIGITS; ++s) {
-        const int dig = (int)((a >> (7 * s)) & 127u);
-        const uint32_t byte = (uint32_t)(uint8_t)(int8_t)(V < 0 ? -dig : dig);
-        packed[s][j >> 2] |= byte << (8 * (j & 3));
-      }
-    }
-    u32x4* op = reinterpret_cast<u32x4*>(o + (size_t)g16 * (16 * DIGITS));
-#pragma unroll
-    for (int s = 0; s < DIGITS; ++s) op[s] = (u32x4){packed[s][0], packed[s][1], packed[s][2], packed[s][3]};
-  }
-}
-
 // Barrier that orders LDS traffic only: global loads issued before it stay in flight across it.
 __device__ __forceinline__ void lds_only_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// A workgroup of 256 threads takes rows blockIdx.x, blockIdx.x + gridDim.x, ...; a thread holds
+// up to MAXS slots of four consecutive elements of the row in registers (slot tid + 256 i: a
+// wavefront's load is 1 KiB of consecutive bytes), so the row is read once: maximum, exponent,
+// digits.  While one row is worked on the loads of the workgroup's next row are in flight (two
+// register sets), so that over the whole grid the reads of later rows overlap the writes of
+// earlier ones (one row per workgroup read everything first and wrote everything last: C5 45 us
+// per layer for 131 MB).  The four lanes of a quad hold the sixteen elements of one group: after a
+// 4 x 4 exchange inside the quad lane q holds digit q of all sixteen, one 16-byte store per lane,
+// consecutive over the wavefront.
+template <int MAXS>
+__global__ __launch_bounds__(256) void slice_digits_kernel(const float* __restrict__ X, int64_t ldx, int d,
+                                                    int8_t* __restrict__ out, int32_t* __restrict__ expo,
+                                                    int32_t* __restrict__ nonzeros, int64_t rows) {
+  static_assert(DIGITS == 4, "the quad exchange is written for four digits");
+  __shared__ float red[2][4];
+  __shared__ int red_nz[2][4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = tid & 3;
+  const bool vec = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);
+  const int nslots = d >> 2;                   // d is a multiple of 64: whole quads
+  auto load = [&](int64_t row, float4 (&xv)[MAXS]) {
+    const float* x = X + row * ldx;
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) {
+      const int slot = tid + 256 * i;
+      if (slot < nslots) {
+        if (vec) xv[i] = reinterpret_cast<const float4*>(x)[slot];
+        else xv[i] = make_float4(x[4 * slot], x[4 * slot + 1], x[4 * slot + 2], x[4 * slot + 3]);
+      } else {
+        xv[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      }
+    }
+  };
+  auto process = [&](int64_t row, const float4 (&xv)[MAXS], int par) {
+    float mx = 0.0f;
+    bool bad = false;
+    int nz = 0;
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) {
+      const float v4[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float v = fabsf(v4[j]);
+        if (!(v <= 3.0e38f)) bad = true;          // infinity or NaN
+        mx = fmaxf(mx, v);
+        nz += v != 0.0f ? 1 : 0;
+      }
+    }
+    if (bad) mx = __int_as_float(0x7f800000);
+    for (int o = 32; o > 0; o >>= 1) {
+      mx = fmaxf(mx, __shfl_xor(mx, o));
+      nz += __shfl_xor(nz, o);
+    }
+    if (lane == 0) { red[par][wave] = mx; red_nz[par][wave] = nz; }
+    lds_only_barrier();
+    // (every thread forms the exponent from the four partial maxima; red[par] is written again two
+    // rows on, with the next row's barrier in between)
+    const float m = fmaxf(fmaxf(red[par][0], red[par][1]), fmaxf(red[par][2], red[par][3]));
+    int e = 0;
+    if (!(m <= 3.0e38f)) e = BAD_ROW;
+    else if (m > 0.0f) (void)frexpf(m, &e);     // m = f * 2^e with f in [0.5, 1): |x| < 2^e
+    if (tid == 0) {
+      if (nonzeros) nonzeros[row] = (red_nz[par][0] + red_nz[par][1]) + (red_nz[par][2] + red_nz[par][3]);
+      expo[row] = e;
+    }
+    u32x4* o = reinterpret_cast<u32x4*>(out + (size_t)row * DIGITS * d);
+    const int sh = e == BAD_ROW ? 0 : FRAC_BITS - e;
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) {
+      const int slot = tid + 256 * i;
+      if (slot >= nslots) break;
+      const float v4[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+      uint32_t dg[DIGITS] = {0u, 0u, 0u, 0u};    // dg[s]: digit s of this slot's four elements, one byte each
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        // exact: a power of two times an fp32 number, below 2^28; then truncation towards zero
+        const int V = e == BAD_ROW ? 0 : (int)ldexpf(v4[j], sh);
+        const uint32_t a = (uint32_t)(V < 0 ? -V : V);
+#pragma unroll
+        for (int t = 0; t < DIGITS; ++t) {
+          const int dig = (int)((a >> (7 * t)) & 127u);
+          dg[t] |= (uint32_t)(uint8_t)(int8_t)(V < 0 ? -dig : dig) << (8 * j);
+        }
+      }
+      // 4 x 4 exchange inside the quad: lane q ends with dg[q] of lanes 0 .. 3 of its quad, in lane order
+      {
+        const uint32_t s0 = (q & 1) ? dg[0] : dg[1], s1 = (q & 1) ? dg[2] : dg[3];
+        const uint32_t r0 = __shfl_xor(s0, 1), r1 = __shfl_xor(s1, 1);
+        if (q & 1) { dg[0] = r0; dg[2] = r1; } else { dg[1] = r0; dg[3] = r1; }
+        // now lane q holds, for its pair of lanes (p, p + 1): dg[0], dg[1] = digit (q & 1) of p, p + 1; dg[2], dg[3] = digit 2 + (q & 1)
+        const uint32_t t0 = (q & 2) ? dg[0] : dg[2], t1 = (q & 2) ? dg[1] : dg[3];
+        const uint32_t u0 = __shfl_xor(t0, 2), u1 = __shfl_xor(t1, 2);
+        if (q & 2) { dg[0] = u0; dg[1] = u1; } else { dg[2] = u0; dg[3] = u1; }
+      }
+      o[slot] = (u32x4){dg[0], dg[1], dg[2], dg[3]};
+    }
+  };
+  float4 ra[MAXS], rb[MAXS];
+  int64_t row = blockIdx.x;
+  if (row >= rows) return;
+  load(row, ra);
+  while (true) {
+    int64_t next = row + gridDim.x;
+    if (next < rows) load(next, rb);
+    process(row, ra, 0);
+    if (next >= rows) break;
+    row = next;
+    next = row + gridDim.x;
+    if (next < rows) load(next, ra);
+    process(row, rb, 1);
+    if (next >= rows) break;
+    row = next;
+  }
 }
 
 __device__ __forceinline__ i32x4 as_i32x4(u32x4 v) { return __builtin_bit_cast(i32x4, v); }
@@ -447,12 +464,14 @@ const int32_t* hash_int_row_exponents(const void* scratch, int B, int d) {
 
 int launch_slice_digits(const float* X, int64_t ldx, int64_t rows, int d, int8_t* out, int32_t* expo,
                         int32_t* nonzeros, hipStream_t s) {
+  // two rows per workgroup once every compute unit has several workgroups either way
+  const unsigned grid = (unsigned)(rows >= 1024 ? (rows + 1) / 2 : rows);
   if (d <= 4096)
-    hipLaunchKernelGGL(slice_digits_kernel<1>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo, nonzeros);
+    hipLaunchKernelGGL(slice_digits_kernel<4>, dim3(grid), dim3(256), 0, s, X, ldx, d, out, expo, nonzeros, rows);
   else if (d <= 8192)
-    hipLaunchKernelGGL(slice_digits_kernel<2>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo, nonzeros);
+    hipLaunchKernelGGL(slice_digits_kernel<8>, dim3(grid), dim3(256), 0, s, X, ldx, d, out, expo, nonzeros, rows);
   else
-    hipLaunchKernelGGL(slice_digits_kernel<4>, dim3((unsigned)rows), dim3(256), 0, s, X, ldx, d, out, expo, nonzeros);
+    hipLaunchKernelGGL(slice_digits_kernel<16>, dim3(grid), dim3(256), 0, s, X, ldx, d, out, expo, nonzeros, rows);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
 }

@@ -671,15 +671,16 @@ namespace {
 // Masked tiles serve 128 queries when their mean list is at least this share of the layer
 // (below it the per-query gather, whose cost grows with batch x budget, is cheaper than the
 // tiles, whose cost per layer is about constant while they fit the chip once: measured
-// break-even on 4096-wide fp32 layers about 0.15 at batch 256, 0.12 at 512, 0.1 at 1024; at batch
-// 128 it lies near 0.35, and the two launches that find nothing to serve cost every smaller
-// budget 13 us per step: the tiles start at batch 160, where three rows of 64 x 64 tiles cost what
-// they cost at batch 192 and the per-query gather has lost the XCD-aware placement of its row
-// blocks).
-// bf16 weights (three MFMAs per block; the alternative is the union of 16 queries' rows on the
-// same cores, whose cost follows the union's size)
+// break-even on 4096-wide fp32 layers, ms per 8192 queries, gather at keep .02 / .04 / .06 / .08
+// against tiles: batch 256 4.4 / 5.4 / 6.4 / 7.7 against 5.9-6.1, batch 512 3.6 / 4.6 / 5.5 / 6.4
+// against 5.0, batch 1024 2.9 / 3.8 / 4.7 / 5.5 against 3.5-3.7; at batch 128 the two launches
+// that find nothing to serve cost every smaller budget 13 us per step: the tiles start at batch
+// 160, where three rows of 64 x 64 tiles cost what they cost at batch 192 and the per-query gather
+// has lost the XCD-aware placement of its row blocks).
+// bf16 weights (two MFMAs per block; the alternative is the union of 16 queries' rows on the
+// bf16 cores, whose cost follows the union's size)
 constexpr int BF16_TILES_MIN_KEEP_PERMILLE = 100;
-int masked_tiles_min_keep_permille(int B) { return B >= 1024 ? 100 : (B >= 512 ? 120 : (B >= 256 ? 150 : 200)); }
+int masked_tiles_min_keep_permille(int B) { return B >= 1024 ? 35 : (B >= 512 ? 50 : (B >= 256 ? 55 : 80)); }
 
 struct PolicyHook {
   const slonn_policy* p = nullptr;
