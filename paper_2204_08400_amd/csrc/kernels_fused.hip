@@ -9,7 +9,8 @@
 //
 // Per activated layer:
 //   hash    FreeHash projections (Def. 2) of the K*L sampled nodes, fp64 accumulation
-//           (the sign is a hash bit), 16 lanes per row;
+//           (the sign is a hash bit).  The hash rows are read input-major and only for the
+//           query's non-zero inputs: the bytes fall with the sparsity of the layer before;
 //   select  keys -> one bucket per table -> merge in rank-major, table-minor order.
 //           All 1024 threads take one slot each per round; a node's first occurrence is
 //           found with an LDS integer min over slot numbers (order-independent, hence
@@ -21,6 +22,8 @@
 //   gather  y_j = act(w_j . x + b_j) for the remaining active rows, four rows per 16-lane
 //           group in flight, written straight into the next layer's input in LDS (dropped
 //           nodes were zeroed there beforehand).
+#include <type_traits>
+
 #include "select_block.h"
 #include "slonn_internal.h"
 
@@ -30,6 +33,7 @@ namespace {
 constexpr int NT = 1024;                 // threads per workgroup
 constexpr int NW = NT / 64;              // wavefronts
 constexpr int GROUPS = NT / 16;          // 16-lane row groups
+constexpr size_t HASH_PART_BYTES = (size_t)NT * 4 * 8;   // partial hash projections: four doubles per thread
 
 __device__ __forceinline__ int budget_of(float keep, int n) {
   double m = floor((double)keep * (double)n + 0.5);
@@ -199,7 +203,7 @@ __device__ __forceinline__ void gather_rows(const void* __restrict__ W, const fl
 
 // LDS needed without the staging area of the in-kernel choice of k (a multiple of 16 bytes)
 __host__ __device__ inline size_t fused_lds_base(const FusedArgs& a) {
-  const size_t bytes = (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 +
+  const size_t bytes = HASH_PART_BYTES + (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 +
                        SelectShared<NT>::words_besides_prio * 4 + (64 + 4) * 4 + (size_t)a.max_na * 2;
   return (bytes + 15) & ~(size_t)15;
 }
@@ -207,7 +211,8 @@ __host__ __device__ inline size_t fused_lds_base(const FusedArgs& a) {
 template <bool POLICY>
 __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  float* xbuf0 = reinterpret_cast<float*>(smem);
+  double* hpart = reinterpret_cast<double*>(smem);                // [NT / (Hp / 4)][Hp] partial projections
+  float* xbuf0 = reinterpret_cast<float*>(smem + HASH_PART_BYTES);
   float* xbuf1 = xbuf0 + a.max_dim;
   float* zs = xbuf1 + a.max_dim;
   uint32_t* prio = reinterpret_cast<uint32_t*>(zs + a.max_H);
@@ -249,43 +254,94 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
       kq = a.keep[(size_t)q * a.keep_qstride + (size_t)li * a.keep_lstride];
 
     if (activated) {
-      // ---- hash: z_h = w_h . x + b_h in fp64, one 16-lane group per row ----
+      // ---- hash: z_h = w_h . x + b_h in fp64, over the non-zero inputs only ----
+      // (the input of a deeper layer is the sparse output of the layer before: at keep fraction k
+      // only k of the hash rows' bytes are read; a zero input adds nothing to an fp64 sum)
       const int H = Ly.K * Ly.L;
-      const int g = tid >> 4, l = tid & 15;
-      const int nv = d >> 2;
-      for (int h0 = g; h0 < H; h0 += 2 * GROUPS) {
-        const int h1 = (h0 + GROUPS < H) ? h0 + GROUPS : h0;
-        const float4* w0 = reinterpret_cast<const float4*>(Ly.Wh + (size_t)h0 * d);
-        const float4* w1 = reinterpret_cast<const float4*>(Ly.Wh + (size_t)h1 * d);
-        double acc0 = 0.0, acc1 = 0.0;
-#pragma unroll 4
-        for (int i = l; i < nv; i += 16) {
-          const float4 u = w0[i], v = w1[i];
-          const float4 x = reinterpret_cast<const float4*>(xs)[i];
-          const double x0 = x.x, x1 = x.y, x2 = x.z, x3 = x.w;
-          acc0 = fma((double)u.x, x0, acc0);
-          acc0 = fma((double)u.y, x1, acc0);
-          acc0 = fma((double)u.z, x2, acc0);
-          acc0 = fma((double)u.w, x3, acc0);
-          acc1 = fma((double)v.x, x0, acc1);
-          acc1 = fma((double)v.y, x1, acc1);
-          acc1 = fma((double)v.z, x2, acc1);
-          acc1 = fma((double)v.w, x3, acc1);
-        }
-        acc0 = reduce16(acc0);
-        acc1 = reduce16(acc1);
-        if (l == 0) {
-          const float z0 = (float)(acc0 + (double)Ly.bh[h0]);
-          zs[h0] = z0;
-          if (Ly.tap_z) Ly.tap_z[(size_t)q * H + h0] = z0;
-          if (h1 != h0) {
-            const float z1 = (float)(acc1 + (double)Ly.bh[h1]);
-            zs[h1] = z1;
-            if (Ly.tap_z) Ly.tap_z[(size_t)q * H + h1] = z1;
+      const int Hp = (H + 3) & ~3;
+      int32_t* nz = reinterpret_cast<int32_t*>(xn);      // indices of the non-zero inputs, ascending
+      int nnz = 0;
+      {
+        const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        int it = 0;
+        for (int base = 0; base < d; base += NT, ++it) {
+          const int i = base + tid;
+          const bool is_nz = i < d && xs[i] != 0.0f;
+          const unsigned long long votes = __ballot(is_nz);
+          int* cnt = sh.wave_cnt + (it & 1) * NW;          // two sets of counts: one barrier per round
+          if (lane == 0) cnt[wave] = __popcll(votes);
+          __syncthreads();
+          int before = 0, total = 0;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) {
+            const int c = cnt[w];
+            before += (w < wave) ? c : 0;
+            total += c;
           }
+          if (is_nz) nz[nnz + before + __popcll(votes & below)] = i;
+          nnz += total;
+        }
+        __syncthreads();
+      }
+      {
+        // thread (r, c): inputs r, r + R, ... of the list against hash columns 4c .. 4c + 3; a
+        // wavefront's loads cover whole rows of WhT, and all of a thread's loads are in flight
+        // together (up to eight).  Partial sums meet in LDS and are added in a fixed order.
+        const int CG = Hp >> 2, R = NT / CG;
+        const int r = tid / CG, c = tid - r * CG;
+        const float bias_h = tid < H ? Ly.bh[tid] : 0.0f;   // on its way while the rows are read
+        if (r < R) {
+          double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+          const float* wt = Ly.WhT + 4 * c;
+          auto rows = [&](auto uc) {
+            constexpr int U = decltype(uc)::value;
+            for (int i0 = r; i0 < nnz; i0 += R * U) {
+              float4 w[U];
+              float x[U];
+#pragma unroll
+              for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * R;
+                const int j = nz[i < nnz ? i : i0];
+                w[u] = *reinterpret_cast<const float4*>(wt + (size_t)j * Hp);
+                x[u] = i < nnz ? xs[j] : 0.0f;
+              }
+#pragma unroll
+              for (int u = 0; u < U; ++u) {
+                const double xd = x[u];
+                a0 = fma((double)w[u].x, xd, a0);
+                a1 = fma((double)w[u].y, xd, a1);
+                a2 = fma((double)w[u].z, xd, a2);
+                a3 = fma((double)w[u].w, xd, a3);
+              }
+            }
+          };
+          if (nnz > 4 * R) rows(std::integral_constant<int, 8>{});
+          else rows(std::integral_constant<int, 4>{});
+          double* p = hpart + (size_t)r * Hp + 4 * c;
+          p[0] = a0; p[1] = a1; p[2] = a2; p[3] = a3;
+        }
+        __syncthreads();
+        // R partial sums per projection, added in two steps: P threads per projection take R / P
+        // consecutive ones each, then one thread adds the P results (fixed order either way)
+        const int P = NT / Hp > 8 ? 8 : (NT / Hp < 1 ? 1 : NT / Hp);
+        const int per = (R + P - 1) / P;
+        const int h = tid % Hp, pp = tid / Hp;
+        double part = 0.0;
+        if (pp < P)
+          for (int rr = pp * per; rr < (pp + 1) * per && rr < R; ++rr) part += hpart[(size_t)rr * Hp + h];
+        __syncthreads();
+        if (pp < P) hpart[(size_t)pp * Hp + h] = part;
+        __syncthreads();
+        if (tid < H) {
+          double acc = 0.0;
+          for (int k = 0; k < P; ++k) acc += hpart[(size_t)k * Hp + tid];
+          const float z = (float)(acc + (double)bias_h);
+          zs[tid] = z;
+          if (Ly.tap_z) Ly.tap_z[(size_t)q * H + tid] = z;
         }
       }
-      // meanwhile: clear the next activation buffer and the first-occurrence map
+      // clear the next activation buffer (it held the list of non-zero inputs) and the
+      // first-occurrence map
       for (int i = tid; i < n; i += NT) { xn[i] = 0.0f; prio[i] = 0xFFFFFFFFu; hmap[i] = Ly.hslot[i]; }
       __syncthreads();
 
@@ -447,7 +503,23 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
   }
 }
 
+__global__ __launch_bounds__(256) void transpose_hash_rows_kernel(const float* __restrict__ Wh, int H, int d, int Hp,
+                                                                  float* __restrict__ WhT) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)d * Hp) return;
+  const int j = (int)(i / Hp), h = (int)(i - (size_t)j * Hp);
+  WhT[i] = h < H ? Wh[(size_t)h * d + j] : 0.0f;
+}
+
 }  // namespace
+
+int launch_transpose_hash_rows(const float* Wh, int H, int d, int Hp, float* WhT, hipStream_t s) {
+  const size_t total = (size_t)d * Hp;
+  hipLaunchKernelGGL(transpose_hash_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, Wh, H, d, Hp,
+                     WhT);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
 
 size_t fused_lds_bytes(const FusedArgs& a) {
   size_t bytes = fused_lds_base(a);

@@ -321,6 +321,19 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
       if (e != hipSuccess) set_error("copying FreeHash rows failed: %s", hipGetErrorString(e));
       return fail(SLONN_EHIP);
     }
+    // layers small enough for the whole-network kernel: the rows once more input-major
+    if ((size_t)L.d_in * L.d_out * (L.w_dtype == SLONN_F32 ? 4 : 2) <= ((size_t)8 << 20)) {
+      const int Hp = (H + 3) & ~3;
+      if ((e = hipMalloc(&L.WhT, (size_t)L.d_in * Hp * 4)) != hipSuccess) {
+        set_error("allocating the input-major FreeHash rows failed: %s", hipGetErrorString(e));
+        return fail(SLONN_EHIP);
+      }
+      if (launch_transpose_hash_rows(L.Wh, H, L.d_in, Hp, L.WhT, nullptr) != SLONN_OK ||
+          (e = hipStreamSynchronize(nullptr)) != hipSuccess) {
+        if (e != hipSuccess) set_error("transposing the FreeHash rows failed: %s", hipGetErrorString(e));
+        return fail(SLONN_EHIP);
+      }
+    }
     // node -> hash row (K*L <= 1024 fits 16 bits): lets the forward pass take a selected hash
     // node's output from its projection instead of fetching the row again
     std::vector<int16_t> hslot((size_t)L.d_out, (int16_t)-1);
@@ -388,6 +401,7 @@ bool fused_eligible(const slonn_model* m, const char** reason) {
     else if (((size_t)L.d_in * esz) % 16 != 0 || L.d_in % 4 != 0) why = "row length is not a multiple of 16 bytes";
     else if (reinterpret_cast<uintptr_t>(L.W) % 16 != 0) why = "weights are not 16-byte aligned";
     else if (l == nl - 1 && L.activated()) why = "Node Activator on the last layer";
+    else if (L.activated() && !L.WhT) why = "no input-major FreeHash rows";
   }
   if (!why) {
     FusedArgs a{};
@@ -477,6 +491,7 @@ int slonn_model_destroy(slonn_model* m) {
   if (!m) return SLONN_OK;
   for (Layer& L : m->layers) {
     if (L.Wh) (void)hipFree(L.Wh);
+    if (L.WhT) (void)hipFree(L.WhT);
     if (L.bh) (void)hipFree(L.bh);
     if (L.hslot) (void)hipFree(L.hslot);
     if (L.hnodes) (void)hipFree(L.hnodes);
@@ -782,7 +797,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
     for (int l = 0; l < nl; ++l) {
       const Layer& L = m->layers[l];
       FusedLayer& f = a.layer[l];
-      f.W = L.W; f.bias = L.bias; f.Wh = L.Wh; f.bh = L.bh; f.hslot = L.hslot; f.hnodes = L.hnodes;
+      f.W = L.W; f.bias = L.bias; f.WhT = L.WhT; f.bh = L.bh; f.hslot = L.hslot; f.hnodes = L.hnodes;
       f.d_in = L.d_in; f.d_out = L.d_out; f.act = L.act; f.w_dtype = L.w_dtype; f.K = L.K; f.L = L.L;
       if (L.activated()) {
         const TableSet* ts = t->for_layer(l);

@@ -39,6 +39,7 @@ struct Layer {
   // library-owned device copies of the FreeHash rows (always fp32) and their biases
   float* Wh = nullptr;           // [H][d_in]
   float* bh = nullptr;           // [H]
+  float* WhT = nullptr;          // small layers: the same rows input-major [d_in][(H + 3) & ~3] (zero-padded columns)
   int16_t* hslot = nullptr;      // [d_out] device: index of the node among the hash rows, or -1
   int32_t* hnodes = nullptr;     // [H] device copy of hash_nodes
   uint16_t* Wt = nullptr;        // large layers: the weights as scaled fp16 parts for the tile kernel [d_out][wt_parts d_in]
@@ -121,7 +122,7 @@ constexpr int FUSED_MAX_LAYERS = 8;
 struct FusedLayer {
   const void* W;
   const float* bias;
-  const float* Wh;
+  const float* WhT;                // FreeHash rows input-major [d_in][(H + 3) & ~3]
   const float* bh;
   const int16_t* hslot;
   const int32_t* hnodes;
@@ -388,6 +389,9 @@ bool policy_trained(const slonn_policy* p);
 // Wh[h][0..d) = row hnodes[h] of W widened to fp32, bh[h] = bias[hnodes[h]] (model set-up).
 int launch_gather_hash_rows(const void* W, int w_dtype, const float* bias, const int32_t* hnodes, int H, int d,
                             float* Wh, float* bh, hipStream_t s);
+// WhT[j][h] = Wh[h][j] for h < H, 0 for H <= h < Hp (model set-up; the whole-network kernel walks
+// the non-zero inputs of a query and reads one contiguous row of WhT per input).
+int launch_transpose_hash_rows(const float* Wh, int H, int d, int Hp, float* WhT, hipStream_t s);
 
 int launch_fill_iota(int32_t* idx, int stride, int32_t* cnt, int n, int B, hipStream_t s);
 

@@ -81,6 +81,10 @@ CASES = [
     dict(dims=(64, 384, 384, 10), K=4, L=8, kind="normal", B=65, w_dtype=wl.W_BF16),
     dict(dims=(75, 333, 21), K=3, L=64, kind="u01", B=5),                       # odd d: scalar path
     dict(dims=(256, 4096, 520, 10), K=6, L=12, kind="clip3", B=37, N_build=128),  # > 3 MiB matrices: row-block gather
+    # hash-row counts that are no multiple of four / that leave few inputs per thread group in the
+    # whole-network kernel's projection over non-zero inputs
+    dict(dims=(128, 1200, 400, 16), K=3, L=7, kind="u01", B=21),
+    dict(dims=(64, 1536, 1100, 10), K=10, L=60, kind="normal", B=9, N_build=128),
 ]
 
 
