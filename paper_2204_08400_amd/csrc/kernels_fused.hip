@@ -1,5 +1,5 @@
-// Whole-network SLO-aware forward pass for small and medium layers: one 1024-thread
-// workgroup walks one query through every layer (the "k% forward propagation" loop of
+// Whole-network SLO-aware forward pass for small and medium layers: one workgroup of 512 or
+// 1024 threads walks one query through every layer (the "k% forward propagation" loop of
 // Section 2.1: for each layer, ask the Node Activator for the active node ids, then
 // compute only those nodes).  The query's activations, hash projections, keys, the
 // de-duplication map and the active list live in LDS from the first layer to the last;
@@ -12,7 +12,7 @@
 //           (the sign is a hash bit).  The hash rows are read input-major and only for the
 //           query's non-zero inputs: the bytes fall with the sparsity of the layer before;
 //   select  keys -> one bucket per table -> merge in rank-major, table-minor order.
-//           All 1024 threads take one slot each per round; a node's first occurrence is
+//           Every thread takes a few slots per round (4096 a round); a node's first occurrence is
 //           found with an LDS integer min over slot numbers (order-independent, hence
 //           deterministic), survivors are compacted in slot order with a ballot and a
 //           two-level prefix sum, no atomic counters;
@@ -30,10 +30,12 @@
 namespace slonn {
 namespace {
 
-constexpr int NT = 1024;                 // threads per workgroup
-constexpr int NW = NT / 64;              // wavefronts
-constexpr int GROUPS = NT / 16;          // 16-lane row groups
-constexpr size_t HASH_PART_BYTES = (size_t)NT * 4 * 8;   // partial hash projections: four doubles per thread
+// Threads per workgroup: 1024 when a batch leaves most compute units free (one query per unit),
+// else 512, so that two queries share a unit and fill each other's memory waits: every phase of a
+// query is a dependent round trip to L2 or a stream bound by one unit's path to L2.
+constexpr int NT_MAX = 1024;
+constexpr size_t HASH_PART_BYTES = (size_t)NT_MAX * 4 * 8;   // partial hash projections: four doubles per thread
+template <int NT> struct SelectMu { static constexpr int value = SELECT_MU * (NT_MAX / NT); };   // 4096 slots per round
 
 __device__ __forceinline__ int budget_of(float keep, int n) {
   double m = floor((double)keep * (double)n + 0.5);
@@ -99,12 +101,13 @@ __device__ __forceinline__ float reduce64(float v) {
 
 // Few rows (a small output layer): one whole wavefront per row, four 16-byte steps in
 // flight, so that ten rows keep ten wavefronts busy instead of ten 16-lane groups.
-template <int WDT>
+template <int WDT, int NT>
 __device__ __forceinline__ void gather_few_rows(const void* __restrict__ W, const float* __restrict__ bias,
                                                 int d, const float* xs, const int32_t* list, int count,
                                                 int act, float* dst) {
   constexpr int ELEMS = (WDT == SLONN_F32) ? 4 : 8;
   constexpr int ESZ = (WDT == SLONN_F32) ? 4 : 2;
+  constexpr int NW = NT / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nv = d / ELEMS;
   for (int t = wave; t < count; t += NW) {
@@ -137,12 +140,13 @@ __device__ __forceinline__ void gather_few_rows(const void* __restrict__ W, cons
 // One pass of the row gather: every 16-lane group takes up to R rows (t0, t0 + GROUPS, ...),
 // all R row streams in flight together.  R is the same for the whole workgroup, so a pass
 // over fewer rows than 4 * GROUPS issues no loads for rows that do not exist.
-template <int WDT, int R>
+template <int WDT, int R, int NT>
 __device__ __forceinline__ void gather_pass(const void* __restrict__ W, const float* __restrict__ bias,
                                             int d, const float* xs, const int32_t* list, int t0, int count,
                                             int act, float* dst) {
   constexpr int ELEMS = (WDT == SLONN_F32) ? 4 : 8;
   constexpr int ESZ = (WDT == SLONN_F32) ? 4 : 2;
+  constexpr int GROUPS = NT / 16;          // 16-lane row groups
   const int l = threadIdx.x & 15;
   const int nv = d / ELEMS;
   int t[R], j[R];
@@ -177,12 +181,13 @@ __device__ __forceinline__ void gather_pass(const void* __restrict__ W, const fl
 }
 
 // rows listed in LDS (list == nullptr: rows 0..count-1) -> dst[j] = act(w_j . x + b_j)
-template <int WDT>
+template <int WDT, int NT>
 __device__ __forceinline__ void gather_rows(const void* __restrict__ W, const float* __restrict__ bias,
                                             int d, const float* xs, const int32_t* list, int count,
                                             int act, float* dst) {
+  constexpr int NW = NT / 64, GROUPS = NT / 16;
   if (count <= 2 * NW) {
-    gather_few_rows<WDT>(W, bias, d, xs, list, count, act, dst);
+    gather_few_rows<WDT, NT>(W, bias, d, xs, list, count, act, dst);
     return;
   }
   const int g = threadIdx.x >> 4;
@@ -190,13 +195,13 @@ __device__ __forceinline__ void gather_rows(const void* __restrict__ W, const fl
     const int left = count - base;                       // same for every thread
     const int t0 = base + g;
     if (left > 3 * GROUPS) {
-      if (t0 < count) gather_pass<WDT, 4>(W, bias, d, xs, list, t0, count, act, dst);
+      if (t0 < count) gather_pass<WDT, 4, NT>(W, bias, d, xs, list, t0, count, act, dst);
     } else if (left > 2 * GROUPS) {
-      if (t0 < count) gather_pass<WDT, 3>(W, bias, d, xs, list, t0, count, act, dst);
+      if (t0 < count) gather_pass<WDT, 3, NT>(W, bias, d, xs, list, t0, count, act, dst);
     } else if (left > GROUPS) {
-      if (t0 < count) gather_pass<WDT, 2>(W, bias, d, xs, list, t0, count, act, dst);
+      if (t0 < count) gather_pass<WDT, 2, NT>(W, bias, d, xs, list, t0, count, act, dst);
     } else {
-      if (t0 < count) gather_pass<WDT, 1>(W, bias, d, xs, list, t0, count, act, dst);
+      if (t0 < count) gather_pass<WDT, 1, NT>(W, bias, d, xs, list, t0, count, act, dst);
     }
   }
 }
@@ -204,12 +209,14 @@ __device__ __forceinline__ void gather_rows(const void* __restrict__ W, const fl
 // LDS needed without the staging area of the in-kernel choice of k (a multiple of 16 bytes)
 __host__ __device__ inline size_t fused_lds_base(const FusedArgs& a) {
   const size_t bytes = HASH_PART_BYTES + (size_t)(2 * a.max_dim + a.max_H) * 4 + (size_t)a.max_na * 8 +
-                       SelectShared<NT>::words_besides_prio * 4 + (64 + 4) * 4 + (size_t)a.max_na * 2;
+                       SelectShared<NT_MAX>::words_besides_prio * 4 + (64 + 4) * 4 + (size_t)a.max_na * 2;
   return (bytes + 15) & ~(size_t)15;
 }
 
-template <bool POLICY>
+template <bool POLICY, int NT>
 __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
+  constexpr int NW = NT / 64;
+  constexpr int MU = SelectMu<NT>::value;
   extern __shared__ __align__(16) unsigned char smem[];
   double* hpart = reinterpret_cast<double*>(smem);                // [NT / (Hp / 4)][Hp] partial projections
   float* xbuf0 = reinterpret_cast<float*>(smem + HASH_PART_BYTES);
@@ -217,12 +224,13 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
   float* zs = xbuf1 + a.max_dim;
   uint32_t* prio = reinterpret_cast<uint32_t*>(zs + a.max_H);
   int32_t* alist = reinterpret_cast<int32_t*>(prio + a.max_na);
-  SelectShared<NT> sh;
+  SelectShared<NT, MU> sh;
   sh.prio = prio;
   sh.s_off = reinterpret_cast<uint32_t*>(alist + a.max_na);
   sh.s_len = sh.s_off + 64;
   sh.wave_cnt = reinterpret_cast<int*>(sh.s_len + 64);
-  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + SELECT_MU * NW);
+  sh.s_misc = reinterpret_cast<uint32_t*>(sh.wave_cnt + MU * NW);
+  static_assert(MU * NW == SELECT_MU * (NT_MAX / 64), "LDS carve-up assumes the counts of the largest workgroup");
   uint32_t* pkey = sh.s_misc + 4;                                 // [64] keys for the choice of k
   float* s_keep = reinterpret_cast<float*>(pkey + 64);            // [4] keep fraction chosen in the kernel
   int16_t* hmap = reinterpret_cast<int16_t*>(s_keep + 4);         // [max_na] node -> hash row or -1
@@ -321,23 +329,27 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
           p[0] = a0; p[1] = a1; p[2] = a2; p[3] = a3;
         }
         __syncthreads();
-        // R partial sums per projection, added in two steps: P threads per projection take R / P
-        // consecutive ones each, then one thread adds the P results (fixed order either way)
-        const int P = NT / Hp > 8 ? 8 : (NT / Hp < 1 ? 1 : NT / Hp);
-        const int per = (R + P - 1) / P;
-        const int h = tid % Hp, pp = tid / Hp;
-        double part = 0.0;
-        if (pp < P)
-          for (int rr = pp * per; rr < (pp + 1) * per && rr < R; ++rr) part += hpart[(size_t)rr * Hp + h];
-        __syncthreads();
-        if (pp < P) hpart[(size_t)pp * Hp + h] = part;
-        __syncthreads();
-        if (tid < H) {
+        // R partial sums per projection, added in a fixed order: where the workgroup has several
+        // threads per projection, P of them take R / P consecutive sums each and one adds the results
+        const int P = NT / Hp > 8 ? 8 : NT / Hp;
+        int nsum = R;
+        if (P > 1) {
+          const int per = (R + P - 1) / P;
+          const int h = tid % Hp, pp = tid / Hp;
+          double part = 0.0;
+          if (pp < P)
+            for (int rr = pp * per; rr < (pp + 1) * per && rr < R; ++rr) part += hpart[(size_t)rr * Hp + h];
+          __syncthreads();
+          if (pp < P) hpart[(size_t)pp * Hp + h] = part;
+          __syncthreads();
+          nsum = P;
+        }
+        for (int h = tid; h < H; h += NT) {
           double acc = 0.0;
-          for (int k = 0; k < P; ++k) acc += hpart[(size_t)k * Hp + tid];
-          const float z = (float)(acc + (double)bias_h);
-          zs[tid] = z;
-          if (Ly.tap_z) Ly.tap_z[(size_t)q * H + tid] = z;
+          for (int k = 0; k < nsum; ++k) acc += hpart[(size_t)k * Hp + h];
+          const float z = (float)(acc + (double)(h == tid ? bias_h : Ly.bh[h]));
+          zs[h] = z;
+          if (Ly.tap_z) Ly.tap_z[(size_t)q * H + h] = z;
         }
       }
       // clear the next activation buffer (it held the list of non-zero inputs) and the
@@ -355,12 +367,12 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
             pkey[lane] = key;
           }
           __syncthreads();
-          // all L*G bucket sums (<= 1024) are fetched at once, one per thread ...
+          // all L*G bucket sums (<= 1024) are fetched at once ...
           const int G = a.pol.G, nb = 1 << Ly.K;
-          if (tid < Ly.L * G) {
-            const int b = tid / G, g = tid - b * G;
+          for (int t = tid; t < Ly.L * G; t += NT) {
+            const int b = t / G, g = t - b * G;
             const size_t bk = (size_t)b * nb + pkey[b];
-            pstage[tid] = a.pol.sum[bk * G + g];
+            pstage[t] = a.pol.sum[bk * G + g];
             if (g == 0) pcount[b] = a.pol.cnt[bk];
           }
           __syncthreads();
@@ -396,12 +408,12 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
       if (m < n) {
         // ---- keys, bucket lookup, merge: first msel distinct nodes in slot order ----
         if (Ly.ids_narrow)
-          select_block<NT, SELECT_MU, uint16_t>(zs, Ly.K, Ly.L, n, msel, Ly.dir, static_cast<const uint16_t*>(Ly.ids),
+          select_block<NT, MU, uint16_t>(zs, Ly.K, Ly.L, n, msel, Ly.dir, static_cast<const uint16_t*>(Ly.ids),
                                                 Ly.global_rank, sh,
                                                 Ly.tap_codes ? Ly.tap_codes + (size_t)q * Ly.L : nullptr, alist,
                                                 Hf ? hmap : nullptr);
         else
-          select_block<NT, SELECT_MU, int32_t>(zs, Ly.K, Ly.L, n, msel, Ly.dir, static_cast<const int32_t*>(Ly.ids),
+          select_block<NT, MU, int32_t>(zs, Ly.K, Ly.L, n, msel, Ly.dir, static_cast<const int32_t*>(Ly.ids),
                                                Ly.global_rank, sh,
                                                Ly.tap_codes ? Ly.tap_codes + (size_t)q * Ly.L : nullptr, alist,
                                                Hf ? hmap : nullptr);
@@ -464,9 +476,9 @@ __global__ __launch_bounds__(NT) void fused_forward_kernel(FusedArgs a) {
     // ---- evaluate the active rows into the next layer's input ----
     const int act = (Ly.act == SLONN_ACT_RELU) ? SLONN_ACT_RELU : SLONN_ACT_NONE;
     if (Ly.w_dtype == SLONN_F32)
-      gather_rows<SLONN_F32>(Ly.W, Ly.bias, d, xs, list, m, act, xn);
+      gather_rows<SLONN_F32, NT>(Ly.W, Ly.bias, d, xs, list, m, act, xn);
     else
-      gather_rows<SLONN_BF16>(Ly.W, Ly.bias, d, xs, list, m, act, xn);
+      gather_rows<SLONN_BF16, NT>(Ly.W, Ly.bias, d, xs, list, m, act, xn);
     __syncthreads();
 
     if (last) {
@@ -527,24 +539,28 @@ size_t fused_lds_bytes(const FusedArgs& a) {
   return bytes;
 }
 
-int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s) {
+namespace {
+template <bool POLICY, int NT>
+int launch_fused_nt(const FusedArgs& a, int B, size_t lds, hipStream_t s) {
+  if (lds > 65536)
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<POLICY, NT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL((fused_forward_kernel<POLICY, NT>), dim3(B), dim3(NT), lds, s, a);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+}  // namespace
+
+int launch_fused_forward(const FusedArgs& a, int B, int n_cu, int max_lds, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_FUSED, s);
   const size_t lds = fused_lds_bytes(a);
   if (lds > (size_t)max_lds)
     SLONN_FAIL(SLONN_EUNSUPPORTED, "fused path needs %zu bytes of LDS, device grants %d", lds, max_lds);
-  if (a.pol.sum) {
-    if (lds > 65536)
-      SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(fused_forward_kernel<true>, dim3(B), dim3(NT), lds, s, a);
-  } else {
-    if (lds > 65536)
-      SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(fused_forward_kernel<false>, dim3(B), dim3(NT), lds, s, a);
-  }
-  SLONN_HIP(hipGetLastError());
-  return SLONN_OK;
+  // 1024 threads per query while at most half the compute units are in use, else 512: two queries
+  // then share a unit (from this launch or from a batch in flight on another stream)
+  const bool wide = 2 * B <= n_cu;
+  if (a.pol.sum) return wide ? launch_fused_nt<true, 1024>(a, B, lds, s) : launch_fused_nt<true, 512>(a, B, lds, s);
+  return wide ? launch_fused_nt<false, 1024>(a, B, lds, s) : launch_fused_nt<false, 512>(a, B, lds, s);
 }
 
 }  // namespace slonn

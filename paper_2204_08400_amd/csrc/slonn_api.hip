@@ -824,7 +824,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       a.pol.layer = hook->layer;
     }
     a.Y = Y->dense; a.argmax = Y->argmax;
-    return launch_fused_forward(a, B, m->max_lds_bytes, s);
+    return launch_fused_forward(a, B, m->n_cu, m->max_lds_bytes, s);
   }
 
   Workspace w;

@@ -148,7 +148,7 @@ struct FusedArgs {
   int max_dim, max_H, max_na;      // LDS carve-up: activations, projections, active list
 };
 size_t fused_lds_bytes(const FusedArgs& a);
-int launch_fused_forward(const FusedArgs& a, int B, int max_lds, hipStream_t s);
+int launch_fused_forward(const FusedArgs& a, int B, int n_cu, int max_lds, hipStream_t s);
 
 // Arguments of the whole-network kernel for wide sparse-input models (ELL input, one small
 // hidden layer stored input-major, activated output layer).
