@@ -83,35 +83,38 @@ class Workload:
 
         self.xq = self.to_dev(self.X_query)
         self.nq_all = self.nq
-        self.set_batch(self.B, self.nq)
-        B = self.B
-        n_last = cfg.dims[-1]
         # Lanes: consecutive batches of a step go to HIP streams in turn (default priority), each with
         # its own workspace and output buffers, so that the launch- and latency-bound kernels of one
-        # batch (hash, select) run beside the matrix-core kernels of another.  Lane 0 is the current stream.
+        # batch (hash, select) run beside the matrix-core kernels of another.  Lane 0 is the current
+        # stream.  Two lanes for large batches, four for batches of up to 256 queries, whose kernels are
+        # chains of dependent memory round trips; the library is told how many batches are in flight.
         self.stream = torch.cuda.current_stream()
+        self.all_lanes = []
         self.lanes = []
-        ws_bytes = slonn.slonn_workspace_bytes(self.net.model, B)
-        for i in range(max(1, args.streams)):
-            lane = {"stream": self.stream if i == 0 else torch.cuda.Stream(device=dev),
-                    "ws": torch.empty(ws_bytes, dtype=torch.uint8, device=dev),
-                    "arg": torch.empty(B, dtype=torch.int32, device=dev),
-                    "yd": torch.empty((B, n_last), dtype=torch.float32, device=dev)}
-            if layers[-1].K > 0:      # activated output layer: compact (id, value) output, no dense row
-                lane["o"] = (torch.empty((B, n_last), dtype=torch.int32, device=dev),
-                             torch.empty((B, n_last), dtype=torch.float32, device=dev),
-                             torch.empty(B, dtype=torch.int32, device=dev))
-                lane["out"] = slonn.make_output(idx=lane["o"][0], val=lane["o"][1], cnt=lane["o"][2], stride=n_last,
-                                                argmax=lane["arg"])
-            else:
-                lane["o"] = torch.empty((B, n_last), dtype=torch.float32, device=dev)
-                lane["out"] = slonn.make_output(dense=lane["o"], argmax=lane["arg"])
-            self.lanes.append(lane)
+        self.set_batch(self.B, self.nq)
         self.out, self.ws, self.out_arg = self.lanes[0]["out"], self.lanes[0]["ws"], self.lanes[0]["arg"]
         self.mixed = None
         if cfg.keep_range:        # one keep fraction per query (mixed SLOs in one batch)
             self.mixed_host = wl.keep_uniform(self.nq, cfg.keep_range[0], cfg.keep_range[1], seed=6)
             self.mixed = torch.from_numpy(self.mixed_host).to(dev)
+
+    def _lane(self, i):
+        torch, slonn, dev, B = self.torch, self.slonn, self.dev, self.B
+        n_last = self.cfg.dims[-1]
+        lane = {"stream": self.stream if i == 0 else torch.cuda.Stream(device=dev),
+                "ws": torch.empty(slonn.slonn_workspace_bytes(self.net.model, B), dtype=torch.uint8, device=dev),
+                "arg": torch.empty(B, dtype=torch.int32, device=dev),
+                "yd": torch.empty((B, n_last), dtype=torch.float32, device=dev)}
+        if self.layers[-1].K > 0:      # activated output layer: compact (id, value) output, no dense row
+            lane["o"] = (torch.empty((B, n_last), dtype=torch.int32, device=dev),
+                         torch.empty((B, n_last), dtype=torch.float32, device=dev),
+                         torch.empty(B, dtype=torch.int32, device=dev))
+            lane["out"] = slonn.make_output(idx=lane["o"][0], val=lane["o"][1], cnt=lane["o"][2], stride=n_last,
+                                            argmax=lane["arg"])
+        else:
+            lane["o"] = torch.empty((B, n_last), dtype=torch.float32, device=dev)
+            lane["out"] = slonn.make_output(dense=lane["o"], argmax=lane["arg"])
+        return lane
 
     def set_batch(self, B, nq=0):
         """the query set (its first nq queries) cut into batches of B, ragged tail included; buffers and
@@ -119,6 +122,11 @@ class Workload:
         slonn, xq = self.slonn, self.xq
         assert B <= self.B
         self.batch = B
+        self.n_streams = self.args.streams if self.args.streams > 0 else (4 if B <= 256 else 2)
+        while len(self.all_lanes) < self.n_streams:
+            self.all_lanes.append(self._lane(len(self.all_lanes)))
+        self.lanes = self.all_lanes[:self.n_streams]
+        slonn.slonn_model_set_batches_in_flight(self.net.model, self.n_streams)
         self.nq = min(nq or self.nq_all, self.nq_all)
         self.sizes = [min(B, self.nq - s) for s in range(0, self.nq, B)]
         self.batches = []
@@ -331,8 +339,9 @@ def main():
                          "reports the union of 16 / 128 queries' active rows over one list, and the rate, both ways")
     ap.add_argument("--input-clusters", type=int, default=0,
                     help="inputs with class structure instead of the configuration's (study of --cluster-by-key only)")
-    ap.add_argument("--streams", type=int, default=2,
-                    help="HIP streams the batches of a step are dealt to in turn (each with its own workspace)")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="HIP streams the batches of a step are dealt to in turn (each with its own workspace); "
+                         "0: two for batches above 256 queries, four up to that")
     ap.add_argument("--markers", action="store_true",
                     help="launch a marker kernel (nextafter) right before and after the timed steps, for profilers")
     ap.add_argument("--no-profile", action="store_true", help="skip the event-instrumented pass (profiler runs)")
@@ -390,7 +399,7 @@ def main():
     head_config = {"workload": f"{args.config}: MLP {'-'.join(map(str, cfg.dims))}, K={cfg.K} L={cfg.L} on "
                                f"{len(cfg.hashed_layers)} layers", "batch": B, "keep": keep_label,
                    "queries_per_step": w.nq, "batches_per_step": len(w.sizes), "table_training_inputs": w.n_build,
-                   "streams": max(1, args.streams),
+                   "streams": w.n_streams,
                    "path": args.path, "hash_nodes_always_active": bool(args.hash_nodes_always_active)}
     traffic_key = f"{args.config}_B{B}_keep{head_keep if head_keep is not None else 'mixed'}"
     extra = {"ms_per_step_median": round(float(np.median(per)), 4),
@@ -572,7 +581,7 @@ def main():
                            "nominal_gathered_GBps": round(w.gathered_bytes_per_step(None) * 3 / s_ / 1e9, 1),
                            "sparse_over_best_dense": round(3 * w.nq / s_ / best, 3)}
             r["config"] = {"workload": head_config["workload"], "batch": b_, "keep": keep_label,
-                           "queries_per_step": w.nq, "streams": max(1, args.streams)}
+                           "queries_per_step": w.nq, "streams": w.n_streams}
             others[f"{args.config}_B{b_}"] = r
             log(f"{args.config} batch {b_}: {r}")
         del w
@@ -586,7 +595,7 @@ def main():
                 r = sweep_and_dense(wk, 3, 1, wk.cfg.keeps)
                 r["config"] = {"workload": f"{name}: MLP {'-'.join(map(str, wk.cfg.dims))}, K={wk.cfg.K} L={wk.cfg.L}",
                                "batch": b_, "queries_per_step": wk.nq, "table_training_inputs": wk.n_build,
-                               "streams": max(1, args.streams)}
+                               "streams": wk.n_streams}
                 others[f"{name}_B{b_}"] = r
                 log(f"{name} batch {b_}: {r}")
             del wk

@@ -152,6 +152,14 @@ int slonn_model_destroy(slonn_model* m);
 enum { SLONN_PATH_AUTO = 0, SLONN_PATH_LAYERS = 1, SLONN_PATH_FUSED = 2 };
 int slonn_model_set_path(slonn_model* m, int path);
 
+/* How many batches the caller keeps in flight on this device at a time (calls on n streams, each
+ * with its own workspace and outputs).  The whole-network kernels give a query a workgroup of 1024
+ * threads while the queries in flight (n times the batch) leave compute units free, and one of 512
+ * threads once they do not, so that two queries share a unit and one's memory waits are the
+ * other's work.  A hint: results do not depend on it.  n >= 1 (default 1).
+ * EINVAL: null model, n < 1.                                                                    */
+int slonn_model_set_batches_in_flight(slonn_model* m, int n);
+
 /* Large batches compute the FreeHash projections on the int8 matrix cores from fixed-point
  * digits of the operands; a projection counts as certain when |z| exceeds `margin` times a
  * rigorous bound on what the fixed-point form loses, every other one is recomputed in fp64.

@@ -551,14 +551,14 @@ int launch_fused_nt(const FusedArgs& a, int B, size_t lds, hipStream_t s) {
 }
 }  // namespace
 
-int launch_fused_forward(const FusedArgs& a, int B, int n_cu, int max_lds, hipStream_t s) {
+int launch_fused_forward(const FusedArgs& a, int B, int in_flight, int n_cu, int max_lds, hipStream_t s) {
   ProfScope prof_(SLONN_PROF_FUSED, s);
   const size_t lds = fused_lds_bytes(a);
   if (lds > (size_t)max_lds)
     SLONN_FAIL(SLONN_EUNSUPPORTED, "fused path needs %zu bytes of LDS, device grants %d", lds, max_lds);
-  // 1024 threads per query while at most half the compute units are in use, else 512: two queries
-  // then share a unit (from this launch or from a batch in flight on another stream)
-  const bool wide = 2 * B <= n_cu;
+  // 1024 threads per query while the queries in flight use at most half the compute units, else
+  // 512: two queries then share a unit (from this launch or from a batch on another stream)
+  const bool wide = 2 * (long long)B * in_flight <= n_cu;
   if (a.pol.sum) return wide ? launch_fused_nt<true, 1024>(a, B, lds, s) : launch_fused_nt<true, 512>(a, B, lds, s);
   return wide ? launch_fused_nt<false, 1024>(a, B, lds, s) : launch_fused_nt<false, 512>(a, B, lds, s);
 }

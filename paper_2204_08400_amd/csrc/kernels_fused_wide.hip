@@ -23,9 +23,7 @@
 namespace slonn {
 namespace {
 
-constexpr int NT = 1024;
-constexpr int NW = NT / 64;
-constexpr int GROUPS = NT / 16;
+constexpr int NT_MAX = 1024;       // threads per workgroup: 1024 or 512
 constexpr int VALS_LDS = 4096;     // lists up to this length keep their logits in LDS
 
 __device__ __forceinline__ int budget_of(float keep, int n) {
@@ -82,7 +80,7 @@ __device__ __forceinline__ float reduce_group(float v) {
 
 // R rows per LPR-lane group in flight: vals[t] = w_{list[t]} . x + b for t = t0 + k * (NT / LPR).
 // Short rows (a few hundred bytes) take 8 lanes so that a pass covers twice as many rows.
-template <int R, int LPR>
+template <int R, int LPR, int NT>
 __device__ __forceinline__ void gather_pass(const void* __restrict__ W, int w_dtype,
                                             const float* __restrict__ bias, int d, const float* xs,
                                             const int32_t* list, int t0, int count, float* vals) {
@@ -115,7 +113,7 @@ __device__ __forceinline__ void gather_pass(const void* __restrict__ W, int w_dt
     if (l == k && t[k] < count) vals[t[k]] = acc[k] + bias[j[k]];
 }
 
-template <int LPR>
+template <int LPR, int NT>
 __device__ __forceinline__ void gather_list(const void* __restrict__ W, int w_dtype,
                                             const float* __restrict__ bias, int d, const float* xs,
                                             const int32_t* list, int total, float* vals) {
@@ -126,15 +124,17 @@ __device__ __forceinline__ void gather_list(const void* __restrict__ W, int w_dt
     const int left = total - base;
     const int t0 = base + g;
     if (t0 >= total) continue;
-    if (LPR == 16 && left > 4 * NG) gather_pass<6, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
-    else if (left > 3 * NG) gather_pass<4, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
-    else if (left > 2 * NG) gather_pass<3, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
-    else if (left > NG) gather_pass<2, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
-    else gather_pass<1, LPR>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+    if (LPR == 16 && left > 4 * NG) gather_pass<6, LPR, NT>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+    else if (left > 3 * NG) gather_pass<4, LPR, NT>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+    else if (left > 2 * NG) gather_pass<3, LPR, NT>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+    else if (left > NG) gather_pass<2, LPR, NT>(W, w_dtype, bias, d, xs, list, t0, total, vals);
+    else gather_pass<1, LPR, NT>(W, w_dtype, bias, d, xs, list, t0, total, vals);
   }
 }
 
+template <int NT>
 __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
+  constexpr int NW = NT / 64, GROUPS = NT / 16;
   extern __shared__ __align__(16) unsigned char smem[];
   // carve-up (every region a multiple of 16 bytes)
   float* part = reinterpret_cast<float*>(smem);                       // [NT][4] partial hidden sums
@@ -294,8 +294,8 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
   float* vals = total <= VALS_LDS ? lvals : gv;
   {
     const int32_t* lp = (m == n2) ? nullptr : list;
-    if (n1 <= 256) gather_list<8>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, total, vals);
-    else gather_list<16>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, total, vals);
+    if (n1 <= 256) gather_list<8, NT>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, total, vals);
+    else gather_list<16, NT>(a.W1, a.w1_dtype, a.b1, n1, xs, lp, total, vals);
   }
   __syncthreads();
 
@@ -346,23 +346,39 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
 
 }  // namespace
 
-size_t fused_wide_lds_bytes(const FusedWideArgs& a) {
+namespace {
+template <int NT>
+size_t wide_lds_bytes(const FusedWideArgs& a) {
   const size_t words = ((size_t)((a.n2 + 31) >> 5) + 3) & ~(size_t)3;
-  return (size_t)NT * 16 + ((size_t)a.n1p + a.Hp + 2 * (size_t)a.ellp + 2 * NW + VALS_LDS) * 4 +
+  return (size_t)NT * 16 + ((size_t)a.n1p + a.Hp + 2 * (size_t)a.ellp + 2 * (NT / 64) + VALS_LDS) * 4 +
          (words + SelectSharedWide<NT>::words_besides_bitmap) * 4;
 }
+}  // namespace
 
-int launch_fused_wide(const FusedWideArgs& a, int B, int max_lds, hipStream_t s) {
-  ProfScope prof_(SLONN_PROF_FUSED, s);
-  const size_t lds = fused_wide_lds_bytes(a);
-  if (lds > (size_t)max_lds)
-    SLONN_FAIL(SLONN_EUNSUPPORTED, "wide fused path needs %zu bytes of LDS, device grants %d", lds, max_lds);
+size_t fused_wide_lds_bytes(const FusedWideArgs& a) { return wide_lds_bytes<NT_MAX>(a); }
+
+namespace {
+template <int NT>
+int launch_wide_nt(const FusedWideArgs& a, int B, size_t lds, hipStream_t s) {
   if (lds > 65536)
-    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fused_wide_kernel),
+    SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fused_wide_kernel<NT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(fused_wide_kernel, dim3(B), dim3(NT), lds, s, a);
+  hipLaunchKernelGGL(fused_wide_kernel<NT>, dim3(B), dim3(NT), lds, s, a);
   SLONN_HIP(hipGetLastError());
   return SLONN_OK;
+}
+}  // namespace
+
+int launch_fused_wide(const FusedWideArgs& a, int B, int in_flight, int n_cu, int max_lds, hipStream_t s) {
+  ProfScope prof_(SLONN_PROF_FUSED, s);
+  // 1024 threads per query while every query in flight can have a compute unit to itself, else 512
+  // (C4, batch 128: one / two / four batches in flight 4.7 / 9.0 / 9.6 M queries/s with 1024
+  // threads, 4.1 / 7.5 / 13.1 M with 512)
+  const bool wide = (long long)B * in_flight <= n_cu;
+  const size_t lds = wide ? wide_lds_bytes<1024>(a) : wide_lds_bytes<512>(a);
+  if (lds > (size_t)max_lds)
+    SLONN_FAIL(SLONN_EUNSUPPORTED, "wide fused path needs %zu bytes of LDS, device grants %d", lds, max_lds);
+  return wide ? launch_wide_nt<1024>(a, B, lds, s) : launch_wide_nt<512>(a, B, lds, s);
 }
 
 }  // namespace slonn

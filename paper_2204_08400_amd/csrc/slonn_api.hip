@@ -467,6 +467,13 @@ int slonn_model_set_hash_margin(slonn_model* m, double margin) {
   return SLONN_OK;
 }
 
+int slonn_model_set_batches_in_flight(slonn_model* m, int n) {
+  if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
+  if (n < 1) SLONN_FAIL(SLONN_EINVAL, "batches in flight must be at least 1");
+  m->batches_in_flight = n;
+  return SLONN_OK;
+}
+
 int slonn_model_set_tables_refreshable(slonn_model* m, int on) {
   if (!m) SLONN_FAIL(SLONN_EINVAL, "model is null");
   m->tables_refreshable = on != 0;
@@ -768,7 +775,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
     a.tap_codes = taps && taps->codes ? taps->codes[1] : nullptr;
     a.tap_z = taps && taps->z ? taps->z[1] : nullptr;
     a.tap_out0 = taps && taps->layer_out ? taps->layer_out[0] : nullptr;
-    rc = launch_fused_wide(a, B, m->max_lds_bytes, s);
+    rc = launch_fused_wide(a, B, m->batches_in_flight, m->n_cu, m->max_lds_bytes, s);
     if (rc) return rc;
     if (tap_idx && a.list != tap_idx)
       SLONN_HIP(hipMemcpy2DAsync(tap_idx, (size_t)O.d_out * 4, a.list, (size_t)a.list_stride * 4,
@@ -824,7 +831,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
       a.pol.layer = hook->layer;
     }
     a.Y = Y->dense; a.argmax = Y->argmax;
-    return launch_fused_forward(a, B, m->n_cu, m->max_lds_bytes, s);
+    return launch_fused_forward(a, B, m->batches_in_flight, m->n_cu, m->max_lds_bytes, s);
   }
 
   Workspace w;

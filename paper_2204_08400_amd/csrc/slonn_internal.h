@@ -78,6 +78,7 @@ struct slonn_model {
   bool hash_first = false;        // hash nodes always computed, never selected (Section 3.4 variant)
   double hash_margin = 2.0;       // integer hash projections: |z| must exceed this many error bounds
   bool tables_refreshable = false; // slonn_build_tables keeps the NodeScore sums for slonn_tables_refresh
+  int batches_in_flight = 1;      // batches the caller keeps in flight on the device (sizes the whole-network workgroups)
   int dense_arith = 0;            // slonn_dense_forward: 0 fp32 matrix cores, 1 fp16 parts on the fp16 matrix cores
   int max_lds_bytes = 65536;      // per-workgroup LDS the device grants on request
   int n_cu = 256;
@@ -148,7 +149,7 @@ struct FusedArgs {
   int max_dim, max_H, max_na;      // LDS carve-up: activations, projections, active list
 };
 size_t fused_lds_bytes(const FusedArgs& a);
-int launch_fused_forward(const FusedArgs& a, int B, int n_cu, int max_lds, hipStream_t s);
+int launch_fused_forward(const FusedArgs& a, int B, int in_flight, int n_cu, int max_lds, hipStream_t s);
 
 // Arguments of the whole-network kernel for wide sparse-input models (ELL input, one small
 // hidden layer stored input-major, activated output layer).
@@ -171,7 +172,7 @@ struct FusedWideArgs {
   uint32_t* tap_codes; float* tap_z; float* tap_out0;
 };
 size_t fused_wide_lds_bytes(const FusedWideArgs& a);
-int launch_fused_wide(const FusedWideArgs& a, int B, int max_lds, hipStream_t s);
+int launch_fused_wide(const FusedWideArgs& a, int B, int in_flight, int n_cu, int max_lds, hipStream_t s);
 
 // Active lists regrouped by weight-row block, so that the workgroups running at the same
 // time read the same few megabytes of the weight matrix (L2-sized blocks of rows).

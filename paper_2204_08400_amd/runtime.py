@@ -58,6 +58,10 @@ class Network:
         """Hash nodes always computed and never selected (see slonn.h)."""
         slonn.slonn_model_set_hash_nodes_always_active(self.model, on)
 
+    def set_batches_in_flight(self, n: int):
+        """Batches kept in flight on separate streams (a hint, see slonn.h)."""
+        slonn.slonn_model_set_batches_in_flight(self.model, n)
+
     def set_hash_margin(self, margin: float):
         """Certification margin of the integer hash projections (diagnostic, see slonn.h)."""
         slonn.slonn_model_set_hash_margin(self.model, margin)

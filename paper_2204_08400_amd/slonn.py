@@ -36,6 +36,7 @@ EXPORTS = [
     "slonn_activation_variance", "slonn_sample_hash_nodes", "slonn_model_set_hash_margin",
     "slonn_sparse_forward_static", "slonn_model_set_dense_arithmetic",
     "slonn_sample_hash_nodes_device", "slonn_model_set_tables_refreshable", "slonn_tables_refresh",
+    "slonn_model_set_batches_in_flight",
 ]
 STATIC_SCRATCH_BYTES = 64 << 20
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused", "tiles")
@@ -184,6 +185,11 @@ def slonn_model_create(layers: Sequence[dict]) -> Model:
 
 def slonn_model_set_path(model: Model, path: int):
     _check(load().slonn_model_set_path(model.h, int(path)))
+
+
+def slonn_model_set_batches_in_flight(model: Model, n: int):
+    """Batches the caller keeps in flight on the device (a hint that sizes workgroups, see slonn.h)."""
+    _check(load().slonn_model_set_batches_in_flight(model.h, int(n)))
 
 
 def slonn_model_set_dense_arithmetic(model: Model, mode: int):

@@ -293,6 +293,47 @@ def test_ell_input_and_activated_softmax_output(rt, oracle, n_out, path):
             assert abs(got["val"][q, :c].sum() - 1.0) < 1e-4
 
 
+def test_batches_in_flight_hint_changes_workgroups_not_results(rt, oracle):
+    """slonn_model_set_batches_in_flight sizes the workgroups of the whole-network kernels (1024
+    threads per query, or 512 so that two queries share a compute unit).  Both sizes must match the
+    oracle, for the dense-input kernel and for the wide sparse-input one."""
+    import copy
+    from paper_2204_08400_amd import slonn
+    dims = (96, 1000, 640, 12)
+    layers, net, _ = make_case(oracle, dims, 6, 10, seed=23, last_act=wl.ACT_SOFTMAX)
+    g = _gpu_net(rt, layers, net, path="fused")
+    X = make_queries(dims, 40, seed=6)
+    keep = wl.keep_uniform(40, 0.01, 0.9, 8)
+    ref = net.sparse_forward(X, keep)
+    for n in (1, 64):
+        _say(f"dense-input whole-network kernel, {n} batches in flight")
+        g.set_batches_in_flight(n)
+        compare_sparse(to_numpy_result(g.sparse_forward(X, _keep_tensor(keep), taps=True)), ref, layers, f"in flight {n}")
+    with pytest.raises(slonn.SlonnError):
+        g.set_batches_in_flight(0)
+    dims = (5000, 128, 50000)
+    layers, net, _ = make_case(oracle, dims, 8, 12, seed=31, hashed=[1], cap=400, last_act=wl.ACT_SOFTMAX,
+                               ell_nnz=40, N_build=300)
+    glayers = [copy.copy(l) for l in layers]
+    glayers[0].W = np.ascontiguousarray(layers[0].W.T)
+    g = rt.Network(glayers, first_layer_rows_are_inputs=True)
+    g.import_tables(net.export_tables())
+    g.set_path("fused")
+    X = make_queries(dims, 50, seed=7, ell_nnz=40)
+    keep = wl.keep_uniform(50, 0.0001, 0.3, 3)
+    ref = net.sparse_forward(X, keep)
+    for n in (1, 64):
+        _say(f"wide sparse-input whole-network kernel, {n} batches in flight")
+        g.set_batches_in_flight(n)
+        got = to_numpy_result(g.sparse_forward(X, _keep_tensor(keep), taps=True, compact=True))
+        compare_sparse(got, ref, layers, f"ELL in flight {n}")
+        ok = ~ref["layers"][1]["tie"]
+        for q in np.nonzero(ok)[0]:
+            c = ref["layers"][1]["cnt"][q]
+            assert got["cnt"][q] == c
+            assert np.array_equal(got["idx"][q, :c], ref["layers"][1]["active"][q, :c])
+
+
 @pytest.mark.parametrize("path", ["layers", "fused"])
 def test_edge_cases(rt, oracle, path):
     import torch
