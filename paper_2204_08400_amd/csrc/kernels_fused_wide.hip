@@ -1,16 +1,18 @@
 // Whole-network kernel for the wide sparse-input models of Table 1 (Wiki10, AmazonCat-13K,
 // Delicious-200K: ~10^5 sparse input features -> one small hidden layer -> 10^4..10^5 labels,
-// Node Activator on the output layer only, Section 4 "Model Pruning").  One 1024-thread
-// workgroup carries one query through both layers in one launch:
+// Node Activator on the output layer only, Section 4 "Model Pruning").  One workgroup
+// of 1024 or 512 threads carries one query through both layers in one launch:
 //
 //   hidden  y1 = act(sum_t val[t] * W0[idx[t]][:] + b0): the first layer is stored input-major,
 //           so every non-zero contributes one contiguous row; 16-byte column chunks across
 //           lanes, the non-zeros split over lane groups, partial sums added in LDS in a fixed
 //           order.  y1 stays in LDS.
-//   hash    FreeHash projections of the output layer's K*L sampled nodes on y1 (Def. 2), fp64.
+//   hash    FreeHash projections of the output layer's K*L sampled nodes on y1 (Def. 2), fp64,
+//           over the non-zero hidden activations only, the hash rows read input-major.
 //   select  keys -> buckets -> first m distinct nodes (Fig. 2 steps 3-4) with one bit per node
-//           in LDS (select_block.h, wide variant); the list goes to global memory (the caller's
-//           compact id array), so its length is not limited by LDS.
+//           in LDS (select_block.h, wide variant); the list is built in LDS while it fits there,
+//           else straight in global memory (the caller's compact id array), so its length is
+//           not limited by LDS.
 //   gather  logits of the listed nodes only, 16 lanes per row, four rows in flight.
 //   tail    argmax and softmax over the computed nodes (Section 2.1), compact (id, value)
 //           output; the dense row is written only when the caller asks for it.
@@ -210,50 +212,73 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
     __syncthreads();
   }
 
-  // ---- hash: z_h = w_h . y1 + b_h in fp64, one 16-lane group per row, six rows in flight ----
+  // ---- hash: z_h = w_h . y1 + b_h in fp64 over the non-zero hidden activations only (a ReLU layer
+  //      leaves about half), the hash rows read input-major: thread (r, c) adds inputs r, r + R, ...
+  //      into hash columns 4c .. 4c + 3; partial sums meet in LDS and are added in a fixed order ----
   const int H = a.K * a.L;
   {
-    constexpr int R = 6;
-    const int g = tid >> 4, l = tid & 15;
-    const int nv = n1 >> 2;
-    for (int hb = g; hb < H; hb += R * GROUPS) {
-      const float4* w[R];
-      double acc[R];
+    const int Hp = a.Hp;
+    int32_t* nz = reinterpret_cast<int32_t*>(lvals);         // [n1 <= VALS_LDS] free until the logits
+    double* hpart = reinterpret_cast<double*>(sh.tkey);       // the select tables' room: set up afterwards
+    const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int nnz = 0, it = 0;
+    for (int base = 0; base < n1; base += NT, ++it) {
+      const int i = base + tid;
+      const bool is_nz = i < n1 && xs[i] != 0.0f;
+      const unsigned long long votes = __ballot(is_nz);
+      int* cnt = sh.wave_cnt + (it & 1) * NW;                 // two sets of counts: one barrier per round
+      if (lane == 0) cnt[wave] = __popcll(votes);
+      __syncthreads();
+      int before = 0, total = 0;
 #pragma unroll
-      for (int k = 0; k < R; ++k) {
-        const int h = hb + k * GROUPS;
-        w[k] = reinterpret_cast<const float4*>(a.Wh + (size_t)(h < H ? h : hb) * n1);
-        acc[k] = 0.0;
+      for (int w = 0; w < NW; ++w) {
+        const int c2 = cnt[w];
+        before += (w < wave) ? c2 : 0;
+        total += c2;
       }
-#pragma unroll 2
-      for (int i = l; i < nv; i += 16) {
-        float4 u[R];
-#pragma unroll
-        for (int k = 0; k < R; ++k) u[k] = w[k][i];
-        const float4 x = reinterpret_cast<const float4*>(xs)[i];
-        const double x0 = x.x, x1 = x.y, x2 = x.z, x3 = x.w;
-#pragma unroll
-        for (int k = 0; k < R; ++k) {
-          acc[k] = fma((double)u[k].x, x0, acc[k]);
-          acc[k] = fma((double)u[k].y, x1, acc[k]);
-          acc[k] = fma((double)u[k].z, x2, acc[k]);
-          acc[k] = fma((double)u[k].w, x3, acc[k]);
-        }
-      }
-#pragma unroll
-      for (int k = 0; k < R; ++k) acc[k] = reduce16(acc[k]);
-#pragma unroll
-      for (int k = 0; k < R; ++k) {
-        const int h = hb + k * GROUPS;
-        if (l == k && h < H) {
-          const float z = (float)(acc[k] + (double)a.bh[h]);
-          zs[h] = z;
-          if (a.tap_z) a.tap_z[(size_t)q * H + h] = z;
-        }
-      }
+      if (is_nz) nz[nnz + before + __popcll(votes & below)] = i;
+      nnz += total;
     }
+    __syncthreads();
+    const int CG = Hp >> 2, R = NT / CG;
+    const int r = tid / CG, cg = tid - r * CG;
+    if (r < R) {
+      double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+      const float* wt = a.WhT + 4 * cg;
+      constexpr int U = 8;
+      for (int i0 = r; i0 < nnz; i0 += R * U) {
+        float4 w[U];
+        float x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int i = i0 + u * R;
+          const int j = nz[i < nnz ? i : i0];
+          w[u] = *reinterpret_cast<const float4*>(wt + (size_t)j * Hp);
+          x[u] = i < nnz ? xs[j] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const double xd = x[u];
+          a0 = fma((double)w[u].x, xd, a0);
+          a1 = fma((double)w[u].y, xd, a1);
+          a2 = fma((double)w[u].z, xd, a2);
+          a3 = fma((double)w[u].w, xd, a3);
+        }
+      }
+      double* p = hpart + (size_t)r * Hp + 4 * cg;
+      p[0] = a0; p[1] = a1; p[2] = a2; p[3] = a3;
+    }
+    __syncthreads();
+    for (int h = tid; h < H; h += NT) {
+      double acc = 0.0;
+      for (int k = 0; k < R; ++k) acc += hpart[(size_t)k * Hp + h];
+      const float z = (float)(acc + (double)a.bh[h]);
+      zs[h] = z;
+      if (a.tap_z) a.tap_z[(size_t)q * H + h] = z;
+    }
+    __syncthreads();
   }
-  // meanwhile: the select state, and the dense output row if one is wanted
+  // the select state, and the dense output row if one is wanted
   for (int i = tid; i < words; i += NT) sh.taken[i] = 0u;
   for (int i = tid; i < TABLE; i += NT) { sh.tkey[i] = -1; sh.tval[i] = 0xFFFFFFFFu; }
   float* y = a.dense ? a.dense + (size_t)q * n2 : nullptr;
@@ -265,7 +290,11 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
   const int m = budget_of(a.keep[(size_t)q * a.keep_qstride], n2);
   const int Hf = (a.hash_first && m < n2) ? H : 0;       // hash nodes at the head of the list
   const int total = (m == n2 || m > Hf) ? m : Hf;
-  int32_t* list = a.list + (size_t)q * a.list_stride;
+  // the list is built in LDS while it fits (the room of the hidden layer's partial sums) and goes
+  // to the caller's array in one coalesced pass at the end
+  int32_t* glist = a.list + (size_t)q * a.list_stride;
+  const bool list_lds = m != n2 && total <= NT * 4;
+  int32_t* list = list_lds ? reinterpret_cast<int32_t*>(part) : glist;
   if (tid == 0) a.cnt[q] = total;
   if (m == n2) {
     if (a.tap_codes && tid < a.L) {
@@ -273,7 +302,7 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
       for (int j = 0; j < a.K; ++j) key |= (zs[tid * a.K + j] > 0.0f ? 1u : 0u) << j;
       a.tap_codes[(size_t)q * a.L + tid] = key;
     }
-    for (int i = tid; i < n2; i += NT) list[i] = i;
+    for (int i = tid; i < n2; i += NT) glist[i] = i;
   } else {
     for (int h = tid; h < Hf; h += NT) list[h] = a.hnodes[h];
     if (a.ids_narrow)
@@ -287,7 +316,7 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
                                                 a.tap_codes ? a.tap_codes + (size_t)q * a.L : nullptr, list + Hf,
                                                 Hf ? a.hslot : nullptr);
   }
-  __syncthreads();          // the list (global memory) is complete and visible to the workgroup
+  __syncthreads();          // the list is complete and visible to the workgroup
 
   // ---- logits of the listed nodes (kept in LDS while they fit, else in the caller's array) ----
   float* gv = a.vals + (size_t)q * a.vals_stride;
@@ -340,7 +369,9 @@ __global__ __launch_bounds__(NT) void fused_wide_kernel(FusedWideArgs a) {
     if (a.act1 == SLONN_ACT_SOFTMAX) v = expf(v - best) * inv;
     else if (a.act1 == SLONN_ACT_RELU) v = v > 0.0f ? v : 0.0f;
     gv[t] = v;
-    if (y) y[(m == n2) ? t : list[t]] = v;
+    const int j = (m == n2) ? t : list[t];
+    if (list_lds) glist[t] = j;
+    if (y) y[j] = v;
   }
 }
 

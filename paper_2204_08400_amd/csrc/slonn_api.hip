@@ -321,8 +321,9 @@ int slonn_model_create(const slonn_layer_desc* layers, int n_layers, slonn_model
       if (e != hipSuccess) set_error("copying FreeHash rows failed: %s", hipGetErrorString(e));
       return fail(SLONN_EHIP);
     }
-    // layers small enough for the whole-network kernel: the rows once more input-major
-    if ((size_t)L.d_in * L.d_out * (L.w_dtype == SLONN_F32 ? 4 : 2) <= ((size_t)8 << 20)) {
+    // the rows once more input-major, for the whole-network kernels (which serve models whose hash
+    // rows are a few megabytes at most)
+    if ((size_t)L.d_in * H * 4 <= ((size_t)16 << 20)) {
       const int Hp = (H + 3) & ~3;
       if ((e = hipMalloc(&L.WhT, (size_t)L.d_in * Hp * 4)) != hipSuccess) {
         set_error("allocating the input-major FreeHash rows failed: %s", hipGetErrorString(e));
@@ -431,6 +432,7 @@ bool fused_wide_eligible(const slonn_model* m, int ell_stride, const char** reas
       why = "hidden width is above 4096 or not a multiple of 16 bytes";
     else if (reinterpret_cast<uintptr_t>(A.W) % 16 != 0 || reinterpret_cast<uintptr_t>(Bl.W) % 16 != 0)
       why = "weights are not 16-byte aligned";
+    else if (!Bl.WhT) why = "no input-major FreeHash rows";
     else if ((unsigned long long)Bl.d_out * (unsigned long long)(A.d_out / 4) > 0xFFFFFFFFull)
       why = "output weight matrix too large for 32-bit row offsets";
     else {
@@ -758,7 +760,7 @@ int forward_impl(const slonn_model* m, const slonn_tables* t, const slonn_input*
     a.idx = X->idx; a.val = X->val; a.nnz = X->nnz; a.ell_stride = X->ell_stride;
     a.ellp = (X->ell_stride + 3) & ~3;
     a.W1 = O.W; a.b1 = O.bias; a.w1_dtype = O.w_dtype; a.act1 = O.act; a.n2 = O.d_out;
-    a.Wh = O.Wh; a.bh = O.bh; a.K = O.K; a.L = O.L; a.Hp = (O.H() + 3) & ~3;
+    a.WhT = O.WhT; a.bh = O.bh; a.K = O.K; a.L = O.L; a.Hp = (O.H() + 3) & ~3;
     a.dir = ts->d_dir; a.ids = ts->d_ids; a.ids_narrow = ts->narrow ? 1 : 0; a.global_rank = ts->d_global_rank;
     a.hnodes = O.hnodes; a.hslot = O.hslot; a.hash_first = m->hash_first ? 1 : 0;
     a.keep = keep + (size_t)1 * keep_lstride; a.keep_qstride = keep_qstride;

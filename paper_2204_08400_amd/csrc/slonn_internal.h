@@ -159,7 +159,7 @@ struct FusedWideArgs {
   const int32_t* idx; const float* val; const int32_t* nnz;
   int w0_dtype, act0, d0, n1, n1p, ccp, ell_stride, ellp;
   // output layer and its Node Activator
-  const void* W1; const float* b1; const float* Wh; const float* bh;
+  const void* W1; const float* b1; const float* WhT; const float* bh;   // WhT: hash rows input-major [n1][Hp]
   const uint32_t* dir; const void* ids; const int32_t* global_rank;
   const int32_t* hnodes; const int16_t* hslot;
   int w1_dtype, act1, n2, K, L, Hp, hash_first, ids_narrow;
