@@ -171,7 +171,7 @@ struct BlockMU { static constexpr int value = 4096 / NT; };
 // the kernel waits on memory round trips, and with the 106 scalar registers it would otherwise take
 // only seven fit, i.e. three workgroups per compute unit instead of four.  The other sizes run one
 // workgroup per compute unit or are bound by their vector registers: no point in spilling scalars.)
-template <int NT, typename IdT>
+template <int NT, typename IdT, int MU = BlockMU<NT>::value>
 __global__ __launch_bounds__(NT, NT == 512 ? 8 : 4) void select_block_kernel(
     const float* Z, int K, int L, int n, const uint32_t* __restrict__ dir,
     const IdT* __restrict__ ids, const int32_t* __restrict__ global_rank,
@@ -180,7 +180,6 @@ __global__ __launch_bounds__(NT, NT == 512 ? 8 : 4) void select_block_kernel(
     float* __restrict__ yzero, int ldy, RowBlocking rb, HashFirst hf, HashSplit hsp,
     const int32_t* __restrict__ order) {
   extern __shared__ __align__(16) uint32_t smem32[];
-  constexpr int MU = BlockMU<NT>::value;
   SelectShared<NT, MU> sh;
   sh.prio = smem32;
   sh.s_off = smem32 + n;
@@ -349,7 +348,19 @@ int launch_select_t(const float* Z, int K, int L, int n, const uint32_t* dir, co
   const size_t lds_block = ((size_t)n + SelectShared<SEL_NT, BlockMU<SEL_NT>::value>::words_besides_prio +
                             (rbv.mask ? (size_t)(n + 31) / 32 : 0)) * 4;
   if (lds_block <= (size_t)max_lds) {
-    if (B <= SEL_BIG_MAX_BATCH) {
+    // Up to four queries on a layer with many tables (the lists of 64 tables overlap so much that a
+    // chosen node costs almost thirty slots): rounds of 12 288 slots, a third of the trips to table
+    // memory (C5 batch 1: 219 -> 212 us per query, batch 4: 335 -> 314; with C3's 32 tables the
+    // deeper rounds fetch more than they save at keep .25 and win 4 % at keep .5)
+    constexpr int MU_FEW = 12;
+    const size_t lds_few = lds_block + (size_t)(MU_FEW - BlockMU<SEL_NT_BIG>::value) * (SEL_NT_BIG / 64) * 4;
+    if (B <= 4 && L >= 48 && lds_few <= (size_t)max_lds) {
+      if (lds_few > 65536)
+        SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG, IdT, MU_FEW>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_few));
+      hipLaunchKernelGGL((select_block_kernel<SEL_NT_BIG, IdT, MU_FEW>), dim3(B), dim3(SEL_NT_BIG), lds_few, s, Z, K, L, n,
+                         dir, ids, global_rank, keep, keep_stride, codes, active, cnt, idx_stride, yzero, ldy, rbv, hf, hsp, order);
+    } else if (B <= SEL_BIG_MAX_BATCH) {
       if (lds_block > 65536)
         SLONN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(select_block_kernel<SEL_NT_BIG, IdT>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_block));

@@ -392,6 +392,22 @@ def test_few_queries_take_a_workgroup_per_row(rt, oracle, w_dtype):
         _say(f"  batch {B}: {compare_sparse(got, ref, layers, f'row kernel batch {B}')}")
 
 
+def test_few_queries_on_layers_with_many_tables(rt, oracle):
+    """Up to four queries on layers with 48 tables or more take rounds of 12 288 slots in the select
+    kernel (a thread takes twelve consecutive slots); budgets from one node to the whole layer and
+    lists that run out (cap 50); five queries take the usual rounds and must agree as well."""
+    dims = (64, 1536, 1100, 10)
+    for cap in (None, 50):
+        layers, net, _ = make_case(oracle, dims, 6, 64, seed=61, cap=cap, N_build=192, kind="normal")
+        g = _gpu_net(rt, layers, net, path="layers")
+        Xq = make_queries(dims, 5, seed=62, kind="normal")
+        keep = np.asarray([[0.3, 0.2, 1], [0.0005, 0.6, 1], [1.0, 0.1, 1], [0.9, 0.05, 1], [0.5, 0.25, 1]], np.float32)
+        for B in (1, 3, 4, 5):
+            ref = net.sparse_forward(Xq[:B], keep[:B])
+            got = to_numpy_result(g.sparse_forward(Xq[:B], _keep_tensor(keep[:B]), taps=True))
+            _say(f"  cap {cap} batch {B}: {compare_sparse(got, ref, layers, f'many tables, cap {cap}, batch {B}')}")
+
+
 @pytest.mark.gpu
 def test_hash_node_choice_matches_oracle(rt, oracle):
     """Section 3.4: per-node activation variance on the device against the oracle's float64
