@@ -122,7 +122,9 @@ class Workload:
         slonn, xq = self.slonn, self.xq
         assert B <= self.B
         self.batch = B
-        self.n_streams = self.args.streams if self.args.streams > 0 else (4 if B <= 256 else 2)
+        # (a model of under a million weights is a 13 us launch: more streams only add host work)
+        small_model = sum(l.d_in * l.d_out for l in self.layers) < (1 << 20)
+        self.n_streams = self.args.streams if self.args.streams > 0 else (4 if B <= 256 and not small_model else 2)
         while len(self.all_lanes) < self.n_streams:
             self.all_lanes.append(self._lane(len(self.all_lanes)))
         self.lanes = self.all_lanes[:self.n_streams]
@@ -341,7 +343,7 @@ def main():
                     help="inputs with class structure instead of the configuration's (study of --cluster-by-key only)")
     ap.add_argument("--streams", type=int, default=0,
                     help="HIP streams the batches of a step are dealt to in turn (each with its own workspace); "
-                         "0: two for batches above 256 queries, four up to that")
+                         "0: two for batches above 256 queries and for tiny models, else four")
     ap.add_argument("--markers", action="store_true",
                     help="launch a marker kernel (nextafter) right before and after the timed steps, for profilers")
     ap.add_argument("--no-profile", action="store_true", help="skip the event-instrumented pass (profiler runs)")

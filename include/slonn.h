@@ -155,8 +155,8 @@ int slonn_model_set_path(slonn_model* m, int path);
 /* How many batches the caller keeps in flight on this device at a time (calls on n streams, each
  * with its own workspace and outputs).  The whole-network kernels give a query a workgroup of 1024
  * threads while the queries in flight (n times the batch) leave compute units free, and one of 512
- * threads once they do not, so that two queries share a unit and one's memory waits are the
- * other's work.  A hint: results do not depend on it.  n >= 1 (default 1).
+ * or 256 threads once they do not, so that several queries share a unit and one's memory waits are
+ * the others' work.  A hint: results do not depend on it.  n >= 1 (default 1).
  * EINVAL: null model, n < 1.                                                                    */
 int slonn_model_set_batches_in_flight(slonn_model* m, int n);
 

@@ -1,4 +1,4 @@
-// Whole-network SLO-aware forward pass for small and medium layers: one workgroup of 512 or
+// Whole-network SLO-aware forward pass for small and medium layers: one workgroup of 256, 512 or
 // 1024 threads walks one query through every layer (the "k% forward propagation" loop of
 // Section 2.1: for each layer, ask the Node Activator for the active node ids, then
 // compute only those nodes).  The query's activations, hash projections, keys, the
@@ -30,9 +30,10 @@
 namespace slonn {
 namespace {
 
-// Threads per workgroup: 1024 when a batch leaves most compute units free (one query per unit),
-// else 512, so that two queries share a unit and fill each other's memory waits: every phase of a
-// query is a dependent round trip to L2 or a stream bound by one unit's path to L2.
+// Threads per workgroup: 1024 when the queries in flight leave most compute units free (one query
+// per unit), else 512 or 256, so that two to four queries share a unit and fill each other's memory
+// waits: every phase of a query is a dependent round trip to L2 or a stream bound by one unit's
+// path to L2.
 constexpr int NT_MAX = 1024;
 constexpr size_t HASH_PART_BYTES = (size_t)NT_MAX * 4 * 8;   // partial hash projections: four doubles per thread
 template <int NT> struct SelectMu { static constexpr int value = SELECT_MU * (NT_MAX / NT); };   // 4096 slots per round
@@ -556,11 +557,18 @@ int launch_fused_forward(const FusedArgs& a, int B, int in_flight, int n_cu, int
   const size_t lds = fused_lds_bytes(a);
   if (lds > (size_t)max_lds)
     SLONN_FAIL(SLONN_EUNSUPPORTED, "fused path needs %zu bytes of LDS, device grants %d", lds, max_lds);
-  // 1024 threads per query while the queries in flight use at most half the compute units, else
-  // 512: two queries then share a unit (from this launch or from a batch on another stream)
-  const bool wide = 2 * (long long)B * in_flight <= n_cu;
-  if (a.pol.sum) return wide ? launch_fused_nt<true, 1024>(a, B, lds, s) : launch_fused_nt<true, 512>(a, B, lds, s);
-  return wide ? launch_fused_nt<false, 1024>(a, B, lds, s) : launch_fused_nt<false, 512>(a, B, lds, s);
+  // 1024 threads per query while the queries in flight use at most half the compute units, 512
+  // up to four queries per unit, 256 beyond: two to four queries then share a unit (from this
+  // launch or from batches on other streams).  C2, batch 256: two batches in flight 9.7 (1024
+  // threads) / 15.7 (512) / 14.4 (256) M queries/s at keep .05, four in flight 16.3 (512) / 19.9 (256)
+  const long long in_flight_q = (long long)B * in_flight;
+  const int nt = 2 * in_flight_q <= n_cu ? 1024 : (in_flight_q >= 4ll * n_cu ? 256 : 512);
+  if (a.pol.sum) {
+    if (nt == 1024) return launch_fused_nt<true, 1024>(a, B, lds, s);
+    return nt == 512 ? launch_fused_nt<true, 512>(a, B, lds, s) : launch_fused_nt<true, 256>(a, B, lds, s);
+  }
+  if (nt == 1024) return launch_fused_nt<false, 1024>(a, B, lds, s);
+  return nt == 512 ? launch_fused_nt<false, 512>(a, B, lds, s) : launch_fused_nt<false, 256>(a, B, lds, s);
 }
 
 }  // namespace slonn

@@ -295,8 +295,8 @@ def test_ell_input_and_activated_softmax_output(rt, oracle, n_out, path):
 
 def test_batches_in_flight_hint_changes_workgroups_not_results(rt, oracle):
     """slonn_model_set_batches_in_flight sizes the workgroups of the whole-network kernels (1024
-    threads per query, or 512 so that two queries share a compute unit).  Both sizes must match the
-    oracle, for the dense-input kernel and for the wide sparse-input one."""
+    threads per query, or 512 / 256 so that several queries share a compute unit).  Every size must
+    match the oracle, for the dense-input kernel and for the wide sparse-input one."""
     import copy
     from paper_2204_08400_amd import slonn
     dims = (96, 1000, 640, 12)
@@ -305,7 +305,7 @@ def test_batches_in_flight_hint_changes_workgroups_not_results(rt, oracle):
     X = make_queries(dims, 40, seed=6)
     keep = wl.keep_uniform(40, 0.01, 0.9, 8)
     ref = net.sparse_forward(X, keep)
-    for n in (1, 64):
+    for n in (1, 8, 64):      # 40 queries a batch: 1024, 512 and 256 threads per query
         _say(f"dense-input whole-network kernel, {n} batches in flight")
         g.set_batches_in_flight(n)
         compare_sparse(to_numpy_result(g.sparse_forward(X, _keep_tensor(keep), taps=True)), ref, layers, f"in flight {n}")
