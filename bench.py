@@ -32,6 +32,18 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+# The side streams of the lanes, shared by every workload of the process: a process has four hardware
+# queues, and streams beyond that share them (a workload with fresh streams of its own may find two
+# of its lanes on one queue).
+_LANE_STREAMS = []
+
+
+def lane_stream(torch, dev, i):
+    while len(_LANE_STREAMS) < i:
+        _LANE_STREAMS.append(torch.cuda.Stream(device=dev))
+    return _LANE_STREAMS[i - 1]
+
+
 class Workload:
     """One configuration set up on the device: weights, hash nodes, tables, the query set cut
     into batches, output buffers and the workspace."""
@@ -89,6 +101,7 @@ class Workload:
         # stream.  Two lanes for large batches, four for batches of up to 256 queries, whose kernels are
         # chains of dependent memory round trips; the library is told how many batches are in flight.
         self.stream = torch.cuda.current_stream()
+        self.graphs, self.keep_tensors = {}, {}
         self.all_lanes = []
         self.lanes = []
         self.set_batch(self.B, self.nq)
@@ -101,7 +114,7 @@ class Workload:
     def _lane(self, i):
         torch, slonn, dev, B = self.torch, self.slonn, self.dev, self.B
         n_last = self.cfg.dims[-1]
-        lane = {"stream": self.stream if i == 0 else torch.cuda.Stream(device=dev),
+        lane = {"stream": self.stream if i == 0 else lane_stream(torch, dev, i),
                 "ws": torch.empty(slonn.slonn_workspace_bytes(self.net.model, B), dtype=torch.uint8, device=dev),
                 "arg": torch.empty(B, dtype=torch.int32, device=dev),
                 "yd": torch.empty((B, n_last), dtype=torch.float32, device=dev)}
@@ -158,8 +171,27 @@ class Workload:
         s, B = self.slonn, self.batch
         lanes = self.lanes[:1] if one_lane else self.lanes
         self._fork(lanes)
+        # (measured: replaying wins where the host's launches bind -- one or two queries a batch with four
+        # batches in flight, C3 batch 1: 25.7 -> 37.9 k queries/s -- and loses about 5 % on one stream)
+        recorded = not one_lane and ((self.args.graphs and B <= 32) or (B <= 2 and len(lanes) >= 4))
         for i, nb in enumerate(self.sizes):
             ln = lanes[i % len(lanes)]
+            if recorded:
+                # small batches are bound by the host's launches (11 per query on C3): each batch's pass is
+                # recorded once (its input, keep fractions, outputs and workspace are fixed device buffers)
+                # and replayed with one call
+                mixed = self.mixed is not None and not uniform
+                key = (B, i, len(lanes), "mixed" if mixed else keep_t.data_ptr())
+                g = self.graphs.get(key)
+                if g is None:
+                    # (create runs a pass on a stream of its own: nothing else may be using this lane's
+                    # workspace and outputs meanwhile)
+                    self.torch.cuda.synchronize()
+                    kp = self.mixed[i * B:i * B + nb] if mixed else keep_t
+                    g = self.graphs[key] = s.slonn_forward_graph_create(
+                        self.net.model, self.net.tables, self.batches[i], nb, kp, 1 if mixed else 0, 0, ln["out"], ln["ws"])
+                g.launch(ln["stream"])
+                continue
             if self.mixed is not None and not uniform:
                 s.slonn_sparse_forward(self.net.model, self.net.tables, self.batches[i], nb,
                                        self.mixed[i * B:i * B + nb], 1, 0, ln["out"], None, ln["ws"], ln["stream"])
@@ -205,12 +237,27 @@ class Workload:
         return max(ev[0].elapsed_time(ev[steps]) / 1e3, wall), per
 
     def keep_tensor(self, keep):
-        return self.torch.full((1,), float(keep if keep is not None else 1.0), dtype=self.torch.float32,
-                               device=self.dev)
+        k = float(keep if keep is not None else 1.0)
+        if k not in self.keep_tensors:       # (one tensor per value: recorded passes bake its address in)
+            self.keep_tensors[k] = self.torch.full((1,), k, dtype=self.torch.float32, device=self.dev)
+        return self.keep_tensors[k]
 
     def time_sparse(self, keep, steps, warm, mark=False, uniform=False):
         kt = self.keep_tensor(keep)
         return self.timed(lambda: self.step(kt, uniform=uniform), steps, warm, mark)
+
+    def steps_for(self, fn, steps, warm, min_seconds=0.1):
+        """(steps, warm-up steps) for a side measurement: at least the given ones, and enough of both for
+        a timed region of about min_seconds behind a warm-up of half that -- a step of a small workload
+        is a millisecond, and a GPU coming out of idle runs its first milliseconds at a low clock"""
+        torch = self.torch
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        t = max(time.perf_counter() - t0, 1e-5)
+        return (min(500, max(steps, int(min_seconds / t) + 1)), min(250, max(warm, int(0.5 * min_seconds / t) + 1)))
 
     def profile_sparse(self, keep, steps):
         """Per-kernel-kind durations over `steps` more steps: every launch bracketed by two HIP events
@@ -344,6 +391,9 @@ def main():
     ap.add_argument("--streams", type=int, default=0,
                     help="HIP streams the batches of a step are dealt to in turn (each with its own workspace); "
                          "0: two for batches above 256 queries and for tiny models, else four")
+    ap.add_argument("--graphs", action="store_true",
+                    help="batches of up to 32 queries: record each batch's pass once (HIP graph) and replay it "
+                         "(always done for batches of one or two queries dealt to four streams)")
     ap.add_argument("--markers", action="store_true",
                     help="launch a marker kernel (nextafter) right before and after the timed steps, for profilers")
     ap.add_argument("--no-profile", action="store_true", help="skip the event-instrumented pass (profiler runs)")
@@ -418,7 +468,10 @@ def main():
     def sweep_and_dense(wk, steps, warm, keeps):
         """the keep fractions of a workload and the full network, a few steps each"""
         res = {"sweep": {}}
+        base_steps, base_warm = steps, warm
         for keep in keeps:
+            kt_ = wk.keep_tensor(keep)
+            steps, warm = wk.steps_for(lambda: wk.step(kt_), base_steps, base_warm)
             s, _ = wk.time_sparse(keep, steps, warm)
             q = steps * wk.nq / s
             res["sweep"][str(keep)] = {"qps": round(q), "ms_per_step": round(s / steps * 1e3, 4),
@@ -430,6 +483,7 @@ def main():
                 continue
             if hasattr(slonn, "slonn_model_set_dense_arithmetic"):
                 slonn.slonn_model_set_dense_arithmetic(wk.net.model, mode)
+            steps, warm = wk.steps_for(wk.dense_step, base_steps, base_warm)
             s, _ = wk.timed(wk.dense_step, steps, warm)
             res["dense_baseline"][label] = {"qps": round(steps * wk.nq / s), "ms_per_step": round(s / steps * 1e3, 4),
                                             "TFLOPs": round(dflops * steps * wk.nq / s / 1e12, 2)}
@@ -439,6 +493,8 @@ def main():
             # small batches: the full network is also run through the sparse path's own kernels with every
             # node active (keep 1.0: no table access, rows spread over all compute units), the "all nodes
             # computed" case of Section 3.4; a matrix-core GEMM has little to offer a handful of queries
+            kt_ = wk.keep_tensor(1.0)
+            steps, warm = wk.steps_for(lambda: wk.step(kt_, uniform=True), base_steps, base_warm)
             s, _ = wk.time_sparse(1.0, steps, warm, uniform=True)
             res["dense_baseline"]["all_nodes_through_the_gather_kernels"] = {
                 "qps": round(steps * wk.nq / s), "ms_per_step": round(s / steps * 1e3, 4),
@@ -577,11 +633,13 @@ def main():
         for b_, q_ in ((32, 1024), (8, 256), (1, 64)):
             w.set_batch(b_, q_)
             r = sweep_and_dense(w, 3, 1, ())
-            s_, _ = w.time_sparse(None, 3, 1)
+            kt_ = w.keep_tensor(None)
+            n_, w_ = w.steps_for(lambda: w.step(kt_), 3, 1)
+            s_, _ = w.time_sparse(None, n_, w_)
             best = max(v["qps"] for v in r["dense_baseline"].values())
-            r["sparse"] = {"qps": round(3 * w.nq / s_), "ms_per_step": round(s_ / 3 * 1e3, 4),
-                           "nominal_gathered_GBps": round(w.gathered_bytes_per_step(None) * 3 / s_ / 1e9, 1),
-                           "sparse_over_best_dense": round(3 * w.nq / s_ / best, 3)}
+            r["sparse"] = {"qps": round(n_ * w.nq / s_), "ms_per_step": round(s_ / n_ * 1e3, 4),
+                           "nominal_gathered_GBps": round(w.gathered_bytes_per_step(None) * n_ / s_ / 1e9, 1),
+                           "sparse_over_best_dense": round(n_ * w.nq / s_ / best, 3)}
             r["config"] = {"workload": head_config["workload"], "batch": b_, "keep": keep_label,
                            "queries_per_step": w.nq, "streams": w.n_streams}
             others[f"{args.config}_B{b_}"] = r

@@ -369,8 +369,11 @@ int slonn_sparse_forward_aclo(const slonn_model* m, const slonn_tables* t, const
  * (same meaning, no debug taps) and then records the same call into a HIP graph; launch replays
  * it on `stream` as one submission.  Every pointer is baked in: between launches the caller
  * rewrites the input (X), keep and reads the output buffers in place; model, tables, workspace and
- * buffers must outlive the graph, and launches of one graph must not overlap.  The recording
- * holds kernel launches only (no memory-set nodes).  EINVAL also while per-kernel timing is on. */
+ * buffers must outlive the graph, and launches of one graph must not overlap.  create runs its
+ * pass on a stream of its own and waits for it: work still in flight on other streams must not
+ * use the same workspace or output buffers meanwhile (graphs that share a workspace are created
+ * and launched one after another on one stream).  The recording holds kernel launches only (no
+ * memory-set nodes).  EINVAL also while per-kernel timing is on.                             */
 int slonn_forward_graph_create(const slonn_model* m, const slonn_tables* t, const slonn_input* X, int B,
                                const float* keep, int keep_qstride, int keep_lstride, slonn_output* Y,
                                void* workspace, size_t ws_bytes, slonn_graph** out);
