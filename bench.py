@@ -623,6 +623,17 @@ def main():
         cpu = {"value": round(done / dt, 1), "unit": "queries/s", "cores": onet.threads, "kind": "oracle",
                "sample": f"first {n_s} queries of the same query set, {done // n_s} passes ({dt:.1f} s of CPU work), "
                          f"keep {keep_label}, all layers, {onet.threads} threads over queries{note}"}
+        # the same oracle on one thread (the paper times one query at a time), on the first queries of the
+        # sample: about two seconds
+        n_1 = max(1, min(n_s, int(2.0 * done / dt / max(onet.threads, 1)) + 1))
+        all_threads, onet.threads = onet.threads, 1
+        X1 = tuple(a[:n_1] for a in Xs) if w.ell else Xs[:n_1]
+        k1 = ks if w.mixed is None else ks[:n_1]
+        t0 = time.perf_counter()
+        onet.sparse_forward(X1, k1, taps=False)
+        cpu["one_thread"] = {"value": round(n_1 / (time.perf_counter() - t0), 2), "unit": "queries/s",
+                             "sample": f"first {n_1} queries, one pass"}
+        onet.threads = all_threads
         log(f"CPU oracle: {cpu}")
         del onet
 
