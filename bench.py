@@ -394,6 +394,8 @@ def main():
     ap.add_argument("--graphs", action="store_true",
                     help="batches of up to 32 queries: record each batch's pass once (HIP graph) and replay it "
                          "(always done for batches of one or two queries dealt to four streams)")
+    ap.add_argument("--full-network", choices=["fp32", "f16"], default=None,
+                    help="time only the full-network pass (the baseline) in the given arithmetic, for profilers")
     ap.add_argument("--markers", action="store_true",
                     help="launch a marker kernel (nextafter) right before and after the timed steps, for profilers")
     ap.add_argument("--no-profile", action="store_true", help="skip the event-instrumented pass (profiler runs)")
@@ -441,6 +443,17 @@ def main():
     w = Workload(args.config, args.batch, args, n_queries=args.queries, n_build=args.build_inputs, top_keep=args.keep)
     cfg, B = w.cfg, w.B
     head_keep = None if w.mixed is not None else args.keep
+    if args.full_network:
+        # profiler runs of the baseline alone: the full-network pass between the markers, nothing else
+        slonn.slonn_model_set_dense_arithmetic(w.net.model, 1 if args.full_network == "f16" else 0)
+        secs, per = w.timed(w.dense_step, K, W, mark=args.markers)
+        print(json.dumps({"metric": "queries/s of the full-network pass (all nodes: the baseline, not the method)",
+                          "value": round(K * w.nq / secs, 1), "unit": "queries/s", "n_gpus": 1, "steps": K, "warmup": W,
+                          "ms_per_step": round(secs / K * 1e3, 5), "higher_is_better": True,
+                          "TFLOPs": round(w.dense_flops_per_query() * K * w.nq / secs / 1e12, 2),
+                          "config": {"workload": args.config, "batch": B, "arithmetic": args.full_network,
+                                     "queries_per_step": w.nq, "streams": w.n_streams}}), flush=True)
+        return
     secs, per = w.time_sparse(head_keep, K, W, mark=args.markers)
     qps = K * w.nq / secs
     gathered = w.gathered_bytes_per_step(head_keep)
