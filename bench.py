@@ -259,6 +259,17 @@ class Workload:
         t = max(time.perf_counter() - t0, 1e-5)
         return (min(500, max(steps, int(min_seconds / t) + 1)), min(250, max(warm, int(0.5 * min_seconds / t) + 1)))
 
+    def latency_us(self, keep, uniform=False):
+        """Mean time per batch with one batch in flight: the query set pass after pass on one stream
+        (eager launches, a batch's kernels start when the batch before has finished), in microseconds."""
+        kt = self.keep_tensor(keep)
+        self.slonn.slonn_model_set_batches_in_flight(self.net.model, 1)
+        fn = lambda: self.step(kt, one_lane=True, uniform=uniform)
+        steps, warm = self.steps_for(fn, 3, 1, min_seconds=0.05)
+        secs, _ = self.timed(fn, steps, warm)
+        self.slonn.slonn_model_set_batches_in_flight(self.net.model, self.n_streams)
+        return round(secs / steps / len(self.sizes) * 1e6, 1)
+
     def profile_sparse(self, keep, steps):
         """Per-kernel-kind durations over `steps` more steps: every launch bracketed by two HIP events
         on the launch stream inside the library."""
@@ -664,6 +675,10 @@ def main():
             r["sparse"] = {"qps": round(n_ * w.nq / s_), "ms_per_step": round(s_ / n_ * 1e3, 4),
                            "nominal_gathered_GBps": round(w.gathered_bytes_per_step(None) * n_ / s_ / 1e9, 1),
                            "sparse_over_best_dense": round(n_ * w.nq / s_ / best, 3)}
+            if b_ == 1:      # the paper's regime: one query at a time, nothing else in flight
+                r["sparse"]["latency_us_one_in_flight"] = w.latency_us(None)
+                r["dense_baseline"]["all_nodes_through_the_gather_kernels"]["latency_us_one_in_flight"] = \
+                    w.latency_us(1.0, uniform=True)
             r["config"] = {"workload": head_config["workload"], "batch": b_, "keep": keep_label,
                            "queries_per_step": w.nq, "streams": w.n_streams}
             others[f"{args.config}_B{b_}"] = r
@@ -677,6 +692,11 @@ def main():
             for b_, q_ in shapes:
                 wk.set_batch(b_, q_)
                 r = sweep_and_dense(wk, 3, 1, wk.cfg.keeps)
+                if b_ == 1:
+                    for k_, v_ in r["sweep"].items():
+                        v_["latency_us_one_in_flight"] = wk.latency_us(float(k_))
+                    r["dense_baseline"]["all_nodes_through_the_gather_kernels"]["latency_us_one_in_flight"] = \
+                        wk.latency_us(1.0, uniform=True)
                 r["config"] = {"workload": f"{name}: MLP {'-'.join(map(str, wk.cfg.dims))}, K={wk.cfg.K} L={wk.cfg.L}",
                                "batch": b_, "queries_per_step": wk.nq, "table_training_inputs": wk.n_build,
                                "streams": wk.n_streams}

@@ -1150,6 +1150,10 @@ int slonn_forward_graph_create(const slonn_model* m, const slonn_tables* t, cons
     set_error("hipGraphInstantiate failed: %s", hipGetErrorString(e));
     return fail(SLONN_EHIP);
   }
+  // the stream was only needed for the recording: a serving loop holds one graph per input buffer,
+  // and hundreds of idle streams slow every later launch of the process down
+  (void)hipStreamDestroy(g->capture_stream);
+  g->capture_stream = nullptr;
   *out = g;
   return SLONN_OK;
 }
