@@ -354,11 +354,21 @@ def roofline_of(w, keep, prof, steps, secs_per_step, traffic_key):
              "method_flops_per_launch": int(own_l), "issued_flops_per_launch": int(issued_l),
              "issued_TFLOPs": round(issued_l / avg_s / 1e12, 1),
              "issued_frac": round(issued_l / avg_s / 1e12 / F16_PEAK_TFLOPS, 4),
+             "mfma_rate_from_registers_TFLOPs": None, "issued_frac_of_mfma_rate_from_registers": None,
              "note": "achieved = the method's own flops (2 d per selected pair) per launch over the mean launch duration; "
                      "issued = what the tile kernel executes for them: every (query, node) pair of a served 128-query tile, "
                      "each fp32-class product as 2 (bf16 weights) or 3 (fp32 weights) fp16 MFMA products.  "
                      "nominal_gathered_GBps is the north-star figure (budget x row bytes over the step time); it exceeds the "
-                     "HBM peak because a weight tile is fetched once per 128 queries, so it is not a roofline fraction"}
+                     "HBM peak because a weight tile is fetched once per 128 queries, so it is not a roofline fraction.  "
+                     "mfma_rate_from_registers = a register-only loop of the same MFMAs on this device in this run "
+                     "(slonn_probe_mfma_rate): what the matrix cores deliver at the clock they hold under load"}
+        try:      # the yardstick beside the published peak, measured now
+            scratch = w.torch.empty(1 << 22, dtype=w.torch.uint8, device=w.dev)
+            rate = w.slonn.slonn_probe_mfma_rate(scratch, w.stream)
+            r["mfma_rate_from_registers_TFLOPs"] = round(rate, 1)
+            r["issued_frac_of_mfma_rate_from_registers"] = round(issued_l / avg_s / 1e12 / rate, 4)
+        except Exception as e:      # (a library without the probe)
+            log(f"no MFMA rate probe: {e}")
     else:
         # gather-type kernels: bytes of the rows this kernel kind evaluates per launch
         per_launch = w.gathered_bytes_per_step(keep, activated_only=(dom != "fused")) / launches_per_step

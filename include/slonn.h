@@ -127,6 +127,15 @@ typedef struct {
 /* Library / device self-description: fills a short human-readable string.          */
 int slonn_version(char* buf, size_t cap);
 
+/* Measurement aid for callers that cannot reach the matrix cores themselves (bench.py): runs a
+ * register-only loop of v_mfma_f32_16x16x32_f16 in the order the tile kernels issue them (two
+ * workgroups of eight wavefronts per compute unit, a few milliseconds) and reports the rate in
+ * TFLOP/s -- what the fp16 matrix cores of this device deliver at the clock they hold under that
+ * load, the yardstick beside the published peak.  scratch: DEVICE memory, 4096 bytes per compute
+ * unit (written, nothing to read back); tflops: HOST.  Synchronises `stream`.
+ * EINVAL: null argument; ENOMEM: scratch too small.                                           */
+int slonn_probe_mfma_rate(void* scratch, size_t scratch_bytes, void* stream, double* tflops);
+
 /* Validate and register a network.  Copies the K*L FreeHash rows of each activated
  * layer into library-owned device memory (synchronises the device once).
  * Errors: EINVAL for null/negative sizes, K > SLONN_MAX_K, L > SLONN_MAX_L, K*L >

@@ -559,4 +559,44 @@ int launch_dense_tiles(const uint16_t* Wp, int w_parts, const int32_t* wexp, con
   return launch_tiles(X2, X, ldx, t.xexp, Wp, w_parts, wexp, bias, nullptr, nullptr, Y, ldy, B, n, d, a, s);
 }
 
+// ---- measurement aid: what the fp16 matrix cores deliver when nothing else is in the way ----
+namespace {
+// Eight wavefronts per workgroup, sixteen accumulators each, operands in registers: 32 MFMAs per
+// iteration in the order the tile kernel issues them (two onto each accumulator, back to back).
+__global__ __launch_bounds__(512) void mfma_rate_probe_kernel(float* __restrict__ out, int iters) {
+  f16x8 a[4], b[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a[i][j] = (_Float16)(0.001f * (float)((threadIdx.x + i + j) & 63));
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) b[i][j] = (_Float16)(0.002f * (float)((threadIdx.x + 3 * i + j) & 63));
+  f32x4 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+      for (int y = 0; y < 4; ++y) {
+        acc[4 * x + y] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[x], b[2 * y + 1], acc[4 * x + y], 0, 0, 0);
+        acc[4 * x + y] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[x], b[2 * y], acc[4 * x + y], 0, 0, 0);
+      }
+  }
+  float sum = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sum += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  out[(size_t)blockIdx.x * 512 + threadIdx.x] = sum;
+}
+}  // namespace
+
+// out: workgroups * 512 floats of device memory (results nobody needs; they keep the loop alive).
+// Returns the flops the launch executes.
+double launch_mfma_rate_probe(float* out, int workgroups, int iters, hipStream_t s) {
+  hipLaunchKernelGGL(mfma_rate_probe_kernel, dim3(workgroups), dim3(512), 0, s, out, iters);
+  return 32.0 * 16384.0 * (double)iters * workgroups * 8;
+}
+
 }  // namespace slonn

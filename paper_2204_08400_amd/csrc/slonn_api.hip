@@ -213,6 +213,31 @@ int slonn_profile_end(double* ms_per_kind, int64_t* launches_per_kind) {
   return rc;
 }
 
+int slonn_probe_mfma_rate(void* scratch, size_t scratch_bytes, void* stream, double* tflops) {
+  if (!scratch || !tflops) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  int dev = 0, n_cu = 256;
+  SLONN_HIP(hipGetDevice(&dev));
+  (void)hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+  const int wgs = 2 * n_cu, iters = 4000;
+  if (scratch_bytes < (size_t)wgs * 512 * 4) SLONN_FAIL(SLONN_ENOMEM, "scratch holds %zu bytes, %zu needed", scratch_bytes, (size_t)wgs * 512 * 4);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  SLONN_HIP(hipEventCreate(&e0));
+  SLONN_HIP(hipEventCreate(&e1));
+  (void)launch_mfma_rate_probe(static_cast<float*>(scratch), wgs, 200, s);       // warm-up
+  SLONN_HIP(hipEventRecord(e0, s));
+  const double flops = launch_mfma_rate_probe(static_cast<float*>(scratch), wgs, iters, s);
+  SLONN_HIP(hipEventRecord(e1, s));
+  SLONN_HIP(hipEventSynchronize(e1));
+  float ms = 0.0f;
+  SLONN_HIP(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  SLONN_HIP(hipGetLastError());
+  *tflops = ms > 0.0f ? flops / (ms * 1e-3) / 1e12 : 0.0;
+  return SLONN_OK;
+}
+
 int slonn_version(char* buf, size_t cap) {
   if (!buf || cap == 0) SLONN_FAIL(SLONN_EINVAL, "null buffer");
   int dev = 0, lds = 0, cus = 0;

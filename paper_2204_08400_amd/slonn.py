@@ -36,7 +36,7 @@ EXPORTS = [
     "slonn_activation_variance", "slonn_sample_hash_nodes", "slonn_model_set_hash_margin",
     "slonn_sparse_forward_static", "slonn_model_set_dense_arithmetic",
     "slonn_sample_hash_nodes_device", "slonn_model_set_tables_refreshable", "slonn_tables_refresh",
-    "slonn_model_set_batches_in_flight",
+    "slonn_model_set_batches_in_flight", "slonn_probe_mfma_rate",
 ]
 STATIC_SCRATCH_BYTES = 64 << 20
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused", "tiles")
@@ -115,6 +115,14 @@ def slonn_version() -> str:
     buf = C.create_string_buffer(128)
     _check(load().slonn_version(buf, C.c_size_t(128)))
     return buf.value.decode()
+
+
+def slonn_probe_mfma_rate(scratch, stream=None) -> float:
+    """TFLOP/s of a register-only loop of the tile kernels' fp16 MFMAs (measurement aid, see slonn.h)."""
+    out = C.c_double(0.0)
+    _check(load().slonn_probe_mfma_rate(C.c_void_p(_ptr(scratch)), C.c_size_t(scratch.numel() * scratch.element_size()),
+                                            C.c_void_p(_stream_ptr(stream)), C.byref(out)))
+    return out.value
 
 
 class Model:
