@@ -459,6 +459,13 @@ def main():
     copy_gbps = 20 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst
     log(f"plain device copy: {copy_gbps:,.0f} GB/s (read + write)")
+    # ---- what the compute units draw from L2 (the bound of the gathers on cache-resident weights) ----
+    l2_all = l2_one = None
+    if hasattr(slonn, "slonn_probe_l_two_read_rate"):
+        scratch = torch.zeros(4 << 20, dtype=torch.uint8, device=dev)
+        l2_all, l2_one = slonn.slonn_probe_l_two_read_rate(scratch, torch.cuda.current_stream())
+        del scratch
+        log(f"16-byte loads of an L2-resident window: {l2_all:,.0f} GB/s with every compute unit busy, {l2_one:,.0f} GB/s for one unit alone")
 
     # ---- headline ----
     w = Workload(args.config, args.batch, args, n_queries=args.queries, n_build=args.build_inputs, top_keep=args.keep)
@@ -490,7 +497,9 @@ def main():
     traffic_key = f"{args.config}_B{B}_keep{head_keep if head_keep is not None else 'mixed'}"
     extra = {"ms_per_step_median": round(float(np.median(per)), 4),
              "nominal_gathered_GBps": round(eff_gbps, 1),
-             "measured_copy_GBps": round(copy_gbps, 1)}
+             "measured_copy_GBps": round(copy_gbps, 1),
+             "measured_l2_read_GBps_all_units": round(l2_all, 1) if l2_all else None,
+             "measured_l2_read_GBps_one_unit": round(l2_one, 1) if l2_one else None}
     roofline = None
     if not args.no_profile:
         prof = w.profile_sparse(head_keep, K)

@@ -136,6 +136,16 @@ int slonn_version(char* buf, size_t cap);
  * EINVAL: null argument; ENOMEM: scratch too small.                                           */
 int slonn_probe_mfma_rate(void* scratch, size_t scratch_bytes, void* stream, double* tflops);
 
+/* Measurement aid: the rate at which compute units read cache-resident rows with 16-byte loads, the
+ * bound of the gather kernels wherever the weights sit in L2 (one 1024-thread workgroup per compute
+ * unit reads one 2 MiB window over and over).  gbps_all_units: GB/s summed over all compute units
+ * busy together; gbps_one_unit: GB/s of one unit with the rest of the device idle (both HOST).
+ * scratch: DEVICE memory, 16-byte aligned, 2 MiB + 4096 bytes per compute unit (any contents; the
+ * tail is written).  Synchronises `stream`.  EINVAL: null or misaligned argument; ENOMEM: scratch
+ * too small.                                                                                    */
+int slonn_probe_l_two_read_rate(void* scratch, size_t scratch_bytes, void* stream, double* gbps_all_units,
+                                double* gbps_one_unit);
+
 /* Validate and register a network.  Copies the K*L FreeHash rows of each activated
  * layer into library-owned device memory (synchronises the device once).
  * Errors: EINVAL for null/negative sizes, K > SLONN_MAX_K, L > SLONN_MAX_L, K*L >

@@ -566,4 +566,30 @@ int launch_finalize(float* Y, int ldy, int n, const int32_t* active, const int32
   return SLONN_OK;
 }
 
+// ---- measurement aid: what a compute unit draws from L2 with 16-byte loads ----
+namespace {
+// Every workgroup (1024 threads, one per compute unit when the grid is the unit count) reads the
+// same 2 MiB window `passes` times, four 16-byte loads in flight per lane: after the first pass the
+// window sits in the L2 of every XCD.
+__global__ __launch_bounds__(1024) void l2_read_probe_kernel(const uint4* __restrict__ buf, int pieces, int passes,
+                                                             uint32_t* __restrict__ out) {
+  uint32_t acc = 0;
+  for (int p = 0; p < passes; ++p)
+    for (int i = threadIdx.x; i + 3 * 1024 < pieces; i += 4 * 1024) {
+      const uint4 a = buf[i], b = buf[i + 1024], c = buf[i + 2048], d = buf[i + 3072];
+      acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+  out[(size_t)blockIdx.x * 1024 + threadIdx.x] = acc;
+}
+}  // namespace
+
+// buf: 2 MiB + workgroups * 4096 bytes of device memory (any contents).  Returns the bytes the launch reads.
+double launch_l2_read_probe(void* buf, int workgroups, int passes, hipStream_t s) {
+  const int pieces = (2 << 20) / 16;
+  uint32_t* out = reinterpret_cast<uint32_t*>(static_cast<char*>(buf) + (2 << 20));
+  hipLaunchKernelGGL(l2_read_probe_kernel, dim3(workgroups), dim3(1024), 0, s, static_cast<const uint4*>(buf), pieces,
+                     passes, out);
+  return (double)pieces * 16.0 * passes * workgroups;
+}
+
 }  // namespace slonn

@@ -238,6 +238,37 @@ int slonn_probe_mfma_rate(void* scratch, size_t scratch_bytes, void* stream, dou
   return SLONN_OK;
 }
 
+int slonn_probe_l_two_read_rate(void* scratch, size_t scratch_bytes, void* stream, double* gbps_all_units,
+                                double* gbps_one_unit) {
+  if (!scratch || !gbps_all_units || !gbps_one_unit) SLONN_FAIL(SLONN_EINVAL, "null argument");
+  int dev = 0, n_cu = 256;
+  SLONN_HIP(hipGetDevice(&dev));
+  (void)hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+  const size_t need = ((size_t)2 << 20) + (size_t)n_cu * 4096;
+  if (scratch_bytes < need) SLONN_FAIL(SLONN_ENOMEM, "scratch holds %zu bytes, %zu needed", scratch_bytes, need);
+  if (reinterpret_cast<uintptr_t>(scratch) % 16 != 0) SLONN_FAIL(SLONN_EINVAL, "scratch must be 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  SLONN_HIP(hipEventCreate(&e0));
+  SLONN_HIP(hipEventCreate(&e1));
+  double* outs[2] = {gbps_all_units, gbps_one_unit};
+  const int grids[2] = {n_cu, 1};
+  for (int k = 0; k < 2; ++k) {
+    (void)launch_l2_read_probe(scratch, grids[k], 4, s);            // warm-up: the window into L2
+    SLONN_HIP(hipEventRecord(e0, s));
+    const double bytes = launch_l2_read_probe(scratch, grids[k], 200, s);
+    SLONN_HIP(hipEventRecord(e1, s));
+    SLONN_HIP(hipEventSynchronize(e1));
+    float ms = 0.0f;
+    SLONN_HIP(hipEventElapsedTime(&ms, e0, e1));
+    *outs[k] = ms > 0.0f ? bytes / (ms * 1e-3) / 1e9 : 0.0;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  SLONN_HIP(hipGetLastError());
+  return SLONN_OK;
+}
+
 int slonn_version(char* buf, size_t cap) {
   if (!buf || cap == 0) SLONN_FAIL(SLONN_EINVAL, "null buffer");
   int dev = 0, lds = 0, cus = 0;

@@ -344,6 +344,8 @@ size_t masked_tiles_workspace_bytes(int B, int n, int d);
 void masked_tiles_buffers(void* scratch, int B, int n, uint32_t** mask, int32_t** flags);
 size_t tile_weights_bytes(int w_dtype, int n, int d);
 int launch_split_weights(const void* W, int w_dtype, int n, int d, uint16_t* out, int32_t* wexp, hipStream_t s);
+// measurement aid: workgroups that read one L2-resident 2 MiB window with 16-byte loads (returns the bytes read)
+double launch_l2_read_probe(void* buf, int workgroups, int passes, hipStream_t s);
 // measurement aid: a register-only loop of the tile kernel's MFMAs (returns the flops of the launch)
 double launch_mfma_rate_probe(float* out, int workgroups, int iters, hipStream_t s);
 int launch_dense_tiles(const uint16_t* Wp, int w_parts, const int32_t* wexp, const float* bias, const float* X, int ldx,

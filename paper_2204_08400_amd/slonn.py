@@ -36,7 +36,7 @@ EXPORTS = [
     "slonn_activation_variance", "slonn_sample_hash_nodes", "slonn_model_set_hash_margin",
     "slonn_sparse_forward_static", "slonn_model_set_dense_arithmetic",
     "slonn_sample_hash_nodes_device", "slonn_model_set_tables_refreshable", "slonn_tables_refresh",
-    "slonn_model_set_batches_in_flight", "slonn_probe_mfma_rate",
+    "slonn_model_set_batches_in_flight", "slonn_probe_mfma_rate", "slonn_probe_l_two_read_rate",
 ]
 STATIC_SCRATCH_BYTES = 64 << 20
 PROF_KINDS = ("hash", "select", "gather", "dense", "ell", "finalize", "fused", "tiles")
@@ -123,6 +123,14 @@ def slonn_probe_mfma_rate(scratch, stream=None) -> float:
     _check(load().slonn_probe_mfma_rate(C.c_void_p(_ptr(scratch)), C.c_size_t(scratch.numel() * scratch.element_size()),
                                             C.c_void_p(_stream_ptr(stream)), C.byref(out)))
     return out.value
+
+
+def slonn_probe_l_two_read_rate(scratch, stream=None):
+    """(GB/s of all compute units together, GB/s of one unit alone) reading L2-resident rows (see slonn.h)."""
+    a, b = C.c_double(0.0), C.c_double(0.0)
+    _check(load().slonn_probe_l_two_read_rate(C.c_void_p(_ptr(scratch)), C.c_size_t(scratch.numel() * scratch.element_size()),
+                                              C.c_void_p(_stream_ptr(stream)), C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 class Model:

@@ -105,6 +105,7 @@ def test_null_handles_are_rejected(slonn):
     assert lib.slonn_model_set_tables_refreshable(None, 1) == slonn.EINVAL
     assert lib.slonn_model_set_batches_in_flight(None, 2) == slonn.EINVAL
     assert lib.slonn_probe_mfma_rate(None, C.c_size_t(0), None, None) == slonn.EINVAL
+    assert lib.slonn_probe_l_two_read_rate(None, C.c_size_t(0), None, None, None) == slonn.EINVAL
     assert lib.slonn_tables_refresh(None, None, None, C.c_int64(1), None) == slonn.EINVAL
     assert lib.slonn_sample_hash_nodes_device(None, 8, 1, 1, None, None, None) == slonn.EINVAL
     assert slonn.load().slonn_last_error()
