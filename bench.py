@@ -504,6 +504,11 @@ def main():
     if not args.no_profile:
         prof = w.profile_sparse(head_keep, K)
         roofline, per_step_us = roofline_of(w, head_keep, prof, K, secs / K, traffic_key)
+        if roofline.get("bound") == "hbm" and roofline.get("achieved") and l2_all:
+            # every gathered byte passes from L2 (or beyond) into a compute unit: the measured rate of
+            # that path bounds the kernel also where HBM does not
+            roofline["measured_l2_read_GBps_all_units"] = round(l2_all, 1)
+            roofline["frac_of_measured_l2_read_rate"] = round(roofline["achieved"] / l2_all, 4)
         extra["per_step_us_by_kernel_kind_with_event_overhead"] = {k: round(v, 1) for k, v in per_step_us.items()}
         extra["avg_launch_us_by_kernel_kind_with_event_overhead"] = \
             {k: round(v[0] * 1e3 / v[1], 2) for k, v in prof.items() if v[1]}
